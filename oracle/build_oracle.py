@@ -1,0 +1,23 @@
+"""Compiles the plain-C oracle (byz_oracle.c) into liboracle.so next to it.
+
+TEST INFRASTRUCTURE ONLY.  Building the checker is not using it.
+"""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(HERE, "byz_oracle.c")
+LIB = os.path.join(HERE, "liboracle.so")
+
+
+def build(force=False):
+    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+        return LIB
+    cmd = ["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fopenmp", "-ffp-contract=off",
+           "-shared", "-fPIC", SRC, "-o", LIB]
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(force=True))

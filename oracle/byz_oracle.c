@@ -1,0 +1,145 @@
+/*
+ * CPU oracle for the ByzShield aggregation path (arXiv 2010.04902), plain C.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Same definitions as byz_oracle.py, written so
+ * that full-size inputs finish in seconds: nothing here is blocked, fused or
+ * reordered beyond "loop over files" and "loop over coordinates".  It shares
+ * no code with the HIP path or its host library.
+ *
+ *   oracle_vote    Eq. 3 + the implementation note of Sec. 2: exact-match
+ *                  counting of whole d-vectors, most frequent copy wins,
+ *                  lowest replica index on ties (paper silent on ties).
+ *   oracle_median  Sec. 2 / Sec. 6.1: coordinate-wise median of f vectors
+ *                  (f odd): sort the f values of a coordinate, take the middle.
+ *                  Order: total order on bit patterns (-NaN < -inf < .. < -0 <
+ *                  +0 < .. < +inf < +NaN); the paper is silent on +-0 / NaN.
+ *   oracle_worst_case  Sec. 5.3.2: exhaustive search over all q-subsets.
+ *
+ * Build: gcc -O2 -fopenmp -shared -fPIC (see build_oracle.py).
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* pair p <-> (a, b), a < b, lexicographic: (0,1),(0,2),..,(1,2),.. */
+static int pair_bit(int r, int a, int b) {
+    int p = 0;
+    for (int x = 0; x < r; ++x)
+        for (int y = x + 1; y < r; ++y) {
+            if (x == a && y == b) return p;
+            ++p;
+        }
+    return -1;
+}
+
+int oracle_vote(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, int f, int r,
+                int32_t *winner_replica, int32_t *winner_row, uint32_t *pair_neq) {
+    if (r < 1 || r > 7 || f < 1) return -1;
+    for (int j = 0; j < f; ++j) {
+        int eq[8][8];
+        for (int a = 0; a < r; ++a)
+            for (int b = 0; b < r; ++b) {
+                const uint32_t *pa = X + (int64_t)rows[j * r + a] * ld;
+                const uint32_t *pb = X + (int64_t)rows[j * r + b] * ld;
+                eq[a][b] = (memcmp(pa, pb, (size_t)d * 4) == 0);
+            }
+        int best = -1, a_star = 0;
+        for (int a = 0; a < r; ++a) {
+            int count = 0;
+            for (int b = 0; b < r; ++b) count += eq[a][b];
+            if (count > best) { best = count; a_star = a; }
+        }
+        winner_replica[j] = a_star;
+        winner_row[j] = rows[j * r + a_star];
+        uint32_t bits = 0;
+        for (int a = 0; a < r; ++a)
+            for (int b = a + 1; b < r; ++b)
+                if (!eq[a][b]) bits |= 1u << pair_bit(r, a, b);
+        pair_neq[j] = bits;
+    }
+    return 0;
+}
+
+static uint32_t order_key(uint32_t u) {
+    return (u >> 31) ? (u ^ 0xFFFFFFFFu) : (u ^ 0x80000000u);
+}
+
+static uint32_t key_to_bits(uint32_t k) {
+    /* inverse of order_key: keys of negative-sign patterns have the top bit clear */
+    return (k >> 31) ? (k ^ 0x80000000u) : (k ^ 0xFFFFFFFFu);
+}
+
+/* returns the number of threads used, or <0 on error */
+int oracle_median(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
+                  uint32_t *out, int threads) {
+    if (f < 1 || f > 1024 || (f % 2) == 0) return -1;
+    int used = 1;
+#ifdef _OPENMP
+    if (threads < 1) threads = 1;
+    used = threads;
+#pragma omp parallel for schedule(static) num_threads(threads)
+#endif
+    for (int64_t c = 0; c < d; ++c) {
+        uint32_t key[1024];
+        for (int j = 0; j < f; ++j) key[j] = order_key(X[(int64_t)row_index[j] * ld + c]);
+        /* insertion sort, ascending */
+        for (int i = 1; i < f; ++i) {
+            uint32_t x = key[i];
+            int t = i - 1;
+            while (t >= 0 && key[t] > x) { key[t + 1] = key[t]; --t; }
+            key[t + 1] = x;
+        }
+        out[c] = key_to_bits(key[(f - 1) / 2]);
+    }
+    return used;
+}
+
+/* vote then median over the winners; returns threads used by the median, <0 on error */
+int oracle_aggregate(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, int f, int r,
+                     uint32_t *out, int32_t *winner_replica, int threads) {
+    int32_t *wrow = (int32_t *)malloc(sizeof(int32_t) * (size_t)f);
+    uint32_t *neq = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)f);
+    if (!wrow || !neq) { free(wrow); free(neq); return -2; }
+    int rc = oracle_vote(X, d, ld, rows, f, r, winner_replica, wrow, neq);
+    if (rc == 0) rc = oracle_median(X, d, ld, wrow, f, out, threads);
+    free(wrow);
+    free(neq);
+    return rc;
+}
+
+/*
+ * H: K x f, row-major 0/1 bytes.  Visits the q-subsets in lexicographic order
+ * and keeps the first one with the largest number of files that have at least
+ * r' = (r+1)/2 copies inside the subset.
+ */
+int oracle_worst_case(const uint8_t *H, int K, int f, int r, int q, int32_t *S_out,
+                      int32_t *cmax_out) {
+    if (q < 0 || q > K || K > 64 || f > 4096) return -1;
+    int rp = (r + 1) / 2;
+    int S[64];
+    for (int i = 0; i < q; ++i) S[i] = i;
+    int best = -1;
+    for (;;) {
+        int c = 0;
+        for (int j = 0; j < f; ++j) {
+            int cnt = 0;
+            for (int i = 0; i < q; ++i) cnt += H[S[i] * f + j];
+            if (cnt >= rp) ++c;
+        }
+        if (c > best) {
+            best = c;
+            for (int i = 0; i < q; ++i) S_out[i] = S[i];
+        }
+        /* next combination in lexicographic order */
+        int i = q - 1;
+        while (i >= 0 && S[i] == K - q + i) --i;
+        if (i < 0) break;
+        ++S[i];
+        for (int t = i + 1; t < q; ++t) S[t] = S[t - 1] + 1;
+    }
+    *cmax_out = best;
+    return 0;
+}

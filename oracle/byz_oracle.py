@@ -1,0 +1,257 @@
+"""CPU oracle for the ByzShield parameter-server aggregation path (arXiv 2010.04902).
+
+TEST INFRASTRUCTURE ONLY.  This module is the plain, slow, by-the-definition
+implementation that the HIP path is checked against.  It shares no code with
+the HIP path or its host library and imports neither; only tests, the smoke
+check and the benchmark's CPU-baseline leg may use it.
+
+Everything follows the paper's notation: K workers U_0..U_{K-1}, f files,
+replication r (odd), r' = (r+1)/2, load l = f*r/K, d coordinates.
+
+Parity status of each function (what pins it, see tests/test_oracle_*.py):
+  latin_square, mols_biadjacency      Table 1, Example 1, Table 2 cell by cell
+  ramanujan_biadjacency               Eq. 6 degrees, Lemma 2 spectrum, Table 4
+  worst_case                          Tables 3-6, Claim 2, naive brute force
+  gamma_bound                         Tables 3-6 (gamma column), closed forms Sec. 5.1
+  vote                                brute force over all equality patterns, Sec. 2
+                                      statements (all-honest, distorted iff >= r')
+  median                              numpy sort/median on ordinary data, brute force
+  tie-break rules (vote plurality ties -> lowest replica; total order of
+  +-0 / NaN in the median; lexicographically first worst-case set):
+      the paper is silent on these -> "parity unpinned" by the paper; both
+      sides implement the reading written here.
+"""
+import itertools
+
+import numpy as np
+
+# --------------------------------------------------------------------------
+# Task assignment (Sec. 4)
+# --------------------------------------------------------------------------
+
+
+def is_prime(n):
+    n = int(n)
+    if n < 2:
+        return False
+    for p in range(2, n):
+        if p * p > n:
+            break
+        if n % p == 0:
+            return False
+    return True
+
+
+def latin_square(l, alpha):
+    """Sec. 4.1.1: the square L_alpha(i, j) = alpha*i + j over F_l (l prime, alpha != 0)."""
+    assert is_prime(l) and alpha % l != 0
+    L = np.zeros((l, l), dtype=np.int64)
+    for i in range(l):
+        for j in range(l):
+            L[i, j] = (alpha * i + j) % l
+    return L
+
+
+def mols_biadjacency(l, r):
+    """Algorithm 2 (MOLS-based assignment): K = r*l workers, f = l*l files.
+
+    For k = 0..r-1 and every symbol s, each cell (i, j) of L_{k+1} that holds s
+    connects file i*l + j to worker U_{k*l + s}.  Returns H (K x f, 0/1), Eq. 4.
+    """
+    assert 1 <= r <= l - 1
+    H = np.zeros((r * l, l * l), dtype=np.int64)
+    for k in range(r):
+        L = latin_square(l, k + 1)
+        for s in range(l):
+            for i in range(l):
+                for j in range(l):
+                    if L[i, j] == s:
+                        H[k * l + s, i * l + j] = 1
+    return H
+
+
+def cyclic_shift_matrix(s):
+    """Sec. 4.2.1 Step 2: P[i][j] = 1 iff j = i - 1 (mod s)."""
+    P = np.zeros((s, s), dtype=np.int64)
+    for i in range(s):
+        P[i, (i - 1) % s] = 1
+    return P
+
+
+def array_code_matrix(m, s):
+    """Sec. 4.2.1 Step 3: B, an s x m grid of s x s blocks, block (a, b) = P^(a*b)."""
+    assert m >= 2 and is_prime(s)
+    P = cyclic_shift_matrix(s)
+    B = np.zeros((s * s, m * s), dtype=np.int64)
+    for a in range(s):
+        for b in range(m):
+            B[a * s:(a + 1) * s, b * s:(b + 1) * s] = np.linalg.matrix_power(P, a * b)
+    return B
+
+
+def ramanujan_biadjacency(m, s):
+    """Sec. 4.2.1 / Eq. 6: H = B when m >= s (Case 2), H = B^T when m < s (Case 1).
+
+    Rows of H are workers, columns are files.
+    """
+    B = array_code_matrix(m, s)
+    return B if m >= s else B.T.copy()
+
+
+def dims(H):
+    """(K, f, l, r) of a biregular biadjacency matrix (Sec. 2: l = f*r/K)."""
+    K, f = H.shape
+    l = int(H[0].sum())
+    r = int(H[:, 0].sum())
+    assert (H.sum(axis=1) == l).all() and (H.sum(axis=0) == r).all()
+    assert l * K == f * r
+    return K, f, l, r
+
+
+def worker_files(H):
+    """N(U_w): ascending list of the l files worker w holds."""
+    return np.array([np.flatnonzero(H[w]) for w in range(H.shape[0])], dtype=np.int32)
+
+
+def file_workers(H):
+    """N(B_j): ascending list of the r workers holding file j (replica k = k-th of them)."""
+    return np.array([np.flatnonzero(H[:, j]) for j in range(H.shape[1])], dtype=np.int32)
+
+
+def file_rows(H):
+    """Row of the stacked returns that holds replica k of file j.
+
+    A worker returns the gradients of its files in ascending file order
+    (Algorithm 1, the return step), worker after worker, so worker w's t-th
+    file sits in row w*l + t.
+    """
+    K, f, l, r = dims(H)
+    wf = worker_files(H)
+    fw = file_workers(H)
+    rows = np.zeros((f, r), dtype=np.int32)
+    for j in range(f):
+        for k in range(r):
+            w = int(fw[j, k])
+            t = list(wf[w]).index(j)
+            rows[j, k] = w * l + t
+    return rows
+
+
+# --------------------------------------------------------------------------
+# Worst-case adversary (Sec. 5.2, 5.3.2) and the expansion bound (Sec. 3)
+# --------------------------------------------------------------------------
+
+
+def distorted_files(H, S):
+    """Files with at least r' of their r copies on workers in S (Sec. 2)."""
+    K, f, l, r = dims(H)
+    rp = (r + 1) // 2
+    S = list(S)
+    cnt = H[S].sum(axis=0) if S else np.zeros(f, dtype=np.int64)
+    return np.flatnonzero(cnt >= rp)
+
+
+def worst_case(H, q):
+    """c_max^(q): exhaustive search over all q-subsets of the K workers (Sec. 5.3.2).
+
+    Subsets are visited in lexicographic order of their ascending tuple and
+    the first one attaining the maximum is returned (the paper only says "a
+    set such that the distortion is maximised").
+    Returns (c_max, S as a tuple, ascending array of distorted files).
+    """
+    K = H.shape[0]
+    best, best_S = -1, None
+    for S in itertools.combinations(range(K), q):
+        c = len(distorted_files(H, S))
+        if c > best:
+            best, best_S = c, S
+    return best, best_S, distorted_files(H, best_S)
+
+
+def gamma_bound(K, f, l, r, q, mu1=None):
+    """Eq. 5 then Claim 1: beta = (q l / r) / (mu1 + (1 - mu1) q / K), gamma = (q l - beta) / ((r - 1)/2).
+
+    mu1 defaults to 1/r (Lemma 2, all three constructions).
+    """
+    if mu1 is None:
+        mu1 = 1.0 / r
+    beta = (q * l / r) / (mu1 + (1.0 - mu1) * q / K)
+    return (q * l - beta) / ((r - 1) / 2.0)
+
+
+# --------------------------------------------------------------------------
+# Majority vote (Eq. 3) and coordinate-wise median (Sec. 2, Sec. 6.1)
+# --------------------------------------------------------------------------
+
+
+def pair_index(r):
+    """Pairs (a, b), a < b, in lexicographic order; bit p of pair_neq is pair p."""
+    return [(a, b) for a in range(r) for b in range(a + 1, r)]
+
+
+def vote(X, rows, d):
+    """Eq. 3 with the paper's implementation note: the copy that appears most often.
+
+    X: [R, ld] array of 32-bit words (float32 or uint32), rows: [f, r] row ids.
+    Two copies are equal iff all d 32-bit words are identical bit patterns.
+    count[a] = number of copies equal to copy a (itself included); the winner
+    is the smallest a with the largest count.
+    Returns (winner_replica[f], winner_row[f], pair_neq[f]) where bit p of
+    pair_neq[j] is 1 iff the copies of pair p (see pair_index) differ.
+    """
+    U = np.ascontiguousarray(X).view(np.uint32)
+    f, r = rows.shape
+    pairs = pair_index(r)
+    winner_replica = np.zeros(f, dtype=np.int32)
+    winner_row = np.zeros(f, dtype=np.int32)
+    pair_neq = np.zeros(f, dtype=np.uint32)
+    for j in range(f):
+        copies = [U[rows[j, k], :d].tobytes() for k in range(r)]
+        count = [sum(1 for b in range(r) if copies[a] == copies[b]) for a in range(r)]
+        best = max(count)
+        a_star = count.index(best)
+        winner_replica[j] = a_star
+        winner_row[j] = rows[j, a_star]
+        bits = 0
+        for p, (a, b) in enumerate(pairs):
+            if copies[a] != copies[b]:
+                bits |= 1 << p
+        pair_neq[j] = bits
+    return winner_replica, winner_row, pair_neq
+
+
+def order_key(u):
+    """Total order on float32 bit patterns used by the median.
+
+    key = bits ^ 0xFFFFFFFF for negative-sign patterns, bits ^ 0x80000000
+    otherwise, compared as unsigned integers:
+      -NaN < -inf < ... < -0 < +0 < ... < +inf < +NaN.
+    On NaN-free data it is the usual '<' except that -0 sorts before +0.
+    """
+    u = np.asarray(u, dtype=np.uint32)
+    neg = (u >> np.uint32(31)).astype(bool)
+    return np.where(neg, u ^ np.uint32(0xFFFFFFFF), u ^ np.uint32(0x80000000))
+
+
+def median(X, row_index, d):
+    """Coordinate-wise median of f rows (f odd): the element of rank (f-1)/2.
+
+    Sorts the f order keys of every coordinate and returns, bit for bit, the
+    input value whose key lands in the middle.
+    """
+    U = np.ascontiguousarray(X).view(np.uint32)
+    row_index = np.asarray(row_index)
+    f = len(row_index)
+    assert f % 2 == 1
+    vals = np.stack([U[int(row_index[j]), :d] for j in range(f)])  # [f, d]
+    keys = order_key(vals)
+    order = np.argsort(keys, axis=0, kind="stable")
+    mid = order[(f - 1) // 2]  # [d] index of the file holding the median
+    out = vals[mid, np.arange(d)]
+    return out.view(np.float32)
+
+
+def aggregate(X, rows, d):
+    """Vote per file, then the coordinate-wise median across the f winners."""
+    winner_replica, winner_row, _ = vote(X, rows, d)
+    return median(X, winner_row, d), winner_replica

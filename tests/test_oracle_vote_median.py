@@ -1,0 +1,221 @@
+"""Pins for the oracle's majority vote (Eq. 3) and coordinate-wise median (Sec. 2, Sec. 6.1)."""
+import itertools
+import struct
+
+import numpy as np
+import pytest
+
+from oracle import byz_oracle as O
+from oracle import c_oracle as C
+
+IMPLS = [("numpy", O.vote, O.median), ("c", C.vote, lambda X, ri, d: C.median(X, ri, d, threads=2))]
+
+
+def _set_partitions(n):
+    """All partitions of {0..n-1} as label lists in restricted-growth form."""
+    def rec(prefix, mx):
+        if len(prefix) == n:
+            yield list(prefix)
+            return
+        for lab in range(mx + 2):
+            yield from rec(prefix + [lab], max(mx, lab))
+    yield from rec([0], 0)
+
+
+def _definition_winner(labels):
+    """Most frequent label; among equally frequent ones the one containing the lowest index."""
+    best_a, best_c = None, -1
+    for a in range(len(labels)):
+        c = labels.count(labels[a])
+        if c > best_c:
+            best_a, best_c = a, c
+    return best_a
+
+
+@pytest.mark.parametrize("name,vote,median", IMPLS)
+@pytest.mark.parametrize("r", [3, 5])
+def test_vote_every_equality_pattern(name, vote, median, r):
+    # 5 patterns for r = 3 (Bell number), 52 for r = 5
+    parts = list(_set_partitions(r))
+    assert len(parts) == {3: 5, 5: 52}[r]
+    rng = np.random.default_rng(11)
+    d = 37
+    for where in ["everywhere", "last", "first"]:
+        base = rng.standard_normal((r + 1, d)).astype(np.float32)
+        X = np.zeros((len(parts) * r, d), dtype=np.float32)
+        rows = np.arange(len(parts) * r, dtype=np.int32).reshape(len(parts), r)
+        for j, labels in enumerate(parts):
+            for k, lab in enumerate(labels):
+                v = base[0].copy()
+                if where == "everywhere":
+                    v = base[lab].copy()
+                elif where == "last":
+                    v[d - 1] = np.float32(lab)  # copies differ only in the last coordinate
+                else:
+                    v[0] = np.float32(lab)
+                X[rows[j, k]] = v
+        wrep, wrow, neq = vote(X, rows, d)
+        pairs = O.pair_index(r)
+        for j, labels in enumerate(parts):
+            a = _definition_winner(labels)
+            assert wrep[j] == a and wrow[j] == rows[j, a]
+            want = sum(1 << p for p, (x, y) in enumerate(pairs) if labels[x] != labels[y])
+            assert neq[j] == want
+
+
+@pytest.mark.parametrize("name,vote,median", IMPLS)
+def test_vote_is_bitwise(name, vote, median):
+    # +0 and -0 are different copies; NaNs with the same payload are the same copy
+    d = 8
+    X = np.zeros((6, d), dtype=np.float32)
+    X[1, 3] = -0.0
+    X[2, 3] = -0.0
+    nan_a = np.array([0x7FC00001], dtype=np.uint32).view(np.float32)[0]
+    nan_b = np.array([0x7FC00002], dtype=np.uint32).view(np.float32)[0]
+    X[3, 5] = nan_a
+    X[4, 5] = nan_a
+    X[5, 5] = nan_b
+    rows = np.array([[0, 1, 2], [3, 4, 5]], dtype=np.int32)
+    wrep, wrow, neq = vote(X, rows, d)
+    assert wrep.tolist() == [1, 0] and neq.tolist() == [0b011, 0b110]
+    # only the first d words are compared: padding beyond d is ignored
+    X2 = np.zeros((3, d + 4), dtype=np.float32)
+    X2[:, d:] = np.arange(12, dtype=np.float32).reshape(3, 4)
+    wrep, _, neq = vote(X2, np.array([[0, 1, 2]], dtype=np.int32), d)
+    assert wrep.tolist() == [0] and neq.tolist() == [0]
+
+
+def _honest_and_attacked(H, S, d, seed, attack):
+    K, f, l, r = O.dims(H)
+    rng = np.random.default_rng(seed)
+    g = (0.01 * rng.standard_normal((f, d))).astype(np.float32)
+    rows = O.file_rows(H)
+    fw = O.file_workers(H)
+    X = np.zeros((K * l, d), dtype=np.float32)
+    for j in range(f):
+        for k in range(r):
+            X[rows[j, k]] = attack(g[j]) if int(fw[j, k]) in S else g[j]
+    return g, X, rows
+
+
+@pytest.mark.parametrize("name,vote,median", IMPLS)
+def test_vote_all_honest_and_below_threshold(name, vote, median):
+    # Sec. 2 / Sec. 5.3.1: with fewer than r' Byzantine copies per file nothing is distorted
+    H = O.mols_biadjacency(5, 3)
+    d = 50
+    for S in [(), (4,), (7,)]:
+        g, X, rows = _honest_and_attacked(H, set(S), d, 3, lambda v: -100.0 * v)
+        wrep, wrow, _ = vote(X, rows, d)
+        for j in range(25):
+            assert np.array_equal(X[wrow[j]], g[j])
+        out = median(X, wrow, d)
+        assert np.array_equal(out, np.median(g, axis=0))
+
+
+@pytest.mark.parametrize("name,vote,median", IMPLS)
+@pytest.mark.parametrize("scheme,a,b,q,cmax", [("mols", 5, 3, 3, 3), ("mols", 5, 3, 4, 5),
+                                               ("ram", 5, 5, 6, 4)])
+def test_vote_distorts_exactly_cmax_files(name, vote, median, scheme, a, b, q, cmax):
+    # Sec. 2: a file is distorted iff at least r' of its copies are Byzantine; for the
+    # worst-case set the number of such files is the c_max the paper's tables print.
+    H = O.mols_biadjacency(a, b) if scheme == "mols" else O.ramanujan_biadjacency(a, b)
+    c, S = C.worst_case(H, q)
+    assert c == cmax
+    d = 40
+    g, X, rows = _honest_and_attacked(H, set(S), d, 5, lambda v: -100.0 * v)
+    wrep, wrow, _ = vote(X, rows, d)
+    wrong = [j for j in range(H.shape[1]) if not np.array_equal(X[wrow[j]], g[j])]
+    assert wrong == O.distorted_files(H, S).tolist() and len(wrong) == cmax
+
+
+def _total_order_rank(u):
+    """IEEE totalOrder written independently: sign-magnitude value of the bit pattern."""
+    sign = u >> 31
+    mag = u & 0x7FFFFFFF
+    return -(mag + 1) if sign else mag
+
+
+def test_order_key_special_values():
+    words = [0xFFC00000, 0xFF800000, 0xC0000000, 0xBF800000, 0x80000001, 0x80000000,
+             0x00000000, 0x00000001, 0x3F800000, 0x40000000, 0x7F800000, 0x7FC00000]
+    keys = O.order_key(np.array(words, dtype=np.uint32)).tolist()
+    assert keys == sorted(keys) and len(set(keys)) == len(keys)  # listed in ascending order
+    rng = np.random.default_rng(0)
+    u = rng.integers(0, 2**32, size=5000, dtype=np.uint64).astype(np.uint32)
+    k = O.order_key(u)
+    ranks = np.array([_total_order_rank(int(x)) for x in u])
+    assert np.array_equal(np.argsort(k, kind="stable"), np.argsort(ranks, kind="stable"))
+
+
+@pytest.mark.parametrize("name,vote,median", IMPLS)
+@pytest.mark.parametrize("f", [1, 3, 9, 25, 49])
+def test_median_matches_numpy_on_ordinary_data(name, vote, median, f):
+    rng = np.random.default_rng(f)
+    d = 301
+    X = rng.standard_normal((f + 3, d)).astype(np.float32)
+    X[:, :7] = np.round(X[:, :7])  # repeated values
+    X[X == 0] = 0.0  # no negative zeros in this test
+    idx = rng.permutation(f + 3)[:f].astype(np.int32)
+    out = median(X, idx, d)
+    assert np.array_equal(out, np.median(X[idx], axis=0))
+    assert np.array_equal(out, np.sort(X[idx], axis=0)[(f - 1) // 2])
+    # invariant under permuting the files, and the median of identical vectors is that vector
+    assert np.array_equal(median(X, idx[::-1].copy(), d), out)
+    same = np.full(f, idx[0], dtype=np.int32)
+    assert np.array_equal(median(X, same, d), X[idx[0]])
+
+
+@pytest.mark.parametrize("name,vote,median", IMPLS)
+def test_median_bruteforce_small_alphabet(name, vote, median):
+    # every vector over a 3-letter alphabet (incl. -0/+0 and a NaN) for f = 5: rank-2 element
+    letters = np.array([0x80000000, 0x00000000, 0x7FC00000], dtype=np.uint32)  # -0 < +0 < NaN
+    combos = list(itertools.product(range(3), repeat=5))
+    X = np.zeros((5, len(combos)), dtype=np.uint32)
+    for c, combo in enumerate(combos):
+        X[:, c] = letters[list(combo)]
+    out = median(X.view(np.float32), np.arange(5, dtype=np.int32), len(combos)).view(np.uint32)
+    for c, combo in enumerate(combos):
+        assert out[c] == letters[sorted(combo)[2]]
+
+
+@pytest.mark.parametrize("name,vote,median", IMPLS)
+def test_median_counting_definition_random_bits(name, vote, median):
+    # rank definition checked by counting, on raw random bit patterns (NaNs, infs, denormals)
+    rng = np.random.default_rng(5)
+    f, d = 25, 400
+    U = rng.integers(0, 2**32, size=(f, d), dtype=np.uint64).astype(np.uint32)
+    out = median(U.view(np.float32), np.arange(f, dtype=np.int32), d).view(np.uint32)
+    for c in range(d):
+        col = [_total_order_rank(int(x)) for x in U[:, c]]
+        m = _total_order_rank(int(out[c]))
+        assert int(out[c]) in [int(x) for x in U[:, c]]
+        assert sum(1 for x in col if x < m) <= (f - 1) // 2
+        assert sum(1 for x in col if x > m) <= (f - 1) // 2
+
+
+@pytest.mark.parametrize("name,vote,median", IMPLS)
+def test_median_stays_within_honest_range(name, vote, median):
+    # with fewer than (f+1)/2 distorted winners the median lies between honest values
+    rng = np.random.default_rng(9)
+    f, d, bad = 25, 200, 12
+    X = rng.standard_normal((f, d)).astype(np.float32)
+    X[:bad // 2] = 1e6
+    X[bad // 2:bad] = -1e6
+    out = median(X, np.arange(f, dtype=np.int32), d)
+    assert (out >= X[bad:].min(axis=0)).all() and (out <= X[bad:].max(axis=0)).all()
+
+
+def test_aggregate_numpy_vs_c():
+    H = O.ramanujan_biadjacency(5, 5)
+    _, S = C.worst_case(H, 6)
+    g, X, rows = _honest_and_attacked(H, set(S), 333, 2, lambda v: np.full_like(v, 1e3))
+    out_py, w_py = O.aggregate(X, rows, 333)
+    out_c, w_c, threads = C.aggregate(X, rows, 333, threads=3)
+    assert threads == 3
+    assert np.array_equal(out_py.view(np.uint32), out_c.view(np.uint32))
+    assert np.array_equal(w_py, w_c)
+
+
+def test_struct_roundtrip_sanity():
+    # the fixtures above build floats from bit patterns; make sure the view does what we think
+    assert struct.unpack("<I", struct.pack("<f", -0.0))[0] == 0x80000000
