@@ -1,0 +1,166 @@
+"""Benchmark of the ByzShield aggregation path (majority vote + coordinate-wise median) on one MI355X.
+
+A step is one pass of the whole path (byz_aggregate: probe, single-pass vote+median kernel,
+finalisation, conditional exact path) over one batch of stacked worker returns that is
+already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--unpadded] [--no-cpu]
+"""
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
+
+
+def _traffic_from_profiles(workload):
+    """HBM bytes per launch from the committed counter summary, or None if absent or stale."""
+    path = os.path.join(ROOT, "profiles", "fused_kernel_%s_hbm_traffic.txt" % workload)
+    if not os.path.exists(path):
+        return None
+    kv = {}
+    with open(path) as fh:
+        for line in fh:
+            if "=" in line and not line.startswith("#"):
+                k, v = line.strip().split("=", 1)
+                kv[k.strip()] = v.strip()
+    src = os.path.join(ROOT, "paper_2010_04902_amd", "csrc", "kernels.hip")
+    sha = hashlib.sha256(open(src, "rb").read()).hexdigest()
+    if kv.get("kernels_hip_sha256") != sha:
+        return None  # the kernel changed since the counters were taken
+    try:
+        return float(kv["hbm_bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2, the headline)")
+    ap.add_argument("--unpadded", action="store_true", help="row pitch ld = d instead of d rounded up to 64")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the path shards by coordinate range, "
+                 "see DESIGN.md); --gpus %d is not supported" % args.gpus)
+
+    import numpy as np
+    import torch
+
+    import paper_2010_04902_amd as B
+    import synth
+
+    dev = "cuda:0"
+    cfg = synth.CONFIGS[args.config - 1]
+    d = cfg.d
+    ld = d if args.unpadded else synth.padded_ld(d, 64)
+    asg = B.byz_build_assignment(cfg.scheme, cfg.a, cfg.b)
+    byz, cmax, _ = B.byz_worst_case(asg, cfg.q)
+    assert cmax == cfg.cmax
+    rows = asg.file_rows()
+    rows_dev = torch.tensor(rows.reshape(-1), dtype=torch.int32, device=dev)
+    fw, wf = asg.file_workers(), asg.worker_files()
+
+    # distinct input buffers: one per step for the multi-step workload (rotating), one otherwise
+    n_buf = min(cfg.steps, 3)
+    bufs = []
+    for t in range(n_buf):
+        G = synth.honest_gradients(asg.f, d, cfg.seed, step=t, device=dev,
+                                   file_scales=bool(cfg.attack.get("file_scales")))
+        bufs.append(synth.build_copies(G, fw, wf, byz, cfg.attack, ld=ld))
+        del G
+    out = torch.empty(d, dtype=torch.float32, device=dev)
+    wrep = torch.empty(asg.f, dtype=torch.int32, device=dev)
+    ws = torch.empty(B.byz_aggregate_workspace_bytes(asg.f, asg.r), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        B.byz_aggregate(bufs[i % n_buf], d, rows_dev, asg.f, asg.r, out=out, winner_replica=wrep,
+                        workspace=ws, stream=stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    exact = B.byz_aggregate_took_exact_path(ws)
+
+    B.byz_profile_enable(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kernel_ms = B.byz_profile_collect(args.steps)
+    B.byz_profile_enable(0)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    coords_per_s = d / (ms_per_step * 1e-3)
+    alg_bytes = 4.0 * (asg.r * asg.f + 1) * d  # every copy read once, one value written
+    result = {
+        "metric": "aggregated coords/sec (vote+median)",
+        "value": coords_per_s,
+        "unit": "coords/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "d": d, "ld": ld, "K": asg.K, "f": asg.f, "r": asg.r,
+                   "l": asg.l, "q": cfg.q, "c_max": cmax, "attack": cfg.attack["kind"],
+                   "rows": asg.f * asg.r, "input_bytes": 4 * asg.f * asg.r * d,
+                   "took_exact_path": bool(exact)},
+        "step_hbm_gbps_algorithmic": alg_bytes / (ms_per_step * 1e-3) / 1e9,
+    }
+    if kernel_ms:
+        avg_ms = sum(kernel_ms) / len(kernel_ms)
+        achieved = alg_bytes / (avg_ms * 1e-3) / 1e9
+        result["roofline"] = {
+            "bound": "hbm", "kernel": "fused_kernel<%d,%d,%d>" % (asg.f, asg.r, 4 if ld % 4 == 0 else (2 if ld % 2 == 0 else 1)),
+            "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBPS,
+            "traffic": _traffic_from_profiles(cfg.name),
+            "algorithmic_bytes_per_launch": alg_bytes,
+            "avg_kernel_ms": avg_ms, "min_kernel_ms": min(kernel_ms), "launches_timed": len(kernel_ms),
+        }
+
+    if not args.no_cpu:
+        from oracle import c_oracle as C
+        Xh = bufs[0].cpu().numpy()
+        threads = C.default_threads()
+        best = None
+        reps = 2
+        for _ in range(reps):
+            c0 = time.perf_counter()
+            out_o, wrep_o, used = C.aggregate(Xh, rows, d, threads=threads)
+            c1 = time.perf_counter()
+            best = (c1 - c0) if best is None else min(best, c1 - c0)
+        step(0)
+        torch.cuda.synchronize()
+        same = bool(np.array_equal(out.cpu().numpy().view(np.uint32), out_o.view(np.uint32))
+                    and np.array_equal(wrep.cpu().numpy(), wrep_o))
+        result["cpu_baseline"] = {
+            "value": d / best, "unit": "coords/s", "cores": int(used), "kind": "oracle",
+            "sample": "whole %s batch (d=%d, %d rows), best of %d runs of the C oracle "
+                      "(vote single-threaded memcmp, median OpenMP over coordinates)"
+                      % (cfg.name, d, asg.f * asg.r, reps),
+            "seconds": best, "gpu_matches_oracle": same,
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

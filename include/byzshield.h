@@ -1,0 +1,201 @@
+/*
+ * byzshield.h -- C-ABI of libbyzshield: the parameter-server aggregation path of
+ * ByzShield (Konstantinidis & Ramamoorthy, arXiv 2010.04902) on one AMD MI355X.
+ *
+ * The path: K workers return R = r*f gradient vectors of d fp32 coordinates (f files,
+ * each replicated on r workers by a MOLS or Ramanujan-bigraph assignment).  The
+ * parameter server takes, per file, the copy that appears most often among its r copies
+ * (majority vote, Eq. 3) and then the coordinate-wise median over the f winners (Sec. 2,
+ * Sec. 6.1).  Host entry points build the assignment (Sec. 4) and search the worst-case
+ * Byzantine set (Sec. 5.3.2); device entry points run vote, median and the fused
+ * vote+median on HIP streams.
+ *
+ * Conventions
+ *   - Every function returns BYZ_OK (0) or a negative byz_status; nothing throws, aborts
+ *     or prints.  byz_strerror() names a code.
+ *   - "host" pointers are ordinary process memory, "device" pointers are HIP device
+ *     memory of the current device, both owned by the caller.  Inputs are never modified.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Device entry
+ *     points only enqueue work: no allocation, no host synchronisation.
+ *   - Stacked returns `copies`: R rows of `ld` 32-bit words, row-major, ld >= d; only the
+ *     first d words of a row are read.  Worker w's t-th file (ascending file index, the
+ *     order in which a worker returns its l gradients in Algorithm 1) is row w*l + t.
+ *     Any base alignment and any ld work; 16-byte aligned base with ld % 4 == 0 is the
+ *     fastest layout, 8-byte / ld % 2 == 0 the next.
+ *   - Equality of two copies is equality of all d 32-bit patterns (+0 != -0; a NaN equals
+ *     a NaN of the same payload).  The median orders values by the total order
+ *     -NaN < -inf < ... < -0 < +0 < ... < +inf < +NaN and returns one of its inputs
+ *     bit for bit; f must be odd.
+ */
+#ifndef BYZSHIELD_H
+#define BYZSHIELD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum byz_status {
+    BYZ_OK = 0,
+    BYZ_EINVAL = -1,       /* null pointer, size out of range, even r, q outside [0,K], ...      */
+    BYZ_EUNSUPPORTED = -2, /* valid in the paper but not built: prime-power l, even f, f > 64 ... */
+    BYZ_ENOMEM = -3,       /* host allocation failed, or the workspace is too small               */
+    BYZ_EDEVICE = -4,      /* a HIP call failed; see byz_last_hip_error()                          */
+    BYZ_EINTERNAL = -5     /* an assignment invariant did not hold (a bug)                         */
+} byz_status;
+
+typedef enum byz_scheme {
+    BYZ_SCHEME_MOLS = 0,     /* Algorithm 2: a = l (prime), b = r <= l-1; K = r*l, f = l*l            */
+    BYZ_SCHEME_RAMANUJAN = 1 /* Sec. 4.2.1: a = s (prime), b = m >= 2; Case 1 (m < s) or 2 (m >= s)  */
+} byz_scheme;
+
+#define BYZ_MAX_F 64 /* largest number of files the device entry points and the search take */
+#define BYZ_MAX_R 7  /* largest replication factor                                           */
+
+/* Opaque worker-file assignment graph G (Sec. 2): host memory owned by the library. */
+typedef struct byz_assignment byz_assignment;
+
+/* ---------------------------------------------------------------- host: assignment (Sec. 4) */
+
+/*
+ * Builds the biregular worker-file graph.
+ *   BYZ_SCHEME_MOLS (Sec. 4.1, Algorithm 2): file i*l+j goes, for k = 0..r-1, to worker
+ *     U_{k*l+s} with s = L_{k+1}(i,j) = (k+1)*i + j mod l.  Needs l prime, 1 <= r <= l-1.
+ *   BYZ_SCHEME_RAMANUJAN (Sec. 4.2.1, Eq. 6): H = B (m >= s) or B^T (m < s), B the s x m
+ *     block matrix of powers P^(a*b) of the cyclic shift P.  Needs s prime, m >= 2.
+ * After building, the library checks the structure the paper proves (every worker holds l
+ * files, every file sits on r workers, each parallel class holds each file once, two workers
+ * share at most one file ...) and returns BYZ_EINTERNAL if any fails.
+ * *out receives the graph (free with byz_free_assignment).  Errors: BYZ_EINVAL (null out,
+ * a < 2, r outside its range, unknown scheme), BYZ_EUNSUPPORTED (a not prime: prime powers
+ * need GF(p^k) arithmetic that is not built), BYZ_ENOMEM.
+ */
+int byz_build_assignment(int scheme, int a, int b, byz_assignment **out);
+
+/* Releases a graph; NULL is allowed. */
+void byz_free_assignment(byz_assignment *g);
+
+/* (K, f, l, r) of Sec. 2: workers, files, files per worker, copies per file.  Any out
+ * pointer may be NULL.  BYZ_EINVAL if g is NULL. */
+int byz_assignment_dims(const byz_assignment *g, int *K, int *f, int *l, int *r);
+
+/* host out[K*l]: the files of worker w, ascending, at out[w*l .. w*l+l-1]  (N(U_w)). */
+int byz_assignment_worker_files(const byz_assignment *g, int32_t *out);
+
+/* host out[f*r]: the workers of file j, ascending (= parallel-class order), at out[j*r ..]  (N(B_j)). */
+int byz_assignment_file_workers(const byz_assignment *g, int32_t *out);
+
+/* host out[f*r]: row of `copies` holding replica k of file j: w*l + t with w the k-th worker of
+ * the file and t the rank of j among w's files. */
+int byz_assignment_file_rows(const byz_assignment *g, int32_t *out);
+
+/* ------------------------------------------------- host: worst-case adversary (Sec. 5.3.2) */
+
+/*
+ * Exhaustive search over all q-subsets S of the K workers for the largest number of files
+ * with at least r' = (r+1)/2 copies on workers of S (c_max^(q) of Claim 1 and Tables 3-6).
+ * Among maximisers the lexicographically first ascending tuple is returned.
+ *   byz_workers_out   host [q], ascending (may be NULL)
+ *   cmax_out          host, c_max^(q) (may be NULL)
+ *   distorted_mask_out host, bit j set iff file j is distorted by the returned set (may be NULL)
+ * Errors: BYZ_EINVAL (null g, q < 0, q > K), BYZ_EUNSUPPORTED (f > 64).
+ * Cost grows as C(K, q); the call is single-threaded and not interruptible.
+ */
+int byz_worst_case(const byz_assignment *g, int q, int32_t *byz_workers_out, int32_t *cmax_out,
+                   uint64_t *distorted_mask_out);
+
+/* Upper bound gamma on c_max^(q): Eq. 5 with mu_1 = 1/r (Lemma 2) put into Claim 1.
+ * Returns NaN if g is NULL or q is outside [0, K]. */
+double byz_gamma_bound(const byz_assignment *g, int q);
+
+/* --------------------------------------------------------------- device: vote (Eq. 3) */
+
+/*
+ * Majority vote per file.
+ *   copies        device [R][ld] fp32 (R = f*r rows are addressed through file_rows_dev)
+ *   file_rows_dev device [f*r] int32, as written by byz_assignment_file_rows
+ *   winner_replica device [f] int32 out: smallest replica index among the copies that
+ *                 appear most often (ties between equally frequent values go to the value
+ *                 held by the lowest replica index; the paper leaves ties open)
+ *   winner_row    device [f] int32 out: file_rows[j][winner_replica[j]]
+ *   pair_neq      device [f] uint32 out: bit p set iff the two copies of pair p differ,
+ *                 pairs (a,b), a < b, numbered lexicographically (0,1),(0,2),..,(1,2),..
+ * Errors: BYZ_EINVAL (null pointers, d < 0, ld < d, f outside [1,64], r even or outside
+ * [3,7]), BYZ_EDEVICE.  Row indices are trusted (not range-checked on the device).
+ * d == 0: every copy is equal (winner 0, pair_neq 0).
+ */
+int byz_vote(const float *copies, int64_t d, int64_t ld, const int32_t *file_rows_dev, int f,
+             int r, int32_t *winner_replica, int32_t *winner_row, uint32_t *pair_neq,
+             void *stream);
+
+/* --------------------------------------------- device: coordinate-wise median (Sec. 2, 6.1) */
+
+/*
+ * out[c] = element of rank (f-1)/2 of { rows_base[row_index[j]*ld + c] : j < f }.
+ *   rows_base     device [*][ld] fp32;  row_index_dev device [f] int32;  out device [d] fp32,
+ *                 must not overlap the input rows (may be NULL when d == 0).
+ * f odd, 1 <= f <= 64; f in {3,5,7,9,25,49} runs a register selection network, other odd f
+ * a slower generic kernel.  Errors: BYZ_EINVAL, BYZ_EUNSUPPORTED (even f), BYZ_EDEVICE.
+ */
+int byz_median(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev,
+               int f, float *out, void *stream);
+
+/* --------------------------------------------------- device: fused vote + median (whole path) */
+
+/* Bytes of device scratch byz_aggregate needs for (f, r); 0 if (f, r) is invalid. */
+size_t byz_aggregate_workspace_bytes(int f, int r);
+
+/*
+ * Whole path in one pass over the R*d inputs: out = median over files of the vote winners,
+ * exactly the result of byz_vote followed by byz_median on winner_row.
+ *   out            device [d] fp32
+ *   winner_replica device [f] int32 out, may be NULL
+ *   workspace      device, >= byz_aggregate_workspace_bytes(f, r) bytes, 256-byte aligned,
+ *                  contents irrelevant on entry; calls sharing a workspace must not overlap.
+ * A small probe compares the copies on a sample of coordinates; the streaming pass then
+ * feeds the probable winner of each file to the median network while checking, over all d
+ * coordinates, every equality the probe assumed.  If a check fails (a copy that matches on
+ * the sample but differs elsewhere) the exact two-step path (vote, then median) runs on the
+ * device right after; the result is the same, only slower.
+ * Errors: as byz_vote / byz_median, plus BYZ_ENOMEM (workspace too small).
+ */
+int byz_aggregate(const float *copies, int64_t d, int64_t ld, const int32_t *file_rows_dev,
+                  int f, int r, float *out, int32_t *winner_replica, void *workspace,
+                  size_t workspace_bytes, void *stream);
+
+/*
+ * After byz_aggregate's work on `stream` has completed: copies 0/1 into *took_exact_path
+ * (host) from the workspace (device) -- 1 if the two-step path had to run.  Synchronises the
+ * stream.  Diagnostic only.
+ */
+int byz_aggregate_took_exact_path(const void *workspace, int *took_exact_path, void *stream);
+
+/* ------------------------------------------------------------------------- measurement */
+
+/*
+ * Timing aid for benchmarks.  byz_profile_enable(n) with n > 0 creates n HIP event pairs for
+ * the calling thread; from then on each byz_aggregate call of that thread that runs the
+ * single-pass kernel records one pair around that kernel (its main launch, not the probe or
+ * the finalisation) on the call's stream, until n calls have been recorded.
+ * byz_profile_enable(0) releases the events.  Errors: BYZ_EINVAL (n < 0 or n > 100000),
+ * BYZ_ENOMEM, BYZ_EDEVICE.
+ * byz_profile_collect waits for the recorded events, writes the kernel durations in
+ * milliseconds to host ms_out[0..*n_out-1] (at most `capacity`), and restarts recording at
+ * the first pair.
+ */
+int byz_profile_enable(int max_calls);
+int byz_profile_collect(float *ms_out, int capacity, int *n_out);
+
+/* ------------------------------------------------------------------------------ misc */
+
+const char *byz_strerror(int code);
+
+/* hipError_t of the last failing HIP call on this thread (0 if none), for BYZ_EDEVICE. */
+int byz_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BYZSHIELD_H */

@@ -1,0 +1,23 @@
+"""ByzShield parameter-server aggregation (majority vote + coordinate-wise median) on MI355X.
+
+Thin Python binding over the C-ABI of libbyzshield.so; every step of the path runs in the
+library's HIP kernels / host code.  PyTorch is used for device memory and streams only.
+"""
+from .binding import (  # noqa: F401
+    BYZ_SCHEME_MOLS,
+    BYZ_SCHEME_RAMANUJAN,
+    Assignment,
+    ByzError,
+    byz_aggregate,
+    byz_aggregate_took_exact_path,
+    byz_aggregate_workspace_bytes,
+    byz_build_assignment,
+    byz_gamma_bound,
+    byz_median,
+    byz_profile_collect,
+    byz_profile_enable,
+    byz_strerror,
+    byz_vote,
+    byz_worst_case,
+    library_path,
+)

@@ -1,0 +1,238 @@
+"""ctypes binding of libbyzshield.so: same names as the C-ABI, argument marshalling only.
+
+Device arguments are torch CUDA tensors (their data_ptr() is passed through); outputs that
+the caller does not supply are allocated with torch.  There is no CPU fallback: if the
+library cannot be loaded the import of this module's functions raises.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libbyzshield.so")
+
+BYZ_SCHEME_MOLS = 0
+BYZ_SCHEME_RAMANUJAN = 1
+BYZ_MAX_F = 64
+BYZ_MAX_R = 7
+
+_lib = None
+
+
+class ByzError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        msg = "%s failed: %d (%s)" % (where, code, byz_strerror(code))
+        if code == -4:
+            msg += ", hipError_t=%d" % _load().byz_last_hip_error()
+        super().__init__(msg)
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        # nothing built yet: build once, loudly
+        from . import build as _build
+        _build.build()
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i32p, u32p, u64p = (ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32),
+                            ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_uint64))
+    ip = ctypes.POINTER(ctypes.c_int)
+    c_int, i64, sz = ctypes.c_int, ctypes.c_int64, ctypes.c_size_t
+    sig = {
+        "byz_build_assignment": (c_int, [c_int, c_int, c_int, ctypes.POINTER(vp)]),
+        "byz_free_assignment": (None, [vp]),
+        "byz_assignment_dims": (c_int, [vp, ip, ip, ip, ip]),
+        "byz_assignment_worker_files": (c_int, [vp, i32p]),
+        "byz_assignment_file_workers": (c_int, [vp, i32p]),
+        "byz_assignment_file_rows": (c_int, [vp, i32p]),
+        "byz_worst_case": (c_int, [vp, c_int, i32p, i32p, u64p]),
+        "byz_gamma_bound": (ctypes.c_double, [vp, c_int]),
+        "byz_vote": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, vp]),
+        "byz_median": (c_int, [vp, i64, i64, vp, c_int, vp, vp]),
+        "byz_aggregate_workspace_bytes": (sz, [c_int, c_int]),
+        "byz_aggregate": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, sz, vp]),
+        "byz_aggregate_took_exact_path": (c_int, [vp, ip, vp]),
+        "byz_profile_enable": (c_int, [c_int]),
+        "byz_profile_collect": (c_int, [ctypes.POINTER(ctypes.c_float), c_int, ip]),
+        "byz_strerror": (ctypes.c_char_p, [c_int]),
+        "byz_last_hip_error": (c_int, []),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = L
+    return L
+
+
+def _check(code, where):
+    if code != 0:
+        raise ByzError(code, where)
+
+
+def byz_strerror(code):
+    return _load().byz_strerror(int(code)).decode()
+
+
+class Assignment:
+    """Owns a byz_assignment handle (worker-file graph of Sec. 4)."""
+
+    def __init__(self, handle):
+        self._h = handle
+        K, f, l, r = (ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), ctypes.c_int())
+        _check(_load().byz_assignment_dims(self._h, K, f, l, r), "byz_assignment_dims")
+        self.K, self.f, self.l, self.r = K.value, f.value, l.value, r.value
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.byz_free_assignment(self._h)
+            self._h = None
+
+    def _table(self, fn, rows, cols):
+        out = np.zeros((rows, cols), dtype=np.int32)
+        _check(getattr(_load(), fn)(self._h, out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))), fn)
+        return out
+
+    def worker_files(self):
+        return self._table("byz_assignment_worker_files", self.K, self.l)
+
+    def file_workers(self):
+        return self._table("byz_assignment_file_workers", self.f, self.r)
+
+    def file_rows(self):
+        return self._table("byz_assignment_file_rows", self.f, self.r)
+
+
+def byz_build_assignment(scheme, a, b):
+    h = ctypes.c_void_p()
+    _check(_load().byz_build_assignment(int(scheme), int(a), int(b), ctypes.byref(h)),
+           "byz_build_assignment")
+    return Assignment(h)
+
+
+def byz_worst_case(asg, q):
+    """Returns (byzantine workers as a tuple, c_max, distorted-file bit mask)."""
+    S = np.zeros(max(int(q), 1), dtype=np.int32)
+    cmax = ctypes.c_int32()
+    mask = ctypes.c_uint64()
+    _check(_load().byz_worst_case(asg._h, int(q), S.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                  ctypes.byref(cmax), ctypes.byref(mask)), "byz_worst_case")
+    return tuple(int(x) for x in S[:max(int(q), 0)]), int(cmax.value), int(mask.value)
+
+
+def byz_gamma_bound(asg, q):
+    return float(_load().byz_gamma_bound(asg._h, int(q)))
+
+
+# ------------------------------------------------------------------ device entry points
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        stream = _torch().cuda.current_stream()
+    return ctypes.c_void_p(getattr(stream, "cuda_stream", stream))
+
+
+def _dev_ptr(t, dtype_names, what):
+    if not t.is_cuda:
+        raise ValueError("%s must be a CUDA tensor" % what)
+    if str(t.dtype).replace("torch.", "") not in dtype_names:
+        raise ValueError("%s has dtype %s" % (what, t.dtype))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % what)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _rows_2d(copies):
+    if copies.dim() != 2:
+        raise ValueError("copies must be [rows, ld]")
+    return int(copies.shape[1])
+
+
+def byz_vote(copies, d, file_rows_dev, f, r, stream=None):
+    """-> (winner_replica[f] int32, winner_row[f] int32, pair_neq[f] int32 bit masks), on device."""
+    torch = _torch()
+    ld = _rows_2d(copies)
+    wrep = torch.empty(f, dtype=torch.int32, device=copies.device)
+    wrow = torch.empty(f, dtype=torch.int32, device=copies.device)
+    neq = torch.empty(f, dtype=torch.int32, device=copies.device)
+    _check(_load().byz_vote(_dev_ptr(copies, ("float32",), "copies"), int(d), ld,
+                            _dev_ptr(file_rows_dev, ("int32",), "file_rows_dev"), int(f), int(r),
+                            _dev_ptr(wrep, ("int32",), "winner_replica"),
+                            _dev_ptr(wrow, ("int32",), "winner_row"),
+                            _dev_ptr(neq, ("int32",), "pair_neq"), _stream_ptr(stream)),
+           "byz_vote")
+    return wrep, wrow, neq
+
+
+def byz_median(rows_base, d, row_index_dev, out=None, stream=None):
+    torch = _torch()
+    ld = _rows_2d(rows_base)
+    f = int(row_index_dev.numel())
+    if out is None:
+        out = torch.empty(int(d), dtype=torch.float32, device=rows_base.device)
+    _check(_load().byz_median(_dev_ptr(rows_base, ("float32",), "rows_base"), int(d), ld,
+                              _dev_ptr(row_index_dev, ("int32",), "row_index_dev"), f,
+                              _dev_ptr(out, ("float32",), "out"), _stream_ptr(stream)),
+           "byz_median")
+    return out
+
+
+def byz_aggregate_workspace_bytes(f, r):
+    return int(_load().byz_aggregate_workspace_bytes(int(f), int(r)))
+
+
+def byz_aggregate(copies, d, file_rows_dev, f, r, out=None, winner_replica=None, workspace=None,
+                  stream=None):
+    """-> (out[d] float32, winner_replica[f] int32, workspace uint8 tensor), on device."""
+    torch = _torch()
+    ld = _rows_2d(copies)
+    if out is None:
+        out = torch.empty(int(d), dtype=torch.float32, device=copies.device)
+    if winner_replica is None:
+        winner_replica = torch.empty(int(f), dtype=torch.int32, device=copies.device)
+    if workspace is None:
+        nbytes = byz_aggregate_workspace_bytes(f, r)
+        if nbytes == 0:
+            raise ByzError(-1, "byz_aggregate_workspace_bytes")
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=copies.device)
+    _check(_load().byz_aggregate(_dev_ptr(copies, ("float32",), "copies"), int(d), ld,
+                                 _dev_ptr(file_rows_dev, ("int32",), "file_rows_dev"), int(f),
+                                 int(r), _dev_ptr(out, ("float32",), "out"),
+                                 _dev_ptr(winner_replica, ("int32",), "winner_replica"),
+                                 _dev_ptr(workspace, ("uint8",), "workspace"),
+                                 int(workspace.numel()), _stream_ptr(stream)), "byz_aggregate")
+    return out, winner_replica, workspace
+
+
+def byz_aggregate_took_exact_path(workspace, stream=None):
+    flag = ctypes.c_int()
+    _check(_load().byz_aggregate_took_exact_path(_dev_ptr(workspace, ("uint8",), "workspace"),
+                                                 ctypes.byref(flag), _stream_ptr(stream)),
+           "byz_aggregate_took_exact_path")
+    return bool(flag.value)
+
+
+def byz_profile_enable(max_calls):
+    _check(_load().byz_profile_enable(int(max_calls)), "byz_profile_enable")
+
+
+def byz_profile_collect(capacity):
+    """-> list of single-pass kernel durations (ms) recorded since the last collect."""
+    buf = (ctypes.c_float * max(int(capacity), 1))()
+    n = ctypes.c_int()
+    _check(_load().byz_profile_collect(buf, int(capacity), ctypes.byref(n)), "byz_profile_collect")
+    return [float(buf[i]) for i in range(n.value)]

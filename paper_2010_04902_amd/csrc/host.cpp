@@ -1,0 +1,289 @@
+// Host side of libbyzshield: worker-file assignment graphs (Sec. 4 of the ByzShield paper)
+// and the exhaustive worst-case adversary search (Sec. 5.3.2).  No GPU is touched here.
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "byzshield.h"
+
+struct byz_assignment {
+    int scheme = 0;
+    int K = 0, f = 0, l = 0, r = 0;
+    int class_size = 0;    // workers per parallel class (one replica of every file per class)
+    int shared_lo = 0;     // two workers of different classes share between shared_lo and
+    int shared_hi = 0;     // shared_hi files
+    std::vector<int32_t> worker_files;  // [K][l] ascending
+    std::vector<int32_t> file_workers;  // [f][r] ascending = class order
+    std::vector<int32_t> file_rows;     // [f][r]
+};
+
+namespace {
+
+bool is_prime(int n) {
+    if (n < 2) return false;
+    for (int p = 2; (int64_t)p * p <= n; ++p)
+        if (n % p == 0) return false;
+    return true;
+}
+
+inline int mod(int64_t x, int m) {
+    int64_t t = x % m;
+    return (int)(t < 0 ? t + m : t);
+}
+
+// Fills per-class "which worker of class k holds file j".  All three constructions are lines
+// of the affine plane over F_p: file (x, y) belongs to the class-k worker whose index inside
+// the class is the value of a linear form in (x, y).
+//   MOLS, Algorithm 2: file i*l+j, class k (square L_{k+1}) -> symbol (k+1)*i + j.
+//   Ramanujan Case 2 (H = B): worker a*s+u holds file b*s+v iff v = u - a*b, so file (b, v)
+//     is held in class a by u = v + a*b.
+//   Ramanujan Case 1 (H = B^T): worker b*s+v holds file a*s+u iff u = v + a*b, so file
+//     (a, u) is held in class b by v = u - a*b.
+int holder_in_class(int scheme, bool case2, int p, int k, int x, int y) {
+    if (scheme == BYZ_SCHEME_MOLS) return mod((int64_t)(k + 1) * x + y, p);
+    if (case2) return mod((int64_t)y + (int64_t)k * x, p);
+    return mod((int64_t)y - (int64_t)k * x, p);
+}
+
+int check_invariants(const byz_assignment &g) {
+    const int K = g.K, f = g.f, l = g.l, r = g.r;
+    if ((int64_t)K * l != (int64_t)f * r) return BYZ_EINTERNAL;
+    std::vector<uint8_t> H((size_t)K * f, 0);
+    for (int w = 0; w < K; ++w) {
+        for (int t = 0; t < l; ++t) {
+            int j = g.worker_files[(size_t)w * l + t];
+            if (j < 0 || j >= f) return BYZ_EINTERNAL;
+            if (t > 0 && g.worker_files[(size_t)w * l + t - 1] >= j) return BYZ_EINTERNAL;
+            H[(size_t)w * f + j] = 1;
+        }
+    }
+    // every file on exactly r workers, one per parallel class, listed in class order
+    for (int j = 0; j < f; ++j) {
+        int cnt = 0;
+        for (int w = 0; w < K; ++w) cnt += H[(size_t)w * f + j];
+        if (cnt != r) return BYZ_EINTERNAL;
+        for (int k = 0; k < r; ++k) {
+            int w = g.file_workers[(size_t)j * r + k];
+            if (w < 0 || w >= K || !H[(size_t)w * f + j]) return BYZ_EINTERNAL;
+            if (w / g.class_size != k) return BYZ_EINTERNAL;
+            int row = g.file_rows[(size_t)j * r + k];
+            if (row / l != w || g.worker_files[row] != j) return BYZ_EINTERNAL;
+        }
+    }
+    // Latin-square / orthogonality consequences (Sec. 4.1.2): same class -> no common file,
+    // different classes -> exactly one (more only for Ramanujan Case 2 with m > s)
+    if ((double)K * K * f > 2e9) return BYZ_OK;  // pairwise check only where it is cheap
+    for (int u = 0; u < K; ++u)
+        for (int v = u + 1; v < K; ++v) {
+            int common = 0;
+            for (int j = 0; j < f; ++j) common += H[(size_t)u * f + j] & H[(size_t)v * f + j];
+            if (u / g.class_size == v / g.class_size) {
+                if (common != 0) return BYZ_EINTERNAL;
+            } else if (common < g.shared_lo || common > g.shared_hi) {
+                return BYZ_EINTERNAL;
+            }
+        }
+    return BYZ_OK;
+}
+
+}  // namespace
+
+extern "C" int byz_build_assignment(int scheme, int a, int b, byz_assignment **out) {
+    if (!out) return BYZ_EINVAL;
+    *out = nullptr;
+    if (scheme != BYZ_SCHEME_MOLS && scheme != BYZ_SCHEME_RAMANUJAN) return BYZ_EINVAL;
+    if (a < 2 || a > 255) return BYZ_EINVAL;
+    int K, f, l, r, classes, class_size, gx, gy;  // files form a gx x gy grid, index x*gy + y
+    bool case2 = false;
+    if (scheme == BYZ_SCHEME_MOLS) {
+        if (b < 1 || b > a - 1) return BYZ_EINVAL;  // Algorithm 2 needs r <= l-1
+        if (!is_prime(a)) return BYZ_EUNSUPPORTED;
+        l = a; r = b; K = r * l; f = l * l; classes = r; class_size = l; gx = l; gy = l;
+    } else {
+        const int s = a, m = b;
+        if (m < 2 || m > 255) return BYZ_EINVAL;
+        if (!is_prime(s)) return BYZ_EUNSUPPORTED;
+        if (m >= s) {  // Eq. 6, Case 2
+            case2 = true;
+            K = s * s; f = m * s; l = m; r = s; classes = s; class_size = s; gx = m; gy = s;
+        } else {  // Eq. 6, Case 1
+            K = m * s; f = s * s; l = s; r = m; classes = m; class_size = s; gx = s; gy = s;
+        }
+    }
+    byz_assignment *g = new (std::nothrow) byz_assignment();
+    if (!g) return BYZ_ENOMEM;
+    try {
+        g->scheme = scheme; g->K = K; g->f = f; g->l = l; g->r = r; g->class_size = class_size;
+        if (case2 && l > class_size) {
+            g->shared_lo = l / class_size;
+            g->shared_hi = (l + class_size - 1) / class_size;
+        } else {
+            g->shared_lo = g->shared_hi = 1;
+        }
+        g->worker_files.assign((size_t)K * l, -1);
+        g->file_workers.assign((size_t)f * r, -1);
+        g->file_rows.assign((size_t)f * r, -1);
+        std::vector<int> fill((size_t)K, 0);
+        // files in ascending order, so each worker's list comes out ascending
+        for (int x = 0; x < gx; ++x)
+            for (int y = 0; y < gy; ++y) {
+                const int j = x * gy + y;
+                for (int k = 0; k < classes; ++k) {
+                    const int w = k * class_size + holder_in_class(scheme, case2, a, k, x, y);
+                    if (fill[w] >= l) { delete g; return BYZ_EINTERNAL; }
+                    g->worker_files[(size_t)w * l + fill[w]] = j;
+                    g->file_workers[(size_t)j * r + k] = w;
+                    g->file_rows[(size_t)j * r + k] = w * l + fill[w];
+                    ++fill[w];
+                }
+            }
+        for (int w = 0; w < K; ++w)
+            if (fill[w] != l) { delete g; return BYZ_EINTERNAL; }
+        int rc = check_invariants(*g);
+        if (rc != BYZ_OK) { delete g; return rc; }
+    } catch (const std::bad_alloc &) {
+        delete g;
+        return BYZ_ENOMEM;
+    }
+    *out = g;
+    return BYZ_OK;
+}
+
+extern "C" void byz_free_assignment(byz_assignment *g) { delete g; }
+
+extern "C" int byz_assignment_dims(const byz_assignment *g, int *K, int *f, int *l, int *r) {
+    if (!g) return BYZ_EINVAL;
+    if (K) *K = g->K;
+    if (f) *f = g->f;
+    if (l) *l = g->l;
+    if (r) *r = g->r;
+    return BYZ_OK;
+}
+
+extern "C" int byz_assignment_worker_files(const byz_assignment *g, int32_t *out) {
+    if (!g || !out) return BYZ_EINVAL;
+    std::memcpy(out, g->worker_files.data(), g->worker_files.size() * sizeof(int32_t));
+    return BYZ_OK;
+}
+
+extern "C" int byz_assignment_file_workers(const byz_assignment *g, int32_t *out) {
+    if (!g || !out) return BYZ_EINVAL;
+    std::memcpy(out, g->file_workers.data(), g->file_workers.size() * sizeof(int32_t));
+    return BYZ_OK;
+}
+
+extern "C" int byz_assignment_file_rows(const byz_assignment *g, int32_t *out) {
+    if (!g || !out) return BYZ_EINVAL;
+    std::memcpy(out, g->file_rows.data(), g->file_rows.size() * sizeof(int32_t));
+    return BYZ_OK;
+}
+
+// ------------------------------------------------------------------ worst-case search
+
+namespace {
+
+// Per-file copy counters for up to 64 files, one bit plane per binary digit (counts <= 7).
+struct Planes {
+    uint64_t c0, c1, c2;
+};
+
+inline Planes add_mask(Planes p, uint64_t m) {
+    uint64_t carry = p.c0 & m;
+    p.c0 ^= m;
+    uint64_t carry2 = p.c1 & carry;
+    p.c1 ^= carry;
+    p.c2 ^= carry2;
+    return p;
+}
+
+// bit j set iff count_j >= need, need in 1..4
+inline uint64_t at_least(const Planes &p, int need) {
+    switch (need) {
+        case 1: return p.c0 | p.c1 | p.c2;
+        case 2: return p.c1 | p.c2;
+        case 3: return p.c2 | (p.c1 & p.c0);
+        default: return p.c2;
+    }
+}
+
+}  // namespace
+
+extern "C" int byz_worst_case(const byz_assignment *g, int q, int32_t *byz_workers_out,
+                              int32_t *cmax_out, uint64_t *distorted_mask_out) {
+    if (!g || q < 0 || q > g->K) return BYZ_EINVAL;
+    if (g->f > BYZ_MAX_F || g->r > BYZ_MAX_R) return BYZ_EUNSUPPORTED;
+    const int K = g->K, l = g->l;
+    const int need = (g->r + 1) / 2;  // r' of Sec. 2
+    std::vector<uint64_t> mask((size_t)K, 0);
+    for (int w = 0; w < K; ++w)
+        for (int t = 0; t < l; ++t) mask[w] |= 1ull << g->worker_files[(size_t)w * l + t];
+
+    int best = -1;
+    uint64_t best_files = 0;
+    std::vector<int> cur((size_t)q + 1, 0), best_set((size_t)q, 0);
+    if (q == 0) {
+        best = 0;
+    } else {
+        // depth-first over ascending tuples = lexicographic order; planes[t] = counters of the
+        // first t chosen workers.  The last position is swept in a tight loop.
+        std::vector<Planes> planes((size_t)q + 1, Planes{0, 0, 0});
+        int t = 0;
+        cur[0] = -1;
+        for (;;) {
+            // advance position t
+            ++cur[t];
+            if (cur[t] > K - (q - t)) {  // exhausted this position
+                if (t == 0) break;
+                --t;
+                continue;
+            }
+            if (t < q - 1) {
+                planes[t + 1] = add_mask(planes[t], mask[cur[t]]);
+                cur[t + 1] = cur[t];
+                ++t;
+                continue;
+            }
+            // last position: sweep all remaining workers
+            const Planes base = planes[t];
+            for (int w = cur[t]; w < K; ++w) {
+                const uint64_t hit = at_least(add_mask(base, mask[w]), need);
+                const int c = __builtin_popcountll(hit);
+                if (c > best) {
+                    best = c;
+                    best_files = hit;
+                    for (int i = 0; i < t; ++i) best_set[i] = cur[i];
+                    best_set[t] = w;
+                }
+            }
+            if (t == 0) break;
+            --t;
+        }
+    }
+    if (byz_workers_out)
+        for (int i = 0; i < q; ++i) byz_workers_out[i] = best_set[i];
+    if (cmax_out) *cmax_out = best;
+    if (distorted_mask_out) *distorted_mask_out = best_files;
+    return BYZ_OK;
+}
+
+extern "C" double byz_gamma_bound(const byz_assignment *g, int q) {
+    if (!g || q < 0 || q > g->K) return std::nan("");
+    const double K = g->K, l = g->l, r = g->r;
+    const double mu1 = 1.0 / r;                                      // Lemma 2
+    const double beta = (q * l / r) / (mu1 + (1.0 - mu1) * q / K);   // Eq. 5
+    return (q * l - beta) / ((r - 1.0) / 2.0);                       // Claim 1
+}
+
+extern "C" const char *byz_strerror(int code) {
+    switch (code) {
+        case BYZ_OK: return "ok";
+        case BYZ_EINVAL: return "invalid argument";
+        case BYZ_EUNSUPPORTED: return "valid but not supported by this build";
+        case BYZ_ENOMEM: return "out of memory or workspace too small";
+        case BYZ_EDEVICE: return "HIP call failed";
+        case BYZ_EINTERNAL: return "internal invariant violated";
+        default: return "unknown byz_status";
+    }
+}

@@ -1,0 +1,29 @@
+"""The five workloads: cluster shapes of the paper's tables with seeded Gaussian gradients.
+
+scheme/a/b follow the library's byz_build_assignment arguments: MOLS (l, r) or
+Ramanujan (s, m).  `cmax` is the value the paper's Tables 3, 4, 6 print for that (graph, q).
+"""
+from collections import namedtuple
+
+Config = namedtuple("Config", "name scheme a b K f l r q cmax d attack steps seed")
+
+MOLS, RAMANUJAN = 0, 1
+
+CONFIGS = [
+    # MOLS l=5, r=3, reversed gradient x(-100), d = 2^20, q = 3
+    Config("cfg1_mols5x3_d1M_reversed", MOLS, 5, 3, 15, 25, 5, 3, 3, 3, 1 << 20,
+           {"kind": "reversed", "c": 100.0}, 1, 20101004 + 0),
+    # ResNet-18-sized d, MOLS l=5, r=3, ALIE z=1.0, q = 4   (the headline workload)
+    Config("cfg2_mols5x3_resnet18_alie", MOLS, 5, 3, 15, 25, 5, 3, 4, 5, 11173962,
+           {"kind": "alie", "z": 1.0}, 1, 20101004 + 1),
+    # MOLS l=7, r=3, reversed gradient, q = 5
+    Config("cfg3_mols7x3_resnet18_reversed", MOLS, 7, 3, 21, 49, 7, 3, 5, 8, 11173962,
+           {"kind": "reversed", "c": 100.0}, 1, 20101004 + 2),
+    # K=25, f=25, r=l=5: the paper's Ramanujan Case 2 cluster (m=s=5), mixed ALIE / constant,
+    # per-file gradient scale U(0.5, 2), q = 6
+    Config("cfg4_ram5x5_resnet18_mixed", RAMANUJAN, 5, 5, 25, 25, 5, 5, 6, 4, 11173962,
+           {"kind": "mixed", "z": 1.0, "value": 1e3, "file_scales": True}, 1, 20101004 + 3),
+    # ResNet-50-sized d, MOLS l=7, r=3, ALIE z=1.5, q = 6, 20 steps of fresh gradients
+    Config("cfg5_mols7x3_resnet50_alie_20steps", MOLS, 7, 3, 21, 49, 7, 3, 6, 12, 25557032,
+           {"kind": "alie", "z": 1.5}, 20, 20101004 + 4),
+]

@@ -1,0 +1,84 @@
+"""GPU parity at the five workloads' full sizes, in the launch configuration bench.py times.
+
+Configs 1-4 and two steps of config 5: every output word against the C oracle run on the
+same bytes (copied back from the device).  The other steps of config 5: the oracle on a
+sample of coordinates (columns gathered from the device buffer).
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2010_04902_amd as B
+import synth
+from oracle import c_oracle as C
+from tests import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _full_check(w, tag):
+    rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+    out, wrep, ws = B.byz_aggregate(w.X, w.d, rows_dev, w.f, w.r)
+    wrep_v, wrow_v, neq_v = B.byz_vote(w.X, w.d, rows_dev, w.f, w.r)
+    out_m = B.byz_median(w.X, w.d, wrow_v)
+    torch.cuda.synchronize()
+    took_exact = B.byz_aggregate_took_exact_path(ws)
+    Xh = w.X.cpu().numpy()
+    wrep_o, wrow_o, neq_o = C.vote(Xh, w.file_rows, w.d)
+    out_o = C.median(Xh, wrow_o, w.d)
+    del Xh
+    assert np.array_equal(wrep.cpu().numpy(), wrep_o), tag
+    assert np.array_equal(wrep_v.cpu().numpy(), wrep_o), tag
+    assert np.array_equal(wrow_v.cpu().numpy(), wrow_o), tag
+    assert np.array_equal(W.bits(neq_v), neq_o), tag
+    assert np.array_equal(W.bits(out), W.bits(out_o)), tag
+    assert np.array_equal(W.bits(out_m), W.bits(out_o)), tag
+    assert not took_exact, tag  # these attacks differ from the honest copy on the probe sample
+    # Sec. 2: exactly the files with >= r' Byzantine copies lose the vote; the paper's c_max
+    wrong = 0
+    for j in range(w.f):
+        byz_copies = sum(1 for k in range(w.r) if int(w.file_workers[j, k]) in w.byz)
+        honest_wins = int(w.file_workers[j, wrep_o[j]]) not in w.byz
+        assert honest_wins == (byz_copies < (w.r + 1) // 2), (tag, j)
+        wrong += 0 if honest_wins else 1
+    return wrong
+
+
+@pytest.mark.parametrize("idx,padded", [(0, False), (1, False), (1, True), (2, True), (3, True),
+                                        (3, False)])
+def test_config_full_size(idx, padded):
+    cfg = synth.CONFIGS[idx]
+    ld = synth.padded_ld(cfg.d, 64) if padded else cfg.d
+    w = W.from_config(cfg, DEV, ld=ld)
+    assert (w.K, w.f, w.l, w.r) == (cfg.K, cfg.f, cfg.l, cfg.r) and w.cmax == cfg.cmax
+    wrong = _full_check(w, cfg.name)
+    assert wrong == cfg.cmax  # number of distorted files = the paper's c_max for this (graph, q)
+
+
+def test_config5_twenty_steps():
+    cfg = synth.CONFIGS[4]
+    ld = synth.padded_ld(cfg.d, 64)
+    rng = np.random.default_rng(55)
+    cols = np.unique(np.concatenate([np.arange(0, 2048), np.arange(cfg.d - 2048, cfg.d),
+                                     rng.integers(0, cfg.d, size=8192)])).astype(np.int64)
+    cols_dev = torch.tensor(cols, device=DEV)
+    prev = None
+    for step in range(cfg.steps):
+        w = W.from_config(cfg, DEV, step=step, ld=ld)
+        if step in (0, cfg.steps - 1):
+            assert _full_check(w, (cfg.name, step)) == cfg.cmax
+        else:
+            rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+            out, wrep, ws = B.byz_aggregate(w.X, w.d, rows_dev, w.f, w.r)
+            torch.cuda.synchronize()
+            Xs = w.X[:, cols_dev].contiguous().cpu().numpy()  # [R, n] sampled columns
+            out_o, wrep_o, _ = C.aggregate(Xs, w.file_rows, len(cols))
+            assert np.array_equal(W.bits(out[cols_dev]), W.bits(out_o)), step
+            assert np.array_equal(wrep.cpu().numpy(), wrep_o), step
+            assert not B.byz_aggregate_took_exact_path(ws)
+        # fresh gradients every step
+        head = w.X[0, :64].clone()
+        assert prev is None or not torch.equal(head, prev)
+        prev = head
+        del w

@@ -1,0 +1,236 @@
+"""GPU parity: the HIP path through the C-ABI against the CPU oracle, bit for bit.
+
+Vote and odd-count median are pure selection, so the bar is exact equality of every output
+word (winner indices, pair bits, median bit patterns).
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2010_04902_amd as B
+import synth
+from oracle import byz_oracle as O
+from oracle import c_oracle as C
+from tests import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+MOLS, RAM = B.BYZ_SCHEME_MOLS, B.BYZ_SCHEME_RAMANUJAN
+
+REVERSED = {"kind": "reversed", "c": 100.0}
+ALIE = {"kind": "alie", "z": 1.0}
+CONST = {"kind": "constant", "value": 1e3}
+MIXED = {"kind": "mixed", "z": 1.0, "value": 1e3, "file_scales": True}
+
+
+def _check_all(X, rows_np, d, f, r, expect_exact=None, tag=""):
+    """Runs vote, median-on-winners and aggregate on the GPU and compares with the oracle."""
+    Xh = X.detach().cpu().numpy()
+    rows_dev = torch.tensor(rows_np.reshape(-1), dtype=torch.int32, device=DEV)
+    wrep_o, wrow_o, neq_o = C.vote(Xh, rows_np, d)
+    out_o = C.median(Xh, wrow_o, d)
+
+    wrep, wrow, neq = B.byz_vote(X, d, rows_dev, f, r)
+    torch.cuda.synchronize()
+    assert np.array_equal(wrep.cpu().numpy(), wrep_o), tag
+    assert np.array_equal(wrow.cpu().numpy(), wrow_o), tag
+    assert np.array_equal(W.bits(neq), neq_o), tag
+
+    out_m = B.byz_median(X, d, wrow)
+    torch.cuda.synchronize()
+    assert np.array_equal(W.bits(out_m), W.bits(out_o)), tag
+
+    out, wrep2, ws = B.byz_aggregate(X, d, rows_dev, f, r)
+    torch.cuda.synchronize()
+    assert np.array_equal(W.bits(out), W.bits(out_o)), tag
+    assert np.array_equal(wrep2.cpu().numpy(), wrep_o), tag
+    took_exact = B.byz_aggregate_took_exact_path(ws)
+    if expect_exact is not None:
+        assert took_exact == expect_exact, tag
+    return out_o, wrep_o, took_exact
+
+
+SMALL_D = [1, 2, 3, 5, 63, 64, 255, 1000, 4099, 70001]
+
+
+@pytest.mark.parametrize("scheme,a,b,q,attack", [
+    (MOLS, 5, 3, 3, REVERSED), (MOLS, 5, 3, 4, ALIE), (MOLS, 7, 3, 5, REVERSED),
+    (RAM, 5, 5, 6, MIXED), (MOLS, 7, 3, 6, ALIE), (RAM, 3, 3, 2, CONST), (MOLS, 7, 5, 5, MIXED),
+    (RAM, 5, 3, 3, CONST)])
+def test_small_sizes_all_layouts(scheme, a, b, q, attack):
+    # sizes below one tile, several tiles and ragged tails; row pitches that give 16-byte,
+    # 8-byte and 4-byte aligned rows
+    for i, d in enumerate(SMALL_D):
+        for ld in sorted({d, d + (-d) % 2, synth.padded_ld(d, 4), synth.padded_ld(d, 64)}):
+            w = W.make(scheme, a, b, q, d, attack, seed=100 + i, ld=ld, device=DEV)
+            out_o, wrep_o, _ = _check_all(w.X, w.file_rows, d, w.f, w.r, tag=(d, ld))
+
+
+def test_all_honest_reproduces_the_honest_median():
+    w = W.make(MOLS, 5, 3, 0, 5000, REVERSED, seed=1, device=DEV)
+    out_o, wrep_o, took_exact = _check_all(w.X, w.file_rows, w.d, w.f, w.r, expect_exact=False)
+    assert (wrep_o == 0).all()
+    honest = np.median(w.G.cpu().numpy(), axis=0)
+    assert np.array_equal(W.bits(out_o), W.bits(honest))
+
+
+def test_unaligned_base_pointer():
+    # a view that starts 4 bytes into an allocation: only dword alignment is guaranteed
+    w = W.make(MOLS, 5, 3, 4, 3001, ALIE, seed=2, device=DEV)
+    R, ld = w.X.shape
+    buf = torch.empty(R * ld + 1, dtype=torch.float32, device=DEV)
+    Xs = buf[1:].view(R, ld)
+    Xs.copy_(w.X)
+    assert Xs.data_ptr() % 8 == 4
+    _check_all(Xs, w.file_rows, w.d, w.f, w.r, expect_exact=False)
+
+
+def test_generic_shapes_without_a_generated_network():
+    # f = 15 (Ramanujan s=3, m=5): two-step path and rank-counting median;
+    # r = 7 (Ramanujan s=7, m=7): two-step path with the f = 49 network
+    for (a, b, q) in [(3, 5, 2), (7, 7, 5)]:
+        w = W.make(RAM, a, b, q, 2222, CONST, seed=3, device=DEV)
+        _check_all(w.X, w.file_rows, w.d, w.f, w.r, expect_exact=True)
+    # byz_median alone for assorted odd f, including rows used more than once
+    rng = np.random.default_rng(5)
+    X = torch.randn(70, 1500, device=DEV)
+    for f in [1, 3, 5, 7, 9, 11, 13, 25, 31, 49, 63]:
+        idx = rng.integers(0, 70, size=f).astype(np.int32)
+        out = B.byz_median(X, 1500, torch.tensor(idx, device=DEV))
+        torch.cuda.synchronize()
+        assert np.array_equal(W.bits(out), W.bits(O.median(X.cpu().numpy(), idx, 1500)))
+
+
+def _plant(X, rows_np, j, k, coords, value):
+    for c in coords:
+        X[int(rows_np[j, k]), c] = value
+
+
+def test_copy_that_matches_on_the_probe_sample_but_differs_elsewhere():
+    # The probe looks at 32 runs of 16 coordinates; a copy that differs only outside them
+    # is caught by the streaming pass and the exact path must take over.
+    d = 100_000
+    w = W.make(MOLS, 5, 3, 0, d, REVERSED, seed=4, device=DEV)
+    stride = (d - 16) // 31
+    unsampled = [c for c in (17, stride - 1, d - 17, d // 2 + 19) if (c % stride) >= 16]
+    assert unsampled
+    X = w.X.clone()
+    # replicas 0 and 2 of file 3 both deviate (identically) at unsampled coordinates:
+    # the true winner is replica 0's value {0,2}; the probe thinks all three are equal
+    for k in (0, 2):
+        _plant(X, w.file_rows, 3, k, unsampled, 7.0)
+    # replica 0 of file 8 deviates alone: winner class {1,2}, winner replica 1
+    _plant(X, w.file_rows, 8, 0, unsampled[:1], -3.0)
+    out_o, wrep_o, took_exact = _check_all(X, w.file_rows, d, w.f, w.r, expect_exact=True)
+    assert wrep_o[3] == 0 and wrep_o[8] == 1
+    # a copy that differs only in the very last coordinate (outside the sample) -> exact path
+    X2 = w.X.clone()
+    _plant(X2, w.file_rows, 5, 1, [d - 1], 9.0)
+    out_o, wrep_o, _ = _check_all(X2, w.file_rows, d, w.f, w.r, expect_exact=True)
+    assert wrep_o[5] == 0
+    # a copy that differs at one sampled coordinate only -> the probe sees it, fast path
+    X3 = w.X.clone()
+    _plant(X3, w.file_rows, 5, 0, [5 * stride + 3], 9.0)
+    out_o, wrep_o, _ = _check_all(X3, w.file_rows, d, w.f, w.r, expect_exact=False)
+    assert wrep_o[5] == 1
+
+
+def test_no_majority_and_ties():
+    d = 3000
+    # r = 3, all three copies different -> replica 0 wins
+    w = W.make(MOLS, 5, 3, 0, d, REVERSED, seed=6, device=DEV)
+    X = w.X.clone()
+    X[int(w.file_rows[4, 1])] *= 2.0
+    X[int(w.file_rows[4, 2])] *= 3.0
+    out_o, wrep_o, _ = _check_all(X, w.file_rows, d, w.f, w.r)
+    assert wrep_o[4] == 0
+    # r = 5: every equality pattern of five copies on one file each (52 set partitions > 25
+    # files, so three rounds), values differing everywhere
+    w5 = W.make(RAM, 5, 5, 0, d, REVERSED, seed=7, device=DEV)
+
+    def partitions(n):
+        def rec(prefix, mx):
+            if len(prefix) == n:
+                yield list(prefix)
+                return
+            for lab in range(mx + 2):
+                yield from rec(prefix + [lab], max(mx, lab))
+        return list(rec([0], 0))
+    parts = partitions(5)
+    assert len(parts) == 52
+    for start in range(0, 52, 25):
+        X = w5.X.clone()
+        chunk = parts[start:start + 25]
+        for j, labels in enumerate(chunk):
+            for k, lab in enumerate(labels):
+                X[int(w5.file_rows[j, k])] = w5.G[j] * float(1 + lab)
+        out_o, wrep_o, _ = _check_all(X, w5.file_rows, d, w5.f, w5.r, tag=start)
+        for j, labels in enumerate(chunk):
+            counts = [labels.count(x) for x in labels]
+            assert wrep_o[j] == counts.index(max(counts))
+
+
+def test_special_values_nan_inf_signed_zero():
+    d = 4096
+    w = W.make(MOLS, 5, 3, 4, d, ALIE, seed=8, device=DEV)
+    X = w.X.clone()
+    Xi = X.view(torch.int32)
+    rng = np.random.default_rng(9)
+    patterns = np.array([0x7FC00000, 0xFFC00000, 0x7F800000, 0xFF800000, 0x80000000, 0x00000000,
+                         0x7FC00001, 0x00000001, 0x80000001], dtype=np.uint32).view(np.int32)
+    # honest copies stay bitwise identical: write the same special word into all honest copies
+    for _ in range(600):
+        j = int(rng.integers(0, w.f))
+        c = int(rng.integers(0, d))
+        p = int(patterns[rng.integers(0, len(patterns))])
+        for k in range(w.r):
+            if int(w.file_workers[j, k]) not in w.byz:
+                Xi[int(w.file_rows[j, k]), c] = p
+    # a column where most files hold a NaN / zeros of both signs
+    for j in range(w.f):
+        for k in range(w.r):
+            Xi[int(w.file_rows[j, k]), 11] = int(patterns[j % 2])
+            Xi[int(w.file_rows[j, k]), 12] = int(patterns[4 + (j % 2)])
+    _check_all(X, w.file_rows, d, w.f, w.r)
+    # raw random bit patterns, each file's copies identical
+    U = torch.randint(-2**31, 2**31 - 1, (w.f, d), dtype=torch.int64, device=DEV).to(torch.int32)
+    Xr = torch.empty_like(X).view(torch.int32)
+    for j in range(w.f):
+        for k in range(w.r):
+            Xr[int(w.file_rows[j, k])] = U[j]
+    _check_all(Xr.view(torch.float32), w.file_rows, d, w.f, w.r, expect_exact=False)
+
+
+def test_argument_errors():
+    w = W.make(MOLS, 5, 3, 3, 100, REVERSED, seed=10, device=DEV)
+    rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+    for (f, r, code) in [(25, 4, -1), (25, 1, -1), (0, 3, -1), (65, 3, -1), (25, 9, -1)]:
+        with pytest.raises(B.ByzError) as e:
+            B.byz_vote(w.X, 100, rows_dev, f, r)
+        assert e.value.code == code
+    with pytest.raises(B.ByzError) as e:
+        B.byz_vote(w.X, 101, rows_dev, 25, 3)  # d > ld
+    assert e.value.code == -1
+    with pytest.raises(B.ByzError) as e:
+        B.byz_median(w.X, 100, rows_dev[:24])  # even f
+    assert e.value.code == -2
+    small = torch.empty(64, dtype=torch.uint8, device=DEV)
+    with pytest.raises(B.ByzError) as e:
+        B.byz_aggregate(w.X, 100, rows_dev, 25, 3, workspace=small)
+    assert e.value.code == -3
+    # d = 0: every copy is trivially equal
+    wrep, wrow, neq = B.byz_vote(w.X, 0, rows_dev, 25, 3)
+    torch.cuda.synchronize()
+    assert (wrep == 0).all() and (neq == 0).all()
+    out, wrep2, _ = B.byz_aggregate(w.X, 0, rows_dev, 25, 3)
+    torch.cuda.synchronize()
+    assert out.numel() == 0 and (wrep2 == 0).all()
+
+
+def test_generator_same_bytes_on_cpu_and_gpu():
+    for fs in (False, True):
+        Gc = synth.honest_gradients(9, 5000, 77, step=3, device="cpu", file_scales=fs)
+        Gg = synth.honest_gradients(9, 5000, 77, step=3, device=DEV, file_scales=fs)
+        assert np.array_equal(W.bits(Gc), W.bits(Gg))
+    assert np.array_equal(W.bits(synth.alie_vector(Gc, 1.5)), W.bits(synth.alie_vector(Gg, 1.5)))
