@@ -2,12 +2,15 @@
 // the ByzShield paper), coordinate-wise median over the f winners (Sec. 2, Sec. 6.1) and the
 // fused single-pass vote+median, plus the C-ABI entry points that launch them.
 //
-// Work decomposition shared by all streaming kernels: one thread owns V consecutive
-// coordinates (V = 4, 2 or 1 dwords, chosen from the alignment of the rows) and walks over
-// all files, so every global load of a wave is one contiguous 64*V*4-byte segment of one row.
+// Work decomposition shared by all streaming kernels: one thread owns V = 4 consecutive
+// coordinates and walks over all files, so every global load of a wave is one contiguous
+// 1 KiB segment of one row (16-byte loads; gfx950 global loads only need dword alignment).
+// Threads past the end of the grid redo the last vector, so loads and wave ballots sit in
+// straight-line code; the d % V trailing words are done by a few threads of the last block.
 // Per-file "copies differ" bits are reduced inside a wave with ballots (scalar registers),
 // parked in lane j for file j, and merged across waves with one atomicOr per file and wave
-// that is skipped when the bits are already set.
+// that is skipped when the bits are already set.  Where a second tiny kernel would only
+// post-process those bits, the block that finishes last (atomic ticket) does it instead.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -37,22 +40,44 @@ struct ProfileState {
 };
 thread_local ProfileState g_prof;
 
-constexpr int kBlock = 256;
+#ifndef BYZ_NT_LOADS
+#define BYZ_NT_LOADS 1
+#endif
+#ifndef BYZ_FUSED_GROUP
+#define BYZ_FUSED_GROUP 1  // files whose loads the single-pass kernel issues together
+#endif
+
+#ifndef BYZ_BLOCK
+#define BYZ_BLOCK 256
+#endif
+constexpr int kBlock = BYZ_BLOCK;
 constexpr int kRowStride = 8;  // slots per file in the permuted row table (>= BYZ_MAX_R)
 
 // ----------------------------------------------------------------------------- helpers
 
 template <int V> struct VecT;
 template <> struct VecT<1> { typedef uint32_t type; };
-template <> struct VecT<2> { typedef uint32_t type __attribute__((ext_vector_type(2))); };
-template <> struct VecT<4> { typedef uint32_t type __attribute__((ext_vector_type(4))); };
+// Vector types that only promise dword alignment: global memory accesses of gfx950 need no
+// more, so rows whose pitch is not a multiple of four words still get 16-byte loads.
+template <> struct VecT<2> {
+    typedef uint32_t type __attribute__((ext_vector_type(2), aligned(4)));
+};
+template <> struct VecT<4> {
+    typedef uint32_t type __attribute__((ext_vector_type(4), aligned(4)));
+};
 
+// Streaming load of V words (each input word is used exactly once: non-temporal hint).
 template <int V>
 __device__ __forceinline__ void load_vec(const uint32_t *p, uint32_t (&x)[V]) {
+    typedef typename VecT<V>::type T;
+#if BYZ_NT_LOADS
+    const T t = __builtin_nontemporal_load(reinterpret_cast<const T *>(p));
+#else
+    const T t = *reinterpret_cast<const T *>(p);
+#endif
     if constexpr (V == 1) {
-        x[0] = *p;
+        x[0] = t;
     } else {
-        typename VecT<V>::type t = *reinterpret_cast<const typename VecT<V>::type *>(p);
 #pragma unroll
         for (int v = 0; v < V; ++v) x[v] = t[v];
     }
@@ -60,14 +85,15 @@ __device__ __forceinline__ void load_vec(const uint32_t *p, uint32_t (&x)[V]) {
 
 template <int V>
 __device__ __forceinline__ void store_vec(uint32_t *p, const uint32_t (&x)[V]) {
+    typedef typename VecT<V>::type T;
+    T t;
     if constexpr (V == 1) {
-        *p = x[0];
+        t = x[0];
     } else {
-        typename VecT<V>::type t;
 #pragma unroll
         for (int v = 0; v < V; ++v) t[v] = x[v];
-        *reinterpret_cast<typename VecT<V>::type *>(p) = t;
     }
+    __builtin_nontemporal_store(t, reinterpret_cast<T *>(p));
 }
 
 // OR over the V words of (a xor b): nonzero iff the two copies differ somewhere in the chunk
@@ -79,7 +105,7 @@ __device__ __forceinline__ uint32_t differ(const uint32_t (&a)[V], const uint32_
     return acc;
 }
 
-// 1 iff any lane of the wave has a nonzero x (wave-uniform result)
+// 1 iff any active lane of the wave has a nonzero x (wave-uniform result)
 __device__ __forceinline__ uint32_t wave_any(uint32_t x) {
     return __builtin_amdgcn_ballot_w64(x != 0) != 0 ? 1u : 0u;
 }
@@ -94,7 +120,7 @@ __device__ __forceinline__ uint32_t from_key(uint32_t k) {
 }
 
 // Bit of pair (a, b), a < b, in lexicographic numbering (0,1),(0,2),..,(1,2),..
-__device__ __host__ __forceinline__ int pair_bit(int r, int a, int b) {
+__device__ __host__ __forceinline__ constexpr int pair_bit(int r, int a, int b) {
     return a * r - a * (a + 1) / 2 + (b - a - 1);
 }
 
@@ -116,13 +142,36 @@ __device__ __forceinline__ int decide_winner(uint32_t neq, int r) {
     return arg;
 }
 
+__device__ __forceinline__ uint32_t load_shared_word(const uint32_t *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Wave-uniform: is any of words[0..n-1] nonzero (n <= 64)?  Used by the kernels of the exact
+// path to return at once when the single pass recorded no violation.
+__device__ __forceinline__ bool any_word_set(const uint32_t *__restrict__ words, int n) {
+    const int lane = threadIdx.x & 63;
+    const uint32_t v = lane < n ? words[lane] : 0u;
+    return __builtin_amdgcn_ballot_w64(v != 0) != 0;
+}
+
 // Merge a wave's per-file bits (lane j = file j) into global words, skipping the atomic when
 // nothing new would be set.  A stale read only costs a redundant atomic.
 __device__ __forceinline__ void merge_flags(uint32_t *words, int f, int lane, uint32_t flags) {
     if (lane < f && flags != 0) {
-        const uint32_t cur = __atomic_load_n(&words[lane], __ATOMIC_RELAXED);
+        const uint32_t cur = load_shared_word(&words[lane]);
         if ((cur & flags) != flags) atomicOr(&words[lane], flags);
     }
+}
+
+// True in every thread of exactly one block of the grid: the one that finishes last.  Each
+// block calls it once, after all its global updates; `ticket` must be 0 at launch.
+__device__ __forceinline__ bool last_block_done(uint32_t *ticket) {
+    __shared__ uint32_t s_last;
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) s_last = (atomicAdd(ticket, 1u) == gridDim.x - 1) ? 1u : 0u;
+    __syncthreads();
+    return s_last != 0;
 }
 
 // ------------------------------------------------------------------- selection networks
@@ -187,96 +236,153 @@ template <> struct SelNet<49> {
 // --------------------------------------------------------------------- device workspace
 
 struct AggWorkspace {
-    uint32_t viol[BYZ_MAX_F];        // fused pass: assumed-equal neighbours that differ
+    uint32_t viol[BYZ_MAX_F];        // single pass: assumed-equal neighbours that differ
     uint32_t pair_neq[BYZ_MAX_F];    // exact path: all pair bits
+    uint64_t perm_off[BYZ_MAX_F * kRowStride];  // byte offsets row*ld*4 of the rows below
     int32_t perm_rows[BYZ_MAX_F * kRowStride];  // rows of a file, probable winner's class first
     uint32_t chain_mask[BYZ_MAX_F];  // bit k-1: permuted copies k-1 and k were equal on the sample
     int32_t prov_winner[BYZ_MAX_F];  // probable winner (original replica index)
     int32_t winner_row[BYZ_MAX_F];   // exact path result
-    int32_t winner_replica[BYZ_MAX_F];
-    uint32_t need_exact;             // 1 iff some assumed equality failed
-    uint32_t pad[63];
+    uint32_t need_exact;             // 1 iff the exact path ran
+    uint32_t ticket_vote;            // blocks of the exact-path vote kernel that have finished
+    uint32_t pad[62];
 };
 
 // ------------------------------------------------------------------------------ kernels
+
+// Clears the accumulators of one two-step aggregation (no hipMemset: callers may capture).
+__global__ void reset_workspace_kernel(AggWorkspace *ws, uint32_t need_exact) {
+    const int i = threadIdx.x;
+    if (i < BYZ_MAX_F) {
+        ws->viol[i] = 0;
+        ws->pair_neq[i] = 0;
+    }
+    if (i == 0) {
+        ws->need_exact = need_exact;
+        ws->ticket_vote = 0;
+    }
+}
 
 __global__ void fill_u32_kernel(uint32_t *p, int n, uint32_t value) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = value;
 }
 
-// Step a1: for every file, which pairs of copies differ anywhere in [c_begin, c_end).
-// (c_end - c_begin) % V == 0 and every row start + c_begin is 4*V-byte aligned.
-template <int R, int V>
-__global__ __launch_bounds__(kBlock) void vote_pairs_kernel(
-    const uint32_t *__restrict__ X, int64_t c_begin, int64_t c_end, int64_t ld,
-    const int32_t *__restrict__ file_rows, int f, uint32_t *pair_neq,
-    const uint32_t *__restrict__ enable) {
-    if (enable != nullptr && *enable == 0) return;
-    const int lane = threadIdx.x & 63;
-    const int64_t c0 = c_begin + ((int64_t)blockIdx.x * kBlock + threadIdx.x) * V;
-    const bool active = c0 < c_end;
-    uint32_t flags = 0;
-    for (int j = 0; j < f; ++j) {
-        uint32_t x[R][V];
-#pragma unroll
-        for (int k = 0; k < R; ++k) {
-#pragma unroll
-            for (int v = 0; v < V; ++v) x[k][v] = 0;
-            if (active) load_vec<V>(X + (int64_t)file_rows[j * R + k] * ld + c0, x[k]);
-        }
-        uint32_t wb = 0;
-#pragma unroll
-        for (int a = 0; a < R; ++a)
-#pragma unroll
-            for (int b = a + 1; b < R; ++b)
-                wb |= wave_any(differ<V>(x[a], x[b])) << pair_bit(R, a, b);
-        if (lane == j) flags |= wb;
-    }
-    merge_flags(pair_neq, f, lane, flags);
-}
-
-// Step a2: winners from the pair bits.
-__global__ void vote_decide_kernel(const uint32_t *__restrict__ pair_neq,
-                                   const int32_t *__restrict__ file_rows, int f, int r,
-                                   int32_t *winner_replica, int32_t *winner_row,
-                                   const uint32_t *__restrict__ enable) {
-    if (enable != nullptr && *enable == 0) return;
+// Step a2: winners from the pair bits (lane j = file j).
+__device__ __forceinline__ void decide_files(const uint32_t *pair_neq,
+                                             const int32_t *__restrict__ file_rows, int f, int r,
+                                             int32_t *winner_replica, int32_t *winner_row) {
     const int j = threadIdx.x;
     if (j >= f) return;
-    const int a = decide_winner(pair_neq[j], r);
+    const int a = decide_winner(load_shared_word(&pair_neq[j]), r);
     if (winner_replica != nullptr) winner_replica[j] = a;
     if (winner_row != nullptr) winner_row[j] = file_rows[j * r + a];
+}
+
+__global__ void vote_decide_kernel(const uint32_t *pair_neq, const int32_t *__restrict__ file_rows,
+                                   int f, int r, int32_t *winner_replica, int32_t *winner_row) {
+    decide_files(pair_neq, file_rows, f, r, winner_replica, winner_row);
+}
+
+// Step a1: for every file, which pairs of copies differ anywhere in [0, d).  Threads own
+// vectors of V words; the d % V trailing words go to the first threads of the last block.
+// If `ticket` is given (zero at launch), the block
+// that finishes last also runs step a2.  If `gate` is given, the kernel only runs when one of
+// gate[0..f-1] is nonzero; otherwise it publishes gate_off_winner as the winners and returns.
+template <int R, int V>
+__global__ __launch_bounds__(kBlock) void vote_pairs_kernel(
+    const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ file_rows,
+    int f, uint32_t *pair_neq, const uint32_t *__restrict__ gate, uint32_t *ticket,
+    int32_t *winner_replica, int32_t *winner_row, const int32_t *__restrict__ gate_off_winner,
+    uint32_t *took_exact) {
+    if (gate != nullptr) {
+        if (!any_word_set(gate, f)) {
+            // nothing to redo: the single pass stands, its probable winners are final
+            if (blockIdx.x == 0 && (int)threadIdx.x < f && winner_replica != nullptr)
+                winner_replica[threadIdx.x] = gate_off_winner[threadIdx.x];
+            return;
+        }
+        if (blockIdx.x == 0 && threadIdx.x == 0) *took_exact = 1;
+    }
+    const int lane = threadIdx.x & 63;
+    const int64_t n_vec = d / V;
+    const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    uint32_t flags = 0;
+    if (n_vec > 0) {
+        // threads past the end redo the last vector: no branches around loads and ballots
+        const uint32_t *base = X + (gt < n_vec ? gt : n_vec - 1) * V;
+        for (int j = 0; j < f; ++j) {
+            uint32_t x[R][V];
+#pragma unroll
+            for (int k = 0; k < R; ++k) load_vec<V>(base + (int64_t)file_rows[j * R + k] * ld, x[k]);
+            uint32_t wb = 0;
+#pragma unroll
+            for (int a = 0; a < R; ++a)
+#pragma unroll
+                for (int b = a + 1; b < R; ++b)
+                    wb |= wave_any(differ<V>(x[a], x[b])) << pair_bit(R, a, b);
+            if (lane == j) flags |= wb;
+        }
+    }
+    const int tail = (int)(d - n_vec * V);
+    if (blockIdx.x == gridDim.x - 1 && (int)threadIdx.x < tail) {
+        const int64_t c = n_vec * V + threadIdx.x;
+        for (int j = 0; j < f; ++j) {
+            uint32_t x[R];
+#pragma unroll
+            for (int k = 0; k < R; ++k) x[k] = X[(int64_t)file_rows[j * R + k] * ld + c];
+            uint32_t bits = 0;
+#pragma unroll
+            for (int a = 0; a < R; ++a)
+#pragma unroll
+                for (int b = a + 1; b < R; ++b)
+                    bits |= (x[a] != x[b] ? 1u : 0u) << pair_bit(R, a, b);
+            if (bits != 0) atomicOr(&pair_neq[j], bits);
+        }
+    }
+    merge_flags(pair_neq, f, lane, flags);
+    if (ticket != nullptr && last_block_done(ticket))
+        decide_files(pair_neq, file_rows, f, R, winner_replica, winner_row);
 }
 
 // Step a3: coordinate-wise median of F rows by a register selection network.
 template <int F, int V>
 __global__ __launch_bounds__(kBlock) void median_kernel(
-    const uint32_t *__restrict__ X, int64_t c_begin, int64_t c_end, int64_t ld,
-    const int32_t *__restrict__ row_index, uint32_t *__restrict__ out,
-    const uint32_t *__restrict__ enable) {
-    if (enable != nullptr && *enable == 0) return;
-    const int64_t c0 = c_begin + ((int64_t)blockIdx.x * kBlock + threadIdx.x) * V;
-    if (c0 >= c_end) return;
-    uint32_t key[V][F];
+    const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
+    uint32_t *__restrict__ out, const uint32_t *__restrict__ gate, int gate_n) {
+    if (gate != nullptr && !any_word_set(gate, gate_n)) return;
+    const int64_t n_vec = d / V;
+    const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (gt < n_vec) {
+        const uint32_t *base = X + gt * V;
+        uint32_t key[V][F];
 #pragma unroll
-    for (int j = 0; j < F; ++j) {
-        uint32_t x[V];
-        load_vec<V>(X + (int64_t)row_index[j] * ld + c0, x);
+        for (int j = 0; j < F; ++j) {
+            uint32_t x[V];
+            load_vec<V>(base + (int64_t)row_index[j] * ld, x);
 #pragma unroll
-        for (int v = 0; v < V; ++v) key[v][j] = to_key(x[v]);
+            for (int v = 0; v < V; ++v) key[v][j] = to_key(x[v]);
+        }
+        uint32_t o[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) o[v] = from_key(SelNet<F>::median(key[v]));
+        store_vec<V>(out + gt * V, o);
     }
-    uint32_t o[V];
+    const int tail = (int)(d - n_vec * V);
+    if (blockIdx.x == gridDim.x - 1 && (int)threadIdx.x < tail) {
+        const int64_t c = n_vec * V + threadIdx.x;
+        uint32_t key[F];
 #pragma unroll
-    for (int v = 0; v < V; ++v) o[v] = from_key(SelNet<F>::median(key[v]));
-    store_vec<V>(out + c0, o);
+        for (int j = 0; j < F; ++j) key[j] = to_key(X[(int64_t)row_index[j] * ld + c]);
+        out[c] = from_key(SelNet<F>::median(key));
+    }
 }
 
 // Step a3 for any odd f <= 64 (no generated network): rank counting, one coordinate a thread.
 __global__ __launch_bounds__(kBlock) void median_generic_kernel(
     const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
-    int f, uint32_t *__restrict__ out, const uint32_t *__restrict__ enable) {
-    if (enable != nullptr && *enable == 0) return;
+    int f, uint32_t *__restrict__ out, const uint32_t *__restrict__ gate, int gate_n) {
+    if (gate != nullptr && !any_word_set(gate, gate_n)) return;
     const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (c >= d) return;
     uint32_t key[BYZ_MAX_F];
@@ -292,13 +398,14 @@ __global__ __launch_bounds__(kBlock) void median_generic_kernel(
 }
 
 // Probe: compares the copies of every file on a sample of <= 512 coordinates (32 runs of 16
-// consecutive words spread over [0, d)), derives the probable equality classes, and lays out
-// the rows of each file with the probable winner first and equal-looking copies adjacent.
-// Also clears the state the later kernels accumulate into.  One block of 512 threads.
-template <int R>
+// consecutive words spread over [0, d); all of [0, d) when d <= 512), derives the probable
+// equality classes, and lays out the rows of each file with the probable winner first and
+// equal-looking copies adjacent.  Also clears the state the later kernels accumulate into.
+// One block of 512 threads.
+template <int F, int R>
 __global__ __launch_bounds__(512) void probe_kernel(const uint32_t *__restrict__ X, int64_t d,
                                                     int64_t ld,
-                                                    const int32_t *__restrict__ file_rows, int f,
+                                                    const int32_t *__restrict__ file_rows,
                                                     AggWorkspace *ws) {
     __shared__ uint32_t s_neq[BYZ_MAX_F];
     const int tid = threadIdx.x;
@@ -308,34 +415,47 @@ __global__ __launch_bounds__(512) void probe_kernel(const uint32_t *__restrict__
         ws->viol[tid] = 0;
         ws->pair_neq[tid] = 0;
     }
-    if (tid == 0) ws->need_exact = 0;
+    if (tid == 0) {
+        ws->need_exact = 0;
+        ws->ticket_vote = 0;
+    }
     __syncthreads();
 
-    int64_t c = -1;
+    // threads without a sample coordinate of their own redo coordinate 0
+    int64_t c = 0;
     if (d <= 512) {
         if (tid < d) c = tid;
     } else {
         const int64_t run = tid >> 4, off = tid & 15;
         c = run * ((d - 16) / 31) + off;
     }
-    const bool active = c >= 0;
+    // files in groups of G: all loads of a group are issued before the first ballot waits
+    constexpr int G = 36 / R;
     uint32_t flags = 0;
-    for (int j = 0; j < f; ++j) {
-        uint32_t x[R];
 #pragma unroll
-        for (int k = 0; k < R; ++k)
-            x[k] = active ? X[(int64_t)file_rows[j * R + k] * ld + c] : 0u;
-        uint32_t wb = 0;
+    for (int j0 = 0; j0 < F; j0 += G) {
+        uint32_t x[G][R];
 #pragma unroll
-        for (int a = 0; a < R; ++a)
+        for (int g = 0; g < G; ++g)
 #pragma unroll
-            for (int b = a + 1; b < R; ++b) wb |= wave_any(x[a] ^ x[b]) << pair_bit(R, a, b);
-        if (lane == j) flags |= wb;
+            for (int k = 0; k < R; ++k)
+                if (j0 + g < F) x[g][k] = X[(int64_t)file_rows[(j0 + g) * R + k] * ld + c];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            if (j0 + g >= F) continue;
+            uint32_t wb = 0;
+#pragma unroll
+            for (int a = 0; a < R; ++a)
+#pragma unroll
+                for (int b = a + 1; b < R; ++b)
+                    wb |= wave_any(x[g][a] ^ x[g][b]) << pair_bit(R, a, b);
+            if (lane == j0 + g) flags |= wb;
+        }
     }
-    if (lane < f && flags != 0) atomicOr(&s_neq[lane], flags);
+    if (lane < F && flags != 0) atomicOr(&s_neq[lane], flags);
     __syncthreads();
 
-    if (tid < f) {
+    if (tid < F) {
         const int j = tid;
         const uint32_t neq = s_neq[j];
         const int w = decide_winner(neq, R);
@@ -358,7 +478,9 @@ __global__ __launch_bounds__(512) void probe_kernel(const uint32_t *__restrict__
         }
         uint32_t chain = 0;
         for (int p = 0; p < R; ++p) {
-            ws->perm_rows[j * kRowStride + p] = file_rows[j * R + perm[p]];
+            const int32_t row = file_rows[j * R + perm[p]];
+            ws->perm_rows[j * kRowStride + p] = row;
+            ws->perm_off[j * kRowStride + p] = (uint64_t)row * (uint64_t)ld * 4u;
             if (p > 0 && label[perm[p]] == label[perm[p - 1]]) chain |= 1u << (p - 1);
         }
         ws->chain_mask[j] = chain;
@@ -368,173 +490,161 @@ __global__ __launch_bounds__(512) void probe_kernel(const uint32_t *__restrict__
 
 // Fused a1+a2+a3: streams all R*F rows once.  The probable winner of each file (slot 0 of
 // its permuted row list) feeds the median network; every equality the probe assumed between
-// neighbouring slots is checked over all coordinates and violations are recorded per file.
+// neighbouring slots is checked over all coordinates and violations are recorded per file
+// (ws->viol).  No violation -> the probable classes are the true ones, the output and the
+// probable winners are final; otherwise the kernels of the exact path, gated on ws->viol, redo
+// the aggregation.
 template <int F, int R, int V>
-__global__ __launch_bounds__(kBlock) void fused_kernel(const uint32_t *__restrict__ X,
-                                                       int64_t c_begin, int64_t c_end, int64_t ld,
-                                                       const AggWorkspace *__restrict__ ws,
-                                                       uint32_t *viol, uint32_t *__restrict__ out) {
+__global__ __launch_bounds__(kBlock) void fused_kernel(
+    const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ perm_rows,
+    const uint64_t *__restrict__ perm_off, const uint32_t *__restrict__ chain_mask,
+    AggWorkspace *ws, uint32_t *__restrict__ out) {
     const int lane = threadIdx.x & 63;
-    const int64_t c0 = c_begin + ((int64_t)blockIdx.x * kBlock + threadIdx.x) * V;
-    const bool active = c0 < c_end;
-    uint32_t key[V][F];
+    const int64_t n_vec = d / V;
+    const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     uint32_t flags = 0;
+    if (n_vec > 0) {
+        // threads past the end redo the last vector: no branches around loads and ballots
+        const uint32_t voff = (uint32_t)((gt < n_vec ? gt : n_vec - 1) * (V * 4));
+        const char *Xb = reinterpret_cast<const char *>(X);
+        uint32_t key[V][F];
+        // files in groups of G: the R*G loads of a group are issued back to back, then consumed
+        constexpr int G = BYZ_FUSED_GROUP;
 #pragma unroll
-    for (int j = 0; j < F; ++j) {
-        uint32_t x[R][V];
+        for (int j0 = 0; j0 < F; j0 += G) {
+            uint32_t x[G][R][V];
 #pragma unroll
-        for (int k = 0; k < R; ++k) {
+            for (int g = 0; g < G; ++g)
 #pragma unroll
-            for (int v = 0; v < V; ++v) x[k][v] = 0;
-            if (active) load_vec<V>(X + (int64_t)ws->perm_rows[j * kRowStride + k] * ld + c0, x[k]);
+                for (int k = 0; k < R; ++k)
+                    if (j0 + g < F)
+                        load_vec<V>(reinterpret_cast<const uint32_t *>(
+                                        Xb + perm_off[(j0 + g) * kRowStride + k] + voff),
+                                    x[g][k]);
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                if (j0 + g >= F) continue;
+                const int j = j0 + g;
+                uint32_t wb = 0;
+#pragma unroll
+                for (int k = 1; k < R; ++k)
+                    wb |= wave_any(differ<V>(x[g][k - 1], x[g][k])) << (k - 1);
+                wb &= chain_mask[j];
+                if (lane == j) flags |= wb;
+#pragma unroll
+                for (int v = 0; v < V; ++v) key[v][j] = to_key(x[g][0][v]);
+            }
         }
-        uint32_t wb = 0;
+        uint32_t o[V];
 #pragma unroll
-        for (int k = 1; k < R; ++k) wb |= wave_any(differ<V>(x[k - 1], x[k])) << (k - 1);
-        wb &= ws->chain_mask[j];
-        if (lane == j) flags |= wb;
-#pragma unroll
-        for (int v = 0; v < V; ++v) key[v][j] = to_key(x[0][v]);
+        for (int v = 0; v < V; ++v) o[v] = from_key(SelNet<F>::median(key[v]));
+        if (gt < n_vec) store_vec<V>(out + gt * V, o);
     }
-    uint32_t o[V];
+    const int tail = (int)(d - n_vec * V);
+    if (blockIdx.x == gridDim.x - 1 && (int)threadIdx.x < tail) {
+        const int64_t c = n_vec * V + threadIdx.x;
+        uint32_t key[F];
 #pragma unroll
-    for (int v = 0; v < V; ++v) o[v] = from_key(SelNet<F>::median(key[v]));
-    if (active) store_vec<V>(out + c0, o);
-    merge_flags(viol, F, lane, flags);
-}
-
-// After the fused pass: if no assumed equality failed, the probable classes are the true
-// ones and the probable winners are final; otherwise request the exact path.
-__global__ void fused_finalize_kernel(AggWorkspace *ws, int f, int32_t *winner_replica) {
-    const int j = threadIdx.x;  // one wave
-    const uint32_t v = j < f ? ws->viol[j] : 0u;
-    const bool bad = __builtin_amdgcn_ballot_w64(v != 0) != 0;
-    if (bad) {
-        if (j == 0) ws->need_exact = 1;
-    } else if (j < f && winner_replica != nullptr) {
-        winner_replica[j] = ws->prov_winner[j];
+        for (int j = 0; j < F; ++j) {
+            uint32_t x[R];
+#pragma unroll
+            for (int k = 0; k < R; ++k) x[k] = X[(int64_t)perm_rows[j * kRowStride + k] * ld + c];
+            uint32_t bits = 0;
+#pragma unroll
+            for (int k = 1; k < R; ++k) bits |= (x[k - 1] != x[k] ? 1u : 0u) << (k - 1);
+            bits &= chain_mask[j];
+            if (bits != 0) atomicOr(&ws->viol[j], bits);
+            key[j] = to_key(x[0]);
+        }
+        out[c] = from_key(SelNet<F>::median(key));
     }
+    merge_flags(ws->viol, F, lane, flags);
 }
 
 // ---------------------------------------------------------------------------- launchers
 
-int vec_width(const void *base, int64_t ld, const void *out) {
-    const uintptr_t a = (uintptr_t)base | (uintptr_t)out;
-    if ((a & 15u) == 0 && (ld & 3) == 0) return 4;
-    if ((a & 7u) == 0 && (ld & 1) == 0) return 2;
-    return 1;
+constexpr int kVec = 4;  // words per thread and load; rows only need dword alignment
+
+// blocks for n_vec vector-owning threads; at least one so the trailing words get a block
+inline unsigned blocks_for(int64_t n_vec) {
+    const int64_t b = (n_vec + kBlock - 1) / kBlock;
+    return (unsigned)(b > 0 ? b : 1);
 }
 
-inline unsigned blocks_for(int64_t n_items) { return (unsigned)((n_items + kBlock - 1) / kBlock); }
-
-constexpr int64_t kMaxCoords = (int64_t)1 << 38;  // keeps every grid below 2^31 blocks
+constexpr int64_t kMaxCoords = (int64_t)1 << 30;  // byte offsets inside a row fit 32 bits
 
 template <int R>
 int launch_vote_pairs(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, int f,
-                      uint32_t *neq, const uint32_t *enable, hipStream_t s) {
-    const int V = vec_width(X, ld, nullptr);
-    const int64_t d_main = d - d % V;
-    if (d_main > 0) {
-        const unsigned g = blocks_for(d_main / V);
-        if (V == 4)
-            vote_pairs_kernel<R, 4><<<g, kBlock, 0, s>>>(X, 0, d_main, ld, rows, f, neq, enable);
-        else if (V == 2)
-            vote_pairs_kernel<R, 2><<<g, kBlock, 0, s>>>(X, 0, d_main, ld, rows, f, neq, enable);
-        else
-            vote_pairs_kernel<R, 1><<<g, kBlock, 0, s>>>(X, 0, d_main, ld, rows, f, neq, enable);
-        BYZ_HIP(hipGetLastError());
-    }
-    if (d_main < d) {
-        vote_pairs_kernel<R, 1><<<1, kBlock, 0, s>>>(X, d_main, d, ld, rows, f, neq, enable);
-        BYZ_HIP(hipGetLastError());
-    }
+                      uint32_t *neq, const uint32_t *gate, uint32_t *ticket,
+                      int32_t *winner_replica, int32_t *winner_row, const int32_t *gate_off_winner,
+                      uint32_t *took_exact, hipStream_t s) {
+    vote_pairs_kernel<R, kVec><<<blocks_for(d / kVec), kBlock, 0, s>>>(
+        X, d, ld, rows, f, neq, gate, ticket, winner_replica, winner_row, gate_off_winner,
+        took_exact);
+    BYZ_HIP(hipGetLastError());
     return BYZ_OK;
 }
 
 int launch_vote_pairs_r(int r, const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows,
-                        int f, uint32_t *neq, const uint32_t *enable, hipStream_t s) {
+                        int f, uint32_t *neq, const uint32_t *gate, uint32_t *ticket,
+                        int32_t *winner_replica, int32_t *winner_row,
+                        const int32_t *gate_off_winner, uint32_t *took_exact, hipStream_t s) {
     switch (r) {
-        case 3: return launch_vote_pairs<3>(X, d, ld, rows, f, neq, enable, s);
-        case 5: return launch_vote_pairs<5>(X, d, ld, rows, f, neq, enable, s);
-        case 7: return launch_vote_pairs<7>(X, d, ld, rows, f, neq, enable, s);
+        case 3:
+            return launch_vote_pairs<3>(X, d, ld, rows, f, neq, gate, ticket, winner_replica,
+                                        winner_row, gate_off_winner, took_exact, s);
+        case 5:
+            return launch_vote_pairs<5>(X, d, ld, rows, f, neq, gate, ticket, winner_replica,
+                                        winner_row, gate_off_winner, took_exact, s);
+        case 7:
+            return launch_vote_pairs<7>(X, d, ld, rows, f, neq, gate, ticket, winner_replica,
+                                        winner_row, gate_off_winner, took_exact, s);
         default: return BYZ_EINVAL;
     }
 }
 
 template <int F>
 int launch_median_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index,
-                      uint32_t *out, const uint32_t *enable, hipStream_t s) {
-    const int V = vec_width(X, ld, out);
-    const int64_t d_main = d - d % V;
-    if (d_main > 0) {
-        const unsigned g = blocks_for(d_main / V);
-        if (V == 4)
-            median_kernel<F, 4><<<g, kBlock, 0, s>>>(X, 0, d_main, ld, row_index, out, enable);
-        else if (V == 2)
-            median_kernel<F, 2><<<g, kBlock, 0, s>>>(X, 0, d_main, ld, row_index, out, enable);
-        else
-            median_kernel<F, 1><<<g, kBlock, 0, s>>>(X, 0, d_main, ld, row_index, out, enable);
-        BYZ_HIP(hipGetLastError());
-    }
-    if (d_main < d) {
-        median_kernel<F, 1><<<1, kBlock, 0, s>>>(X, d_main, d, ld, row_index, out, enable);
-        BYZ_HIP(hipGetLastError());
-    }
+                      uint32_t *out, const uint32_t *gate, int gate_n, hipStream_t s) {
+    median_kernel<F, kVec><<<blocks_for(d / kVec), kBlock, 0, s>>>(X, d, ld, row_index, out, gate,
+                                                                  gate_n);
+    BYZ_HIP(hipGetLastError());
     return BYZ_OK;
 }
 
 int launch_median(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
-                  uint32_t *out, const uint32_t *enable, hipStream_t s) {
+                  uint32_t *out, const uint32_t *gate, int gate_n, hipStream_t s) {
     if (d == 0) return BYZ_OK;
     switch (f) {
-        case 1: return launch_median_net<1>(X, d, ld, row_index, out, enable, s);
-        case 3: return launch_median_net<3>(X, d, ld, row_index, out, enable, s);
-        case 5: return launch_median_net<5>(X, d, ld, row_index, out, enable, s);
-        case 7: return launch_median_net<7>(X, d, ld, row_index, out, enable, s);
-        case 9: return launch_median_net<9>(X, d, ld, row_index, out, enable, s);
-        case 25: return launch_median_net<25>(X, d, ld, row_index, out, enable, s);
-        case 49: return launch_median_net<49>(X, d, ld, row_index, out, enable, s);
+        case 1: return launch_median_net<1>(X, d, ld, row_index, out, gate, gate_n, s);
+        case 3: return launch_median_net<3>(X, d, ld, row_index, out, gate, gate_n, s);
+        case 5: return launch_median_net<5>(X, d, ld, row_index, out, gate, gate_n, s);
+        case 7: return launch_median_net<7>(X, d, ld, row_index, out, gate, gate_n, s);
+        case 9: return launch_median_net<9>(X, d, ld, row_index, out, gate, gate_n, s);
+        case 25: return launch_median_net<25>(X, d, ld, row_index, out, gate, gate_n, s);
+        case 49: return launch_median_net<49>(X, d, ld, row_index, out, gate, gate_n, s);
         default:
             median_generic_kernel<<<blocks_for(d), kBlock, 0, s>>>(X, d, ld, row_index, f, out,
-                                                                   enable);
+                                                                   gate, gate_n);
             BYZ_HIP(hipGetLastError());
             return BYZ_OK;
     }
 }
 
 template <int F, int R>
-int launch_fused(const uint32_t *X, int64_t d, int64_t ld, AggWorkspace *ws, uint32_t *out,
-                 hipStream_t s) {
-    const int V = vec_width(X, ld, out);
-    const int64_t d_main = d - d % V;
-    if (d_main > 0) {
-        const unsigned g = blocks_for(d_main / V);
-        const bool timed = g_prof.count < g_prof.capacity;
-        if (timed) BYZ_HIP(hipEventRecord(g_prof.start[g_prof.count], s));
-        if (V == 4)
-            fused_kernel<F, R, 4><<<g, kBlock, 0, s>>>(X, 0, d_main, ld, ws, ws->viol, out);
-        else if (V == 2)
-            fused_kernel<F, R, 2><<<g, kBlock, 0, s>>>(X, 0, d_main, ld, ws, ws->viol, out);
-        else
-            fused_kernel<F, R, 1><<<g, kBlock, 0, s>>>(X, 0, d_main, ld, ws, ws->viol, out);
-        BYZ_HIP(hipGetLastError());
-        if (timed) {
-            BYZ_HIP(hipEventRecord(g_prof.stop[g_prof.count], s));
-            ++g_prof.count;
-        }
-    }
-    if (d_main < d) {
-        fused_kernel<F, R, 1><<<1, kBlock, 0, s>>>(X, d_main, d, ld, ws, ws->viol, out);
-        BYZ_HIP(hipGetLastError());
-    }
-    return BYZ_OK;
-}
-
-template <int R>
-int launch_probe(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, int f,
-                 AggWorkspace *ws, hipStream_t s) {
-    probe_kernel<R><<<1, 512, 0, s>>>(X, d, ld, rows, f, ws);
+int launch_fused(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, AggWorkspace *ws,
+                 uint32_t *out, hipStream_t s) {
+    probe_kernel<F, R><<<1, 512, 0, s>>>(X, d, ld, rows, ws);
     BYZ_HIP(hipGetLastError());
+    const bool timed = g_prof.count < g_prof.capacity;
+    if (timed) BYZ_HIP(hipEventRecord(g_prof.start[g_prof.count], s));
+    fused_kernel<F, R, kVec><<<blocks_for(d / kVec), kBlock, 0, s>>>(
+        X, d, ld, ws->perm_rows, ws->perm_off, ws->chain_mask, ws, out);
+    BYZ_HIP(hipGetLastError());
+    if (timed) {
+        BYZ_HIP(hipEventRecord(g_prof.stop[g_prof.count], s));
+        ++g_prof.count;
+    }
     return BYZ_OK;
 }
 
@@ -568,11 +678,12 @@ extern "C" int byz_vote(const float *copies, int64_t d, int64_t ld, const int32_
     fill_u32_kernel<<<1, BYZ_MAX_F, 0, s>>>(pair_neq, f, 0u);
     BYZ_HIP(hipGetLastError());
     if (d > 0) {
-        rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, pair_neq, nullptr, s);
+        rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, pair_neq, nullptr, nullptr,
+                                 nullptr, nullptr, nullptr, nullptr, s);
         if (rc != BYZ_OK) return rc;
     }
     vote_decide_kernel<<<1, BYZ_MAX_F, 0, s>>>(pair_neq, file_rows_dev, f, r, winner_replica,
-                                               winner_row, nullptr);
+                                               winner_row);
     BYZ_HIP(hipGetLastError());
     return BYZ_OK;
 }
@@ -585,7 +696,7 @@ extern "C" int byz_median(const float *rows_base, int64_t d, int64_t ld,
     if (f < 1 || f > BYZ_MAX_F) return BYZ_EINVAL;
     if ((f % 2) == 0) return BYZ_EUNSUPPORTED;
     return launch_median(reinterpret_cast<const uint32_t *>(rows_base), d, ld, row_index_dev, f,
-                         reinterpret_cast<uint32_t *>(out), nullptr, (hipStream_t)stream);
+                         reinterpret_cast<uint32_t *>(out), nullptr, 0, (hipStream_t)stream);
 }
 
 extern "C" size_t byz_aggregate_workspace_bytes(int f, int r) {
@@ -610,38 +721,34 @@ extern "C" int byz_aggregate(const float *copies, int64_t d, int64_t ld,
 
     if (!has_fused(f, r) || d == 0) {
         // two-step path, unconditionally: vote (a1, a2), then median (a3) over the winners
-        fill_u32_kernel<<<1, BYZ_MAX_F, 0, s>>>(ws->pair_neq, BYZ_MAX_F, 0u);
-        BYZ_HIP(hipGetLastError());
-        fill_u32_kernel<<<1, 1, 0, s>>>(&ws->need_exact, 1, 1u);
+        reset_workspace_kernel<<<1, BYZ_MAX_F, 0, s>>>(ws, 1u);
         BYZ_HIP(hipGetLastError());
         if (d > 0) {
-            rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, nullptr, s);
+            rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, nullptr,
+                                     &ws->ticket_vote, winner_replica, ws->winner_row, nullptr,
+                                     nullptr, s);
             if (rc != BYZ_OK) return rc;
+        } else {
+            vote_decide_kernel<<<1, BYZ_MAX_F, 0, s>>>(ws->pair_neq, file_rows_dev, f, r,
+                                                       winner_replica, ws->winner_row);
+            BYZ_HIP(hipGetLastError());
         }
-        vote_decide_kernel<<<1, BYZ_MAX_F, 0, s>>>(ws->pair_neq, file_rows_dev, f, r,
-                                                   winner_replica, ws->winner_row, nullptr);
-        BYZ_HIP(hipGetLastError());
-        return launch_median(X, d, ld, ws->winner_row, f, O, nullptr, s);
+        return launch_median(X, d, ld, ws->winner_row, f, O, nullptr, 0, s);
     }
 
-    // probe -> fused pass -> finalize -> (only if an assumed equality failed) exact path
-    rc = (r == 3) ? launch_probe<3>(X, d, ld, file_rows_dev, f, ws, s)
-                  : launch_probe<5>(X, d, ld, file_rows_dev, f, ws, s);
+    // probe -> single pass -> exact path, whose two kernels return at once unless the single
+    // pass recorded a violated assumption
+    if (f == 9) rc = launch_fused<9, 3>(X, d, ld, file_rows_dev, ws, O, s);
+    else if (f == 25 && r == 3) rc = launch_fused<25, 3>(X, d, ld, file_rows_dev, ws, O, s);
+    else if (f == 25 && r == 5) rc = launch_fused<25, 5>(X, d, ld, file_rows_dev, ws, O, s);
+    else if (f == 49 && r == 3) rc = launch_fused<49, 3>(X, d, ld, file_rows_dev, ws, O, s);
+    else rc = launch_fused<49, 5>(X, d, ld, file_rows_dev, ws, O, s);
     if (rc != BYZ_OK) return rc;
-    if (f == 9) rc = launch_fused<9, 3>(X, d, ld, ws, O, s);
-    else if (f == 25 && r == 3) rc = launch_fused<25, 3>(X, d, ld, ws, O, s);
-    else if (f == 25 && r == 5) rc = launch_fused<25, 5>(X, d, ld, ws, O, s);
-    else if (f == 49 && r == 3) rc = launch_fused<49, 3>(X, d, ld, ws, O, s);
-    else rc = launch_fused<49, 5>(X, d, ld, ws, O, s);
+    rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, ws->viol,
+                             &ws->ticket_vote, winner_replica, ws->winner_row, ws->prov_winner,
+                             &ws->need_exact, s);
     if (rc != BYZ_OK) return rc;
-    fused_finalize_kernel<<<1, 64, 0, s>>>(ws, f, winner_replica);
-    BYZ_HIP(hipGetLastError());
-    rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, &ws->need_exact, s);
-    if (rc != BYZ_OK) return rc;
-    vote_decide_kernel<<<1, BYZ_MAX_F, 0, s>>>(ws->pair_neq, file_rows_dev, f, r, winner_replica,
-                                               ws->winner_row, &ws->need_exact);
-    BYZ_HIP(hipGetLastError());
-    return launch_median(X, d, ld, ws->winner_row, f, O, &ws->need_exact, s);
+    return launch_median(X, d, ld, ws->winner_row, f, O, ws->viol, f, s);
 }
 
 extern "C" int byz_profile_enable(int max_calls) {
