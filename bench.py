@@ -1,7 +1,7 @@
 """Benchmark of the ByzShield aggregation path (majority vote + coordinate-wise median) on one MI355X.
 
 A step is one pass of the whole path (byz_aggregate: probe, single-pass vote+median kernel,
-finalisation, conditional exact path) over one batch of stacked worker returns that is
+gated exact path) over one batch of stacked worker returns that is
 already resident in HBM.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--unpadded] [--no-cpu]
@@ -49,6 +49,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2, the headline)")
     ap.add_argument("--unpadded", action="store_true", help="row pitch ld = d instead of d rounded up to 64")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (reference for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path shards by coordinate range, "
@@ -87,6 +89,16 @@ def main():
     def step(i):
         B.byz_aggregate(bufs[i % n_buf], d, rows_dev, asg.f, asg.r, out=out, winner_replica=wrep,
                         workspace=ws, stream=stream)
+
+    if args.calibration_copy:
+        # a plain copy of known size: reads 2^30 bytes and writes 2^30 bytes
+        src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        B.byz_calibration_copy(src, dst, stream=stream)
+        torch.cuda.synchronize()
+        assert torch.equal(src[-1024:], dst[-1024:])
+        del src, dst
 
     for i in range(args.warmup):
         step(i)
@@ -129,7 +141,7 @@ def main():
         avg_ms = sum(kernel_ms) / len(kernel_ms)
         achieved = alg_bytes / (avg_ms * 1e-3) / 1e9
         result["roofline"] = {
-            "bound": "hbm", "kernel": "fused_kernel<%d,%d,%d>" % (asg.f, asg.r, 4 if ld % 4 == 0 else (2 if ld % 2 == 0 else 1)),
+            "bound": "hbm", "kernel": "fused_kernel<%d,%d,4>" % (asg.f, asg.r),
             "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBPS,
             "traffic": _traffic_from_profiles(cfg.name),

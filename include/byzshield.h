@@ -188,6 +188,14 @@ int byz_aggregate_took_exact_path(const void *workspace, int *took_exact_path, v
 int byz_profile_enable(int max_calls);
 int byz_profile_collect(float *ms_out, int capacity, int *n_out);
 
+/*
+ * Reference kernel for hardware HBM counters: copies `bytes` (a multiple of 16) from device
+ * src to device dst, non-overlapping, with the same 16-byte non-temporal loads and stores the
+ * streaming kernels use, so that it reads exactly `bytes` and writes exactly `bytes`.
+ * Asynchronous on `stream`.  Errors: BYZ_EINVAL, BYZ_EDEVICE.
+ */
+int byz_calibration_copy(const void *src, void *dst, size_t bytes, void *stream);
+
 /* ------------------------------------------------------------------------------ misc */
 
 const char *byz_strerror(int code);

@@ -60,6 +60,7 @@ def _load():
         "byz_aggregate_workspace_bytes": (sz, [c_int, c_int]),
         "byz_aggregate": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, sz, vp]),
         "byz_aggregate_took_exact_path": (c_int, [vp, ip, vp]),
+        "byz_calibration_copy": (c_int, [vp, vp, sz, vp]),
         "byz_profile_enable": (c_int, [c_int]),
         "byz_profile_collect": (c_int, [ctypes.POINTER(ctypes.c_float), c_int, ip]),
         "byz_strerror": (ctypes.c_char_p, [c_int]),
@@ -236,3 +237,12 @@ def byz_profile_collect(capacity):
     n = ctypes.c_int()
     _check(_load().byz_profile_collect(buf, int(capacity), ctypes.byref(n)), "byz_profile_collect")
     return [float(buf[i]) for i in range(n.value)]
+
+
+def byz_calibration_copy(src, dst, stream=None):
+    """dst <- src (same-sized contiguous CUDA tensors) with the library's plain copy kernel."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes or not (src.is_contiguous() and dst.is_contiguous()):
+        raise ValueError("src and dst must be contiguous and of equal size")
+    _check(_load().byz_calibration_copy(ctypes.c_void_p(src.data_ptr()), ctypes.c_void_p(dst.data_ptr()),
+                                        nbytes, _stream_ptr(stream)), "byz_calibration_copy")

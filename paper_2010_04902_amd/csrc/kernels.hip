@@ -263,6 +263,18 @@ __global__ void reset_workspace_kernel(AggWorkspace *ws, uint32_t need_exact) {
     }
 }
 
+// Plain copy with the same load/store flavour as the streaming kernels (16-byte non-temporal):
+// a reference of known traffic for reading hardware HBM counters.
+__global__ __launch_bounds__(kBlock) void calibration_copy_kernel(const uint32_t *__restrict__ src,
+                                                                  uint32_t *__restrict__ dst,
+                                                                  int64_t n_vec) {
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n_vec) return;
+    uint32_t x[4];
+    load_vec<4>(src + i * 4, x);
+    store_vec<4>(dst + i * 4, x);
+}
+
 __global__ void fill_u32_kernel(uint32_t *p, int n, uint32_t value) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = value;
@@ -749,6 +761,16 @@ extern "C" int byz_aggregate(const float *copies, int64_t d, int64_t ld,
                              &ws->need_exact, s);
     if (rc != BYZ_OK) return rc;
     return launch_median(X, d, ld, ws->winner_row, f, O, ws->viol, f, s);
+}
+
+extern "C" int byz_calibration_copy(const void *src, void *dst, size_t bytes, void *stream) {
+    if (src == nullptr || dst == nullptr || bytes == 0 || (bytes % 16) != 0) return BYZ_EINVAL;
+    if ((((uintptr_t)src | (uintptr_t)dst) & 3u) != 0 || bytes > ((size_t)1 << 40)) return BYZ_EINVAL;
+    const int64_t n_vec = (int64_t)(bytes / 16);
+    calibration_copy_kernel<<<blocks_for(n_vec), kBlock, 0, (hipStream_t)stream>>>(
+        reinterpret_cast<const uint32_t *>(src), reinterpret_cast<uint32_t *>(dst), n_vec);
+    BYZ_HIP(hipGetLastError());
+    return BYZ_OK;
 }
 
 extern "C" int byz_profile_enable(int max_calls) {
