@@ -43,10 +43,12 @@ thread_local ProfileState g_prof;
 #ifndef BYZ_NT_LOADS
 #define BYZ_NT_LOADS 1
 #endif
-#ifndef BYZ_FUSED_GROUP
-#define BYZ_FUSED_GROUP 1  // files whose loads the single-pass kernel issues together
-#endif
 
+// Files the single-pass kernel prefetches ahead of the one it consumes.  Measured on MI355X:
+// f = 25 (4 waves per SIMD) is fastest with 1, f = 49 (2 waves per SIMD) with 3.
+#ifndef BYZ_AHEAD_EXPR
+#define BYZ_AHEAD_EXPR (F >= 49 ? 3 : 1)
+#endif
 #ifndef BYZ_BLOCK
 #define BYZ_BLOCK 256
 #endif
@@ -500,14 +502,52 @@ __global__ __launch_bounds__(512) void probe_kernel(const uint32_t *__restrict__
     }
 }
 
+// Steps of the generated streamed programs (selnet_stream_<f>.inc), written against the local
+// names of fused_kernel.
+#define BYZ_S_LOAD_(j)                                                                        \
+    _Pragma("unroll") for (int k_ = 0; k_ < R; ++k_)                                          \
+        load_vec<V>(reinterpret_cast<const uint32_t *>(                                       \
+                        Xb + perm_off[(j) * kRowStride + k_] + voff),                         \
+                    stage[(j) % (kAhead + 1)][k_]);
+#define BYZ_S_LOAD1(j) if constexpr (kAhead == 1) { BYZ_S_LOAD_(j) }
+#define BYZ_S_LOAD2(j) if constexpr (kAhead == 2) { BYZ_S_LOAD_(j) }
+#define BYZ_S_LOAD3(j) if constexpr (kAhead == 3) { BYZ_S_LOAD_(j) }
+#define BYZ_S_USE(j)                                                                          \
+    {                                                                                         \
+        uint32_t wb_ = 0;                                                                     \
+        _Pragma("unroll") for (int k_ = 1; k_ < R; ++k_)                                      \
+            wb_ |= wave_any(differ<V>(stage[(j) % (kAhead + 1)][k_ - 1], stage[(j) % (kAhead + 1)][k_])) << (k_ - 1); \
+        wb_ &= chain_mask[j];                                                                 \
+        if (lane == (j)) flags |= wb_;                                                        \
+        _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_)                                      \
+            key[v_][j] = to_key(stage[(j) % (kAhead + 1)][0][v_]);                                       \
+    }
+#define BYZ_S_CE(i, j)                                                                        \
+    _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_) {                                        \
+        const uint32_t a_ = key[v_][i], b_ = key[v_][j];                                      \
+        key[v_][i] = a_ < b_ ? a_ : b_;                                                       \
+        key[v_][j] = a_ < b_ ? b_ : a_;                                                       \
+    }
+#define BYZ_S_CE_LO(i, j)                                                                     \
+    _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_)                                          \
+        key[v_][i] = key[v_][i] < key[v_][j] ? key[v_][i] : key[v_][j];
+#define BYZ_S_CE_HI(i, j)                                                                     \
+    _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_)                                          \
+        key[v_][j] = key[v_][i] < key[v_][j] ? key[v_][j] : key[v_][i];
+#define BYZ_S_MEDIAN(w)                                                                       \
+    _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_) o[v_] = from_key(key[v_][w]);
+
 // Fused a1+a2+a3: streams all R*F rows once.  The probable winner of each file (slot 0 of
 // its permuted row list) feeds the median network; every equality the probe assumed between
 // neighbouring slots is checked over all coordinates and violations are recorded per file
 // (ws->viol).  No violation -> the probable classes are the true ones, the output and the
 // probable winners are final; otherwise the kernels of the exact path, gated on ws->viol, redo
 // the aggregation.
+#ifndef BYZ_FUSED_ATTR
+#define BYZ_FUSED_ATTR
+#endif
 template <int F, int R, int V>
-__global__ __launch_bounds__(kBlock) void fused_kernel(
+__global__ __launch_bounds__(kBlock) BYZ_FUSED_ATTR void fused_kernel(
     const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ perm_rows,
     const uint64_t *__restrict__ perm_off, const uint32_t *__restrict__ chain_mask,
     AggWorkspace *ws, uint32_t *__restrict__ out) {
@@ -519,37 +559,22 @@ __global__ __launch_bounds__(kBlock) void fused_kernel(
         // threads past the end redo the last vector: no branches around loads and ballots
         const uint32_t voff = (uint32_t)((gt < n_vec ? gt : n_vec - 1) * (V * 4));
         const char *Xb = reinterpret_cast<const char *>(X);
-        uint32_t key[V][F];
-        // files in groups of G: the R*G loads of a group are issued back to back, then consumed
-        constexpr int G = BYZ_FUSED_GROUP;
-#pragma unroll
-        for (int j0 = 0; j0 < F; j0 += G) {
-            uint32_t x[G][R][V];
-#pragma unroll
-            for (int g = 0; g < G; ++g)
-#pragma unroll
-                for (int k = 0; k < R; ++k)
-                    if (j0 + g < F)
-                        load_vec<V>(reinterpret_cast<const uint32_t *>(
-                                        Xb + perm_off[(j0 + g) * kRowStride + k] + voff),
-                                    x[g][k]);
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                if (j0 + g >= F) continue;
-                const int j = j0 + g;
-                uint32_t wb = 0;
-#pragma unroll
-                for (int k = 1; k < R; ++k)
-                    wb |= wave_any(differ<V>(x[g][k - 1], x[g][k])) << (k - 1);
-                wb &= chain_mask[j];
-                if (lane == j) flags |= wb;
-#pragma unroll
-                for (int v = 0; v < V; ++v) key[v][j] = to_key(x[g][0][v]);
-            }
-        }
+        uint32_t key[V][F];       // wire j of the median network = file j
+        // files prefetched ahead of the one being consumed
+        constexpr int kAhead = BYZ_AHEAD_EXPR;
+        uint32_t stage[kAhead + 1][R][V];  // copies of the file in use and of those in flight
         uint32_t o[V];
-#pragma unroll
-        for (int v = 0; v < V; ++v) o[v] = from_key(SelNet<F>::median(key[v]));
+        // The generated program walks the files in order: the loads of file j+1 are issued
+        // before file j is consumed (compares, key), followed by every comparator of the
+        // median network whose inputs are complete by then.
+        if constexpr (F == 9) {
+#include "generated/selnet_stream_9.inc"
+        } else if constexpr (F == 25) {
+#include "generated/selnet_stream_25.inc"
+        } else {
+            static_assert(F == 49, "no streamed network generated for this f");
+#include "generated/selnet_stream_49.inc"
+        }
         if (gt < n_vec) store_vec<V>(out + gt * V, o);
     }
     const int tail = (int)(d - n_vec * V);
@@ -575,7 +600,10 @@ __global__ __launch_bounds__(kBlock) void fused_kernel(
 
 // ---------------------------------------------------------------------------- launchers
 
-constexpr int kVec = 4;  // words per thread and load; rows only need dword alignment
+#ifndef BYZ_VEC
+#define BYZ_VEC 4
+#endif
+constexpr int kVec = BYZ_VEC;  // words per thread and load; rows only need dword alignment
 
 // blocks for n_vec vector-owning threads; at least one so the trailing words get a block
 inline unsigned blocks_for(int64_t n_vec) {

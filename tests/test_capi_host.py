@@ -179,3 +179,19 @@ def test_selection_network_49_near_balanced_inputs():
     vals = rng.integers(0, 1000, size=(2000, f))
     for row in vals:
         assert gen_selnet.apply_network(ops, row.tolist())[wire] == sorted(row.tolist())[24]
+
+
+@pytest.mark.parametrize("f", gen_selnet.STREAMED_SIZES)
+def test_streamed_program_is_the_same_network_in_a_valid_order(f):
+    # the single-pass kernel runs the network interleaved with its file loop: every depth's
+    # program must use a file only after loading it, and select the median
+    prog = gen_selnet.streamed_program(f)
+    ops, wire = gen_selnet.best_network(f)
+    assert [s[1:] for s in prog if s[0] == "ce"].__len__() == len(ops)
+    rng = np.random.default_rng(f)
+    for depth in gen_selnet.DEPTHS:
+        loads = [s[2] for s in prog if s[0] == "load" and s[1] == depth]
+        assert loads == list(range(f))
+        for _ in range(200):
+            vals = rng.integers(0, 60, size=f).tolist()
+            assert gen_selnet.run_streamed(prog, vals, depth) == sorted(vals)[(f - 1) // 2]
