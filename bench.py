@@ -49,6 +49,7 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2, the headline)")
     ap.add_argument("--unpadded", action="store_true", help="row pitch ld = d instead of d rounded up to 64")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-early", action="store_true", help="skip the early-majority leg")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (reference for HBM counters)")
     args = ap.parse_args()
@@ -86,9 +87,26 @@ def main():
     ws = torch.empty(B.byz_aggregate_workspace_bytes(asg.f, asg.r), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
 
-    def step(i):
-        B.byz_aggregate(bufs[i % n_buf], d, rows_dev, asg.f, asg.r, out=out, winner_replica=wrep,
-                        workspace=ws, stream=stream)
+    def step(i, flags=0):
+        B.byz_aggregate_opts(bufs[i % n_buf], d, rows_dev, asg.f, asg.r, flags, out=out,
+                             winner_replica=wrep, workspace=ws, stream=stream)
+
+    def timed(flags):
+        """W warm-up steps, then K timed steps; returns (ms per step, kernel ms list, exact?)."""
+        for i in range(args.warmup):
+            step(i, flags)
+        torch.cuda.synchronize()
+        exact = B.byz_aggregate_took_exact_path(ws)
+        B.byz_profile_enable(args.steps)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(i, flags)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        kernel_ms = B.byz_profile_collect(args.steps)
+        B.byz_profile_enable(0)
+        return (t1 - t0) * 1e3 / args.steps, kernel_ms, exact
 
     if args.calibration_copy:
         # a plain copy of known size: reads 2^30 bytes and writes 2^30 bytes
@@ -100,22 +118,7 @@ def main():
         assert torch.equal(src[-1024:], dst[-1024:])
         del src, dst
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    exact = B.byz_aggregate_took_exact_path(ws)
-
-    B.byz_profile_enable(args.steps)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    kernel_ms = B.byz_profile_collect(args.steps)
-    B.byz_profile_enable(0)
-
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step, kernel_ms, exact = timed(0)
     coords_per_s = d / (ms_per_step * 1e-3)
     alg_bytes = 4.0 * (asg.r * asg.f + 1) * d  # every copy read once, one value written
     result = {
@@ -147,6 +150,26 @@ def main():
             "traffic": _traffic_from_profiles(cfg.name),
             "algorithmic_bytes_per_launch": alg_bytes,
             "avg_kernel_ms": avg_ms, "min_kernel_ms": min(kernel_ms), "launches_timed": len(kernel_ms),
+        }
+
+    # Same result with fewer bytes: r' identical copies already are the majority, so the
+    # other r - r' copies of a file need not be read (BYZ_AGG_EARLY_MAJORITY).  Reported
+    # beside the headline, never as `value`.
+    if not args.no_early:
+        rp = (asg.r + 1) // 2
+        e_ms, e_kernel_ms, e_exact = timed(B.BYZ_AGG_EARLY_MAJORITY)
+        e_bytes = 4.0 * (rp * asg.f + 1) * d
+        e_avg = sum(e_kernel_ms) / len(e_kernel_ms) if e_kernel_ms else None
+        result["early_majority"] = {
+            "value": d / (e_ms * 1e-3), "unit": "coords/s", "ms_per_step": e_ms,
+            "took_exact_path": bool(e_exact),
+            "note": "reads r'=%d of r=%d copies of a file when the probe finds a majority class; "
+                    "falls back to all r (as the headline run) if any file has none" % (rp, asg.r),
+            "roofline": None if e_avg is None else {
+                "bound": "hbm", "achieved": e_bytes / (e_avg * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": e_bytes / (e_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                "algorithmic_bytes_per_launch_if_all_files_have_a_majority": e_bytes,
+                "avg_kernel_ms": e_avg},
         }
 
     if not args.no_cpu:

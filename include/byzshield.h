@@ -166,6 +166,20 @@ int byz_aggregate(const float *copies, int64_t d, int64_t ld, const int32_t *fil
                   size_t workspace_bytes, void *stream);
 
 /*
+ * byz_aggregate with options.  flags = 0 is byz_aggregate.
+ *   BYZ_AGG_EARLY_MAJORITY  r' = (r+1)/2 copies that are identical on all d coordinates are the
+ *     majority whatever the other r - r' copies hold (Sec. 2: a file is distorted only if at
+ *     least r' of its copies are), so for every file whose probable winner's class has at
+ *     least r' members only r' copies are read and verified.  Same output as flags = 0 for
+ *     every input; HBM traffic drops from 4(rf+1) towards 4(r'f+1) bytes per coordinate.
+ * Errors: as byz_aggregate; BYZ_EINVAL for unknown flag bits.
+ */
+#define BYZ_AGG_EARLY_MAJORITY 1u
+int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld, const int32_t *file_rows_dev,
+                       int f, int r, float *out, int32_t *winner_replica, void *workspace,
+                       size_t workspace_bytes, unsigned flags, void *stream);
+
+/*
  * After byz_aggregate's work on `stream` has completed: copies 0/1 into *took_exact_path
  * (host) from the workspace (device) -- 1 if the two-step path had to run.  Synchronises the
  * stream.  Diagnostic only.

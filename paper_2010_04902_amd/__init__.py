@@ -4,11 +4,13 @@ Thin Python binding over the C-ABI of libbyzshield.so; every step of the path ru
 library's HIP kernels / host code.  PyTorch is used for device memory and streams only.
 """
 from .binding import (  # noqa: F401
+    BYZ_AGG_EARLY_MAJORITY,
     BYZ_SCHEME_MOLS,
     BYZ_SCHEME_RAMANUJAN,
     Assignment,
     ByzError,
     byz_aggregate,
+    byz_aggregate_opts,
     byz_aggregate_took_exact_path,
     byz_aggregate_workspace_bytes,
     byz_build_assignment,

@@ -59,6 +59,8 @@ def _load():
         "byz_median": (c_int, [vp, i64, i64, vp, c_int, vp, vp]),
         "byz_aggregate_workspace_bytes": (sz, [c_int, c_int]),
         "byz_aggregate": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, sz, vp]),
+        "byz_aggregate_opts": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, sz,
+                                       ctypes.c_uint, vp]),
         "byz_aggregate_took_exact_path": (c_int, [vp, ip, vp]),
         "byz_calibration_copy": (c_int, [vp, vp, sz, vp]),
         "byz_profile_enable": (c_int, [c_int]),
@@ -196,8 +198,18 @@ def byz_aggregate_workspace_bytes(f, r):
     return int(_load().byz_aggregate_workspace_bytes(int(f), int(r)))
 
 
+BYZ_AGG_EARLY_MAJORITY = 1
+
+
+def byz_aggregate_opts(copies, d, file_rows_dev, f, r, flags, out=None, winner_replica=None,
+                       workspace=None, stream=None):
+    """byz_aggregate with option flags (BYZ_AGG_EARLY_MAJORITY); same returns."""
+    return byz_aggregate(copies, d, file_rows_dev, f, r, out=out, winner_replica=winner_replica,
+                         workspace=workspace, stream=stream, _flags=int(flags))
+
+
 def byz_aggregate(copies, d, file_rows_dev, f, r, out=None, winner_replica=None, workspace=None,
-                  stream=None):
+                  stream=None, _flags=None):
     """-> (out[d] float32, winner_replica[f] int32, workspace uint8 tensor), on device."""
     torch = _torch()
     ld = _rows_2d(copies)
@@ -210,12 +222,15 @@ def byz_aggregate(copies, d, file_rows_dev, f, r, out=None, winner_replica=None,
         if nbytes == 0:
             raise ByzError(-1, "byz_aggregate_workspace_bytes")
         workspace = torch.empty(nbytes, dtype=torch.uint8, device=copies.device)
-    _check(_load().byz_aggregate(_dev_ptr(copies, ("float32",), "copies"), int(d), ld,
-                                 _dev_ptr(file_rows_dev, ("int32",), "file_rows_dev"), int(f),
-                                 int(r), _dev_ptr(out, ("float32",), "out"),
-                                 _dev_ptr(winner_replica, ("int32",), "winner_replica"),
-                                 _dev_ptr(workspace, ("uint8",), "workspace"),
-                                 int(workspace.numel()), _stream_ptr(stream)), "byz_aggregate")
+    args = [_dev_ptr(copies, ("float32",), "copies"), int(d), ld,
+            _dev_ptr(file_rows_dev, ("int32",), "file_rows_dev"), int(f), int(r),
+            _dev_ptr(out, ("float32",), "out"),
+            _dev_ptr(winner_replica, ("int32",), "winner_replica"),
+            _dev_ptr(workspace, ("uint8",), "workspace"), int(workspace.numel())]
+    if _flags is None:
+        _check(_load().byz_aggregate(*args, _stream_ptr(stream)), "byz_aggregate")
+    else:
+        _check(_load().byz_aggregate_opts(*args, _flags, _stream_ptr(stream)), "byz_aggregate_opts")
     return out, winner_replica, workspace
 
 

@@ -44,11 +44,24 @@ thread_local ProfileState g_prof;
 #define BYZ_NT_LOADS 1
 #endif
 
-// Files the single-pass kernel prefetches ahead of the one it consumes.  Measured on MI355X:
-// f = 25 (4 waves per SIMD) is fastest with 1, f = 49 (2 waves per SIMD) with 3.
-#ifndef BYZ_AHEAD_EXPR
-#define BYZ_AHEAD_EXPR (F >= 49 ? 3 : 1)
+// Files the single-pass kernel prefetches ahead of the one it consumes, from the number of
+// 16-byte loads per thread it should keep in flight.  Measured on MI355X: about 6 for f = 25
+// (3-4 waves per SIMD), about 12 for f = 49 (2 waves per SIMD); more is slower.
+#ifndef BYZ_INFLIGHT_SMALL
+#define BYZ_INFLIGHT_SMALL 6
 #endif
+#ifndef BYZ_INFLIGHT_LARGE
+#define BYZ_INFLIGHT_LARGE 12
+#endif
+constexpr int prefetch_depth(int f, int slots) {
+    const int target = f >= 49 ? BYZ_INFLIGHT_LARGE : BYZ_INFLIGHT_SMALL;
+    const int a = (target + slots - 1) / slots - 1;
+    return a < 1 ? 1 : (a > 5 ? 5 : a);
+}
+#ifndef BYZ_PROBE
+#define BYZ_PROBE 256
+#endif
+constexpr int kProbe = BYZ_PROBE;  // sampled coordinates = threads of the probe block
 #ifndef BYZ_BLOCK
 #define BYZ_BLOCK 256
 #endif
@@ -246,8 +259,9 @@ struct AggWorkspace {
     int32_t prov_winner[BYZ_MAX_F];  // probable winner (original replica index)
     int32_t winner_row[BYZ_MAX_F];   // exact path result
     uint32_t need_exact;             // 1 iff the exact path ran
+    uint32_t slots_per_file;         // slots of every file the single pass reads: r or r'
     uint32_t ticket_vote;            // blocks of the exact-path vote kernel that have finished
-    uint32_t pad[62];
+    uint32_t pad[61];
 };
 
 // ------------------------------------------------------------------------------ kernels
@@ -411,17 +425,18 @@ __global__ __launch_bounds__(kBlock) void median_generic_kernel(
     out[c] = from_key(result);
 }
 
-// Probe: compares the copies of every file on a sample of <= 512 coordinates (32 runs of 16
-// consecutive words spread over [0, d); all of [0, d) when d <= 512), derives the probable
+// Probe: compares the copies of every file on a sample of <= kProbe coordinates (kProbe/16 runs
+// of 16 consecutive words spread over [0, d); all of [0, d) when d <= kProbe), derives the probable
 // equality classes, and lays out the rows of each file with the probable winner first and
 // equal-looking copies adjacent.  Also clears the state the later kernels accumulate into.
-// One block of 512 threads.
+// One block of kProbe threads.
 template <int F, int R>
-__global__ __launch_bounds__(512) void probe_kernel(const uint32_t *__restrict__ X, int64_t d,
+__global__ __launch_bounds__(kProbe) void probe_kernel(const uint32_t *__restrict__ X, int64_t d,
                                                     int64_t ld,
                                                     const int32_t *__restrict__ file_rows,
-                                                    AggWorkspace *ws) {
+                                                    AggWorkspace *ws, int early_majority) {
     __shared__ uint32_t s_neq[BYZ_MAX_F];
+    __shared__ uint32_t s_all_majority;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     if (tid < BYZ_MAX_F) {
@@ -430,6 +445,7 @@ __global__ __launch_bounds__(512) void probe_kernel(const uint32_t *__restrict__
         ws->pair_neq[tid] = 0;
     }
     if (tid == 0) {
+        s_all_majority = 1;
         ws->need_exact = 0;
         ws->ticket_vote = 0;
     }
@@ -437,14 +453,14 @@ __global__ __launch_bounds__(512) void probe_kernel(const uint32_t *__restrict__
 
     // threads without a sample coordinate of their own redo coordinate 0
     int64_t c = 0;
-    if (d <= 512) {
+    if (d <= kProbe) {
         if (tid < d) c = tid;
     } else {
         const int64_t run = tid >> 4, off = tid & 15;
-        c = run * ((d - 16) / 31) + off;
+        c = run * ((d - 16) / (kProbe / 16 - 1)) + off;
     }
     // files in groups of G: all loads of a group are issued before the first ballot waits
-    constexpr int G = 36 / R;
+    constexpr int G = (F * R <= 192) ? F : 192 / R;
     uint32_t flags = 0;
 #pragma unroll
     for (int j0 = 0; j0 < F; j0 += G) {
@@ -490,37 +506,52 @@ __global__ __launch_bounds__(512) void probe_kernel(const uint32_t *__restrict__
             for (int k = 0; k < R; ++k)
                 if (label[k] == c0) perm[n++] = k;
         }
+        // Early-majority mode: once r' = (R+1)/2 copies are known to be identical they are the
+        // majority whatever the other copies hold (Sec. 2), so when the probable winner's class
+        // has at least r' members only its first r' are read and verified; the remaining slots
+        // repeat slot 0 (served from cache) and carry no assumption.
+        int members = 0;
+        for (int k = 0; k < R; ++k) members += label[k] == label[w] ? 1 : 0;
+        const int need = (R + 1) / 2;
+        const int slots = (early_majority != 0 && members >= need) ? need : R;
         uint32_t chain = 0;
         for (int p = 0; p < R; ++p) {
-            const int32_t row = file_rows[j * R + perm[p]];
+            const int32_t row = file_rows[j * R + perm[p < slots ? p : 0]];
             ws->perm_rows[j * kRowStride + p] = row;
             ws->perm_off[j * kRowStride + p] = (uint64_t)row * (uint64_t)ld * 4u;
-            if (p > 0 && label[perm[p]] == label[perm[p - 1]]) chain |= 1u << (p - 1);
+            if (p > 0 && p < slots && label[perm[p]] == label[perm[p - 1]]) chain |= 1u << (p - 1);
         }
         ws->chain_mask[j] = chain;
         ws->prov_winner[j] = w;
+        if (slots != need) s_all_majority = 0;
     }
+    __syncthreads();
+    // if every file gets by with r' slots, the single pass loads only those
+    if (tid == 0) ws->slots_per_file = (early_majority != 0 && s_all_majority != 0) ? (R + 1) / 2 : R;
 }
 
 // Steps of the generated streamed programs (selnet_stream_<f>.inc), written against the local
 // names of fused_kernel.
 #define BYZ_S_LOAD_(j)                                                                        \
-    _Pragma("unroll") for (int k_ = 0; k_ < R; ++k_)                                          \
+    _Pragma("unroll") for (int k_ = 0; k_ < NS; ++k_)                                         \
         load_vec<V>(reinterpret_cast<const uint32_t *>(                                       \
                         Xb + perm_off[(j) * kRowStride + k_] + voff),                         \
                     stage[(j) % (kAhead + 1)][k_]);
 #define BYZ_S_LOAD1(j) if constexpr (kAhead == 1) { BYZ_S_LOAD_(j) }
 #define BYZ_S_LOAD2(j) if constexpr (kAhead == 2) { BYZ_S_LOAD_(j) }
 #define BYZ_S_LOAD3(j) if constexpr (kAhead == 3) { BYZ_S_LOAD_(j) }
+#define BYZ_S_LOAD4(j) if constexpr (kAhead == 4) { BYZ_S_LOAD_(j) }
+#define BYZ_S_LOAD5(j) if constexpr (kAhead == 5) { BYZ_S_LOAD_(j) }
 #define BYZ_S_USE(j)                                                                          \
     {                                                                                         \
         uint32_t wb_ = 0;                                                                     \
-        _Pragma("unroll") for (int k_ = 1; k_ < R; ++k_)                                      \
-            wb_ |= wave_any(differ<V>(stage[(j) % (kAhead + 1)][k_ - 1], stage[(j) % (kAhead + 1)][k_])) << (k_ - 1); \
+        _Pragma("unroll") for (int k_ = 1; k_ < NS; ++k_)                                     \
+            wb_ |= wave_any(differ<V>(stage[(j) % (kAhead + 1)][k_ - 1],                      \
+                                      stage[(j) % (kAhead + 1)][k_])) << (k_ - 1);            \
         wb_ &= chain_mask[j];                                                                 \
         if (lane == (j)) flags |= wb_;                                                        \
         _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_)                                      \
-            key[v_][j] = to_key(stage[(j) % (kAhead + 1)][0][v_]);                                       \
+            key[v_][j] = to_key(stage[(j) % (kAhead + 1)][0][v_]);                            \
     }
 #define BYZ_S_CE(i, j)                                                                        \
     _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_) {                                        \
@@ -537,20 +568,19 @@ __global__ __launch_bounds__(512) void probe_kernel(const uint32_t *__restrict__
 #define BYZ_S_MEDIAN(w)                                                                       \
     _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_) o[v_] = from_key(key[v_][w]);
 
-// Fused a1+a2+a3: streams all R*F rows once.  The probable winner of each file (slot 0 of
-// its permuted row list) feeds the median network; every equality the probe assumed between
-// neighbouring slots is checked over all coordinates and violations are recorded per file
-// (ws->viol).  No violation -> the probable classes are the true ones, the output and the
-// probable winners are final; otherwise the kernels of the exact path, gated on ws->viol, redo
-// the aggregation.
-#ifndef BYZ_FUSED_ATTR
-#define BYZ_FUSED_ATTR
-#endif
-template <int F, int R, int V>
-__global__ __launch_bounds__(kBlock) BYZ_FUSED_ATTR void fused_kernel(
-    const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ perm_rows,
-    const uint64_t *__restrict__ perm_off, const uint32_t *__restrict__ chain_mask,
-    AggWorkspace *ws, uint32_t *__restrict__ out) {
+// Fused a1+a2+a3: streams the first NS slots of every file's permuted row list once (NS = R:
+// every copy; NS = r' = (R+1)/2 in early-majority mode when every file has a probable
+// majority).  Slot 0 (the probable winner) feeds the median network; every equality the
+// probe assumed between neighbouring slots is checked over all coordinates and violations are
+// recorded per file (ws->viol).  No violation -> the probable classes are the true ones, the
+// output and the probable winners are final; otherwise the kernels of the exact path, gated
+// on ws->viol, redo the aggregation.
+template <int F, int R, int NS, int V>
+__device__ __forceinline__ void fused_body(const uint32_t *__restrict__ X, int64_t d, int64_t ld,
+                                           const int32_t *__restrict__ perm_rows,
+                                           const uint64_t *__restrict__ perm_off,
+                                           const uint32_t *__restrict__ chain_mask,
+                                           AggWorkspace *ws, uint32_t *__restrict__ out) {
     const int lane = threadIdx.x & 63;
     const int64_t n_vec = d / V;
     const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
@@ -561,12 +591,12 @@ __global__ __launch_bounds__(kBlock) BYZ_FUSED_ATTR void fused_kernel(
         const char *Xb = reinterpret_cast<const char *>(X);
         uint32_t key[V][F];       // wire j of the median network = file j
         // files prefetched ahead of the one being consumed
-        constexpr int kAhead = BYZ_AHEAD_EXPR;
-        uint32_t stage[kAhead + 1][R][V];  // copies of the file in use and of those in flight
+        constexpr int kAhead = prefetch_depth(F, NS);
+        uint32_t stage[kAhead + 1][NS][V];  // copies of the file in use and of those in flight
         uint32_t o[V];
-        // The generated program walks the files in order: the loads of file j+1 are issued
-        // before file j is consumed (compares, key), followed by every comparator of the
-        // median network whose inputs are complete by then.
+        // The generated program walks the files in order: the loads of file j+kAhead are
+        // issued before file j is consumed (compares, key), followed by every comparator of
+        // the median network whose inputs are complete by then.
         if constexpr (F == 9) {
 #include "generated/selnet_stream_9.inc"
         } else if constexpr (F == 25) {
@@ -583,12 +613,12 @@ __global__ __launch_bounds__(kBlock) BYZ_FUSED_ATTR void fused_kernel(
         uint32_t key[F];
 #pragma unroll
         for (int j = 0; j < F; ++j) {
-            uint32_t x[R];
+            uint32_t x[NS];
 #pragma unroll
-            for (int k = 0; k < R; ++k) x[k] = X[(int64_t)perm_rows[j * kRowStride + k] * ld + c];
+            for (int k = 0; k < NS; ++k) x[k] = X[(int64_t)perm_rows[j * kRowStride + k] * ld + c];
             uint32_t bits = 0;
 #pragma unroll
-            for (int k = 1; k < R; ++k) bits |= (x[k - 1] != x[k] ? 1u : 0u) << (k - 1);
+            for (int k = 1; k < NS; ++k) bits |= (x[k - 1] != x[k] ? 1u : 0u) << (k - 1);
             bits &= chain_mask[j];
             if (bits != 0) atomicOr(&ws->viol[j], bits);
             key[j] = to_key(x[0]);
@@ -596,6 +626,21 @@ __global__ __launch_bounds__(kBlock) BYZ_FUSED_ATTR void fused_kernel(
         out[c] = from_key(SelNet<F>::median(key));
     }
     merge_flags(ws->viol, F, lane, flags);
+}
+
+#ifndef BYZ_FUSED_ATTR
+#define BYZ_FUSED_ATTR
+#endif
+template <int F, int R, int V>
+__global__ __launch_bounds__(kBlock) BYZ_FUSED_ATTR void fused_kernel(
+    const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ perm_rows,
+    const uint64_t *__restrict__ perm_off, const uint32_t *__restrict__ chain_mask,
+    const uint32_t *__restrict__ slots_per_file, AggWorkspace *ws, uint32_t *__restrict__ out) {
+    // wave-uniform choice written by the probe
+    if (*slots_per_file == (R + 1) / 2)
+        fused_body<F, R, (R + 1) / 2, V>(X, d, ld, perm_rows, perm_off, chain_mask, ws, out);
+    else
+        fused_body<F, R, R, V>(X, d, ld, perm_rows, perm_off, chain_mask, ws, out);
 }
 
 // ---------------------------------------------------------------------------- launchers
@@ -673,13 +718,13 @@ int launch_median(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_i
 
 template <int F, int R>
 int launch_fused(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, AggWorkspace *ws,
-                 uint32_t *out, hipStream_t s) {
-    probe_kernel<F, R><<<1, 512, 0, s>>>(X, d, ld, rows, ws);
+                 uint32_t *out, int early_majority, hipStream_t s) {
+    probe_kernel<F, R><<<1, kProbe, 0, s>>>(X, d, ld, rows, ws, early_majority);
     BYZ_HIP(hipGetLastError());
     const bool timed = g_prof.count < g_prof.capacity;
     if (timed) BYZ_HIP(hipEventRecord(g_prof.start[g_prof.count], s));
     fused_kernel<F, R, kVec><<<blocks_for(d / kVec), kBlock, 0, s>>>(
-        X, d, ld, ws->perm_rows, ws->perm_off, ws->chain_mask, ws, out);
+        X, d, ld, ws->perm_rows, ws->perm_off, ws->chain_mask, &ws->slots_per_file, ws, out);
     BYZ_HIP(hipGetLastError());
     if (timed) {
         BYZ_HIP(hipEventRecord(g_prof.stop[g_prof.count], s));
@@ -744,10 +789,12 @@ extern "C" size_t byz_aggregate_workspace_bytes(int f, int r) {
     return sizeof(AggWorkspace);
 }
 
-extern "C" int byz_aggregate(const float *copies, int64_t d, int64_t ld,
-                             const int32_t *file_rows_dev, int f, int r, float *out,
-                             int32_t *winner_replica, void *workspace, size_t workspace_bytes,
-                             void *stream) {
+extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
+                                  const int32_t *file_rows_dev, int f, int r, float *out,
+                                  int32_t *winner_replica, void *workspace, size_t workspace_bytes,
+                                  unsigned flags, void *stream) {
+    if ((flags & ~(unsigned)BYZ_AGG_EARLY_MAJORITY) != 0) return BYZ_EINVAL;
+    const int early = (flags & BYZ_AGG_EARLY_MAJORITY) != 0 ? 1 : 0;
     int rc = check_common(copies, d, ld, file_rows_dev, f, r);
     if (rc != BYZ_OK) return rc;
     if ((out == nullptr && d > 0) || workspace == nullptr) return BYZ_EINVAL;
@@ -778,17 +825,25 @@ extern "C" int byz_aggregate(const float *copies, int64_t d, int64_t ld,
 
     // probe -> single pass -> exact path, whose two kernels return at once unless the single
     // pass recorded a violated assumption
-    if (f == 9) rc = launch_fused<9, 3>(X, d, ld, file_rows_dev, ws, O, s);
-    else if (f == 25 && r == 3) rc = launch_fused<25, 3>(X, d, ld, file_rows_dev, ws, O, s);
-    else if (f == 25 && r == 5) rc = launch_fused<25, 5>(X, d, ld, file_rows_dev, ws, O, s);
-    else if (f == 49 && r == 3) rc = launch_fused<49, 3>(X, d, ld, file_rows_dev, ws, O, s);
-    else rc = launch_fused<49, 5>(X, d, ld, file_rows_dev, ws, O, s);
+    if (f == 9) rc = launch_fused<9, 3>(X, d, ld, file_rows_dev, ws, O, early, s);
+    else if (f == 25 && r == 3) rc = launch_fused<25, 3>(X, d, ld, file_rows_dev, ws, O, early, s);
+    else if (f == 25 && r == 5) rc = launch_fused<25, 5>(X, d, ld, file_rows_dev, ws, O, early, s);
+    else if (f == 49 && r == 3) rc = launch_fused<49, 3>(X, d, ld, file_rows_dev, ws, O, early, s);
+    else rc = launch_fused<49, 5>(X, d, ld, file_rows_dev, ws, O, early, s);
     if (rc != BYZ_OK) return rc;
     rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, ws->viol,
                              &ws->ticket_vote, winner_replica, ws->winner_row, ws->prov_winner,
                              &ws->need_exact, s);
     if (rc != BYZ_OK) return rc;
     return launch_median(X, d, ld, ws->winner_row, f, O, ws->viol, f, s);
+}
+
+extern "C" int byz_aggregate(const float *copies, int64_t d, int64_t ld,
+                             const int32_t *file_rows_dev, int f, int r, float *out,
+                             int32_t *winner_replica, void *workspace, size_t workspace_bytes,
+                             void *stream) {
+    return byz_aggregate_opts(copies, d, ld, file_rows_dev, f, r, out, winner_replica, workspace,
+                              workspace_bytes, 0u, stream);
 }
 
 extern "C" int byz_calibration_copy(const void *src, void *dst, size_t bytes, void *stream) {

@@ -20,6 +20,8 @@ DEV = "cuda:0"
 def _full_check(w, tag):
     rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
     out, wrep, ws = B.byz_aggregate(w.X, w.d, rows_dev, w.f, w.r)
+    out_e, wrep_e, ws_e = B.byz_aggregate_opts(w.X, w.d, rows_dev, w.f, w.r,
+                                               B.BYZ_AGG_EARLY_MAJORITY)
     wrep_v, wrow_v, neq_v = B.byz_vote(w.X, w.d, rows_dev, w.f, w.r)
     out_m = B.byz_median(w.X, w.d, wrow_v)
     torch.cuda.synchronize()
@@ -33,6 +35,9 @@ def _full_check(w, tag):
     assert np.array_equal(wrow_v.cpu().numpy(), wrow_o), tag
     assert np.array_equal(W.bits(neq_v), neq_o), tag
     assert np.array_equal(W.bits(out), W.bits(out_o)), tag
+    assert np.array_equal(W.bits(out_e), W.bits(out_o)), tag
+    assert np.array_equal(wrep_e.cpu().numpy(), wrep_o), tag
+    assert not B.byz_aggregate_took_exact_path(ws_e), tag
     assert np.array_equal(W.bits(out_m), W.bits(out_o)), tag
     assert not took_exact, tag  # these attacks differ from the honest copy on the probe sample
     # Sec. 2: exactly the files with >= r' Byzantine copies lose the vote; the paper's c_max

@@ -41,13 +41,18 @@ def _check_all(X, rows_np, d, f, r, expect_exact=None, tag=""):
     torch.cuda.synchronize()
     assert np.array_equal(W.bits(out_m), W.bits(out_o)), tag
 
+    for flags in (B.BYZ_AGG_EARLY_MAJORITY, 0):
+        out, wrep2, ws = B.byz_aggregate_opts(X, d, rows_dev, f, r, flags)
+        torch.cuda.synchronize()
+        assert np.array_equal(W.bits(out), W.bits(out_o)), (tag, flags)
+        assert np.array_equal(wrep2.cpu().numpy(), wrep_o), (tag, flags)
+        took_exact = B.byz_aggregate_took_exact_path(ws)
+        if expect_exact is not None and flags == 0:
+            assert took_exact == expect_exact, tag
     out, wrep2, ws = B.byz_aggregate(X, d, rows_dev, f, r)
     torch.cuda.synchronize()
     assert np.array_equal(W.bits(out), W.bits(out_o)), tag
     assert np.array_equal(wrep2.cpu().numpy(), wrep_o), tag
-    took_exact = B.byz_aggregate_took_exact_path(ws)
-    if expect_exact is not None:
-        assert took_exact == expect_exact, tag
     return out_o, wrep_o, took_exact
 
 
@@ -108,11 +113,11 @@ def _plant(X, rows_np, j, k, coords, value):
 
 
 def test_copy_that_matches_on_the_probe_sample_but_differs_elsewhere():
-    # The probe looks at 32 runs of 16 coordinates; a copy that differs only outside them
+    # The probe looks at 16 runs of 16 coordinates; a copy that differs only outside them
     # is caught by the streaming pass and the exact path must take over.
     d = 100_000
     w = W.make(MOLS, 5, 3, 0, d, REVERSED, seed=4, device=DEV)
-    stride = (d - 16) // 31
+    stride = (d - 16) // 15  # start of run u is u * stride
     unsampled = [c for c in (17, stride - 1, d - 17, d // 2 + 19) if (c % stride) >= 16]
     assert unsampled
     X = w.X.clone()
