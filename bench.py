@@ -50,6 +50,8 @@ def main():
     ap.add_argument("--unpadded", action="store_true", help="row pitch ld = d instead of d rounded up to 64")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-early", action="store_true", help="skip the early-majority leg")
+    ap.add_argument("--components", action="store_true",
+                    help="also time the two-step path's kernels (byz_vote, byz_median) on their own")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (reference for HBM counters)")
     args = ap.parse_args()
@@ -170,6 +172,30 @@ def main():
                 "unit": "GB/s", "frac": e_bytes / (e_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                 "algorithmic_bytes_per_launch_if_all_files_have_a_majority": e_bytes,
                 "avg_kernel_ms": e_avg},
+        }
+
+    if args.components:
+        # the separate kernels of the two-step path, each timed with events on the launch stream
+        def timed_call(fn):
+            for _ in range(args.warmup):
+                fn()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            for _ in range(args.steps):
+                fn()
+            b.record(stream)
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / args.steps
+        wrep_v, wrow_v, neq_v = B.byz_vote(bufs[0], d, rows_dev, asg.f, asg.r, stream=stream)
+        ms_vote = timed_call(lambda: B.byz_vote(bufs[0], d, rows_dev, asg.f, asg.r, stream=stream))
+        ms_med = timed_call(lambda: B.byz_median(bufs[0], d, wrow_v, out=out, stream=stream))
+        vb, mb = 4.0 * asg.r * asg.f * d, 4.0 * (asg.f + 1) * d
+        result["components"] = {
+            "byz_vote": {"ms": ms_vote, "algorithmic_bytes": vb, "gbps": vb / ms_vote / 1e6,
+                         "frac": vb / ms_vote / 1e6 / HBM_PEAK_GBPS,
+                         "note": "fill + vote_pairs_kernel + vote_decide_kernel"},
+            "byz_median": {"ms": ms_med, "algorithmic_bytes": mb, "gbps": mb / ms_med / 1e6,
+                           "frac": mb / ms_med / 1e6 / HBM_PEAK_GBPS},
         }
 
     if not args.no_cpu:

@@ -373,6 +373,47 @@ __global__ __launch_bounds__(kBlock) void vote_pairs_kernel(
         decide_files(pair_neq, file_rows, f, R, winner_replica, winner_row);
 }
 
+// Steps of the generated streamed programs (selnet_stream_<f>.inc), written against local names
+// of the kernel that includes them: NS slots per file, V words per thread, kAhead, stage, key,
+// o, lane, flags, chain_mask, and BYZ_S_ROW_ADDR(j, k) = address of this thread's vector in
+// slot k of file j.
+#define BYZ_S_LOAD_(j)                                                                        \
+    _Pragma("unroll") for (int k_ = 0; k_ < NS; ++k_)                                         \
+        load_vec<V>(reinterpret_cast<const uint32_t *>(BYZ_S_ROW_ADDR(j, k_)),                \
+                    stage[(j) % (kAhead + 1)][k_]);
+#define BYZ_S_LOAD1(j) if constexpr (kAhead == 1) { BYZ_S_LOAD_(j) }
+#define BYZ_S_LOAD2(j) if constexpr (kAhead == 2) { BYZ_S_LOAD_(j) }
+#define BYZ_S_LOAD3(j) if constexpr (kAhead == 3) { BYZ_S_LOAD_(j) }
+#define BYZ_S_LOAD4(j) if constexpr (kAhead == 4) { BYZ_S_LOAD_(j) }
+#define BYZ_S_LOAD5(j) if constexpr (kAhead == 5) { BYZ_S_LOAD_(j) }
+#define BYZ_S_USE(j)                                                                          \
+    {                                                                                         \
+        if constexpr (NS > 1) {                                                               \
+        uint32_t wb_ = 0;                                                                     \
+        _Pragma("unroll") for (int k_ = 1; k_ < NS; ++k_)                                     \
+            wb_ |= wave_any(differ<V>(stage[(j) % (kAhead + 1)][k_ - 1],                      \
+                                      stage[(j) % (kAhead + 1)][k_])) << (k_ - 1);            \
+        wb_ &= chain_mask[j];                                                                 \
+        if (lane == (j)) flags |= wb_;                                                        \
+        }                                                                                     \
+        _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_)                                      \
+            key[v_][j] = to_key(stage[(j) % (kAhead + 1)][0][v_]);                            \
+    }
+#define BYZ_S_CE(i, j)                                                                        \
+    _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_) {                                        \
+        const uint32_t a_ = key[v_][i], b_ = key[v_][j];                                      \
+        key[v_][i] = a_ < b_ ? a_ : b_;                                                       \
+        key[v_][j] = a_ < b_ ? b_ : a_;                                                       \
+    }
+#define BYZ_S_CE_LO(i, j)                                                                     \
+    _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_)                                          \
+        key[v_][i] = key[v_][i] < key[v_][j] ? key[v_][i] : key[v_][j];
+#define BYZ_S_CE_HI(i, j)                                                                     \
+    _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_)                                          \
+        key[v_][j] = key[v_][i] < key[v_][j] ? key[v_][j] : key[v_][i];
+#define BYZ_S_MEDIAN(w)                                                                       \
+    _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_) o[v_] = from_key(key[v_][w]);
+
 // Step a3: coordinate-wise median of F rows by a register selection network.
 template <int F, int V>
 __global__ __launch_bounds__(kBlock) void median_kernel(
@@ -382,18 +423,40 @@ __global__ __launch_bounds__(kBlock) void median_kernel(
     const int64_t n_vec = d / V;
     const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (gt < n_vec) {
-        const uint32_t *base = X + gt * V;
         uint32_t key[V][F];
-#pragma unroll
-        for (int j = 0; j < F; ++j) {
-            uint32_t x[V];
-            load_vec<V>(base + (int64_t)row_index[j] * ld, x);
-#pragma unroll
-            for (int v = 0; v < V; ++v) key[v][j] = to_key(x[v]);
-        }
         uint32_t o[V];
+        if constexpr (F == 9 || F == 25 || F == 49) {
+            // same streamed program as the single-pass kernel, one slot per file, no compares
+            constexpr int NS = 1;
+            constexpr int kAhead = prefetch_depth(F, NS);
+            const uint32_t voff = (uint32_t)(gt * (V * 4));
+            const char *Xb = reinterpret_cast<const char *>(X);
+            uint32_t stage[kAhead + 1][NS][V];
+            const uint32_t *chain_mask = nullptr;  // unused with one slot per file
+            const int lane = 0;
+            uint32_t flags = 0;
+            (void)chain_mask; (void)lane; (void)flags;
+#define BYZ_S_ROW_ADDR(j, k) (Xb + (uint64_t)(uint32_t)row_index[j] * (uint64_t)ld * 4u + voff)
+            if constexpr (F == 9) {
+#include "generated/selnet_stream_9.inc"
+            } else if constexpr (F == 25) {
+#include "generated/selnet_stream_25.inc"
+            } else {
+#include "generated/selnet_stream_49.inc"
+            }
+#undef BYZ_S_ROW_ADDR
+        } else {
+            const uint32_t *base = X + gt * V;
 #pragma unroll
-        for (int v = 0; v < V; ++v) o[v] = from_key(SelNet<F>::median(key[v]));
+            for (int j = 0; j < F; ++j) {
+                uint32_t x[V];
+                load_vec<V>(base + (int64_t)row_index[j] * ld, x);
+#pragma unroll
+                for (int v = 0; v < V; ++v) key[v][j] = to_key(x[v]);
+            }
+#pragma unroll
+            for (int v = 0; v < V; ++v) o[v] = from_key(SelNet<F>::median(key[v]));
+        }
         store_vec<V>(out + gt * V, o);
     }
     const int tail = (int)(d - n_vec * V);
@@ -530,44 +593,6 @@ __global__ __launch_bounds__(kProbe) void probe_kernel(const uint32_t *__restric
     if (tid == 0) ws->slots_per_file = (early_majority != 0 && s_all_majority != 0) ? (R + 1) / 2 : R;
 }
 
-// Steps of the generated streamed programs (selnet_stream_<f>.inc), written against the local
-// names of fused_kernel.
-#define BYZ_S_LOAD_(j)                                                                        \
-    _Pragma("unroll") for (int k_ = 0; k_ < NS; ++k_)                                         \
-        load_vec<V>(reinterpret_cast<const uint32_t *>(                                       \
-                        Xb + perm_off[(j) * kRowStride + k_] + voff),                         \
-                    stage[(j) % (kAhead + 1)][k_]);
-#define BYZ_S_LOAD1(j) if constexpr (kAhead == 1) { BYZ_S_LOAD_(j) }
-#define BYZ_S_LOAD2(j) if constexpr (kAhead == 2) { BYZ_S_LOAD_(j) }
-#define BYZ_S_LOAD3(j) if constexpr (kAhead == 3) { BYZ_S_LOAD_(j) }
-#define BYZ_S_LOAD4(j) if constexpr (kAhead == 4) { BYZ_S_LOAD_(j) }
-#define BYZ_S_LOAD5(j) if constexpr (kAhead == 5) { BYZ_S_LOAD_(j) }
-#define BYZ_S_USE(j)                                                                          \
-    {                                                                                         \
-        uint32_t wb_ = 0;                                                                     \
-        _Pragma("unroll") for (int k_ = 1; k_ < NS; ++k_)                                     \
-            wb_ |= wave_any(differ<V>(stage[(j) % (kAhead + 1)][k_ - 1],                      \
-                                      stage[(j) % (kAhead + 1)][k_])) << (k_ - 1);            \
-        wb_ &= chain_mask[j];                                                                 \
-        if (lane == (j)) flags |= wb_;                                                        \
-        _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_)                                      \
-            key[v_][j] = to_key(stage[(j) % (kAhead + 1)][0][v_]);                            \
-    }
-#define BYZ_S_CE(i, j)                                                                        \
-    _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_) {                                        \
-        const uint32_t a_ = key[v_][i], b_ = key[v_][j];                                      \
-        key[v_][i] = a_ < b_ ? a_ : b_;                                                       \
-        key[v_][j] = a_ < b_ ? b_ : a_;                                                       \
-    }
-#define BYZ_S_CE_LO(i, j)                                                                     \
-    _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_)                                          \
-        key[v_][i] = key[v_][i] < key[v_][j] ? key[v_][i] : key[v_][j];
-#define BYZ_S_CE_HI(i, j)                                                                     \
-    _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_)                                          \
-        key[v_][j] = key[v_][i] < key[v_][j] ? key[v_][j] : key[v_][i];
-#define BYZ_S_MEDIAN(w)                                                                       \
-    _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_) o[v_] = from_key(key[v_][w]);
-
 // Fused a1+a2+a3: streams the first NS slots of every file's permuted row list once (NS = R:
 // every copy; NS = r' = (R+1)/2 in early-majority mode when every file has a probable
 // majority).  Slot 0 (the probable winner) feeds the median network; every equality the
@@ -597,6 +622,7 @@ __device__ __forceinline__ void fused_body(const uint32_t *__restrict__ X, int64
         // The generated program walks the files in order: the loads of file j+kAhead are
         // issued before file j is consumed (compares, key), followed by every comparator of
         // the median network whose inputs are complete by then.
+#define BYZ_S_ROW_ADDR(j, k) (Xb + perm_off[(j) * kRowStride + (k)] + voff)
         if constexpr (F == 9) {
 #include "generated/selnet_stream_9.inc"
         } else if constexpr (F == 25) {
@@ -605,6 +631,7 @@ __device__ __forceinline__ void fused_body(const uint32_t *__restrict__ X, int64
             static_assert(F == 49, "no streamed network generated for this f");
 #include "generated/selnet_stream_49.inc"
         }
+#undef BYZ_S_ROW_ADDR
         if (gt < n_vec) store_vec<V>(out + gt * V, o);
     }
     const int tail = (int)(d - n_vec * V);
