@@ -26,4 +26,7 @@ CONFIGS = [
     # ResNet-50-sized d, MOLS l=7, r=3, ALIE z=1.5, q = 6, 20 steps of fresh gradients
     Config("cfg5_mols7x3_resnet50_alie_20steps", MOLS, 7, 3, 21, 49, 7, 3, 6, 12, 25557032,
            {"kind": "alie", "z": 1.5}, 20, 20101004 + 4),
+    # beyond the five: the paper's Table 5 cluster, MOLS l=7, r=5 (245 rows), mixed attack, q = 6
+    Config("cfg6_mols7x5_resnet18_mixed", MOLS, 7, 5, 35, 49, 7, 5, 6, 4, 11173962,
+           {"kind": "mixed", "z": 1.0, "value": 1e3, "file_scales": True}, 1, 20101004 + 35),
 ]

@@ -87,3 +87,14 @@ def test_config5_twenty_steps():
         assert prev is None or not torch.equal(head, prev)
         prev = head
         del w
+
+
+def test_table5_cluster_shape_full_size():
+    # MOLS (K,f,l,r) = (35,49,7,5) of the paper's Table 5 (245 rows), q = 6 worst-case set
+    # (c_max = 4), mixed ALIE / constant attack, at the ResNet-18 size
+    attack = {"kind": "mixed", "z": 1.0, "value": 1e3, "file_scales": True}
+    d = 11173962
+    w = W.make(B.BYZ_SCHEME_MOLS, 7, 5, 6, d, attack, seed=20101004 + 35, ld=synth.padded_ld(d, 64),
+               device=DEV)
+    assert (w.K, w.f, w.l, w.r) == (35, 49, 7, 5) and w.cmax == 4
+    assert _full_check(w, "mols7x5") == 4
