@@ -101,7 +101,8 @@ int byz_assignment_file_rows(const byz_assignment *g, int32_t *out);
  *   cmax_out          host, c_max^(q) (may be NULL)
  *   distorted_mask_out host, bit j set iff file j is distorted by the returned set (may be NULL)
  * Errors: BYZ_EINVAL (null g, q < 0, q > K), BYZ_EUNSUPPORTED (f > 64).
- * Cost grows as C(K, q); the call is single-threaded and not interruptible.
+ * Cost grows as C(K, q) (about 2*10^8 subsets per second and core); searches above 2*10^7
+ * subsets use up to 16 host threads.  Not interruptible.
  */
 int byz_worst_case(const byz_assignment *g, int q, int32_t *byz_workers_out, int32_t *cmax_out,
                    uint64_t *distorted_mask_out);

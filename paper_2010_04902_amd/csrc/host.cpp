@@ -3,7 +3,10 @@
 #include <cmath>
 #include <cstdint>
 #include <cstring>
+#include <atomic>
 #include <new>
+#include <system_error>
+#include <thread>
 #include <vector>
 
 #include "byzshield.h"
@@ -208,6 +211,66 @@ inline uint64_t at_least(const Planes &p, int need) {
     }
 }
 
+struct SearchResult {
+    int best = -1;
+    uint64_t files = 0;
+    std::vector<int> set;
+};
+
+// All q-subsets that start with the ascending workers prefix[0..p-1] (p < q or p == q == 1),
+// in lexicographic order; keeps the first one with the largest number of files that have at
+// least `need` copies inside the subset.
+SearchResult search_with_prefix(const std::vector<uint64_t> &mask, int K, int q, int need,
+                                const int *prefix, int p) {
+    SearchResult res;
+    res.set.assign((size_t)q, 0);
+    std::vector<int> cur((size_t)q + 1, 0);
+    // planes[t] = per-file counters of the first t chosen workers
+    std::vector<Planes> planes((size_t)q + 1, Planes{0, 0, 0});
+    for (int i = 0; i < p; ++i) {
+        cur[i] = prefix[i];
+        planes[i + 1] = add_mask(planes[i], mask[prefix[i]]);
+    }
+    if (p == q) {
+        const uint64_t hit = at_least(planes[p], need);
+        res.best = __builtin_popcountll(hit);
+        res.files = hit;
+        for (int i = 0; i < q; ++i) res.set[i] = prefix[i];
+        return res;
+    }
+    int t = p;
+    cur[p] = prefix[p - 1];
+    for (;;) {
+        ++cur[t];
+        if (cur[t] > K - (q - t)) {  // exhausted this position
+            if (t == p) break;
+            --t;
+            continue;
+        }
+        if (t < q - 1) {
+            planes[t + 1] = add_mask(planes[t], mask[cur[t]]);
+            cur[t + 1] = cur[t];
+            ++t;
+            continue;
+        }
+        // last position: sweep all remaining workers in a tight loop
+        const Planes base = planes[t];
+        for (int w = cur[t]; w < K; ++w) {
+            const uint64_t hit = at_least(add_mask(base, mask[w]), need);
+            const int c = __builtin_popcountll(hit);
+            if (c > res.best) {
+                res.best = c;
+                res.files = hit;
+                for (int i = 0; i < t; ++i) res.set[i] = cur[i];
+                res.set[t] = w;
+            }
+        }
+        if (t == p) break;
+        --t;
+    }
+    return res;
+}
+
 }  // namespace
 
 extern "C" int byz_worst_case(const byz_assignment *g, int q, int32_t *byz_workers_out,
@@ -222,43 +285,65 @@ extern "C" int byz_worst_case(const byz_assignment *g, int q, int32_t *byz_worke
 
     int best = -1;
     uint64_t best_files = 0;
-    std::vector<int> cur((size_t)q + 1, 0), best_set((size_t)q, 0);
+    std::vector<int> best_set((size_t)q, 0);
     if (q == 0) {
         best = 0;
     } else {
-        // depth-first over ascending tuples = lexicographic order; planes[t] = counters of the
-        // first t chosen workers.  The last position is swept in a tight loop.
-        std::vector<Planes> planes((size_t)q + 1, Planes{0, 0, 0});
-        int t = 0;
-        cur[0] = -1;
-        for (;;) {
-            // advance position t
-            ++cur[t];
-            if (cur[t] > K - (q - t)) {  // exhausted this position
-                if (t == 0) break;
-                --t;
-                continue;
-            }
-            if (t < q - 1) {
-                planes[t + 1] = add_mask(planes[t], mask[cur[t]]);
-                cur[t + 1] = cur[t];
-                ++t;
-                continue;
-            }
-            // last position: sweep all remaining workers
-            const Planes base = planes[t];
-            for (int w = cur[t]; w < K; ++w) {
-                const uint64_t hit = at_least(add_mask(base, mask[w]), need);
-                const int c = __builtin_popcountll(hit);
-                if (c > best) {
-                    best = c;
-                    best_files = hit;
-                    for (int i = 0; i < t; ++i) best_set[i] = cur[i];
-                    best_set[t] = w;
+        // One task per choice of the first one or two (smallest) workers of the set, listed in
+        // lexicographic order.  Inside a task the tuples are visited depth-first in ascending =
+        // lexicographic order, so a task's result is its first maximiser; merging the tasks in
+        // order and keeping a result only when it is strictly better keeps the overall first
+        // maximiser.
+        const int p = q >= 3 ? 2 : 1;
+        std::vector<int> prefixes;
+        for (int a0 = 0; a0 <= K - q; ++a0) {
+            if (p == 1) {
+                prefixes.push_back(a0);
+            } else {
+                for (int a1 = a0 + 1; a1 <= K - q + 1; ++a1) {
+                    prefixes.push_back(a0);
+                    prefixes.push_back(a1);
                 }
             }
-            if (t == 0) break;
-            --t;
+        }
+        const int n_tasks = (int)prefixes.size() / p;
+        std::vector<SearchResult> results((size_t)n_tasks);
+        double subsets = 1.0;
+        for (int i = 0; i < q; ++i) subsets = subsets * (K - i) / (i + 1);
+        unsigned n_threads = 1;
+        if (subsets > 2e7) {
+            n_threads = std::thread::hardware_concurrency();
+            if (n_threads < 1) n_threads = 1;
+            if (n_threads > 16) n_threads = 16;
+            if (n_threads > (unsigned)n_tasks) n_threads = (unsigned)n_tasks;
+        }
+        std::atomic<int> next_task(0);
+        auto worker = [&]() {
+            for (;;) {
+                const int first = next_task.fetch_add(1);
+                if (first >= n_tasks) break;
+                results[(size_t)first] =
+                    search_with_prefix(mask, K, q, need, &prefixes[(size_t)first * p], p);
+            }
+        };
+        if (n_threads <= 1) {
+            worker();
+        } else {
+            try {
+                std::vector<std::thread> pool;
+                for (unsigned i = 0; i < n_threads; ++i) pool.emplace_back(worker);
+                for (auto &th : pool) th.join();
+            } catch (const std::system_error &) {
+                return BYZ_ENOMEM;  // threads could not be started
+            }
+        }
+        for (int first = 0; first < n_tasks; ++first) {
+            const SearchResult &res = results[(size_t)first];
+            if (res.best > best) {
+                best = res.best;
+                best_files = res.files;
+                best_set = res.set;
+            }
         }
     }
     if (byz_workers_out)

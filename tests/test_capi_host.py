@@ -195,3 +195,20 @@ def test_streamed_program_is_the_same_network_in_a_valid_order(f):
         for _ in range(200):
             vals = rng.integers(0, 60, size=f).tolist()
             assert gen_selnet.run_streamed(prog, vals, depth) == sorted(vals)[(f - 1) // 2]
+
+
+def test_worst_case_edges_and_threaded_search():
+    asg = _build("mols", 5, 3)
+    assert B.byz_worst_case(asg, 0) == ((), 0, 0)
+    S, c, mask = B.byz_worst_case(asg, asg.K)
+    assert S == tuple(range(asg.K)) and c == asg.f and mask == (1 << asg.f) - 1
+    # a search large enough for the multi-threaded path must return what the one-thread
+    # oracle enumeration returns, including the first maximiser: C(25,9) = 2.0e6 (1 thread)
+    # and C(25,12) = 5.2e6 are below the threshold, C(35,8) = 2.35e7 is above
+    big = _build("mols", 7, 5)
+    S, c, mask = B.byz_worst_case(big, 8)
+    c_o, S_o = C.worst_case(_H(big), 8)
+    assert (c, S) == (c_o, S_o) and c == 8
+    # beyond the last row the paper could compute (q = 13): still below Claim 1's bound
+    S14, c14, _ = B.byz_worst_case(big, 14)
+    assert 20 <= c14 <= B.byz_gamma_bound(big, 14) and len(O.distorted_files(_H(big), S14)) == c14
