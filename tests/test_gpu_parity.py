@@ -239,3 +239,77 @@ def test_generator_same_bytes_on_cpu_and_gpu():
         Gg = synth.honest_gradients(9, 5000, 77, step=3, device=DEV, file_scales=fs)
         assert np.array_equal(W.bits(Gc), W.bits(Gg))
     assert np.array_equal(W.bits(synth.alie_vector(Gc, 1.5)), W.bits(synth.alie_vector(Gg, 1.5)))
+
+
+def test_largest_shapes_f63_r7():
+    # Ramanujan s=7, m=9 (Case 2): K=49 workers, f=63 files (largest odd f), r=7 (largest r),
+    # l=9: two-step path, 21 pair bits per file, rank-counting median
+    w = W.make(RAM, 7, 9, 6, 1537, MIXED, seed=12, device=DEV)
+    assert (w.K, w.f, w.l, w.r) == (49, 63, 9, 7)
+    _check_all(w.X, w.file_rows, w.d, w.f, w.r, expect_exact=True)
+    # every copy of one file different (seven singletons), 3-3-1 and 2-2-2-1 splits on others
+    X = w.X.clone()
+    for j, labels in enumerate([[0, 1, 2, 3, 4, 5, 6], [1, 0, 1, 0, 1, 0, 2], [0, 0, 1, 1, 2, 2, 3],
+                                [3, 2, 2, 1, 1, 1, 0]]):
+        for k, lab in enumerate(labels):
+            X[int(w.file_rows[j, k])] = w.G[j] * float(1 + lab)
+    out_o, wrep_o, _ = _check_all(X, w.file_rows, w.d, w.f, w.r, expect_exact=True)
+    assert wrep_o[:4].tolist() == [0, 0, 0, 3]
+
+
+def test_hip_graph_capture_and_replay():
+    # the entry points enqueue kernels only (no memset, no allocation, no sync), so a caller
+    # can capture them; every replay must give the eager result, with eager work in between
+    w = W.make(MOLS, 5, 3, 4, 200_003, ALIE, seed=13, ld=200_064, device=DEV)
+    rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+    out_e, wrep_e, _ = B.byz_aggregate(w.X, w.d, rows_dev, w.f, w.r)
+    torch.cuda.synchronize()
+    Xs = w.X.clone()  # static input buffer of the graph
+    out = torch.empty(w.d, dtype=torch.float32, device=DEV)
+    wrep = torch.empty(w.f, dtype=torch.int32, device=DEV)
+    ws = torch.empty(B.byz_aggregate_workspace_bytes(w.f, w.r), dtype=torch.uint8, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        B.byz_aggregate(Xs, w.d, rows_dev, w.f, w.r, out=out, winner_replica=wrep, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.byz_aggregate(Xs, w.d, rows_dev, w.f, w.r, out=out, winner_replica=wrep, workspace=ws)
+    # second input: another Byzantine payload, a copy that defeats the probe (exact path)
+    X2 = w.X.clone()
+    X2[int(w.file_rows[3, 0]), 12345] = 7.0
+    out_e2, wrep_e2, ws_e2 = B.byz_aggregate(X2, w.d, rows_dev, w.f, w.r)
+    torch.cuda.synchronize()
+    for rep, (src, want_out, want_rep) in enumerate([(w.X, out_e, wrep_e), (X2, out_e2, wrep_e2),
+                                                     (w.X, out_e, wrep_e), (X2, out_e2, wrep_e2)]):
+        Xs.copy_(src)
+        out.zero_()
+        wrep.fill_(-1)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int32), want_out.view(torch.int32)), rep
+        assert torch.equal(wrep, want_rep), rep
+        # eager work between replays
+        chk, _, _ = B.byz_aggregate(src, w.d, rows_dev, w.f, w.r)
+        torch.cuda.synchronize()
+        assert torch.equal(chk.view(torch.int32), want_out.view(torch.int32))
+    assert wrep_e2[3].item() == 1 and B.byz_aggregate_took_exact_path(ws_e2)
+
+
+def test_measurement_aids():
+    src = torch.randn(1 << 20, device=DEV)
+    dst = torch.zeros_like(src)
+    B.byz_calibration_copy(src, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    w = W.make(MOLS, 5, 3, 3, 50_000, REVERSED, seed=14, device=DEV)
+    rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+    B.byz_profile_enable(2)
+    for _ in range(3):
+        B.byz_aggregate(w.X, w.d, rows_dev, w.f, w.r)
+    ms = B.byz_profile_collect(8)
+    B.byz_profile_enable(0)
+    assert len(ms) == 2 and all(0 < t < 50 for t in ms)
+    assert B.byz_profile_collect(8) == []
