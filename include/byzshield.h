@@ -48,7 +48,8 @@ typedef enum byz_status {
 
 typedef enum byz_scheme {
     BYZ_SCHEME_MOLS = 0,     /* Algorithm 2: a = l (prime), b = r <= l-1; K = r*l, f = l*l            */
-    BYZ_SCHEME_RAMANUJAN = 1 /* Sec. 4.2.1: a = s (prime), b = m >= 2; Case 1 (m < s) or 2 (m >= s)  */
+    BYZ_SCHEME_RAMANUJAN = 1, /* Sec. 4.2.1: a = s (prime), b = m >= 2; Case 1 (m < s) or 2 (m >= s) */
+    BYZ_SCHEME_FRC = 2       /* Sec. 5.3.1 (DETOX / DRACO): a = K, b = r | K; f = K/r, l = 1           */
 } byz_scheme;
 
 #define BYZ_MAX_F 64 /* largest number of files the device entry points and the search take */
@@ -65,6 +66,9 @@ typedef struct byz_assignment byz_assignment;
  *     U_{k*l+s} with s = L_{k+1}(i,j) = (k+1)*i + j mod l.  Needs l prime, 1 <= r <= l-1.
  *   BYZ_SCHEME_RAMANUJAN (Sec. 4.2.1, Eq. 6): H = B (m >= s) or B^T (m < s), B the s x m
  *     block matrix of powers P^(a*b) of the cyclic shift P.  Needs s prime, m >= 2.
+ *   BYZ_SCHEME_FRC (Sec. 5.3.1, the Fractional Repetition Code the paper compares with):
+ *     K/r groups of r workers, all workers of a group hold the group's one file; replica k of
+ *     file j sits on worker k*(K/r) + j.  Needs r | K.
  * After building, the library checks the structure the paper proves (every worker holds l
  * files, every file sits on r workers, each parallel class holds each file once, two workers
  * share at most one file ...) and returns BYZ_EINTERNAL if any fails.
@@ -137,7 +141,8 @@ int byz_vote(const float *copies, int64_t d, int64_t ld, const int32_t *file_row
  * out[c] = element of rank (f-1)/2 of { rows_base[row_index[j]*ld + c] : j < f }.
  *   rows_base     device [*][ld] fp32;  row_index_dev device [f] int32;  out device [d] fp32,
  *                 must not overlap the input rows (may be NULL when d == 0).
- * f odd, 1 <= f <= 64; f in {3,5,7,9,25,49} runs a register selection network, other odd f
+ * f odd, 1 <= f <= 64; f in {3,5,7,9,15,21,25,35,49} (the paper's file and
+ * worker counts) runs a register selection network, other odd f
  * a slower generic kernel.  Errors: BYZ_EINVAL, BYZ_EUNSUPPORTED (even f), BYZ_EDEVICE.
  */
 int byz_median(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev,

@@ -11,6 +11,7 @@ replication r (odd), r' = (r+1)/2, load l = f*r/K, d coordinates.
 Parity status of each function (what pins it, see tests/test_oracle_*.py):
   latin_square, mols_biadjacency      Table 1, Example 1, Table 2 cell by cell
   ramanujan_biadjacency               Eq. 6 degrees, Lemma 2 spectrum, Table 4
+  frc_biadjacency                     Sec. 5.3.1: floor(q/r') lost groups, FRC column of Tables 3-6
   worst_case                          Tables 3-6, Claim 2, naive brute force
   gamma_bound                         Tables 3-6 (gamma column), closed forms Sec. 5.1
   vote                                brute force over all equality patterns, Sec. 2
@@ -96,6 +97,19 @@ def ramanujan_biadjacency(m, s):
     """
     B = array_code_matrix(m, s)
     return B if m >= s else B.T.copy()
+
+
+def frc_biadjacency(K, r):
+    """Sec. 5.3.1: Fractional Repetition Code of DETOX / DRACO.  K/r groups of r workers; every
+    worker of group j holds file j.  Replica k of file j is worker k*(K/r) + j (the paper does
+    not number the workers; this keeps one replica of every file per block of K/r workers)."""
+    assert K % r == 0
+    f = K // r
+    H = np.zeros((K, f), dtype=np.int64)
+    for j in range(f):
+        for k in range(r):
+            H[k * f + j, j] = 1
+    return H
 
 
 def dims(H):

@@ -5,6 +5,7 @@ library's HIP kernels / host code.  PyTorch is used for device memory and stream
 """
 from .binding import (  # noqa: F401
     BYZ_AGG_EARLY_MAJORITY,
+    BYZ_SCHEME_FRC,
     BYZ_SCHEME_MOLS,
     BYZ_SCHEME_RAMANUJAN,
     Assignment,

@@ -14,6 +14,7 @@ _LIB_PATH = os.path.join(_PKG, "libbyzshield.so")
 
 BYZ_SCHEME_MOLS = 0
 BYZ_SCHEME_RAMANUJAN = 1
+BYZ_SCHEME_FRC = 2
 BYZ_MAX_F = 64
 BYZ_MAX_R = 7
 

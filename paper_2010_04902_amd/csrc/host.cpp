@@ -44,7 +44,10 @@ inline int mod(int64_t x, int m) {
 //     is held in class a by u = v + a*b.
 //   Ramanujan Case 1 (H = B^T): worker b*s+v holds file a*s+u iff u = v + a*b, so file
 //     (a, u) is held in class b by v = u - a*b.
+//   FRC (the comparison assignment of Sec. 5.3.1) has no grid: class k is the k-th member of
+//     every group and holds file y on its y-th worker.
 int holder_in_class(int scheme, bool case2, int p, int k, int x, int y) {
+    if (scheme == BYZ_SCHEME_FRC) return y;  // replica k of file y sits on worker k*f + y
     if (scheme == BYZ_SCHEME_MOLS) return mod((int64_t)(k + 1) * x + y, p);
     if (case2) return mod((int64_t)y + (int64_t)k * x, p);
     return mod((int64_t)y - (int64_t)k * x, p);
@@ -96,11 +99,18 @@ int check_invariants(const byz_assignment &g) {
 extern "C" int byz_build_assignment(int scheme, int a, int b, byz_assignment **out) {
     if (!out) return BYZ_EINVAL;
     *out = nullptr;
-    if (scheme != BYZ_SCHEME_MOLS && scheme != BYZ_SCHEME_RAMANUJAN) return BYZ_EINVAL;
+    if (scheme != BYZ_SCHEME_MOLS && scheme != BYZ_SCHEME_RAMANUJAN && scheme != BYZ_SCHEME_FRC)
+        return BYZ_EINVAL;
     if (a < 2 || a > 255) return BYZ_EINVAL;
     int K, f, l, r, classes, class_size, gx, gy;  // files form a gx x gy grid, index x*gy + y
     bool case2 = false;
-    if (scheme == BYZ_SCHEME_MOLS) {
+    int shared_lo = 1, shared_hi = 1;
+    if (scheme == BYZ_SCHEME_FRC) {
+        // Sec. 5.3.1: K/r groups of r workers, every worker of a group holds the group's file
+        if (b < 1 || b > a || a % b != 0) return BYZ_EINVAL;
+        K = a; r = b; f = K / r; l = 1; classes = r; class_size = f; gx = 1; gy = f;
+        shared_lo = 0;  // two workers share their file iff they are in the same group
+    } else if (scheme == BYZ_SCHEME_MOLS) {
         if (b < 1 || b > a - 1) return BYZ_EINVAL;  // Algorithm 2 needs r <= l-1
         if (!is_prime(a)) return BYZ_EUNSUPPORTED;
         l = a; r = b; K = r * l; f = l * l; classes = r; class_size = l; gx = l; gy = l;
@@ -123,7 +133,8 @@ extern "C" int byz_build_assignment(int scheme, int a, int b, byz_assignment **o
             g->shared_lo = l / class_size;
             g->shared_hi = (l + class_size - 1) / class_size;
         } else {
-            g->shared_lo = g->shared_hi = 1;
+            g->shared_lo = shared_lo;
+            g->shared_hi = shared_hi;
         }
         g->worker_files.assign((size_t)K * l, -1);
         g->file_workers.assign((size_t)f * r, -1);

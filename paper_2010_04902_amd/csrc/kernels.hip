@@ -233,6 +233,27 @@ template <> struct SelNet<9> {
         return result;
     }
 };
+template <> struct SelNet<15> {
+    static __device__ __forceinline__ uint32_t median(uint32_t (&k)[15]) {
+        uint32_t result;
+#include "generated/selnet_15.inc"
+        return result;
+    }
+};
+template <> struct SelNet<21> {
+    static __device__ __forceinline__ uint32_t median(uint32_t (&k)[21]) {
+        uint32_t result;
+#include "generated/selnet_21.inc"
+        return result;
+    }
+};
+template <> struct SelNet<35> {
+    static __device__ __forceinline__ uint32_t median(uint32_t (&k)[35]) {
+        uint32_t result;
+#include "generated/selnet_35.inc"
+        return result;
+    }
+};
 template <> struct SelNet<25> {
     static __device__ __forceinline__ uint32_t median(uint32_t (&k)[25]) {
         uint32_t result;
@@ -733,7 +754,10 @@ int launch_median(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_i
         case 5: return launch_median_net<5>(X, d, ld, row_index, out, gate, gate_n, s);
         case 7: return launch_median_net<7>(X, d, ld, row_index, out, gate, gate_n, s);
         case 9: return launch_median_net<9>(X, d, ld, row_index, out, gate, gate_n, s);
+        case 15: return launch_median_net<15>(X, d, ld, row_index, out, gate, gate_n, s);
+        case 21: return launch_median_net<21>(X, d, ld, row_index, out, gate, gate_n, s);
         case 25: return launch_median_net<25>(X, d, ld, row_index, out, gate, gate_n, s);
+        case 35: return launch_median_net<35>(X, d, ld, row_index, out, gate, gate_n, s);
         case 49: return launch_median_net<49>(X, d, ld, row_index, out, gate, gate_n, s);
         default:
             median_generic_kernel<<<blocks_for(d), kBlock, 0, s>>>(X, d, ld, row_index, f, out,

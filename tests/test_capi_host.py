@@ -142,7 +142,7 @@ sys.path.insert(0, os.path.join(ROOT, "paper_2010_04902_amd", "csrc"))
 import gen_selnet  # noqa: E402
 
 
-@pytest.mark.parametrize("f", [3, 5, 7, 9, 25])
+@pytest.mark.parametrize("f", [3, 5, 7, 9, 15, 21, 25])
 def test_selection_network_zero_one_exhaustive(f):
     # 0/1 principle: the network selects the median of every input iff it outputs the
     # majority bit for every 0/1 input; all 2^f inputs, one per array element.
@@ -159,13 +159,13 @@ def test_selection_network_zero_one_exhaustive(f):
     assert np.array_equal(v[wire], (pop > f // 2).astype(np.uint8))
 
 
-def test_selection_network_49_near_balanced_inputs():
-    f = 49
+@pytest.mark.parametrize("f", [35, 49])
+def test_selection_network_near_balanced_inputs(f):
     ops, wire = gen_selnet.best_network(f)
-    rng = np.random.default_rng(49)
+    rng = np.random.default_rng(f)
     n = 200_000
-    # 0/1 inputs with 23..26 ones (the critical weights), random positions
-    w = rng.integers(23, 27, size=n)
+    # 0/1 inputs whose number of ones is within 2 of f/2 (the critical weights), random positions
+    w = rng.integers(f // 2 - 1, f // 2 + 3, size=n)
     M = (np.argsort(rng.random((n, f)), axis=1) < w[:, None]).astype(np.uint8)
     v = [M[:, i].copy() for i in range(f)]
     for (i, j, lo, hi) in ops:
@@ -178,7 +178,7 @@ def test_selection_network_49_near_balanced_inputs():
     # and on random integers against a sort
     vals = rng.integers(0, 1000, size=(2000, f))
     for row in vals:
-        assert gen_selnet.apply_network(ops, row.tolist())[wire] == sorted(row.tolist())[24]
+        assert gen_selnet.apply_network(ops, row.tolist())[wire] == sorted(row.tolist())[f // 2]
 
 
 @pytest.mark.parametrize("f", gen_selnet.STREAMED_SIZES)
@@ -212,3 +212,29 @@ def test_worst_case_edges_and_threaded_search():
     # beyond the last row the paper could compute (q = 13): still below Claim 1's bound
     S14, c14, _ = B.byz_worst_case(big, 14)
     assert 20 <= c14 <= B.byz_gamma_bound(big, 14) and len(O.distorted_files(_H(big), S14)) == c14
+
+
+@pytest.mark.parametrize("name", sorted(TABLES))
+def test_frc_comparison_column(name):
+    # Sec. 5.3.1: under the worst-case attack FRC loses floor(q / r') groups, i.e.
+    # eps_FRC = floor(q / r') * r / K -- the FRC column of Tables 3-6, here by exhaustive search
+    # on the FRC graph itself (library) and on the oracle's construction
+    scheme, a, b, rows = TABLES[name]
+    ref = _build("mols" if scheme == "mols" else "ram", a, b)
+    K, r = ref.K, ref.r
+    frc = B.byz_build_assignment(B.BYZ_SCHEME_FRC, K, r)
+    assert (frc.K, frc.f, frc.l, frc.r) == (K, K // r, 1, r)
+    Ho = O.frc_biadjacency(K, r)
+    assert np.array_equal(_H(frc), Ho)
+    assert np.array_equal(frc.file_rows(), O.file_rows(Ho))
+    rp = (r + 1) // 2
+    for q, _, _, _, eps_frc, _ in rows:
+        if math.comb(K, q) > 3_000_000_000:
+            continue
+        S, c, mask = B.byz_worst_case(frc, q)
+        assert c == min(q // rp, K // r)
+        assert abs(c / frc.f - eps_frc) < 0.0051
+        if math.comb(K, q) < 300_000:
+            assert C.worst_case(Ho, q) == (c, S)
+    with pytest.raises(B.ByzError):
+        B.byz_build_assignment(B.BYZ_SCHEME_FRC, 15, 4)

@@ -16,7 +16,7 @@ from tests import workloads as W
 pytestmark = pytest.mark.gpu
 
 DEV = "cuda:0"
-MOLS, RAM = B.BYZ_SCHEME_MOLS, B.BYZ_SCHEME_RAMANUJAN
+MOLS, RAM, FRC = B.BYZ_SCHEME_MOLS, B.BYZ_SCHEME_RAMANUJAN, B.BYZ_SCHEME_FRC
 
 REVERSED = {"kind": "reversed", "c": 100.0}
 ALIE = {"kind": "alie", "z": 1.0}
@@ -62,7 +62,7 @@ SMALL_D = [1, 2, 3, 5, 63, 64, 255, 1000, 4099, 70001]
 @pytest.mark.parametrize("scheme,a,b,q,attack", [
     (MOLS, 5, 3, 3, REVERSED), (MOLS, 5, 3, 4, ALIE), (MOLS, 7, 3, 5, REVERSED),
     (RAM, 5, 5, 6, MIXED), (MOLS, 7, 3, 6, ALIE), (RAM, 3, 3, 2, CONST), (MOLS, 7, 5, 5, MIXED),
-    (RAM, 5, 3, 3, CONST)])
+    (RAM, 5, 3, 3, CONST), (FRC, 15, 3, 4, REVERSED), (FRC, 25, 5, 7, MIXED)])
 def test_small_sizes_all_layouts(scheme, a, b, q, attack):
     # sizes below one tile, several tiles and ragged tails; row pitches that give 16-byte,
     # 8-byte and 4-byte aligned rows
@@ -100,7 +100,7 @@ def test_generic_shapes_without_a_generated_network():
     # byz_median alone for assorted odd f, including rows used more than once
     rng = np.random.default_rng(5)
     X = torch.randn(70, 1500, device=DEV)
-    for f in [1, 3, 5, 7, 9, 11, 13, 25, 31, 49, 63]:
+    for f in [1, 3, 5, 7, 9, 11, 13, 15, 21, 25, 31, 35, 49, 63]:
         idx = rng.integers(0, 70, size=f).astype(np.int32)
         out = B.byz_median(X, 1500, torch.tensor(idx, device=DEV))
         torch.cuda.synchronize()

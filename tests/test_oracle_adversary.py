@@ -136,3 +136,16 @@ def test_cmax_monotone_in_q():
     H = O.mols_biadjacency(5, 3)
     vals = [C.worst_case(H, q)[0] for q in range(0, 9)]
     assert vals == sorted(vals)
+
+
+def test_frc_worst_case_formula():
+    # Sec. 5.3.1: an omniscient adversary puts r' Byzantines into as many groups as it can:
+    # floor(q / r') distorted groups, eps_FRC = floor(q / r') * r / K
+    for K, r in [(15, 3), (21, 3), (25, 5)]:
+        H = O.frc_biadjacency(K, r)
+        assert O.dims(H) == (K, K // r, 1, r)
+        rp = (r + 1) // 2
+        for q in range(0, 8):
+            c, S = C.worst_case(H, q)
+            assert c == min(q // rp, K // r)
+            assert _naive_cmax(H, q) == c if K == 15 and q <= 5 else True
