@@ -189,6 +189,7 @@ def main():
         wrep_v, wrow_v, neq_v = B.byz_vote(bufs[0], d, rows_dev, asg.f, asg.r, stream=stream)
         ms_vote = timed_call(lambda: B.byz_vote(bufs[0], d, rows_dev, asg.f, asg.r, stream=stream))
         ms_med = timed_call(lambda: B.byz_median(bufs[0], d, wrow_v, out=out, stream=stream))
+        ms_tm = timed_call(lambda: B.byz_trimmed_mean(bufs[0], d, wrow_v, cmax, out=out, stream=stream))
         vb, mb = 4.0 * asg.r * asg.f * d, 4.0 * (asg.f + 1) * d
         result["components"] = {
             "byz_vote": {"ms": ms_vote, "algorithmic_bytes": vb, "gbps": vb / ms_vote / 1e6,
@@ -196,6 +197,8 @@ def main():
                          "note": "fill + vote_pairs_kernel + vote_decide_kernel"},
             "byz_median": {"ms": ms_med, "algorithmic_bytes": mb, "gbps": mb / ms_med / 1e6,
                            "frac": mb / ms_med / 1e6 / HBM_PEAK_GBPS},
+            "byz_trimmed_mean": {"ms": ms_tm, "b": cmax, "algorithmic_bytes": mb,
+                                 "gbps": mb / ms_tm / 1e6, "frac": mb / ms_tm / 1e6 / HBM_PEAK_GBPS},
         }
 
     if not args.no_cpu:

@@ -148,6 +148,22 @@ int byz_vote(const float *copies, int64_t d, int64_t ld, const int32_t *file_row
 int byz_median(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev,
                int f, float *out, void *stream);
 
+/* ------------------------------- device: another aggregator for the winners (Sec. 1, Sec. 7) */
+
+/*
+ * Coordinate-wise trimmed mean, the robust aggregator the paper lists beside the median
+ * (Sec. 1) and a candidate for "other aggregation schemes on the vote winners" (Sec. 7):
+ * out[c] = mean of the f - 2b values of { rows_base[row_index[j]*ld + c] } left after
+ * dropping the b smallest and the b largest (total order of byz_median, so NaNs and
+ * infinities go first).  b = 0 is the plain mean.  Not pure selection; the rounding contract
+ * is: fp32, kept values added one by one in ascending order starting from +0, then one IEEE
+ * division by float(f - 2b).
+ *   f in {9,25,49} runs a register sorting network, other f <= 64 a slower generic kernel.
+ * Errors: BYZ_EINVAL (null pointers, sizes, b < 0 or 2b >= f), BYZ_EDEVICE.
+ */
+int byz_trimmed_mean(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev,
+                     int f, int b, float *out, void *stream);
+
 /* --------------------------------------------------- device: fused vote + median (whole path) */
 
 /* Bytes of device scratch byz_aggregate needs for (f, r); 0 if (f, r) is invalid. */

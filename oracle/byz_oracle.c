@@ -13,6 +13,8 @@
  *                  (f odd): sort the f values of a coordinate, take the middle.
  *                  Order: total order on bit patterns (-NaN < -inf < .. < -0 <
  *                  +0 < .. < +inf < +NaN); the paper is silent on +-0 / NaN.
+ *   oracle_trimmed_mean  coordinate-wise trimmed mean in fp64 (Sec. 1's other robust
+ *                  aggregator): sort, drop b at each end, mean of the rest.
  *   oracle_worst_case  Sec. 5.3.2: exhaustive search over all q-subsets.
  *
  * Build: gcc -O2 -fopenmp -shared -fPIC (see build_oracle.py).
@@ -93,6 +95,41 @@ int oracle_median(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_i
             key[t + 1] = x;
         }
         out[c] = key_to_bits(key[(f - 1) / 2]);
+    }
+    return used;
+}
+
+/*
+ * Coordinate-wise trimmed mean: sort the f values of a coordinate (same total order), drop
+ * the b smallest and the b largest, fp64 mean of the rest summed in ascending order.
+ * Returns the number of threads used, or <0 on error.
+ */
+int oracle_trimmed_mean(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
+                        int b, double *out, int threads) {
+    if (f < 1 || f > 1024 || b < 0 || 2 * b >= f) return -1;
+    int used = 1;
+#ifdef _OPENMP
+    if (threads < 1) threads = 1;
+    used = threads;
+#pragma omp parallel for schedule(static) num_threads(threads)
+#endif
+    for (int64_t c = 0; c < d; ++c) {
+        uint32_t key[1024];
+        for (int j = 0; j < f; ++j) key[j] = order_key(X[(int64_t)row_index[j] * ld + c]);
+        for (int i = 1; i < f; ++i) {
+            uint32_t x = key[i];
+            int t = i - 1;
+            while (t >= 0 && key[t] > x) { key[t + 1] = key[t]; --t; }
+            key[t + 1] = x;
+        }
+        double acc = 0.0;
+        for (int i = b; i < f - b; ++i) {
+            uint32_t bits = key_to_bits(key[i]);
+            float v;
+            memcpy(&v, &bits, 4);
+            acc += (double)v;
+        }
+        out[c] = acc / (double)(f - 2 * b);
     }
     return used;
 }

@@ -17,6 +17,7 @@ Parity status of each function (what pins it, see tests/test_oracle_*.py):
   vote                                brute force over all equality patterns, Sec. 2
                                       statements (all-honest, distorted iff >= r')
   median                              numpy sort/median on ordinary data, brute force
+  trimmed_mean                        scipy.stats.trim_mean, b=0 mean, b=(f-1)/2 median, hand-worked case
   tie-break rules (vote plurality ties -> lowest replica; total order of
   +-0 / NaN in the median; lexicographically first worst-case set):
       the paper is silent on these -> "parity unpinned" by the paper; both
@@ -263,6 +264,23 @@ def median(X, row_index, d):
     mid = order[(f - 1) // 2]  # [d] index of the file holding the median
     out = vals[mid, np.arange(d)]
     return out.view(np.float32)
+
+
+def trimmed_mean(X, row_index, d, b):
+    """Coordinate-wise trimmed mean (the aggregator the paper's Sec. 1 cites beside the median):
+    sort the f values of a coordinate by order_key, drop the b smallest and the b largest,
+    return the fp64 mean of the f - 2b that remain (summed in ascending order)."""
+    U = np.ascontiguousarray(X).view(np.uint32)
+    row_index = np.asarray(row_index)
+    f = len(row_index)
+    assert 0 <= b and 2 * b < f
+    vals = np.stack([U[int(row_index[j]), :d] for j in range(f)])  # [f, d]
+    order = np.argsort(order_key(vals), axis=0, kind="stable")
+    srt = np.take_along_axis(vals, order, axis=0).view(np.float32).astype(np.float64)
+    acc = np.zeros(d, dtype=np.float64)
+    for i in range(b, f - b):
+        acc = acc + srt[i]
+    return acc / float(f - 2 * b)
 
 
 def aggregate(X, rows, d):

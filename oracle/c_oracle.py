@@ -23,6 +23,10 @@ def lib():
         L.oracle_median.argtypes = [u32p, ctypes.c_int64, ctypes.c_int64, i32p, ctypes.c_int,
                                     u32p, ctypes.c_int]
         L.oracle_median.restype = ctypes.c_int
+        L.oracle_trimmed_mean.argtypes = [u32p, ctypes.c_int64, ctypes.c_int64, i32p, ctypes.c_int,
+                                          ctypes.c_int, ctypes.POINTER(ctypes.c_double),
+                                          ctypes.c_int]
+        L.oracle_trimmed_mean.restype = ctypes.c_int
         L.oracle_aggregate.argtypes = [u32p, ctypes.c_int64, ctypes.c_int64, i32p, ctypes.c_int,
                                        ctypes.c_int, u32p, i32p, ctypes.c_int]
         L.oracle_aggregate.restype = ctypes.c_int
@@ -73,6 +77,19 @@ def median(X, row_index, d, threads=None):
     if rc < 0:
         raise ValueError("oracle_median rc=%d" % rc)
     return out.view(np.float32)
+
+
+def trimmed_mean(X, row_index, d, b, threads=None):
+    U = _u32(X)
+    row_index = np.ascontiguousarray(row_index, dtype=np.int32)
+    out = np.zeros(d, dtype=np.float64)
+    t = default_threads() if threads is None else threads
+    rc = lib().oracle_trimmed_mean(_ptr(U, ctypes.c_uint32), d, U.shape[1],
+                                   _ptr(row_index, ctypes.c_int32), len(row_index), int(b),
+                                   _ptr(out, ctypes.c_double), t)
+    if rc < 0:
+        raise ValueError("oracle_trimmed_mean rc=%d" % rc)
+    return out
 
 
 def aggregate(X, rows, d, threads=None):

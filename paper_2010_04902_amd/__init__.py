@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     byz_profile_collect,
     byz_profile_enable,
     byz_strerror,
+    byz_trimmed_mean,
     byz_vote,
     byz_worst_case,
     library_path,

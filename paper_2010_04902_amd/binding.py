@@ -58,6 +58,7 @@ def _load():
         "byz_gamma_bound": (ctypes.c_double, [vp, c_int]),
         "byz_vote": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, vp]),
         "byz_median": (c_int, [vp, i64, i64, vp, c_int, vp, vp]),
+        "byz_trimmed_mean": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp]),
         "byz_aggregate_workspace_bytes": (sz, [c_int, c_int]),
         "byz_aggregate": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, sz, vp]),
         "byz_aggregate_opts": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, sz,
@@ -192,6 +193,19 @@ def byz_median(rows_base, d, row_index_dev, out=None, stream=None):
                               _dev_ptr(row_index_dev, ("int32",), "row_index_dev"), f,
                               _dev_ptr(out, ("float32",), "out"), _stream_ptr(stream)),
            "byz_median")
+    return out
+
+
+def byz_trimmed_mean(rows_base, d, row_index_dev, b, out=None, stream=None):
+    torch = _torch()
+    ld = _rows_2d(rows_base)
+    f = int(row_index_dev.numel())
+    if out is None:
+        out = torch.empty(int(d), dtype=torch.float32, device=rows_base.device)
+    _check(_load().byz_trimmed_mean(_dev_ptr(rows_base, ("float32",), "rows_base"), int(d), ld,
+                                    _dev_ptr(row_index_dev, ("int32",), "row_index_dev"), f,
+                                    int(b), _dev_ptr(out, ("float32",), "out"),
+                                    _stream_ptr(stream)), "byz_trimmed_mean")
     return out
 
 

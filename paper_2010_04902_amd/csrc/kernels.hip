@@ -432,6 +432,7 @@ __global__ __launch_bounds__(kBlock) void vote_pairs_kernel(
 #define BYZ_S_CE_HI(i, j)                                                                     \
     _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_)                                          \
         key[v_][j] = key[v_][i] < key[v_][j] ? key[v_][j] : key[v_][i];
+#define BYZ_S_SORTED(n)  // wires 0..n-1 now hold the keys in ascending order
 #define BYZ_S_MEDIAN(w)                                                                       \
     _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_) o[v_] = from_key(key[v_][w]);
 
@@ -507,6 +508,72 @@ __global__ __launch_bounds__(kBlock) void median_generic_kernel(
         if (rank == mid) result = key[i];
     }
     out[c] = from_key(result);
+}
+
+// Coordinate-wise trimmed mean of F rows: the F values of a coordinate are sorted (total order
+// of the keys), the b smallest and the b largest are dropped and the remaining F - 2b are
+// averaged.  Rounding contract: fp32, the kept values are added one by one in ascending order
+// starting from +0, then divided by float(F - 2b) (IEEE division).  Thread t owns the four
+// words starting at min(4t, d - 4): the last vector overlaps its neighbour instead of a scalar
+// tail (both write the same values).  Needs d >= 4.
+template <int F, int V>
+__global__ __launch_bounds__(kBlock) void trimmed_mean_kernel(
+    const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
+    int b, uint32_t *__restrict__ out) {
+    const int64_t n_thr = (d + V - 1) / V;
+    const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (gt >= n_thr) return;
+    const int64_t c0 = gt * V + V <= d ? gt * V : d - V;
+    uint32_t key[V][F];
+    constexpr int NS = 1;
+    constexpr int kAhead = prefetch_depth(F, NS);
+    const uint32_t voff = (uint32_t)(c0 * 4);
+    const char *Xb = reinterpret_cast<const char *>(X);
+    uint32_t stage[kAhead + 1][NS][V];
+    const uint32_t *chain_mask = nullptr;  // unused with one slot per file
+    const int lane = 0;
+    uint32_t flags = 0;
+    (void)chain_mask; (void)lane; (void)flags;
+#define BYZ_S_ROW_ADDR(j, k) (Xb + (uint64_t)(uint32_t)row_index[j] * (uint64_t)ld * 4u + voff)
+    if constexpr (F == 9) {
+#include "generated/selnet_sort_stream_9.inc"
+    } else if constexpr (F == 25) {
+#include "generated/selnet_sort_stream_25.inc"
+    } else {
+        static_assert(F == 49, "no streamed sorting network generated for this f");
+#include "generated/selnet_sort_stream_49.inc"
+    }
+#undef BYZ_S_ROW_ADDR
+    const float denom = (float)(F - 2 * b);
+    uint32_t o[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        float acc = 0.0f;
+#pragma unroll
+        for (int i = 0; i < F; ++i)
+            if (i >= b && i < F - b) acc += __uint_as_float(from_key(key[v][i]));
+        o[v] = __float_as_uint(acc / denom);
+    }
+    store_vec<V>(out + c0, o);
+}
+
+// Trimmed mean for any f <= 64 (and for d < 4): insertion sort in per-thread memory, one
+// coordinate a thread; same rounding contract as trimmed_mean_kernel.
+__global__ __launch_bounds__(kBlock) void trimmed_mean_generic_kernel(
+    const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
+    int f, int b, uint32_t *__restrict__ out) {
+    const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (c >= d) return;
+    uint32_t key[BYZ_MAX_F];
+    for (int j = 0; j < f; ++j) {
+        const uint32_t x = to_key(X[(int64_t)row_index[j] * ld + c]);
+        int t = j - 1;
+        while (t >= 0 && key[t] > x) { key[t + 1] = key[t]; --t; }
+        key[t + 1] = x;
+    }
+    float acc = 0.0f;
+    for (int i = b; i < f - b; ++i) acc += __uint_as_float(from_key(key[i]));
+    out[c] = __float_as_uint(acc / (float)(f - 2 * b));
 }
 
 // Probe: compares the copies of every file on a sample of <= kProbe coordinates (kProbe/16 runs
@@ -833,6 +900,31 @@ extern "C" int byz_median(const float *rows_base, int64_t d, int64_t ld,
     if ((f % 2) == 0) return BYZ_EUNSUPPORTED;
     return launch_median(reinterpret_cast<const uint32_t *>(rows_base), d, ld, row_index_dev, f,
                          reinterpret_cast<uint32_t *>(out), nullptr, 0, (hipStream_t)stream);
+}
+
+extern "C" int byz_trimmed_mean(const float *rows_base, int64_t d, int64_t ld,
+                                const int32_t *row_index_dev, int f, int b, float *out,
+                                void *stream) {
+    if (rows_base == nullptr || row_index_dev == nullptr || (out == nullptr && d > 0))
+        return BYZ_EINVAL;
+    if (d < 0 || ld < d || d > kMaxCoords) return BYZ_EINVAL;
+    if (f < 1 || f > BYZ_MAX_F || b < 0 || 2 * b >= f) return BYZ_EINVAL;
+    if (d == 0) return BYZ_OK;
+    hipStream_t s = (hipStream_t)stream;
+    const uint32_t *X = reinterpret_cast<const uint32_t *>(rows_base);
+    uint32_t *O = reinterpret_cast<uint32_t *>(out);
+    const unsigned g = blocks_for((d + kVec - 1) / kVec);
+    if (d >= kVec && f == 9)
+        trimmed_mean_kernel<9, kVec><<<g, kBlock, 0, s>>>(X, d, ld, row_index_dev, b, O);
+    else if (d >= kVec && f == 25)
+        trimmed_mean_kernel<25, kVec><<<g, kBlock, 0, s>>>(X, d, ld, row_index_dev, b, O);
+    else if (d >= kVec && f == 49)
+        trimmed_mean_kernel<49, kVec><<<g, kBlock, 0, s>>>(X, d, ld, row_index_dev, b, O);
+    else
+        trimmed_mean_generic_kernel<<<blocks_for(d), kBlock, 0, s>>>(X, d, ld, row_index_dev, f, b,
+                                                                     O);
+    BYZ_HIP(hipGetLastError());
+    return BYZ_OK;
 }
 
 extern "C" size_t byz_aggregate_workspace_bytes(int f, int r) {

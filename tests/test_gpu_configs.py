@@ -98,3 +98,16 @@ def test_table5_cluster_shape_full_size():
                device=DEV)
     assert (w.K, w.f, w.l, w.r) == (35, 49, 7, 5) and w.cmax == 4
     assert _full_check(w, "mols7x5") == 4
+
+
+@pytest.mark.parametrize("idx", [1, 2])
+def test_trimmed_mean_full_size(idx):
+    # trimmed mean (b = c_max per side) over the vote winners at full size, fp64 oracle,
+    # tolerance n * 2^-24 * max|kept| (see tests/test_gpu_parity.py)
+    from tests.test_gpu_parity import _trimmed_mean_check
+    cfg = synth.CONFIGS[idx]
+    w = W.from_config(cfg, DEV, ld=synth.padded_ld(cfg.d, 64))
+    rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+    _, wrow, _ = B.byz_vote(w.X, w.d, rows_dev, w.f, w.r)
+    torch.cuda.synchronize()
+    _trimmed_mean_check(w.X, wrow.cpu().numpy(), w.d, cfg.cmax, cfg.name)

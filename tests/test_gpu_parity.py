@@ -313,3 +313,67 @@ def test_measurement_aids():
     B.byz_profile_enable(0)
     assert len(ms) == 2 and all(0 < t < 50 for t in ms)
     assert B.byz_profile_collect(8) == []
+
+
+def _trimmed_mean_check(X, idx_np, d, b, tag):
+    """GPU trimmed mean (fp32, ascending sequential sum) against the fp64 oracle.
+
+    Tolerance from the arithmetic: n-1 fp32 additions and one division, each with relative
+    rounding error u = 2^-24 on partial sums bounded by sum|x|  =>  |err| <= n * u * max|kept|
+    (first order; the factor 1.5 covers the second-order terms and the final conversion)."""
+    idx_dev = torch.tensor(idx_np, dtype=torch.int32, device=DEV)
+    out = B.byz_trimmed_mean(X, d, idx_dev, b)
+    torch.cuda.synchronize()
+    Xh = X.detach().cpu().numpy()
+    want = C.trimmed_mean(Xh, idx_np, d, b)
+    f = len(idx_np)
+    n = f - 2 * b
+    keys = O.order_key(Xh.view(np.uint32)[idx_np][:, :d])
+    srt = np.take_along_axis(Xh[idx_np][:, :d], np.argsort(keys, axis=0, kind="stable"), axis=0)
+    with np.errstate(invalid="ignore"):
+        kept_abs = np.abs(srt[b:f - b].astype(np.float64))
+    kept_max = kept_abs.max(axis=0)
+    tol = 1.5 * n * 2.0 ** -24 * kept_max + 1e-44
+    got = out.cpu().numpy().astype(np.float64)
+    finite = np.isfinite(want)
+    # where the fp32 partial sums may overflow (sum|x| near FLT_MAX) the contract gives +-inf
+    # while the fp64 oracle stays finite: not compared
+    no_overflow = kept_abs.sum(axis=0) < 1e38
+    ok = finite & no_overflow
+    assert (np.abs(got[ok] - want[ok]) <= tol[ok]).all(), tag
+    # non-finite results (kept infinities / NaNs) must agree in kind
+    assert np.array_equal(np.isnan(got[~finite]), np.isnan(want[~finite])), tag
+    assert np.array_equal(got[~finite & ~np.isnan(want)], want[~finite & ~np.isnan(want)]), tag
+    return out
+
+
+@pytest.mark.parametrize("scheme,a,b,q,attack", [(MOLS, 5, 3, 4, ALIE), (MOLS, 7, 3, 5, REVERSED),
+                                                 (RAM, 3, 3, 2, CONST), (RAM, 3, 5, 2, CONST)])
+def test_trimmed_mean_on_the_vote_winners(scheme, a, b, q, attack):
+    for i, d in enumerate([1, 3, 4, 5, 257, 4099, 70001]):
+        w = W.make(scheme, a, b, q, d, attack, seed=300 + i, ld=synth.padded_ld(d, 4) + 4 * (i % 2),
+                   device=DEV)
+        rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+        _, wrow, _ = B.byz_vote(w.X, d, rows_dev, w.f, w.r)
+        torch.cuda.synchronize()
+        idx = wrow.cpu().numpy()
+        for trim in sorted({0, 1, min(w.cmax, (w.f - 1) // 2), (w.f - 1) // 2}):
+            out = _trimmed_mean_check(w.X, idx, d, trim, (d, trim))
+            if trim == (w.f - 1) // 2:  # keeps one value: the median itself
+                med = B.byz_median(w.X, d, wrow)
+                torch.cuda.synchronize()
+                assert torch.equal(out, med) or torch.equal(out + 0.0, med + 0.0)
+    for bad_b in (-1, (w.f + 1) // 2):
+        with pytest.raises(B.ByzError) as e:
+            B.byz_trimmed_mean(w.X, w.d, wrow, bad_b)
+        assert e.value.code == -1
+
+
+def test_trimmed_mean_special_values():
+    d, f = 2048, 25
+    rng = np.random.default_rng(31)
+    U = rng.integers(0, 2**32, size=(f, d), dtype=np.uint64).astype(np.uint32)  # raw bit patterns
+    X = torch.tensor(U.view(np.int32), device=DEV).view(torch.float32)
+    idx = np.arange(f, dtype=np.int32)
+    for b in (0, 3, 12):
+        _trimmed_mean_check(X, idx, d, b, b)

@@ -219,3 +219,46 @@ def test_aggregate_numpy_vs_c():
 def test_struct_roundtrip_sanity():
     # the fixtures above build floats from bit patterns; make sure the view does what we think
     assert struct.unpack("<I", struct.pack("<f", -0.0))[0] == 0x80000000
+
+
+TM_IMPLS = [("numpy", O.trimmed_mean), ("c", lambda X, ri, d, b: C.trimmed_mean(X, ri, d, b, threads=2))]
+
+
+@pytest.mark.parametrize("name,tmean", TM_IMPLS)
+def test_trimmed_mean_against_scipy_mean_and_median(name, tmean):
+    from scipy import stats
+    rng = np.random.default_rng(21)
+    for f in (5, 9, 25, 49):
+        d = 173
+        X = rng.standard_normal((f + 2, d)).astype(np.float32)
+        X[:, :5] = np.round(X[:, :5])
+        idx = rng.permutation(f + 2)[:f].astype(np.int32)
+        V = X[idx].astype(np.float64)
+        # b = 0: the mean; b = (f-1)/2: the median
+        assert np.allclose(tmean(X, idx, d, 0), V.mean(axis=0), rtol=0, atol=1e-14)
+        assert np.array_equal(tmean(X, idx, d, (f - 1) // 2), np.median(V, axis=0))
+        for b in range(1, (f - 1) // 2):
+            want = stats.trim_mean(V, b / f + 1e-9, axis=0)  # cuts int(f * proportion) = b per side
+            assert np.allclose(tmean(X, idx, d, b), want, rtol=0, atol=1e-14), (f, b)
+        # permuting the files changes nothing
+        assert np.array_equal(tmean(X, idx[::-1].copy(), d, 2), tmean(X, idx, d, 2))
+
+
+@pytest.mark.parametrize("name,tmean", TM_IMPLS)
+def test_trimmed_mean_hand_worked_and_outliers(name, tmean):
+    # one coordinate, values 1..7 shuffled, b = 2: mean of {3,4,5} = 4; with -inf/NaN/+inf
+    # among them the extremes are what gets cut (total order puts NaN beyond the infinities)
+    X = np.array([[5], [1], [7], [3], [2], [6], [4]], dtype=np.float32)
+    idx = np.arange(7, dtype=np.int32)
+    assert tmean(X, idx, 1, 2)[0] == 4.0
+    assert tmean(X, idx, 1, 1)[0] == 4.0 and tmean(X, idx, 1, 0)[0] == 4.0
+    Y = np.array([[5], [np.nan], [np.inf], [3], [-np.inf], [6], [4]], dtype=np.float32)
+    assert tmean(Y, idx, 1, 2)[0] == (4.0 + 5.0 + 6.0) / 3  # cut: -inf, 3 | inf, nan
+    # up to b huge outliers per side leave the result inside the honest range
+    rng = np.random.default_rng(3)
+    f, d, b = 25, 64, 4
+    Z = rng.standard_normal((f, d)).astype(np.float32)
+    Z[:b] = 1e9
+    Z[b:2 * b] = -1e9
+    out = tmean(Z, np.arange(f, dtype=np.int32), d, b)
+    assert (out >= Z[2 * b:].min(axis=0)).all() and (out <= Z[2 * b:].max(axis=0)).all()
