@@ -190,6 +190,7 @@ def main():
         ms_vote = timed_call(lambda: B.byz_vote(bufs[0], d, rows_dev, asg.f, asg.r, stream=stream))
         ms_med = timed_call(lambda: B.byz_median(bufs[0], d, wrow_v, out=out, stream=stream))
         ms_tm = timed_call(lambda: B.byz_trimmed_mean(bufs[0], d, wrow_v, cmax, out=out, stream=stream))
+        ms_agg_tm = timed_call(lambda: step(0, B.BYZ_AGG_TRIM(cmax)))
         vb, mb = 4.0 * asg.r * asg.f * d, 4.0 * (asg.f + 1) * d
         result["components"] = {
             "byz_vote": {"ms": ms_vote, "algorithmic_bytes": vb, "gbps": vb / ms_vote / 1e6,
@@ -197,6 +198,10 @@ def main():
                          "note": "fill + vote_pairs_kernel + vote_decide_kernel"},
             "byz_median": {"ms": ms_med, "algorithmic_bytes": mb, "gbps": mb / ms_med / 1e6,
                            "frac": mb / ms_med / 1e6 / HBM_PEAK_GBPS},
+            "byz_aggregate_trimmed_mean": {"ms": ms_agg_tm, "b": cmax, "algorithmic_bytes": alg_bytes,
+                                           "gbps": alg_bytes / ms_agg_tm / 1e6,
+                                           "frac": alg_bytes / ms_agg_tm / 1e6 / HBM_PEAK_GBPS,
+                                           "note": "whole path with the trimmed mean in the single pass"},
             "byz_trimmed_mean": {"ms": ms_tm, "b": cmax, "algorithmic_bytes": mb,
                                  "gbps": mb / ms_tm / 1e6, "frac": mb / ms_tm / 1e6 / HBM_PEAK_GBPS},
         }

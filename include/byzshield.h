@@ -197,6 +197,12 @@ int byz_aggregate(const float *copies, int64_t d, int64_t ld, const int32_t *fil
  * Errors: as byz_aggregate; BYZ_EINVAL for unknown flag bits.
  */
 #define BYZ_AGG_EARLY_MAJORITY 1u
+/*   BYZ_AGG_TRIM(b)  aggregate the winners by the trimmed mean of byz_trimmed_mean (b values
+ *     dropped at each end, 0 <= 2b < f, b <= 255) instead of the median, in the same single
+ *     pass; result = byz_vote followed by byz_trimmed_mean on winner_row, to its rounding
+ *     contract.  May be combined with BYZ_AGG_EARLY_MAJORITY. */
+#define BYZ_AGG_TRIMMED_MEAN 2u
+#define BYZ_AGG_TRIM(b) (BYZ_AGG_TRIMMED_MEAN | ((unsigned)(b) << 8))
 int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld, const int32_t *file_rows_dev,
                        int f, int r, float *out, int32_t *winner_replica, void *workspace,
                        size_t workspace_bytes, unsigned flags, void *stream);

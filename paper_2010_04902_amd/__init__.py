@@ -5,6 +5,8 @@ library's HIP kernels / host code.  PyTorch is used for device memory and stream
 """
 from .binding import (  # noqa: F401
     BYZ_AGG_EARLY_MAJORITY,
+    BYZ_AGG_TRIM,
+    BYZ_AGG_TRIMMED_MEAN,
     BYZ_SCHEME_FRC,
     BYZ_SCHEME_MOLS,
     BYZ_SCHEME_RAMANUJAN,

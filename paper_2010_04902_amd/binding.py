@@ -214,6 +214,11 @@ def byz_aggregate_workspace_bytes(f, r):
 
 
 BYZ_AGG_EARLY_MAJORITY = 1
+BYZ_AGG_TRIMMED_MEAN = 2
+
+
+def BYZ_AGG_TRIM(b):
+    return BYZ_AGG_TRIMMED_MEAN | (int(b) << 8)
 
 
 def byz_aggregate_opts(copies, d, file_rows_dev, f, r, flags, out=None, winner_replica=None,

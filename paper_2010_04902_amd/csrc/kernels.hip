@@ -510,6 +510,22 @@ __global__ __launch_bounds__(kBlock) void median_generic_kernel(
     out[c] = from_key(result);
 }
 
+// Rounding contract of the trimmed mean: fp32, the kept values (ranks b .. F-b-1 of the sorted
+// keys) are added one by one in ascending order starting from +0, then one IEEE division.
+template <int F, int V>
+__device__ __forceinline__ void trimmed_mean_of_sorted(const uint32_t (&key)[V][F], int b,
+                                                       uint32_t (&o)[V]) {
+    const float denom = (float)(F - 2 * b);
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        float acc = 0.0f;
+#pragma unroll
+        for (int i = 0; i < F; ++i)
+            if (i >= b && i < F - b) acc += __uint_as_float(from_key(key[v][i]));
+        o[v] = __float_as_uint(acc / denom);
+    }
+}
+
 // Coordinate-wise trimmed mean of F rows: the F values of a coordinate are sorted (total order
 // of the keys), the b smallest and the b largest are dropped and the remaining F - 2b are
 // averaged.  Rounding contract: fp32, the kept values are added one by one in ascending order
@@ -519,7 +535,8 @@ __global__ __launch_bounds__(kBlock) void median_generic_kernel(
 template <int F, int V>
 __global__ __launch_bounds__(kBlock) void trimmed_mean_kernel(
     const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
-    int b, uint32_t *__restrict__ out) {
+    int b, uint32_t *__restrict__ out, const uint32_t *__restrict__ gate, int gate_n) {
+    if (gate != nullptr && !any_word_set(gate, gate_n)) return;
     const int64_t n_thr = (d + V - 1) / V;
     const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (gt >= n_thr) return;
@@ -544,16 +561,8 @@ __global__ __launch_bounds__(kBlock) void trimmed_mean_kernel(
 #include "generated/selnet_sort_stream_49.inc"
     }
 #undef BYZ_S_ROW_ADDR
-    const float denom = (float)(F - 2 * b);
     uint32_t o[V];
-#pragma unroll
-    for (int v = 0; v < V; ++v) {
-        float acc = 0.0f;
-#pragma unroll
-        for (int i = 0; i < F; ++i)
-            if (i >= b && i < F - b) acc += __uint_as_float(from_key(key[v][i]));
-        o[v] = __float_as_uint(acc / denom);
-    }
+    trimmed_mean_of_sorted<F, V>(key, b, o);
     store_vec<V>(out + c0, o);
 }
 
@@ -561,7 +570,8 @@ __global__ __launch_bounds__(kBlock) void trimmed_mean_kernel(
 // coordinate a thread; same rounding contract as trimmed_mean_kernel.
 __global__ __launch_bounds__(kBlock) void trimmed_mean_generic_kernel(
     const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
-    int f, int b, uint32_t *__restrict__ out) {
+    int f, int b, uint32_t *__restrict__ out, const uint32_t *__restrict__ gate, int gate_n) {
+    if (gate != nullptr && !any_word_set(gate, gate_n)) return;
     const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (c >= d) return;
     uint32_t key[BYZ_MAX_F];
@@ -688,29 +698,32 @@ __global__ __launch_bounds__(kProbe) void probe_kernel(const uint32_t *__restric
 // recorded per file (ws->viol).  No violation -> the probable classes are the true ones, the
 // output and the probable winners are final; otherwise the kernels of the exact path, gated
 // on ws->viol, redo the aggregation.
-template <int F, int R, int NS, int V>
+template <int F, int R, int NS, bool TRIM, int V>
 __device__ __forceinline__ void fused_body(const uint32_t *__restrict__ X, int64_t d, int64_t ld,
-                                           const int32_t *__restrict__ perm_rows,
                                            const uint64_t *__restrict__ perm_off,
                                            const uint32_t *__restrict__ chain_mask,
-                                           AggWorkspace *ws, uint32_t *__restrict__ out) {
+                                           AggWorkspace *ws, int trim_b,
+                                           uint32_t *__restrict__ out) {
     const int lane = threadIdx.x & 63;
-    const int64_t n_vec = d / V;
+    // Thread t owns the V words starting at min(V*t, d - V): the last vector of a row overlaps
+    // its neighbour instead of a scalar tail, and threads past the end redo it, so there are
+    // no branches around loads and ballots (d >= V is the launcher's business).
+    const int64_t n_thr = (d + V - 1) / V;
     const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t c0 = (gt + 1) * V <= d ? gt * V : d - V;
     uint32_t flags = 0;
-    if (n_vec > 0) {
-        // threads past the end redo the last vector: no branches around loads and ballots
-        const uint32_t voff = (uint32_t)((gt < n_vec ? gt : n_vec - 1) * (V * 4));
-        const char *Xb = reinterpret_cast<const char *>(X);
-        uint32_t key[V][F];       // wire j of the median network = file j
-        // files prefetched ahead of the one being consumed
-        constexpr int kAhead = prefetch_depth(F, NS);
-        uint32_t stage[kAhead + 1][NS][V];  // copies of the file in use and of those in flight
-        uint32_t o[V];
-        // The generated program walks the files in order: the loads of file j+kAhead are
-        // issued before file j is consumed (compares, key), followed by every comparator of
-        // the median network whose inputs are complete by then.
+    const uint32_t voff = (uint32_t)(c0 * 4);
+    const char *Xb = reinterpret_cast<const char *>(X);
+    uint32_t key[V][F];       // wire j of the network = file j
+    // files prefetched ahead of the one being consumed
+    constexpr int kAhead = prefetch_depth(F, NS);
+    uint32_t stage[kAhead + 1][NS][V];  // copies of the file in use and of those in flight
+    uint32_t o[V];
+    // The generated program walks the files in order: the loads of file j+kAhead are issued
+    // before file j is consumed (compares, key), followed by every comparator of the median
+    // (or, for the trimmed mean, sorting) network whose inputs are complete by then.
 #define BYZ_S_ROW_ADDR(j, k) (Xb + perm_off[(j) * kRowStride + (k)] + voff)
+    if constexpr (!TRIM) {
         if constexpr (F == 9) {
 #include "generated/selnet_stream_9.inc"
         } else if constexpr (F == 25) {
@@ -719,43 +732,34 @@ __device__ __forceinline__ void fused_body(const uint32_t *__restrict__ X, int64
             static_assert(F == 49, "no streamed network generated for this f");
 #include "generated/selnet_stream_49.inc"
         }
-#undef BYZ_S_ROW_ADDR
-        if (gt < n_vec) store_vec<V>(out + gt * V, o);
-    }
-    const int tail = (int)(d - n_vec * V);
-    if (blockIdx.x == gridDim.x - 1 && (int)threadIdx.x < tail) {
-        const int64_t c = n_vec * V + threadIdx.x;
-        uint32_t key[F];
-#pragma unroll
-        for (int j = 0; j < F; ++j) {
-            uint32_t x[NS];
-#pragma unroll
-            for (int k = 0; k < NS; ++k) x[k] = X[(int64_t)perm_rows[j * kRowStride + k] * ld + c];
-            uint32_t bits = 0;
-#pragma unroll
-            for (int k = 1; k < NS; ++k) bits |= (x[k - 1] != x[k] ? 1u : 0u) << (k - 1);
-            bits &= chain_mask[j];
-            if (bits != 0) atomicOr(&ws->viol[j], bits);
-            key[j] = to_key(x[0]);
+    } else {
+        if constexpr (F == 9) {
+#include "generated/selnet_sort_stream_9.inc"
+        } else if constexpr (F == 25) {
+#include "generated/selnet_sort_stream_25.inc"
+        } else {
+#include "generated/selnet_sort_stream_49.inc"
         }
-        out[c] = from_key(SelNet<F>::median(key));
+        trimmed_mean_of_sorted<F, V>(key, trim_b, o);
     }
+#undef BYZ_S_ROW_ADDR
+    if (gt < n_thr) store_vec<V>(out + c0, o);
     merge_flags(ws->viol, F, lane, flags);
 }
 
 #ifndef BYZ_FUSED_ATTR
 #define BYZ_FUSED_ATTR
 #endif
-template <int F, int R, int V>
+template <int F, int R, bool TRIM, int V>
 __global__ __launch_bounds__(kBlock) BYZ_FUSED_ATTR void fused_kernel(
-    const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ perm_rows,
-    const uint64_t *__restrict__ perm_off, const uint32_t *__restrict__ chain_mask,
-    const uint32_t *__restrict__ slots_per_file, AggWorkspace *ws, uint32_t *__restrict__ out) {
+    const uint32_t *__restrict__ X, int64_t d, int64_t ld, const uint64_t *__restrict__ perm_off,
+    const uint32_t *__restrict__ chain_mask, const uint32_t *__restrict__ slots_per_file,
+    AggWorkspace *ws, int trim_b, uint32_t *__restrict__ out) {
     // wave-uniform choice written by the probe
     if (*slots_per_file == (R + 1) / 2)
-        fused_body<F, R, (R + 1) / 2, V>(X, d, ld, perm_rows, perm_off, chain_mask, ws, out);
+        fused_body<F, R, (R + 1) / 2, TRIM, V>(X, d, ld, perm_off, chain_mask, ws, trim_b, out);
     else
-        fused_body<F, R, R, V>(X, d, ld, perm_rows, perm_off, chain_mask, ws, out);
+        fused_body<F, R, R, TRIM, V>(X, d, ld, perm_off, chain_mask, ws, trim_b, out);
 }
 
 // ---------------------------------------------------------------------------- launchers
@@ -836,18 +840,40 @@ int launch_median(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_i
 
 template <int F, int R>
 int launch_fused(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, AggWorkspace *ws,
-                 uint32_t *out, int early_majority, hipStream_t s) {
+                 uint32_t *out, int early_majority, int trim_b, hipStream_t s) {
     probe_kernel<F, R><<<1, kProbe, 0, s>>>(X, d, ld, rows, ws, early_majority);
     BYZ_HIP(hipGetLastError());
     const bool timed = g_prof.count < g_prof.capacity;
     if (timed) BYZ_HIP(hipEventRecord(g_prof.start[g_prof.count], s));
-    fused_kernel<F, R, kVec><<<blocks_for(d / kVec), kBlock, 0, s>>>(
-        X, d, ld, ws->perm_rows, ws->perm_off, ws->chain_mask, &ws->slots_per_file, ws, out);
+    const unsigned g = blocks_for((d + kVec - 1) / kVec);
+    if (trim_b < 0)
+        fused_kernel<F, R, false, kVec><<<g, kBlock, 0, s>>>(
+            X, d, ld, ws->perm_off, ws->chain_mask, &ws->slots_per_file, ws, 0, out);
+    else
+        fused_kernel<F, R, true, kVec><<<g, kBlock, 0, s>>>(
+            X, d, ld, ws->perm_off, ws->chain_mask, &ws->slots_per_file, ws, trim_b, out);
     BYZ_HIP(hipGetLastError());
     if (timed) {
         BYZ_HIP(hipEventRecord(g_prof.stop[g_prof.count], s));
         ++g_prof.count;
     }
+    return BYZ_OK;
+}
+
+int launch_trimmed_mean(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
+                        int b, uint32_t *O, const uint32_t *gate, int gate_n, hipStream_t s) {
+    if (d == 0) return BYZ_OK;
+    const unsigned g = blocks_for((d + kVec - 1) / kVec);
+    if (d >= kVec && f == 9)
+        trimmed_mean_kernel<9, kVec><<<g, kBlock, 0, s>>>(X, d, ld, row_index, b, O, gate, gate_n);
+    else if (d >= kVec && f == 25)
+        trimmed_mean_kernel<25, kVec><<<g, kBlock, 0, s>>>(X, d, ld, row_index, b, O, gate, gate_n);
+    else if (d >= kVec && f == 49)
+        trimmed_mean_kernel<49, kVec><<<g, kBlock, 0, s>>>(X, d, ld, row_index, b, O, gate, gate_n);
+    else
+        trimmed_mean_generic_kernel<<<blocks_for(d), kBlock, 0, s>>>(X, d, ld, row_index, f, b, O,
+                                                                     gate, gate_n);
+    BYZ_HIP(hipGetLastError());
     return BYZ_OK;
 }
 
@@ -910,21 +936,9 @@ extern "C" int byz_trimmed_mean(const float *rows_base, int64_t d, int64_t ld,
     if (d < 0 || ld < d || d > kMaxCoords) return BYZ_EINVAL;
     if (f < 1 || f > BYZ_MAX_F || b < 0 || 2 * b >= f) return BYZ_EINVAL;
     if (d == 0) return BYZ_OK;
-    hipStream_t s = (hipStream_t)stream;
-    const uint32_t *X = reinterpret_cast<const uint32_t *>(rows_base);
-    uint32_t *O = reinterpret_cast<uint32_t *>(out);
-    const unsigned g = blocks_for((d + kVec - 1) / kVec);
-    if (d >= kVec && f == 9)
-        trimmed_mean_kernel<9, kVec><<<g, kBlock, 0, s>>>(X, d, ld, row_index_dev, b, O);
-    else if (d >= kVec && f == 25)
-        trimmed_mean_kernel<25, kVec><<<g, kBlock, 0, s>>>(X, d, ld, row_index_dev, b, O);
-    else if (d >= kVec && f == 49)
-        trimmed_mean_kernel<49, kVec><<<g, kBlock, 0, s>>>(X, d, ld, row_index_dev, b, O);
-    else
-        trimmed_mean_generic_kernel<<<blocks_for(d), kBlock, 0, s>>>(X, d, ld, row_index_dev, f, b,
-                                                                     O);
-    BYZ_HIP(hipGetLastError());
-    return BYZ_OK;
+    return launch_trimmed_mean(reinterpret_cast<const uint32_t *>(rows_base), d, ld, row_index_dev,
+                               f, b, reinterpret_cast<uint32_t *>(out), nullptr, 0,
+                               (hipStream_t)stream);
 }
 
 extern "C" size_t byz_aggregate_workspace_bytes(int f, int r) {
@@ -936,8 +950,13 @@ extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
                                   const int32_t *file_rows_dev, int f, int r, float *out,
                                   int32_t *winner_replica, void *workspace, size_t workspace_bytes,
                                   unsigned flags, void *stream) {
-    if ((flags & ~(unsigned)BYZ_AGG_EARLY_MAJORITY) != 0) return BYZ_EINVAL;
+    if ((flags & ~(unsigned)(BYZ_AGG_EARLY_MAJORITY | BYZ_AGG_TRIMMED_MEAN | 0xFF00u)) != 0)
+        return BYZ_EINVAL;
     const int early = (flags & BYZ_AGG_EARLY_MAJORITY) != 0 ? 1 : 0;
+    // trim_b < 0: median; otherwise trimmed mean dropping trim_b values at each end
+    const int trim_b = (flags & BYZ_AGG_TRIMMED_MEAN) != 0 ? (int)((flags >> 8) & 0xFFu) : -1;
+    if (trim_b < 0 && (flags & 0xFF00u) != 0) return BYZ_EINVAL;
+    if (trim_b >= 0 && 2 * trim_b >= f) return BYZ_EINVAL;
     int rc = check_common(copies, d, ld, file_rows_dev, f, r);
     if (rc != BYZ_OK) return rc;
     if ((out == nullptr && d > 0) || workspace == nullptr) return BYZ_EINVAL;
@@ -949,7 +968,7 @@ extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
     uint32_t *O = reinterpret_cast<uint32_t *>(out);
     AggWorkspace *ws = reinterpret_cast<AggWorkspace *>(workspace);
 
-    if (!has_fused(f, r) || d == 0) {
+    if (!has_fused(f, r) || d < kVec) {
         // two-step path, unconditionally: vote (a1, a2), then median (a3) over the winners
         reset_workspace_kernel<<<1, BYZ_MAX_F, 0, s>>>(ws, 1u);
         BYZ_HIP(hipGetLastError());
@@ -963,21 +982,25 @@ extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
                                                        winner_replica, ws->winner_row);
             BYZ_HIP(hipGetLastError());
         }
+        if (trim_b >= 0)
+            return launch_trimmed_mean(X, d, ld, ws->winner_row, f, trim_b, O, nullptr, 0, s);
         return launch_median(X, d, ld, ws->winner_row, f, O, nullptr, 0, s);
     }
 
     // probe -> single pass -> exact path, whose two kernels return at once unless the single
     // pass recorded a violated assumption
-    if (f == 9) rc = launch_fused<9, 3>(X, d, ld, file_rows_dev, ws, O, early, s);
-    else if (f == 25 && r == 3) rc = launch_fused<25, 3>(X, d, ld, file_rows_dev, ws, O, early, s);
-    else if (f == 25 && r == 5) rc = launch_fused<25, 5>(X, d, ld, file_rows_dev, ws, O, early, s);
-    else if (f == 49 && r == 3) rc = launch_fused<49, 3>(X, d, ld, file_rows_dev, ws, O, early, s);
-    else rc = launch_fused<49, 5>(X, d, ld, file_rows_dev, ws, O, early, s);
+    if (f == 9) rc = launch_fused<9, 3>(X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
+    else if (f == 25 && r == 3) rc = launch_fused<25, 3>(X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
+    else if (f == 25 && r == 5) rc = launch_fused<25, 5>(X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
+    else if (f == 49 && r == 3) rc = launch_fused<49, 3>(X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
+    else rc = launch_fused<49, 5>(X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
     if (rc != BYZ_OK) return rc;
     rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, ws->viol,
                              &ws->ticket_vote, winner_replica, ws->winner_row, ws->prov_winner,
                              &ws->need_exact, s);
     if (rc != BYZ_OK) return rc;
+    if (trim_b >= 0)
+        return launch_trimmed_mean(X, d, ld, ws->winner_row, f, trim_b, O, ws->viol, f, s);
     return launch_median(X, d, ld, ws->winner_row, f, O, ws->viol, f, s);
 }
 

@@ -53,6 +53,15 @@ def _check_all(X, rows_np, d, f, r, expect_exact=None, tag=""):
     torch.cuda.synchronize()
     assert np.array_equal(W.bits(out), W.bits(out_o)), tag
     assert np.array_equal(wrep2.cpu().numpy(), wrep_o), tag
+    # trimmed mean in the single pass: same bits as vote followed by byz_trimmed_mean (both
+    # follow one rounding contract; byz_trimmed_mean itself is checked against the fp64 oracle)
+    trim = min(2, (f - 1) // 2)
+    out_t2 = B.byz_trimmed_mean(X, d, wrow, trim)
+    for flags in (B.BYZ_AGG_TRIM(trim), B.BYZ_AGG_TRIM(trim) | B.BYZ_AGG_EARLY_MAJORITY):
+        out_t, wrep3, _ = B.byz_aggregate_opts(X, d, rows_dev, f, r, flags)
+        torch.cuda.synchronize()
+        assert np.array_equal(W.bits(out_t), W.bits(out_t2)), (tag, flags)
+        assert np.array_equal(wrep3.cpu().numpy(), wrep_o), (tag, flags)
     return out_o, wrep_o, took_exact
 
 
@@ -220,6 +229,10 @@ def test_argument_errors():
     with pytest.raises(B.ByzError) as e:
         B.byz_median(w.X, 100, rows_dev[:24])  # even f
     assert e.value.code == -2
+    for bad in (4, 0x100, B.BYZ_AGG_TRIM(13)):  # unknown bit, b without the flag, 2b >= f
+        with pytest.raises(B.ByzError) as e:
+            B.byz_aggregate_opts(w.X, 100, rows_dev, 25, 3, bad)
+        assert e.value.code == -1
     small = torch.empty(64, dtype=torch.uint8, device=DEV)
     with pytest.raises(B.ByzError) as e:
         B.byz_aggregate(w.X, 100, rows_dev, 25, 3, workspace=small)
