@@ -191,6 +191,11 @@ def main():
         ms_med = timed_call(lambda: B.byz_median(bufs[0], d, wrow_v, out=out, stream=stream))
         ms_tm = timed_call(lambda: B.byz_trimmed_mean(bufs[0], d, wrow_v, cmax, out=out, stream=stream))
         ms_agg_tm = timed_call(lambda: step(0, B.BYZ_AGG_TRIM(cmax)))
+        mk_m = asg.f - cmax
+        mk_ws = torch.empty(B.byz_multi_krum_workspace_bytes(asg.f), dtype=torch.uint8, device=dev)
+        ms_mk = timed_call(lambda: B.byz_multi_krum(bufs[0], d, wrow_v, cmax, mk_m, out=out,
+                                                    workspace=mk_ws, stream=stream))
+        kb = 4.0 * asg.f * d + 4.0 * (mk_m + 1) * d  # Gram pass over f rows + mean of m rows
         vb, mb = 4.0 * asg.r * asg.f * d, 4.0 * (asg.f + 1) * d
         result["components"] = {
             "byz_vote": {"ms": ms_vote, "algorithmic_bytes": vb, "gbps": vb / ms_vote / 1e6,
@@ -202,6 +207,10 @@ def main():
                                            "gbps": alg_bytes / ms_agg_tm / 1e6,
                                            "frac": alg_bytes / ms_agg_tm / 1e6 / HBM_PEAK_GBPS,
                                            "note": "whole path with the trimmed mean in the single pass"},
+            "byz_multi_krum": {"ms": ms_mk, "c": cmax, "m": mk_m, "algorithmic_bytes": kb,
+                               "gbps": kb / ms_mk / 1e6, "frac": kb / ms_mk / 1e6 / HBM_PEAK_GBPS,
+                               "gram_tflops": 2.0 * asg.f * asg.f * d / ms_mk / 1e9,
+                               "note": "Gram (fp32 MFMA) + reduce + select + mean of m rows"},
             "byz_trimmed_mean": {"ms": ms_tm, "b": cmax, "algorithmic_bytes": mb,
                                  "gbps": mb / ms_tm / 1e6, "frac": mb / ms_tm / 1e6 / HBM_PEAK_GBPS},
         }

@@ -164,6 +164,32 @@ int byz_median(const float *rows_base, int64_t d, int64_t ld, const int32_t *row
 int byz_trimmed_mean(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev,
                      int f, int b, float *out, void *stream);
 
+/*
+ * Multi-Krum over f vectors (the aggregator Sec. 6.1 and Sec. 7 name as an alternative to the
+ * median on the vote winners; the rule itself is the published one): with c of the f vectors
+ * possibly Byzantine, f >= 2c + 3 (the requirement Sec. 6.1 quotes),
+ *   score(i) = sum of the f - c - 2 smallest squared Euclidean distances from vector i to the
+ *              other vectors,
+ *   the m vectors of lowest score are selected (equal scores: lower index first), 1 <= m <= f - c
+ *   (m = 1 is Krum, m = f - c the usual Multi-Krum), and out = their coordinate-wise mean.
+ * Arithmetic: the Gram matrix of the f rows is accumulated by fp32 matrix instructions over
+ * 512 fixed coordinate slices and the slices are added in fp64 in a fixed order (results are
+ * reproducible); distances d(i,j) = G_ii + G_jj - 2 G_ij, scores and ranking in fp64; the mean
+ * is fp32, selected rows added one by one in ascending index from +0, one IEEE division by m.
+ *   rows_base / row_index_dev  as byz_median (f rows gathered through the index table)
+ *   out           device [d] fp32
+ *   selected_out  device [f] int32 out: 1 for the selected rows, else 0
+ *   scores_out    device [f] double out, may be NULL
+ *   dist_out      device [f*f] double out, may be NULL
+ *   workspace     device, >= byz_multi_krum_workspace_bytes(f) bytes, 256-byte aligned
+ * Errors: BYZ_EINVAL (null pointers, f < 2c + 3, m outside [1, f - c], sizes), BYZ_ENOMEM
+ * (workspace too small), BYZ_EDEVICE.
+ */
+size_t byz_multi_krum_workspace_bytes(int f);
+int byz_multi_krum(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev,
+                   int f, int c, int m, float *out, int32_t *selected_out, double *scores_out,
+                   double *dist_out, void *workspace, size_t workspace_bytes, void *stream);
+
 /* --------------------------------------------------- device: fused vote + median (whole path) */
 
 /* Bytes of device scratch byz_aggregate needs for (f, r); 0 if (f, r) is invalid. */

@@ -17,6 +17,8 @@ Parity status of each function (what pins it, see tests/test_oracle_*.py):
   vote                                brute force over all equality patterns, Sec. 2
                                       statements (all-honest, distorted iff >= r')
   median                              numpy sort/median on ordinary data, brute force
+  multi_krum                          scipy cdist, hand-worked line example, outlier exclusion
+                                      (the paper cites but does not define the rule)
   trimmed_mean                        scipy.stats.trim_mean, b=0 mean, b=(f-1)/2 median, hand-worked case
   tie-break rules (vote plurality ties -> lowest replica; total order of
   +-0 / NaN in the median; lexicographically first worst-case set):
@@ -281,6 +283,35 @@ def trimmed_mean(X, row_index, d, b):
     for i in range(b, f - b):
         acc = acc + srt[i]
     return acc / float(f - 2 * b)
+
+
+def multi_krum(X, row_index, d, c, m):
+    """Multi-Krum (the aggregator Sec. 6.1 / Sec. 7 of the paper name for use on the vote
+    winners; rule as published by Blanchard et al. and Damaskinos et al.): with f vectors of
+    which c may be Byzantine (f >= 2c + 3), score(i) = sum of the f - c - 2 smallest squared
+    distances from vector i to the others; the m lowest scores (ties: lower index) are
+    selected and averaged.  Everything in fp64, distances as sums of squared differences.
+    Returns (mean[d], selected[f] 0/1, scores[f], dist[f, f])."""
+    V = np.stack([np.ascontiguousarray(X)[int(j), :d] for j in row_index]).astype(np.float64)
+    f = V.shape[0]
+    assert f >= 2 * c + 3 and 1 <= m <= f - c
+    dist = np.zeros((f, f))
+    for i in range(f):
+        for j in range(f):
+            diff = V[i] - V[j]
+            dist[i, j] = float(np.dot(diff, diff))
+    scores = np.zeros(f)
+    for i in range(f):
+        others = sorted(dist[i, j] for j in range(f) if j != i)
+        scores[i] = sum(others[:f - c - 2])
+    order = sorted(range(f), key=lambda i: (scores[i], i))
+    selected = np.zeros(f, dtype=np.int32)
+    selected[order[:m]] = 1
+    acc = np.zeros(d)
+    for i in range(f):
+        if selected[i]:
+            acc = acc + V[i]
+    return acc / m, selected, scores, dist
 
 
 def aggregate(X, rows, d):

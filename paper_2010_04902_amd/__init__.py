@@ -20,6 +20,8 @@ from .binding import (  # noqa: F401
     byz_calibration_copy,
     byz_gamma_bound,
     byz_median,
+    byz_multi_krum,
+    byz_multi_krum_workspace_bytes,
     byz_profile_collect,
     byz_profile_enable,
     byz_strerror,

@@ -59,6 +59,8 @@ def _load():
         "byz_vote": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, vp]),
         "byz_median": (c_int, [vp, i64, i64, vp, c_int, vp, vp]),
         "byz_trimmed_mean": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp]),
+        "byz_multi_krum_workspace_bytes": (sz, [c_int]),
+        "byz_multi_krum": (c_int, [vp, i64, i64, vp, c_int, c_int, c_int, vp, vp, vp, vp, vp, sz, vp]),
         "byz_aggregate_workspace_bytes": (sz, [c_int, c_int]),
         "byz_aggregate": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, sz, vp]),
         "byz_aggregate_opts": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, sz,
@@ -207,6 +209,34 @@ def byz_trimmed_mean(rows_base, d, row_index_dev, b, out=None, stream=None):
                                     int(b), _dev_ptr(out, ("float32",), "out"),
                                     _stream_ptr(stream)), "byz_trimmed_mean")
     return out
+
+
+def byz_multi_krum_workspace_bytes(f):
+    return int(_load().byz_multi_krum_workspace_bytes(int(f)))
+
+
+def byz_multi_krum(rows_base, d, row_index_dev, c, m, out=None, workspace=None, stream=None):
+    """-> (out[d] float32, selected[f] int32, scores[f] float64, dist[f, f] float64), on device."""
+    torch = _torch()
+    ld = _rows_2d(rows_base)
+    f = int(row_index_dev.numel())
+    dev = rows_base.device
+    if out is None:
+        out = torch.empty(int(d), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(max(byz_multi_krum_workspace_bytes(f), 256), dtype=torch.uint8, device=dev)
+    selected = torch.empty(f, dtype=torch.int32, device=dev)
+    scores = torch.empty(f, dtype=torch.float64, device=dev)
+    dist = torch.empty((f, f), dtype=torch.float64, device=dev)
+    _check(_load().byz_multi_krum(_dev_ptr(rows_base, ("float32",), "rows_base"), int(d), ld,
+                                  _dev_ptr(row_index_dev, ("int32",), "row_index_dev"), f, int(c),
+                                  int(m), _dev_ptr(out, ("float32",), "out"),
+                                  _dev_ptr(selected, ("int32",), "selected"),
+                                  _dev_ptr(scores, ("float64",), "scores"),
+                                  _dev_ptr(dist, ("float64",), "dist"),
+                                  _dev_ptr(workspace, ("uint8",), "workspace"),
+                                  int(workspace.numel()), _stream_ptr(stream)), "byz_multi_krum")
+    return out, selected, scores, dist
 
 
 def byz_aggregate_workspace_bytes(f, r):

@@ -16,6 +16,7 @@
 #include <cstdint>
 #include <new>
 
+#include "byz_internal.h"
 #include "byzshield.h"
 
 namespace {
@@ -894,6 +895,8 @@ int check_common(const void *copies, int64_t d, int64_t ld, const void *rows, in
 // ---------------------------------------------------------------------------- C-ABI
 
 extern "C" int byz_last_hip_error(void) { return g_last_hip_error; }
+
+void byz_internal_set_hip_error(int code) { g_last_hip_error = code; }
 
 extern "C" int byz_vote(const float *copies, int64_t d, int64_t ld, const int32_t *file_rows_dev,
                         int f, int r, int32_t *winner_replica, int32_t *winner_row,

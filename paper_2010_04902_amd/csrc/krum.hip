@@ -1,0 +1,337 @@
+// Multi-Krum on the vote winners (gfx950).  The ByzShield paper pairs its vote with the
+// coordinate-wise median and names Multi-Krum and Bulyan as aggregators that can take the
+// median's place (Sec. 6.1, Sec. 7); it defines neither, so this file follows the published
+// rule: with f vectors of which c may be Byzantine (f >= 2c + 3, the requirement quoted in
+// Sec. 6.1), the score of vector i is the sum of its f - c - 2 smallest squared distances to
+// other vectors; the m vectors of lowest score are averaged.
+//
+// The pairwise squared distances come from the Gram matrix G = W W^T of the f x d matrix of
+// winners: the one dense contraction of the whole path, done with fp32 MFMA tiles
+// (v_mfma_f32_32x32x2f32).  A block stages a 256-coordinate chunk of all f rows in LDS (global
+// loads stay 1 KiB-contiguous per wave), each of its four waves multiplies 64 of those
+// coordinates, and the blocks walk the chunks grid-stride.  Per-block partial tiles are
+// added in fp64 in block order, so the result does not depend on scheduling.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "byz_internal.h"
+#include "byzshield.h"
+
+namespace {
+
+#define BYZ_HIP(call)                              \
+    do {                                           \
+        hipError_t e_ = (call);                    \
+        if (e_ != hipSuccess) {                    \
+            byz_internal_set_hip_error((int)e_);   \
+            return BYZ_EDEVICE;                    \
+        }                                          \
+    } while (0)
+
+constexpr int kBlock = 256;            // 4 waves
+constexpr int kChunk = 256;            // coordinates staged per block and step
+constexpr int kStride = kChunk + 1;    // odd row pitch in LDS: conflict-free MFMA operand reads
+constexpr int kGramBlocks = 512;       // partial Gram tiles (2 blocks per CU)
+constexpr int kTile = 32 * 32;         // outputs of one MFMA tile
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4u __attribute__((ext_vector_type(4), aligned(4)));
+
+// The 32x32 MFMA result: accumulator register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4,
+// column l%32 (gram_at below inverts this).
+
+// Partial Gram tiles of the rows row_index[0..f-1] over this block's chunks.
+// NT = 1: f <= 32, one tile.  NT = 2: f <= 64, tiles (0,0), (0,1), (1,1) of the 64x64 matrix.
+// RW = rows a wave stages per chunk (rows wave, wave+4, ...): ceil(f / 4) rounded up to a
+// compiled value.  partial: [gridDim.x][NTILES][1024] floats, position v*64 + lane.
+// Per chunk: the rows' 16-byte loads for the NEXT chunk are issued, then the current chunk
+// (already in registers) goes to LDS, is multiplied, and the loop turns: global latency hides
+// behind the matrix instructions.
+template <int NT, int RW>
+__global__ __launch_bounds__(kBlock) void gram_partial_kernel(const float *__restrict__ X, int64_t d,
+                                                              int64_t ld,
+                                                              const int32_t *__restrict__ row_index,
+                                                              int f, float *__restrict__ partial) {
+    extern __shared__ float T[];  // [32*NT][kStride]; rows >= f stay zero
+    constexpr int NTILES = NT == 1 ? 1 : 3;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    for (int i = tid; i < (32 * NT - f) * kStride; i += kBlock) T[f * kStride + i] = 0.0f;
+    f32x16 acc00 = {0}, acc01 = {0}, acc11 = {0};
+    const int64_t n_chunks = (d + kChunk - 1) / kChunk;
+
+    // this wave's rows; slots past f repeat the last row (loaded, never stored)
+    const float *rowp[RW];
+#pragma unroll
+    for (int t = 0; t < RW; ++t) {
+        const int j = wave + 4 * t;
+        rowp[t] = X + (int64_t)row_index[j < f ? j : f - 1] * ld + 4 * lane;
+    }
+    float reg[RW][4];
+    auto fetch = [&](int64_t chunk) {
+        const int64_t c0 = chunk * kChunk + 4 * lane;
+        if ((chunk + 1) * kChunk <= d) {  // whole chunk inside the row: branch-free loads
+#pragma unroll
+            for (int t = 0; t < RW; ++t) {
+                const f32x4u v = __builtin_nontemporal_load(
+                    reinterpret_cast<const f32x4u *>(rowp[t] + chunk * kChunk));
+                reg[t][0] = v[0]; reg[t][1] = v[1]; reg[t][2] = v[2]; reg[t][3] = v[3];
+            }
+        } else {  // the ragged last chunk: missing coordinates count as zero
+#pragma unroll
+            for (int t = 0; t < RW; ++t)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    reg[t][e] = c0 + e < d ? rowp[t][chunk * kChunk + e] : 0.0f;
+        }
+    };
+
+    int64_t chunk = blockIdx.x;
+    if (chunk < n_chunks) fetch(chunk);
+    for (; chunk < n_chunks; chunk += gridDim.x) {
+#pragma unroll
+        for (int t = 0; t < RW; ++t) {
+            const int j = wave + 4 * t;
+            if (j < f) {
+                float *dst = T + j * kStride + 4 * lane;
+                dst[0] = reg[t][0]; dst[1] = reg[t][1]; dst[2] = reg[t][2]; dst[3] = reg[t][3];
+            }
+        }
+        __syncthreads();
+        if (chunk + gridDim.x < n_chunks) fetch(chunk + gridDim.x);
+        // wave w multiplies coordinates [64w, 64w+64) of the chunk, two per MFMA: lane l holds
+        // A[row = l%32][k = l/32], which is also B[k][col = l%32] of the transposed operand
+        const float *t0 = T + (lane & 31) * kStride + wave * 64 + (lane >> 5);
+#pragma unroll
+        for (int s0 = 0; s0 < 32; s0 += 16) {
+            float x0[16], x1[16];
+#pragma unroll
+            for (int s = 0; s < 16; ++s) {
+                x0[s] = t0[2 * (s0 + s)];
+                if constexpr (NT == 2) x1[s] = t0[32 * kStride + 2 * (s0 + s)];
+            }
+#pragma unroll
+            for (int s = 0; s < 16; ++s) {
+                acc00 = __builtin_amdgcn_mfma_f32_32x32x2f32(x0[s], x0[s], acc00, 0, 0, 0);
+                if constexpr (NT == 2) {
+                    acc01 = __builtin_amdgcn_mfma_f32_32x32x2f32(x0[s], x1[s], acc01, 0, 0, 0);
+                    acc11 = __builtin_amdgcn_mfma_f32_32x32x2f32(x1[s], x1[s], acc11, 0, 0, 0);
+                }
+            }
+        }
+        __syncthreads();
+    }
+    // add the four waves' tiles through LDS (the staging tile is free now), then store
+    float *red = T;  // [4][NTILES][1024] floats = 16 or 48 KiB <= the staging tile
+    for (int v = 0; v < 16; ++v) {
+        red[(wave * NTILES + 0) * kTile + v * 64 + lane] = acc00[v];
+        if constexpr (NT == 2) {
+            red[(wave * NTILES + 1) * kTile + v * 64 + lane] = acc01[v];
+            red[(wave * NTILES + 2) * kTile + v * 64 + lane] = acc11[v];
+        }
+    }
+    __syncthreads();
+    float *dst = partial + (int64_t)blockIdx.x * NTILES * kTile;
+    for (int i = tid; i < NTILES * kTile; i += kBlock)
+        dst[i] = ((red[i] + red[NTILES * kTile + i]) + red[2 * NTILES * kTile + i]) +
+                 red[3 * NTILES * kTile + i];
+}
+
+// gram[t][pos] = sum over blocks of partial[block][t][pos] in fp64, in a fixed order: thread
+// (pos, g) adds the blocks g, g+8, g+16, ... one by one, then the eight group sums are added
+// in order.  Block = 32 positions x 8 groups.
+__global__ __launch_bounds__(kBlock) void gram_reduce_kernel(const float *__restrict__ partial,
+                                                             int n_partial, int ntiles,
+                                                             double *__restrict__ gram) {
+    __shared__ double s_sum[8][32];
+    const int lp = threadIdx.x & 31, g = threadIdx.x >> 5;
+    const int i = blockIdx.x * 32 + lp;  // ntiles * 1024 is a multiple of 32
+    double acc = 0.0;
+#pragma unroll 8
+    for (int p = g; p < n_partial; p += 8) acc += (double)partial[(int64_t)p * ntiles * kTile + i];
+    s_sum[g][lp] = acc;
+    __syncthreads();
+    if (g == 0) {
+        double total = s_sum[0][lp];
+        for (int k = 1; k < 8; ++k) total += s_sum[k][lp];
+        gram[i] = total;
+    }
+}
+
+__device__ inline double gram_at(const double *gram, int i, int j) {
+    // entry (i, j) of the symmetric matrix from the stored tiles (0,0), (0,1), (1,1)
+    if (i > j) { const int t = i; i = j; j = t; }
+    const int ti = i / 32, tj = j / 32;
+    const int tile = ti == 0 ? (tj == 0 ? 0 : 1) : 2;
+    const int r = i % 32, c = j % 32;
+    // row r = 8*(v/4) + 4*(l/32) + v%4, column c = l%32  =>
+    const int v = 4 * (r / 8) + (r % 4), l = c + 32 * ((r / 4) % 2);
+    return gram[tile * kTile + v * 64 + l];
+}
+
+// One block of 256 threads: distances (all threads), then scores and selection (thread i < f).
+__global__ __launch_bounds__(kBlock) void krum_select_kernel(const double *__restrict__ gram, int f,
+                                                             int c, int m, double *dist_out,
+                                                             double *scores_out, int32_t *selected_out,
+                                                             double *sorted_rows, int32_t *selected_list,
+                                                             int32_t *n_selected) {
+    __shared__ double s_dist[BYZ_MAX_F * BYZ_MAX_F];
+    __shared__ double s_score[BYZ_MAX_F];
+    __shared__ int32_t s_sel[BYZ_MAX_F];
+    const int tid = threadIdx.x;
+    for (int e = tid; e < f * f; e += kBlock) {
+        const int i = e / f, j = e % f;
+        double dij = gram_at(gram, i, i) + gram_at(gram, j, j) - 2.0 * gram_at(gram, i, j);
+        if (dij < 0.0 || j == i) dij = 0.0;
+        s_dist[e] = dij;
+        if (dist_out != nullptr) dist_out[e] = dij;
+    }
+    __syncthreads();
+    // sorted_rows[i][rank] = distance of rank `rank` among row i's distances to the others
+    // (value, then index, orders them): every (i, j) finds its own rank, all threads at work
+    for (int e = tid; e < f * f; e += kBlock) {
+        const int i = e / f, j = e % f;
+        if (i == j) continue;
+        const double v = s_dist[e];
+        int rank = 0;
+        for (int k = 0; k < f; ++k) {
+            if (k == i) continue;
+            const double u = s_dist[i * f + k];
+            rank += (u < v || (u == v && k < j)) ? 1 : 0;
+        }
+        sorted_rows[i * f + rank] = v;
+    }
+    __syncthreads();
+    const int i = tid;
+    if (i < f) {
+        // score = the f-c-2 smallest distances to others, added one by one in ascending order
+        double score = 0.0;
+        for (int t = 0; t < f - c - 2; ++t) score += sorted_rows[i * f + t];
+        s_score[i] = score;
+        if (scores_out != nullptr) scores_out[i] = score;
+    }
+    __syncthreads();
+    if (i < f) {
+        int rank = 0;
+        for (int k = 0; k < f; ++k)
+            rank += (s_score[k] < s_score[i] || (s_score[k] == s_score[i] && k < i)) ? 1 : 0;
+        s_sel[i] = rank < m ? 1 : 0;
+        selected_out[i] = s_sel[i];
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int n = 0;
+        for (int k = 0; k < f; ++k)
+            if (s_sel[k] != 0) selected_list[n++] = k;
+        *n_selected = n;
+    }
+}
+
+// out[c] = mean of the selected rows: fp32, added one by one in ascending file index starting
+// from +0, one IEEE division by the count.  Thread t owns the words from min(4t, d-4) (d >= 4).
+__global__ __launch_bounds__(kBlock) void selected_mean_kernel(const float *__restrict__ X, int64_t d,
+                                                               int64_t ld,
+                                                               const int32_t *__restrict__ row_index,
+                                                               const int32_t *__restrict__ selected_list,
+                                                               const int32_t *__restrict__ n_selected,
+                                                               float *__restrict__ out) {
+    const int n = *n_selected;
+    if (d >= 4) {
+        const int64_t n_thr = (d + 3) / 4;
+        const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+        if (gt >= n_thr) return;
+        const int64_t c0 = (gt + 1) * 4 <= d ? gt * 4 : d - 4;
+        float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+#pragma unroll 4
+        for (int t = 0; t < n; ++t) {
+            const float *p = X + (int64_t)row_index[selected_list[t]] * ld + c0;
+            const f32x4u v = __builtin_nontemporal_load(reinterpret_cast<const f32x4u *>(p));
+            a0 += v[0]; a1 += v[1]; a2 += v[2]; a3 += v[3];
+        }
+        const float dn = (float)n;
+        f32x4u o;
+        o[0] = a0 / dn; o[1] = a1 / dn; o[2] = a2 / dn; o[3] = a3 / dn;
+        __builtin_nontemporal_store(o, reinterpret_cast<f32x4u *>(out + c0));
+    } else {
+        const int64_t cc = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+        if (cc >= d) return;
+        float a = 0.0f;
+        for (int t = 0; t < n; ++t) a += X[(int64_t)row_index[selected_list[t]] * ld + cc];
+        out[cc] = a / (float)n;
+    }
+}
+
+struct KrumWorkspace {
+    double gram[3 * kTile];
+    double sorted_rows[BYZ_MAX_F * BYZ_MAX_F];
+    int32_t selected_list[BYZ_MAX_F];
+    int32_t n_selected;
+    int32_t pad[63];
+    float partial[(size_t)kGramBlocks * 3 * kTile];
+};
+
+}  // namespace
+
+extern "C" size_t byz_multi_krum_workspace_bytes(int f) {
+    if (f < 1 || f > BYZ_MAX_F) return 0;
+    return sizeof(KrumWorkspace);
+}
+
+extern "C" int byz_multi_krum(const float *rows_base, int64_t d, int64_t ld,
+                              const int32_t *row_index_dev, int f, int c, int m, float *out,
+                              int32_t *selected_out, double *scores_out, double *dist_out,
+                              void *workspace, size_t workspace_bytes, void *stream) {
+    if (rows_base == nullptr || row_index_dev == nullptr || selected_out == nullptr ||
+        workspace == nullptr || (out == nullptr && d > 0))
+        return BYZ_EINVAL;
+    if (d < 0 || ld < d || d > ((int64_t)1 << 30)) return BYZ_EINVAL;
+    if (f < 3 || f > BYZ_MAX_F || c < 0 || f < 2 * c + 3) return BYZ_EINVAL;  // Sec. 6.1
+    if (m < 1 || m > f - c) return BYZ_EINVAL;
+    if (((uintptr_t)workspace & 255u) != 0) return BYZ_EINVAL;
+    if (workspace_bytes < sizeof(KrumWorkspace)) return BYZ_ENOMEM;
+    hipStream_t s = (hipStream_t)stream;
+    KrumWorkspace *ws = reinterpret_cast<KrumWorkspace *>(workspace);
+    const int nt = f <= 32 ? 1 : 2;
+    const int ntiles = nt == 1 ? 1 : 3;
+    int64_t n_chunks = (d + kChunk - 1) / kChunk;
+    if (n_chunks < 1) n_chunks = 1;  // d == 0: one block writes zero tiles
+    const int grid = n_chunks < kGramBlocks ? (int)n_chunks : kGramBlocks;
+    const size_t lds = (size_t)32 * nt * kStride * sizeof(float);
+    // rows a wave stages per chunk: ceil(f / 4), rounded up to a compiled value
+    if (f <= 16) {
+        gram_partial_kernel<1, 4><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
+                                                           ws->partial);
+    } else if (f <= 28) {
+        gram_partial_kernel<1, 7><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
+                                                           ws->partial);
+    } else if (f <= 32) {
+        gram_partial_kernel<1, 8><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
+                                                           ws->partial);
+    } else {
+        // 64 rows x 257 words is a little over the 64 KiB a kernel may use without asking
+        if (f <= 52) {
+            BYZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&gram_partial_kernel<2, 13>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            gram_partial_kernel<2, 13><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
+                                                                ws->partial);
+        } else {
+            BYZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&gram_partial_kernel<2, 16>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            gram_partial_kernel<2, 16><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
+                                                                ws->partial);
+        }
+    }
+    BYZ_HIP(hipGetLastError());
+    gram_reduce_kernel<<<ntiles * kTile / 32, kBlock, 0, s>>>(ws->partial, grid, ntiles, ws->gram);
+    BYZ_HIP(hipGetLastError());
+    krum_select_kernel<<<1, kBlock, 0, s>>>(ws->gram, f, c, m, dist_out, scores_out, selected_out,
+                                            ws->sorted_rows, ws->selected_list, &ws->n_selected);
+    BYZ_HIP(hipGetLastError());
+    if (d > 0) {
+        const int64_t n_thr = d >= 4 ? (d + 3) / 4 : d;
+        selected_mean_kernel<<<(unsigned)((n_thr + kBlock - 1) / kBlock), kBlock, 0, s>>>(
+            rows_base, d, ld, row_index_dev, ws->selected_list, &ws->n_selected, out);
+        BYZ_HIP(hipGetLastError());
+    }
+    return BYZ_OK;
+}

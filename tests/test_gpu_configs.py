@@ -111,3 +111,15 @@ def test_trimmed_mean_full_size(idx):
     _, wrow, _ = B.byz_vote(w.X, w.d, rows_dev, w.f, w.r)
     torch.cuda.synchronize()
     _trimmed_mean_check(w.X, wrow.cpu().numpy(), w.d, cfg.cmax, cfg.name)
+
+
+def test_multi_krum_full_size():
+    # Multi-Krum over the vote winners of workload 2 (c = c_max = 5, m = f - c = 20) at full
+    # size: 11,173,962 coordinates = 43,649 chunks, 86 per block
+    from tests.test_gpu_parity import _multi_krum_check
+    cfg = synth.CONFIGS[1]
+    w = W.from_config(cfg, DEV, ld=synth.padded_ld(cfg.d, 64))
+    rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+    _, wrow, _ = B.byz_vote(w.X, w.d, rows_dev, w.f, w.r)
+    torch.cuda.synchronize()
+    _multi_krum_check(w.X, wrow.cpu().numpy(), w.d, cfg.cmax, w.f - cfg.cmax, cfg.name)

@@ -390,3 +390,64 @@ def test_trimmed_mean_special_values():
     idx = np.arange(f, dtype=np.int32)
     for b in (0, 3, 12):
         _trimmed_mean_check(X, idx, d, b, b)
+
+
+def _multi_krum_check(X, idx_np, d, c, m, tag):
+    """GPU Multi-Krum against the fp64 oracle.
+
+    Tolerances from the arithmetic: a Gram entry is accumulated in fp32 over at most L products
+    per block (L = coordinates a block handles) plus a few adds, then in fp64, so
+    |dG_ij| <= (L + 8) * 2^-24 * (G_ii + G_jj) / 2 and |dD_ij| <= 2 * (L + 8) * 2^-24 * (G_ii + G_jj).
+    A score adds at most f distances.  The selection is compared where the oracle's scores are
+    further from the cut than twice that; the mean is checked for the rows the GPU selected
+    (fp32 sequential sum: m * 2^-24 * max|x|)."""
+    idx_dev = torch.tensor(idx_np, dtype=torch.int32, device=DEV)
+    out, sel, scores, dist = B.byz_multi_krum(X, d, idx_dev, c, m)
+    torch.cuda.synchronize()
+    Xh = X.detach().cpu().numpy()
+    mean_o, sel_o, scores_o, dist_o = O.multi_krum(Xh, idx_np, d, c, m)
+    f = len(idx_np)
+    n_chunks = max(1, -(-d // 256))
+    L = -(-n_chunks // min(n_chunks, 512)) * 256
+    norms = np.diag(dist_o * 0) + np.array([float(np.dot(Xh[j, :d].astype(np.float64), Xh[j, :d].astype(np.float64))) for j in idx_np])
+    tol_d = 2.0 * (L + 8) * 2.0 ** -24 * (norms[:, None] + norms[None, :]) + 1e-300
+    dist_g = dist.cpu().numpy()
+    assert (np.abs(dist_g - dist_o) <= tol_d).all(), tag
+    assert (np.diag(dist_g) == 0).all() and np.array_equal(dist_g, dist_g.T), tag
+    tol_s = f * tol_d.max()
+    assert (np.abs(scores.cpu().numpy() - scores_o) <= tol_s).all(), tag
+    sel_g = sel.cpu().numpy()
+    assert sel_g.sum() == m, tag
+    cut = np.sort(scores_o)[m - 1]
+    assert (sel_g[scores_o < cut - 2 * tol_s] == 1).all(), tag
+    assert (sel_g[scores_o > cut + 2 * tol_s] == 0).all(), tag
+    rows = Xh[idx_np[sel_g == 1]][:, :d].astype(np.float64)
+    want = rows.mean(axis=0)
+    tol_m = 1.5 * m * 2.0 ** -24 * np.abs(rows).max(axis=0) + 1e-44
+    assert (np.abs(out.cpu().numpy().astype(np.float64) - want) <= tol_m).all(), tag
+    return sel_g, sel_o
+
+
+@pytest.mark.parametrize("scheme,a,b,q,attack", [(MOLS, 5, 3, 4, ALIE), (MOLS, 7, 3, 5, REVERSED),
+                                                 (RAM, 5, 5, 6, MIXED), (RAM, 3, 3, 1, CONST),
+                                                 (RAM, 3, 5, 2, CONST), (RAM, 7, 9, 6, CONST)])
+def test_multi_krum_on_the_vote_winners(scheme, a, b, q, attack):
+    for i, d in enumerate([1, 3, 255, 256, 257, 5000, 70001, 300001]):
+        w = W.make(scheme, a, b, q, d, attack, seed=400 + i, ld=synth.padded_ld(d, 4) + 4 * (i % 2),
+                   device=DEV)
+        rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+        wrep, wrow, _ = B.byz_vote(w.X, d, rows_dev, w.f, w.r)
+        torch.cuda.synchronize()
+        idx = wrow.cpu().numpy()
+        c = min(w.cmax, (w.f - 3) // 2)
+        for m in sorted({1, w.f - c}):
+            sel_g, sel_o = _multi_krum_check(w.X, idx, d, c, m, (d, m))
+        if d >= 5000 and attack["kind"] in ("reversed", "constant") and c == w.cmax:
+            # the distorted winners (far-away payloads) are exactly the ones left out
+            lost = [j for j in range(w.f) if int(w.file_workers[j, wrep[j].item()]) in w.byz]
+            assert [j for j in range(w.f) if sel_g[j] == 0] == lost
+    rows_dev = None
+    for (c, m) in [(-1, 1), ((w.f - 1) // 2, 1), (2, 0), (2, w.f - 1)]:  # f < 2c + 3, m outside [1, f - c]
+        with pytest.raises(B.ByzError) as e:
+            B.byz_multi_krum(w.X, w.d, wrow, c, m)
+        assert e.value.code == -1

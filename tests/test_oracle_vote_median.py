@@ -262,3 +262,35 @@ def test_trimmed_mean_hand_worked_and_outliers(name, tmean):
     Z[b:2 * b] = -1e9
     out = tmean(Z, np.arange(f, dtype=np.int32), d, b)
     assert (out >= Z[2 * b:].min(axis=0)).all() and (out <= Z[2 * b:].max(axis=0)).all()
+
+
+def test_multi_krum_hand_worked_and_invariants():
+    from scipy.spatial.distance import cdist
+    # five points on a line: 0, 1, 2, 3, 100; c = 1 -> each score sums the f-c-2 = 2 nearest
+    X = np.array([[0.0], [1.0], [2.0], [3.0], [100.0]], dtype=np.float32)
+    idx = np.arange(5, dtype=np.int32)
+    mean, sel, scores, dist = O.multi_krum(X, idx, 1, c=1, m=4)
+    assert scores.tolist() == [1 + 4, 1 + 1, 1 + 1, 1 + 4, 97 ** 2 + 98 ** 2]
+    assert sel.tolist() == [1, 1, 1, 1, 0] and mean[0] == 1.5
+    # Krum (m = 1): lowest score, lower index on the tie between points 1 and 2
+    mean, sel, _, _ = O.multi_krum(X, idx, 1, c=1, m=1)
+    assert sel.tolist() == [0, 1, 0, 0, 0] and mean[0] == 1.0
+    # distances equal an independent library routine; selection excludes far outliers
+    rng = np.random.default_rng(8)
+    f, d, c = 25, 300, 5
+    V = (0.01 * rng.standard_normal((f, d))).astype(np.float32)
+    bad = [2, 7, 11, 19, 24]
+    V[bad] = 1e3
+    mean, sel, scores, dist = O.multi_krum(V, np.arange(f, dtype=np.int32), d, c=c, m=f - c)
+    assert np.allclose(dist, cdist(V.astype(np.float64), V.astype(np.float64), "sqeuclidean"),
+                       rtol=1e-12, atol=0)
+    assert [i for i in range(f) if sel[i] == 0] == bad
+    good = [i for i in range(f) if i not in bad]
+    assert np.allclose(mean, V[good].astype(np.float64).mean(axis=0), rtol=1e-12, atol=1e-18)
+    # all vectors identical: every score is zero, the first m are selected, the mean is the vector
+    W_ = np.tile(V[:1], (7, 1))
+    mean, sel, scores, _ = O.multi_krum(W_, np.arange(7, dtype=np.int32), d, c=2, m=5)
+    assert (scores == 0).all() and sel.tolist() == [1, 1, 1, 1, 1, 0, 0]
+    assert np.array_equal(mean, V[0].astype(np.float64))
+    with pytest.raises(AssertionError):
+        O.multi_krum(V, np.arange(6, dtype=np.int32), d, c=2, m=1)  # needs f >= 2c + 3
