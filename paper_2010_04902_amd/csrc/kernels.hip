@@ -41,32 +41,17 @@ struct ProfileState {
 };
 thread_local ProfileState g_prof;
 
-#ifndef BYZ_NT_LOADS
-#define BYZ_NT_LOADS 1
-#endif
 
 // Files the single-pass kernel prefetches ahead of the one it consumes, from the number of
 // 16-byte loads per thread it should keep in flight.  Measured on MI355X: about 6 for f = 25
 // (3-4 waves per SIMD), about 12 for f = 49 (2 waves per SIMD); more is slower.
-#ifndef BYZ_INFLIGHT_SMALL
-#define BYZ_INFLIGHT_SMALL 6
-#endif
-#ifndef BYZ_INFLIGHT_LARGE
-#define BYZ_INFLIGHT_LARGE 12
-#endif
 constexpr int prefetch_depth(int f, int slots) {
-    const int target = f >= 49 ? BYZ_INFLIGHT_LARGE : BYZ_INFLIGHT_SMALL;
+    const int target = f >= 49 ? 12 : 6;
     const int a = (target + slots - 1) / slots - 1;
     return a < 1 ? 1 : (a > 5 ? 5 : a);
 }
-#ifndef BYZ_PROBE
-#define BYZ_PROBE 256
-#endif
-constexpr int kProbe = BYZ_PROBE;  // sampled coordinates = threads of the probe block
-#ifndef BYZ_BLOCK
-#define BYZ_BLOCK 256
-#endif
-constexpr int kBlock = BYZ_BLOCK;
+constexpr int kProbe = 256;  // sampled coordinates = threads of the probe block (512: 2x slower)
+constexpr int kBlock = 256;  // threads per block of the streaming kernels (128/512/1024: slower)
 constexpr int kRowStride = 8;  // slots per file in the permuted row table (>= BYZ_MAX_R)
 
 // ----------------------------------------------------------------------------- helpers
@@ -86,11 +71,7 @@ template <> struct VecT<4> {
 template <int V>
 __device__ __forceinline__ void load_vec(const uint32_t *p, uint32_t (&x)[V]) {
     typedef typename VecT<V>::type T;
-#if BYZ_NT_LOADS
     const T t = __builtin_nontemporal_load(reinterpret_cast<const T *>(p));
-#else
-    const T t = *reinterpret_cast<const T *>(p);
-#endif
     if constexpr (V == 1) {
         x[0] = t;
     } else {
@@ -275,8 +256,8 @@ template <> struct SelNet<49> {
 struct AggWorkspace {
     uint32_t viol[BYZ_MAX_F];        // single pass: assumed-equal neighbours that differ
     uint32_t pair_neq[BYZ_MAX_F];    // exact path: all pair bits
-    uint64_t perm_off[BYZ_MAX_F * kRowStride];  // byte offsets row*ld*4 of the rows below
-    int32_t perm_rows[BYZ_MAX_F * kRowStride];  // rows of a file, probable winner's class first
+    // byte offsets row*ld*4 of a file's rows, probable winner's class first
+    uint64_t perm_off[BYZ_MAX_F * kRowStride];
     uint32_t chain_mask[BYZ_MAX_F];  // bit k-1: permuted copies k-1 and k were equal on the sample
     int32_t prov_winner[BYZ_MAX_F];  // probable winner (original replica index)
     int32_t winner_row[BYZ_MAX_F];   // exact path result
@@ -679,7 +660,6 @@ __global__ __launch_bounds__(kProbe) void probe_kernel(const uint32_t *__restric
         uint32_t chain = 0;
         for (int p = 0; p < R; ++p) {
             const int32_t row = file_rows[j * R + perm[p < slots ? p : 0]];
-            ws->perm_rows[j * kRowStride + p] = row;
             ws->perm_off[j * kRowStride + p] = (uint64_t)row * (uint64_t)ld * 4u;
             if (p > 0 && p < slots && label[perm[p]] == label[perm[p - 1]]) chain |= 1u << (p - 1);
         }
@@ -748,11 +728,8 @@ __device__ __forceinline__ void fused_body(const uint32_t *__restrict__ X, int64
     merge_flags(ws->viol, F, lane, flags);
 }
 
-#ifndef BYZ_FUSED_ATTR
-#define BYZ_FUSED_ATTR
-#endif
 template <int F, int R, bool TRIM, int V>
-__global__ __launch_bounds__(kBlock) BYZ_FUSED_ATTR void fused_kernel(
+__global__ __launch_bounds__(kBlock) void fused_kernel(
     const uint32_t *__restrict__ X, int64_t d, int64_t ld, const uint64_t *__restrict__ perm_off,
     const uint32_t *__restrict__ chain_mask, const uint32_t *__restrict__ slots_per_file,
     AggWorkspace *ws, int trim_b, uint32_t *__restrict__ out) {
@@ -765,10 +742,7 @@ __global__ __launch_bounds__(kBlock) BYZ_FUSED_ATTR void fused_kernel(
 
 // ---------------------------------------------------------------------------- launchers
 
-#ifndef BYZ_VEC
-#define BYZ_VEC 4
-#endif
-constexpr int kVec = BYZ_VEC;  // words per thread and load; rows only need dword alignment
+constexpr int kVec = 4;  // words per thread and load; rows only need dword alignment
 
 // blocks for n_vec vector-owning threads; at least one so the trailing words get a block
 inline unsigned blocks_for(int64_t n_vec) {
