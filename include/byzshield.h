@@ -158,7 +158,8 @@ int byz_median(const float *rows_base, int64_t d, int64_t ld, const int32_t *row
  * infinities go first).  b = 0 is the plain mean.  Not pure selection; the rounding contract
  * is: fp32, kept values added one by one in ascending order starting from +0, then one IEEE
  * division by float(f - 2b).
- *   f in {9,25,49} runs a register sorting network, other f <= 64 a slower generic kernel.
+ *   f in {9,15,21,25,35,49} runs a register sorting network, other f <= 64 a slower generic
+ *   kernel.
  * Errors: BYZ_EINVAL (null pointers, sizes, b < 0 or 2b >= f), BYZ_EDEVICE.
  */
 int byz_trimmed_mean(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev,

@@ -50,6 +50,11 @@ constexpr int prefetch_depth(int f, int slots) {
     const int a = (target + slots - 1) / slots - 1;
     return a < 1 ? 1 : (a > 5 ? 5 : a);
 }
+// f with a generated streamed network (gen_selnet.py STREAMED_SIZES): the paper's file counts
+// l^2 (MOLS, Ramanujan Case 1) and m*s (Ramanujan Case 2)
+constexpr bool has_streamed_network(int f) {
+    return f == 9 || f == 15 || f == 21 || f == 25 || f == 35 || f == 49;
+}
 constexpr int kProbe = 256;  // sampled coordinates = threads of the probe block (512: 2x slower)
 constexpr int kBlock = 256;  // threads per block of the streaming kernels (128/512/1024: slower)
 constexpr int kRowStride = 8;  // slots per file in the permuted row table (>= BYZ_MAX_R)
@@ -429,7 +434,7 @@ __global__ __launch_bounds__(kBlock) void median_kernel(
     if (gt < n_vec) {
         uint32_t key[V][F];
         uint32_t o[V];
-        if constexpr (F == 9 || F == 25 || F == 49) {
+        if constexpr (has_streamed_network(F)) {
             // same streamed program as the single-pass kernel, one slot per file, no compares
             constexpr int NS = 1;
             constexpr int kAhead = prefetch_depth(F, NS);
@@ -441,13 +446,7 @@ __global__ __launch_bounds__(kBlock) void median_kernel(
             uint32_t flags = 0;
             (void)chain_mask; (void)lane; (void)flags;
 #define BYZ_S_ROW_ADDR(j, k) (Xb + (uint64_t)(uint32_t)row_index[j] * (uint64_t)ld * 4u + voff)
-            if constexpr (F == 9) {
-#include "generated/selnet_stream_9.inc"
-            } else if constexpr (F == 25) {
-#include "generated/selnet_stream_25.inc"
-            } else {
-#include "generated/selnet_stream_49.inc"
-            }
+#include "generated/selnet_stream_dispatch.inc"
 #undef BYZ_S_ROW_ADDR
         } else {
             const uint32_t *base = X + gt * V;
@@ -534,14 +533,7 @@ __global__ __launch_bounds__(kBlock) void trimmed_mean_kernel(
     uint32_t flags = 0;
     (void)chain_mask; (void)lane; (void)flags;
 #define BYZ_S_ROW_ADDR(j, k) (Xb + (uint64_t)(uint32_t)row_index[j] * (uint64_t)ld * 4u + voff)
-    if constexpr (F == 9) {
-#include "generated/selnet_sort_stream_9.inc"
-    } else if constexpr (F == 25) {
-#include "generated/selnet_sort_stream_25.inc"
-    } else {
-        static_assert(F == 49, "no streamed sorting network generated for this f");
-#include "generated/selnet_sort_stream_49.inc"
-    }
+#include "generated/selnet_sort_stream_dispatch.inc"
 #undef BYZ_S_ROW_ADDR
     uint32_t o[V];
     trimmed_mean_of_sorted<F, V>(key, b, o);
@@ -705,22 +697,9 @@ __device__ __forceinline__ void fused_body(const uint32_t *__restrict__ X, int64
     // (or, for the trimmed mean, sorting) network whose inputs are complete by then.
 #define BYZ_S_ROW_ADDR(j, k) (Xb + perm_off[(j) * kRowStride + (k)] + voff)
     if constexpr (!TRIM) {
-        if constexpr (F == 9) {
-#include "generated/selnet_stream_9.inc"
-        } else if constexpr (F == 25) {
-#include "generated/selnet_stream_25.inc"
-        } else {
-            static_assert(F == 49, "no streamed network generated for this f");
-#include "generated/selnet_stream_49.inc"
-        }
+#include "generated/selnet_stream_dispatch.inc"
     } else {
-        if constexpr (F == 9) {
-#include "generated/selnet_sort_stream_9.inc"
-        } else if constexpr (F == 25) {
-#include "generated/selnet_sort_stream_25.inc"
-        } else {
-#include "generated/selnet_sort_stream_49.inc"
-        }
+#include "generated/selnet_sort_stream_dispatch.inc"
         trimmed_mean_of_sorted<F, V>(key, trim_b, o);
     }
 #undef BYZ_S_ROW_ADDR
@@ -841,8 +820,14 @@ int launch_trimmed_mean(const uint32_t *X, int64_t d, int64_t ld, const int32_t 
     const unsigned g = blocks_for((d + kVec - 1) / kVec);
     if (d >= kVec && f == 9)
         trimmed_mean_kernel<9, kVec><<<g, kBlock, 0, s>>>(X, d, ld, row_index, b, O, gate, gate_n);
+    else if (d >= kVec && f == 15)
+        trimmed_mean_kernel<15, kVec><<<g, kBlock, 0, s>>>(X, d, ld, row_index, b, O, gate, gate_n);
+    else if (d >= kVec && f == 21)
+        trimmed_mean_kernel<21, kVec><<<g, kBlock, 0, s>>>(X, d, ld, row_index, b, O, gate, gate_n);
     else if (d >= kVec && f == 25)
         trimmed_mean_kernel<25, kVec><<<g, kBlock, 0, s>>>(X, d, ld, row_index, b, O, gate, gate_n);
+    else if (d >= kVec && f == 35)
+        trimmed_mean_kernel<35, kVec><<<g, kBlock, 0, s>>>(X, d, ld, row_index, b, O, gate, gate_n);
     else if (d >= kVec && f == 49)
         trimmed_mean_kernel<49, kVec><<<g, kBlock, 0, s>>>(X, d, ld, row_index, b, O, gate, gate_n);
     else
@@ -852,8 +837,11 @@ int launch_trimmed_mean(const uint32_t *X, int64_t d, int64_t ld, const int32_t 
     return BYZ_OK;
 }
 
+// (f, r) with a compiled single-pass kernel: MOLS / Ramanujan Case 1 (f = l^2: 9, 25, 49) with
+// r = 3 or 5, and the Ramanujan Case 2 shapes f = m*s with r = s: (15,3), (21,3), (35,5)
 bool has_fused(int f, int r) {
-    return (f == 9 && r == 3) || ((f == 25 || f == 49) && (r == 3 || r == 5));
+    return (f == 9 && r == 3) || ((f == 25 || f == 49) && (r == 3 || r == 5)) ||
+           ((f == 15 || f == 21) && r == 3) || (f == 35 && r == 5);
 }
 
 int check_common(const void *copies, int64_t d, int64_t ld, const void *rows, int f, int r) {
@@ -967,6 +955,9 @@ extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
     // probe -> single pass -> exact path, whose two kernels return at once unless the single
     // pass recorded a violated assumption
     if (f == 9) rc = launch_fused<9, 3>(X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
+    else if (f == 15) rc = launch_fused<15, 3>(X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
+    else if (f == 21) rc = launch_fused<21, 3>(X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
+    else if (f == 35) rc = launch_fused<35, 5>(X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
     else if (f == 25 && r == 3) rc = launch_fused<25, 3>(X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
     else if (f == 25 && r == 5) rc = launch_fused<25, 5>(X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
     else if (f == 49 && r == 3) rc = launch_fused<49, 3>(X, d, ld, file_rows_dev, ws, O, early, trim_b, s);

@@ -1,7 +1,7 @@
 """The five workloads: cluster shapes of the paper's tables with seeded Gaussian gradients.
 
 scheme/a/b follow the library's byz_build_assignment arguments: MOLS (l, r) or
-Ramanujan (s, m).  `cmax` is the value the paper's Tables 3, 4, 6 print for that (graph, q).
+Ramanujan (s, m).  `cmax` is the value the paper's Tables 3, 4, 6 print for that (graph, q) where one does.
 """
 from collections import namedtuple
 
@@ -29,4 +29,8 @@ CONFIGS = [
     # beyond the five: the paper's Table 5 cluster, MOLS l=7, r=5 (245 rows), mixed attack, q = 6
     Config("cfg6_mols7x5_resnet18_mixed", MOLS, 7, 5, 35, 49, 7, 5, 6, 4, 11173962,
            {"kind": "mixed", "z": 1.0, "value": 1e3, "file_scales": True}, 1, 20101004 + 35),
+    # Ramanujan Case 2 with m > s (Sec. 4.2.1): m=7, s=5, (K,f,l,r) = (25,35,7,5), 175 rows,
+    # reversed gradient, q = 6; c_max = 6 is the exhaustive search's value (no table prints it)
+    Config("cfg7_ram5x7_resnet18_reversed", RAMANUJAN, 5, 7, 25, 35, 7, 5, 6, 6, 11173962,
+           {"kind": "reversed", "c": 100.0}, 1, 20101004 + 57),
 ]

@@ -100,6 +100,19 @@ def test_table5_cluster_shape_full_size():
     assert _full_check(w, "mols7x5") == 4
 
 
+def test_ramanujan_case2_cluster_full_size():
+    # Ramanujan m=7 > s=5 (Sec. 4.2.1, Case 2): (K,f,l,r) = (25,35,7,5), 175 rows, q = 6
+    # worst-case set, reversed gradient, at the ResNet-18 size.  No table of the paper has this
+    # cluster: c_max comes from the oracle's exhaustive search.
+    from oracle import byz_oracle as O
+    cfg = synth.CONFIGS[6]
+    w = W.from_config(cfg, DEV, ld=synth.padded_ld(cfg.d, 64))
+    assert (w.K, w.f, w.l, w.r) == (25, 35, 7, 5)
+    cmax_o, _ = C.worst_case(O.ramanujan_biadjacency(7, 5), cfg.q)
+    assert w.cmax == cmax_o == cfg.cmax
+    assert _full_check(w, cfg.name) == cmax_o
+
+
 @pytest.mark.parametrize("idx", [1, 2])
 def test_trimmed_mean_full_size(idx):
     # trimmed mean (b = c_max per side) over the vote winners at full size, fp64 oracle,

@@ -71,7 +71,9 @@ SMALL_D = [1, 2, 3, 5, 63, 64, 255, 1000, 4099, 70001]
 @pytest.mark.parametrize("scheme,a,b,q,attack", [
     (MOLS, 5, 3, 3, REVERSED), (MOLS, 5, 3, 4, ALIE), (MOLS, 7, 3, 5, REVERSED),
     (RAM, 5, 5, 6, MIXED), (MOLS, 7, 3, 6, ALIE), (RAM, 3, 3, 2, CONST), (MOLS, 7, 5, 5, MIXED),
-    (RAM, 5, 3, 3, CONST), (FRC, 15, 3, 4, REVERSED), (FRC, 25, 5, 7, MIXED)])
+    (RAM, 5, 3, 3, CONST), (FRC, 15, 3, 4, REVERSED), (FRC, 25, 5, 7, MIXED),
+    # Ramanujan Case 2 (m > s): f = m*s = 15, 21, 35
+    (RAM, 3, 5, 2, CONST), (RAM, 3, 7, 2, ALIE), (RAM, 5, 7, 6, MIXED)])
 def test_small_sizes_all_layouts(scheme, a, b, q, attack):
     # sizes below one tile, several tiles and ragged tails; row pitches that give 16-byte,
     # 8-byte and 4-byte aligned rows
@@ -101,9 +103,9 @@ def test_unaligned_base_pointer():
 
 
 def test_generic_shapes_without_a_generated_network():
-    # f = 15 (Ramanujan s=3, m=5): two-step path and rank-counting median;
+    # f = 27 (Ramanujan s=3, m=9): two-step path and rank-counting median;
     # r = 7 (Ramanujan s=7, m=7): two-step path with the f = 49 network
-    for (a, b, q) in [(3, 5, 2), (7, 7, 5)]:
+    for (a, b, q) in [(3, 9, 2), (7, 7, 5)]:
         w = W.make(RAM, a, b, q, 2222, CONST, seed=3, device=DEV)
         _check_all(w.X, w.file_rows, w.d, w.f, w.r, expect_exact=True)
     # byz_median alone for assorted odd f, including rows used more than once
