@@ -10,6 +10,9 @@ replication r (odd), r' = (r+1)/2, load l = f*r/K, d coordinates.
 
 Parity status of each function (what pins it, see tests/test_oracle_*.py):
   latin_square, mols_biadjacency      Table 1, Example 1, Table 2 cell by cell
+  finite_field (prime-power l)        field axioms by brute force, textbook products in
+                                      GF(4), GF(8), GF(9); Definition 2 (orthogonality) cell by cell;
+                                      numbering of the elements: paper silent, "parity unpinned"
   ramanujan_biadjacency               Eq. 6 degrees, Lemma 2 spectrum, Table 4
   frc_biadjacency                     Sec. 5.3.1: floor(q/r') lost groups, FRC column of Tables 3-6
   worst_case                          Tables 3-6, Claim 2, naive brute force
@@ -46,13 +49,74 @@ def is_prime(n):
     return True
 
 
+def prime_power(l):
+    """(p, k) with l = p**k and p prime, or None."""
+    l = int(l)
+    for p in range(2, l + 1):
+        if is_prime(p) and l % p == 0:
+            k, t = 0, l
+            while t % p == 0:
+                t //= p
+                k += 1
+            return (p, k) if t == 1 else None
+    return None
+
+
+def finite_field(l):
+    """Addition and multiplication tables (l x l) of F_l for a prime power l = p**k.
+
+    The paper (Sec. 4.1.1) takes R = C = S = F_l = {0, .., l-1} without saying which integer is
+    which field element when k > 1.  Reading used here: integer n stands for the polynomial
+    whose coefficients are the base-p digits of n (lowest digit = constant term); products are
+    reduced modulo the monic degree-k polynomial x^k + c(x) with the smallest integer c for
+    which the result is a field.  For k = 1 this is arithmetic modulo p.
+
+    Written from the definition: schoolbook polynomial product, the substitution
+    x^k -> -c(x) applied from the top degree down, and "field" tested as "no two nonzero
+    elements multiply to zero".
+    """
+    pk = prime_power(l)
+    assert pk is not None, "l must be a prime power"
+    p, k = pk
+
+    def digits(n):
+        return [(n // p ** t) % p for t in range(k)]
+
+    def number(coeffs):
+        return sum(int(c) * p ** t for t, c in enumerate(coeffs))
+
+    add = np.zeros((l, l), dtype=np.int64)
+    for a in range(l):
+        for b in range(l):
+            add[a, b] = number([(x + y) % p for x, y in zip(digits(a), digits(b))])
+    for c in range(l):
+        low = digits(c)
+        mul = np.zeros((l, l), dtype=np.int64)
+        for a in range(l):
+            for b in range(l):
+                prod = [0] * (2 * k - 1)
+                for i, x in enumerate(digits(a)):
+                    for j, y in enumerate(digits(b)):
+                        prod[i + j] = (prod[i + j] + x * y) % p
+                for t in range(2 * k - 2, k - 1, -1):  # x^t = x^(t-k) * x^k = -x^(t-k) * c(x)
+                    top, prod[t] = prod[t], 0
+                    for j in range(k):
+                        prod[t - k + j] = (prod[t - k + j] - top * low[j]) % p
+                mul[a, b] = number(prod[:k])
+        if (mul[1:, 1:] != 0).all():
+            return add, mul
+    raise AssertionError("no irreducible polynomial found")
+
+
 def latin_square(l, alpha):
-    """Sec. 4.1.1: the square L_alpha(i, j) = alpha*i + j over F_l (l prime, alpha != 0)."""
-    assert is_prime(l) and alpha % l != 0
+    """Sec. 4.1.1: the square L_alpha(i, j) = alpha*i + j over F_l (l a prime power, alpha a
+    nonzero element; elements numbered as in finite_field)."""
+    assert 0 < alpha < l
+    add, mul = finite_field(l)
     L = np.zeros((l, l), dtype=np.int64)
     for i in range(l):
         for j in range(l):
-            L[i, j] = (alpha * i + j) % l
+            L[i, j] = add[mul[alpha, i], j]
     return L
 
 

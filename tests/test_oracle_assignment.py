@@ -14,7 +14,7 @@ def test_table1_squares_cell_by_cell():
         assert O.latin_square(5, alpha).tolist() == cells
 
 
-@pytest.mark.parametrize("l", [3, 5, 7, 11])
+@pytest.mark.parametrize("l", [3, 4, 5, 7, 8, 9, 11, 16])
 def test_squares_are_latin_and_mutually_orthogonal(l):
     # Definitions 1 and 2 (Sec. 4.1.1)
     squares = [O.latin_square(l, a) for a in range(1, l)]
@@ -25,6 +25,52 @@ def test_squares_are_latin_and_mutually_orthogonal(l):
     for L1, L2 in itertools.combinations(squares, 2):
         pairs = {(int(L1[i, j]), int(L2[i, j])) for i in range(l) for j in range(l)}
         assert len(pairs) == l * l
+
+
+@pytest.mark.parametrize("l", [2, 3, 4, 5, 7, 8, 9, 16, 25, 27])
+def test_finite_field_axioms(l):
+    # F_l of Sec. 4.1.1 for prime powers: commutative ring with 0 and 1 in which every nonzero
+    # element has an inverse, of characteristic p
+    add, mul = O.finite_field(l)
+    p, k = O.prime_power(l)
+    E = range(l)
+    assert (add == add.T).all() and (mul == mul.T).all()
+    assert (add[0] == np.arange(l)).all() and (mul[1] == np.arange(l)).all() and (mul[0] == 0).all()
+    for a in E:
+        assert sorted(add[a].tolist()) == list(E)          # a + . is a bijection
+        if a:
+            assert sorted(mul[a].tolist()) == list(E)      # a * . is a bijection (inverse exists)
+        x = 0
+        for _ in range(p):
+            x = add[x, a]
+        assert x == 0                                      # characteristic p
+    rng = np.random.default_rng(l)
+    for a, b, c in rng.integers(0, l, size=(300, 3)):
+        assert add[add[a, b], c] == add[a, add[b, c]]
+        assert mul[mul[a, b], c] == mul[a, mul[b, c]]
+        assert mul[a, add[b, c]] == add[mul[a, b], mul[a, c]]
+    if k == 1:
+        assert all(add[a, b] == (a + b) % l and mul[a, b] == (a * b) % l for a in E for b in E)
+
+
+def test_finite_field_textbook_products():
+    # GF(4) = F_2[x]/(x^2+x+1), elements 0, 1, x=2, x+1=3: x*x = x+1, x*(x+1) = 1, (x+1)^2 = x
+    _, m4 = O.finite_field(4)
+    assert (m4[2, 2], m4[2, 3], m4[3, 3]) == (3, 1, 2)
+    # GF(8) = F_2[x]/(x^3+x+1) (x^3+x+1 = 1011b is below x^3+x^2+1 = 1101b): x^3 = x+1,
+    # x^4 = x^2+x, x^7 = 1
+    a8, m8 = O.finite_field(8)
+    assert m8[2, 4] == 3 and m8[4, 4] == 6
+    x = 1
+    for _ in range(7):
+        x = m8[x, 2]
+    assert x == 1
+    # GF(9) = F_3[i]/(i^2+1): i = 3, i*i = -1 = 2, (1+i)^2 = 2i = 6
+    _, m9 = O.finite_field(9)
+    assert m9[3, 3] == 2 and m9[4, 4] == 6
+    # not prime powers
+    for l in (6, 10, 12, 15):
+        assert O.prime_power(l) is None
 
 
 def test_example1_worker0():
@@ -45,7 +91,8 @@ def test_table2_full_allocation():
         assert wf[w].tolist() == files
 
 
-@pytest.mark.parametrize("l,r", [(5, 3), (7, 3), (7, 5), (5, 4), (11, 3)])
+@pytest.mark.parametrize("l,r", [(5, 3), (7, 3), (7, 5), (5, 4), (11, 3), (4, 3), (8, 5), (9, 3),
+                                 (9, 7)])
 def test_mols_structure(l, r):
     H = O.mols_biadjacency(l, r)
     K, f, ll, rr = O.dims(H)
@@ -71,7 +118,7 @@ def _spectrum(H):
     return np.sort(np.linalg.eigvalsh(A @ A.T))[::-1], (K, f, l, r)
 
 
-@pytest.mark.parametrize("l,r", [(5, 3), (7, 3), (7, 5)])
+@pytest.mark.parametrize("l,r", [(5, 3), (7, 3), (7, 5), (4, 3), (8, 3), (9, 5)])
 def test_lemma2_spectrum_mols(l, r):
     # Lemma 2: {(1,1), (1/r, r(l-1)), (0, r-1)}
     ev, _ = _spectrum(O.mols_biadjacency(l, r))
