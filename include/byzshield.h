@@ -40,14 +40,14 @@ extern "C" {
 typedef enum byz_status {
     BYZ_OK = 0,
     BYZ_EINVAL = -1,       /* null pointer, size out of range, even r, q outside [0,K], ...      */
-    BYZ_EUNSUPPORTED = -2, /* valid in the paper but not built: prime-power l, even f, f > 64 ... */
+    BYZ_EUNSUPPORTED = -2, /* valid in the paper but not built: even f, f > 64, l > 255 ...         */
     BYZ_ENOMEM = -3,       /* host allocation failed, or the workspace is too small               */
     BYZ_EDEVICE = -4,      /* a HIP call failed; see byz_last_hip_error()                          */
     BYZ_EINTERNAL = -5     /* an assignment invariant did not hold (a bug)                         */
 } byz_status;
 
 typedef enum byz_scheme {
-    BYZ_SCHEME_MOLS = 0,     /* Algorithm 2: a = l (prime), b = r <= l-1; K = r*l, f = l*l            */
+    BYZ_SCHEME_MOLS = 0,     /* Algorithm 2: a = l (prime power), b = r <= l-1; K = r*l, f = l*l      */
     BYZ_SCHEME_RAMANUJAN = 1, /* Sec. 4.2.1: a = s (prime), b = m >= 2; Case 1 (m < s) or 2 (m >= s) */
     BYZ_SCHEME_FRC = 2       /* Sec. 5.3.1 (DETOX / DRACO): a = K, b = r | K; f = K/r, l = 1           */
 } byz_scheme;
@@ -63,7 +63,12 @@ typedef struct byz_assignment byz_assignment;
 /*
  * Builds the biregular worker-file graph.
  *   BYZ_SCHEME_MOLS (Sec. 4.1, Algorithm 2): file i*l+j goes, for k = 0..r-1, to worker
- *     U_{k*l+s} with s = L_{k+1}(i,j) = (k+1)*i + j mod l.  Needs l prime, 1 <= r <= l-1.
+ *     U_{k*l+s} with s = L_{k+1}(i,j) = (k+1)*i + j in F_l.  Needs l a prime power <= 255,
+ *     1 <= r <= l-1.  For l = p^k with k > 1 (the paper does not number the field's elements)
+ *     integer n stands for the polynomial over F_p whose coefficients are the base-p digits
+ *     of n, lowest digit = constant term, and products are taken modulo the monic irreducible
+ *     polynomial of degree k with the smallest number (GF(4): x^2+x+1, GF(8): x^3+x+1,
+ *     GF(9): x^2+1); for prime l this is arithmetic modulo l.
  *   BYZ_SCHEME_RAMANUJAN (Sec. 4.2.1, Eq. 6): H = B (m >= s) or B^T (m < s), B the s x m
  *     block matrix of powers P^(a*b) of the cyclic shift P.  Needs s prime, m >= 2.
  *   BYZ_SCHEME_FRC (Sec. 5.3.1, the Fractional Repetition Code the paper compares with):
@@ -73,8 +78,8 @@ typedef struct byz_assignment byz_assignment;
  * files, every file sits on r workers, each parallel class holds each file once, two workers
  * share at most one file ...) and returns BYZ_EINTERNAL if any fails.
  * *out receives the graph (free with byz_free_assignment).  Errors: BYZ_EINVAL (null out,
- * a < 2, r outside its range, unknown scheme), BYZ_EUNSUPPORTED (a not prime: prime powers
- * need GF(p^k) arithmetic that is not built), BYZ_ENOMEM.
+ * a < 2 or > 255, r outside its range, unknown scheme), BYZ_EUNSUPPORTED (l not a prime power,
+ * s not prime), BYZ_ENOMEM.
  */
 int byz_build_assignment(int scheme, int a, int b, byz_assignment **out);
 

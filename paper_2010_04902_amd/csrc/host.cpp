@@ -36,19 +36,98 @@ inline int mod(int64_t x, int m) {
     return (int)(t < 0 ? t + m : t);
 }
 
+// F_q for a prime power q = p^k <= 255 (Sec. 4.1.1 takes row, column and symbol sets to be
+// F_l).  Element n is the polynomial whose coefficients are the base-p digits of n, lowest
+// digit = constant term; products are reduced modulo the monic irreducible polynomial of degree
+// k with the smallest number.  For k = 1 this is arithmetic modulo p.
+struct Field {
+    int q = 0, p = 0, k = 0;
+    std::vector<uint8_t> add_tab, mul_tab;  // [q][q]
+    int add(int a, int b) const { return add_tab[(size_t)a * q + b]; }
+    int mul(int a, int b) const { return mul_tab[(size_t)a * q + b]; }
+};
+
+// Remainder of polynomial num (degree < n_num) by monic polynomial den of degree deg, over F_p.
+// Coefficient vectors, lowest degree first; den has deg + 1 entries with den[deg] == 1.
+void poly_rem(std::vector<int> &num, const std::vector<int> &den, int deg, int p) {
+    for (int t = (int)num.size() - 1; t >= deg; --t) {
+        const int c = num[t];
+        if (c == 0) continue;
+        for (int j = 0; j <= deg; ++j) num[t - deg + j] = mod((int64_t)num[t - deg + j] - (int64_t)c * den[j], p);
+    }
+    num.resize((size_t)deg);
+}
+
+bool make_field(int q, Field &F) {
+    int p = 0;
+    for (int c = 2; c <= q; ++c)
+        if (q % c == 0) { p = c; break; }  // smallest divisor > 1 is prime
+    if (p == 0) return false;
+    int k = 0, t = q;
+    while (t % p == 0) { t /= p; ++k; }
+    if (t != 1) return false;
+    F.q = q; F.p = p; F.k = k;
+    auto digits = [&](int n, int len) {
+        std::vector<int> c((size_t)len, 0);
+        for (int i = 0; i < len && n > 0; ++i) { c[i] = n % p; n /= p; }
+        return c;
+    };
+    auto number = [&](const std::vector<int> &c) {
+        int n = 0;
+        for (int i = (int)c.size() - 1; i >= 0; --i) n = n * p + c[i];
+        return n;
+    };
+    // modulus x^k + (digits of low): the first one with no monic divisor of degree 1..k/2
+    std::vector<int> modulus;
+    for (int low = 0; low < q && modulus.empty(); ++low) {
+        std::vector<int> cand = digits(low, k);
+        cand.push_back(1);
+        bool irreducible = true;
+        int count = p;  // monic polynomials of degree deg: p^deg
+        for (int deg = 1; deg <= k / 2 && irreducible; ++deg, count *= p)
+            for (int n = 0; n < count && irreducible; ++n) {
+                std::vector<int> den = digits(n, deg);
+                den.push_back(1);
+                std::vector<int> rem = cand;
+                poly_rem(rem, den, deg, p);
+                bool zero = true;
+                for (int c : rem) zero = zero && c == 0;
+                if (zero) irreducible = false;
+            }
+        if (irreducible) modulus = cand;
+    }
+    if (modulus.empty()) return false;
+    F.add_tab.assign((size_t)q * q, 0);
+    F.mul_tab.assign((size_t)q * q, 0);
+    for (int a = 0; a < q; ++a) {
+        const std::vector<int> ca = digits(a, k);
+        for (int b = 0; b < q; ++b) {
+            const std::vector<int> cb = digits(b, k);
+            std::vector<int> sum((size_t)k), prod((size_t)(2 * k - 1), 0);
+            for (int i = 0; i < k; ++i) sum[i] = (ca[i] + cb[i]) % p;
+            for (int i = 0; i < k; ++i)
+                for (int j = 0; j < k; ++j) prod[i + j] = (prod[i + j] + ca[i] * cb[j]) % p;
+            poly_rem(prod, modulus, k, p);
+            F.add_tab[(size_t)a * q + b] = (uint8_t)number(sum);
+            F.mul_tab[(size_t)a * q + b] = (uint8_t)number(prod);
+        }
+    }
+    return true;
+}
+
 // Fills per-class "which worker of class k holds file j".  All three constructions are lines
-// of the affine plane over F_p: file (x, y) belongs to the class-k worker whose index inside
-// the class is the value of a linear form in (x, y).
-//   MOLS, Algorithm 2: file i*l+j, class k (square L_{k+1}) -> symbol (k+1)*i + j.
+// of the affine plane over F_p (F_l for MOLS): file (x, y) belongs to the class-k worker whose
+// index inside the class is the value of a linear form in (x, y).
+//   MOLS, Algorithm 2: file i*l+j, class k (square L_{k+1}) -> symbol (k+1)*i + j in F_l.
 //   Ramanujan Case 2 (H = B): worker a*s+u holds file b*s+v iff v = u - a*b, so file (b, v)
 //     is held in class a by u = v + a*b.
 //   Ramanujan Case 1 (H = B^T): worker b*s+v holds file a*s+u iff u = v + a*b, so file
 //     (a, u) is held in class b by v = u - a*b.
 //   FRC (the comparison assignment of Sec. 5.3.1) has no grid: class k is the k-th member of
 //     every group and holds file y on its y-th worker.
-int holder_in_class(int scheme, bool case2, int p, int k, int x, int y) {
+int holder_in_class(int scheme, bool case2, int p, const Field &F, int k, int x, int y) {
     if (scheme == BYZ_SCHEME_FRC) return y;  // replica k of file y sits on worker k*f + y
-    if (scheme == BYZ_SCHEME_MOLS) return mod((int64_t)(k + 1) * x + y, p);
+    if (scheme == BYZ_SCHEME_MOLS) return F.add(F.mul(k + 1, x), y);
     if (case2) return mod((int64_t)y + (int64_t)k * x, p);
     return mod((int64_t)y - (int64_t)k * x, p);
 }
@@ -105,6 +184,7 @@ extern "C" int byz_build_assignment(int scheme, int a, int b, byz_assignment **o
     int K, f, l, r, classes, class_size, gx, gy;  // files form a gx x gy grid, index x*gy + y
     bool case2 = false;
     int shared_lo = 1, shared_hi = 1;
+    Field field;
     if (scheme == BYZ_SCHEME_FRC) {
         // Sec. 5.3.1: K/r groups of r workers, every worker of a group holds the group's file
         if (b < 1 || b > a || a % b != 0) return BYZ_EINVAL;
@@ -112,7 +192,7 @@ extern "C" int byz_build_assignment(int scheme, int a, int b, byz_assignment **o
         shared_lo = 0;  // two workers share their file iff they are in the same group
     } else if (scheme == BYZ_SCHEME_MOLS) {
         if (b < 1 || b > a - 1) return BYZ_EINVAL;  // Algorithm 2 needs r <= l-1
-        if (!is_prime(a)) return BYZ_EUNSUPPORTED;
+        if (!make_field(a, field)) return BYZ_EUNSUPPORTED;  // l must be a prime power
         l = a; r = b; K = r * l; f = l * l; classes = r; class_size = l; gx = l; gy = l;
     } else {
         const int s = a, m = b;
@@ -145,7 +225,7 @@ extern "C" int byz_build_assignment(int scheme, int a, int b, byz_assignment **o
             for (int y = 0; y < gy; ++y) {
                 const int j = x * gy + y;
                 for (int k = 0; k < classes; ++k) {
-                    const int w = k * class_size + holder_in_class(scheme, case2, a, k, x, y);
+                    const int w = k * class_size + holder_in_class(scheme, case2, a, field, k, x, y);
                     if (fill[w] >= l) { delete g; return BYZ_EINTERNAL; }
                     g->worker_files[(size_t)w * l + fill[w]] = j;
                     g->file_workers[(size_t)j * r + k] = w;

@@ -52,7 +52,11 @@ def test_table2_through_the_library():
 @pytest.mark.parametrize("scheme,a,b", [("mols", 5, 3), ("mols", 7, 3), ("mols", 7, 5),
                                         ("mols", 11, 3), ("mols", 3, 1), ("mols", 5, 4),
                                         ("ram", 5, 5), ("ram", 5, 3), ("ram", 7, 3), ("ram", 5, 10),
-                                        ("ram", 3, 3), ("ram", 3, 2), ("ram", 5, 7), ("ram", 2, 2)])
+                                        ("ram", 3, 3), ("ram", 3, 2), ("ram", 5, 7), ("ram", 2, 2),
+                                        # prime-power l: F_4, F_8, F_9, F_16, F_25, F_27
+                                        ("mols", 4, 3), ("mols", 8, 7), ("mols", 9, 3),
+                                        ("mols", 9, 8), ("mols", 16, 3), ("mols", 25, 3),
+                                        ("mols", 27, 2)])
 def test_assignment_equals_oracle_construction(scheme, a, b):
     asg = _build(scheme, a, b)
     Ho = O.mols_biadjacency(a, b) if scheme == "mols" else O.ramanujan_biadjacency(b, a)
@@ -70,9 +74,9 @@ def test_build_errors():
         return e.value.code
     assert code(B.BYZ_SCHEME_MOLS, 5, 5) == -1        # Algorithm 2 needs r <= l-1
     assert code(B.BYZ_SCHEME_MOLS, 5, 0) == -1
-    assert code(B.BYZ_SCHEME_MOLS, 4, 3) == -2        # prime power: GF(4) not built
-    assert code(B.BYZ_SCHEME_MOLS, 9, 3) == -2
-    assert code(B.BYZ_SCHEME_MOLS, 6, 3) == -2
+    assert code(B.BYZ_SCHEME_MOLS, 6, 3) == -2        # l must be a prime power
+    assert code(B.BYZ_SCHEME_MOLS, 12, 3) == -2
+    assert code(B.BYZ_SCHEME_MOLS, 256, 3) == -1
     assert code(B.BYZ_SCHEME_RAMANUJAN, 4, 3) == -2   # s must be prime
     assert code(B.BYZ_SCHEME_RAMANUJAN, 5, 1) == -1   # m >= 2
     assert code(7, 5, 3) == -1
