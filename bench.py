@@ -46,7 +46,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, help="workload 1..7 (default 2, the headline)")
+    ap.add_argument("--config", type=int, default=2, help="workload 1..8 (default 2, the headline)")
     ap.add_argument("--unpadded", action="store_true", help="row pitch ld = d instead of d rounded up to 64")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-early", action="store_true", help="skip the early-majority leg")
@@ -120,9 +120,16 @@ def main():
         assert torch.equal(src[-1024:], dst[-1024:])
         del src, dst
 
+    single_pass = B.byz_aggregate_has_single_pass(asg.f, asg.r)
     ms_per_step, kernel_ms, exact = timed(0)
     coords_per_s = d / (ms_per_step * 1e-3)
-    alg_bytes = 4.0 * (asg.r * asg.f + 1) * d  # every copy read once, one value written
+    if single_pass:
+        alg_bytes = 4.0 * (asg.r * asg.f + 1) * d  # every copy read once, one value written
+        kernel_bytes, kernel_name = alg_bytes, "fused_kernel<%d,%d,4>" % (asg.f, asg.r)
+    else:
+        # vote kernel, then median kernel over the winners: the winners are read twice
+        alg_bytes = 4.0 * ((asg.r + 1) * asg.f + 1) * d
+        kernel_bytes, kernel_name = 4.0 * asg.r * asg.f * d, "vote_pairs_kernel<%d,4>" % asg.r
     result = {
         "metric": "aggregated coords/sec (vote+median)",
         "value": coords_per_s,
@@ -144,20 +151,20 @@ def main():
     }
     if kernel_ms:
         avg_ms = sum(kernel_ms) / len(kernel_ms)
-        achieved = alg_bytes / (avg_ms * 1e-3) / 1e9
+        achieved = kernel_bytes / (avg_ms * 1e-3) / 1e9
         result["roofline"] = {
-            "bound": "hbm", "kernel": "fused_kernel<%d,%d,4>" % (asg.f, asg.r),
+            "bound": "hbm", "kernel": kernel_name,
             "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBPS,
-            "traffic": _traffic_from_profiles(cfg.name),
-            "algorithmic_bytes_per_launch": alg_bytes,
+            "traffic": _traffic_from_profiles(cfg.name) if single_pass else None,
+            "algorithmic_bytes_per_launch": kernel_bytes,
             "avg_kernel_ms": avg_ms, "min_kernel_ms": min(kernel_ms), "launches_timed": len(kernel_ms),
         }
 
     # Same result with fewer bytes: r' identical copies already are the majority, so the
     # other r - r' copies of a file need not be read (BYZ_AGG_EARLY_MAJORITY).  Reported
     # beside the headline, never as `value`.
-    if not args.no_early:
+    if not args.no_early and single_pass:
         rp = (asg.r + 1) // 2
         e_ms, e_kernel_ms, e_exact = timed(B.BYZ_AGG_EARLY_MAJORITY)
         e_bytes = 4.0 * (rp * asg.f + 1) * d
@@ -192,9 +199,11 @@ def main():
         ms_tm = timed_call(lambda: B.byz_trimmed_mean(bufs[0], d, wrow_v, cmax, out=out, stream=stream))
         ms_agg_tm = timed_call(lambda: step(0, B.BYZ_AGG_TRIM(cmax)))
         mk_m = asg.f - cmax
-        mk_ws = torch.empty(B.byz_multi_krum_workspace_bytes(asg.f), dtype=torch.uint8, device=dev)
-        ms_mk = timed_call(lambda: B.byz_multi_krum(bufs[0], d, wrow_v, cmax, mk_m, out=out,
-                                                    workspace=mk_ws, stream=stream))
+        ms_mk = None
+        if asg.f <= B.BYZ_MAX_F:
+            mk_ws = torch.empty(B.byz_multi_krum_workspace_bytes(asg.f), dtype=torch.uint8, device=dev)
+            ms_mk = timed_call(lambda: B.byz_multi_krum(bufs[0], d, wrow_v, cmax, mk_m, out=out,
+                                                        workspace=mk_ws, stream=stream))
         kb = 4.0 * asg.f * d + 4.0 * (mk_m + 1) * d  # Gram pass over f rows + mean of m rows
         vb, mb = 4.0 * asg.r * asg.f * d, 4.0 * (asg.f + 1) * d
         result["components"] = {
@@ -206,11 +215,12 @@ def main():
             "byz_aggregate_trimmed_mean": {"ms": ms_agg_tm, "b": cmax, "algorithmic_bytes": alg_bytes,
                                            "gbps": alg_bytes / ms_agg_tm / 1e6,
                                            "frac": alg_bytes / ms_agg_tm / 1e6 / HBM_PEAK_GBPS,
-                                           "note": "whole path with the trimmed mean in the single pass"},
-            "byz_multi_krum": {"ms": ms_mk, "c": cmax, "m": mk_m, "algorithmic_bytes": kb,
-                               "gbps": kb / ms_mk / 1e6, "frac": kb / ms_mk / 1e6 / HBM_PEAK_GBPS,
-                               "gram_tflops": 2.0 * asg.f * asg.f * d / ms_mk / 1e9,
-                               "note": "Gram (fp32 MFMA) + reduce + select + mean of m rows"},
+                                           "note": "whole path with the trimmed mean instead of the median"},
+            "byz_multi_krum": None if ms_mk is None else {
+                "ms": ms_mk, "c": cmax, "m": mk_m, "algorithmic_bytes": kb,
+                "gbps": kb / ms_mk / 1e6, "frac": kb / ms_mk / 1e6 / HBM_PEAK_GBPS,
+                "gram_tflops": 2.0 * asg.f * asg.f * d / ms_mk / 1e9,
+                "note": "Gram (fp32 MFMA) + reduce + select + mean of m rows"},
             "byz_trimmed_mean": {"ms": ms_tm, "b": cmax, "algorithmic_bytes": mb,
                                  "gbps": mb / ms_tm / 1e6, "frac": mb / ms_tm / 1e6 / HBM_PEAK_GBPS},
         }

@@ -52,7 +52,8 @@ typedef enum byz_scheme {
     BYZ_SCHEME_FRC = 2       /* Sec. 5.3.1 (DETOX / DRACO): a = K, b = r | K; f = K/r, l = 1           */
 } byz_scheme;
 
-#define BYZ_MAX_F 64 /* largest number of files the device entry points and the search take */
+#define BYZ_MAX_F 64       /* largest f of the register-network kernels, the trimmed mean and Multi-Krum */
+#define BYZ_MAX_F_WIDE 256 /* largest f of byz_vote, byz_median, byz_aggregate and the search            */
 #define BYZ_MAX_R 7  /* largest replication factor                                           */
 
 /* Opaque worker-file assignment graph G (Sec. 2): host memory owned by the library. */
@@ -108,8 +109,9 @@ int byz_assignment_file_rows(const byz_assignment *g, int32_t *out);
  * Among maximisers the lexicographically first ascending tuple is returned.
  *   byz_workers_out   host [q], ascending (may be NULL)
  *   cmax_out          host, c_max^(q) (may be NULL)
- *   distorted_mask_out host, bit j set iff file j is distorted by the returned set (may be NULL)
- * Errors: BYZ_EINVAL (null g, q < 0, q > K), BYZ_EUNSUPPORTED (f > 64).
+ *   distorted_mask_out host [ceil(f/64)] words, bit j%64 of word j/64 set iff file j is
+ *                     distorted by the returned set (may be NULL)
+ * Errors: BYZ_EINVAL (null g, q < 0, q > K), BYZ_EUNSUPPORTED (f > BYZ_MAX_F_WIDE).
  * Cost grows as C(K, q) (about 2*10^8 subsets per second and core); searches above 2*10^7
  * subsets use up to 16 host threads.  Not interruptible.
  */
@@ -132,8 +134,8 @@ double byz_gamma_bound(const byz_assignment *g, int q);
  *   winner_row    device [f] int32 out: file_rows[j][winner_replica[j]]
  *   pair_neq      device [f] uint32 out: bit p set iff the two copies of pair p differ,
  *                 pairs (a,b), a < b, numbered lexicographically (0,1),(0,2),..,(1,2),..
- * Errors: BYZ_EINVAL (null pointers, d < 0, ld < d, f outside [1,64], r even or outside
- * [3,7]), BYZ_EDEVICE.  Row indices are trusted (not range-checked on the device).
+ * Errors: BYZ_EINVAL (null pointers, d < 0, ld < d, f outside [1,BYZ_MAX_F_WIDE], r even or
+ * outside [3,7]), BYZ_EDEVICE.  Row indices are trusted (not range-checked on the device).
  * d == 0: every copy is equal (winner 0, pair_neq 0).
  */
 int byz_vote(const float *copies, int64_t d, int64_t ld, const int32_t *file_rows_dev, int f,
@@ -146,9 +148,10 @@ int byz_vote(const float *copies, int64_t d, int64_t ld, const int32_t *file_row
  * out[c] = element of rank (f-1)/2 of { rows_base[row_index[j]*ld + c] : j < f }.
  *   rows_base     device [*][ld] fp32;  row_index_dev device [f] int32;  out device [d] fp32,
  *                 must not overlap the input rows (may be NULL when d == 0).
- * f odd, 1 <= f <= 64; f in {3,5,7,9,15,21,25,35,49} (the paper's file and
- * worker counts) runs a register selection network, other odd f
- * a slower generic kernel.  Errors: BYZ_EINVAL, BYZ_EUNSUPPORTED (even f), BYZ_EDEVICE.
+ * f odd, 1 <= f <= BYZ_MAX_F_WIDE; f in {3,5,7,9,15,21,25,35,49} (the paper's file and
+ * worker counts) runs a register selection network, other odd f <= 64 a slower generic kernel,
+ * 64 < f a kernel that keeps the f keys of a coordinate in LDS and finds the median by
+ * bisection on the key (32 counting passes; about 2-3x off the HBM bound).  Errors: BYZ_EINVAL, BYZ_EUNSUPPORTED (even f), BYZ_EDEVICE.
  */
 int byz_median(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev,
                int f, float *out, void *stream);
@@ -164,7 +167,7 @@ int byz_median(const float *rows_base, int64_t d, int64_t ld, const int32_t *row
  * is: fp32, kept values added one by one in ascending order starting from +0, then one IEEE
  * division by float(f - 2b).
  *   f in {9,15,21,25,35,49} runs a register sorting network, other f <= 64 a slower generic
- *   kernel.
+ *   kernel, 64 < f <= BYZ_MAX_F_WIDE an insertion sort of the coordinate's keys in LDS.
  * Errors: BYZ_EINVAL (null pointers, sizes, b < 0 or 2b >= f), BYZ_EDEVICE.
  */
 int byz_trimmed_mean(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev,
@@ -239,6 +242,11 @@ int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld, const int32_t
                        int f, int r, float *out, int32_t *winner_replica, void *workspace,
                        size_t workspace_bytes, unsigned flags, void *stream);
 
+/* 1 if byz_aggregate runs (f, r) as the single pass described above, 0 if it runs byz_vote's and
+ * byz_median's kernels one after the other (shapes without a compiled single-pass kernel, or
+ * invalid (f, r)). */
+int byz_aggregate_has_single_pass(int f, int r);
+
 /*
  * After byz_aggregate's work on `stream` has completed: copies 0/1 into *took_exact_path
  * (host) from the workspace (device) -- 1 if the two-step path had to run.  Synchronises the
@@ -250,9 +258,10 @@ int byz_aggregate_took_exact_path(const void *workspace, int *took_exact_path, v
 
 /*
  * Timing aid for benchmarks.  byz_profile_enable(n) with n > 0 creates n HIP event pairs for
- * the calling thread; from then on each byz_aggregate call of that thread that runs the
- * single-pass kernel records one pair around that kernel (its main launch, not the probe or
- * the finalisation) on the call's stream, until n calls have been recorded.
+ * the calling thread; from then on each byz_aggregate call of that thread records one pair
+ * around its dominant kernel -- the single-pass kernel (its main launch, not the probe or the
+ * finalisation), or the vote kernel for shapes without one -- on the call's stream, until n
+ * calls have been recorded.
  * byz_profile_enable(0) releases the events.  Errors: BYZ_EINVAL (n < 0 or n > 100000),
  * BYZ_ENOMEM, BYZ_EDEVICE.
  * byz_profile_collect waits for the recorded events, writes the kernel durations in

@@ -10,9 +10,12 @@ from .binding import (  # noqa: F401
     BYZ_SCHEME_FRC,
     BYZ_SCHEME_MOLS,
     BYZ_SCHEME_RAMANUJAN,
+    BYZ_MAX_F,
+    BYZ_MAX_F_WIDE,
     Assignment,
     ByzError,
     byz_aggregate,
+    byz_aggregate_has_single_pass,
     byz_aggregate_opts,
     byz_aggregate_took_exact_path,
     byz_aggregate_workspace_bytes,

@@ -16,6 +16,7 @@ BYZ_SCHEME_MOLS = 0
 BYZ_SCHEME_RAMANUJAN = 1
 BYZ_SCHEME_FRC = 2
 BYZ_MAX_F = 64
+BYZ_MAX_F_WIDE = 256
 BYZ_MAX_R = 7
 
 _lib = None
@@ -62,6 +63,7 @@ def _load():
         "byz_multi_krum_workspace_bytes": (sz, [c_int]),
         "byz_multi_krum": (c_int, [vp, i64, i64, vp, c_int, c_int, c_int, vp, vp, vp, vp, vp, sz, vp]),
         "byz_aggregate_workspace_bytes": (sz, [c_int, c_int]),
+        "byz_aggregate_has_single_pass": (c_int, [c_int, c_int]),
         "byz_aggregate": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, sz, vp]),
         "byz_aggregate_opts": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, sz,
                                        ctypes.c_uint, vp]),
@@ -129,10 +131,13 @@ def byz_worst_case(asg, q):
     """Returns (byzantine workers as a tuple, c_max, distorted-file bit mask)."""
     S = np.zeros(max(int(q), 1), dtype=np.int32)
     cmax = ctypes.c_int32()
-    mask = ctypes.c_uint64()
+    words = np.zeros(max((asg.f + 63) // 64, 1), dtype=np.uint64)
     _check(_load().byz_worst_case(asg._h, int(q), S.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
-                                  ctypes.byref(cmax), ctypes.byref(mask)), "byz_worst_case")
-    return tuple(int(x) for x in S[:max(int(q), 0)]), int(cmax.value), int(mask.value)
+                                  ctypes.byref(cmax),
+                                  words.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64))),
+           "byz_worst_case")
+    mask = sum(int(w) << (64 * i) for i, w in enumerate(words))
+    return tuple(int(x) for x in S[:max(int(q), 0)]), int(cmax.value), mask
 
 
 def byz_gamma_bound(asg, q):
@@ -163,6 +168,12 @@ def _dev_ptr(t, dtype_names, what):
     return ctypes.c_void_p(t.data_ptr())
 
 
+def _need(t, n, what):
+    """The C side trusts pointer/size pairs: refuse a tensor shorter than the call will read."""
+    if n > 0 and int(t.numel()) < n:
+        raise ValueError("%s has %d elements, the call needs %d" % (what, int(t.numel()), n))
+
+
 def _rows_2d(copies):
     if copies.dim() != 2:
         raise ValueError("copies must be [rows, ld]")
@@ -173,9 +184,10 @@ def byz_vote(copies, d, file_rows_dev, f, r, stream=None):
     """-> (winner_replica[f] int32, winner_row[f] int32, pair_neq[f] int32 bit masks), on device."""
     torch = _torch()
     ld = _rows_2d(copies)
-    wrep = torch.empty(f, dtype=torch.int32, device=copies.device)
-    wrow = torch.empty(f, dtype=torch.int32, device=copies.device)
-    neq = torch.empty(f, dtype=torch.int32, device=copies.device)
+    _need(file_rows_dev, int(f) * int(r), "file_rows_dev")
+    wrep = torch.empty(max(int(f), 0), dtype=torch.int32, device=copies.device)
+    wrow = torch.empty(max(int(f), 0), dtype=torch.int32, device=copies.device)
+    neq = torch.empty(max(int(f), 0), dtype=torch.int32, device=copies.device)
     _check(_load().byz_vote(_dev_ptr(copies, ("float32",), "copies"), int(d), ld,
                             _dev_ptr(file_rows_dev, ("int32",), "file_rows_dev"), int(f), int(r),
                             _dev_ptr(wrep, ("int32",), "winner_replica"),
@@ -191,6 +203,7 @@ def byz_median(rows_base, d, row_index_dev, out=None, stream=None):
     f = int(row_index_dev.numel())
     if out is None:
         out = torch.empty(int(d), dtype=torch.float32, device=rows_base.device)
+    _need(out, int(d), "out")
     _check(_load().byz_median(_dev_ptr(rows_base, ("float32",), "rows_base"), int(d), ld,
                               _dev_ptr(row_index_dev, ("int32",), "row_index_dev"), f,
                               _dev_ptr(out, ("float32",), "out"), _stream_ptr(stream)),
@@ -204,6 +217,7 @@ def byz_trimmed_mean(rows_base, d, row_index_dev, b, out=None, stream=None):
     f = int(row_index_dev.numel())
     if out is None:
         out = torch.empty(int(d), dtype=torch.float32, device=rows_base.device)
+    _need(out, int(d), "out")
     _check(_load().byz_trimmed_mean(_dev_ptr(rows_base, ("float32",), "rows_base"), int(d), ld,
                                     _dev_ptr(row_index_dev, ("int32",), "row_index_dev"), f,
                                     int(b), _dev_ptr(out, ("float32",), "out"),
@@ -272,6 +286,9 @@ def byz_aggregate(copies, d, file_rows_dev, f, r, out=None, winner_replica=None,
         if nbytes == 0:
             raise ByzError(-1, "byz_aggregate_workspace_bytes")
         workspace = torch.empty(nbytes, dtype=torch.uint8, device=copies.device)
+    _need(file_rows_dev, int(f) * int(r), "file_rows_dev")
+    _need(out, int(d), "out")
+    _need(winner_replica, int(f), "winner_replica")
     args = [_dev_ptr(copies, ("float32",), "copies"), int(d), ld,
             _dev_ptr(file_rows_dev, ("int32",), "file_rows_dev"), int(f), int(r),
             _dev_ptr(out, ("float32",), "out"),
@@ -282,6 +299,10 @@ def byz_aggregate(copies, d, file_rows_dev, f, r, out=None, winner_replica=None,
     else:
         _check(_load().byz_aggregate_opts(*args, _flags, _stream_ptr(stream)), "byz_aggregate_opts")
     return out, winner_replica, workspace
+
+
+def byz_aggregate_has_single_pass(f, r):
+    return bool(_load().byz_aggregate_has_single_pass(int(f), int(r)))
 
 
 def byz_aggregate_took_exact_path(workspace, stream=None):

@@ -278,53 +278,71 @@ extern "C" int byz_assignment_file_rows(const byz_assignment *g, int32_t *out) {
 
 namespace {
 
-// Per-file copy counters for up to 64 files, one bit plane per binary digit (counts <= 7).
-struct Planes {
-    uint64_t c0, c1, c2;
+// Per-file copy counters for up to 64*W files, one bit plane per binary digit (counts <= 7).
+template <int W> struct FileSet {
+    uint64_t w[W];
 };
 
-inline Planes add_mask(Planes p, uint64_t m) {
-    uint64_t carry = p.c0 & m;
-    p.c0 ^= m;
-    uint64_t carry2 = p.c1 & carry;
-    p.c1 ^= carry;
-    p.c2 ^= carry2;
+template <int W> struct Planes {
+    FileSet<W> c0, c1, c2;
+};
+
+template <int W> inline Planes<W> add_mask(Planes<W> p, const FileSet<W> &m) {
+    for (int i = 0; i < W; ++i) {
+        const uint64_t carry = p.c0.w[i] & m.w[i];
+        p.c0.w[i] ^= m.w[i];
+        const uint64_t carry2 = p.c1.w[i] & carry;
+        p.c1.w[i] ^= carry;
+        p.c2.w[i] ^= carry2;
+    }
     return p;
 }
 
 // bit j set iff count_j >= need, need in 1..4
-inline uint64_t at_least(const Planes &p, int need) {
-    switch (need) {
-        case 1: return p.c0 | p.c1 | p.c2;
-        case 2: return p.c1 | p.c2;
-        case 3: return p.c2 | (p.c1 & p.c0);
-        default: return p.c2;
+template <int W> inline FileSet<W> at_least(const Planes<W> &p, int need) {
+    FileSet<W> out;
+    for (int i = 0; i < W; ++i) {
+        const uint64_t c0 = p.c0.w[i], c1 = p.c1.w[i], c2 = p.c2.w[i];
+        switch (need) {
+            case 1: out.w[i] = c0 | c1 | c2; break;
+            case 2: out.w[i] = c1 | c2; break;
+            case 3: out.w[i] = c2 | (c1 & c0); break;
+            default: out.w[i] = c2; break;
+        }
     }
+    return out;
 }
 
-struct SearchResult {
+template <int W> inline int count(const FileSet<W> &s) {
+    int c = 0;
+    for (int i = 0; i < W; ++i) c += __builtin_popcountll(s.w[i]);
+    return c;
+}
+
+template <int W> struct SearchResult {
     int best = -1;
-    uint64_t files = 0;
+    FileSet<W> files = {};
     std::vector<int> set;
 };
 
 // All q-subsets that start with the ascending workers prefix[0..p-1] (p < q or p == q == 1),
 // in lexicographic order; keeps the first one with the largest number of files that have at
 // least `need` copies inside the subset.
-SearchResult search_with_prefix(const std::vector<uint64_t> &mask, int K, int q, int need,
-                                const int *prefix, int p) {
-    SearchResult res;
+template <int W>
+SearchResult<W> search_with_prefix(const std::vector<FileSet<W>> &mask, int K, int q, int need,
+                                   const int *prefix, int p) {
+    SearchResult<W> res;
     res.set.assign((size_t)q, 0);
     std::vector<int> cur((size_t)q + 1, 0);
     // planes[t] = per-file counters of the first t chosen workers
-    std::vector<Planes> planes((size_t)q + 1, Planes{0, 0, 0});
+    std::vector<Planes<W>> planes((size_t)q + 1, Planes<W>{});
     for (int i = 0; i < p; ++i) {
         cur[i] = prefix[i];
         planes[i + 1] = add_mask(planes[i], mask[prefix[i]]);
     }
     if (p == q) {
-        const uint64_t hit = at_least(planes[p], need);
-        res.best = __builtin_popcountll(hit);
+        const FileSet<W> hit = at_least(planes[p], need);
+        res.best = count(hit);
         res.files = hit;
         for (int i = 0; i < q; ++i) res.set[i] = prefix[i];
         return res;
@@ -345,10 +363,10 @@ SearchResult search_with_prefix(const std::vector<uint64_t> &mask, int K, int q,
             continue;
         }
         // last position: sweep all remaining workers in a tight loop
-        const Planes base = planes[t];
+        const Planes<W> base = planes[t];
         for (int w = cur[t]; w < K; ++w) {
-            const uint64_t hit = at_least(add_mask(base, mask[w]), need);
-            const int c = __builtin_popcountll(hit);
+            const FileSet<W> hit = at_least(add_mask(base, mask[w]), need);
+            const int c = count(hit);
             if (c > res.best) {
                 res.best = c;
                 res.files = hit;
@@ -362,20 +380,20 @@ SearchResult search_with_prefix(const std::vector<uint64_t> &mask, int K, int q,
     return res;
 }
 
-}  // namespace
-
-extern "C" int byz_worst_case(const byz_assignment *g, int q, int32_t *byz_workers_out,
-                              int32_t *cmax_out, uint64_t *distorted_mask_out) {
-    if (!g || q < 0 || q > g->K) return BYZ_EINVAL;
-    if (g->f > BYZ_MAX_F || g->r > BYZ_MAX_R) return BYZ_EUNSUPPORTED;
+template <int W>
+int worst_case_impl(const byz_assignment *g, int q, int32_t *byz_workers_out, int32_t *cmax_out,
+                    uint64_t *distorted_mask_out) {
     const int K = g->K, l = g->l;
     const int need = (g->r + 1) / 2;  // r' of Sec. 2
-    std::vector<uint64_t> mask((size_t)K, 0);
+    std::vector<FileSet<W>> mask((size_t)K, FileSet<W>{});
     for (int w = 0; w < K; ++w)
-        for (int t = 0; t < l; ++t) mask[w] |= 1ull << g->worker_files[(size_t)w * l + t];
+        for (int t = 0; t < l; ++t) {
+            const int j = g->worker_files[(size_t)w * l + t];
+            mask[w].w[j >> 6] |= 1ull << (j & 63);
+        }
 
     int best = -1;
-    uint64_t best_files = 0;
+    FileSet<W> best_files = {};
     std::vector<int> best_set((size_t)q, 0);
     if (q == 0) {
         best = 0;
@@ -398,7 +416,7 @@ extern "C" int byz_worst_case(const byz_assignment *g, int q, int32_t *byz_worke
             }
         }
         const int n_tasks = (int)prefixes.size() / p;
-        std::vector<SearchResult> results((size_t)n_tasks);
+        std::vector<SearchResult<W>> results((size_t)n_tasks);
         double subsets = 1.0;
         for (int i = 0; i < q; ++i) subsets = subsets * (K - i) / (i + 1);
         unsigned n_threads = 1;
@@ -414,7 +432,7 @@ extern "C" int byz_worst_case(const byz_assignment *g, int q, int32_t *byz_worke
                 const int first = next_task.fetch_add(1);
                 if (first >= n_tasks) break;
                 results[(size_t)first] =
-                    search_with_prefix(mask, K, q, need, &prefixes[(size_t)first * p], p);
+                    search_with_prefix<W>(mask, K, q, need, &prefixes[(size_t)first * p], p);
             }
         };
         if (n_threads <= 1) {
@@ -429,7 +447,7 @@ extern "C" int byz_worst_case(const byz_assignment *g, int q, int32_t *byz_worke
             }
         }
         for (int first = 0; first < n_tasks; ++first) {
-            const SearchResult &res = results[(size_t)first];
+            const SearchResult<W> &res = results[(size_t)first];
             if (res.best > best) {
                 best = res.best;
                 best_files = res.files;
@@ -440,8 +458,20 @@ extern "C" int byz_worst_case(const byz_assignment *g, int q, int32_t *byz_worke
     if (byz_workers_out)
         for (int i = 0; i < q; ++i) byz_workers_out[i] = best_set[i];
     if (cmax_out) *cmax_out = best;
-    if (distorted_mask_out) *distorted_mask_out = best_files;
+    if (distorted_mask_out)
+        for (int i = 0; i < (g->f + 63) / 64; ++i) distorted_mask_out[i] = best_files.w[i];
     return BYZ_OK;
+}
+
+}  // namespace
+
+extern "C" int byz_worst_case(const byz_assignment *g, int q, int32_t *byz_workers_out,
+                              int32_t *cmax_out, uint64_t *distorted_mask_out) {
+    if (!g || q < 0 || q > g->K) return BYZ_EINVAL;
+    if (g->f > BYZ_MAX_F_WIDE || g->r > BYZ_MAX_R) return BYZ_EUNSUPPORTED;
+    if (g->f <= 64) return worst_case_impl<1>(g, q, byz_workers_out, cmax_out, distorted_mask_out);
+    if (g->f <= 128) return worst_case_impl<2>(g, q, byz_workers_out, cmax_out, distorted_mask_out);
+    return worst_case_impl<4>(g, q, byz_workers_out, cmax_out, distorted_mask_out);
 }
 
 extern "C" double byz_gamma_bound(const byz_assignment *g, int q) {

@@ -44,8 +44,11 @@ thread_local ProfileState g_prof;
 
 // Files the single-pass kernel prefetches ahead of the one it consumes, from the number of
 // 16-byte loads per thread it should keep in flight.  Measured on MI355X: about 6 for f = 25
-// (3-4 waves per SIMD), about 12 for f = 49 (2 waves per SIMD); more is slower.
+// (3-4 waves per SIMD), about 12 for f = 49 (2 waves per SIMD); more is slower.  f = 121 runs
+// one word per thread (4-byte loads) and gains up to 20 files ahead; f = 81 (two words per
+// thread, 253 registers) has no room for more than 5.
 constexpr int prefetch_depth(int f, int slots) {
+    if (f > 81) return 20;
     const int target = f >= 49 ? 12 : 6;
     const int a = (target + slots - 1) / slots - 1;
     return a < 1 ? 1 : (a > 5 ? 5 : a);
@@ -53,10 +56,14 @@ constexpr int prefetch_depth(int f, int slots) {
 // f with a generated streamed network (gen_selnet.py STREAMED_SIZES): the paper's file counts
 // l^2 (MOLS, Ramanujan Case 1) and m*s (Ramanujan Case 2)
 constexpr bool has_streamed_network(int f) {
-    return f == 9 || f == 15 || f == 21 || f == 25 || f == 35 || f == 49;
+    return f == 9 || f == 15 || f == 21 || f == 25 || f == 35 || f == 49 || f == 81 || f == 121;
 }
+// words per thread: fewer for the large networks, whose keys fill the register file
+constexpr int vec_for(int f) { return f <= 49 ? 4 : (f <= 81 ? 2 : 1); }
 constexpr int kProbe = 256;  // sampled coordinates = threads of the probe block (512: 2x slower)
 constexpr int kBlock = 256;  // threads per block of the streaming kernels (128/512/1024: slower)
+constexpr int kWide = BYZ_MAX_F_WIDE;  // largest f of the vote and the LDS column kernels
+static_assert(kWide <= kBlock, "one thread per file in the deciding block");
 constexpr int kRowStride = 8;  // slots per file in the permuted row table (>= BYZ_MAX_R)
 
 // ----------------------------------------------------------------------------- helpers
@@ -260,12 +267,12 @@ template <> struct SelNet<49> {
 
 struct AggWorkspace {
     uint32_t viol[BYZ_MAX_F];        // single pass: assumed-equal neighbours that differ
-    uint32_t pair_neq[BYZ_MAX_F];    // exact path: all pair bits
+    uint32_t pair_neq[kWide];        // exact path: all pair bits
     // byte offsets row*ld*4 of a file's rows, probable winner's class first
     uint64_t perm_off[BYZ_MAX_F * kRowStride];
     uint32_t chain_mask[BYZ_MAX_F];  // bit k-1: permuted copies k-1 and k were equal on the sample
     int32_t prov_winner[BYZ_MAX_F];  // probable winner (original replica index)
-    int32_t winner_row[BYZ_MAX_F];   // exact path result
+    int32_t winner_row[kWide];       // exact path result
     uint32_t need_exact;             // 1 iff the exact path ran
     uint32_t slots_per_file;         // slots of every file the single pass reads: r or r'
     uint32_t ticket_vote;            // blocks of the exact-path vote kernel that have finished
@@ -277,10 +284,8 @@ struct AggWorkspace {
 // Clears the accumulators of one two-step aggregation (no hipMemset: callers may capture).
 __global__ void reset_workspace_kernel(AggWorkspace *ws, uint32_t need_exact) {
     const int i = threadIdx.x;
-    if (i < BYZ_MAX_F) {
-        ws->viol[i] = 0;
-        ws->pair_neq[i] = 0;
-    }
+    if (i < BYZ_MAX_F) ws->viol[i] = 0;
+    if (i < kWide) ws->pair_neq[i] = 0;
     if (i == 0) {
         ws->need_exact = need_exact;
         ws->ticket_vote = 0;
@@ -343,21 +348,27 @@ __global__ __launch_bounds__(kBlock) void vote_pairs_kernel(
     const int lane = threadIdx.x & 63;
     const int64_t n_vec = d / V;
     const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    uint32_t flags = 0;
     if (n_vec > 0) {
         // threads past the end redo the last vector: no branches around loads and ballots
         const uint32_t *base = X + (gt < n_vec ? gt : n_vec - 1) * V;
-        for (int j = 0; j < f; ++j) {
-            uint32_t x[R][V];
+        // files in groups of 64: lane j - j0 collects the bits of file j
+        for (int j0 = 0; j0 < f; j0 += 64) {
+            const int j1 = j0 + 64 < f ? j0 + 64 : f;
+            uint32_t flags = 0;
+            for (int j = j0; j < j1; ++j) {
+                uint32_t x[R][V];
 #pragma unroll
-            for (int k = 0; k < R; ++k) load_vec<V>(base + (int64_t)file_rows[j * R + k] * ld, x[k]);
-            uint32_t wb = 0;
+                for (int k = 0; k < R; ++k)
+                    load_vec<V>(base + (int64_t)file_rows[j * R + k] * ld, x[k]);
+                uint32_t wb = 0;
 #pragma unroll
-            for (int a = 0; a < R; ++a)
+                for (int a = 0; a < R; ++a)
 #pragma unroll
-                for (int b = a + 1; b < R; ++b)
-                    wb |= wave_any(differ<V>(x[a], x[b])) << pair_bit(R, a, b);
-            if (lane == j) flags |= wb;
+                    for (int b = a + 1; b < R; ++b)
+                        wb |= wave_any(differ<V>(x[a], x[b])) << pair_bit(R, a, b);
+                if (lane == j - j0) flags |= wb;
+            }
+            merge_flags(pair_neq + j0, j1 - j0, lane, flags);
         }
     }
     const int tail = (int)(d - n_vec * V);
@@ -376,7 +387,6 @@ __global__ __launch_bounds__(kBlock) void vote_pairs_kernel(
             if (bits != 0) atomicOr(&pair_neq[j], bits);
         }
     }
-    merge_flags(pair_neq, f, lane, flags);
     if (ticket != nullptr && last_block_done(ticket))
         decide_files(pair_neq, file_rows, f, R, winner_replica, winner_row);
 }
@@ -394,6 +404,10 @@ __global__ __launch_bounds__(kBlock) void vote_pairs_kernel(
 #define BYZ_S_LOAD3(j) if constexpr (kAhead == 3) { BYZ_S_LOAD_(j) }
 #define BYZ_S_LOAD4(j) if constexpr (kAhead == 4) { BYZ_S_LOAD_(j) }
 #define BYZ_S_LOAD5(j) if constexpr (kAhead == 5) { BYZ_S_LOAD_(j) }
+#define BYZ_S_LOAD8(j) if constexpr (kAhead == 8) { BYZ_S_LOAD_(j) }
+#define BYZ_S_LOAD12(j) if constexpr (kAhead == 12) { BYZ_S_LOAD_(j) }
+#define BYZ_S_LOAD16(j) if constexpr (kAhead == 16) { BYZ_S_LOAD_(j) }
+#define BYZ_S_LOAD20(j) if constexpr (kAhead == 20) { BYZ_S_LOAD_(j) }
 #define BYZ_S_USE(j)                                                                          \
     {                                                                                         \
         if constexpr (NS > 1) {                                                               \
@@ -470,6 +484,35 @@ __global__ __launch_bounds__(kBlock) void median_kernel(
         for (int j = 0; j < F; ++j) key[j] = to_key(X[(int64_t)row_index[j] * ld + c]);
         out[c] = from_key(SelNet<F>::median(key));
     }
+}
+
+// Step a3 for the large generated networks (F = 81, 121: MOLS over F_9 and F_11): the streamed
+// program with V = vec_for(F) words per thread.  Thread t owns the words starting at
+// min(V*t, d - V): the last vector overlaps its neighbour (both write the same values).
+// Needs d >= V.
+template <int F, int V>
+__global__ __launch_bounds__(kBlock) void median_large_kernel(
+    const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
+    uint32_t *__restrict__ out) {
+    const int64_t n_thr = (d + V - 1) / V;
+    const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (gt >= n_thr) return;
+    const int64_t c0 = gt * V < d - V ? gt * V : d - V;
+    uint32_t key[V][F];
+    uint32_t o[V];
+    constexpr int NS = 1;
+    constexpr int kAhead = prefetch_depth(F, NS);
+    const uint32_t voff = (uint32_t)(c0 * 4);
+    const char *Xb = reinterpret_cast<const char *>(X);
+    uint32_t stage[kAhead + 1][NS][V];
+    const uint32_t *chain_mask = nullptr;  // unused with one slot per file
+    const int lane = 0;
+    uint32_t flags = 0;
+    (void)chain_mask; (void)lane; (void)flags;
+#define BYZ_S_ROW_ADDR(j, k) (Xb + (uint64_t)(uint32_t)row_index[j] * (uint64_t)ld * 4u + voff)
+#include "generated/selnet_stream_dispatch.inc"
+#undef BYZ_S_ROW_ADDR
+    store_vec<V>(out + c0, o);
 }
 
 // Step a3 for any odd f <= 64 (no generated network): rank counting, one coordinate a thread.
@@ -558,6 +601,51 @@ __global__ __launch_bounds__(kBlock) void trimmed_mean_generic_kernel(
     float acc = 0.0f;
     for (int i = b; i < f - b; ++i) acc += __uint_as_float(from_key(key[i]));
     out[c] = __float_as_uint(acc / (float)(f - 2 * b));
+}
+
+// Median and trimmed mean for 64 < f <= 256: one wave a block, one coordinate a lane, the f keys
+// of a coordinate in an LDS column (word j*64 + lane: conflict-free).  Dynamic LDS: f*256 bytes.
+//   b < 0   median by bisection on the key: the result is the largest u with
+//           #{keys < u} <= (f-1)/2, built from the top bit down (32 counting passes).
+//   b >= 0  trimmed mean: insertion sort of the column, then the rounding contract of
+//           trimmed_mean_kernel (fp32, kept values added in ascending order, one division).
+__global__ __launch_bounds__(64) void column_wide_kernel(
+    const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
+    int f, int b, uint32_t *__restrict__ out) {
+    extern __shared__ uint32_t s_col[];
+    const int lane = threadIdx.x;
+    const int64_t c_raw = (int64_t)blockIdx.x * 64 + lane;
+    const int64_t c = c_raw < d ? c_raw : d - 1;  // lanes past the end redo the last coordinate
+    uint32_t *col = s_col + lane;
+#pragma unroll 8
+    for (int j = 0; j < f; ++j) col[j * 64] = to_key(X[(int64_t)row_index[j] * ld + c]);
+    uint32_t o;
+    if (b < 0) {
+        const int mid = (f - 1) / 2;
+        uint32_t result = 0;
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t trial = result | (1u << bit);
+            int below = 0;
+#pragma unroll 8
+            for (int j = 0; j < f; ++j) below += col[j * 64] < trial ? 1 : 0;
+            if (below <= mid) result = trial;
+        }
+        o = from_key(result);
+    } else {
+        for (int i = 1; i < f; ++i) {
+            const uint32_t x = col[i * 64];
+            int t = i - 1;
+            while (t >= 0 && col[t * 64] > x) {
+                col[(t + 1) * 64] = col[t * 64];
+                --t;
+            }
+            col[(t + 1) * 64] = x;
+        }
+        float acc = 0.0f;
+        for (int i = b; i < f - b; ++i) acc += __uint_as_float(from_key(col[i * 64]));
+        o = __float_as_uint(acc / (float)(f - 2 * b));
+    }
+    if (c_raw < d) out[c_raw] = o;
 }
 
 // Probe: compares the copies of every file on a sample of <= kProbe coordinates (kProbe/16 runs
@@ -761,6 +849,16 @@ int launch_vote_pairs_r(int r, const uint32_t *X, int64_t d, int64_t ld, const i
     }
 }
 
+// f > 64 (never gated: the single pass does not exist for these f)
+int launch_column_wide(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
+                       int b, uint32_t *out, hipStream_t s) {
+    if (d == 0) return BYZ_OK;
+    const size_t lds = (size_t)f * 64 * sizeof(uint32_t);  // <= 64 KiB for f <= 256
+    column_wide_kernel<<<(unsigned)((d + 63) / 64), 64, lds, s>>>(X, d, ld, row_index, f, b, out);
+    BYZ_HIP(hipGetLastError());
+    return BYZ_OK;
+}
+
 template <int F>
 int launch_median_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index,
                       uint32_t *out, const uint32_t *gate, int gate_n, hipStream_t s) {
@@ -784,7 +882,21 @@ int launch_median(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_i
         case 25: return launch_median_net<25>(X, d, ld, row_index, out, gate, gate_n, s);
         case 35: return launch_median_net<35>(X, d, ld, row_index, out, gate, gate_n, s);
         case 49: return launch_median_net<49>(X, d, ld, row_index, out, gate, gate_n, s);
+        case 81:
+            if (d < vec_for(81)) return launch_column_wide(X, d, ld, row_index, f, -1, out, s);
+            median_large_kernel<81, vec_for(81)>
+                <<<blocks_for((d + vec_for(81) - 1) / vec_for(81)), kBlock, 0, s>>>(X, d, ld,
+                                                                                  row_index, out);
+            BYZ_HIP(hipGetLastError());
+            return BYZ_OK;
+        case 121:
+            median_large_kernel<121, vec_for(121)>
+                <<<blocks_for((d + vec_for(121) - 1) / vec_for(121)), kBlock, 0, s>>>(
+                    X, d, ld, row_index, out);
+            BYZ_HIP(hipGetLastError());
+            return BYZ_OK;
         default:
+            if (f > BYZ_MAX_F) return launch_column_wide(X, d, ld, row_index, f, -1, out, s);
             median_generic_kernel<<<blocks_for(d), kBlock, 0, s>>>(X, d, ld, row_index, f, out,
                                                                    gate, gate_n);
             BYZ_HIP(hipGetLastError());
@@ -814,25 +926,35 @@ int launch_fused(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, 
     return BYZ_OK;
 }
 
+template <int F>
+int launch_trimmed_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int b,
+                       uint32_t *O, const uint32_t *gate, int gate_n, hipStream_t s) {
+    constexpr int V = vec_for(F);
+    trimmed_mean_kernel<F, V><<<blocks_for((d + V - 1) / V), kBlock, 0, s>>>(X, d, ld, row_index,
+                                                                             b, O, gate, gate_n);
+    BYZ_HIP(hipGetLastError());
+    return BYZ_OK;
+}
+
 int launch_trimmed_mean(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
                         int b, uint32_t *O, const uint32_t *gate, int gate_n, hipStream_t s) {
     if (d == 0) return BYZ_OK;
-    const unsigned g = blocks_for((d + kVec - 1) / kVec);
-    if (d >= kVec && f == 9)
-        trimmed_mean_kernel<9, kVec><<<g, kBlock, 0, s>>>(X, d, ld, row_index, b, O, gate, gate_n);
-    else if (d >= kVec && f == 15)
-        trimmed_mean_kernel<15, kVec><<<g, kBlock, 0, s>>>(X, d, ld, row_index, b, O, gate, gate_n);
-    else if (d >= kVec && f == 21)
-        trimmed_mean_kernel<21, kVec><<<g, kBlock, 0, s>>>(X, d, ld, row_index, b, O, gate, gate_n);
-    else if (d >= kVec && f == 25)
-        trimmed_mean_kernel<25, kVec><<<g, kBlock, 0, s>>>(X, d, ld, row_index, b, O, gate, gate_n);
-    else if (d >= kVec && f == 35)
-        trimmed_mean_kernel<35, kVec><<<g, kBlock, 0, s>>>(X, d, ld, row_index, b, O, gate, gate_n);
-    else if (d >= kVec && f == 49)
-        trimmed_mean_kernel<49, kVec><<<g, kBlock, 0, s>>>(X, d, ld, row_index, b, O, gate, gate_n);
-    else
-        trimmed_mean_generic_kernel<<<blocks_for(d), kBlock, 0, s>>>(X, d, ld, row_index, f, b, O,
-                                                                     gate, gate_n);
+    if (has_streamed_network(f) && d >= vec_for(f)) {
+        switch (f) {
+            case 9: return launch_trimmed_net<9>(X, d, ld, row_index, b, O, gate, gate_n, s);
+            case 15: return launch_trimmed_net<15>(X, d, ld, row_index, b, O, gate, gate_n, s);
+            case 21: return launch_trimmed_net<21>(X, d, ld, row_index, b, O, gate, gate_n, s);
+            case 25: return launch_trimmed_net<25>(X, d, ld, row_index, b, O, gate, gate_n, s);
+            case 35: return launch_trimmed_net<35>(X, d, ld, row_index, b, O, gate, gate_n, s);
+            case 49: return launch_trimmed_net<49>(X, d, ld, row_index, b, O, gate, gate_n, s);
+            case 81: return launch_trimmed_net<81>(X, d, ld, row_index, b, O, gate, gate_n, s);
+            case 121: return launch_trimmed_net<121>(X, d, ld, row_index, b, O, gate, gate_n, s);
+            default: break;
+        }
+    }
+    if (f > BYZ_MAX_F) return launch_column_wide(X, d, ld, row_index, f, b, O, s);
+    trimmed_mean_generic_kernel<<<blocks_for(d), kBlock, 0, s>>>(X, d, ld, row_index, f, b, O,
+                                                                 gate, gate_n);
     BYZ_HIP(hipGetLastError());
     return BYZ_OK;
 }
@@ -847,7 +969,7 @@ bool has_fused(int f, int r) {
 int check_common(const void *copies, int64_t d, int64_t ld, const void *rows, int f, int r) {
     if (copies == nullptr || rows == nullptr) return BYZ_EINVAL;
     if (d < 0 || ld < d || d > kMaxCoords) return BYZ_EINVAL;
-    if (f < 1 || f > BYZ_MAX_F) return BYZ_EINVAL;
+    if (f < 1 || f > kWide) return BYZ_EINVAL;
     if (r < 3 || r > BYZ_MAX_R || (r % 2) == 0) return BYZ_EINVAL;
     return BYZ_OK;
 }
@@ -869,14 +991,14 @@ extern "C" int byz_vote(const float *copies, int64_t d, int64_t ld, const int32_
         return BYZ_EINVAL;
     hipStream_t s = (hipStream_t)stream;
     const uint32_t *X = reinterpret_cast<const uint32_t *>(copies);
-    fill_u32_kernel<<<1, BYZ_MAX_F, 0, s>>>(pair_neq, f, 0u);
+    fill_u32_kernel<<<1, kWide, 0, s>>>(pair_neq, f, 0u);
     BYZ_HIP(hipGetLastError());
     if (d > 0) {
         rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, pair_neq, nullptr, nullptr,
                                  nullptr, nullptr, nullptr, nullptr, s);
         if (rc != BYZ_OK) return rc;
     }
-    vote_decide_kernel<<<1, BYZ_MAX_F, 0, s>>>(pair_neq, file_rows_dev, f, r, winner_replica,
+    vote_decide_kernel<<<1, kWide, 0, s>>>(pair_neq, file_rows_dev, f, r, winner_replica,
                                                winner_row);
     BYZ_HIP(hipGetLastError());
     return BYZ_OK;
@@ -887,7 +1009,7 @@ extern "C" int byz_median(const float *rows_base, int64_t d, int64_t ld,
     if (rows_base == nullptr || row_index_dev == nullptr || (out == nullptr && d > 0))
         return BYZ_EINVAL;
     if (d < 0 || ld < d || d > kMaxCoords) return BYZ_EINVAL;
-    if (f < 1 || f > BYZ_MAX_F) return BYZ_EINVAL;
+    if (f < 1 || f > kWide) return BYZ_EINVAL;
     if ((f % 2) == 0) return BYZ_EUNSUPPORTED;
     return launch_median(reinterpret_cast<const uint32_t *>(rows_base), d, ld, row_index_dev, f,
                          reinterpret_cast<uint32_t *>(out), nullptr, 0, (hipStream_t)stream);
@@ -899,7 +1021,7 @@ extern "C" int byz_trimmed_mean(const float *rows_base, int64_t d, int64_t ld,
     if (rows_base == nullptr || row_index_dev == nullptr || (out == nullptr && d > 0))
         return BYZ_EINVAL;
     if (d < 0 || ld < d || d > kMaxCoords) return BYZ_EINVAL;
-    if (f < 1 || f > BYZ_MAX_F || b < 0 || 2 * b >= f) return BYZ_EINVAL;
+    if (f < 1 || f > kWide || b < 0 || 2 * b >= f) return BYZ_EINVAL;
     if (d == 0) return BYZ_OK;
     return launch_trimmed_mean(reinterpret_cast<const uint32_t *>(rows_base), d, ld, row_index_dev,
                                f, b, reinterpret_cast<uint32_t *>(out), nullptr, 0,
@@ -907,9 +1029,11 @@ extern "C" int byz_trimmed_mean(const float *rows_base, int64_t d, int64_t ld,
 }
 
 extern "C" size_t byz_aggregate_workspace_bytes(int f, int r) {
-    if (f < 1 || f > BYZ_MAX_F || r < 3 || r > BYZ_MAX_R || (r % 2) == 0) return 0;
+    if (f < 1 || f > kWide || r < 3 || r > BYZ_MAX_R || (r % 2) == 0) return 0;
     return sizeof(AggWorkspace);
 }
+
+extern "C" int byz_aggregate_has_single_pass(int f, int r) { return has_fused(f, r) ? 1 : 0; }
 
 extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
                                   const int32_t *file_rows_dev, int f, int r, float *out,
@@ -935,18 +1059,23 @@ extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
 
     if (!has_fused(f, r) || d < kVec) {
         // two-step path, unconditionally: vote (a1, a2), then median (a3) over the winners
-        reset_workspace_kernel<<<1, BYZ_MAX_F, 0, s>>>(ws, 1u);
+        reset_workspace_kernel<<<1, kWide, 0, s>>>(ws, 1u);
         BYZ_HIP(hipGetLastError());
+        // (no last-block ticket here: its per-block fence costs more than a third launch)
         if (d > 0) {
-            rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, nullptr,
-                                     &ws->ticket_vote, winner_replica, ws->winner_row, nullptr,
-                                     nullptr, s);
+            const bool timed = g_prof.count < g_prof.capacity;
+            if (timed) BYZ_HIP(hipEventRecord(g_prof.start[g_prof.count], s));
+            rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, nullptr, nullptr,
+                                     nullptr, nullptr, nullptr, nullptr, s);
             if (rc != BYZ_OK) return rc;
-        } else {
-            vote_decide_kernel<<<1, BYZ_MAX_F, 0, s>>>(ws->pair_neq, file_rows_dev, f, r,
-                                                       winner_replica, ws->winner_row);
-            BYZ_HIP(hipGetLastError());
+            if (timed) {
+                BYZ_HIP(hipEventRecord(g_prof.stop[g_prof.count], s));
+                ++g_prof.count;
+            }
         }
+        vote_decide_kernel<<<1, kWide, 0, s>>>(ws->pair_neq, file_rows_dev, f, r, winner_replica,
+                                               ws->winner_row);
+        BYZ_HIP(hipGetLastError());
         if (trim_b >= 0)
             return launch_trimmed_mean(X, d, ld, ws->winner_row, f, trim_b, O, nullptr, 0, s);
         return launch_median(X, d, ld, ws->winner_row, f, O, nullptr, 0, s);

@@ -33,4 +33,8 @@ CONFIGS = [
     # reversed gradient, q = 6; c_max = 6 is the exhaustive search's value (no table prints it)
     Config("cfg7_ram5x7_resnet18_reversed", RAMANUJAN, 5, 7, 25, 35, 7, 5, 6, 6, 11173962,
            {"kind": "reversed", "c": 100.0}, 1, 20101004 + 57),
+    # MOLS over F_9 (prime-power l, Sec. 4.1.1): (K,f,l,r) = (27,81,9,3), 243 rows, ALIE, q = 5;
+    # c_max = 8 from the exhaustive search.  f > 64: two-step path with the LDS median kernel
+    Config("cfg8_mols9x3_resnet18_alie", MOLS, 9, 3, 27, 81, 9, 3, 5, 8, 11173962,
+           {"kind": "alie", "z": 1.0}, 1, 20101004 + 93),
 ]

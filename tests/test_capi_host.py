@@ -131,13 +131,30 @@ def test_worst_case_errors():
         with pytest.raises(B.ByzError) as e:
             B.byz_worst_case(asg, q)
         assert e.value.code == -1
-    big = _build("ram", 5, 13)  # f = 65 > 64
+    big = _build("mols", 17, 3)  # f = 289 > 256
     with pytest.raises(B.ByzError) as e:
         B.byz_worst_case(big, 2)
     assert e.value.code == -2
     assert math.isnan(B.byz_gamma_bound(asg, 99))
-    assert B.byz_aggregate_workspace_bytes(25, 3) > 0
-    assert B.byz_aggregate_workspace_bytes(25, 4) == 0 and B.byz_aggregate_workspace_bytes(65, 3) == 0
+    assert B.byz_aggregate_workspace_bytes(25, 3) > 0 and B.byz_aggregate_workspace_bytes(255, 3) > 0
+    assert B.byz_aggregate_workspace_bytes(25, 4) == 0 and B.byz_aggregate_workspace_bytes(257, 3) == 0
+
+
+@pytest.mark.parametrize("scheme,a,b,qs", [("ram", 5, 13, (0, 1, 2, 3, 5)),     # f = 65, K = 25
+                                           ("mols", 9, 3, (2, 3, 4)),            # F_9: f = 81
+                                           ("mols", 11, 3, (2, 4)),              # f = 121
+                                           ("mols", 13, 3, (3,)),                # f = 169
+                                           ("mols", 16, 3, (2, 3))])             # F_16: f = 256
+def test_worst_case_more_than_64_files(scheme, a, b, qs):
+    asg = _build(scheme, a, b)
+    H = _H(asg)
+    for q in qs:
+        S, c, mask = B.byz_worst_case(asg, q)
+        c_o, S_o = C.worst_case(H, q)
+        assert (c, tuple(S)) == (c_o, tuple(S_o)), q
+        files = O.distorted_files(H, S)
+        assert mask == sum(1 << int(j) for j in files) and len(files) == c
+        assert c <= B.byz_gamma_bound(asg, q)  # Claim 1
 
 
 # ------------------------------------------------------------- selection network generator
@@ -163,7 +180,7 @@ def test_selection_network_zero_one_exhaustive(f):
     assert np.array_equal(v[wire], (pop > f // 2).astype(np.uint8))
 
 
-@pytest.mark.parametrize("f", [35, 49])
+@pytest.mark.parametrize("f", [35, 49, 81, 121])
 def test_selection_network_near_balanced_inputs(f):
     ops, wire = gen_selnet.best_network(f)
     rng = np.random.default_rng(f)

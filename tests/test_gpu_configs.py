@@ -113,6 +113,32 @@ def test_ramanujan_case2_cluster_full_size():
     assert _full_check(w, cfg.name) == cmax_o
 
 
+def test_prime_power_cluster_full_size():
+    # MOLS over F_9: (K,f,l,r) = (27,81,9,3), 243 rows of the ResNet-18 size, q = 5 worst-case
+    # set, ALIE.  f > 64: vote in two 64-file groups, median by bisection in LDS.
+    from oracle import byz_oracle as O
+    cfg = synth.CONFIGS[7]
+    w = W.from_config(cfg, DEV, ld=synth.padded_ld(cfg.d, 64))
+    assert (w.K, w.f, w.l, w.r) == (27, 81, 9, 3)
+    cmax_o, S_o = C.worst_case(O.mols_biadjacency(9, 3), cfg.q)
+    assert w.cmax == cmax_o == cfg.cmax and tuple(w.byz) == S_o
+    rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+    out, wrep, ws = B.byz_aggregate(w.X, w.d, rows_dev, w.f, w.r)
+    wrep_v, wrow_v, neq_v = B.byz_vote(w.X, w.d, rows_dev, w.f, w.r)
+    out_m = B.byz_median(w.X, w.d, wrow_v)
+    torch.cuda.synchronize()
+    Xh = w.X.cpu().numpy()
+    wrep_o, wrow_o, neq_o = C.vote(Xh, w.file_rows, w.d)
+    out_o = C.median(Xh, wrow_o, w.d)
+    del Xh
+    assert np.array_equal(wrep.cpu().numpy(), wrep_o) and np.array_equal(wrep_v.cpu().numpy(), wrep_o)
+    assert np.array_equal(wrow_v.cpu().numpy(), wrow_o) and np.array_equal(W.bits(neq_v), neq_o)
+    assert np.array_equal(W.bits(out), W.bits(out_o))
+    assert np.array_equal(W.bits(out_m), W.bits(out_o))
+    lost = sum(1 for j in range(w.f) if int(w.file_workers[j, wrep_o[j]]) in w.byz)
+    assert lost == cmax_o
+
+
 @pytest.mark.parametrize("idx", [1, 2])
 def test_trimmed_mean_full_size(idx):
     # trimmed mean (b = c_max per side) over the vote winners at full size, fp64 oracle,

@@ -221,10 +221,17 @@ def test_special_values_nan_inf_signed_zero():
 def test_argument_errors():
     w = W.make(MOLS, 5, 3, 3, 100, REVERSED, seed=10, device=DEV)
     rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
-    for (f, r, code) in [(25, 4, -1), (25, 1, -1), (0, 3, -1), (65, 3, -1), (25, 9, -1)]:
+    # the library rejects these before any launch; the row table is long enough for each so
+    # that the binding's own length check does not fire first
+    rows_long = torch.zeros(257 * 9, dtype=torch.int32, device=DEV)
+    for (f, r, code) in [(25, 4, -1), (25, 1, -1), (0, 3, -1), (257, 3, -1), (25, 9, -1)]:
         with pytest.raises(B.ByzError) as e:
-            B.byz_vote(w.X, 100, rows_dev, f, r)
+            B.byz_vote(w.X, 100, rows_long, f, r)
         assert e.value.code == code
+    with pytest.raises(ValueError):
+        B.byz_vote(w.X, 100, rows_dev, 65, 3)  # 75-entry table, the call would read 195
+    with pytest.raises(ValueError):
+        B.byz_aggregate(w.X, 100, rows_dev, 81, 3)
     with pytest.raises(B.ByzError) as e:
         B.byz_vote(w.X, 101, rows_dev, 25, 3)  # d > ld
     assert e.value.code == -1
@@ -392,6 +399,47 @@ def test_trimmed_mean_special_values():
     idx = np.arange(f, dtype=np.int32)
     for b in (0, 3, 12):
         _trimmed_mean_check(X, idx, d, b, b)
+
+
+@pytest.mark.parametrize("scheme,a,b,q,attack", [
+    (RAM, 5, 13, 5, MIXED),      # Ramanujan Case 2, f = 65, r = 5: first size past one lane per file
+    (MOLS, 9, 3, 4, ALIE),       # F_9: f = 81
+    (MOLS, 11, 3, 4, REVERSED),  # f = 121
+    (MOLS, 13, 3, 3, CONST),     # f = 169
+    (RAM, 3, 85, 2, ALIE)])      # f = 255, the largest odd f
+def test_more_than_64_files(scheme, a, b, q, attack):
+    # vote with several 64-file groups, median by bisection in LDS, trimmed mean by LDS sort
+    for i, d in enumerate([1, 5, 64, 65, 1000, 4099]):
+        ld = d if i % 2 == 0 else synth.padded_ld(d, 4) + 4
+        w = W.make(scheme, a, b, q, d, attack, seed=700 + i, ld=ld, device=DEV)
+        assert w.f > 64
+        out_o, wrep_o, took_exact = _check_all(w.X, w.file_rows, d, w.f, w.r, tag=(w.f, d))
+        idx = np.array([w.file_rows[j, wrep_o[j]] for j in range(w.f)], dtype=np.int32)
+        for trim in (0, w.cmax, (w.f - 1) // 2):
+            _trimmed_mean_check(w.X, idx, d, trim, (w.f, d, trim))
+
+
+def test_more_than_64_rows_of_raw_bit_patterns():
+    # byz_median / byz_trimmed_mean alone on random words (NaNs, infinities, signed zeros, many
+    # equal keys through repeated rows)
+    rng = np.random.default_rng(77)
+    d = 1500
+    U = rng.integers(0, 2**32, size=(300, d), dtype=np.uint64).astype(np.uint32)
+    U[:, :200] &= np.uint32(0x80000003)  # few distinct values: ties everywhere
+    X = torch.tensor(U.view(np.int32), device=DEV).view(torch.float32)
+    for f in (65, 67, 127, 129, 191, 255):
+        idx = rng.integers(0, 300, size=f).astype(np.int32)
+        out = B.byz_median(X, d, torch.tensor(idx, device=DEV))
+        torch.cuda.synchronize()
+        assert np.array_equal(W.bits(out), W.bits(C.median(U, idx, d))), f
+        for b in (0, 7, (f - 1) // 2):
+            _trimmed_mean_check(X, idx, d, b, (f, b))
+    idx = rng.integers(0, 300, size=256).astype(np.int32)  # even f: trimmed mean only
+    _trimmed_mean_check(X, idx, d, 100, 256)
+    for f in (257, 1000):
+        with pytest.raises(B.ByzError) as e:
+            B.byz_median(X, d, torch.zeros(f, dtype=torch.int32, device=DEV))
+        assert e.value.code == -1
 
 
 def _multi_krum_check(X, idx_np, d, c, m, tag):
