@@ -15,6 +15,7 @@
  *                  +0 < .. < +inf < +NaN); the paper is silent on +-0 / NaN.
  *   oracle_trimmed_mean  coordinate-wise trimmed mean in fp64 (Sec. 1's other robust
  *                  aggregator): sort, drop b at each end, mean of the rest.
+ *   oracle_bulyan  Bulyan on f vectors (repeated Krum, then mean around the median), fp64.
  *   oracle_worst_case  Sec. 5.3.2: exhaustive search over all q-subsets.
  *
  * Build: gcc -O2 -fopenmp -shared -fPIC (see build_oracle.py).
@@ -130,6 +131,117 @@ int oracle_trimmed_mean(const uint32_t *X, int64_t d, int64_t ld, const int32_t 
             acc += (double)v;
         }
         out[c] = acc / (double)(f - 2 * b);
+    }
+    return used;
+}
+
+/*
+ * Bulyan (El Mhamdi, Guerraoui, Rouault 2018), which Sec. 7 names as an aggregator that can
+ * replace the median on the vote winners: theta = f - 2c vectors are chosen by applying Krum
+ * again and again to the vectors not yet chosen, then every coordinate is the mean of the
+ * beta = theta - 2c chosen values closest to their median.
+ *   Krum round on the remaining set (size n'): score(i) = sum, in ascending order, of the
+ *   n' - c - 2 smallest squared distances to the other remaining vectors (no terms if that is
+ *   <= 0); lowest score wins, lowest index on ties.
+ *   Closest to the median: the chosen values in the total order of oracle_median; the window
+ *   starts at the middle one and grows by one neighbour at a time, the lower one when
+ *   (float)(median - lower) <= (float)(upper - median) or no upper one is left.
+ * Squared distances and the mean in fp64.  chosen_out[theta]: indices into row_index in the
+ * order chosen.  dist_out[f*f] may be NULL.  Returns threads used, <0 on error.
+ */
+int oracle_bulyan(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f, int c,
+                  double *out, int32_t *chosen_out, double *dist_out, int threads) {
+    if (f < 1 || f > 1024 || c < 0 || f < 4 * c + 3) return -1;
+    int used = 1;
+#ifdef _OPENMP
+    if (threads < 1) threads = 1;
+    used = threads;
+#endif
+    const int theta = f - 2 * c, beta = theta - 2 * c;
+    double *dist = (double *)malloc(sizeof(double) * (size_t)f * f);
+    if (!dist) return -2;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic) num_threads(threads)
+#endif
+    for (int p = 0; p < f * f; ++p) {
+        const int i = p / f, j = p % f;
+        const uint32_t *a = X + (int64_t)row_index[i] * ld, *b = X + (int64_t)row_index[j] * ld;
+        double acc = 0.0;
+        for (int64_t t = 0; t < d; ++t) {
+            float x, y;
+            memcpy(&x, a + t, 4);
+            memcpy(&y, b + t, 4);
+            const double diff = (double)x - (double)y;
+            acc += diff * diff;
+        }
+        dist[p] = acc;
+    }
+    if (dist_out) memcpy(dist_out, dist, sizeof(double) * (size_t)f * f);
+    /* phase 1: repeated Krum */
+    int remaining[1024];
+    double others[1024];
+    for (int i = 0; i < f; ++i) remaining[i] = 1;
+    for (int round = 0; round < theta; ++round) {
+        int k = (f - round) - c - 2;
+        if (k < 0) k = 0;
+        int best = -1;
+        double best_score = 0.0;
+        for (int i = 0; i < f; ++i) {
+            if (!remaining[i]) continue;
+            int n = 0;
+            for (int j = 0; j < f; ++j) {
+                if (!remaining[j] || j == i) continue;
+                double v = dist[i * f + j];
+                int t = n - 1;
+                while (t >= 0 && others[t] > v) { others[t + 1] = others[t]; --t; }
+                others[t + 1] = v;
+                ++n;
+            }
+            double score = 0.0;
+            for (int t = 0; t < k; ++t) score += others[t];
+            if (best < 0 || score < best_score) { best = i; best_score = score; }
+        }
+        chosen_out[round] = best;
+        remaining[best] = 0;
+    }
+    free(dist);
+    /* phase 2: mean around the median, coordinate by coordinate */
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) num_threads(threads)
+#endif
+    for (int64_t t = 0; t < d; ++t) {
+        uint32_t key[1024];
+        float s[1024];
+        for (int j = 0; j < theta; ++j)
+            key[j] = order_key(X[(int64_t)row_index[chosen_out[j]] * ld + t]);
+        for (int i = 1; i < theta; ++i) {
+            uint32_t x = key[i];
+            int u = i - 1;
+            while (u >= 0 && key[u] > x) { key[u + 1] = key[u]; --u; }
+            key[u + 1] = x;
+        }
+        for (int j = 0; j < theta; ++j) {
+            uint32_t bits = key_to_bits(key[j]);
+            memcpy(&s[j], &bits, 4);
+        }
+        const int h = (theta - 1) / 2;
+        const float med = s[h];
+        int lo = h, hi = h;
+        for (int step = 1; step < beta; ++step) {
+            const int can_l = lo > 0, can_r = hi < theta - 1;
+            int take_left = 0;
+            if (can_l && !can_r) {
+                take_left = 1;
+            } else if (can_l && can_r) {
+                const float dl = med - s[lo - 1];
+                const float dr = s[hi + 1] - med;
+                take_left = dl <= dr;
+            }
+            if (take_left) --lo; else ++hi;
+        }
+        double acc = 0.0;
+        for (int j = lo; j <= hi; ++j) acc += (double)s[j];
+        out[t] = acc / (double)beta;
     }
     return used;
 }

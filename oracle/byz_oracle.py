@@ -22,6 +22,10 @@ Parity status of each function (what pins it, see tests/test_oracle_*.py):
   median                              numpy sort/median on ordinary data, brute force
   multi_krum                          scipy cdist, hand-worked line example, outlier exclusion
                                       (the paper cites but does not define the rule)
+  bulyan_select, mean_around_median, bulyan
+                                      first pick = Krum (cdist), c = 0 -> plain mean, brute force over
+                                      subsets (closest-to-median set), hand-worked cases, honest-range
+                                      property (the paper cites but does not define the rule)
   trimmed_mean                        scipy.stats.trim_mean, b=0 mean, b=(f-1)/2 median, hand-worked case
   tie-break rules (vote plurality ties -> lowest replica; total order of
   +-0 / NaN in the median; lexicographically first worst-case set):
@@ -376,6 +380,96 @@ def multi_krum(X, row_index, d, c, m):
         if selected[i]:
             acc = acc + V[i]
     return acc / m, selected, scores, dist
+
+
+def bulyan_select(dist, c):
+    """First phase of Bulyan (El Mhamdi, Guerraoui, Rouault 2018; the paper cites it as an
+    aggregator that can take the median's place, Sec. 7, without defining it): Krum is applied
+    again and again to the vectors not yet chosen until theta = n - 2c are chosen.
+
+    One round on the remaining set R (n' = |R|): score(i) = sum of the n' - c - 2 smallest
+    dist[i, j], j in R, j != i (no terms when n' - c - 2 <= 0, which happens in the last rounds:
+    the published rule is silent there; all scores are then 0); the lowest score wins, ties go
+    to the lowest index.  Returns the chosen indices in the order they were chosen.
+    """
+    n = dist.shape[0]
+    assert c >= 0 and n >= 4 * c + 3
+    remaining = list(range(n))
+    chosen = []
+    while len(chosen) < n - 2 * c:
+        k = max(len(remaining) - c - 2, 0)
+        best, best_score = None, None
+        for i in remaining:
+            others = sorted(dist[i, j] for j in remaining if j != i)
+            score = 0.0
+            for v in others[:k]:
+                score += v
+            if best is None or score < best_score:
+                best, best_score = i, score
+        chosen.append(best)
+        remaining.remove(best)
+    return chosen
+
+
+def mean_around_median(values, beta):
+    """Second phase of Bulyan for one coordinate: the beta values closest to the median of
+    `values` (odd count), averaged.  The values are put in the total order of the median
+    kernel; starting from the middle one the window grows one neighbour at a time, taking the
+    lower neighbour when its distance to the median, computed in fp32 as (median - x), is <=
+    the upper neighbour's (x - median) or there is no upper neighbour left (comparisons with
+    NaN are false, as in IEEE arithmetic).  The mean is taken in fp64 over the window in
+    ascending order.  Returns (mean, lo, hi): window = sorted positions lo..hi inclusive.
+    """
+    v = np.asarray(values, dtype=np.float32)
+    n = len(v)
+    assert n % 2 == 1 and 1 <= beta <= n
+    order = np.argsort(order_key(v.view(np.uint32)), kind="stable")
+    s = v[order]
+    h = (n - 1) // 2
+    med = s[h]
+    lo = hi = h
+    with np.errstate(invalid="ignore", over="ignore"):
+        for _ in range(beta - 1):
+            can_l, can_r = lo > 0, hi < n - 1
+            take_left = False
+            if can_l and not can_r:
+                take_left = True
+            elif can_l and can_r:
+                dl = np.float32(med - s[lo - 1])
+                dr = np.float32(s[hi + 1] - med)
+                take_left = bool(dl <= dr)
+            if take_left:
+                lo -= 1
+            else:
+                hi += 1
+        acc = 0.0
+        for t in range(lo, hi + 1):
+            acc += float(s[t])
+    return acc / beta, lo, hi
+
+
+def bulyan(X, row_index, d, c):
+    """Bulyan over the f rows row_index of X with c of them possibly Byzantine (f >= 4c + 3,
+    the requirement Sec. 6.1 of the paper quotes): theta = f - 2c vectors are chosen by
+    repeated Krum (bulyan_select, squared distances in fp64 as sums of squared differences),
+    then every coordinate is the mean of the beta = theta - 2c chosen values closest to their
+    median (mean_around_median).  Returns (out[d] fp64, chosen indices in order, dist[f, f])."""
+    V32 = np.stack([np.ascontiguousarray(X)[int(j), :d] for j in row_index]).astype(np.float32)
+    V = V32.astype(np.float64)
+    f = V.shape[0]
+    assert f >= 4 * c + 3
+    dist = np.zeros((f, f))
+    for i in range(f):
+        for j in range(f):
+            diff = V[i] - V[j]
+            dist[i, j] = float(np.dot(diff, diff))
+    chosen = bulyan_select(dist, c)
+    beta = f - 4 * c
+    out = np.zeros(d)
+    S = V32[chosen]
+    for t in range(d):
+        out[t] = mean_around_median(S[:, t], beta)[0]
+    return out, chosen, dist
 
 
 def aggregate(X, rows, d):

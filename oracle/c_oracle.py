@@ -27,6 +27,10 @@ def lib():
                                           ctypes.c_int, ctypes.POINTER(ctypes.c_double),
                                           ctypes.c_int]
         L.oracle_trimmed_mean.restype = ctypes.c_int
+        L.oracle_bulyan.argtypes = [u32p, ctypes.c_int64, ctypes.c_int64, i32p, ctypes.c_int,
+                                    ctypes.c_int, ctypes.POINTER(ctypes.c_double), i32p,
+                                    ctypes.POINTER(ctypes.c_double), ctypes.c_int]
+        L.oracle_bulyan.restype = ctypes.c_int
         L.oracle_aggregate.argtypes = [u32p, ctypes.c_int64, ctypes.c_int64, i32p, ctypes.c_int,
                                        ctypes.c_int, u32p, i32p, ctypes.c_int]
         L.oracle_aggregate.restype = ctypes.c_int
@@ -90,6 +94,24 @@ def trimmed_mean(X, row_index, d, b, threads=None):
     if rc < 0:
         raise ValueError("oracle_trimmed_mean rc=%d" % rc)
     return out
+
+
+def bulyan(X, row_index, d, c, threads=None):
+    """Returns (out[d] float64, chosen indices in order, dist[f, f] float64)."""
+    U = _u32(X)
+    row_index = np.ascontiguousarray(row_index, dtype=np.int32)
+    f = len(row_index)
+    out = np.zeros(d, dtype=np.float64)
+    chosen = np.zeros(max(f - 2 * int(c), 1), dtype=np.int32)
+    dist = np.zeros((f, f), dtype=np.float64)
+    t = default_threads() if threads is None else threads
+    rc = lib().oracle_bulyan(_ptr(U, ctypes.c_uint32), d, U.shape[1],
+                             _ptr(row_index, ctypes.c_int32), f, int(c),
+                             _ptr(out, ctypes.c_double), _ptr(chosen, ctypes.c_int32),
+                             _ptr(dist, ctypes.c_double), t)
+    if rc < 0:
+        raise ValueError("oracle_bulyan rc=%d" % rc)
+    return out, [int(x) for x in chosen[:f - 2 * int(c)]], dist
 
 
 def aggregate(X, rows, d, threads=None):

@@ -294,3 +294,120 @@ def test_multi_krum_hand_worked_and_invariants():
     assert np.array_equal(mean, V[0].astype(np.float64))
     with pytest.raises(AssertionError):
         O.multi_krum(V, np.arange(6, dtype=np.int32), d, c=2, m=1)  # needs f >= 2c + 3
+
+
+def test_mean_around_median_against_brute_force_and_by_hand():
+    # by hand: values 1 2 3 10 20 (median 3): the 3 closest are {1,2,3} (distances 2,1,0 < 7)
+    m, lo, hi = O.mean_around_median([10, 1, 3, 20, 2], 3)
+    assert (m, lo, hi) == (2.0, 0, 2)
+    # beta = 1: the median itself; beta = n: the plain mean
+    assert O.mean_around_median([10, 1, 3, 20, 2], 1)[0] == 3.0
+    assert O.mean_around_median([10, 1, 3, 20, 2], 5)[0] == 36.0 / 5
+    # tie between a lower and an upper neighbour at the same distance: the lower one is taken
+    assert O.mean_around_median([1, 2, 3, 4, 5], 2)[0] == 2.5
+    assert O.mean_around_median([1, 2, 3, 4, 5], 4)[0] == 2.5   # {3,2,4,1}
+    # brute force: among all subsets of size beta that contain the median element, the chosen
+    # window has the smallest sum of distances to the median (unique when the distances differ)
+    rng = np.random.default_rng(4)
+    for n in (3, 5, 7, 9, 11):
+        for _ in range(20):
+            v = rng.standard_normal(n).astype(np.float32)
+            med = np.median(v)
+            dist = np.abs(v.astype(np.float64) - float(med))
+            for beta in range(1, n + 1):
+                got, lo, hi = O.mean_around_median(v, beta)
+                best = min(itertools.combinations(range(n), beta),
+                           key=lambda S: sum(dist[i] for i in S))
+                assert got == pytest.approx(float(np.mean(v[list(best)].astype(np.float64))), abs=1e-12)
+                assert hi - lo + 1 == beta
+    # special values: the infinities are the farthest, NaNs sort beyond them
+    m, lo, hi = O.mean_around_median([np.inf, 1, 2, 3, -np.inf, 4, np.nan], 3)
+    # sorted: -inf 1 2 3 4 inf nan, median 3 -> window {2,3,4}
+    assert (m, lo, hi) == (3.0, 2, 4)
+
+
+def test_bulyan_selection_and_whole_rule():
+    from scipy.spatial.distance import cdist
+    # points on a line 0 1 2 3 4 5 100, c = 1: theta = 5 picks, beta = 3
+    X = np.array([[0.0], [1.0], [2.0], [3.0], [4.0], [5.0], [100.0]], dtype=np.float32)
+    idx = np.arange(7, dtype=np.int32)
+    out, chosen, dist = O.bulyan(X, idx, 1, 1)
+    # round 1 (n'=7, 4 nearest): scores 0:1+4+9+16=30, 1:1+1+4+9=15, 2:1+1+4+4=10, 3:10, 4:15,
+    #   5:30 -> point 2 (tie with 3: lower index); round 2 on {0,1,3,4,5,100} (3 nearest):
+    #   0:1+9+16=26, 1:1+4+9=14, 3:1+4+4=9, 4:1+1+9=11, 5:1+4+16=21 -> 3; round 3 on
+    #   {0,1,4,5,100} (2 nearest): 0:1+16=17, 1:1+9=10, 4:1+9=10, 5:1+16=17 -> 1; round 4 on
+    #   {0,4,5,100} (1 nearest): 0:16, 4:1, 5:1 -> 4; round 5 on {0,5,100} (0 terms) -> 0
+    assert chosen == [2, 3, 1, 4, 0]
+    # chosen values 0 1 2 3 4, median 2, the 3 closest: {1,2,3}
+    assert out[0] == 2.0
+    # the first pick is Krum's pick (same score rule on the full set), distances as cdist
+    rng = np.random.default_rng(12)
+    f, d, c = 23, 40, 5
+    V = rng.standard_normal((f, d)).astype(np.float32) * rng.uniform(0.5, 2.0, size=(f, 1)).astype(np.float32)
+    bad = [0, 5, 9, 17, 22]
+    V[bad] = 50.0 * rng.standard_normal((len(bad), d)).astype(np.float32)  # far from all, also from each other
+    out, chosen, dist = O.bulyan(V, np.arange(f, dtype=np.int32), d, c)
+    assert np.allclose(dist, cdist(V.astype(np.float64), V.astype(np.float64), "sqeuclidean"),
+                       rtol=1e-12, atol=0)
+    _, sel1, _, _ = O.multi_krum(V, np.arange(f, dtype=np.int32), d, c=c, m=1)
+    assert chosen[0] == int(np.argmax(sel1))
+    assert len(chosen) == f - 2 * c and len(set(chosen)) == len(chosen)
+    assert not set(chosen) & set(bad)                      # far outliers are never chosen
+    good = [i for i in range(f) if i not in bad]
+    assert (out >= V[good].min(axis=0)).all() and (out <= V[good].max(axis=0)).all()
+    # colluding outliers (c identical far vectors) do get chosen in the last rounds, where a
+    # score has at most c - 1 terms and theirs is zero; the per-coordinate phase removes them
+    U = V.copy()
+    U[bad] = 50.0
+    outu, chosenu, _ = O.bulyan(U, np.arange(f, dtype=np.int32), d, c)
+    assert 1 <= len(set(chosenu) & set(bad)) <= c and set(chosenu[:f - 3 * c]).isdisjoint(bad)
+    assert (outu >= U[good].min(axis=0)).all() and (outu <= U[good].max(axis=0)).all()
+    # c = 0: every vector is chosen and every coordinate is the plain mean
+    out0, chosen0, _ = O.bulyan(V, np.arange(f, dtype=np.int32), d, 0)
+    assert sorted(chosen0) == list(range(f))
+    assert np.allclose(out0, V.astype(np.float64).mean(axis=0), rtol=0, atol=1e-12)
+    # identical vectors: lowest indices first, the output is the vector
+    W_ = np.tile(V[1:2], (11, 1))
+    outi, choseni, _ = O.bulyan(W_, np.arange(11, dtype=np.int32), d, 2)
+    assert choseni == list(range(7)) and np.array_equal(outi, V[1].astype(np.float64))
+    # even with c Byzantine vectors chosen, the 2c trimmed per coordinate keep the output inside
+    # the honest range: place the Byzantine vectors close enough to be chosen
+    Z = rng.standard_normal((f, d)).astype(np.float32)
+    Z[bad] = Z[good].mean(axis=0) + 3.0 * np.sign(rng.standard_normal(d)).astype(np.float32)
+    outz, chosenz, _ = O.bulyan(Z, np.arange(f, dtype=np.int32), d, c)
+    assert (outz >= Z[good].min(axis=0)).all() and (outz <= Z[good].max(axis=0)).all()
+    with pytest.raises(AssertionError):
+        O.bulyan(V, np.arange(22, dtype=np.int32), d, 5)    # needs f >= 4c + 3
+
+
+def test_c_oracle_bulyan_equals_the_definition():
+    # the plain-C oracle (used at full sizes) against the NumPy one on the hand-worked line,
+    # on random data with colluding and with scattered outliers, signed zeros and ties
+    X = np.array([[0.0], [1.0], [2.0], [3.0], [4.0], [5.0], [100.0]], dtype=np.float32)
+    out, chosen, _ = C.bulyan(X, np.arange(7, dtype=np.int32), 1, 1)
+    assert chosen == [2, 3, 1, 4, 0] and out[0] == 2.0
+    rng = np.random.default_rng(21)
+    for f, c, d in [(7, 1, 33), (11, 2, 50), (23, 5, 64), (25, 5, 40), (25, 3, 40), (9, 0, 20)]:
+        V = np.zeros((f + 3, d + 5), dtype=np.float32)
+        V[:, :d] = rng.standard_normal((f + 3, d)) * rng.uniform(0.5, 2.0, size=(f + 3, 1))
+        idx = rng.permutation(f + 3)[:f].astype(np.int32)
+        for kind in ("collude", "scatter", "none"):
+            W_ = V.copy()
+            if kind == "collude":
+                W_[idx[:c], :d] = 30.0
+            elif kind == "scatter":
+                W_[idx[:c], :d] = 30.0 * rng.standard_normal((c, d))
+            # signed zeros and exact ties (non-finite values make the distances of the first
+            # phase NaN, for which the rule says nothing: not exercised)
+            W_[idx[-1], 0] = -0.0
+            W_[idx[-2], 0] = 0.0
+            W_[idx[-3], 2] = W_[idx[-1], 2]
+            out_p, chosen_p, dist_p = O.bulyan(W_, idx, d, c)
+            out_c, chosen_c, dist_c = C.bulyan(W_, idx, d, c)
+            finite = np.isfinite(dist_p)
+            assert np.array_equal(finite, np.isfinite(dist_c))
+            assert np.allclose(dist_c[finite], dist_p[finite], rtol=1e-12, atol=0)
+            assert chosen_c == chosen_p, (f, c, kind)
+            assert np.array_equal(np.isnan(out_c), np.isnan(out_p))
+            ok = ~np.isnan(out_p)
+            assert np.allclose(out_c[ok], out_p[ok], rtol=0, atol=1e-12), (f, c, kind)
