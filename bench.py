@@ -204,6 +204,11 @@ def main():
             mk_ws = torch.empty(B.byz_multi_krum_workspace_bytes(asg.f), dtype=torch.uint8, device=dev)
             ms_mk = timed_call(lambda: B.byz_multi_krum(bufs[0], d, wrow_v, cmax, mk_m, out=out,
                                                         workspace=mk_ws, stream=stream))
+        ms_bu, bu_c = None, min(cmax, (asg.f - 3) // 4)
+        if asg.f <= B.BYZ_MAX_F:
+            ms_bu = timed_call(lambda: B.byz_bulyan(bufs[0], d, wrow_v, bu_c, out=out,
+                                                    workspace=mk_ws, stream=stream))
+        bb = 4.0 * asg.f * d + 4.0 * (asg.f - 2 * bu_c + 1) * d  # Gram pass + theta rows + output
         kb = 4.0 * asg.f * d + 4.0 * (mk_m + 1) * d  # Gram pass over f rows + mean of m rows
         vb, mb = 4.0 * asg.r * asg.f * d, 4.0 * (asg.f + 1) * d
         result["components"] = {
@@ -221,6 +226,11 @@ def main():
                 "gbps": kb / ms_mk / 1e6, "frac": kb / ms_mk / 1e6 / HBM_PEAK_GBPS,
                 "gram_tflops": 2.0 * asg.f * asg.f * d / ms_mk / 1e9,
                 "note": "Gram (fp32 MFMA) + reduce + select + mean of m rows"},
+            "byz_bulyan": None if ms_bu is None else {
+                "ms": ms_bu, "c": bu_c, "theta": asg.f - 2 * bu_c, "beta": asg.f - 4 * bu_c,
+                "algorithmic_bytes": bb, "gbps": bb / ms_bu / 1e6,
+                "frac": bb / ms_bu / 1e6 / HBM_PEAK_GBPS,
+                "note": "Gram + reduce + repeated Krum + mean around the median of theta rows"},
             "byz_trimmed_mean": {"ms": ms_tm, "b": cmax, "algorithmic_bytes": mb,
                                  "gbps": mb / ms_tm / 1e6, "frac": mb / ms_tm / 1e6 / HBM_PEAK_GBPS},
         }

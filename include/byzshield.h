@@ -199,6 +199,36 @@ int byz_multi_krum(const float *rows_base, int64_t d, int64_t ld, const int32_t 
                    int f, int c, int m, float *out, int32_t *selected_out, double *scores_out,
                    double *dist_out, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Bulyan over f vectors (named with Multi-Krum in Sec. 6.1 and Sec. 7 as an aggregator for the
+ * vote winners; the rule is the published one): with c of the f vectors possibly Byzantine,
+ * f >= 4c + 3 (the requirement Sec. 6.1 quotes),
+ *   phase 1: theta = f - 2c vectors are chosen by applying Krum again and again to the vectors
+ *            not yet chosen: with n' vectors left, score(i) = sum of the n' - c - 2 smallest
+ *            squared distances from i to the other vectors left (no terms when n' - c - 2 <= 0,
+ *            as in the last rounds); lowest score wins, lowest index among equal scores;
+ *   phase 2: out[t] = mean of the beta = theta - 2c chosen values of coordinate t closest to
+ *            their median: in the total order of byz_median, starting from the middle value
+ *            the window grows one neighbour at a time, the lower one when
+ *            (median - lower) <= (upper - median), both differences in fp32, or when no upper
+ *            neighbour is left.
+ * Arithmetic: distances as in byz_multi_krum (fp32 matrix instructions, fp64 reduction in a
+ * fixed order), scores in fp64 added in ascending order; the mean is fp32, window values added
+ * one by one in ascending order from +0, one IEEE division by float(beta).  Inputs with
+ * non-finite values give NaN distances, for which phase 1 is not specified.
+ *   selected_out  device [f] int32 out: 1 for the theta chosen rows, else 0
+ *   order_out     device [theta] int32 out, may be NULL: indices (into row_index_dev) in the
+ *                 order chosen
+ *   dist_out      device [f*f] double out, may be NULL
+ *   workspace     device, >= byz_bulyan_workspace_bytes(f) bytes, 256-byte aligned
+ * Errors: BYZ_EINVAL (null pointers, f < 4c + 3, f > BYZ_MAX_F, sizes), BYZ_ENOMEM (workspace
+ * too small), BYZ_EDEVICE.
+ */
+size_t byz_bulyan_workspace_bytes(int f);
+int byz_bulyan(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev, int f,
+               int c, float *out, int32_t *selected_out, int32_t *order_out, double *dist_out,
+               void *workspace, size_t workspace_bytes, void *stream);
+
 /* --------------------------------------------------- device: fused vote + median (whole path) */
 
 /* Bytes of device scratch byz_aggregate needs for (f, r); 0 if (f, r) is invalid. */

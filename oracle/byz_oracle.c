@@ -136,6 +136,60 @@ int oracle_trimmed_mean(const uint32_t *X, int64_t d, int64_t ld, const int32_t 
 }
 
 /*
+ * Second phase of Bulyan on its own: for every coordinate the mean (fp64) of the beta values
+ * closest to the median among the theta rows row_index[chosen[0..theta-1]] (theta odd).
+ * The window rule is the one described at oracle_bulyan.  Returns threads used, <0 on error.
+ */
+int oracle_mean_around_median(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index,
+                              const int32_t *chosen, int theta, int beta, double *out,
+                              int threads) {
+    if (theta < 1 || theta > 1024 || (theta % 2) == 0 || beta < 1 || beta > theta) return -1;
+    int used = 1;
+#ifdef _OPENMP
+    if (threads < 1) threads = 1;
+    used = threads;
+#endif
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) num_threads(threads)
+#endif
+    for (int64_t t = 0; t < d; ++t) {
+        uint32_t key[1024];
+        float s[1024];
+        for (int j = 0; j < theta; ++j)
+            key[j] = order_key(X[(int64_t)row_index[chosen[j]] * ld + t]);
+        for (int i = 1; i < theta; ++i) {
+            uint32_t x = key[i];
+            int u = i - 1;
+            while (u >= 0 && key[u] > x) { key[u + 1] = key[u]; --u; }
+            key[u + 1] = x;
+        }
+        for (int j = 0; j < theta; ++j) {
+            uint32_t bits = key_to_bits(key[j]);
+            memcpy(&s[j], &bits, 4);
+        }
+        const int h = (theta - 1) / 2;
+        const float med = s[h];
+        int lo = h, hi = h;
+        for (int step = 1; step < beta; ++step) {
+            const int can_l = lo > 0, can_r = hi < theta - 1;
+            int take_left = 0;
+            if (can_l && !can_r) {
+                take_left = 1;
+            } else if (can_l && can_r) {
+                const float dl = med - s[lo - 1];
+                const float dr = s[hi + 1] - med;
+                take_left = dl <= dr;
+            }
+            if (take_left) --lo; else ++hi;
+        }
+        double acc = 0.0;
+        for (int j = lo; j <= hi; ++j) acc += (double)s[j];
+        out[t] = acc / (double)beta;
+    }
+    return used;
+}
+
+/*
  * Bulyan (El Mhamdi, Guerraoui, Rouault 2018), which Sec. 7 names as an aggregator that can
  * replace the median on the vote winners: theta = f - 2c vectors are chosen by applying Krum
  * again and again to the vectors not yet chosen, then every coordinate is the mean of the
@@ -205,43 +259,9 @@ int oracle_bulyan(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_i
         remaining[best] = 0;
     }
     free(dist);
-    /* phase 2: mean around the median, coordinate by coordinate */
-#ifdef _OPENMP
-#pragma omp parallel for schedule(static) num_threads(threads)
-#endif
-    for (int64_t t = 0; t < d; ++t) {
-        uint32_t key[1024];
-        float s[1024];
-        for (int j = 0; j < theta; ++j)
-            key[j] = order_key(X[(int64_t)row_index[chosen_out[j]] * ld + t]);
-        for (int i = 1; i < theta; ++i) {
-            uint32_t x = key[i];
-            int u = i - 1;
-            while (u >= 0 && key[u] > x) { key[u + 1] = key[u]; --u; }
-            key[u + 1] = x;
-        }
-        for (int j = 0; j < theta; ++j) {
-            uint32_t bits = key_to_bits(key[j]);
-            memcpy(&s[j], &bits, 4);
-        }
-        const int h = (theta - 1) / 2;
-        const float med = s[h];
-        int lo = h, hi = h;
-        for (int step = 1; step < beta; ++step) {
-            const int can_l = lo > 0, can_r = hi < theta - 1;
-            int take_left = 0;
-            if (can_l && !can_r) {
-                take_left = 1;
-            } else if (can_l && can_r) {
-                const float dl = med - s[lo - 1];
-                const float dr = s[hi + 1] - med;
-                take_left = dl <= dr;
-            }
-            if (take_left) --lo; else ++hi;
-        }
-        double acc = 0.0;
-        for (int j = lo; j <= hi; ++j) acc += (double)s[j];
-        out[t] = acc / (double)beta;
+    {
+        int rc2 = oracle_mean_around_median(X, d, ld, row_index, chosen_out, theta, beta, out, threads);
+        if (rc2 < 0) return rc2;
     }
     return used;
 }

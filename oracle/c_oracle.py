@@ -31,6 +31,10 @@ def lib():
                                     ctypes.c_int, ctypes.POINTER(ctypes.c_double), i32p,
                                     ctypes.POINTER(ctypes.c_double), ctypes.c_int]
         L.oracle_bulyan.restype = ctypes.c_int
+        L.oracle_mean_around_median.argtypes = [u32p, ctypes.c_int64, ctypes.c_int64, i32p, i32p,
+                                                ctypes.c_int, ctypes.c_int,
+                                                ctypes.POINTER(ctypes.c_double), ctypes.c_int]
+        L.oracle_mean_around_median.restype = ctypes.c_int
         L.oracle_aggregate.argtypes = [u32p, ctypes.c_int64, ctypes.c_int64, i32p, ctypes.c_int,
                                        ctypes.c_int, u32p, i32p, ctypes.c_int]
         L.oracle_aggregate.restype = ctypes.c_int
@@ -112,6 +116,22 @@ def bulyan(X, row_index, d, c, threads=None):
     if rc < 0:
         raise ValueError("oracle_bulyan rc=%d" % rc)
     return out, [int(x) for x in chosen[:f - 2 * int(c)]], dist
+
+
+def mean_around_median(X, row_index, chosen, d, beta, threads=None):
+    """Second phase of Bulyan on the rows row_index[chosen]: out[d] float64."""
+    U = _u32(X)
+    row_index = np.ascontiguousarray(row_index, dtype=np.int32)
+    chosen = np.ascontiguousarray(chosen, dtype=np.int32)
+    out = np.zeros(d, dtype=np.float64)
+    t = default_threads() if threads is None else threads
+    rc = lib().oracle_mean_around_median(_ptr(U, ctypes.c_uint32), d, U.shape[1],
+                                         _ptr(row_index, ctypes.c_int32),
+                                         _ptr(chosen, ctypes.c_int32), len(chosen), int(beta),
+                                         _ptr(out, ctypes.c_double), t)
+    if rc < 0:
+        raise ValueError("oracle_mean_around_median rc=%d" % rc)
+    return out
 
 
 def aggregate(X, rows, d, threads=None):

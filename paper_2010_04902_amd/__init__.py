@@ -20,6 +20,8 @@ from .binding import (  # noqa: F401
     byz_aggregate_took_exact_path,
     byz_aggregate_workspace_bytes,
     byz_build_assignment,
+    byz_bulyan,
+    byz_bulyan_workspace_bytes,
     byz_calibration_copy,
     byz_gamma_bound,
     byz_median,

@@ -64,6 +64,8 @@ def _load():
         "byz_multi_krum": (c_int, [vp, i64, i64, vp, c_int, c_int, c_int, vp, vp, vp, vp, vp, sz, vp]),
         "byz_aggregate_workspace_bytes": (sz, [c_int, c_int]),
         "byz_aggregate_has_single_pass": (c_int, [c_int, c_int]),
+        "byz_bulyan_workspace_bytes": (sz, [c_int]),
+        "byz_bulyan": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, vp, vp, sz, vp]),
         "byz_aggregate": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, sz, vp]),
         "byz_aggregate_opts": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, sz,
                                        ctypes.c_uint, vp]),
@@ -251,6 +253,35 @@ def byz_multi_krum(rows_base, d, row_index_dev, c, m, out=None, workspace=None, 
                                   _dev_ptr(workspace, ("uint8",), "workspace"),
                                   int(workspace.numel()), _stream_ptr(stream)), "byz_multi_krum")
     return out, selected, scores, dist
+
+
+def byz_bulyan_workspace_bytes(f):
+    return int(_load().byz_bulyan_workspace_bytes(int(f)))
+
+
+def byz_bulyan(rows_base, d, row_index_dev, c, out=None, workspace=None, stream=None):
+    """-> (out[d] float32, selected[f] int32, order[f-2c] int32, dist[f, f] float64), on device."""
+    torch = _torch()
+    ld = _rows_2d(rows_base)
+    f = int(row_index_dev.numel())
+    dev = rows_base.device
+    if out is None:
+        out = torch.empty(int(d), dtype=torch.float32, device=dev)
+    _need(out, int(d), "out")
+    if workspace is None:
+        workspace = torch.empty(max(byz_bulyan_workspace_bytes(f), 256), dtype=torch.uint8, device=dev)
+    selected = torch.empty(f, dtype=torch.int32, device=dev)
+    order = torch.empty(max(f - 2 * int(c), 1), dtype=torch.int32, device=dev)
+    dist = torch.empty((f, f), dtype=torch.float64, device=dev)
+    _check(_load().byz_bulyan(_dev_ptr(rows_base, ("float32",), "rows_base"), int(d), ld,
+                              _dev_ptr(row_index_dev, ("int32",), "row_index_dev"), f, int(c),
+                              _dev_ptr(out, ("float32",), "out"),
+                              _dev_ptr(selected, ("int32",), "selected"),
+                              _dev_ptr(order, ("int32",), "order"),
+                              _dev_ptr(dist, ("float64",), "dist"),
+                              _dev_ptr(workspace, ("uint8",), "workspace"),
+                              int(workspace.numel()), _stream_ptr(stream)), "byz_bulyan")
+    return out, selected, order[:max(f - 2 * int(c), 0)], dist
 
 
 def byz_aggregate_workspace_bytes(f, r):

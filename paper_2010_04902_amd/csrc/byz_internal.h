@@ -5,4 +5,10 @@
 // Records the hipError_t that byz_last_hip_error() reports for the calling thread.
 void byz_internal_set_hip_error(int code);
 
+// Second phase of Bulyan (kernels.hip): out[c] = mean of the beta values closest to the median
+// among the theta rows row_index[selected_list[0..theta-1]].  Returns a byz_status.
+int byz_internal_launch_bulyan_mean(const float *rows_base, long long d, long long ld,
+                                    const int *row_index_dev, const int *selected_list_dev, int f,
+                                    int theta, int beta, float *out, void *stream);
+
 #endif

@@ -395,10 +395,16 @@ __global__ __launch_bounds__(kBlock) void vote_pairs_kernel(
 // of the kernel that includes them: NS slots per file, V words per thread, kAhead, stage, key,
 // o, lane, flags, chain_mask, and BYZ_S_ROW_ADDR(j, k) = address of this thread's vector in
 // slot k of file j.
+// Hooks a kernel may redefine around the include: BYZ_S_LIVE(j) = does file j exist (else its
+// loads are skipped), BYZ_S_KEY(j, x) = key of word x of file j.
+#define BYZ_S_LIVE(j) true
+#define BYZ_S_KEY(j, x) to_key(x)
 #define BYZ_S_LOAD_(j)                                                                        \
-    _Pragma("unroll") for (int k_ = 0; k_ < NS; ++k_)                                         \
-        load_vec<V>(reinterpret_cast<const uint32_t *>(BYZ_S_ROW_ADDR(j, k_)),                \
-                    stage[(j) % (kAhead + 1)][k_]);
+    if (BYZ_S_LIVE(j)) {                                                                      \
+        _Pragma("unroll") for (int k_ = 0; k_ < NS; ++k_)                                     \
+            load_vec<V>(reinterpret_cast<const uint32_t *>(BYZ_S_ROW_ADDR(j, k_)),            \
+                        stage[(j) % (kAhead + 1)][k_]);                                       \
+    }
 #define BYZ_S_LOAD1(j) if constexpr (kAhead == 1) { BYZ_S_LOAD_(j) }
 #define BYZ_S_LOAD2(j) if constexpr (kAhead == 2) { BYZ_S_LOAD_(j) }
 #define BYZ_S_LOAD3(j) if constexpr (kAhead == 3) { BYZ_S_LOAD_(j) }
@@ -419,7 +425,7 @@ __global__ __launch_bounds__(kBlock) void vote_pairs_kernel(
         if (lane == (j)) flags |= wb_;                                                        \
         }                                                                                     \
         _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_)                                      \
-            key[v_][j] = to_key(stage[(j) % (kAhead + 1)][0][v_]);                            \
+            key[v_][j] = BYZ_S_KEY(j, stage[(j) % (kAhead + 1)][0][v_]);                      \
     }
 #define BYZ_S_CE(i, j)                                                                        \
     _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_) {                                        \
@@ -646,6 +652,99 @@ __global__ __launch_bounds__(64) void column_wide_kernel(
         o = __float_as_uint(acc / (float)(f - 2 * b));
     }
     if (c_raw < d) out[c_raw] = o;
+}
+
+// Mean around the median (second phase of Bulyan) for one coordinate whose theta values sit
+// in ascending order in col[0], col[stride], ..: the window starts at the middle value and
+// grows one neighbour at a time, the lower one when (median - lower) <= (upper - median) in
+// fp32 or when no upper one is left; the beta values of the window are added in ascending order
+// from +0 in fp32 and divided by float(beta).
+__device__ __forceinline__ float mean_around_median(const float *col, int stride, int theta,
+                                                    int beta) {
+    const int h = (theta - 1) / 2;
+    const float med = col[h * stride];
+    int lo = h, hi = h;
+    for (int step = 1; step < beta; ++step) {
+        const bool can_l = lo > 0, can_r = hi < theta - 1;
+        const float xl = col[(can_l ? lo - 1 : lo) * stride];
+        const float xr = col[(can_r ? hi + 1 : hi) * stride];
+        const bool take_left = can_l && (!can_r || (med - xl) <= (xr - med));
+        lo -= take_left ? 1 : 0;
+        hi += take_left ? 0 : 1;
+    }
+    float acc = 0.0f;
+    for (int t = 0; t < beta; ++t) acc += col[(lo + t) * stride];
+    return acc / (float)beta;
+}
+
+// Second phase of Bulyan on F candidate rows of which the theta listed in selected_list take
+// part: the streamed full-sort network runs on F wires, wires of rows that take no part are
+// tied to the largest key without loading anything, so wires 0..theta-1 end up holding the
+// chosen values in ascending order.  They go to an LDS column of the thread (word i*kBlock +
+// thread), where the window around the median is found with run-time indices.
+// Thread t owns the words from min(V*t, d - V); needs d >= V.  Dynamic LDS: F*kBlock*4 bytes.
+template <int F, int V>
+__global__ __launch_bounds__(kBlock) void bulyan_mean_kernel(
+    const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
+    const int32_t *__restrict__ selected_list, int theta, int beta, uint32_t *__restrict__ out) {
+    extern __shared__ float s_bulyan_col[];
+    const int64_t n_thr = (d + V - 1) / V;
+    const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (gt >= n_thr) return;
+    const int64_t c0 = gt * V + V <= d ? gt * V : d - V;
+    uint32_t key[V][F];
+    constexpr int NS = 1;
+    constexpr int kAhead = prefetch_depth(F, NS);
+    const uint32_t voff = (uint32_t)(c0 * 4);
+    const char *Xb = reinterpret_cast<const char *>(X);
+    uint32_t stage[kAhead + 1][NS][V];
+    const uint32_t *chain_mask = nullptr;  // unused with one slot per file
+    const int lane = 0;
+    uint32_t flags = 0;
+    (void)chain_mask; (void)lane; (void)flags;
+#undef BYZ_S_LIVE
+#undef BYZ_S_KEY
+#define BYZ_S_LIVE(j) ((j) < theta)
+#define BYZ_S_KEY(j, x) ((j) < theta ? to_key(x) : 0xFFFFFFFFu)
+#define BYZ_S_ROW_ADDR(j, k) \
+    (Xb + (uint64_t)(uint32_t)row_index[selected_list[(j) < theta ? (j) : 0]] * (uint64_t)ld * 4u + voff)
+#include "generated/selnet_sort_stream_dispatch.inc"
+#undef BYZ_S_ROW_ADDR
+#undef BYZ_S_LIVE
+#undef BYZ_S_KEY
+#define BYZ_S_LIVE(j) true
+#define BYZ_S_KEY(j, x) to_key(x)
+    float *col = s_bulyan_col + threadIdx.x;
+    uint32_t o[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+#pragma unroll
+        for (int i = 0; i < F; ++i) col[i * kBlock] = __uint_as_float(from_key(key[v][i]));
+        o[v] = __float_as_uint(mean_around_median(col, kBlock, theta, beta));
+    }
+    store_vec<V>(out + c0, o);
+}
+
+// Second phase of Bulyan for any f <= 64 (and for d < 4): one coordinate a thread, the chosen
+// values insertion-sorted in the thread's LDS column.  Dynamic LDS: theta*kBlock*4 bytes.
+__global__ __launch_bounds__(kBlock) void bulyan_mean_generic_kernel(
+    const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
+    const int32_t *__restrict__ selected_list, int theta, int beta, uint32_t *__restrict__ out) {
+    extern __shared__ float s_bulyan_col[];
+    const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (c >= d) return;
+    uint32_t *kcol = reinterpret_cast<uint32_t *>(s_bulyan_col) + threadIdx.x;
+    for (int j = 0; j < theta; ++j) {
+        const uint32_t x = to_key(X[(int64_t)row_index[selected_list[j]] * ld + c]);
+        int t = j - 1;
+        while (t >= 0 && kcol[t * kBlock] > x) {
+            kcol[(t + 1) * kBlock] = kcol[t * kBlock];
+            --t;
+        }
+        kcol[(t + 1) * kBlock] = x;
+    }
+    for (int j = 0; j < theta; ++j) kcol[j * kBlock] = from_key(kcol[j * kBlock]);
+    out[c] = __float_as_uint(mean_around_median(s_bulyan_col + threadIdx.x, kBlock, theta, beta));
 }
 
 // Probe: compares the copies of every file on a sample of <= kProbe coordinates (kProbe/16 runs
@@ -959,6 +1058,17 @@ int launch_trimmed_mean(const uint32_t *X, int64_t d, int64_t ld, const int32_t 
     return BYZ_OK;
 }
 
+template <int F>
+int launch_bulyan_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index,
+                      const int32_t *selected_list, int theta, int beta, uint32_t *O,
+                      hipStream_t s) {
+    constexpr int V = vec_for(F);
+    bulyan_mean_kernel<F, V><<<blocks_for((d + V - 1) / V), kBlock, (size_t)F * kBlock * 4, s>>>(
+        X, d, ld, row_index, selected_list, theta, beta, O);
+    BYZ_HIP(hipGetLastError());
+    return BYZ_OK;
+}
+
 // (f, r) with a compiled single-pass kernel: MOLS / Ramanujan Case 1 (f = l^2: 9, 25, 49) with
 // r = 3 or 5, and the Ramanujan Case 2 shapes f = m*s with r = s: (15,3), (21,3), (35,5)
 bool has_fused(int f, int r) {
@@ -977,6 +1087,33 @@ int check_common(const void *copies, int64_t d, int64_t ld, const void *rows, in
 }  // namespace
 
 // ---------------------------------------------------------------------------- C-ABI
+
+int byz_internal_launch_bulyan_mean(const float *rows_base, long long d, long long ld,
+                                    const int *row_index_dev, const int *selected_list_dev, int f,
+                                    int theta, int beta, float *out, void *stream) {
+    if (d == 0) return BYZ_OK;
+    if (f < 1 || f > BYZ_MAX_F || theta < 1 || theta > f || (theta % 2) == 0 || beta < 1 ||
+        beta > theta)
+        return BYZ_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    const uint32_t *X = reinterpret_cast<const uint32_t *>(rows_base);
+    uint32_t *O = reinterpret_cast<uint32_t *>(out);
+    if (d >= kVec) {
+        switch (f) {
+            case 9: return launch_bulyan_net<9>(X, d, ld, row_index_dev, selected_list_dev, theta, beta, O, s);
+            case 15: return launch_bulyan_net<15>(X, d, ld, row_index_dev, selected_list_dev, theta, beta, O, s);
+            case 21: return launch_bulyan_net<21>(X, d, ld, row_index_dev, selected_list_dev, theta, beta, O, s);
+            case 25: return launch_bulyan_net<25>(X, d, ld, row_index_dev, selected_list_dev, theta, beta, O, s);
+            case 35: return launch_bulyan_net<35>(X, d, ld, row_index_dev, selected_list_dev, theta, beta, O, s);
+            case 49: return launch_bulyan_net<49>(X, d, ld, row_index_dev, selected_list_dev, theta, beta, O, s);
+            default: break;
+        }
+    }
+    bulyan_mean_generic_kernel<<<blocks_for(d), kBlock, (size_t)theta * kBlock * 4, s>>>(
+        X, d, ld, row_index_dev, selected_list_dev, theta, beta, O);
+    BYZ_HIP(hipGetLastError());
+    return BYZ_OK;
+}
 
 extern "C" int byz_last_hip_error(void) { return g_last_hip_error; }
 

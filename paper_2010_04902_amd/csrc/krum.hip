@@ -227,6 +227,101 @@ __global__ __launch_bounds__(kBlock) void krum_select_kernel(const double *__res
     }
 }
 
+// First phase of Bulyan: Krum applied again and again to the vectors not yet chosen, until
+// theta = f - 2c are chosen.  Round with n' vectors left: score(i) = the n' - c - 2 smallest
+// distances from i to the other vectors left, added one by one in ascending order (no terms
+// when that count is <= 0); lowest score wins, lowest index among equal scores.
+// One block of 256 threads sets up distances and, per row, the other vectors sorted by
+// distance; then the first wave runs the rounds with lane i = vector i: the vectors left are
+// a 64-bit mask in registers, a score is one walk over the lane's sorted row, and the winner
+// comes from a wave-wide butterfly on (score, index).
+__global__ __launch_bounds__(kBlock) void bulyan_select_kernel(const double *__restrict__ gram, int f,
+                                                               int c, double *dist_out,
+                                                               int32_t *selected_out,
+                                                               int32_t *order_out,
+                                                               int32_t *selected_list,
+                                                               int32_t *n_selected) {
+    __shared__ double s_dist[BYZ_MAX_F * BYZ_MAX_F];   // distances, later each row sorted
+    __shared__ double s_sorted[BYZ_MAX_F * (BYZ_MAX_F / 2)];  // staging for the sorted rows
+    __shared__ uint8_t s_nbr[BYZ_MAX_F * BYZ_MAX_F];   // s_nbr[i][t] = t-th nearest other vector
+    const int tid = threadIdx.x;
+    for (int e = tid; e < f * f; e += kBlock) {
+        const int i = e / f, j = e % f;
+        double dij = gram_at(gram, i, i) + gram_at(gram, j, j) - 2.0 * gram_at(gram, i, j);
+        if (dij < 0.0 || j == i) dij = 0.0;
+        s_dist[e] = dij;
+        if (dist_out != nullptr) dist_out[e] = dij;
+    }
+    __syncthreads();
+    // every (i, j) finds the rank of j among row i's other entries (value, then index)
+    for (int e = tid; e < f * f; e += kBlock) {
+        const int i = e / f, j = e % f;
+        if (i == j) continue;
+        const double v = s_dist[e];
+        int rank = 0;
+        for (int k = 0; k < f; ++k) {
+            if (k == i) continue;
+            const double u = s_dist[i * f + k];
+            rank += (u < v || (u == v && k < j)) ? 1 : 0;
+        }
+        s_nbr[i * f + rank] = (uint8_t)j;
+    }
+    __syncthreads();
+    // sort the rows in place, half of the rows at a time through the staging array
+    for (int half = 0; half < 2; ++half) {
+        const int i0 = half * (BYZ_MAX_F / 2);
+        for (int e = tid; e < (BYZ_MAX_F / 2) * f; e += kBlock) {
+            const int i = i0 + e / f, t = e % f;
+            if (i < f && t < f - 1) s_sorted[(i - i0) * f + t] = s_dist[i * f + s_nbr[i * f + t]];
+        }
+        __syncthreads();
+        for (int e = tid; e < (BYZ_MAX_F / 2) * f; e += kBlock) {
+            const int i = i0 + e / f, t = e % f;
+            if (i < f && t < f - 1) s_dist[i * f + t] = s_sorted[(i - i0) * f + t];
+        }
+        __syncthreads();
+    }
+    if (tid < f) selected_out[tid] = 0;
+    if (tid >= 64) return;
+    const int i = tid;
+    const int theta = f - 2 * c;
+    uint64_t left = f == 64 ? ~0ull : ((1ull << f) - 1ull);
+    const double *row = s_dist + i * f;
+    const uint8_t *nbr = s_nbr + i * f;
+    for (int round = 0; round < theta; ++round) {
+        int k = (f - round) - c - 2;
+        if (k < 0) k = 0;
+        double score = __builtin_huge_val();
+        if (i < f && ((left >> i) & 1ull) != 0) {
+            score = 0.0;
+            int n = 0;
+            for (int t = 0; t < f - 1; ++t) {
+                const bool take = ((left >> nbr[t]) & 1ull) != 0 && n < k;
+                if (take) {
+                    score += row[t];
+                    ++n;
+                }
+            }
+        }
+        int best = i;
+        for (int off = 1; off < 64; off <<= 1) {
+            const double o_score = __shfl_xor(score, off, 64);
+            const int o_best = __shfl_xor(best, off, 64);
+            if (o_score < score || (o_score == score && o_best < best)) {
+                score = o_score;
+                best = o_best;
+            }
+        }
+        left &= ~(1ull << best);
+        if (i == 0) {
+            selected_list[round] = best;
+            selected_out[best] = 1;
+            if (order_out != nullptr) order_out[round] = best;
+        }
+    }
+    if (i == 0) *n_selected = theta;
+}
+
 // out[c] = mean of the selected rows: fp32, added one by one in ascending file index starting
 // from +0, one IEEE division by the count.  Thread t owns the words from min(4t, d-4) (d >= 4).
 __global__ __launch_bounds__(kBlock) void selected_mean_kernel(const float *__restrict__ X, int64_t d,
@@ -270,27 +365,9 @@ struct KrumWorkspace {
     float partial[(size_t)kGramBlocks * 3 * kTile];
 };
 
-}  // namespace
-
-extern "C" size_t byz_multi_krum_workspace_bytes(int f) {
-    if (f < 1 || f > BYZ_MAX_F) return 0;
-    return sizeof(KrumWorkspace);
-}
-
-extern "C" int byz_multi_krum(const float *rows_base, int64_t d, int64_t ld,
-                              const int32_t *row_index_dev, int f, int c, int m, float *out,
-                              int32_t *selected_out, double *scores_out, double *dist_out,
-                              void *workspace, size_t workspace_bytes, void *stream) {
-    if (rows_base == nullptr || row_index_dev == nullptr || selected_out == nullptr ||
-        workspace == nullptr || (out == nullptr && d > 0))
-        return BYZ_EINVAL;
-    if (d < 0 || ld < d || d > ((int64_t)1 << 30)) return BYZ_EINVAL;
-    if (f < 3 || f > BYZ_MAX_F || c < 0 || f < 2 * c + 3) return BYZ_EINVAL;  // Sec. 6.1
-    if (m < 1 || m > f - c) return BYZ_EINVAL;
-    if (((uintptr_t)workspace & 255u) != 0) return BYZ_EINVAL;
-    if (workspace_bytes < sizeof(KrumWorkspace)) return BYZ_ENOMEM;
-    hipStream_t s = (hipStream_t)stream;
-    KrumWorkspace *ws = reinterpret_cast<KrumWorkspace *>(workspace);
+// Gram matrix of the f rows into ws->gram (partial tiles, then the fp64 reduction).
+int launch_gram(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev, int f,
+                KrumWorkspace *ws, hipStream_t s) {
     const int nt = f <= 32 ? 1 : 2;
     const int ntiles = nt == 1 ? 1 : 3;
     int64_t n_chunks = (d + kChunk - 1) / kChunk;
@@ -324,6 +401,32 @@ extern "C" int byz_multi_krum(const float *rows_base, int64_t d, int64_t ld,
     BYZ_HIP(hipGetLastError());
     gram_reduce_kernel<<<ntiles * kTile / 32, kBlock, 0, s>>>(ws->partial, grid, ntiles, ws->gram);
     BYZ_HIP(hipGetLastError());
+    return BYZ_OK;
+}
+
+}  // namespace
+
+extern "C" size_t byz_multi_krum_workspace_bytes(int f) {
+    if (f < 1 || f > BYZ_MAX_F) return 0;
+    return sizeof(KrumWorkspace);
+}
+
+extern "C" int byz_multi_krum(const float *rows_base, int64_t d, int64_t ld,
+                              const int32_t *row_index_dev, int f, int c, int m, float *out,
+                              int32_t *selected_out, double *scores_out, double *dist_out,
+                              void *workspace, size_t workspace_bytes, void *stream) {
+    if (rows_base == nullptr || row_index_dev == nullptr || selected_out == nullptr ||
+        workspace == nullptr || (out == nullptr && d > 0))
+        return BYZ_EINVAL;
+    if (d < 0 || ld < d || d > ((int64_t)1 << 30)) return BYZ_EINVAL;
+    if (f < 3 || f > BYZ_MAX_F || c < 0 || f < 2 * c + 3) return BYZ_EINVAL;  // Sec. 6.1
+    if (m < 1 || m > f - c) return BYZ_EINVAL;
+    if (((uintptr_t)workspace & 255u) != 0) return BYZ_EINVAL;
+    if (workspace_bytes < sizeof(KrumWorkspace)) return BYZ_ENOMEM;
+    hipStream_t s = (hipStream_t)stream;
+    KrumWorkspace *ws = reinterpret_cast<KrumWorkspace *>(workspace);
+    int rc = launch_gram(rows_base, d, ld, row_index_dev, f, ws, s);
+    if (rc != BYZ_OK) return rc;
     krum_select_kernel<<<1, kBlock, 0, s>>>(ws->gram, f, c, m, dist_out, scores_out, selected_out,
                                             ws->sorted_rows, ws->selected_list, &ws->n_selected);
     BYZ_HIP(hipGetLastError());
@@ -334,4 +437,29 @@ extern "C" int byz_multi_krum(const float *rows_base, int64_t d, int64_t ld,
         BYZ_HIP(hipGetLastError());
     }
     return BYZ_OK;
+}
+
+extern "C" size_t byz_bulyan_workspace_bytes(int f) { return byz_multi_krum_workspace_bytes(f); }
+
+extern "C" int byz_bulyan(const float *rows_base, int64_t d, int64_t ld,
+                          const int32_t *row_index_dev, int f, int c, float *out,
+                          int32_t *selected_out, int32_t *order_out, double *dist_out,
+                          void *workspace, size_t workspace_bytes, void *stream) {
+    if (rows_base == nullptr || row_index_dev == nullptr || selected_out == nullptr ||
+        workspace == nullptr || (out == nullptr && d > 0))
+        return BYZ_EINVAL;
+    if (d < 0 || ld < d || d > ((int64_t)1 << 30)) return BYZ_EINVAL;
+    if (f < 3 || f > BYZ_MAX_F || c < 0 || f < 4 * c + 3) return BYZ_EINVAL;  // Sec. 6.1
+    if (((uintptr_t)workspace & 255u) != 0) return BYZ_EINVAL;
+    if (workspace_bytes < sizeof(KrumWorkspace)) return BYZ_ENOMEM;
+    hipStream_t s = (hipStream_t)stream;
+    KrumWorkspace *ws = reinterpret_cast<KrumWorkspace *>(workspace);
+    int rc = launch_gram(rows_base, d, ld, row_index_dev, f, ws, s);
+    if (rc != BYZ_OK) return rc;
+    bulyan_select_kernel<<<1, kBlock, 0, s>>>(ws->gram, f, c, dist_out, selected_out, order_out,
+                                              ws->selected_list, &ws->n_selected);
+    BYZ_HIP(hipGetLastError());
+    const int theta = f - 2 * c;
+    return byz_internal_launch_bulyan_mean(rows_base, d, ld, row_index_dev, ws->selected_list, f,
+                                           theta, theta - 2 * c, out, stream);
 }

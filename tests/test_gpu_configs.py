@@ -162,3 +162,15 @@ def test_multi_krum_full_size():
     _, wrow, _ = B.byz_vote(w.X, w.d, rows_dev, w.f, w.r)
     torch.cuda.synchronize()
     _multi_krum_check(w.X, wrow.cpu().numpy(), w.d, cfg.cmax, w.f - cfg.cmax, cfg.name)
+
+
+def test_bulyan_full_size():
+    # Bulyan over the vote winners of workload 2 (f = 25, c = c_max = 5: theta = 15, beta = 5)
+    # at full size, against the plain-C oracle
+    from tests.test_gpu_parity import _bulyan_check
+    cfg = synth.CONFIGS[1]
+    w = W.from_config(cfg, DEV, ld=synth.padded_ld(cfg.d, 64))
+    rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+    _, wrow, _ = B.byz_vote(w.X, w.d, rows_dev, w.f, w.r)
+    torch.cuda.synchronize()
+    _bulyan_check(w.X, wrow.cpu().numpy(), w.d, cfg.cmax, cfg.name, big=True)

@@ -501,3 +501,100 @@ def test_multi_krum_on_the_vote_winners(scheme, a, b, q, attack):
         with pytest.raises(B.ByzError) as e:
             B.byz_multi_krum(w.X, w.d, wrow, c, m)
         assert e.value.code == -1
+
+
+def _bulyan_check(X, idx_np, d, c, tag, big=False, exact_order=False):
+    """GPU Bulyan against the fp64 oracle.
+
+    Distances: tolerance of the Multi-Krum check (fp32 Gram over L products per block).  Phase 1
+    is a chain of argmin decisions on fp64 scores computed from those distances: the order
+    chosen must equal the oracle's whenever, in every round, the oracle's best score is further
+    than twice the score tolerance from its second best; in any case each GPU pick must be
+    within that tolerance of the round's best oracle score (a valid pick).  Phase 2 is checked
+    on the set the GPU chose, against the oracle's mean around the median of that set
+    (fp32 sequential sum of beta values: 1.5 * beta * 2^-24 * max|x|)."""
+    idx_dev = torch.tensor(idx_np, dtype=torch.int32, device=DEV)
+    out, sel, order, dist = B.byz_bulyan(X, d, idx_dev, c)
+    torch.cuda.synchronize()
+    Xh = X.detach().cpu().numpy()
+    f = len(idx_np)
+    theta, beta = f - 2 * c, f - 4 * c
+    out_o, chosen_o, dist_o = (C.bulyan if big else O.bulyan)(Xh, idx_np, d, c)
+    n_chunks = max(1, -(-d // 256))
+    L = -(-n_chunks // min(n_chunks, 512)) * 256
+    norms = np.array([float(np.dot(Xh[j, :d].astype(np.float64), Xh[j, :d].astype(np.float64))) for j in idx_np])
+    tol_d = 2.0 * (L + 8) * 2.0 ** -24 * (norms[:, None] + norms[None, :]) + 1e-300
+    dist_g = dist.cpu().numpy()
+    assert (np.abs(dist_g - dist_o) <= tol_d).all(), tag
+    tol_s = f * tol_d.max()
+    order_g = [int(x) for x in order.cpu().numpy()]
+    sel_g = sel.cpu().numpy()
+    assert len(order_g) == theta and len(set(order_g)) == theta, tag
+    assert sorted(order_g) == [i for i in range(f) if sel_g[i] == 1], tag
+    # replay the rounds along the GPU's picks with the oracle's distances
+    remaining = list(range(f))
+    decisive = True
+    for pick in order_g:
+        k = max(len(remaining) - c - 2, 0)
+        scores = {i: sum(sorted(dist_o[i, j] for j in remaining if j != i)[:k]) for i in remaining}
+        ranked = sorted(remaining, key=lambda i: (scores[i], i))
+        assert scores[pick] <= scores[ranked[0]] + 2 * tol_s, (tag, pick)
+        if len(ranked) > 1 and scores[ranked[1]] - scores[ranked[0]] <= 2 * tol_s and k > 0:
+            decisive = False
+        remaining.remove(pick)
+    if decisive or exact_order:
+        assert order_g == chosen_o, tag
+    chosen = np.array(order_g, dtype=np.int32)
+    if order_g == chosen_o:
+        want = out_o
+    elif big:
+        want = C.mean_around_median(Xh, idx_np, chosen, d, beta)
+    else:
+        want = np.array([O.mean_around_median(Xh[idx_np[chosen], t], beta)[0] for t in range(d)])
+    vmax = np.abs(Xh[idx_np[chosen]][:, :d].astype(np.float64)).max(axis=0)
+    tol_m = 1.5 * beta * 2.0 ** -24 * vmax + 1e-44
+    assert (np.abs(out.cpu().numpy().astype(np.float64) - want) <= tol_m).all(), tag
+    return order_g, chosen_o
+
+
+@pytest.mark.parametrize("scheme,a,b,q,attack", [(MOLS, 5, 3, 4, ALIE), (MOLS, 7, 3, 5, REVERSED),
+                                                 (RAM, 5, 5, 6, MIXED), (RAM, 3, 3, 1, CONST),
+                                                 (RAM, 3, 5, 2, CONST), (RAM, 3, 9, 2, ALIE)])
+def test_bulyan_on_the_vote_winners(scheme, a, b, q, attack):
+    # per-file gradient scales make the honest vectors' scores differ by far more than the fp32
+    # Gram error, so the order chosen is decided and compared exactly in most cases
+    attack = dict(attack, file_scales=True)
+    for i, d in enumerate([1, 3, 4, 257, 5000, 70001]):
+        w = W.make(scheme, a, b, q, d, attack, seed=500 + i, ld=synth.padded_ld(d, 4) + 4 * (i % 2),
+                   device=DEV)
+        rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+        wrep, wrow, _ = B.byz_vote(w.X, d, rows_dev, w.f, w.r)
+        torch.cuda.synchronize()
+        idx = wrow.cpu().numpy()
+        for c in sorted({0, 1, (w.f - 3) // 4}):
+            order_g, chosen_o = _bulyan_check(w.X, idx, d, c, (w.f, d, c))
+    for c in (-1, (w.f - 3) // 4 + 1):  # f < 4c + 3
+        with pytest.raises(B.ByzError) as e:
+            B.byz_bulyan(w.X, w.d, wrow, c)
+        assert e.value.code == -1
+
+
+def test_bulyan_ties_and_identical_vectors():
+    # identical vectors: all distances 0, picks in index order, output = the vector; and a case
+    # with exact ties in the window rule (integers around the median)
+    d, f = 300, 25
+    base = torch.randn(1, d, device=DEV)
+    X = base.repeat(f, 1).contiguous()
+    idx = np.arange(f, dtype=np.int32)
+    out, sel, order, dist = B.byz_bulyan(X, d, torch.tensor(idx, device=DEV), 4)
+    torch.cuda.synchronize()
+    assert order.cpu().tolist() == list(range(f - 8)) and (dist == 0).all()
+    # nine equal values added in fp32 and divided by nine: within a few ulp of the value
+    assert (out - base[0]).abs().max().item() <= 9 * 2.0 ** -24 * base.abs().max().item()
+    # every vector is one distinct small integer (equal in all coordinates): distances, scores
+    # and the fp32 Gram are exact, equal scores abound (lowest index wins), and the window
+    # around the median meets equal distances on both sides (the lower value is taken)
+    vals = np.array([3, -2, 7, 0, 1, -1, 5, 2, -3, 4, 6, -4, 8, -5, 9], dtype=np.float32)
+    Y = torch.tensor(np.repeat(vals[:, None], 16, axis=1), device=DEV)
+    _bulyan_check(Y, np.arange(15, dtype=np.int32), 16, 2, "integer ties", exact_order=True)
+    _bulyan_check(Y, np.arange(15, dtype=np.int32), 16, 3, "integer ties", exact_order=True)

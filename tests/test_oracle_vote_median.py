@@ -411,3 +411,20 @@ def test_c_oracle_bulyan_equals_the_definition():
             assert np.array_equal(np.isnan(out_c), np.isnan(out_p))
             ok = ~np.isnan(out_p)
             assert np.allclose(out_c[ok], out_p[ok], rtol=0, atol=1e-12), (f, c, kind)
+
+
+def test_c_oracle_mean_around_median_equals_the_definition_on_special_values():
+    # phase 2 alone, including infinities, NaNs, signed zeros and many ties
+    rng = np.random.default_rng(33)
+    d, n = 400, 17
+    U = rng.standard_normal((n + 2, d)).astype(np.float32)
+    special = np.array([np.inf, -np.inf, np.nan, 0.0, -0.0, 1.0, 1.0, -1.0], dtype=np.float32)
+    mask = rng.random((n + 2, d)) < 0.3
+    U[mask] = special[rng.integers(0, len(special), size=int(mask.sum()))]
+    row_index = rng.permutation(n + 2).astype(np.int32)
+    for theta, beta in [(17, 1), (17, 5), (17, 17), (9, 4), (3, 2), (1, 1)]:
+        chosen = rng.permutation(n)[:theta].astype(np.int32)
+        got = C.mean_around_median(U, row_index, chosen, d, beta)
+        for t in range(d):
+            want = O.mean_around_median(U[row_index[chosen], t], beta)[0]
+            assert (np.isnan(got[t]) and np.isnan(want)) or got[t] == pytest.approx(want, abs=1e-12), (theta, beta, t)
