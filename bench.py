@@ -20,9 +20,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 
 
-def _traffic_from_profiles(workload):
+def _traffic_from_profiles(workload, kernel="fused_kernel"):
     """HBM bytes per launch from the committed counter summary, or None if absent or stale."""
-    path = os.path.join(ROOT, "profiles", "fused_kernel_%s_hbm_traffic.txt" % workload)
+    path = os.path.join(ROOT, "profiles", "%s_%s_hbm_traffic.txt" % (kernel, workload))
     if not os.path.exists(path):
         return None
     kv = {}
@@ -156,7 +156,7 @@ def main():
             "bound": "hbm", "kernel": kernel_name,
             "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBPS,
-            "traffic": _traffic_from_profiles(cfg.name) if single_pass else None,
+            "traffic": _traffic_from_profiles(cfg.name, "fused_kernel" if single_pass else "vote_pairs_kernel"),
             "algorithmic_bytes_per_launch": kernel_bytes,
             "avg_kernel_ms": avg_ms, "min_kernel_ms": min(kernel_ms), "launches_timed": len(kernel_ms),
         }

@@ -395,16 +395,12 @@ __global__ __launch_bounds__(kBlock) void vote_pairs_kernel(
 // of the kernel that includes them: NS slots per file, V words per thread, kAhead, stage, key,
 // o, lane, flags, chain_mask, and BYZ_S_ROW_ADDR(j, k) = address of this thread's vector in
 // slot k of file j.
-// Hooks a kernel may redefine around the include: BYZ_S_LIVE(j) = does file j exist (else its
-// loads are skipped), BYZ_S_KEY(j, x) = key of word x of file j.
-#define BYZ_S_LIVE(j) true
+// Hook a kernel may redefine around the include: BYZ_S_KEY(j, x) = key of word x of file j.
 #define BYZ_S_KEY(j, x) to_key(x)
 #define BYZ_S_LOAD_(j)                                                                        \
-    if (BYZ_S_LIVE(j)) {                                                                      \
-        _Pragma("unroll") for (int k_ = 0; k_ < NS; ++k_)                                     \
-            load_vec<V>(reinterpret_cast<const uint32_t *>(BYZ_S_ROW_ADDR(j, k_)),            \
-                        stage[(j) % (kAhead + 1)][k_]);                                       \
-    }
+    _Pragma("unroll") for (int k_ = 0; k_ < NS; ++k_)                                         \
+        load_vec<V>(reinterpret_cast<const uint32_t *>(BYZ_S_ROW_ADDR(j, k_)),                \
+                    stage[(j) % (kAhead + 1)][k_]);
 #define BYZ_S_LOAD1(j) if constexpr (kAhead == 1) { BYZ_S_LOAD_(j) }
 #define BYZ_S_LOAD2(j) if constexpr (kAhead == 2) { BYZ_S_LOAD_(j) }
 #define BYZ_S_LOAD3(j) if constexpr (kAhead == 3) { BYZ_S_LOAD_(j) }
@@ -655,38 +651,63 @@ __global__ __launch_bounds__(64) void column_wide_kernel(
 }
 
 // Mean around the median (second phase of Bulyan) for one coordinate whose theta values sit
-// in ascending order in col[0], col[stride], ..: the window starts at the middle value and
-// grows one neighbour at a time, the lower one when (median - lower) <= (upper - median) in
-// fp32 or when no upper one is left; the beta values of the window are added in ascending order
-// from +0 in fp32 and divided by float(beta).
+// in ascending order in col[0], col[stride], ..: the beta values closest to the middle one
+// (the median), added in ascending order from +0 in fp32 and divided by float(beta).
+// Growing the window from the median one neighbour at a time -- the lower one when
+// (median - lower) <= (upper - median) in fp32, or when no upper one is left -- ends, for
+// finite values, at the window that starts at the first position s (from max(0, h-beta+1) to
+// h, h the median's position) whose value is taken before the one beta places above it:
+// s + beta beyond the end, or (median - col[s]) <= (col[s+beta] - median).  That test is
+// false up to s and true from s on (rounded differences stay monotone), so the start is the
+// lowest candidate plus the number of failed tests: independent LDS reads, no chain.
 __device__ __forceinline__ float mean_around_median(const float *col, int stride, int theta,
                                                     int beta) {
     const int h = (theta - 1) / 2;
     const float med = col[h * stride];
-    int lo = h, hi = h;
-    for (int step = 1; step < beta; ++step) {
-        const bool can_l = lo > 0, can_r = hi < theta - 1;
-        const float xl = col[(can_l ? lo - 1 : lo) * stride];
-        const float xr = col[(can_r ? hi + 1 : hi) * stride];
-        const bool take_left = can_l && (!can_r || (med - xl) <= (xr - med));
-        lo -= take_left ? 1 : 0;
-        hi += take_left ? 0 : 1;
+    const int s_min = h - beta + 1 > 0 ? h - beta + 1 : 0;
+    // eight candidates at a time: all their LDS reads first (indices clamped into the column,
+    // results of positions past the last candidate discarded), then the tests
+    int fails = 0;
+    for (int s0 = s_min; s0 < h; s0 += 8) {
+        float xl[8], xr[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int s = s0 + u < h ? s0 + u : h;
+            const int up = s + beta <= theta - 1 ? s + beta : theta - 1;
+            xl[u] = col[s * stride];
+            xr[u] = col[up * stride];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int s = s0 + u;
+            const bool taken = s + beta > theta - 1 || (med - xl[u]) <= (xr[u] - med);
+            fails += (s < h && !taken) ? 1 : 0;
+        }
     }
+    const int lo = s_min + fails;
     float acc = 0.0f;
-    for (int t = 0; t < beta; ++t) acc += col[(lo + t) * stride];
+    for (int t0 = 0; t0 < beta; t0 += 8) {
+        float x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = col[(lo + (t0 + u < beta ? t0 + u : beta - 1)) * stride];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc = t0 + u < beta ? acc + x[u] : acc;
+    }
     return acc / (float)beta;
 }
 
-// Second phase of Bulyan on F candidate rows of which the theta listed in selected_list take
-// part: the streamed full-sort network runs on F wires, wires of rows that take no part are
-// tied to the largest key without loading anything, so wires 0..theta-1 end up holding the
-// chosen values in ascending order.  They go to an LDS column of the thread (word i*kBlock +
-// thread), where the window around the median is found with run-time indices.
-// Thread t owns the words from min(V*t, d - V); needs d >= V.  Dynamic LDS: F*kBlock*4 bytes.
+// Second phase of Bulyan: the theta rows selected_rows[0..theta-1] are sorted per coordinate
+// by the streamed full-sort network on N >= theta wires (N the next generated size); the
+// N - theta spare wires load whatever valid row the table names and are tied to the largest
+// key, so wires 0..theta-1
+// end up holding the chosen values in ascending order.  They go to an LDS column of the thread
+// (word i*kBlock + thread: conflict-free), where the window around the median is found with
+// run-time indices.  Thread t owns the words from min(V*t, d - V); needs d >= V.
+// Dynamic LDS: N*kBlock*4 bytes.
 template <int F, int V>
 __global__ __launch_bounds__(kBlock) void bulyan_mean_kernel(
-    const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
-    const int32_t *__restrict__ selected_list, int theta, int beta, uint32_t *__restrict__ out) {
+    const uint32_t *__restrict__ X, int64_t d, int64_t ld,
+    const int32_t *__restrict__ selected_rows, int theta, int beta, uint32_t *__restrict__ out) {
     extern __shared__ float s_bulyan_col[];
     const int64_t n_thr = (d + V - 1) / V;
     const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
@@ -702,17 +723,12 @@ __global__ __launch_bounds__(kBlock) void bulyan_mean_kernel(
     const int lane = 0;
     uint32_t flags = 0;
     (void)chain_mask; (void)lane; (void)flags;
-#undef BYZ_S_LIVE
 #undef BYZ_S_KEY
-#define BYZ_S_LIVE(j) ((j) < theta)
 #define BYZ_S_KEY(j, x) ((j) < theta ? to_key(x) : 0xFFFFFFFFu)
-#define BYZ_S_ROW_ADDR(j, k) \
-    (Xb + (uint64_t)(uint32_t)row_index[selected_list[(j) < theta ? (j) : 0]] * (uint64_t)ld * 4u + voff)
+#define BYZ_S_ROW_ADDR(j, k) (Xb + (uint64_t)(uint32_t)selected_rows[j] * (uint64_t)ld * 4u + voff)
 #include "generated/selnet_sort_stream_dispatch.inc"
 #undef BYZ_S_ROW_ADDR
-#undef BYZ_S_LIVE
 #undef BYZ_S_KEY
-#define BYZ_S_LIVE(j) true
 #define BYZ_S_KEY(j, x) to_key(x)
     float *col = s_bulyan_col + threadIdx.x;
     uint32_t o[V];
@@ -728,14 +744,14 @@ __global__ __launch_bounds__(kBlock) void bulyan_mean_kernel(
 // Second phase of Bulyan for any f <= 64 (and for d < 4): one coordinate a thread, the chosen
 // values insertion-sorted in the thread's LDS column.  Dynamic LDS: theta*kBlock*4 bytes.
 __global__ __launch_bounds__(kBlock) void bulyan_mean_generic_kernel(
-    const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
-    const int32_t *__restrict__ selected_list, int theta, int beta, uint32_t *__restrict__ out) {
+    const uint32_t *__restrict__ X, int64_t d, int64_t ld,
+    const int32_t *__restrict__ selected_rows, int theta, int beta, uint32_t *__restrict__ out) {
     extern __shared__ float s_bulyan_col[];
     const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (c >= d) return;
     uint32_t *kcol = reinterpret_cast<uint32_t *>(s_bulyan_col) + threadIdx.x;
     for (int j = 0; j < theta; ++j) {
-        const uint32_t x = to_key(X[(int64_t)row_index[selected_list[j]] * ld + c]);
+        const uint32_t x = to_key(X[(int64_t)selected_rows[j] * ld + c]);
         int t = j - 1;
         while (t >= 0 && kcol[t * kBlock] > x) {
             kcol[(t + 1) * kBlock] = kcol[t * kBlock];
@@ -1059,12 +1075,11 @@ int launch_trimmed_mean(const uint32_t *X, int64_t d, int64_t ld, const int32_t 
 }
 
 template <int F>
-int launch_bulyan_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index,
-                      const int32_t *selected_list, int theta, int beta, uint32_t *O,
-                      hipStream_t s) {
+int launch_bulyan_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *selected_rows,
+                      int theta, int beta, uint32_t *O, hipStream_t s) {
     constexpr int V = vec_for(F);
     bulyan_mean_kernel<F, V><<<blocks_for((d + V - 1) / V), kBlock, (size_t)F * kBlock * 4, s>>>(
-        X, d, ld, row_index, selected_list, theta, beta, O);
+        X, d, ld, selected_rows, theta, beta, O);
     BYZ_HIP(hipGetLastError());
     return BYZ_OK;
 }
@@ -1089,8 +1104,8 @@ int check_common(const void *copies, int64_t d, int64_t ld, const void *rows, in
 // ---------------------------------------------------------------------------- C-ABI
 
 int byz_internal_launch_bulyan_mean(const float *rows_base, long long d, long long ld,
-                                    const int *row_index_dev, const int *selected_list_dev, int f,
-                                    int theta, int beta, float *out, void *stream) {
+                                    const int *selected_rows_dev, int f, int theta, int beta,
+                                    float *out, void *stream) {
     if (d == 0) return BYZ_OK;
     if (f < 1 || f > BYZ_MAX_F || theta < 1 || theta > f || (theta % 2) == 0 || beta < 1 ||
         beta > theta)
@@ -1099,18 +1114,16 @@ int byz_internal_launch_bulyan_mean(const float *rows_base, long long d, long lo
     const uint32_t *X = reinterpret_cast<const uint32_t *>(rows_base);
     uint32_t *O = reinterpret_cast<uint32_t *>(out);
     if (d >= kVec) {
-        switch (f) {
-            case 9: return launch_bulyan_net<9>(X, d, ld, row_index_dev, selected_list_dev, theta, beta, O, s);
-            case 15: return launch_bulyan_net<15>(X, d, ld, row_index_dev, selected_list_dev, theta, beta, O, s);
-            case 21: return launch_bulyan_net<21>(X, d, ld, row_index_dev, selected_list_dev, theta, beta, O, s);
-            case 25: return launch_bulyan_net<25>(X, d, ld, row_index_dev, selected_list_dev, theta, beta, O, s);
-            case 35: return launch_bulyan_net<35>(X, d, ld, row_index_dev, selected_list_dev, theta, beta, O, s);
-            case 49: return launch_bulyan_net<49>(X, d, ld, row_index_dev, selected_list_dev, theta, beta, O, s);
-            default: break;
-        }
+        // the smallest generated network that holds the theta chosen rows
+        if (theta <= 9) return launch_bulyan_net<9>(X, d, ld, selected_rows_dev, theta, beta, O, s);
+        if (theta <= 15) return launch_bulyan_net<15>(X, d, ld, selected_rows_dev, theta, beta, O, s);
+        if (theta <= 21) return launch_bulyan_net<21>(X, d, ld, selected_rows_dev, theta, beta, O, s);
+        if (theta <= 25) return launch_bulyan_net<25>(X, d, ld, selected_rows_dev, theta, beta, O, s);
+        if (theta <= 35) return launch_bulyan_net<35>(X, d, ld, selected_rows_dev, theta, beta, O, s);
+        if (theta <= 49) return launch_bulyan_net<49>(X, d, ld, selected_rows_dev, theta, beta, O, s);
     }
     bulyan_mean_generic_kernel<<<blocks_for(d), kBlock, (size_t)theta * kBlock * 4, s>>>(
-        X, d, ld, row_index_dev, selected_list_dev, theta, beta, O);
+        X, d, ld, selected_rows_dev, theta, beta, O);
     BYZ_HIP(hipGetLastError());
     return BYZ_OK;
 }

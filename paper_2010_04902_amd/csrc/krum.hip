@@ -169,44 +169,77 @@ __device__ inline double gram_at(const double *gram, int i, int j) {
     return gram[tile * kTile + v * 64 + l];
 }
 
-// One block of 256 threads: distances (all threads), then scores and selection (thread i < f).
-__global__ __launch_bounds__(kBlock) void krum_select_kernel(const double *__restrict__ gram, int f,
-                                                             int c, int m, double *dist_out,
-                                                             double *scores_out, int32_t *selected_out,
-                                                             double *sorted_rows, int32_t *selected_list,
-                                                             int32_t *n_selected) {
-    __shared__ double s_dist[BYZ_MAX_F * BYZ_MAX_F];
-    __shared__ double s_score[BYZ_MAX_F];
-    __shared__ int32_t s_sel[BYZ_MAX_F];
+// Shared set-up of the selection kernels (one block of 256 threads): squared distances
+// d(i,j) = G_ii + G_jj - 2 G_ij (clamped at 0, exactly 0 on the diagonal) into dist_out, and for
+// every row i its distances to the other vectors in ascending order (value, then index) in
+// s_dist[i*f + t], t < f-1, with the vector they belong to in s_nbr[i*f + t].
+// s_stage: BYZ_MAX_F * BYZ_MAX_F / 2 doubles of scratch.  Ends with a block barrier.
+__device__ __forceinline__ void sorted_distance_rows(const double *__restrict__ gram, int f,
+                                                     double *dist_out, double *s_dist,
+                                                     double *s_stage, uint8_t *s_nbr) {
     const int tid = threadIdx.x;
+    double *s_diag = s_stage;  // G_ii once per vector instead of two loads per pair
+    if (tid < f) s_diag[tid] = gram_at(gram, tid, tid);
+    __syncthreads();
+#pragma unroll 4
     for (int e = tid; e < f * f; e += kBlock) {
         const int i = e / f, j = e % f;
-        double dij = gram_at(gram, i, i) + gram_at(gram, j, j) - 2.0 * gram_at(gram, i, j);
+        double dij = s_diag[i] + s_diag[j] - 2.0 * gram_at(gram, i, j);
         if (dij < 0.0 || j == i) dij = 0.0;
         s_dist[e] = dij;
         if (dist_out != nullptr) dist_out[e] = dij;
     }
     __syncthreads();
-    // sorted_rows[i][rank] = distance of rank `rank` among row i's distances to the others
-    // (value, then index, orders them): every (i, j) finds its own rank, all threads at work
+    // every (i, j) finds the rank of j among row i's other entries
     for (int e = tid; e < f * f; e += kBlock) {
         const int i = e / f, j = e % f;
         if (i == j) continue;
         const double v = s_dist[e];
         int rank = 0;
+#pragma unroll 8
         for (int k = 0; k < f; ++k) {
-            if (k == i) continue;
             const double u = s_dist[i * f + k];
-            rank += (u < v || (u == v && k < j)) ? 1 : 0;
+            rank += (k != i && (u < v || (u == v && k < j))) ? 1 : 0;
         }
-        sorted_rows[i * f + rank] = v;
+        s_nbr[i * f + rank] = (uint8_t)j;
     }
     __syncthreads();
+    // sort the rows in place, half of the rows at a time through the staging array
+    for (int half = 0; half < 2; ++half) {
+        const int i0 = half * (BYZ_MAX_F / 2);
+        for (int e = tid; e < (BYZ_MAX_F / 2) * f; e += kBlock) {
+            const int i = i0 + e / f, t = e % f;
+            if (i < f && t < f - 1) s_stage[(i - i0) * f + t] = s_dist[i * f + s_nbr[i * f + t]];
+        }
+        __syncthreads();
+        for (int e = tid; e < (BYZ_MAX_F / 2) * f; e += kBlock) {
+            const int i = i0 + e / f, t = e % f;
+            if (i < f && t < f - 1) s_dist[i * f + t] = s_stage[(i - i0) * f + t];
+        }
+        __syncthreads();
+    }
+}
+
+// One block of 256 threads: sorted distance rows (all threads), then scores and selection
+// (thread i < f).
+__global__ __launch_bounds__(kBlock) void krum_select_kernel(const double *__restrict__ gram, int f,
+                                                             int c, int m, double *dist_out,
+                                                             double *scores_out, int32_t *selected_out,
+                                                             int32_t *selected_list,
+                                                             int32_t *n_selected) {
+    __shared__ double s_dist[BYZ_MAX_F * BYZ_MAX_F];
+    __shared__ double s_stage[BYZ_MAX_F * (BYZ_MAX_F / 2)];
+    __shared__ uint8_t s_nbr[BYZ_MAX_F * BYZ_MAX_F];
+    __shared__ double s_score[BYZ_MAX_F];
+    __shared__ int32_t s_sel[BYZ_MAX_F];
+    const int tid = threadIdx.x;
+    sorted_distance_rows(gram, f, dist_out, s_dist, s_stage, s_nbr);
     const int i = tid;
     if (i < f) {
         // score = the f-c-2 smallest distances to others, added one by one in ascending order
         double score = 0.0;
-        for (int t = 0; t < f - c - 2; ++t) score += sorted_rows[i * f + t];
+#pragma unroll 8
+        for (int t = 0; t < f - c - 2; ++t) score += s_dist[i * f + t];
         s_score[i] = score;
         if (scores_out != nullptr) scores_out[i] = score;
     }
@@ -231,76 +264,56 @@ __global__ __launch_bounds__(kBlock) void krum_select_kernel(const double *__res
 // theta = f - 2c are chosen.  Round with n' vectors left: score(i) = the n' - c - 2 smallest
 // distances from i to the other vectors left, added one by one in ascending order (no terms
 // when that count is <= 0); lowest score wins, lowest index among equal scores.
-// One block of 256 threads sets up distances and, per row, the other vectors sorted by
-// distance; then the first wave runs the rounds with lane i = vector i: the vectors left are
-// a 64-bit mask in registers, a score is one walk over the lane's sorted row, and the winner
-// comes from a wave-wide butterfly on (score, index).
+// One block of 256 threads sets up the sorted distance rows; then the first wave runs the
+// rounds with lane i = vector i: the vectors left are a 64-bit mask in registers, a score is
+// one walk over the lane's sorted row (held in registers), and the winner comes from a
+// wave-wide butterfly on (score, index).
 __global__ __launch_bounds__(kBlock) void bulyan_select_kernel(const double *__restrict__ gram, int f,
                                                                int c, double *dist_out,
                                                                int32_t *selected_out,
                                                                int32_t *order_out,
                                                                int32_t *selected_list,
-                                                               int32_t *n_selected) {
-    __shared__ double s_dist[BYZ_MAX_F * BYZ_MAX_F];   // distances, later each row sorted
-    __shared__ double s_sorted[BYZ_MAX_F * (BYZ_MAX_F / 2)];  // staging for the sorted rows
-    __shared__ uint8_t s_nbr[BYZ_MAX_F * BYZ_MAX_F];   // s_nbr[i][t] = t-th nearest other vector
+                                                               int32_t *n_selected,
+                                                               const int32_t *__restrict__ row_index,
+                                                               int32_t *selected_rows) {
+    __shared__ double s_dist[BYZ_MAX_F * BYZ_MAX_F];
+    __shared__ double s_stage[BYZ_MAX_F * (BYZ_MAX_F / 2)];
+    __shared__ uint8_t s_nbr[BYZ_MAX_F * BYZ_MAX_F];
     const int tid = threadIdx.x;
-    for (int e = tid; e < f * f; e += kBlock) {
-        const int i = e / f, j = e % f;
-        double dij = gram_at(gram, i, i) + gram_at(gram, j, j) - 2.0 * gram_at(gram, i, j);
-        if (dij < 0.0 || j == i) dij = 0.0;
-        s_dist[e] = dij;
-        if (dist_out != nullptr) dist_out[e] = dij;
-    }
-    __syncthreads();
-    // every (i, j) finds the rank of j among row i's other entries (value, then index)
-    for (int e = tid; e < f * f; e += kBlock) {
-        const int i = e / f, j = e % f;
-        if (i == j) continue;
-        const double v = s_dist[e];
-        int rank = 0;
-        for (int k = 0; k < f; ++k) {
-            if (k == i) continue;
-            const double u = s_dist[i * f + k];
-            rank += (u < v || (u == v && k < j)) ? 1 : 0;
-        }
-        s_nbr[i * f + rank] = (uint8_t)j;
-    }
-    __syncthreads();
-    // sort the rows in place, half of the rows at a time through the staging array
-    for (int half = 0; half < 2; ++half) {
-        const int i0 = half * (BYZ_MAX_F / 2);
-        for (int e = tid; e < (BYZ_MAX_F / 2) * f; e += kBlock) {
-            const int i = i0 + e / f, t = e % f;
-            if (i < f && t < f - 1) s_sorted[(i - i0) * f + t] = s_dist[i * f + s_nbr[i * f + t]];
-        }
-        __syncthreads();
-        for (int e = tid; e < (BYZ_MAX_F / 2) * f; e += kBlock) {
-            const int i = i0 + e / f, t = e % f;
-            if (i < f && t < f - 1) s_dist[i * f + t] = s_sorted[(i - i0) * f + t];
-        }
-        __syncthreads();
-    }
+    sorted_distance_rows(gram, f, dist_out, s_dist, s_stage, s_nbr);
     if (tid < f) selected_out[tid] = 0;
     if (tid >= 64) return;
     const int i = tid;
     const int theta = f - 2 * c;
     uint64_t left = f == 64 ? ~0ull : ((1ull << f) - 1ull);
-    const double *row = s_dist + i * f;
-    const uint8_t *nbr = s_nbr + i * f;
+    int first = 0;
+    // the lane's sorted row in registers: distance and index of its t-th nearest other vector
+    constexpr int kMaxOthers = BYZ_MAX_F - 1;
+    double rdist[kMaxOthers];
+    uint32_t rnbr[kMaxOthers];
+#pragma unroll
+    for (int t = 0; t < kMaxOthers; ++t) {
+        const bool have = i < f && t < f - 1;
+        rdist[t] = have ? s_dist[i * f + t] : 0.0;
+        rnbr[t] = have ? s_nbr[i * f + t] : 0u;
+    }
     for (int round = 0; round < theta; ++round) {
         int k = (f - round) - c - 2;
         if (k < 0) k = 0;
-        double score = __builtin_huge_val();
-        if (i < f && ((left >> i) & 1ull) != 0) {
-            score = 0.0;
-            int n = 0;
-            for (int t = 0; t < f - 1; ++t) {
-                const bool take = ((left >> nbr[t]) & 1ull) != 0 && n < k;
-                if (take) {
-                    score += row[t];
-                    ++n;
+        const bool mine = i < f && ((left >> i) & 1ull) != 0;
+        double score = mine ? 0.0 : __builtin_huge_val();
+        int n = mine ? 0 : k;
+        bool done = false;
+#pragma unroll
+        for (int t0 = 0; t0 < kMaxOthers; t0 += 16) {
+            if (!done && t0 < f - 1) {
+#pragma unroll
+                for (int t = t0; t < t0 + 16 && t < kMaxOthers; ++t) {
+                    const bool take = t < f - 1 && ((left >> rnbr[t]) & 1ull) != 0 && n < k;
+                    score += take ? rdist[t] : 0.0;
+                    n += take ? 1 : 0;
                 }
+                done = __builtin_amdgcn_ballot_w64(n < k) == 0;  // every lane has its k terms
             }
         }
         int best = i;
@@ -313,12 +326,16 @@ __global__ __launch_bounds__(kBlock) void bulyan_select_kernel(const double *__r
             }
         }
         left &= ~(1ull << best);
+        if (round == 0) first = best;
         if (i == 0) {
             selected_list[round] = best;
+            selected_rows[round] = row_index[best];
             selected_out[best] = 1;
             if (order_out != nullptr) order_out[round] = best;
         }
     }
+    // rows of the chosen vectors for the second phase; the spare entries repeat the first one
+    if (i >= theta) selected_rows[i] = row_index[first];
     if (i == 0) *n_selected = theta;
 }
 
@@ -358,10 +375,10 @@ __global__ __launch_bounds__(kBlock) void selected_mean_kernel(const float *__re
 
 struct KrumWorkspace {
     double gram[3 * kTile];
-    double sorted_rows[BYZ_MAX_F * BYZ_MAX_F];
     int32_t selected_list[BYZ_MAX_F];
+    int32_t selected_rows[BYZ_MAX_F];  // Bulyan: rows of the chosen vectors, spare entries valid
     int32_t n_selected;
-    int32_t pad[63];
+    int32_t pad[63 + BYZ_MAX_F];
     float partial[(size_t)kGramBlocks * 3 * kTile];
 };
 
@@ -428,7 +445,7 @@ extern "C" int byz_multi_krum(const float *rows_base, int64_t d, int64_t ld,
     int rc = launch_gram(rows_base, d, ld, row_index_dev, f, ws, s);
     if (rc != BYZ_OK) return rc;
     krum_select_kernel<<<1, kBlock, 0, s>>>(ws->gram, f, c, m, dist_out, scores_out, selected_out,
-                                            ws->sorted_rows, ws->selected_list, &ws->n_selected);
+                                            ws->selected_list, &ws->n_selected);
     BYZ_HIP(hipGetLastError());
     if (d > 0) {
         const int64_t n_thr = d >= 4 ? (d + 3) / 4 : d;
@@ -457,9 +474,10 @@ extern "C" int byz_bulyan(const float *rows_base, int64_t d, int64_t ld,
     int rc = launch_gram(rows_base, d, ld, row_index_dev, f, ws, s);
     if (rc != BYZ_OK) return rc;
     bulyan_select_kernel<<<1, kBlock, 0, s>>>(ws->gram, f, c, dist_out, selected_out, order_out,
-                                              ws->selected_list, &ws->n_selected);
+                                              ws->selected_list, &ws->n_selected, row_index_dev,
+                                              ws->selected_rows);
     BYZ_HIP(hipGetLastError());
     const int theta = f - 2 * c;
-    return byz_internal_launch_bulyan_mean(rows_base, d, ld, row_index_dev, ws->selected_list, f,
-                                           theta, theta - 2 * c, out, stream);
+    return byz_internal_launch_bulyan_mean(rows_base, d, ld, ws->selected_rows, f, theta,
+                                           theta - 2 * c, out, stream);
 }
