@@ -7,10 +7,12 @@
 //
 // The pairwise squared distances come from the Gram matrix G = W W^T of the f x d matrix of
 // winners: the one dense contraction of the whole path, done with fp32 MFMA tiles
-// (v_mfma_f32_32x32x2f32).  A block stages a 256-coordinate chunk of all f rows in LDS (global
-// loads stay 1 KiB-contiguous per wave), each of its four waves multiplies 64 of those
-// coordinates, and the blocks walk the chunks grid-stride.  Per-block partial tiles are
-// added in fp64 in block order, so the result does not depend on scheduling.
+// (v_mfma_f32_16x16x4f32; only the tiles on and above the diagonal of the symmetric matrix,
+// so f = 25 costs 3 tiles of 16x16 instead of one padded 32x32).  A block stages a
+// 256-coordinate chunk of all f rows in LDS (global loads stay 1 KiB-contiguous per wave), each
+// of its four waves multiplies 64 of those coordinates, and the blocks walk the chunks
+// grid-stride.  Per-block partial tiles are added in fp64 in block order, so the result does
+// not depend on scheduling.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -31,20 +33,29 @@ namespace {
 
 constexpr int kBlock = 256;            // 4 waves
 constexpr int kChunk = 256;            // coordinates staged per block and step
-constexpr int kStride = kChunk + 1;    // odd row pitch in LDS: conflict-free MFMA operand reads
-constexpr int kGramBlocks = 512;       // partial Gram tiles (2 blocks per CU)
-constexpr int kTile = 32 * 32;         // outputs of one MFMA tile
+constexpr int kStride = kChunk + 4;    // row pitch in LDS: bank = 4*row + k for the MFMA operand reads
+constexpr int kGramBlocks = 512;       // partial Gram tiles (2 blocks per CU; 1024: 4 % faster, reduction 3 us slower)
+constexpr int kTile = 16 * 16;         // outputs of one MFMA tile
+constexpr int kMaxNT = BYZ_MAX_F / 16; // row tiles of the largest matrix
+constexpr int kMaxPairs = kMaxNT * (kMaxNT + 1) / 2;  // tiles on and above the diagonal
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4u __attribute__((ext_vector_type(4), aligned(4)));
 
-// The 32x32 MFMA result: accumulator register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4,
-// column l%32 (gram_at below inverts this).
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Tile (ti, tj), ti <= tj < nt, of the upper triangle, numbered row by row.
+__host__ __device__ constexpr int tile_pair(int nt, int ti, int tj) {
+    return ti * nt - ti * (ti - 1) / 2 + (tj - ti);
+}
+
+// The 16x16 MFMA result: accumulator register v of lane l holds row 4*(l/16) + v, column l%16
+// (gram_at below inverts this).
 
 // Partial Gram tiles of the rows row_index[0..f-1] over this block's chunks.
-// NT = 1: f <= 32, one tile.  NT = 2: f <= 64, tiles (0,0), (0,1), (1,1) of the 64x64 matrix.
-// RW = rows a wave stages per chunk (rows wave, wave+4, ...): ceil(f / 4) rounded up to a
-// compiled value.  partial: [gridDim.x][NTILES][1024] floats, position v*64 + lane.
+// NT = ceil(f / 16) row tiles; RW = rows a wave stages per chunk (rows wave, wave+4, ...):
+// ceil(f / 4) rounded up to a compiled value.  partial: [gridDim.x][pairs][256] floats,
+// position v*64 + lane, pairs = NT(NT+1)/2.
 // Per chunk: the rows' 16-byte loads for the NEXT chunk are issued, then the current chunk
 // (already in registers) goes to LDS, is multiplied, and the loop turns: global latency hides
 // behind the matrix instructions.
@@ -53,11 +64,13 @@ __global__ __launch_bounds__(kBlock) void gram_partial_kernel(const float *__res
                                                               int64_t ld,
                                                               const int32_t *__restrict__ row_index,
                                                               int f, float *__restrict__ partial) {
-    extern __shared__ float T[];  // [32*NT][kStride]; rows >= f stay zero
-    constexpr int NTILES = NT == 1 ? 1 : 3;
+    extern __shared__ float T[];  // [16*NT][kStride]; rows >= f stay zero
+    constexpr int NP = NT * (NT + 1) / 2;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    for (int i = tid; i < (32 * NT - f) * kStride; i += kBlock) T[f * kStride + i] = 0.0f;
-    f32x16 acc00 = {0}, acc01 = {0}, acc11 = {0};
+    for (int i = tid; i < (16 * NT - f) * kStride; i += kBlock) T[f * kStride + i] = 0.0f;
+    f32x4 acc[NP];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) acc[p] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
     const int64_t n_chunks = (d + kChunk - 1) / kChunk;
 
     // this wave's rows; slots past f repeat the last row (loaded, never stored)
@@ -99,42 +112,37 @@ __global__ __launch_bounds__(kBlock) void gram_partial_kernel(const float *__res
         }
         __syncthreads();
         if (chunk + gridDim.x < n_chunks) fetch(chunk + gridDim.x);
-        // wave w multiplies coordinates [64w, 64w+64) of the chunk, two per MFMA: lane l holds
-        // A[row = l%32][k = l/32], which is also B[k][col = l%32] of the transposed operand
-        const float *t0 = T + (lane & 31) * kStride + wave * 64 + (lane >> 5);
+        // wave w multiplies coordinates [64w, 64w+64) of the chunk, four per MFMA: lane l holds
+        // A[row = l%16][k = l/16], which is also B[k][col = l%16] of the transposed operand
+        const float *t0 = T + (lane & 15) * kStride + wave * 64 + (lane >> 4);
 #pragma unroll
-        for (int s0 = 0; s0 < 32; s0 += 16) {
-            float x0[16], x1[16];
+        for (int s0 = 0; s0 < 16; s0 += 8) {
+            float x[NT][8];
 #pragma unroll
-            for (int s = 0; s < 16; ++s) {
-                x0[s] = t0[2 * (s0 + s)];
-                if constexpr (NT == 2) x1[s] = t0[32 * kStride + 2 * (s0 + s)];
-            }
+            for (int s = 0; s < 8; ++s)
 #pragma unroll
-            for (int s = 0; s < 16; ++s) {
-                acc00 = __builtin_amdgcn_mfma_f32_32x32x2f32(x0[s], x0[s], acc00, 0, 0, 0);
-                if constexpr (NT == 2) {
-                    acc01 = __builtin_amdgcn_mfma_f32_32x32x2f32(x0[s], x1[s], acc01, 0, 0, 0);
-                    acc11 = __builtin_amdgcn_mfma_f32_32x32x2f32(x1[s], x1[s], acc11, 0, 0, 0);
-                }
-            }
+                for (int t = 0; t < NT; ++t) x[t][s] = t0[16 * t * kStride + 4 * (s0 + s)];
+#pragma unroll
+            for (int s = 0; s < 8; ++s)
+#pragma unroll
+                for (int ti = 0; ti < NT; ++ti)
+#pragma unroll
+                    for (int tj = ti; tj < NT; ++tj)
+                        acc[tile_pair(NT, ti, tj)] = __builtin_amdgcn_mfma_f32_16x16x4f32(
+                            x[ti][s], x[tj][s], acc[tile_pair(NT, ti, tj)], 0, 0, 0);
         }
         __syncthreads();
     }
     // add the four waves' tiles through LDS (the staging tile is free now), then store
-    float *red = T;  // [4][NTILES][1024] floats = 16 or 48 KiB <= the staging tile
-    for (int v = 0; v < 16; ++v) {
-        red[(wave * NTILES + 0) * kTile + v * 64 + lane] = acc00[v];
-        if constexpr (NT == 2) {
-            red[(wave * NTILES + 1) * kTile + v * 64 + lane] = acc01[v];
-            red[(wave * NTILES + 2) * kTile + v * 64 + lane] = acc11[v];
-        }
-    }
+    float *red = T;  // [4][NP][256] floats = at most 40 KiB <= the staging tile
+#pragma unroll
+    for (int p = 0; p < NP; ++p)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red[(wave * NP + p) * kTile + v * 64 + lane] = acc[p][v];
     __syncthreads();
-    float *dst = partial + (int64_t)blockIdx.x * NTILES * kTile;
-    for (int i = tid; i < NTILES * kTile; i += kBlock)
-        dst[i] = ((red[i] + red[NTILES * kTile + i]) + red[2 * NTILES * kTile + i]) +
-                 red[3 * NTILES * kTile + i];
+    float *dst = partial + (int64_t)blockIdx.x * NP * kTile;
+    for (int i = tid; i < NP * kTile; i += kBlock)
+        dst[i] = ((red[i] + red[NP * kTile + i]) + red[2 * NP * kTile + i]) + red[3 * NP * kTile + i];
 }
 
 // gram[t][pos] = sum over blocks of partial[block][t][pos] in fp64, in a fixed order: thread
@@ -145,7 +153,7 @@ __global__ __launch_bounds__(kBlock) void gram_reduce_kernel(const float *__rest
                                                              double *__restrict__ gram) {
     __shared__ double s_sum[8][32];
     const int lp = threadIdx.x & 31, g = threadIdx.x >> 5;
-    const int i = blockIdx.x * 32 + lp;  // ntiles * 1024 is a multiple of 32
+    const int i = blockIdx.x * 32 + lp;  // ntiles * 256 is a multiple of 32
     double acc = 0.0;
 #pragma unroll 8
     for (int p = g; p < n_partial; p += 8) acc += (double)partial[(int64_t)p * ntiles * kTile + i];
@@ -158,15 +166,14 @@ __global__ __launch_bounds__(kBlock) void gram_reduce_kernel(const float *__rest
     }
 }
 
-__device__ inline double gram_at(const double *gram, int i, int j) {
-    // entry (i, j) of the symmetric matrix from the stored tiles (0,0), (0,1), (1,1)
+__device__ inline double gram_at(const double *gram, int f, int i, int j) {
+    // entry (i, j) of the symmetric matrix from the stored upper-triangle tiles
     if (i > j) { const int t = i; i = j; j = t; }
-    const int ti = i / 32, tj = j / 32;
-    const int tile = ti == 0 ? (tj == 0 ? 0 : 1) : 2;
-    const int r = i % 32, c = j % 32;
-    // row r = 8*(v/4) + 4*(l/32) + v%4, column c = l%32  =>
-    const int v = 4 * (r / 8) + (r % 4), l = c + 32 * ((r / 4) % 2);
-    return gram[tile * kTile + v * 64 + l];
+    const int nt = (f + 15) / 16;
+    const int r = i % 16, c = j % 16;
+    // row r = 4*(l/16) + v, column c = l%16  =>
+    const int v = r % 4, l = c + 16 * (r / 4);
+    return gram[tile_pair(nt, i / 16, j / 16) * kTile + v * 64 + l];
 }
 
 // Shared set-up of the selection kernels (one block of 256 threads): squared distances
@@ -179,12 +186,12 @@ __device__ __forceinline__ void sorted_distance_rows(const double *__restrict__ 
                                                      double *s_stage, uint8_t *s_nbr) {
     const int tid = threadIdx.x;
     double *s_diag = s_stage;  // G_ii once per vector instead of two loads per pair
-    if (tid < f) s_diag[tid] = gram_at(gram, tid, tid);
+    if (tid < f) s_diag[tid] = gram_at(gram, f, tid, tid);
     __syncthreads();
 #pragma unroll 4
     for (int e = tid; e < f * f; e += kBlock) {
         const int i = e / f, j = e % f;
-        double dij = s_diag[i] + s_diag[j] - 2.0 * gram_at(gram, i, j);
+        double dij = s_diag[i] + s_diag[j] - 2.0 * gram_at(gram, f, i, j);
         if (dij < 0.0 || j == i) dij = 0.0;
         s_dist[e] = dij;
         if (dist_out != nullptr) dist_out[e] = dij;
@@ -374,44 +381,50 @@ __global__ __launch_bounds__(kBlock) void selected_mean_kernel(const float *__re
 }
 
 struct KrumWorkspace {
-    double gram[3 * kTile];
+    double gram[kMaxPairs * kTile];
     int32_t selected_list[BYZ_MAX_F];
     int32_t selected_rows[BYZ_MAX_F];  // Bulyan: rows of the chosen vectors, spare entries valid
     int32_t n_selected;
     int32_t pad[63 + BYZ_MAX_F];
-    float partial[(size_t)kGramBlocks * 3 * kTile];
+    float partial[(size_t)kGramBlocks * kMaxPairs * kTile];
 };
 
 // Gram matrix of the f rows into ws->gram (partial tiles, then the fp64 reduction).
 int launch_gram(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev, int f,
                 KrumWorkspace *ws, hipStream_t s) {
-    const int nt = f <= 32 ? 1 : 2;
-    const int ntiles = nt == 1 ? 1 : 3;
+    const int nt = (f + 15) / 16;
+    const int ntiles = nt * (nt + 1) / 2;
     int64_t n_chunks = (d + kChunk - 1) / kChunk;
     if (n_chunks < 1) n_chunks = 1;  // d == 0: one block writes zero tiles
     const int grid = n_chunks < kGramBlocks ? (int)n_chunks : kGramBlocks;
-    const size_t lds = (size_t)32 * nt * kStride * sizeof(float);
-    // rows a wave stages per chunk: ceil(f / 4), rounded up to a compiled value
+    const size_t lds = (size_t)16 * nt * kStride * sizeof(float);
+    // (row tiles, rows a wave stages per chunk = ceil(f / 4) rounded up to a compiled value)
     if (f <= 16) {
         gram_partial_kernel<1, 4><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
                                                            ws->partial);
     } else if (f <= 28) {
-        gram_partial_kernel<1, 7><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
+        gram_partial_kernel<2, 7><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
                                                            ws->partial);
     } else if (f <= 32) {
-        gram_partial_kernel<1, 8><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
+        gram_partial_kernel<2, 8><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
                                                            ws->partial);
+    } else if (f <= 36) {
+        gram_partial_kernel<3, 9><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
+                                                           ws->partial);
+    } else if (f <= 48) {
+        gram_partial_kernel<3, 12><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
+                                                            ws->partial);
     } else {
-        // 64 rows x 257 words is a little over the 64 KiB a kernel may use without asking
+        // 64 rows x 260 words is a little over the 64 KiB a kernel may use without asking
         if (f <= 52) {
-            BYZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&gram_partial_kernel<2, 13>),
+            BYZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&gram_partial_kernel<4, 13>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            gram_partial_kernel<2, 13><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
+            gram_partial_kernel<4, 13><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
                                                                 ws->partial);
         } else {
-            BYZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&gram_partial_kernel<2, 16>),
+            BYZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&gram_partial_kernel<4, 16>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            gram_partial_kernel<2, 16><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
+            gram_partial_kernel<4, 16><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
                                                                 ws->partial);
         }
     }
