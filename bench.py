@@ -125,7 +125,7 @@ def main():
     coords_per_s = d / (ms_per_step * 1e-3)
     if single_pass:
         alg_bytes = 4.0 * (asg.r * asg.f + 1) * d  # every copy read once, one value written
-        kernel_bytes, kernel_name = alg_bytes, "fused_kernel<%d,%d,4>" % (asg.f, asg.r)
+        kernel_bytes, kernel_name = alg_bytes, "fused_kernel<%d,%d>" % (asg.f, asg.r)
     else:
         # vote kernel, then median kernel over the winners: the winners are read twice
         alg_bytes = 4.0 * ((asg.r + 1) * asg.f + 1) * d

@@ -12,4 +12,19 @@ int byz_internal_launch_bulyan_mean(const float *rows_base, long long d, long lo
                                     const int *selected_rows_dev, int f, int theta, int beta,
                                     float *out, void *stream);
 
+// Probe + single-pass kernel for the (f, r) of group n (kernels.hip, part n); the arguments are
+// byz_aggregate_opts' after validation, ws its workspace.  Returns a byz_status.
+#define BYZ_DECLARE_SINGLE_PASS(n)                                                              \
+    int byz_internal_launch_single_pass_##n(int f, int r, const void *X, long long d,           \
+                                            long long ld, const int *rows, void *ws, void *out, \
+                                            int early, int trim_b, void *stream)
+BYZ_DECLARE_SINGLE_PASS(1);
+BYZ_DECLARE_SINGLE_PASS(2);
+BYZ_DECLARE_SINGLE_PASS(3);
+BYZ_DECLARE_SINGLE_PASS(4);
+
+// Records the event before (which = 0) or after (1) the dominant kernel of an aggregation, if
+// byz_profile_enable has armed any.  Returns a byz_status.
+int byz_internal_profile_mark(int which, void *stream);
+
 #endif

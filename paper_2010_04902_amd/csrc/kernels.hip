@@ -19,20 +19,30 @@
 #include "byz_internal.h"
 #include "byzshield.h"
 
+// The build compiles this file once per BYZ_PART, in parallel, because the single-pass kernels
+// are large: part 0 holds every entry point and all other kernels, parts 1..4 one group of
+// single-pass instantiations each (byz_internal_launch_single_pass_<n>).  Without BYZ_PART
+// the whole library is this one translation unit.
+#ifndef BYZ_PART
+#define BYZ_PART -1
+#endif
+#define BYZ_IN_PART(p) (BYZ_PART == -1 || BYZ_PART == (p))
+
 namespace {
 
-thread_local int g_last_hip_error = 0;
-
-#define BYZ_HIP(call)                         \
-    do {                                      \
-        hipError_t e_ = (call);               \
-        if (e_ != hipSuccess) {               \
-            g_last_hip_error = (int)e_;       \
-            return BYZ_EDEVICE;               \
-        }                                     \
+#define BYZ_HIP(call)                                \
+    do {                                             \
+        hipError_t e_ = (call);                      \
+        if (e_ != hipSuccess) {                      \
+            byz_internal_set_hip_error((int)e_);     \
+            return BYZ_EDEVICE;                      \
+        }                                            \
     } while (0)
 
-// Optional timing of the streaming kernel: event pairs recorded around it by byz_aggregate.
+#if BYZ_IN_PART(0)
+thread_local int g_last_hip_error = 0;
+
+// Optional timing of the dominant kernel: event pairs recorded around it by byz_aggregate.
 struct ProfileState {
     int capacity = 0;
     int count = 0;
@@ -40,15 +50,16 @@ struct ProfileState {
     hipEvent_t *stop = nullptr;
 };
 thread_local ProfileState g_prof;
+#endif
 
 
 // Files the single-pass kernel prefetches ahead of the one it consumes, from the number of
 // 16-byte loads per thread it should keep in flight.  Measured on MI355X: about 6 for f = 25
 // (3-4 waves per SIMD), about 12 for f = 49 (2 waves per SIMD); more is slower.  f = 121 runs
-// one word per thread (4-byte loads) and gains up to 20 files ahead; f = 81 (two words per
-// thread, 253 registers) has no room for more than 5.
+// one word per thread (4-byte loads) and, with one slot per file, gains up to 20 files ahead;
+// f = 81 (two words per thread, 253 registers) has no room for more than 5.
 constexpr int prefetch_depth(int f, int slots) {
-    if (f > 81) return 20;
+    if (f > 81) return slots == 1 ? 20 : 5;
     const int target = f >= 49 ? 12 : 6;
     const int a = (target + slots - 1) / slots - 1;
     return a < 1 ? 1 : (a > 5 ? 5 : a);
@@ -155,12 +166,16 @@ __device__ __forceinline__ uint32_t load_shared_word(const uint32_t *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Wave-uniform: is any of words[0..n-1] nonzero (n <= 64)?  Used by the kernels of the exact
-// path to return at once when the single pass recorded no violation.
+// Wave-uniform: is any of words[0..n-1] nonzero?  Used by the kernels of the exact path to
+// return at once when the single pass recorded no violation.
 __device__ __forceinline__ bool any_word_set(const uint32_t *__restrict__ words, int n) {
     const int lane = threadIdx.x & 63;
-    const uint32_t v = lane < n ? words[lane] : 0u;
-    return __builtin_amdgcn_ballot_w64(v != 0) != 0;
+    bool any = false;
+    for (int n0 = 0; n0 < n; n0 += 64) {
+        const uint32_t v = n0 + lane < n ? words[n0 + lane] : 0u;
+        any = any || __builtin_amdgcn_ballot_w64(v != 0) != 0;
+    }
+    return any;
 }
 
 // Merge a wave's per-file bits (lane j = file j) into global words, skipping the atomic when
@@ -266,12 +281,12 @@ template <> struct SelNet<49> {
 // --------------------------------------------------------------------- device workspace
 
 struct AggWorkspace {
-    uint32_t viol[BYZ_MAX_F];        // single pass: assumed-equal neighbours that differ
+    uint32_t viol[kWide];            // single pass: assumed-equal neighbours that differ
     uint32_t pair_neq[kWide];        // exact path: all pair bits
     // byte offsets row*ld*4 of a file's rows, probable winner's class first
-    uint64_t perm_off[BYZ_MAX_F * kRowStride];
-    uint32_t chain_mask[BYZ_MAX_F];  // bit k-1: permuted copies k-1 and k were equal on the sample
-    int32_t prov_winner[BYZ_MAX_F];  // probable winner (original replica index)
+    uint64_t perm_off[kWide * kRowStride];
+    uint32_t chain_mask[kWide];      // bit k-1: permuted copies k-1 and k were equal on the sample
+    int32_t prov_winner[kWide];      // probable winner (original replica index)
     int32_t winner_row[kWide];       // exact path result
     uint32_t need_exact;             // 1 iff the exact path ran
     uint32_t slots_per_file;         // slots of every file the single pass reads: r or r'
@@ -284,8 +299,10 @@ struct AggWorkspace {
 // Clears the accumulators of one two-step aggregation (no hipMemset: callers may capture).
 __global__ void reset_workspace_kernel(AggWorkspace *ws, uint32_t need_exact) {
     const int i = threadIdx.x;
-    if (i < BYZ_MAX_F) ws->viol[i] = 0;
-    if (i < kWide) ws->pair_neq[i] = 0;
+    if (i < kWide) {
+        ws->viol[i] = 0;
+        ws->pair_neq[i] = 0;
+    }
     if (i == 0) {
         ws->need_exact = need_exact;
         ws->ticket_vote = 0;
@@ -393,7 +410,7 @@ __global__ __launch_bounds__(kBlock) void vote_pairs_kernel(
 
 // Steps of the generated streamed programs (selnet_stream_<f>.inc), written against local names
 // of the kernel that includes them: NS slots per file, V words per thread, kAhead, stage, key,
-// o, lane, flags, chain_mask, and BYZ_S_ROW_ADDR(j, k) = address of this thread's vector in
+// o, lane, flags (one word per 64 files), chain_mask, and BYZ_S_ROW_ADDR(j, k) = address of this thread's vector in
 // slot k of file j.
 // Hook a kernel may redefine around the include: BYZ_S_KEY(j, x) = key of word x of file j.
 #define BYZ_S_KEY(j, x) to_key(x)
@@ -406,9 +423,6 @@ __global__ __launch_bounds__(kBlock) void vote_pairs_kernel(
 #define BYZ_S_LOAD3(j) if constexpr (kAhead == 3) { BYZ_S_LOAD_(j) }
 #define BYZ_S_LOAD4(j) if constexpr (kAhead == 4) { BYZ_S_LOAD_(j) }
 #define BYZ_S_LOAD5(j) if constexpr (kAhead == 5) { BYZ_S_LOAD_(j) }
-#define BYZ_S_LOAD8(j) if constexpr (kAhead == 8) { BYZ_S_LOAD_(j) }
-#define BYZ_S_LOAD12(j) if constexpr (kAhead == 12) { BYZ_S_LOAD_(j) }
-#define BYZ_S_LOAD16(j) if constexpr (kAhead == 16) { BYZ_S_LOAD_(j) }
 #define BYZ_S_LOAD20(j) if constexpr (kAhead == 20) { BYZ_S_LOAD_(j) }
 #define BYZ_S_USE(j)                                                                          \
     {                                                                                         \
@@ -418,7 +432,7 @@ __global__ __launch_bounds__(kBlock) void vote_pairs_kernel(
             wb_ |= wave_any(differ<V>(stage[(j) % (kAhead + 1)][k_ - 1],                      \
                                       stage[(j) % (kAhead + 1)][k_])) << (k_ - 1);            \
         wb_ &= chain_mask[j];                                                                 \
-        if (lane == (j)) flags |= wb_;                                                        \
+        if (lane == ((j) & 63)) flags[(j) >> 6] |= wb_;                                       \
         }                                                                                     \
         _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_)                                      \
             key[v_][j] = BYZ_S_KEY(j, stage[(j) % (kAhead + 1)][0][v_]);                      \
@@ -459,7 +473,7 @@ __global__ __launch_bounds__(kBlock) void median_kernel(
             uint32_t stage[kAhead + 1][NS][V];
             const uint32_t *chain_mask = nullptr;  // unused with one slot per file
             const int lane = 0;
-            uint32_t flags = 0;
+            uint32_t flags[(F + 63) / 64] = {};
             (void)chain_mask; (void)lane; (void)flags;
 #define BYZ_S_ROW_ADDR(j, k) (Xb + (uint64_t)(uint32_t)row_index[j] * (uint64_t)ld * 4u + voff)
 #include "generated/selnet_stream_dispatch.inc"
@@ -495,7 +509,8 @@ __global__ __launch_bounds__(kBlock) void median_kernel(
 template <int F, int V>
 __global__ __launch_bounds__(kBlock) void median_large_kernel(
     const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
-    uint32_t *__restrict__ out) {
+    uint32_t *__restrict__ out, const uint32_t *__restrict__ gate, int gate_n) {
+    if (gate != nullptr && !any_word_set(gate, gate_n)) return;
     const int64_t n_thr = (d + V - 1) / V;
     const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (gt >= n_thr) return;
@@ -509,7 +524,7 @@ __global__ __launch_bounds__(kBlock) void median_large_kernel(
     uint32_t stage[kAhead + 1][NS][V];
     const uint32_t *chain_mask = nullptr;  // unused with one slot per file
     const int lane = 0;
-    uint32_t flags = 0;
+    uint32_t flags[(F + 63) / 64] = {};
     (void)chain_mask; (void)lane; (void)flags;
 #define BYZ_S_ROW_ADDR(j, k) (Xb + (uint64_t)(uint32_t)row_index[j] * (uint64_t)ld * 4u + voff)
 #include "generated/selnet_stream_dispatch.inc"
@@ -575,7 +590,7 @@ __global__ __launch_bounds__(kBlock) void trimmed_mean_kernel(
     uint32_t stage[kAhead + 1][NS][V];
     const uint32_t *chain_mask = nullptr;  // unused with one slot per file
     const int lane = 0;
-    uint32_t flags = 0;
+    uint32_t flags[(F + 63) / 64] = {};
     (void)chain_mask; (void)lane; (void)flags;
 #define BYZ_S_ROW_ADDR(j, k) (Xb + (uint64_t)(uint32_t)row_index[j] * (uint64_t)ld * 4u + voff)
 #include "generated/selnet_sort_stream_dispatch.inc"
@@ -613,7 +628,8 @@ __global__ __launch_bounds__(kBlock) void trimmed_mean_generic_kernel(
 //           trimmed_mean_kernel (fp32, kept values added in ascending order, one division).
 __global__ __launch_bounds__(64) void column_wide_kernel(
     const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
-    int f, int b, uint32_t *__restrict__ out) {
+    int f, int b, uint32_t *__restrict__ out, const uint32_t *__restrict__ gate, int gate_n) {
+    if (gate != nullptr && !any_word_set(gate, gate_n)) return;
     extern __shared__ uint32_t s_col[];
     const int lane = threadIdx.x;
     const int64_t c_raw = (int64_t)blockIdx.x * 64 + lane;
@@ -721,7 +737,7 @@ __global__ __launch_bounds__(kBlock) void bulyan_mean_kernel(
     uint32_t stage[kAhead + 1][NS][V];
     const uint32_t *chain_mask = nullptr;  // unused with one slot per file
     const int lane = 0;
-    uint32_t flags = 0;
+    uint32_t flags[(F + 63) / 64] = {};
     (void)chain_mask; (void)lane; (void)flags;
 #undef BYZ_S_KEY
 #define BYZ_S_KEY(j, x) ((j) < theta ? to_key(x) : 0xFFFFFFFFu)
@@ -773,11 +789,12 @@ __global__ __launch_bounds__(kProbe) void probe_kernel(const uint32_t *__restric
                                                     int64_t ld,
                                                     const int32_t *__restrict__ file_rows,
                                                     AggWorkspace *ws, int early_majority) {
-    __shared__ uint32_t s_neq[BYZ_MAX_F];
+    __shared__ uint32_t s_neq[kWide];
     __shared__ uint32_t s_all_majority;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    if (tid < BYZ_MAX_F) {
+    static_assert(kProbe >= kWide, "one probe thread per file");
+    if (tid < kWide) {
         s_neq[tid] = 0;
         ws->viol[tid] = 0;
         ws->pair_neq[tid] = 0;
@@ -799,7 +816,7 @@ __global__ __launch_bounds__(kProbe) void probe_kernel(const uint32_t *__restric
     }
     // files in groups of G: all loads of a group are issued before the first ballot waits
     constexpr int G = (F * R <= 192) ? F : 192 / R;
-    uint32_t flags = 0;
+    uint32_t flags[(F + 63) / 64] = {};  // lane j%64 collects the bits of file j
 #pragma unroll
     for (int j0 = 0; j0 < F; j0 += G) {
         uint32_t x[G][R];
@@ -817,10 +834,12 @@ __global__ __launch_bounds__(kProbe) void probe_kernel(const uint32_t *__restric
 #pragma unroll
                 for (int b = a + 1; b < R; ++b)
                     wb |= wave_any(x[g][a] ^ x[g][b]) << pair_bit(R, a, b);
-            if (lane == j0 + g) flags |= wb;
+            if (lane == ((j0 + g) & 63)) flags[(j0 + g) >> 6] |= wb;
         }
     }
-    if (lane < F && flags != 0) atomicOr(&s_neq[lane], flags);
+#pragma unroll
+    for (int w = 0; w < (F + 63) / 64; ++w)
+        if (64 * w + lane < F && flags[w] != 0) atomicOr(&s_neq[64 * w + lane], flags[w]);
     __syncthreads();
 
     if (tid < F) {
@@ -887,7 +906,7 @@ __device__ __forceinline__ void fused_body(const uint32_t *__restrict__ X, int64
     const int64_t n_thr = (d + V - 1) / V;
     const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     const int64_t c0 = (gt + 1) * V <= d ? gt * V : d - V;
-    uint32_t flags = 0;
+    uint32_t flags[(F + 63) / 64] = {};  // lane j%64 collects the violation bits of file j
     const uint32_t voff = (uint32_t)(c0 * 4);
     const char *Xb = reinterpret_cast<const char *>(X);
     uint32_t key[V][F];       // wire j of the network = file j
@@ -907,7 +926,9 @@ __device__ __forceinline__ void fused_body(const uint32_t *__restrict__ X, int64
     }
 #undef BYZ_S_ROW_ADDR
     if (gt < n_thr) store_vec<V>(out + c0, o);
-    merge_flags(ws->viol, F, lane, flags);
+#pragma unroll
+    for (int w = 0; w < (F + 63) / 64; ++w)
+        merge_flags(ws->viol + 64 * w, F - 64 * w < 64 ? F - 64 * w : 64, lane, flags[w]);
 }
 
 template <int F, int R, bool TRIM, int V>
@@ -924,7 +945,7 @@ __global__ __launch_bounds__(kBlock) void fused_kernel(
 
 // ---------------------------------------------------------------------------- launchers
 
-constexpr int kVec = 4;  // words per thread and load; rows only need dword alignment
+[[maybe_unused]] constexpr int kVec = 4;  // words per thread and load; rows only need dword alignment
 
 // blocks for n_vec vector-owning threads; at least one so the trailing words get a block
 inline unsigned blocks_for(int64_t n_vec) {
@@ -932,8 +953,9 @@ inline unsigned blocks_for(int64_t n_vec) {
     return (unsigned)(b > 0 ? b : 1);
 }
 
-constexpr int64_t kMaxCoords = (int64_t)1 << 30;  // byte offsets inside a row fit 32 bits
+[[maybe_unused]] constexpr int64_t kMaxCoords = (int64_t)1 << 30;  // byte offsets inside a row fit 32 bits
 
+#if BYZ_IN_PART(0)
 template <int R>
 int launch_vote_pairs(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, int f,
                       uint32_t *neq, const uint32_t *gate, uint32_t *ticket,
@@ -964,12 +986,13 @@ int launch_vote_pairs_r(int r, const uint32_t *X, int64_t d, int64_t ld, const i
     }
 }
 
-// f > 64 (never gated: the single pass does not exist for these f)
+// 64 < f <= 256 without a generated network
 int launch_column_wide(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
-                       int b, uint32_t *out, hipStream_t s) {
+                       int b, uint32_t *out, const uint32_t *gate, int gate_n, hipStream_t s) {
     if (d == 0) return BYZ_OK;
     const size_t lds = (size_t)f * 64 * sizeof(uint32_t);  // <= 64 KiB for f <= 256
-    column_wide_kernel<<<(unsigned)((d + 63) / 64), 64, lds, s>>>(X, d, ld, row_index, f, b, out);
+    column_wide_kernel<<<(unsigned)((d + 63) / 64), 64, lds, s>>>(X, d, ld, row_index, f, b, out,
+                                                                 gate, gate_n);
     BYZ_HIP(hipGetLastError());
     return BYZ_OK;
 }
@@ -998,20 +1021,20 @@ int launch_median(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_i
         case 35: return launch_median_net<35>(X, d, ld, row_index, out, gate, gate_n, s);
         case 49: return launch_median_net<49>(X, d, ld, row_index, out, gate, gate_n, s);
         case 81:
-            if (d < vec_for(81)) return launch_column_wide(X, d, ld, row_index, f, -1, out, s);
+            if (d < vec_for(81)) return launch_column_wide(X, d, ld, row_index, f, -1, out, gate, gate_n, s);
             median_large_kernel<81, vec_for(81)>
-                <<<blocks_for((d + vec_for(81) - 1) / vec_for(81)), kBlock, 0, s>>>(X, d, ld,
-                                                                                  row_index, out);
+                <<<blocks_for((d + vec_for(81) - 1) / vec_for(81)), kBlock, 0, s>>>(
+                    X, d, ld, row_index, out, gate, gate_n);
             BYZ_HIP(hipGetLastError());
             return BYZ_OK;
         case 121:
             median_large_kernel<121, vec_for(121)>
                 <<<blocks_for((d + vec_for(121) - 1) / vec_for(121)), kBlock, 0, s>>>(
-                    X, d, ld, row_index, out);
+                    X, d, ld, row_index, out, gate, gate_n);
             BYZ_HIP(hipGetLastError());
             return BYZ_OK;
         default:
-            if (f > BYZ_MAX_F) return launch_column_wide(X, d, ld, row_index, f, -1, out, s);
+            if (f > BYZ_MAX_F) return launch_column_wide(X, d, ld, row_index, f, -1, out, gate, gate_n, s);
             median_generic_kernel<<<blocks_for(d), kBlock, 0, s>>>(X, d, ld, row_index, f, out,
                                                                    gate, gate_n);
             BYZ_HIP(hipGetLastError());
@@ -1019,28 +1042,28 @@ int launch_median(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_i
     }
 }
 
+#endif  // part 0
+
 template <int F, int R>
 int launch_fused(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, AggWorkspace *ws,
                  uint32_t *out, int early_majority, int trim_b, hipStream_t s) {
     probe_kernel<F, R><<<1, kProbe, 0, s>>>(X, d, ld, rows, ws, early_majority);
     BYZ_HIP(hipGetLastError());
-    const bool timed = g_prof.count < g_prof.capacity;
-    if (timed) BYZ_HIP(hipEventRecord(g_prof.start[g_prof.count], s));
-    const unsigned g = blocks_for((d + kVec - 1) / kVec);
+    int rc = byz_internal_profile_mark(0, s);
+    if (rc != BYZ_OK) return rc;
+    constexpr int V = vec_for(F);
+    const unsigned g = blocks_for((d + V - 1) / V);
     if (trim_b < 0)
-        fused_kernel<F, R, false, kVec><<<g, kBlock, 0, s>>>(
+        fused_kernel<F, R, false, V><<<g, kBlock, 0, s>>>(
             X, d, ld, ws->perm_off, ws->chain_mask, &ws->slots_per_file, ws, 0, out);
     else
-        fused_kernel<F, R, true, kVec><<<g, kBlock, 0, s>>>(
+        fused_kernel<F, R, true, V><<<g, kBlock, 0, s>>>(
             X, d, ld, ws->perm_off, ws->chain_mask, &ws->slots_per_file, ws, trim_b, out);
     BYZ_HIP(hipGetLastError());
-    if (timed) {
-        BYZ_HIP(hipEventRecord(g_prof.stop[g_prof.count], s));
-        ++g_prof.count;
-    }
-    return BYZ_OK;
+    return byz_internal_profile_mark(1, s);
 }
 
+#if BYZ_IN_PART(0)
 template <int F>
 int launch_trimmed_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int b,
                        uint32_t *O, const uint32_t *gate, int gate_n, hipStream_t s) {
@@ -1067,7 +1090,7 @@ int launch_trimmed_mean(const uint32_t *X, int64_t d, int64_t ld, const int32_t 
             default: break;
         }
     }
-    if (f > BYZ_MAX_F) return launch_column_wide(X, d, ld, row_index, f, b, O, s);
+    if (f > BYZ_MAX_F) return launch_column_wide(X, d, ld, row_index, f, b, O, gate, gate_n, s);
     trimmed_mean_generic_kernel<<<blocks_for(d), kBlock, 0, s>>>(X, d, ld, row_index, f, b, O,
                                                                  gate, gate_n);
     BYZ_HIP(hipGetLastError());
@@ -1085,10 +1108,12 @@ int launch_bulyan_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *s
 }
 
 // (f, r) with a compiled single-pass kernel: MOLS / Ramanujan Case 1 (f = l^2: 9, 25, 49) with
-// r = 3 or 5, and the Ramanujan Case 2 shapes f = m*s with r = s: (15,3), (21,3), (35,5)
+// r = 3 or 5, the Ramanujan Case 2 shapes f = m*s with r = s: (15,3), (21,3), (35,5), and MOLS
+// over F_9 and F_11 with r = 3: (81,3), (121,3)
 bool has_fused(int f, int r) {
     return (f == 9 && r == 3) || ((f == 25 || f == 49) && (r == 3 || r == 5)) ||
-           ((f == 15 || f == 21) && r == 3) || (f == 35 && r == 5);
+           ((f == 15 || f == 21) && r == 3) || (f == 35 && r == 5) ||
+           ((f == 81 || f == 121) && r == 3);
 }
 
 int check_common(const void *copies, int64_t d, int64_t ld, const void *rows, int f, int r) {
@@ -1099,9 +1124,83 @@ int check_common(const void *copies, int64_t d, int64_t ld, const void *rows, in
     return BYZ_OK;
 }
 
+#endif  // part 0
+
 }  // namespace
 
+// ------------------------------------------------- single-pass launchers, one group per part
+
+#if BYZ_IN_PART(1)
+int byz_internal_launch_single_pass_1(int f, int r, const void *X, long long d, long long ld,
+                                      const int *rows, void *ws, void *out, int early, int trim_b,
+                                      void *stream) {
+    const uint32_t *x = static_cast<const uint32_t *>(X);
+    AggWorkspace *w = static_cast<AggWorkspace *>(ws);
+    uint32_t *o = static_cast<uint32_t *>(out);
+    hipStream_t s = (hipStream_t)stream;
+    if (f == 9 && r == 3) return launch_fused<9, 3>(x, d, ld, rows, w, o, early, trim_b, s);
+    if (f == 15 && r == 3) return launch_fused<15, 3>(x, d, ld, rows, w, o, early, trim_b, s);
+    if (f == 21 && r == 3) return launch_fused<21, 3>(x, d, ld, rows, w, o, early, trim_b, s);
+    if (f == 25 && r == 3) return launch_fused<25, 3>(x, d, ld, rows, w, o, early, trim_b, s);
+    if (f == 25 && r == 5) return launch_fused<25, 5>(x, d, ld, rows, w, o, early, trim_b, s);
+    if (f == 35 && r == 5) return launch_fused<35, 5>(x, d, ld, rows, w, o, early, trim_b, s);
+    return BYZ_EINTERNAL;
+}
+#endif
+
+#if BYZ_IN_PART(2)
+int byz_internal_launch_single_pass_2(int f, int r, const void *X, long long d, long long ld,
+                                      const int *rows, void *ws, void *out, int early, int trim_b,
+                                      void *stream) {
+    const uint32_t *x = static_cast<const uint32_t *>(X);
+    AggWorkspace *w = static_cast<AggWorkspace *>(ws);
+    uint32_t *o = static_cast<uint32_t *>(out);
+    hipStream_t s = (hipStream_t)stream;
+    if (f == 49 && r == 3) return launch_fused<49, 3>(x, d, ld, rows, w, o, early, trim_b, s);
+    if (f == 49 && r == 5) return launch_fused<49, 5>(x, d, ld, rows, w, o, early, trim_b, s);
+    return BYZ_EINTERNAL;
+}
+#endif
+
+#if BYZ_IN_PART(3)
+int byz_internal_launch_single_pass_3(int f, int r, const void *X, long long d, long long ld,
+                                      const int *rows, void *ws, void *out, int early, int trim_b,
+                                      void *stream) {
+    if (f == 81 && r == 3)
+        return launch_fused<81, 3>(static_cast<const uint32_t *>(X), d, ld, rows,
+                                   static_cast<AggWorkspace *>(ws), static_cast<uint32_t *>(out),
+                                   early, trim_b, (hipStream_t)stream);
+    return BYZ_EINTERNAL;
+}
+#endif
+
+#if BYZ_IN_PART(4)
+int byz_internal_launch_single_pass_4(int f, int r, const void *X, long long d, long long ld,
+                                      const int *rows, void *ws, void *out, int early, int trim_b,
+                                      void *stream) {
+    if (f == 121 && r == 3)
+        return launch_fused<121, 3>(static_cast<const uint32_t *>(X), d, ld, rows,
+                                    static_cast<AggWorkspace *>(ws), static_cast<uint32_t *>(out),
+                                    early, trim_b, (hipStream_t)stream);
+    return BYZ_EINTERNAL;
+}
+#endif
+
+#if BYZ_IN_PART(0)
+
 // ---------------------------------------------------------------------------- C-ABI
+
+// which: 0 = before, 1 = after the dominant kernel of an aggregation on `stream`
+int byz_internal_profile_mark(int which, void *stream) {
+    if (g_prof.count >= g_prof.capacity) return BYZ_OK;
+    if (which == 0) {
+        BYZ_HIP(hipEventRecord(g_prof.start[g_prof.count], (hipStream_t)stream));
+    } else {
+        BYZ_HIP(hipEventRecord(g_prof.stop[g_prof.count], (hipStream_t)stream));
+        ++g_prof.count;
+    }
+    return BYZ_OK;
+}
 
 int byz_internal_launch_bulyan_mean(const float *rows_base, long long d, long long ld,
                                     const int *selected_rows_dev, int f, int theta, int beta,
@@ -1213,15 +1312,13 @@ extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
         BYZ_HIP(hipGetLastError());
         // (no last-block ticket here: its per-block fence costs more than a third launch)
         if (d > 0) {
-            const bool timed = g_prof.count < g_prof.capacity;
-            if (timed) BYZ_HIP(hipEventRecord(g_prof.start[g_prof.count], s));
+            rc = byz_internal_profile_mark(0, s);
+            if (rc != BYZ_OK) return rc;
             rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, nullptr, nullptr,
                                      nullptr, nullptr, nullptr, nullptr, s);
             if (rc != BYZ_OK) return rc;
-            if (timed) {
-                BYZ_HIP(hipEventRecord(g_prof.stop[g_prof.count], s));
-                ++g_prof.count;
-            }
+            rc = byz_internal_profile_mark(1, s);
+            if (rc != BYZ_OK) return rc;
         }
         vote_decide_kernel<<<1, kWide, 0, s>>>(ws->pair_neq, file_rows_dev, f, r, winner_replica,
                                                ws->winner_row);
@@ -1233,14 +1330,14 @@ extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
 
     // probe -> single pass -> exact path, whose two kernels return at once unless the single
     // pass recorded a violated assumption
-    if (f == 9) rc = launch_fused<9, 3>(X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
-    else if (f == 15) rc = launch_fused<15, 3>(X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
-    else if (f == 21) rc = launch_fused<21, 3>(X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
-    else if (f == 35) rc = launch_fused<35, 5>(X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
-    else if (f == 25 && r == 3) rc = launch_fused<25, 3>(X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
-    else if (f == 25 && r == 5) rc = launch_fused<25, 5>(X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
-    else if (f == 49 && r == 3) rc = launch_fused<49, 3>(X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
-    else rc = launch_fused<49, 5>(X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
+    if (f == 121)
+        rc = byz_internal_launch_single_pass_4(f, r, X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
+    else if (f == 81)
+        rc = byz_internal_launch_single_pass_3(f, r, X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
+    else if (f == 49)
+        rc = byz_internal_launch_single_pass_2(f, r, X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
+    else
+        rc = byz_internal_launch_single_pass_1(f, r, X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
     if (rc != BYZ_OK) return rc;
     rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, ws->viol,
                              &ws->ticket_vote, winner_replica, ws->winner_row, ws->prov_winner,
@@ -1327,3 +1424,5 @@ extern "C" int byz_aggregate_took_exact_path(const void *workspace, int *took_ex
     *took_exact_path = (int)v;
     return BYZ_OK;
 }
+
+#endif  // part 0
