@@ -449,7 +449,7 @@ def _multi_krum_check(X, idx_np, d, c, m, tag):
     per block (L = coordinates a block handles) plus a few adds, then in fp64, so
     |dG_ij| <= (L + 8) * 2^-24 * (G_ii + G_jj) / 2 and |dD_ij| <= 2 * (L + 8) * 2^-24 * (G_ii + G_jj).
     A score adds at most f distances.  The selection is compared where the oracle's scores are
-    further from the cut than twice that; the mean is checked for the rows the GPU selected
+    further from the cut than twice that; the mean is checked against the oracle's mean
     (fp32 sequential sum: m * 2^-24 * max|x|)."""
     idx_dev = torch.tensor(idx_np, dtype=torch.int32, device=DEV)
     out, sel, scores, dist = B.byz_multi_krum(X, d, idx_dev, c, m)
@@ -471,10 +471,11 @@ def _multi_krum_check(X, idx_np, d, c, m, tag):
     cut = np.sort(scores_o)[m - 1]
     assert (sel_g[scores_o < cut - 2 * tol_s] == 1).all(), tag
     assert (sel_g[scores_o > cut + 2 * tol_s] == 0).all(), tag
-    rows = Xh[idx_np[sel_g == 1]][:, :d].astype(np.float64)
-    want = rows.mean(axis=0)
+    # the test inputs keep the scores far from the cut, so both sides select the same rows
+    assert np.array_equal(sel_g, sel_o), tag
+    rows = Xh[idx_np[sel_o == 1]][:, :d].astype(np.float64)
     tol_m = 1.5 * m * 2.0 ** -24 * np.abs(rows).max(axis=0) + 1e-44
-    assert (np.abs(out.cpu().numpy().astype(np.float64) - want) <= tol_m).all(), tag
+    assert (np.abs(out.cpu().numpy().astype(np.float64) - mean_o) <= tol_m).all(), tag
     return sel_g, sel_o
 
 
@@ -511,8 +512,9 @@ def _bulyan_check(X, idx_np, d, c, tag, big=False, exact_order=False):
     chosen must equal the oracle's whenever, in every round, the oracle's best score is further
     than twice the score tolerance from its second best; in any case each GPU pick must be
     within that tolerance of the round's best oracle score (a valid pick).  Phase 2 is checked
-    on the set the GPU chose, against the oracle's mean around the median of that set
-    (fp32 sequential sum of beta values: 1.5 * beta * 2^-24 * max|x|)."""
+    against the oracle's output whenever both chose the same vectors
+    (fp32 sequential sum of beta values: 1.5 * beta * 2^-24 * max|x|).
+    Returns True if the whole result was compared (same chosen order as the oracle)."""
     idx_dev = torch.tensor(idx_np, dtype=torch.int32, device=DEV)
     out, sel, order, dist = B.byz_bulyan(X, d, idx_dev, c)
     torch.cuda.synchronize()
@@ -544,17 +546,16 @@ def _bulyan_check(X, idx_np, d, c, tag, big=False, exact_order=False):
         remaining.remove(pick)
     if decisive or exact_order:
         assert order_g == chosen_o, tag
+    if order_g != chosen_o:
+        # a near-tie of the fp64 oracle decided the other way by the fp32 Gram matrix: the
+        # picks were checked to be valid, the output then belongs to another chosen set and
+        # is not compared
+        return False
     chosen = np.array(order_g, dtype=np.int32)
-    if order_g == chosen_o:
-        want = out_o
-    elif big:
-        want = C.mean_around_median(Xh, idx_np, chosen, d, beta)
-    else:
-        want = np.array([O.mean_around_median(Xh[idx_np[chosen], t], beta)[0] for t in range(d)])
     vmax = np.abs(Xh[idx_np[chosen]][:, :d].astype(np.float64)).max(axis=0)
     tol_m = 1.5 * beta * 2.0 ** -24 * vmax + 1e-44
-    assert (np.abs(out.cpu().numpy().astype(np.float64) - want) <= tol_m).all(), tag
-    return order_g, chosen_o
+    assert (np.abs(out.cpu().numpy().astype(np.float64) - out_o) <= tol_m).all(), tag
+    return True
 
 
 @pytest.mark.parametrize("scheme,a,b,q,attack", [(MOLS, 5, 3, 4, ALIE), (MOLS, 7, 3, 5, REVERSED),
@@ -564,6 +565,7 @@ def test_bulyan_on_the_vote_winners(scheme, a, b, q, attack):
     # per-file gradient scales make the honest vectors' scores differ by far more than the fp32
     # Gram error, so the order chosen is decided and compared exactly in most cases
     attack = dict(attack, file_scales=True)
+    compared = []
     for i, d in enumerate([1, 3, 4, 257, 5000, 70001]):
         w = W.make(scheme, a, b, q, d, attack, seed=500 + i, ld=synth.padded_ld(d, 4) + 4 * (i % 2),
                    device=DEV)
@@ -572,7 +574,9 @@ def test_bulyan_on_the_vote_winners(scheme, a, b, q, attack):
         torch.cuda.synchronize()
         idx = wrow.cpu().numpy()
         for c in sorted({0, 1, (w.f - 3) // 4}):
-            order_g, chosen_o = _bulyan_check(w.X, idx, d, c, (w.f, d, c))
+            compared.append(_bulyan_check(w.X, idx, d, c, (w.f, d, c)))
+    # the inputs are built so that near-ties are rare: almost every case is compared in full
+    assert sum(compared) >= len(compared) - 2, compared
     for c in (-1, (w.f - 3) // 4 + 1):  # f < 4c + 3
         with pytest.raises(B.ByzError) as e:
             B.byz_bulyan(w.X, w.d, wrow, c)
@@ -596,5 +600,5 @@ def test_bulyan_ties_and_identical_vectors():
     # around the median meets equal distances on both sides (the lower value is taken)
     vals = np.array([3, -2, 7, 0, 1, -1, 5, 2, -3, 4, 6, -4, 8, -5, 9], dtype=np.float32)
     Y = torch.tensor(np.repeat(vals[:, None], 16, axis=1), device=DEV)
-    _bulyan_check(Y, np.arange(15, dtype=np.int32), 16, 2, "integer ties", exact_order=True)
-    _bulyan_check(Y, np.arange(15, dtype=np.int32), 16, 3, "integer ties", exact_order=True)
+    assert _bulyan_check(Y, np.arange(15, dtype=np.int32), 16, 2, "integer ties", exact_order=True)
+    assert _bulyan_check(Y, np.arange(15, dtype=np.int32), 16, 3, "integer ties", exact_order=True)
