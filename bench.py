@@ -56,8 +56,8 @@ def main():
                     help="also run one plain 1 GiB device-to-device copy (reference for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (the path shards by coordinate range, "
-                 "see DESIGN.md); --gpus %d is not supported" % args.gpus)
+        sys.exit("bench.py: this library runs on one GPU only (the path would shard by coordinate "
+                 "range); --gpus %d is not supported" % args.gpus)
 
     import numpy as np
     import torch

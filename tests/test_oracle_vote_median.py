@@ -332,11 +332,11 @@ def test_bulyan_selection_and_whole_rule():
     X = np.array([[0.0], [1.0], [2.0], [3.0], [4.0], [5.0], [100.0]], dtype=np.float32)
     idx = np.arange(7, dtype=np.int32)
     out, chosen, dist = O.bulyan(X, idx, 1, 1)
-    # round 1 (n'=7, 4 nearest): scores 0:1+4+9+16=30, 1:1+1+4+9=15, 2:1+1+4+4=10, 3:10, 4:15,
-    #   5:30 -> point 2 (tie with 3: lower index); round 2 on {0,1,3,4,5,100} (3 nearest):
-    #   0:1+9+16=26, 1:1+4+9=14, 3:1+4+4=9, 4:1+1+9=11, 5:1+4+16=21 -> 3; round 3 on
-    #   {0,1,4,5,100} (2 nearest): 0:1+16=17, 1:1+9=10, 4:1+9=10, 5:1+16=17 -> 1; round 4 on
-    #   {0,4,5,100} (1 nearest): 0:16, 4:1, 5:1 -> 4; round 5 on {0,5,100} (0 terms) -> 0
+    # Krum pass 1 (n'=7, 4 nearest): scores 0:1+4+9+16=30, 1:1+1+4+9=15, 2:1+1+4+4=10, 3:10, 4:15,
+    #   5:30 -> point 2 (tie with 3: lower index); pass 2 on {0,1,3,4,5,100} (3 nearest):
+    #   0:1+9+16=26, 1:1+4+9=14, 3:1+4+4=9, 4:1+1+9=11, 5:1+4+16=21 -> 3; pass 3 on
+    #   {0,1,4,5,100} (2 nearest): 0:1+16=17, 1:1+9=10, 4:1+9=10, 5:1+16=17 -> 1; pass 4 on
+    #   {0,4,5,100} (1 nearest): 0:16, 4:1, 5:1 -> 4; pass 5 on {0,5,100} (0 terms) -> 0
     assert chosen == [2, 3, 1, 4, 0]
     # chosen values 0 1 2 3 4, median 2, the 3 closest: {1,2,3}
     assert out[0] == 2.0
