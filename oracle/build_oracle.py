@@ -14,7 +14,7 @@ def build(force=False):
     if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
         return LIB
     cmd = ["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fopenmp", "-ffp-contract=off",
-           "-shared", "-fPIC", SRC, "-o", LIB]
+           "-shared", "-fPIC", SRC, "-o", LIB, "-lm"]
     subprocess.run(cmd, check=True)
     return LIB
 

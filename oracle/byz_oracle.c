@@ -9,6 +9,7 @@
  *   oracle_vote    Eq. 3 + the implementation note of Sec. 2: exact-match
  *                  counting of whole d-vectors, most frequent copy wins,
  *                  lowest replica index on ties (paper silent on ties).
+ *   oracle_vote_tolerant  the same vote with "close" instead of "identical" copies (fp32 test).
  *   oracle_median  Sec. 2 / Sec. 6.1: coordinate-wise median of f vectors
  *                  (f odd): sort the f values of a coordinate, take the middle.
  *                  Order: total order on bit patterns (-NaN < -inf < .. < -0 <
@@ -20,6 +21,7 @@
  *
  * Build: gcc -O2 -fopenmp -shared -fPIC (see build_oracle.py).
  */
+#include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -62,6 +64,55 @@ int oracle_vote(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, i
             for (int b = a + 1; b < r; ++b)
                 if (!eq[a][b]) bits |= 1u << pair_bit(r, a, b);
         pair_neq[j] = bits;
+    }
+    return 0;
+}
+
+/*
+ * Tolerant vote (Sec. 2: precision issues "can be handled by ... appropriate clusters"; the
+ * paper gives no rule).  Two words are close iff their bit patterns are identical or
+ * |a - b| <= atol + rtol * max(|a|, |b|), every operation rounded to fp32; two copies are close
+ * iff all d words are; count[a] = copies close to a (itself included); smallest a with the
+ * largest count wins.  pair_far: bit p set iff pair p is not close.
+ */
+int oracle_vote_tolerant(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, int f,
+                         int r, float atol, float rtol, int32_t *winner_replica,
+                         int32_t *winner_row, uint32_t *pair_far) {
+    if (r < 1 || r > 7 || f < 1) return -1;
+    for (int j = 0; j < f; ++j) {
+        int close[8][8];
+        for (int a = 0; a < r; ++a)
+            for (int b = a; b < r; ++b) {
+                const uint32_t *pa = X + (int64_t)rows[j * r + a] * ld;
+                const uint32_t *pb = X + (int64_t)rows[j * r + b] * ld;
+                int ok = 1;
+                for (int64_t t = 0; t < d && ok; ++t) {
+                    if (pa[t] == pb[t]) continue;
+                    float x, y;
+                    memcpy(&x, pa + t, 4);
+                    memcpy(&y, pb + t, 4);
+                    const float diff = fabsf(x - y);
+                    const float ax = fabsf(x), ay = fabsf(y);
+                    const float big = ax > ay ? ax : ay;  /* a NaN makes diff NaN: not close either way */
+                    const float prod = rtol * big;
+                    const float bound = atol + prod;
+                    if (!(diff <= bound)) ok = 0;
+                }
+                close[a][b] = close[b][a] = ok;
+            }
+        int best = -1, a_star = 0;
+        for (int a = 0; a < r; ++a) {
+            int count = 0;
+            for (int b = 0; b < r; ++b) count += close[a][b];
+            if (count > best) { best = count; a_star = a; }
+        }
+        winner_replica[j] = a_star;
+        winner_row[j] = rows[j * r + a_star];
+        uint32_t bits = 0;
+        for (int a = 0; a < r; ++a)
+            for (int b = a + 1; b < r; ++b)
+                if (!close[a][b]) bits |= 1u << pair_bit(r, a, b);
+        pair_far[j] = bits;
     }
     return 0;
 }

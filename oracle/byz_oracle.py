@@ -19,6 +19,9 @@ Parity status of each function (what pins it, see tests/test_oracle_*.py):
   gamma_bound                         Tables 3-6 (gamma column), closed forms Sec. 5.1
   vote                                brute force over all equality patterns, Sec. 2
                                       statements (all-honest, distorted iff >= r')
+  vote_tolerant, words_close          numpy.isclose both ways, zero tolerance = exact vote, hand-worked
+                                      chain a~b~c, Sec. 2 majority property under noise (the paper
+                                      gives no rule: "parity unpinned")
   median                              numpy sort/median on ordinary data, brute force
   multi_krum                          scipy cdist, hand-worked line example, outlier exclusion
                                       (the paper cites but does not define the rule)
@@ -303,6 +306,52 @@ def vote(X, rows, d):
                 bits |= 1 << p
         pair_neq[j] = bits
     return winner_replica, winner_row, pair_neq
+
+
+def words_close(xa, xb, atol, rtol):
+    """Element-wise "close" test of the tolerant vote, all in fp32: two words are close iff their
+    bit patterns are identical, or |xa - xb| <= atol + rtol * max(|xa|, |xb|) with the
+    subtraction, the product and the sum each rounded to fp32 (comparisons with NaN are false)."""
+    xa = np.ascontiguousarray(xa, dtype=np.float32)
+    xb = np.ascontiguousarray(xb, dtype=np.float32)
+    same_bits = xa.view(np.uint32) == xb.view(np.uint32)
+    with np.errstate(invalid="ignore", over="ignore"):
+        diff = np.abs((xa - xb).astype(np.float32))
+        big = np.maximum(np.abs(xa), np.abs(xb)).astype(np.float32)
+        prod = (np.float32(rtol) * big).astype(np.float32)
+        bound = (np.float32(atol) + prod).astype(np.float32)
+        return same_bits | (diff <= bound)
+
+
+def vote_tolerant(X, rows, d, atol, rtol):
+    """Majority vote for honest copies that agree only up to rounding (Sec. 2 notes that
+    precision issues "can be handled by deciding the majority by defining appropriate clusters"
+    and gives no rule).  Reading used here: two copies are close iff every one of their d
+    coordinates is close (words_close); count[a] = number of copies close to copy a, itself
+    included; the winner is the smallest a with the largest count.  Closeness is not
+    transitive, so this is a count of neighbours, not a partition.
+    Returns (winner_replica[f], winner_row[f], pair_far[f]): bit p of pair_far[j] is 1 iff the
+    copies of pair p (see pair_index) are not close."""
+    V = np.ascontiguousarray(X).view(np.float32)
+    f, r = rows.shape
+    pairs = pair_index(r)
+    winner_replica = np.zeros(f, dtype=np.int32)
+    winner_row = np.zeros(f, dtype=np.int32)
+    pair_far = np.zeros(f, dtype=np.uint32)
+    for j in range(f):
+        close = np.eye(r, dtype=bool)
+        bits = 0
+        for p, (a, b) in enumerate(pairs):
+            ok = bool(words_close(V[rows[j, a], :d], V[rows[j, b], :d], atol, rtol).all())
+            close[a, b] = close[b, a] = ok
+            if not ok:
+                bits |= 1 << p
+        count = [int(close[a].sum()) for a in range(r)]
+        a_star = count.index(max(count))
+        winner_replica[j] = a_star
+        winner_row[j] = rows[j, a_star]
+        pair_far[j] = bits
+    return winner_replica, winner_row, pair_far
 
 
 def order_key(u):

@@ -20,6 +20,10 @@ def lib():
         L.oracle_vote.argtypes = [u32p, ctypes.c_int64, ctypes.c_int64, i32p, ctypes.c_int,
                                   ctypes.c_int, i32p, i32p, u32p]
         L.oracle_vote.restype = ctypes.c_int
+        L.oracle_vote_tolerant.argtypes = [u32p, ctypes.c_int64, ctypes.c_int64, i32p, ctypes.c_int,
+                                           ctypes.c_int, ctypes.c_float, ctypes.c_float, i32p,
+                                           i32p, u32p]
+        L.oracle_vote_tolerant.restype = ctypes.c_int
         L.oracle_median.argtypes = [u32p, ctypes.c_int64, ctypes.c_int64, i32p, ctypes.c_int,
                                     u32p, ctypes.c_int]
         L.oracle_median.restype = ctypes.c_int
@@ -72,6 +76,22 @@ def vote(X, rows, d):
     if rc != 0:
         raise ValueError("oracle_vote rc=%d" % rc)
     return wrep, wrow, neq
+
+
+def vote_tolerant(X, rows, d, atol, rtol):
+    U = _u32(X)
+    rows = np.ascontiguousarray(rows, dtype=np.int32)
+    f, r = rows.shape
+    wrep = np.zeros(f, dtype=np.int32)
+    wrow = np.zeros(f, dtype=np.int32)
+    far = np.zeros(f, dtype=np.uint32)
+    rc = lib().oracle_vote_tolerant(_ptr(U, ctypes.c_uint32), d, U.shape[1],
+                                    _ptr(rows, ctypes.c_int32), f, r, float(atol), float(rtol),
+                                    _ptr(wrep, ctypes.c_int32), _ptr(wrow, ctypes.c_int32),
+                                    _ptr(far, ctypes.c_uint32))
+    if rc != 0:
+        raise ValueError("oracle_vote_tolerant rc=%d" % rc)
+    return wrep, wrow, far
 
 
 def median(X, row_index, d, threads=None):

@@ -428,3 +428,105 @@ def test_c_oracle_mean_around_median_equals_the_definition_on_special_values():
         for t in range(d):
             want = O.mean_around_median(U[row_index[chosen], t], beta)[0]
             assert (np.isnan(got[t]) and np.isnan(want)) or got[t] == pytest.approx(want, abs=1e-12), (theta, beta, t)
+
+
+TOL_VOTES = [("numpy", O.vote_tolerant), ("c", C.vote_tolerant)]
+
+
+@pytest.mark.parametrize("name,tvote", TOL_VOTES)
+def test_tolerant_vote_closeness_is_isclose_both_ways(name, tvote):
+    # |a-b| <= atol + rtol*max(|a|,|b|)  <=>  isclose(a, b) or isclose(b, a) (numpy's test uses
+    # |b| alone); identical bit patterns (same-sign infinities, equal NaNs) are close as well
+    rng = np.random.default_rng(5)
+    d = 64
+    for atol, rtol in [(1e-6, 0.0), (0.0, 1e-5), (1e-7, 1e-6), (0.0, 0.0)]:
+        for trial in range(40):
+            a = rng.standard_normal(d).astype(np.float32)
+            b = a + (rng.standard_normal(d) * rng.choice([0.0, 1e-7, 1e-6, 1e-3])).astype(np.float32)
+            if trial % 5 == 0:
+                a[3] = b[3] = np.inf
+                a[4] = b[4] = np.nan
+            if trial % 7 == 0:
+                a[5], b[5] = 0.0, -0.0
+            X = np.stack([a, b, a]).astype(np.float32)
+            rows = np.array([[0, 1, 2]], dtype=np.int32)
+            _, _, far = tvote(X, rows, d, atol, rtol)
+            with np.errstate(invalid="ignore"):
+                close = (np.isclose(a, b, rtol=rtol, atol=atol) | np.isclose(b, a, rtol=rtol, atol=atol)
+                         | (a.view(np.uint32) == b.view(np.uint32)))
+            want_far_01 = not close.all()
+            assert bool(far[0] & 1) == want_far_01          # pair (0,1)
+            assert not (far[0] & 2)                          # pair (0,2): identical copies
+            assert bool(far[0] & 4) == want_far_01          # pair (1,2)
+
+
+@pytest.mark.parametrize("name,tvote", TOL_VOTES)
+def test_tolerant_vote_hand_worked_and_limits(name, tvote):
+    one = np.ones((1, 8), dtype=np.float32)
+    # a chain: 0, 0.9, 1.8 with atol = 1: a~b, b~c, a!~c -> counts 2, 3, 2 -> replica 1 wins
+    X = np.concatenate([0.0 * one, 0.9 * one, 1.8 * one])
+    rows = np.array([[0, 1, 2]], dtype=np.int32)
+    wrep, wrow, far = tvote(X, rows, 8, 1.0, 0.0)
+    assert (wrep[0], wrow[0], far[0]) == (1, 1, 0b010)      # only pair (0,2) is far
+    # two close copies against one far copy: lower replica of the close pair
+    X = np.concatenate([5.0 * one, 1.0 * one, (1.0 + 1e-6) * one]).astype(np.float32)
+    wrep, _, far = tvote(X, rows, 8, 1e-5, 0.0)
+    assert (wrep[0], far[0]) == (1, 0b011)
+    # nothing close: replica 0
+    wrep, _, far = tvote(X, rows, 8, 1e-9, 0.0)
+    assert (wrep[0], far[0]) == (0, 0b111)
+    # one coordinate out of tolerance is enough to be far
+    Y = np.concatenate([one, one, one]).astype(np.float32)
+    Y[2, 7] = 1.5
+    wrep, _, far = tvote(Y, rows, 8, 1e-3, 1e-3)
+    assert (wrep[0], far[0]) == (0, 0b110)
+    # zero tolerance: the exact vote, except that +0 and -0 (equal as numbers) count as close
+    rng = np.random.default_rng(6)
+    H = O.mols_biadjacency(5, 3)
+    rows5 = O.file_rows(H)
+    G = rng.standard_normal((25, 50)).astype(np.float32)
+    Xc = np.zeros((75, 50), dtype=np.float32)
+    for j in range(25):
+        for k in range(3):
+            Xc[rows5[j, k]] = G[j]
+    for j in (2, 9, 17):
+        Xc[rows5[j, 1]] *= 2.0
+    Xc[rows5[4, 0]], Xc[rows5[4, 2]] = 1.0, 7.0
+    want = O.vote(Xc, rows5, 50)
+    got = tvote(Xc, rows5, 50, 0.0, 0.0)
+    for a, b in zip(want, got):
+        assert np.array_equal(a, b)
+    Xz = Xc.copy()
+    Xz[rows5[0, 0], 0], Xz[rows5[0, 1], 0], Xz[rows5[0, 2], 0] = 0.0, -0.0, 0.0
+    assert O.vote(Xz, rows5, 50)[2][0] == 0b101 and tvote(Xz, rows5, 50, 0.0, 0.0)[2][0] == 0
+
+
+@pytest.mark.parametrize("name,tvote", TOL_VOTES)
+def test_tolerant_vote_majority_property_under_rounding_noise(name, tvote):
+    # Sec. 2: a file is distorted iff at least r' of its copies are Byzantine -- still true when
+    # the honest copies differ by rounding noise below the tolerance and the Byzantine copies
+    # are far (and, colluding, close to each other)
+    rng = np.random.default_rng(7)
+    H = O.ramanujan_biadjacency(5, 5)
+    K, f, l, r = O.dims(H)
+    rows = O.file_rows(H)
+    fw = O.file_workers(H)
+    d = 40
+    G = rng.standard_normal((f, d)).astype(np.float32)
+    byz = {0, 1, 5, 7, 14, 20}
+    X = np.zeros((K * l, d), dtype=np.float32)
+    for j in range(f):
+        for k in range(r):
+            if int(fw[j, k]) in byz:
+                X[rows[j, k]] = -100.0 * G[j] * np.float32(1.0 + 1e-7 * k)
+            else:
+                X[rows[j, k]] = G[j] * (1.0 + 3e-7 * rng.standard_normal(d)).astype(np.float32)
+    wrep, wrow, far = tvote(X, rows, d, 1e-6, 1e-5)
+    exact_wrep, _, exact_neq = O.vote(X, rows, d)
+    assert (exact_neq != 0).all()                      # bitwise, no two copies agree any more
+    for j in range(f):
+        n_byz = sum(1 for k in range(r) if int(fw[j, k]) in byz)
+        honest_wins = int(fw[j, wrep[j]]) not in byz
+        assert honest_wins == (n_byz < (r + 1) // 2), j
+    assert np.array_equal(np.stack(O.vote_tolerant(X, rows, d, 1e-6, 1e-5)),
+                          np.stack(C.vote_tolerant(X, rows, d, 1e-6, 1e-5)))
