@@ -142,6 +142,24 @@ int byz_vote(const float *copies, int64_t d, int64_t ld, const int32_t *file_row
              int r, int32_t *winner_replica, int32_t *winner_row, uint32_t *pair_neq,
              void *stream);
 
+/*
+ * Majority vote for honest copies that agree only up to rounding.  Sec. 2 notes that precision
+ * issues between honest workers "can be handled by ... defining appropriate clusters amongst
+ * the returned gradients" and gives no rule; the rule here: two words are close iff their bit
+ * patterns are identical or |a - b| <= atol + rtol * max(|a|, |b|), the subtraction, the
+ * product and the sum each rounded to fp32 (a NaN is close only to an identical NaN); two
+ * copies are close iff all d words are; the winner of a file is the copy with the most close
+ * copies (itself included), the lowest replica index among equals.  Closeness is not
+ * transitive: this counts neighbours, it does not partition.  atol = rtol = 0 is byz_vote
+ * except that +0 and -0 count as close.
+ *   pair_far      device [f] uint32 out: bit p set iff the copies of pair p are not close
+ *   other arguments and errors as byz_vote; BYZ_EINVAL also for negative or NaN atol / rtol.
+ * Feed winner_row to byz_median (or another aggregator) as after byz_vote.
+ */
+int byz_vote_tolerant(const float *copies, int64_t d, int64_t ld, const int32_t *file_rows_dev,
+                      int f, int r, float atol, float rtol, int32_t *winner_replica,
+                      int32_t *winner_row, uint32_t *pair_far, void *stream);
+
 /* --------------------------------------------- device: coordinate-wise median (Sec. 2, 6.1) */
 
 /*

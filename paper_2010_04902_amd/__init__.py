@@ -32,6 +32,7 @@ from .binding import (  # noqa: F401
     byz_strerror,
     byz_trimmed_mean,
     byz_vote,
+    byz_vote_tolerant,
     byz_worst_case,
     library_path,
 )

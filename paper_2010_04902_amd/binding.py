@@ -58,6 +58,8 @@ def _load():
         "byz_worst_case": (c_int, [vp, c_int, i32p, i32p, u64p]),
         "byz_gamma_bound": (ctypes.c_double, [vp, c_int]),
         "byz_vote": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, vp]),
+        "byz_vote_tolerant": (c_int, [vp, i64, i64, vp, c_int, c_int, ctypes.c_float,
+                                      ctypes.c_float, vp, vp, vp, vp]),
         "byz_median": (c_int, [vp, i64, i64, vp, c_int, vp, vp]),
         "byz_trimmed_mean": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp]),
         "byz_multi_krum_workspace_bytes": (sz, [c_int]),
@@ -197,6 +199,24 @@ def byz_vote(copies, d, file_rows_dev, f, r, stream=None):
                             _dev_ptr(neq, ("int32",), "pair_neq"), _stream_ptr(stream)),
            "byz_vote")
     return wrep, wrow, neq
+
+
+def byz_vote_tolerant(copies, d, file_rows_dev, f, r, atol, rtol, stream=None):
+    """-> (winner_replica[f] int32, winner_row[f] int32, pair_far[f] int32 bit masks), on device."""
+    torch = _torch()
+    ld = _rows_2d(copies)
+    _need(file_rows_dev, int(f) * int(r), "file_rows_dev")
+    wrep = torch.empty(max(int(f), 0), dtype=torch.int32, device=copies.device)
+    wrow = torch.empty(max(int(f), 0), dtype=torch.int32, device=copies.device)
+    far = torch.empty(max(int(f), 0), dtype=torch.int32, device=copies.device)
+    _check(_load().byz_vote_tolerant(_dev_ptr(copies, ("float32",), "copies"), int(d), ld,
+                                     _dev_ptr(file_rows_dev, ("int32",), "file_rows_dev"),
+                                     int(f), int(r), float(atol), float(rtol),
+                                     _dev_ptr(wrep, ("int32",), "winner_replica"),
+                                     _dev_ptr(wrow, ("int32",), "winner_row"),
+                                     _dev_ptr(far, ("int32",), "pair_far"), _stream_ptr(stream)),
+           "byz_vote_tolerant")
+    return wrep, wrow, far
 
 
 def byz_median(rows_base, d, row_index_dev, out=None, stream=None):

@@ -408,6 +408,72 @@ __global__ __launch_bounds__(kBlock) void vote_pairs_kernel(
         decide_files(pair_neq, file_rows, f, R, winner_replica, winner_row);
 }
 
+// Nonzero iff some word of the two chunks is not close: bit patterns differ and
+// |a - b| > atol + rtol * max(|a|, |b|) (or the test involves a NaN).  Every operation is
+// rounded to fp32 on its own (no fused multiply-add), as the CPU reference does.
+template <int V>
+__device__ __forceinline__ uint32_t far_apart(const uint32_t (&a)[V], const uint32_t (&b)[V],
+                                              float atol, float rtol) {
+    uint32_t acc = 0;
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const float x = __uint_as_float(a[v]), y = __uint_as_float(b[v]);
+        const float diff = fabsf(__fsub_rn(x, y));
+        const float bound = __fadd_rn(atol, __fmul_rn(rtol, fmaxf(fabsf(x), fabsf(y))));
+        acc |= (a[v] != b[v] && !(diff <= bound)) ? 1u : 0u;
+    }
+    return acc;
+}
+
+// Tolerant variant of step a1 (Sec. 2: rounding differences between honest copies can be
+// handled by clustering the copies): for every file, which pairs of copies are not close
+// somewhere in [0, d).  Same decomposition as vote_pairs_kernel.
+template <int R, int V>
+__global__ __launch_bounds__(kBlock) void vote_pairs_tolerant_kernel(
+    const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ file_rows,
+    int f, float atol, float rtol, uint32_t *pair_far) {
+    const int lane = threadIdx.x & 63;
+    const int64_t n_vec = d / V;
+    const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (n_vec > 0) {
+        const uint32_t *base = X + (gt < n_vec ? gt : n_vec - 1) * V;
+        for (int j0 = 0; j0 < f; j0 += 64) {
+            const int j1 = j0 + 64 < f ? j0 + 64 : f;
+            uint32_t flags = 0;
+            for (int j = j0; j < j1; ++j) {
+                uint32_t x[R][V];
+#pragma unroll
+                for (int k = 0; k < R; ++k)
+                    load_vec<V>(base + (int64_t)file_rows[j * R + k] * ld, x[k]);
+                uint32_t wb = 0;
+#pragma unroll
+                for (int a = 0; a < R; ++a)
+#pragma unroll
+                    for (int b = a + 1; b < R; ++b)
+                        wb |= wave_any(far_apart<V>(x[a], x[b], atol, rtol)) << pair_bit(R, a, b);
+                if (lane == j - j0) flags |= wb;
+            }
+            merge_flags(pair_far + j0, j1 - j0, lane, flags);
+        }
+    }
+    const int tail = (int)(d - n_vec * V);
+    if (blockIdx.x == gridDim.x - 1 && (int)threadIdx.x < tail) {
+        const int64_t c = n_vec * V + threadIdx.x;
+        for (int j = 0; j < f; ++j) {
+            uint32_t x[R][1];
+#pragma unroll
+            for (int k = 0; k < R; ++k) x[k][0] = X[(int64_t)file_rows[j * R + k] * ld + c];
+            uint32_t bits = 0;
+#pragma unroll
+            for (int a = 0; a < R; ++a)
+#pragma unroll
+                for (int b = a + 1; b < R; ++b)
+                    bits |= far_apart<1>(x[a], x[b], atol, rtol) << pair_bit(R, a, b);
+            if (bits != 0) atomicOr(&pair_far[j], bits);
+        }
+    }
+}
+
 // Steps of the generated streamed programs (selnet_stream_<f>.inc), written against local names
 // of the kernel that includes them: NS slots per file, V words per thread, kAhead, stage, key,
 // o, lane, flags (one word per 64 files), chain_mask, and BYZ_S_ROW_ADDR(j, k) = address of this thread's vector in
@@ -986,6 +1052,26 @@ int launch_vote_pairs_r(int r, const uint32_t *X, int64_t d, int64_t ld, const i
     }
 }
 
+int launch_vote_pairs_tolerant(int r, const uint32_t *X, int64_t d, int64_t ld,
+                               const int32_t *rows, int f, float atol, float rtol, uint32_t *far,
+                               hipStream_t s) {
+    const unsigned g = blocks_for(d / kVec);
+    switch (r) {
+        case 3:
+            vote_pairs_tolerant_kernel<3, kVec><<<g, kBlock, 0, s>>>(X, d, ld, rows, f, atol, rtol, far);
+            break;
+        case 5:
+            vote_pairs_tolerant_kernel<5, kVec><<<g, kBlock, 0, s>>>(X, d, ld, rows, f, atol, rtol, far);
+            break;
+        case 7:
+            vote_pairs_tolerant_kernel<7, kVec><<<g, kBlock, 0, s>>>(X, d, ld, rows, f, atol, rtol, far);
+            break;
+        default: return BYZ_EINVAL;
+    }
+    BYZ_HIP(hipGetLastError());
+    return BYZ_OK;
+}
+
 // 64 < f <= 256 without a generated network
 int launch_column_wide(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
                        int b, uint32_t *out, const uint32_t *gate, int gate_n, hipStream_t s) {
@@ -1249,6 +1335,29 @@ extern "C" int byz_vote(const float *copies, int64_t d, int64_t ld, const int32_
     }
     vote_decide_kernel<<<1, kWide, 0, s>>>(pair_neq, file_rows_dev, f, r, winner_replica,
                                                winner_row);
+    BYZ_HIP(hipGetLastError());
+    return BYZ_OK;
+}
+
+extern "C" int byz_vote_tolerant(const float *copies, int64_t d, int64_t ld,
+                                 const int32_t *file_rows_dev, int f, int r, float atol, float rtol,
+                                 int32_t *winner_replica, int32_t *winner_row, uint32_t *pair_far,
+                                 void *stream) {
+    int rc = check_common(copies, d, ld, file_rows_dev, f, r);
+    if (rc != BYZ_OK) return rc;
+    if (winner_replica == nullptr || winner_row == nullptr || pair_far == nullptr)
+        return BYZ_EINVAL;
+    if (!(atol >= 0.0f) || !(rtol >= 0.0f)) return BYZ_EINVAL;  // also rejects NaN
+    hipStream_t s = (hipStream_t)stream;
+    const uint32_t *X = reinterpret_cast<const uint32_t *>(copies);
+    fill_u32_kernel<<<1, kWide, 0, s>>>(pair_far, f, 0u);
+    BYZ_HIP(hipGetLastError());
+    if (d > 0) {
+        rc = launch_vote_pairs_tolerant(r, X, d, ld, file_rows_dev, f, atol, rtol, pair_far, s);
+        if (rc != BYZ_OK) return rc;
+    }
+    vote_decide_kernel<<<1, kWide, 0, s>>>(pair_far, file_rows_dev, f, r, winner_replica,
+                                           winner_row);
     BYZ_HIP(hipGetLastError());
     return BYZ_OK;
 }

@@ -178,3 +178,23 @@ def test_bulyan_full_size():
     _, wrow, _ = B.byz_vote(w.X, w.d, rows_dev, w.f, w.r)
     torch.cuda.synchronize()
     assert _bulyan_check(w.X, wrow.cpu().numpy(), w.d, cfg.cmax, cfg.name, big=True)
+
+
+def test_tolerant_vote_full_size():
+    # workload 2 with relative rounding noise on every copy: bitwise no two copies agree, the
+    # tolerant vote still loses exactly the c_max files with r' Byzantine copies
+    from tests.test_gpu_parity import _tolerant_check
+    cfg = synth.CONFIGS[1]
+    w = W.from_config(cfg, DEV, ld=synth.padded_ld(cfg.d, 64))
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(20101004)
+    X = w.X
+    for row in range(X.shape[0]):  # row by row: no second full-size buffer
+        X[row, :w.d] *= 1.0 + 2e-7 * torch.randn(w.d, device=DEV, generator=gen)
+    wrep_o, far_o = _tolerant_check(X, w.file_rows, w.d, w.f, w.r, 1e-6, 1e-5, cfg.name)
+    lost = [j for j in range(w.f) if int(w.file_workers[j, wrep_o[j]]) in w.byz]
+    assert len(lost) == cfg.cmax
+    wrep_v, _, neq_v = B.byz_vote(X, w.d, torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32,
+                                                       device=DEV), w.f, w.r)
+    torch.cuda.synchronize()
+    assert (W.bits(neq_v) == 7).all()  # the exact vote finds no two equal copies

@@ -602,3 +602,67 @@ def test_bulyan_ties_and_identical_vectors():
     Y = torch.tensor(np.repeat(vals[:, None], 16, axis=1), device=DEV)
     assert _bulyan_check(Y, np.arange(15, dtype=np.int32), 16, 2, "integer ties", exact_order=True)
     assert _bulyan_check(Y, np.arange(15, dtype=np.int32), 16, 3, "integer ties", exact_order=True)
+
+
+def _tolerant_check(X, rows_np, d, f, r, atol, rtol, tag):
+    rows_dev = torch.tensor(rows_np.reshape(-1), dtype=torch.int32, device=DEV)
+    wrep, wrow, far = B.byz_vote_tolerant(X, d, rows_dev, f, r, atol, rtol)
+    torch.cuda.synchronize()
+    wrep_o, wrow_o, far_o = C.vote_tolerant(X.detach().cpu().numpy(), rows_np, d, atol, rtol)
+    # the decision is taken in fp32 on both sides: every word must agree
+    assert np.array_equal(W.bits(far), far_o), tag
+    assert np.array_equal(wrep.cpu().numpy(), wrep_o), tag
+    assert np.array_equal(wrow.cpu().numpy(), wrow_o), tag
+    return wrep_o, far_o
+
+
+@pytest.mark.parametrize("scheme,a,b,q", [(MOLS, 5, 3, 4), (RAM, 5, 5, 6), (RAM, 7, 7, 3),
+                                          (MOLS, 9, 3, 4)])
+def test_tolerant_vote(scheme, a, b, q):
+    # honest copies of a file differ by relative rounding noise, Byzantine copies are far away
+    rng = np.random.default_rng(900 + a)
+    for i, d in enumerate([1, 2, 3, 5, 64, 1000, 4099, 70001]):
+        ld = d if i % 2 == 0 else synth.padded_ld(d, 4) + 4
+        w = W.make(scheme, a, b, q, d, REVERSED, seed=800 + i, ld=ld, device=DEV)
+        X = w.X.clone()
+        noise = torch.tensor(rng.standard_normal((X.shape[0], d)).astype(np.float32), device=DEV)
+        X[:, :d] *= (1.0 + 2e-7 * noise)
+        for atol, rtol in [(1e-6, 1e-5), (0.0, 1e-6), (0.0, 3e-7), (1e-7, 0.0), (0.0, 0.0)]:
+            wrep_o, far_o = _tolerant_check(X, w.file_rows, d, w.f, w.r, atol, rtol, (d, atol, rtol))
+        # with the widest tolerance honest copies are close to each other and the vote behaves
+        # as Sec. 2 says: a file is lost iff at least r' of its copies are Byzantine
+        wrep_o, _ = _tolerant_check(X, w.file_rows, d, w.f, w.r, 1e-6, 1e-5, d)
+        lost = [j for j in range(w.f) if int(w.file_workers[j, wrep_o[j]]) in w.byz]
+        assert len(lost) == w.cmax
+    # noise right at the tolerance: many element-wise decisions fall within an ulp of the bound
+    w = W.make(MOLS, 5, 3, 0, 3, REVERSED, seed=77, device=DEV)
+    for trial in range(20):
+        X = w.X.clone()
+        noise = torch.tensor(rng.standard_normal((X.shape[0], 3)).astype(np.float32), device=DEV)
+        X[:, :3] *= (1.0 + 1e-6 * noise)
+        _, far_o = _tolerant_check(X, w.file_rows, 3, w.f, w.r, 0.0, 2e-6, trial)
+    assert 0 < np.count_nonzero(far_o) < w.f  # the last trial has both outcomes
+
+
+def test_tolerant_vote_special_values_and_errors():
+    d = 2048
+    w = W.make(MOLS, 5, 3, 4, d, ALIE, seed=81, device=DEV)
+    X = w.X.clone()
+    Xi = X.view(torch.int32)
+    rng = np.random.default_rng(82)
+    patterns = np.array([0x7FC00000, 0xFFC00000, 0x7F800000, 0xFF800000, 0x80000000, 0x00000000,
+                         0x00000001, 0x80000001, 0x7F7FFFFF], dtype=np.uint32).view(np.int32)
+    for _ in range(800):
+        row = int(rng.integers(0, X.shape[0]))
+        c = int(rng.integers(0, d))
+        Xi[row, c] = int(patterns[rng.integers(0, len(patterns))])
+    for atol, rtol in [(0.0, 0.0), (1e-3, 1e-3), (float("inf"), 0.0)]:
+        _tolerant_check(X, w.file_rows, d, w.f, w.r, atol, rtol, (atol, rtol))
+    rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+    for atol, rtol in [(-1.0, 0.0), (0.0, -1e-3), (float("nan"), 0.0)]:
+        with pytest.raises(B.ByzError) as e:
+            B.byz_vote_tolerant(X, d, rows_dev, w.f, w.r, atol, rtol)
+        assert e.value.code == -1
+    wrep, wrow, far = B.byz_vote_tolerant(X, 0, rows_dev, w.f, w.r, 0.0, 0.0)
+    torch.cuda.synchronize()
+    assert (wrep == 0).all() and (far == 0).all()
