@@ -666,3 +666,49 @@ def test_tolerant_vote_special_values_and_errors():
     wrep, wrow, far = B.byz_vote_tolerant(X, 0, rows_dev, w.f, w.r, 0.0, 0.0)
     torch.cuda.synchronize()
     assert (wrep == 0).all() and (far == 0).all()
+
+
+@pytest.mark.parametrize("l", [5, 7])
+def test_hip_graph_capture_of_the_other_entry_points(l):
+    # vote (exact and tolerant), trimmed mean, Multi-Krum and Bulyan also enqueue kernels only;
+    # f = 49 uses the Gram kernel that asks for more than 64 KiB of LDS
+    w = W.make(MOLS, l, 3, 3, 50_001, dict(REVERSED, file_scales=True), seed=14, device=DEV)
+    rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+    c = 2
+
+    def run(X):
+        wrep, wrow, neq = B.byz_vote(X, w.d, rows_dev, w.f, w.r)
+        trep, trow, far = B.byz_vote_tolerant(X, w.d, rows_dev, w.f, w.r, 1e-6, 1e-5)
+        tm = B.byz_trimmed_mean(X, w.d, wrow, c)
+        mk, sel, scores, dist = B.byz_multi_krum(X, w.d, wrow, c, w.f - c)
+        bu, bsel, order, bdist = B.byz_bulyan(X, w.d, trow, c)
+        return [wrep, neq, trep, far, tm, mk, sel, bu, bsel, order]
+
+    X2 = w.X.clone()
+    X2[int(w.file_rows[2, 1])] *= 3.0
+    X2[int(w.file_rows[2, 2])] *= 3.0   # two equal wrong copies win file 2
+    eager = [[t.clone() for t in run(X)] for X in (w.X, X2)]
+    torch.cuda.synchronize()
+    assert eager[0][0][2].item() == 0 and eager[1][0][2].item() == 1
+    Xs = w.X.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(Xs)  # warm-up outside the capture (first-call set-up of the library and of torch)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        outs = run(Xs)
+    for rep, which in enumerate([0, 1, 0, 1]):
+        Xs.copy_((w.X, X2)[which])
+        for t in outs:
+            t.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip(outs, eager[which]):
+            assert torch.equal(got.view(torch.int32), want.view(torch.int32)), (rep, which)
+        again = run((w.X, X2)[which])  # eager work between replays
+        torch.cuda.synchronize()
+        for got, want in zip(again, eager[which]):
+            assert torch.equal(got.view(torch.int32), want.view(torch.int32))
