@@ -33,7 +33,8 @@ namespace {
 
 constexpr int kBlock = 256;            // 4 waves
 constexpr int kChunk = 256;            // coordinates staged per block and step
-constexpr int kStride = kChunk + 4;    // row pitch in LDS: bank = 4*row + k for the MFMA operand reads
+constexpr int kStride = kChunk + 2;    // row pitch in LDS: the 32 lanes served per cycle by an MFMA
+                                       // operand read hit bank 2*row + k, all different (32 banks)
 constexpr int kGramBlocks = 512;       // partial Gram tiles (2 blocks per CU; 1024: 4 % faster, reduction 3 us slower)
 constexpr int kTile = 16 * 16;         // outputs of one MFMA tile
 constexpr int kMaxNT = BYZ_MAX_F / 16; // row tiles of the largest matrix
@@ -415,7 +416,7 @@ int launch_gram(const float *rows_base, int64_t d, int64_t ld, const int32_t *ro
         gram_partial_kernel<3, 12><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
                                                             ws->partial);
     } else {
-        // 64 rows x 260 words is a little over the 64 KiB a kernel may use without asking
+        // 64 rows x 258 words is a little over the 64 KiB a kernel may use without asking
         if (f <= 52) {
             BYZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&gram_partial_kernel<4, 13>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
