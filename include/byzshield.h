@@ -166,10 +166,13 @@ int byz_vote_tolerant(const float *copies, int64_t d, int64_t ld, const int32_t 
  * out[c] = element of rank (f-1)/2 of { rows_base[row_index[j]*ld + c] : j < f }.
  *   rows_base     device [*][ld] fp32;  row_index_dev device [f] int32;  out device [d] fp32,
  *                 must not overlap the input rows (may be NULL when d == 0).
- * f odd, 1 <= f <= BYZ_MAX_F_WIDE; f in {3,5,7,9,15,21,25,35,49} (the paper's file and
- * worker counts) runs a register selection network, other odd f <= 64 a slower generic kernel,
- * 64 < f a kernel that keeps the f keys of a coordinate in LDS and finds the median by
- * bisection on the key (32 counting passes; about 2-3x off the HBM bound).  Errors: BYZ_EINVAL, BYZ_EUNSUPPORTED (even f), BYZ_EDEVICE.
+ * f odd, 1 <= f <= BYZ_MAX_F_WIDE.  A register selection network does the work for every
+ * f <= 121: generated for f in {3,5,7,9,15,21,25,35,49,81,121} (the paper's file and worker
+ * counts and MOLS over F_9, F_11), any other f on the next of those sizes with the spare wires
+ * tied half to the smallest and half to the largest key (f = 27: 0.23 ms for 11.2 M
+ * coordinates, f = 63: 1.1 ms).  121 < f keeps the f keys of a coordinate in LDS and finds the
+ * median by bisection on the key (slow).  Errors: BYZ_EINVAL, BYZ_EUNSUPPORTED (even f),
+ * BYZ_EDEVICE.
  */
 int byz_median(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev,
                int f, float *out, void *stream);
@@ -184,8 +187,9 @@ int byz_median(const float *rows_base, int64_t d, int64_t ld, const int32_t *row
  * infinities go first).  b = 0 is the plain mean.  Not pure selection; the rounding contract
  * is: fp32, kept values added one by one in ascending order starting from +0, then one IEEE
  * division by float(f - 2b).
- *   f in {9,15,21,25,35,49} runs a register sorting network, other f <= 64 a slower generic
- *   kernel, 64 < f <= BYZ_MAX_F_WIDE an insertion sort of the coordinate's keys in LDS.
+ *   f in {9,15,21,25,35,49,81,121} runs a generated register sorting network, any other
+ *   f <= 121 the next of those sizes with the spare wires tied to the largest key, 121 < f <=
+ *   BYZ_MAX_F_WIDE an insertion sort of the coordinate's keys in LDS (slow).
  * Errors: BYZ_EINVAL (null pointers, sizes, b < 0 or 2b >= f), BYZ_EDEVICE.
  */
 int byz_trimmed_mean(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev,

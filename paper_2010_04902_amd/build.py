@@ -12,7 +12,7 @@ LIB = os.path.join(PKG, "libbyzshield.so")
 KERNELS = os.path.join(CSRC, "kernels.hip")
 # kernels.hip is compiled once per part (-DBYZ_PART=n): the single-pass kernels are large and
 # build in parallel this way
-KERNEL_PARTS = (0, 1, 2, 3, 4)
+KERNEL_PARTS = (0, 1, 2, 3, 4, 5, 6)
 OTHER_SOURCES = [os.path.join(CSRC, "krum.hip"), os.path.join(CSRC, "host.cpp")]
 
 

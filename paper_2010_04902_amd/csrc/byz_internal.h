@@ -23,6 +23,15 @@ BYZ_DECLARE_SINGLE_PASS(2);
 BYZ_DECLARE_SINGLE_PASS(3);
 BYZ_DECLARE_SINGLE_PASS(4);
 
+// Coordinate-wise median / trimmed mean of the rows row_index[0..f-1] (kernels.hip, parts 5 and
+// 6): picks the network kernel for f; gate != NULL makes the kernels return at once unless one
+// of gate[0..gate_n-1] is nonzero.  Device pointers.  Returns a byz_status.
+int byz_internal_launch_median(const void *X, long long d, long long ld, const int *row_index,
+                               int f, void *out, const void *gate, int gate_n, void *stream);
+int byz_internal_launch_trimmed_mean(const void *X, long long d, long long ld,
+                                     const int *row_index, int f, int b, void *out,
+                                     const void *gate, int gate_n, void *stream);
+
 // Records the event before (which = 0) or after (1) the dominant kernel of an aggregation, if
 // byz_profile_enable has armed any.  Returns a byz_status.
 int byz_internal_profile_mark(int which, void *stream);

@@ -20,8 +20,9 @@
 #include "byzshield.h"
 
 // The build compiles this file once per BYZ_PART, in parallel, because the single-pass kernels
-// are large: part 0 holds every entry point and all other kernels, parts 1..4 one group of
-// single-pass instantiations each (byz_internal_launch_single_pass_<n>).  Without BYZ_PART
+// are large: part 0 holds every entry point, the vote and the Bulyan kernels, parts 1..4 one
+// group of single-pass instantiations each (byz_internal_launch_single_pass_<n>), part 5 the
+// median kernels and part 6 the trimmed-mean kernels.  Without BYZ_PART
 // the whole library is this one translation unit.
 #ifndef BYZ_PART
 #define BYZ_PART -1
@@ -568,15 +569,19 @@ __global__ __launch_bounds__(kBlock) void median_kernel(
     }
 }
 
-// Step a3 for the large generated networks (F = 81, 121: MOLS over F_9 and F_11): the streamed
-// program with V = vec_for(F) words per thread.  Thread t owns the words starting at
-// min(V*t, d - V): the last vector overlaps its neighbour (both write the same values).
-// Needs d >= V.
-template <int F, int V>
+// Step a3 by the streamed program of the generated network on F wires with V = vec_for(F)
+// words per thread: the large networks (F = 81, 121: MOLS over F_9 and F_11) and, with PAD,
+// any odd f < F on the next generated size -- the F - f spare wires reload row_index[0] and
+// are tied half to the smallest and half to the largest key, which leaves the median where
+// it was.  Thread t owns the words starting at min(V*t, d - V): the last vector overlaps its
+// neighbour (both write the same values).  Needs d >= V.
+template <int F, int V, bool PAD>
 __global__ __launch_bounds__(kBlock) void median_large_kernel(
     const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
-    uint32_t *__restrict__ out, const uint32_t *__restrict__ gate, int gate_n) {
+    int f, uint32_t *__restrict__ out, const uint32_t *__restrict__ gate, int gate_n) {
     if (gate != nullptr && !any_word_set(gate, gate_n)) return;
+    const int pad_low_end = f + (F - f) / 2;  // wires [f, pad_low_end) smallest key, rest largest
+    (void)pad_low_end;
     const int64_t n_thr = (d + V - 1) / V;
     const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (gt >= n_thr) return;
@@ -592,13 +597,19 @@ __global__ __launch_bounds__(kBlock) void median_large_kernel(
     const int lane = 0;
     uint32_t flags[(F + 63) / 64] = {};
     (void)chain_mask; (void)lane; (void)flags;
-#define BYZ_S_ROW_ADDR(j, k) (Xb + (uint64_t)(uint32_t)row_index[j] * (uint64_t)ld * 4u + voff)
+#undef BYZ_S_KEY
+#define BYZ_S_KEY(j, x) \
+    (!PAD || (j) < f ? to_key(x) : ((j) < pad_low_end ? 0u : 0xFFFFFFFFu))
+#define BYZ_S_ROW_ADDR(j, k) \
+    (Xb + (uint64_t)(uint32_t)row_index[!PAD || (j) < f ? (j) : 0] * (uint64_t)ld * 4u + voff)
 #include "generated/selnet_stream_dispatch.inc"
 #undef BYZ_S_ROW_ADDR
+#undef BYZ_S_KEY
+#define BYZ_S_KEY(j, x) to_key(x)
     store_vec<V>(out + c0, o);
 }
 
-// Step a3 for any odd f <= 64 (no generated network): rank counting, one coordinate a thread.
+// Step a3 for d below the vector width of the network kernels: rank counting, one coordinate a thread (f <= 64): rank counting, one coordinate a thread.
 __global__ __launch_bounds__(kBlock) void median_generic_kernel(
     const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
     int f, uint32_t *__restrict__ out, const uint32_t *__restrict__ gate, int gate_n) {
@@ -620,15 +631,16 @@ __global__ __launch_bounds__(kBlock) void median_generic_kernel(
 // Rounding contract of the trimmed mean: fp32, the kept values (ranks b .. F-b-1 of the sorted
 // keys) are added one by one in ascending order starting from +0, then one IEEE division.
 template <int F, int V>
-__device__ __forceinline__ void trimmed_mean_of_sorted(const uint32_t (&key)[V][F], int b,
+__device__ __forceinline__ void trimmed_mean_of_sorted(const uint32_t (&key)[V][F], int f, int b,
                                                        uint32_t (&o)[V]) {
-    const float denom = (float)(F - 2 * b);
+    // wires 0..f-1 hold the f values in ascending order (f = F unless the network is padded)
+    const float denom = (float)(f - 2 * b);
 #pragma unroll
     for (int v = 0; v < V; ++v) {
         float acc = 0.0f;
 #pragma unroll
         for (int i = 0; i < F; ++i)
-            if (i >= b && i < F - b) acc += __uint_as_float(from_key(key[v][i]));
+            if (i >= b && i < f - b) acc += __uint_as_float(from_key(key[v][i]));
         o[v] = __float_as_uint(acc / denom);
     }
 }
@@ -639,10 +651,10 @@ __device__ __forceinline__ void trimmed_mean_of_sorted(const uint32_t (&key)[V][
 // starting from +0, then divided by float(F - 2b) (IEEE division).  Thread t owns the four
 // words starting at min(4t, d - 4): the last vector overlaps its neighbour instead of a scalar
 // tail (both write the same values).  Needs d >= 4.
-template <int F, int V>
+template <int F, int V, bool PAD>
 __global__ __launch_bounds__(kBlock) void trimmed_mean_kernel(
     const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
-    int b, uint32_t *__restrict__ out, const uint32_t *__restrict__ gate, int gate_n) {
+    int f, int b, uint32_t *__restrict__ out, const uint32_t *__restrict__ gate, int gate_n) {
     if (gate != nullptr && !any_word_set(gate, gate_n)) return;
     const int64_t n_thr = (d + V - 1) / V;
     const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
@@ -658,11 +670,18 @@ __global__ __launch_bounds__(kBlock) void trimmed_mean_kernel(
     const int lane = 0;
     uint32_t flags[(F + 63) / 64] = {};
     (void)chain_mask; (void)lane; (void)flags;
-#define BYZ_S_ROW_ADDR(j, k) (Xb + (uint64_t)(uint32_t)row_index[j] * (uint64_t)ld * 4u + voff)
+    // PAD: f < F rows on the next generated size; the spare wires reload row_index[0] and carry
+    // the largest key, so wires 0..f-1 end up holding the f values in ascending order
+#undef BYZ_S_KEY
+#define BYZ_S_KEY(j, x) (!PAD || (j) < f ? to_key(x) : 0xFFFFFFFFu)
+#define BYZ_S_ROW_ADDR(j, k) \
+    (Xb + (uint64_t)(uint32_t)row_index[!PAD || (j) < f ? (j) : 0] * (uint64_t)ld * 4u + voff)
 #include "generated/selnet_sort_stream_dispatch.inc"
 #undef BYZ_S_ROW_ADDR
+#undef BYZ_S_KEY
+#define BYZ_S_KEY(j, x) to_key(x)
     uint32_t o[V];
-    trimmed_mean_of_sorted<F, V>(key, b, o);
+    trimmed_mean_of_sorted<F, V>(key, PAD ? f : F, b, o);
     store_vec<V>(out + c0, o);
 }
 
@@ -988,7 +1007,7 @@ __device__ __forceinline__ void fused_body(const uint32_t *__restrict__ X, int64
 #include "generated/selnet_stream_dispatch.inc"
     } else {
 #include "generated/selnet_sort_stream_dispatch.inc"
-        trimmed_mean_of_sorted<F, V>(key, trim_b, o);
+        trimmed_mean_of_sorted<F, V>(key, F, trim_b, o);
     }
 #undef BYZ_S_ROW_ADDR
     if (gt < n_thr) store_vec<V>(out + c0, o);
@@ -1072,6 +1091,9 @@ int launch_vote_pairs_tolerant(int r, const uint32_t *X, int64_t d, int64_t ld,
     return BYZ_OK;
 }
 
+#endif  // part 0
+
+#if BYZ_IN_PART(5) || BYZ_IN_PART(6)
 // 64 < f <= 256 without a generated network
 int launch_column_wide(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
                        int b, uint32_t *out, const uint32_t *gate, int gate_n, hipStream_t s) {
@@ -1083,11 +1105,24 @@ int launch_column_wide(const uint32_t *X, int64_t d, int64_t ld, const int32_t *
     return BYZ_OK;
 }
 
+#endif  // parts 5, 6
+
+#if BYZ_IN_PART(5)
 template <int F>
 int launch_median_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index,
                       uint32_t *out, const uint32_t *gate, int gate_n, hipStream_t s) {
     median_kernel<F, kVec><<<blocks_for(d / kVec), kBlock, 0, s>>>(X, d, ld, row_index, out, gate,
                                                                   gate_n);
+    BYZ_HIP(hipGetLastError());
+    return BYZ_OK;
+}
+
+template <int F, bool PAD>
+int launch_median_large(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
+                        uint32_t *out, const uint32_t *gate, int gate_n, hipStream_t s) {
+    constexpr int V = vec_for(F);
+    median_large_kernel<F, V, PAD><<<blocks_for((d + V - 1) / V), kBlock, 0, s>>>(
+        X, d, ld, row_index, f, out, gate, gate_n);
     BYZ_HIP(hipGetLastError());
     return BYZ_OK;
 }
@@ -1106,29 +1141,30 @@ int launch_median(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_i
         case 25: return launch_median_net<25>(X, d, ld, row_index, out, gate, gate_n, s);
         case 35: return launch_median_net<35>(X, d, ld, row_index, out, gate, gate_n, s);
         case 49: return launch_median_net<49>(X, d, ld, row_index, out, gate, gate_n, s);
-        case 81:
-            if (d < vec_for(81)) return launch_column_wide(X, d, ld, row_index, f, -1, out, gate, gate_n, s);
-            median_large_kernel<81, vec_for(81)>
-                <<<blocks_for((d + vec_for(81) - 1) / vec_for(81)), kBlock, 0, s>>>(
-                    X, d, ld, row_index, out, gate, gate_n);
-            BYZ_HIP(hipGetLastError());
-            return BYZ_OK;
-        case 121:
-            median_large_kernel<121, vec_for(121)>
-                <<<blocks_for((d + vec_for(121) - 1) / vec_for(121)), kBlock, 0, s>>>(
-                    X, d, ld, row_index, out, gate, gate_n);
-            BYZ_HIP(hipGetLastError());
-            return BYZ_OK;
-        default:
-            if (f > BYZ_MAX_F) return launch_column_wide(X, d, ld, row_index, f, -1, out, gate, gate_n, s);
-            median_generic_kernel<<<blocks_for(d), kBlock, 0, s>>>(X, d, ld, row_index, f, out,
-                                                                   gate, gate_n);
-            BYZ_HIP(hipGetLastError());
-            return BYZ_OK;
+        default: break;
     }
+    if (d < kVec && f <= BYZ_MAX_F) {  // too short for the vector kernels: cost is irrelevant
+        median_generic_kernel<<<blocks_for(d), kBlock, 0, s>>>(X, d, ld, row_index, f, out, gate,
+                                                               gate_n);
+        BYZ_HIP(hipGetLastError());
+        return BYZ_OK;
+    }
+    // any other odd f: the next generated size with spare wires, if d allows its vector width
+    if (f <= 15) return launch_median_large<15, true>(X, d, ld, row_index, f, out, gate, gate_n, s);
+    if (f <= 21) return launch_median_large<21, true>(X, d, ld, row_index, f, out, gate, gate_n, s);
+    if (f <= 25) return launch_median_large<25, true>(X, d, ld, row_index, f, out, gate, gate_n, s);
+    if (f <= 35) return launch_median_large<35, true>(X, d, ld, row_index, f, out, gate, gate_n, s);
+    if (f <= 49) return launch_median_large<49, true>(X, d, ld, row_index, f, out, gate, gate_n, s);
+    if (f == 81 && d >= vec_for(81))
+        return launch_median_large<81, false>(X, d, ld, row_index, f, out, gate, gate_n, s);
+    if (f <= 81 && d >= vec_for(81))
+        return launch_median_large<81, true>(X, d, ld, row_index, f, out, gate, gate_n, s);
+    if (f == 121) return launch_median_large<121, false>(X, d, ld, row_index, f, out, gate, gate_n, s);
+    if (f <= 121) return launch_median_large<121, true>(X, d, ld, row_index, f, out, gate, gate_n, s);
+    return launch_column_wide(X, d, ld, row_index, f, -1, out, gate, gate_n, s);
 }
 
-#endif  // part 0
+#endif  // part 5
 
 template <int F, int R>
 int launch_fused(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, AggWorkspace *ws,
@@ -1149,13 +1185,13 @@ int launch_fused(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, 
     return byz_internal_profile_mark(1, s);
 }
 
-#if BYZ_IN_PART(0)
-template <int F>
-int launch_trimmed_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int b,
-                       uint32_t *O, const uint32_t *gate, int gate_n, hipStream_t s) {
+#if BYZ_IN_PART(6)
+template <int F, bool PAD>
+int launch_trimmed_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
+                       int b, uint32_t *O, const uint32_t *gate, int gate_n, hipStream_t s) {
     constexpr int V = vec_for(F);
-    trimmed_mean_kernel<F, V><<<blocks_for((d + V - 1) / V), kBlock, 0, s>>>(X, d, ld, row_index,
-                                                                             b, O, gate, gate_n);
+    trimmed_mean_kernel<F, V, PAD><<<blocks_for((d + V - 1) / V), kBlock, 0, s>>>(
+        X, d, ld, row_index, f, b, O, gate, gate_n);
     BYZ_HIP(hipGetLastError());
     return BYZ_OK;
 }
@@ -1163,26 +1199,42 @@ int launch_trimmed_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *
 int launch_trimmed_mean(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
                         int b, uint32_t *O, const uint32_t *gate, int gate_n, hipStream_t s) {
     if (d == 0) return BYZ_OK;
-    if (has_streamed_network(f) && d >= vec_for(f)) {
-        switch (f) {
-            case 9: return launch_trimmed_net<9>(X, d, ld, row_index, b, O, gate, gate_n, s);
-            case 15: return launch_trimmed_net<15>(X, d, ld, row_index, b, O, gate, gate_n, s);
-            case 21: return launch_trimmed_net<21>(X, d, ld, row_index, b, O, gate, gate_n, s);
-            case 25: return launch_trimmed_net<25>(X, d, ld, row_index, b, O, gate, gate_n, s);
-            case 35: return launch_trimmed_net<35>(X, d, ld, row_index, b, O, gate, gate_n, s);
-            case 49: return launch_trimmed_net<49>(X, d, ld, row_index, b, O, gate, gate_n, s);
-            case 81: return launch_trimmed_net<81>(X, d, ld, row_index, b, O, gate, gate_n, s);
-            case 121: return launch_trimmed_net<121>(X, d, ld, row_index, b, O, gate, gate_n, s);
-            default: break;
-        }
+    if (d < kVec && f <= BYZ_MAX_F) {  // too short for the vector kernels: cost is irrelevant
+        trimmed_mean_generic_kernel<<<blocks_for(d), kBlock, 0, s>>>(X, d, ld, row_index, f, b, O,
+                                                                     gate, gate_n);
+        BYZ_HIP(hipGetLastError());
+        return BYZ_OK;
     }
-    if (f > BYZ_MAX_F) return launch_column_wide(X, d, ld, row_index, f, b, O, gate, gate_n, s);
-    trimmed_mean_generic_kernel<<<blocks_for(d), kBlock, 0, s>>>(X, d, ld, row_index, f, b, O,
-                                                                 gate, gate_n);
-    BYZ_HIP(hipGetLastError());
-    return BYZ_OK;
+    // the generated full-sort network of size f, else the next size with spare wires
+    switch (f) {
+        case 9: return launch_trimmed_net<9, false>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
+        case 15: return launch_trimmed_net<15, false>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
+        case 21: return launch_trimmed_net<21, false>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
+        case 25: return launch_trimmed_net<25, false>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
+        case 35: return launch_trimmed_net<35, false>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
+        case 49: return launch_trimmed_net<49, false>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
+        default: break;
+    }
+    if (d >= kVec) {
+        if (f <= 9) return launch_trimmed_net<9, true>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
+        if (f <= 15) return launch_trimmed_net<15, true>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
+        if (f <= 21) return launch_trimmed_net<21, true>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
+        if (f <= 25) return launch_trimmed_net<25, true>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
+        if (f <= 35) return launch_trimmed_net<35, true>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
+        if (f <= 49) return launch_trimmed_net<49, true>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
+    }
+    if (f == 81 && d >= vec_for(81))
+        return launch_trimmed_net<81, false>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
+    if (f <= 81 && d >= vec_for(81))
+        return launch_trimmed_net<81, true>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
+    if (f == 121) return launch_trimmed_net<121, false>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
+    if (f <= 121) return launch_trimmed_net<121, true>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
+    return launch_column_wide(X, d, ld, row_index, f, b, O, gate, gate_n, s);
 }
 
+#endif  // part 6
+
+#if BYZ_IN_PART(0)
 template <int F>
 int launch_bulyan_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *selected_rows,
                       int theta, int beta, uint32_t *O, hipStream_t s) {
@@ -1213,6 +1265,27 @@ int check_common(const void *copies, int64_t d, int64_t ld, const void *rows, in
 #endif  // part 0
 
 }  // namespace
+
+// --------------------------------------- median and trimmed-mean launchers, a part each
+
+#if BYZ_IN_PART(5)
+int byz_internal_launch_median(const void *X, long long d, long long ld, const int *row_index,
+                               int f, void *out, const void *gate, int gate_n, void *stream) {
+    return launch_median(static_cast<const uint32_t *>(X), d, ld, row_index, f,
+                         static_cast<uint32_t *>(out), static_cast<const uint32_t *>(gate), gate_n,
+                         (hipStream_t)stream);
+}
+#endif
+
+#if BYZ_IN_PART(6)
+int byz_internal_launch_trimmed_mean(const void *X, long long d, long long ld,
+                                     const int *row_index, int f, int b, void *out,
+                                     const void *gate, int gate_n, void *stream) {
+    return launch_trimmed_mean(static_cast<const uint32_t *>(X), d, ld, row_index, f, b,
+                               static_cast<uint32_t *>(out), static_cast<const uint32_t *>(gate),
+                               gate_n, (hipStream_t)stream);
+}
+#endif
 
 // ------------------------------------------------- single-pass launchers, one group per part
 
@@ -1369,8 +1442,7 @@ extern "C" int byz_median(const float *rows_base, int64_t d, int64_t ld,
     if (d < 0 || ld < d || d > kMaxCoords) return BYZ_EINVAL;
     if (f < 1 || f > kWide) return BYZ_EINVAL;
     if ((f % 2) == 0) return BYZ_EUNSUPPORTED;
-    return launch_median(reinterpret_cast<const uint32_t *>(rows_base), d, ld, row_index_dev, f,
-                         reinterpret_cast<uint32_t *>(out), nullptr, 0, (hipStream_t)stream);
+    return byz_internal_launch_median(rows_base, d, ld, row_index_dev, f, out, nullptr, 0, stream);
 }
 
 extern "C" int byz_trimmed_mean(const float *rows_base, int64_t d, int64_t ld,
@@ -1381,9 +1453,8 @@ extern "C" int byz_trimmed_mean(const float *rows_base, int64_t d, int64_t ld,
     if (d < 0 || ld < d || d > kMaxCoords) return BYZ_EINVAL;
     if (f < 1 || f > kWide || b < 0 || 2 * b >= f) return BYZ_EINVAL;
     if (d == 0) return BYZ_OK;
-    return launch_trimmed_mean(reinterpret_cast<const uint32_t *>(rows_base), d, ld, row_index_dev,
-                               f, b, reinterpret_cast<uint32_t *>(out), nullptr, 0,
-                               (hipStream_t)stream);
+    return byz_internal_launch_trimmed_mean(rows_base, d, ld, row_index_dev, f, b, out, nullptr, 0,
+                                            stream);
 }
 
 extern "C" size_t byz_aggregate_workspace_bytes(int f, int r) {
@@ -1433,8 +1504,9 @@ extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
                                                ws->winner_row);
         BYZ_HIP(hipGetLastError());
         if (trim_b >= 0)
-            return launch_trimmed_mean(X, d, ld, ws->winner_row, f, trim_b, O, nullptr, 0, s);
-        return launch_median(X, d, ld, ws->winner_row, f, O, nullptr, 0, s);
+            return byz_internal_launch_trimmed_mean(X, d, ld, ws->winner_row, f, trim_b, O, nullptr,
+                                                    0, s);
+        return byz_internal_launch_median(X, d, ld, ws->winner_row, f, O, nullptr, 0, s);
     }
 
     // probe -> single pass -> exact path, whose two kernels return at once unless the single
@@ -1453,8 +1525,9 @@ extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
                              &ws->need_exact, s);
     if (rc != BYZ_OK) return rc;
     if (trim_b >= 0)
-        return launch_trimmed_mean(X, d, ld, ws->winner_row, f, trim_b, O, ws->viol, f, s);
-    return launch_median(X, d, ld, ws->winner_row, f, O, ws->viol, f, s);
+        return byz_internal_launch_trimmed_mean(X, d, ld, ws->winner_row, f, trim_b, O, ws->viol, f,
+                                                s);
+    return byz_internal_launch_median(X, d, ld, ws->winner_row, f, O, ws->viol, f, s);
 }
 
 extern "C" int byz_aggregate(const float *copies, int64_t d, int64_t ld,
