@@ -198,3 +198,60 @@ def test_tolerant_vote_full_size():
                                                        device=DEV), w.f, w.r)
     torch.cuda.synchronize()
     assert (W.bits(neq_v) == 7).all()  # the exact vote finds no two equal copies
+
+
+def test_largest_d():
+    # d = 2^30, the largest the entry points take (byte offsets inside a row use all 32 bits):
+    # Ramanujan (s=3, m=3): (K,f,l,r) = (9,9,3,3), 27 rows of 4 GiB.  The oracle runs on sampled
+    # coordinates (head, tail, random), gathered column-wise from the device buffer; the
+    # winners follow from how the rows are built.
+    d = 1 << 30
+    asg = B.byz_build_assignment(B.BYZ_SCHEME_RAMANUJAN, 3, 3)
+    rows_np = asg.file_rows()
+    f, r = asg.f, asg.r
+    free_bytes, _ = torch.cuda.mem_get_info()
+    if free_bytes < (f * r + 3) * 4 * d:
+        pytest.skip("needs %d GiB of device memory" % ((f * r + 3) * 4 * d >> 30))
+    X = torch.empty((f * r, d), dtype=torch.float32, device=DEV)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(2010)
+    for j in range(f):
+        X[int(rows_np[j, 0])].normal_(generator=gen)
+        for k in range(1, r):
+            X[int(rows_np[j, k])].copy_(X[int(rows_np[j, 0])])
+    # file 2: copies 0 and 1 carry the same wrong vector (they win); file 5: copy 2 differs in
+    # the last word only; file 7: copy 0 differs in one word no probe sample touches
+    X[int(rows_np[2, 0])].mul_(-100.0)
+    X[int(rows_np[2, 1])].copy_(X[int(rows_np[2, 0])])
+    X[int(rows_np[5, 2]), d - 1] += 1.0
+    hidden = (d // 2) + 12345
+    X[int(rows_np[7, 0]), hidden] += 1.0
+    rows_dev = torch.tensor(rows_np.reshape(-1), dtype=torch.int32, device=DEV)
+    out, wrep, ws = B.byz_aggregate(X, d, rows_dev, f, r)
+    wrep_v, wrow_v, neq_v = B.byz_vote(X, d, rows_dev, f, r)
+    out_m = B.byz_median(X, d, wrow_v)
+    torch.cuda.synchronize()
+    want_rep = np.zeros(f, dtype=np.int32)
+    want_rep[7] = 1                                   # copies 1 and 2 of file 7 agree
+    want_neq = np.zeros(f, dtype=np.uint32)
+    want_neq[2] = 0b110                               # pairs (0,2), (1,2)
+    want_neq[5] = 0b110
+    want_neq[7] = 0b011                               # pairs (0,1), (0,2)
+    assert np.array_equal(wrep.cpu().numpy(), want_rep)
+    assert np.array_equal(wrep_v.cpu().numpy(), want_rep)
+    assert np.array_equal(W.bits(neq_v), want_neq)
+    assert B.byz_aggregate_took_exact_path(ws)        # file 7's difference is off the sample
+    assert torch.equal(out.view(torch.int32), out_m.view(torch.int32))
+    rng = np.random.default_rng(30)
+    cols = np.unique(np.concatenate([np.arange(0, 2048), np.arange(d - 2048, d),
+                                     np.array([hidden - 1, hidden, hidden + 1]),
+                                     rng.integers(0, d, size=200_000)]))
+    cols_dev = torch.tensor(cols, dtype=torch.int64, device=DEV)
+    Xs = X[:, cols_dev].cpu().numpy()
+    # a vote on the sample alone cannot see the single differing words of files 5 and 7 unless
+    # they were drawn, so the oracle's median runs on the winners' rows derived above
+    win_rows = np.array([rows_np[j, want_rep[j]] for j in range(f)], dtype=np.int32)
+    out_w = C.median(np.ascontiguousarray(Xs), win_rows, len(cols))
+    assert np.array_equal(W.bits(out[cols_dev]), W.bits(out_w))
+    del X, out, out_m
+    torch.cuda.empty_cache()
