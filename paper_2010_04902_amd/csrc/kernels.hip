@@ -1,16 +1,17 @@
 // Device side of libbyzshield (gfx950): majority vote over the r copies of each file (Eq. 3 of
-// the ByzShield paper), coordinate-wise median over the f winners (Sec. 2, Sec. 6.1) and the
-// fused single-pass vote+median, plus the C-ABI entry points that launch them.
+// the ByzShield paper; exact and tolerant), coordinate-wise median over the f winners (Sec. 2,
+// Sec. 6.1), the fused single-pass vote+median, the trimmed mean and the second phase of
+// Bulyan, plus the C-ABI entry points that launch them.
 //
-// Work decomposition shared by all streaming kernels: one thread owns V = 4 consecutive
-// coordinates and walks over all files, so every global load of a wave is one contiguous
-// 1 KiB segment of one row (16-byte loads; gfx950 global loads only need dword alignment).
-// Threads past the end of the grid redo the last vector, so loads and wave ballots sit in
-// straight-line code; the d % V trailing words are done by a few threads of the last block.
+// Work decomposition shared by all streaming kernels: one thread owns V consecutive
+// coordinates (4; 2 or 1 for the largest networks) and walks over all files, so every global
+// load of a wave is one contiguous segment of one row (1 KiB with 16-byte loads; gfx950 global
+// loads only need dword alignment).  Threads past the end of the grid redo the last vector, so
+// loads and wave ballots sit in straight-line code; trailing words are done by a few threads
+// of the last block or by letting the last vector overlap its neighbour.
 // Per-file "copies differ" bits are reduced inside a wave with ballots (scalar registers),
-// parked in lane j for file j, and merged across waves with one atomicOr per file and wave
-// that is skipped when the bits are already set.  Where a second tiny kernel would only
-// post-process those bits, the block that finishes last (atomic ticket) does it instead.
+// parked in lane j mod 64 for file j (one word per 64 files), and merged across waves with one
+// atomicOr per file and wave that is skipped when the bits are already set.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -22,8 +23,8 @@
 // The build compiles this file once per BYZ_PART, in parallel, because the single-pass kernels
 // are large: part 0 holds every entry point, the vote and the Bulyan kernels, parts 1..4 one
 // group of single-pass instantiations each (byz_internal_launch_single_pass_<n>), part 5 the
-// median kernels and part 6 the trimmed-mean kernels.  Without BYZ_PART
-// the whole library is this one translation unit.
+// median kernels and part 6 the trimmed-mean kernels.  Without BYZ_PART the whole library is
+// this one translation unit.
 #ifndef BYZ_PART
 #define BYZ_PART -1
 #endif
@@ -53,7 +54,6 @@ struct ProfileState {
 thread_local ProfileState g_prof;
 #endif
 
-
 // Files the single-pass kernel prefetches ahead of the one it consumes, from the number of
 // 16-byte loads per thread it should keep in flight.  Measured on MI355X: about 6 for f = 25
 // (3-4 waves per SIMD), about 12 for f = 49 (2 waves per SIMD); more is slower.  f = 121 runs
@@ -66,7 +66,7 @@ constexpr int prefetch_depth(int f, int slots) {
     return a < 1 ? 1 : (a > 5 ? 5 : a);
 }
 // f with a generated streamed network (gen_selnet.py STREAMED_SIZES): the paper's file counts
-// l^2 (MOLS, Ramanujan Case 1) and m*s (Ramanujan Case 2)
+// l^2 (MOLS, Ramanujan Case 1; 81 and 121 for l = 9, 11) and m*s (Ramanujan Case 2)
 constexpr bool has_streamed_network(int f) {
     return f == 9 || f == 15 || f == 21 || f == 25 || f == 35 || f == 49 || f == 81 || f == 121;
 }
@@ -327,7 +327,7 @@ __global__ void fill_u32_kernel(uint32_t *p, int n, uint32_t value) {
     if (i < n) p[i] = value;
 }
 
-// Step a2: winners from the pair bits (lane j = file j).
+// Vote, decision: winners from the pair bits (thread j = file j).
 __device__ __forceinline__ void decide_files(const uint32_t *pair_neq,
                                              const int32_t *__restrict__ file_rows, int f, int r,
                                              int32_t *winner_replica, int32_t *winner_row) {
@@ -343,10 +343,10 @@ __global__ void vote_decide_kernel(const uint32_t *pair_neq, const int32_t *__re
     decide_files(pair_neq, file_rows, f, r, winner_replica, winner_row);
 }
 
-// Step a1: for every file, which pairs of copies differ anywhere in [0, d).  Threads own
+// Vote, comparison: for every file, which pairs of copies differ anywhere in [0, d).  Threads own
 // vectors of V words; the d % V trailing words go to the first threads of the last block.
 // If `ticket` is given (zero at launch), the block
-// that finishes last also runs step a2.  If `gate` is given, the kernel only runs when one of
+// that finishes last also takes the decision.  If `gate` is given, the kernel only runs when one of
 // gate[0..f-1] is nonzero; otherwise it publishes gate_off_winner as the winners and returns.
 template <int R, int V>
 __global__ __launch_bounds__(kBlock) void vote_pairs_kernel(
@@ -426,7 +426,7 @@ __device__ __forceinline__ uint32_t far_apart(const uint32_t (&a)[V], const uint
     return acc;
 }
 
-// Tolerant variant of step a1 (Sec. 2: rounding differences between honest copies can be
+// Tolerant variant of the vote's comparison (Sec. 2: rounding differences between honest copies can be
 // handled by clustering the copies): for every file, which pairs of copies are not close
 // somewhere in [0, d).  Same decomposition as vote_pairs_kernel.
 template <int R, int V>
@@ -520,7 +520,7 @@ __global__ __launch_bounds__(kBlock) void vote_pairs_tolerant_kernel(
 #define BYZ_S_MEDIAN(w)                                                                       \
     _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_) o[v_] = from_key(key[v_][w]);
 
-// Step a3: coordinate-wise median of F rows by a register selection network.
+// Coordinate-wise median of F rows by a register selection network.
 template <int F, int V>
 __global__ __launch_bounds__(kBlock) void median_kernel(
     const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
@@ -569,7 +569,7 @@ __global__ __launch_bounds__(kBlock) void median_kernel(
     }
 }
 
-// Step a3 by the streamed program of the generated network on F wires with V = vec_for(F)
+// Coordinate-wise median by the streamed program of the generated network on F wires with V = vec_for(F)
 // words per thread: the large networks (F = 81, 121: MOLS over F_9 and F_11) and, with PAD,
 // any odd f < F on the next generated size -- the F - f spare wires reload row_index[0] and
 // are tied half to the smallest and half to the largest key, which leaves the median where
@@ -609,7 +609,8 @@ __global__ __launch_bounds__(kBlock) void median_large_kernel(
     store_vec<V>(out + c0, o);
 }
 
-// Step a3 for d below the vector width of the network kernels: rank counting, one coordinate a thread (f <= 64): rank counting, one coordinate a thread.
+// Coordinate-wise median for d below the vector width of the network kernels (f <= 64): rank
+// counting, one coordinate a thread.
 __global__ __launch_bounds__(kBlock) void median_generic_kernel(
     const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
     int f, uint32_t *__restrict__ out, const uint32_t *__restrict__ gate, int gate_n) {
@@ -685,8 +686,8 @@ __global__ __launch_bounds__(kBlock) void trimmed_mean_kernel(
     store_vec<V>(out + c0, o);
 }
 
-// Trimmed mean for any f <= 64 (and for d < 4): insertion sort in per-thread memory, one
-// coordinate a thread; same rounding contract as trimmed_mean_kernel.
+// Trimmed mean for d below the vector width of the network kernels (f <= 64): insertion sort
+// in per-thread memory, one coordinate a thread; same rounding contract as trimmed_mean_kernel.
 __global__ __launch_bounds__(kBlock) void trimmed_mean_generic_kernel(
     const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
     int f, int b, uint32_t *__restrict__ out, const uint32_t *__restrict__ gate, int gate_n) {
@@ -842,7 +843,7 @@ __global__ __launch_bounds__(kBlock) void bulyan_mean_kernel(
     store_vec<V>(out + c0, o);
 }
 
-// Second phase of Bulyan for any f <= 64 (and for d < 4): one coordinate a thread, the chosen
+// Second phase of Bulyan for theta > 49 and for d < 4: one coordinate a thread, the chosen
 // values insertion-sorted in the thread's LDS column.  Dynamic LDS: theta*kBlock*4 bytes.
 __global__ __launch_bounds__(kBlock) void bulyan_mean_generic_kernel(
     const uint32_t *__restrict__ X, int64_t d, int64_t ld,
@@ -971,7 +972,7 @@ __global__ __launch_bounds__(kProbe) void probe_kernel(const uint32_t *__restric
     if (tid == 0) ws->slots_per_file = (early_majority != 0 && s_all_majority != 0) ? (R + 1) / 2 : R;
 }
 
-// Fused a1+a2+a3: streams the first NS slots of every file's permuted row list once (NS = R:
+// Vote and median in one pass: streams the first NS slots of every file's permuted row list once (NS = R:
 // every copy; NS = r' = (R+1)/2 in early-majority mode when every file has a probable
 // majority).  Slot 0 (the probable winner) feeds the median network; every equality the
 // probe assumed between neighbouring slots is checked over all coordinates and violations are
