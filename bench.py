@@ -20,6 +20,19 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 
 
+def kernel_code_digest():
+    """sha256 of kernels.hip without // comments, blank lines and indentation: changes when the
+    code does, not when a comment is reworded."""
+    src = os.path.join(ROOT, "paper_2010_04902_amd", "csrc", "kernels.hip")
+    lines = []
+    with open(src) as fh:
+        for line in fh:
+            code = line.split("//", 1)[0].strip()
+            if code:
+                lines.append(" ".join(code.split()))
+    return hashlib.sha256("\n".join(lines).encode()).hexdigest()
+
+
 def _traffic_from_profiles(workload, kernel="fused_kernel"):
     """HBM bytes per launch from the committed counter summary, or None if absent or stale."""
     path = os.path.join(ROOT, "profiles", "%s_%s_hbm_traffic.txt" % (kernel, workload))
@@ -31,10 +44,8 @@ def _traffic_from_profiles(workload, kernel="fused_kernel"):
             if "=" in line and not line.startswith("#"):
                 k, v = line.strip().split("=", 1)
                 kv[k.strip()] = v.strip()
-    src = os.path.join(ROOT, "paper_2010_04902_amd", "csrc", "kernels.hip")
-    sha = hashlib.sha256(open(src, "rb").read()).hexdigest()
-    if kv.get("kernels_hip_sha256") != sha:
-        return None  # the kernel changed since the counters were taken
+    if kv.get("kernels_hip_code_sha256") != kernel_code_digest():
+        return None  # the kernels' code changed since the counters were taken
     try:
         return float(kv["hbm_bytes_per_launch"])
     except (KeyError, ValueError):
