@@ -268,6 +268,10 @@ size_t byz_aggregate_workspace_bytes(int f, int r);
  * coordinates, every equality the probe assumed.  If a check fails (a copy that matches on
  * the sample but differs elsewhere) the exact two-step path (vote, then median) runs on the
  * device right after; the result is the same, only slower.
+ * The single pass is compiled for (f, r) = (9,3), (15,3), (21,3), (25,3), (25,5), (35,5),
+ * (49,3), (49,5), (81,3), (121,3) (byz_aggregate_has_single_pass); for every other valid
+ * (f, r), and for d < 4, the call runs byz_vote's kernels and then byz_median's, reading the
+ * winners a second time.
  * Errors: as byz_vote / byz_median, plus BYZ_ENOMEM (workspace too small).
  */
 int byz_aggregate(const float *copies, int64_t d, int64_t ld, const int32_t *file_rows_dev,
@@ -281,6 +285,7 @@ int byz_aggregate(const float *copies, int64_t d, int64_t ld, const int32_t *fil
  *     least r' of its copies are), so for every file whose probable winner's class has at
  *     least r' members only r' copies are read and verified.  Same output as flags = 0 for
  *     every input; HBM traffic drops from 4(rf+1) towards 4(r'f+1) bytes per coordinate.
+ *     Ignored where the single pass does not run.
  * Errors: as byz_aggregate; BYZ_EINVAL for unknown flag bits.
  */
 #define BYZ_AGG_EARLY_MAJORITY 1u
