@@ -33,8 +33,8 @@ namespace {
 
 constexpr int kBlock = 256;            // 4 waves
 constexpr int kChunk = 256;            // coordinates staged per block and step
-constexpr int kStride = kChunk + 2;    // row pitch in LDS: the 32 lanes served per cycle by an MFMA
-                                       // operand read hit bank 2*row + k, all different (32 banks)
+constexpr int kStride = kChunk + 4;    // row pitch in LDS: rows stay 16-byte aligned (one 16-byte
+                                       // staging write per lane); see the column swizzle below
 constexpr int kGramBlocks = 512;       // partial Gram tiles (2 blocks per CU; 1024: 4 % faster, reduction 3 us slower)
 constexpr int kTile = 16 * 16;         // outputs of one MFMA tile
 constexpr int kMaxNT = BYZ_MAX_F / 16; // row tiles of the largest matrix
@@ -107,15 +107,24 @@ __global__ __launch_bounds__(kBlock) void gram_partial_kernel(const float *__res
         for (int t = 0; t < RW; ++t) {
             const int j = wave + 4 * t;
             if (j < f) {
-                float *dst = T + j * kStride + 4 * lane;
-                dst[0] = reg[t][0]; dst[1] = reg[t][1]; dst[2] = reg[t][2]; dst[3] = reg[t][3];
+                // column c of row j lives at c ^ 2 if bit 3 of j is set: with pitch 260 the 32
+                // lanes an operand read serves per cycle (rows 0..15, k = 0,1 or 2,3) then hit
+                // bank 4*(row % 8) + (k ^ 2*(row / 8)), all different
+                f32x4 *dst = reinterpret_cast<f32x4 *>(T + j * kStride + 4 * lane);
+                const bool swz = (j & 8) != 0;
+                f32x4 v;
+                v[0] = swz ? reg[t][2] : reg[t][0];
+                v[1] = swz ? reg[t][3] : reg[t][1];
+                v[2] = swz ? reg[t][0] : reg[t][2];
+                v[3] = swz ? reg[t][1] : reg[t][3];
+                *dst = v;
             }
         }
         __syncthreads();
         if (chunk + gridDim.x < n_chunks) fetch(chunk + gridDim.x);
         // wave w multiplies coordinates [64w, 64w+64) of the chunk, four per MFMA: lane l holds
         // A[row = l%16][k = l/16], which is also B[k][col = l%16] of the transposed operand
-        const float *t0 = T + (lane & 15) * kStride + wave * 64 + (lane >> 4);
+        const float *t0 = T + (lane & 15) * kStride + wave * 64 + ((lane >> 4) ^ ((lane & 8) >> 2));
 #pragma unroll
         for (int s0 = 0; s0 < 16; s0 += 8) {
             float x[NT][8];
@@ -416,7 +425,7 @@ int launch_gram(const float *rows_base, int64_t d, int64_t ld, const int32_t *ro
         gram_partial_kernel<3, 12><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
                                                             ws->partial);
     } else {
-        // 64 rows x 258 words is a little over the 64 KiB a kernel may use without asking
+        // 64 rows x 260 words is a little over the 64 KiB a kernel may use without asking
         if (f <= 52) {
             BYZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&gram_partial_kernel<4, 13>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
