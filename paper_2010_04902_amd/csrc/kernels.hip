@@ -72,7 +72,9 @@ constexpr bool has_streamed_network(int f) {
 }
 // words per thread: fewer for the large networks, whose keys fill the register file
 constexpr int vec_for(int f) { return f <= 49 ? 4 : (f <= 81 ? 2 : 1); }
-constexpr int kProbe = 256;  // sampled coordinates = threads of the probe block (512: 2x slower)
+constexpr int kProbe = 256;  // sampled coordinates of the probe (512: 2x slower)
+constexpr int kProbeSplit = 4;  // the files are dealt out to this many groups of kProbe threads
+constexpr int kProbeThreads = kProbe * kProbeSplit;
 constexpr int kBlock = 256;  // threads per block of the streaming kernels (128/512/1024: slower)
 constexpr int kWide = BYZ_MAX_F_WIDE;  // largest f of the vote and the LDS column kernels
 static_assert(kWide <= kBlock, "one thread per file in the deciding block");
@@ -869,12 +871,14 @@ __global__ __launch_bounds__(kBlock) void bulyan_mean_generic_kernel(
 // of 16 consecutive words spread over [0, d); all of [0, d) when d <= kProbe), derives the probable
 // equality classes, and lays out the rows of each file with the probable winner first and
 // equal-looking copies adjacent.  Also clears the state the later kernels accumulate into.
-// One block of kProbe threads.
+// One block of kProbeThreads threads: thread group q = tid / kProbe takes the files
+// q, q + kProbeSplit, ..., every group on the same kProbe sample coordinates, so a thread waits
+// for F*R / kProbeSplit loads.
 template <int F, int R>
-__global__ __launch_bounds__(kProbe) void probe_kernel(const uint32_t *__restrict__ X, int64_t d,
-                                                    int64_t ld,
-                                                    const int32_t *__restrict__ file_rows,
-                                                    AggWorkspace *ws, int early_majority) {
+__global__ __launch_bounds__(kProbeThreads) void probe_kernel(const uint32_t *__restrict__ X,
+                                                           int64_t d, int64_t ld,
+                                                           const int32_t *__restrict__ file_rows,
+                                                           AggWorkspace *ws, int early_majority) {
     __shared__ uint32_t s_neq[kWide];
     __shared__ uint32_t s_all_majority;
     const int tid = threadIdx.x;
@@ -893,34 +897,43 @@ __global__ __launch_bounds__(kProbe) void probe_kernel(const uint32_t *__restric
     __syncthreads();
 
     // threads without a sample coordinate of their own redo coordinate 0
+    const int ct = tid % kProbe;  // which sample coordinate
+    const int q = tid / kProbe;   // which share of the files (wave-uniform: kProbe % 64 == 0)
     int64_t c = 0;
     if (d <= kProbe) {
-        if (tid < d) c = tid;
+        if (ct < d) c = ct;
     } else {
-        const int64_t run = tid >> 4, off = tid & 15;
+        const int64_t run = ct >> 4, off = ct & 15;
         c = run * ((d - 16) / (kProbe / 16 - 1)) + off;
     }
-    // files in groups of G: all loads of a group are issued before the first ballot waits
-    constexpr int G = (F * R <= 192) ? F : 192 / R;
-    uint32_t flags[(F + 63) / 64] = {};  // lane j%64 collects the bits of file j
+    // this group's files in batches of G: all loads of a batch are issued before the first
+    // ballot waits; the bits of file j are parked in lane j % 64, word j / 64
+    constexpr int kMine = (F + kProbeSplit - 1) / kProbeSplit;  // files per group, at most
+    constexpr int G = (kMine * R <= 96) ? kMine : 96 / R;
+    uint32_t flags[(F + 63) / 64] = {};
 #pragma unroll
-    for (int j0 = 0; j0 < F; j0 += G) {
+    for (int t0 = 0; t0 < kMine; t0 += G) {
         uint32_t x[G][R];
 #pragma unroll
-        for (int g = 0; g < G; ++g)
+        for (int g = 0; g < G; ++g) {
+            const int j = q + kProbeSplit * (t0 + g);
 #pragma unroll
             for (int k = 0; k < R; ++k)
-                if (j0 + g < F) x[g][k] = X[(int64_t)file_rows[(j0 + g) * R + k] * ld + c];
+                if (t0 + g < kMine && j < F) x[g][k] = X[(int64_t)file_rows[j * R + k] * ld + c];
+        }
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            if (j0 + g >= F) continue;
+            const int j = q + kProbeSplit * (t0 + g);
+            if (t0 + g >= kMine || j >= F) continue;
             uint32_t wb = 0;
 #pragma unroll
             for (int a = 0; a < R; ++a)
 #pragma unroll
                 for (int b = a + 1; b < R; ++b)
                     wb |= wave_any(x[g][a] ^ x[g][b]) << pair_bit(R, a, b);
-            if (lane == ((j0 + g) & 63)) flags[(j0 + g) >> 6] |= wb;
+#pragma unroll
+            for (int w = 0; w < (F + 63) / 64; ++w)
+                if (lane == (j & 63) && (j >> 6) == w) flags[w] |= wb;
         }
     }
 #pragma unroll
@@ -1170,7 +1183,7 @@ int launch_median(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_i
 template <int F, int R>
 int launch_fused(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, AggWorkspace *ws,
                  uint32_t *out, int early_majority, int trim_b, hipStream_t s) {
-    probe_kernel<F, R><<<1, kProbe, 0, s>>>(X, d, ld, rows, ws, early_majority);
+    probe_kernel<F, R><<<1, kProbeThreads, 0, s>>>(X, d, ld, rows, ws, early_majority);
     BYZ_HIP(hipGetLastError());
     int rc = byz_internal_profile_mark(0, s);
     if (rc != BYZ_OK) return rc;
