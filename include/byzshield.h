@@ -111,12 +111,29 @@ int byz_assignment_file_rows(const byz_assignment *g, int32_t *out);
  *   cmax_out          host, c_max^(q) (may be NULL)
  *   distorted_mask_out host [ceil(f/64)] words, bit j%64 of word j/64 set iff file j is
  *                     distorted by the returned set (may be NULL)
- * Errors: BYZ_EINVAL (null g, q < 0, q > K), BYZ_EUNSUPPORTED (f > BYZ_MAX_F_WIDE).
+ * Errors: BYZ_EINVAL (null g, q < 0, q > K), BYZ_EUNSUPPORTED (f > BYZ_MAX_F_WIDE), BYZ_ENOMEM.
  * Cost grows as C(K, q) (about 2*10^8 subsets per second and core); searches above 2*10^7
  * subsets use up to 16 host threads.  Not interruptible.
+ *
+ * Above 2*10^6 subsets the search first finds the value c_max over one representative per orbit
+ * of the assignment's symmetries -- translations of the file grid, which permute the workers of
+ * every parallel class among themselves: a set can be moved so that it contains the first
+ * worker of the lowest class it touches and, for MOLS and Ramanujan with m <= s, also the first
+ * worker of the next class (about K/q resp. l times fewer subsets) -- and then walks the
+ * subsets in lexicographic order only until the first one that reaches c_max.  Every symmetry
+ * is checked on the graph before it is used; the result is the same as the plain search's.
  */
 int byz_worst_case(const byz_assignment *g, int q, int32_t *byz_workers_out, int32_t *cmax_out,
                    uint64_t *distorted_mask_out);
+
+/* byz_worst_case with the strategy fixed: flags = 0 chooses as described above. */
+#define BYZ_SEARCH_EXHAUSTIVE 1u /* plain search over all C(K, q) subsets             */
+#define BYZ_SEARCH_SYMMETRY 2u   /* symmetry-reduced search whatever the size        */
+int byz_worst_case_opts(const byz_assignment *g, int q, unsigned flags, int32_t *byz_workers_out,
+                        int32_t *cmax_out, uint64_t *distorted_mask_out);
+
+/* Subsets evaluated by the calling thread's last byz_worst_case / byz_worst_case_opts call. */
+uint64_t byz_worst_case_last_visited(void);
 
 /* Upper bound gamma on c_max^(q): Eq. 5 with mu_1 = 1/r (Lemma 2) put into Claim 1.
  * Returns NaN if g is NULL or q is outside [0, K]. */

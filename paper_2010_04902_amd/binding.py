@@ -56,6 +56,8 @@ def _load():
         "byz_assignment_file_workers": (c_int, [vp, i32p]),
         "byz_assignment_file_rows": (c_int, [vp, i32p]),
         "byz_worst_case": (c_int, [vp, c_int, i32p, i32p, u64p]),
+        "byz_worst_case_opts": (c_int, [vp, c_int, ctypes.c_uint, i32p, i32p, u64p]),
+        "byz_worst_case_last_visited": (ctypes.c_uint64, []),
         "byz_gamma_bound": (ctypes.c_double, [vp, c_int]),
         "byz_vote": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, vp]),
         "byz_vote_tolerant": (c_int, [vp, i64, i64, vp, c_int, c_int, ctypes.c_float,
@@ -131,17 +133,26 @@ def byz_build_assignment(scheme, a, b):
     return Assignment(h)
 
 
-def byz_worst_case(asg, q):
+BYZ_SEARCH_EXHAUSTIVE = 1
+BYZ_SEARCH_SYMMETRY = 2
+
+
+def byz_worst_case(asg, q, flags=0):
     """Returns (byzantine workers as a tuple, c_max, distorted-file bit mask)."""
     S = np.zeros(max(int(q), 1), dtype=np.int32)
     cmax = ctypes.c_int32()
     words = np.zeros(max((asg.f + 63) // 64, 1), dtype=np.uint64)
-    _check(_load().byz_worst_case(asg._h, int(q), S.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
-                                  ctypes.byref(cmax),
-                                  words.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64))),
+    _check(_load().byz_worst_case_opts(asg._h, int(q), int(flags),
+                                       S.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                       ctypes.byref(cmax),
+                                       words.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64))),
            "byz_worst_case")
     mask = sum(int(w) << (64 * i) for i, w in enumerate(words))
     return tuple(int(x) for x in S[:max(int(q), 0)]), int(cmax.value), mask
+
+
+def byz_worst_case_last_visited():
+    return int(_load().byz_worst_case_last_visited())
 
 
 def byz_gamma_bound(asg, q):

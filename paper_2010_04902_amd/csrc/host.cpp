@@ -3,7 +3,9 @@
 #include <cmath>
 #include <cstdint>
 #include <cstring>
+#include <algorithm>
 #include <atomic>
+#include <map>
 #include <new>
 #include <system_error>
 #include <thread>
@@ -20,6 +22,11 @@ struct byz_assignment {
     std::vector<int32_t> worker_files;  // [K][l] ascending
     std::vector<int32_t> file_workers;  // [f][r] ascending = class order
     std::vector<int32_t> file_rows;     // [f][r]
+    // the files as a gx x gy grid (index x*gy + y) and the addition used on its coordinates
+    // (empty: modulo gx resp. gy; else the table of F_l, gx == gy == l): what the search's
+    // symmetry reduction translates the grid with
+    int gx = 1, gy = 1;
+    std::vector<uint8_t> add_tab;
 };
 
 namespace {
@@ -209,6 +216,8 @@ extern "C" int byz_build_assignment(int scheme, int a, int b, byz_assignment **o
     if (!g) return BYZ_ENOMEM;
     try {
         g->scheme = scheme; g->K = K; g->f = f; g->l = l; g->r = r; g->class_size = class_size;
+        g->gx = gx; g->gy = gy;
+        if (scheme == BYZ_SCHEME_MOLS && field.k > 1) g->add_tab = field.add_tab;
         if (case2 && l > class_size) {
             g->shared_lo = l / class_size;
             g->shared_hi = (l + class_size - 1) / class_size;
@@ -323,14 +332,18 @@ template <int W> struct SearchResult {
     int best = -1;
     FileSet<W> files = {};
     std::vector<int> set;
+    uint64_t visited = 0;  // subsets evaluated
 };
 
-// All q-subsets that start with the ascending workers prefix[0..p-1] (p < q or p == q == 1),
-// in lexicographic order; keeps the first one with the largest number of files that have at
-// least `need` copies inside the subset.
+// All q-subsets that start with the ascending workers prefix[0..p-1] (1 <= p <= q), in
+// lexicographic order; keeps the first one with the largest number of files that have at least
+// `need` copies inside the subset.  With target >= 0 the walk ends at the first subset that
+// reaches target files, and gives up (best stays below target) as soon as *stop_below holds a
+// task number smaller than my_task (an earlier task has already found one).
 template <int W>
 SearchResult<W> search_with_prefix(const std::vector<FileSet<W>> &mask, int K, int q, int need,
-                                   const int *prefix, int p) {
+                                   const int *prefix, int p, int target = -1,
+                                   const std::atomic<int> *stop_below = nullptr, int my_task = 0) {
     SearchResult<W> res;
     res.set.assign((size_t)q, 0);
     std::vector<int> cur((size_t)q + 1, 0);
@@ -344,6 +357,7 @@ SearchResult<W> search_with_prefix(const std::vector<FileSet<W>> &mask, int K, i
         const FileSet<W> hit = at_least(planes[p], need);
         res.best = count(hit);
         res.files = hit;
+        res.visited = 1;
         for (int i = 0; i < q; ++i) res.set[i] = prefix[i];
         return res;
     }
@@ -364,6 +378,7 @@ SearchResult<W> search_with_prefix(const std::vector<FileSet<W>> &mask, int K, i
         }
         // last position: sweep all remaining workers in a tight loop
         const Planes<W> base = planes[t];
+        res.visited += (uint64_t)(K - cur[t]);
         for (int w = cur[t]; w < K; ++w) {
             const FileSet<W> hit = at_least(add_mask(base, mask[w]), need);
             const int c = count(hit);
@@ -372,17 +387,140 @@ SearchResult<W> search_with_prefix(const std::vector<FileSet<W>> &mask, int K, i
                 res.files = hit;
                 for (int i = 0; i < t; ++i) res.set[i] = cur[i];
                 res.set[t] = w;
+                if (target >= 0 && c >= target) return res;
             }
         }
+        if (stop_below != nullptr && stop_below->load(std::memory_order_relaxed) < my_task)
+            return res;
         if (t == p) break;
         --t;
     }
     return res;
 }
 
+// Runs tasks (prefixes) over up to 16 host threads; on_result(task, result) is called for
+// every finished task, from the worker threads, under no lock.
+template <int W, class F>
+int run_tasks(const std::vector<FileSet<W>> &mask, int K, int q, int need,
+              const std::vector<std::vector<int>> &tasks, double work, int target,
+              std::atomic<int> *stop_below, F on_result) {
+    const int n_tasks = (int)tasks.size();
+    unsigned n_threads = 1;
+    if (work > 2e7) {
+        n_threads = std::thread::hardware_concurrency();
+        if (n_threads < 1) n_threads = 1;
+        if (n_threads > 16) n_threads = 16;
+        if (n_threads > (unsigned)n_tasks) n_threads = (unsigned)n_tasks;
+    }
+    std::atomic<int> next_task(0);
+    auto worker = [&]() {
+        for (;;) {
+            const int i = next_task.fetch_add(1);
+            if (i >= n_tasks) break;
+            if (stop_below != nullptr && stop_below->load(std::memory_order_relaxed) < i) continue;
+            on_result(i, search_with_prefix<W>(mask, K, q, need, tasks[(size_t)i].data(),
+                                               (int)tasks[(size_t)i].size(), target, stop_below, i));
+        }
+    };
+    if (n_threads <= 1) {
+        worker();
+        return BYZ_OK;
+    }
+    try {
+        std::vector<std::thread> pool;
+        for (unsigned i = 0; i < n_threads; ++i) pool.emplace_back(worker);
+        for (auto &th : pool) th.join();
+    } catch (const std::system_error &) {
+        return BYZ_ENOMEM;  // threads could not be started
+    }
+    return BYZ_OK;
+}
+
+// Symmetries of the assignment that the search may use: translations of the file grid that
+// map every worker's file set onto another worker's of the same parallel class.  All three
+// constructions are lines of an affine plane, so translating the files permutes the lines of
+// every direction (class) among themselves; each candidate is nevertheless checked on the graph
+// itself, and what does not check out is not used.
+struct Symmetry {
+    std::vector<std::vector<int>> worker_perm;  // verified automorphisms, as worker maps
+    bool level1 = false;  // every class is one orbit
+    bool level2 = false;  // ... and the maps fixing a class pointwise act transitively on every other
+};
+
+Symmetry find_symmetry(const byz_assignment &g) {
+    Symmetry sym;
+    const int K = g.K, f = g.f, l = g.l, cs = g.class_size, classes = K / cs;
+    if (g.gx * g.gy != f || cs < 1 || K % cs != 0) return sym;
+    // worker by (class, files): with FRC several workers, one per class, hold the same files
+    std::map<std::vector<int>, int> by_files;
+    for (int w = 0; w < K; ++w) {
+        std::vector<int> key(g.worker_files.begin() + (size_t)w * l,
+                             g.worker_files.begin() + (size_t)(w + 1) * l);
+        key.push_back(w / cs);
+        by_files[key] = w;
+    }
+    auto shift = [&](int a, int by, int n) {
+        return g.add_tab.empty() ? (a + by) % n : (int)g.add_tab[(size_t)a * n + by];
+    };
+    for (int u = 0; u < g.gx; ++u)
+        for (int v = 0; v < g.gy; ++v) {
+            if (u == 0 && v == 0) continue;
+            std::vector<int> perm((size_t)K, -1);
+            bool ok = true;
+            for (int w = 0; w < K && ok; ++w) {
+                std::vector<int> img((size_t)l);
+                for (int t = 0; t < l; ++t) {
+                    const int j = g.worker_files[(size_t)w * l + t];
+                    img[(size_t)t] = shift(j / g.gy, u, g.gx) * g.gy + shift(j % g.gy, v, g.gy);
+                }
+                std::sort(img.begin(), img.end());
+                img.push_back(w / cs);
+                auto it = by_files.find(img);
+                if (it == by_files.end()) ok = false;
+                else perm[(size_t)w] = it->second;
+            }
+            if (ok) sym.worker_perm.push_back(perm);
+        }
+    // level 1: the first worker of every class reaches the whole class
+    auto orbit_covers = [&](const std::vector<const std::vector<int> *> &maps, int cls) {
+        std::vector<char> seen((size_t)K, 0);
+        std::vector<int> todo(1, cls * cs);
+        seen[(size_t)(cls * cs)] = 1;
+        int n = 1;
+        while (!todo.empty()) {
+            const int w = todo.back();
+            todo.pop_back();
+            for (const auto *m : maps) {
+                const int x = (*m)[(size_t)w];
+                if (!seen[(size_t)x]) { seen[(size_t)x] = 1; ++n; todo.push_back(x); }
+            }
+        }
+        return n == cs;
+    };
+    std::vector<const std::vector<int> *> all;
+    for (const auto &m : sym.worker_perm) all.push_back(&m);
+    sym.level1 = true;
+    for (int c = 0; c < classes; ++c) sym.level1 = sym.level1 && orbit_covers(all, c);
+    if (!sym.level1) return sym;
+    sym.level2 = classes >= 2 && cs <= 20;  // the step-1 tasks enumerate 2^(cs-1) partial classes
+    for (int c0 = 0; c0 < classes && sym.level2; ++c0) {
+        std::vector<const std::vector<int> *> fixing;
+        for (const auto &m : sym.worker_perm) {
+            bool fixes = true;
+            for (int i = 0; i < cs; ++i) fixes = fixes && m[(size_t)(c0 * cs + i)] == c0 * cs + i;
+            if (fixes) fixing.push_back(&m);
+        }
+        for (int c1 = c0 + 1; c1 < classes; ++c1)
+            sym.level2 = sym.level2 && orbit_covers(fixing, c1);
+    }
+    return sym;
+}
+
+thread_local uint64_t g_last_visited = 0;
+
 template <int W>
-int worst_case_impl(const byz_assignment *g, int q, int32_t *byz_workers_out, int32_t *cmax_out,
-                    uint64_t *distorted_mask_out) {
+int worst_case_impl(const byz_assignment *g, int q, unsigned flags, int32_t *byz_workers_out,
+                    int32_t *cmax_out, uint64_t *distorted_mask_out) {
     const int K = g->K, l = g->l;
     const int need = (g->r + 1) / 2;  // r' of Sec. 2
     std::vector<FileSet<W>> mask((size_t)K, FileSet<W>{});
@@ -391,69 +529,120 @@ int worst_case_impl(const byz_assignment *g, int q, int32_t *byz_workers_out, in
             const int j = g->worker_files[(size_t)w * l + t];
             mask[w].w[j >> 6] |= 1ull << (j & 63);
         }
-
+    g_last_visited = 0;
     int best = -1;
     FileSet<W> best_files = {};
     std::vector<int> best_set((size_t)q, 0);
     if (q == 0) {
         best = 0;
     } else {
-        // One task per choice of the first one or two (smallest) workers of the set, listed in
-        // lexicographic order.  Inside a task the tuples are visited depth-first in ascending =
+        double subsets = 1.0;
+        for (int i = 0; i < q; ++i) subsets = subsets * (K - i) / (i + 1);
+        std::atomic<uint64_t> visited(0);
+        // Lexicographic tasks: one per choice of the first one or two (smallest) workers of
+        // the set.  Inside a task the tuples are visited depth-first in ascending =
         // lexicographic order, so a task's result is its first maximiser; merging the tasks in
         // order and keeping a result only when it is strictly better keeps the overall first
         // maximiser.
         const int p = q >= 3 ? 2 : 1;
-        std::vector<int> prefixes;
+        std::vector<std::vector<int>> lex_tasks;
         for (int a0 = 0; a0 <= K - q; ++a0) {
             if (p == 1) {
-                prefixes.push_back(a0);
+                lex_tasks.push_back({a0});
             } else {
-                for (int a1 = a0 + 1; a1 <= K - q + 1; ++a1) {
-                    prefixes.push_back(a0);
-                    prefixes.push_back(a1);
+                for (int a1 = a0 + 1; a1 <= K - q + 1; ++a1) lex_tasks.push_back({a0, a1});
+            }
+        }
+        Symmetry sym;
+        const bool want_sym = (flags & BYZ_SEARCH_EXHAUSTIVE) == 0 && q >= 2 &&
+                              ((flags & BYZ_SEARCH_SYMMETRY) != 0 || subsets > 2e6);
+        if (want_sym) sym = find_symmetry(*g);
+        if (!sym.level1) {
+            // plain exhaustive search
+            std::vector<SearchResult<W>> results(lex_tasks.size());
+            int rc = run_tasks<W>(mask, K, q, need, lex_tasks, subsets, -1, nullptr,
+                                  [&](int i, SearchResult<W> r) {
+                                      visited += r.visited;
+                                      results[(size_t)i] = std::move(r);
+                                  });
+            if (rc != BYZ_OK) return rc;
+            for (const auto &res : results)
+                if (res.best > best) {
+                    best = res.best;
+                    best_files = res.files;
+                    best_set = res.set;
+                }
+        } else {
+            // Step 1, the value c_max alone, over one representative per orbit: every set can
+            // be translated so that, of the lowest class c0 it touches, it contains the first
+            // worker w0; with level 2, keeping class c0 in place, also so that of the next
+            // class c1 it touches it contains the first worker w1.  Workers of one class share
+            // no file, so the members of c0 beside w0 are free, nothing lies between the
+            // classes, and the rest of the set comes after w1.
+            const int cs = g->class_size, classes = K / cs;
+            std::vector<std::vector<int>> tasks;
+            for (int c0 = 0; c0 < classes; ++c0) {
+                const int w0 = c0 * cs;
+                if (q <= cs) {  // all inside class c0: equivalent sets, one stands for all
+                    std::vector<int> inside;
+                    for (int i = 0; i < q; ++i) inside.push_back(w0 + i);
+                    tasks.push_back(inside);
+                }
+                if (!sym.level2) {
+                    // second member anywhere after w0 (sets inside the class are visited again:
+                    // harmless)
+                    for (int a1 = w0 + 1; a1 <= K - q + 1; ++a1) tasks.push_back({w0, a1});
+                    continue;
+                }
+                for (int c1 = c0 + 1; c1 < classes; ++c1) {
+                    const int w1 = c1 * cs;
+                    // subsets A of the other cs - 1 workers of class c0, by bit mask
+                    for (uint32_t bits = 0; bits < (1u << (cs - 1)); ++bits) {
+                        const int a = __builtin_popcount(bits);
+                        if (a > q - 2 || K - w1 - 1 < q - 2 - a) continue;
+                        std::vector<int> prefix(1, w0);
+                        for (int i = 0; i < cs - 1; ++i)
+                            if ((bits >> i) & 1u) prefix.push_back(w0 + 1 + i);
+                        prefix.push_back(w1);
+                        tasks.push_back(prefix);
+                    }
                 }
             }
+            std::atomic<int> best_value(-1);
+            int rc = run_tasks<W>(mask, K, q, need, tasks, subsets / cs, -1, nullptr,
+                                  [&](int, SearchResult<W> r) {
+                                      visited += r.visited;
+                                      int seen = best_value.load();
+                                      while (r.best > seen &&
+                                             !best_value.compare_exchange_weak(seen, r.best)) {
+                                      }
+                                  });
+            if (rc != BYZ_OK) return rc;
+            const int cmax = best_value.load();
+            // Step 2, the lexicographically first set that reaches c_max: lexicographic
+            // tasks again, each ending at its first hit, later tasks dropped once an earlier
+            // one has hit.
+            std::vector<SearchResult<W>> results(lex_tasks.size());
+            std::atomic<int> first_hit((int)lex_tasks.size());
+            rc = run_tasks<W>(mask, K, q, need, lex_tasks, subsets, cmax, &first_hit,
+                              [&](int i, SearchResult<W> r) {
+                                  visited += r.visited;
+                                  if (r.best >= cmax) {
+                                      int seen = first_hit.load();
+                                      while (i < seen && !first_hit.compare_exchange_weak(seen, i)) {
+                                      }
+                                  }
+                                  results[(size_t)i] = std::move(r);
+                              });
+            if (rc != BYZ_OK) return rc;
+            const int hit = first_hit.load();
+            if (hit >= (int)lex_tasks.size() || results[(size_t)hit].best != cmax)
+                return BYZ_EINTERNAL;  // the symmetric step found a value no set attains
+            best = cmax;
+            best_files = results[(size_t)hit].files;
+            best_set = results[(size_t)hit].set;
         }
-        const int n_tasks = (int)prefixes.size() / p;
-        std::vector<SearchResult<W>> results((size_t)n_tasks);
-        double subsets = 1.0;
-        for (int i = 0; i < q; ++i) subsets = subsets * (K - i) / (i + 1);
-        unsigned n_threads = 1;
-        if (subsets > 2e7) {
-            n_threads = std::thread::hardware_concurrency();
-            if (n_threads < 1) n_threads = 1;
-            if (n_threads > 16) n_threads = 16;
-            if (n_threads > (unsigned)n_tasks) n_threads = (unsigned)n_tasks;
-        }
-        std::atomic<int> next_task(0);
-        auto worker = [&]() {
-            for (;;) {
-                const int first = next_task.fetch_add(1);
-                if (first >= n_tasks) break;
-                results[(size_t)first] =
-                    search_with_prefix<W>(mask, K, q, need, &prefixes[(size_t)first * p], p);
-            }
-        };
-        if (n_threads <= 1) {
-            worker();
-        } else {
-            try {
-                std::vector<std::thread> pool;
-                for (unsigned i = 0; i < n_threads; ++i) pool.emplace_back(worker);
-                for (auto &th : pool) th.join();
-            } catch (const std::system_error &) {
-                return BYZ_ENOMEM;  // threads could not be started
-            }
-        }
-        for (int first = 0; first < n_tasks; ++first) {
-            const SearchResult<W> &res = results[(size_t)first];
-            if (res.best > best) {
-                best = res.best;
-                best_files = res.files;
-                best_set = res.set;
-            }
-        }
+        g_last_visited = visited.load();
     }
     if (byz_workers_out)
         for (int i = 0; i < q; ++i) byz_workers_out[i] = best_set[i];
@@ -465,14 +654,31 @@ int worst_case_impl(const byz_assignment *g, int q, int32_t *byz_workers_out, in
 
 }  // namespace
 
+extern "C" int byz_worst_case_opts(const byz_assignment *g, int q, unsigned flags,
+                                   int32_t *byz_workers_out, int32_t *cmax_out,
+                                   uint64_t *distorted_mask_out) {
+    if (!g || q < 0 || q > g->K) return BYZ_EINVAL;
+    if ((flags & ~(unsigned)(BYZ_SEARCH_EXHAUSTIVE | BYZ_SEARCH_SYMMETRY)) != 0 ||
+        flags == (BYZ_SEARCH_EXHAUSTIVE | BYZ_SEARCH_SYMMETRY))
+        return BYZ_EINVAL;
+    if (g->f > BYZ_MAX_F_WIDE || g->r > BYZ_MAX_R) return BYZ_EUNSUPPORTED;
+    try {
+        if (g->f <= 64)
+            return worst_case_impl<1>(g, q, flags, byz_workers_out, cmax_out, distorted_mask_out);
+        if (g->f <= 128)
+            return worst_case_impl<2>(g, q, flags, byz_workers_out, cmax_out, distorted_mask_out);
+        return worst_case_impl<4>(g, q, flags, byz_workers_out, cmax_out, distorted_mask_out);
+    } catch (const std::bad_alloc &) {
+        return BYZ_ENOMEM;
+    }
+}
+
 extern "C" int byz_worst_case(const byz_assignment *g, int q, int32_t *byz_workers_out,
                               int32_t *cmax_out, uint64_t *distorted_mask_out) {
-    if (!g || q < 0 || q > g->K) return BYZ_EINVAL;
-    if (g->f > BYZ_MAX_F_WIDE || g->r > BYZ_MAX_R) return BYZ_EUNSUPPORTED;
-    if (g->f <= 64) return worst_case_impl<1>(g, q, byz_workers_out, cmax_out, distorted_mask_out);
-    if (g->f <= 128) return worst_case_impl<2>(g, q, byz_workers_out, cmax_out, distorted_mask_out);
-    return worst_case_impl<4>(g, q, byz_workers_out, cmax_out, distorted_mask_out);
+    return byz_worst_case_opts(g, q, 0u, byz_workers_out, cmax_out, distorted_mask_out);
 }
+
+extern "C" uint64_t byz_worst_case_last_visited(void) { return g_last_visited; }
 
 extern "C" double byz_gamma_bound(const byz_assignment *g, int q) {
     if (!g || q < 0 || q > g->K) return std::nan("");

@@ -259,3 +259,41 @@ def test_frc_comparison_column(name):
             assert C.worst_case(Ho, q) == (c, S)
     with pytest.raises(B.ByzError):
         B.byz_build_assignment(B.BYZ_SCHEME_FRC, 15, 4)
+
+
+@pytest.mark.parametrize("scheme,a,b,qs", [
+    ("mols", 5, 3, range(0, 9)), ("mols", 7, 3, range(2, 8)), ("mols", 7, 5, (6, 8)),
+    ("ram", 5, 5, range(2, 9)), ("ram", 5, 3, range(2, 7)), ("ram", 3, 5, range(2, 6)),
+    ("ram", 5, 7, range(2, 8)), ("ram", 5, 13, (2, 4)), ("frc", 15, 3, range(1, 7)),
+    ("frc", 25, 5, (5, 7)), ("mols", 4, 3, range(2, 6)), ("mols", 8, 3, (3, 5)),
+    ("mols", 9, 3, range(2, 6)), ("mols", 11, 3, (3, 4))])
+def test_symmetry_reduced_search_equals_the_exhaustive_one(scheme, a, b, qs):
+    # Sec. 5.3.2's search over one representative per orbit of the design's translations, then
+    # the first maximiser by an early-exit walk: same value, same first set, same file mask
+    code = {"mols": B.BYZ_SCHEME_MOLS, "ram": B.BYZ_SCHEME_RAMANUJAN, "frc": B.BYZ_SCHEME_FRC}[scheme]
+    asg = B.byz_build_assignment(code, a, b)
+    fewer = 0
+    for q in qs:
+        plain = B.byz_worst_case(asg, q, B.BYZ_SEARCH_EXHAUSTIVE)
+        v_plain = B.byz_worst_case_last_visited()
+        assert v_plain == (math.comb(asg.K, q) if q > 0 else 0)
+        reduced = B.byz_worst_case(asg, q, B.BYZ_SEARCH_SYMMETRY)
+        v_reduced = B.byz_worst_case_last_visited()
+        assert reduced == plain, q
+        assert B.byz_worst_case(asg, q) == plain
+        fewer += v_reduced < v_plain
+    assert fewer >= len(list(qs)) - 2  # q <= 1 has nothing to reduce
+
+
+def test_symmetry_reduced_search_on_the_largest_table_row():
+    # Table 5's last row, C(35,13) = 1.48e9 subsets: a fifth of them visited, same answer as
+    # the table; the default strategy picks the reduced search at this size
+    big = _build("mols", 7, 5)
+    S, c, mask = B.byz_worst_case(big, 13)
+    assert c == 20 and B.byz_worst_case_last_visited() < 0.3 * math.comb(35, 13)
+    S12, c12, _ = B.byz_worst_case(big, 12, B.BYZ_SEARCH_EXHAUSTIVE)
+    assert (S12, c12) == B.byz_worst_case(big, 12, B.BYZ_SEARCH_SYMMETRY)[:2] and c12 == 16
+    for flags in (3, 4, 8):
+        with pytest.raises(B.ByzError) as e:
+            B.byz_worst_case(big, 3, flags)
+        assert e.value.code == -1
