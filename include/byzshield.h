@@ -184,10 +184,10 @@ int byz_vote_tolerant(const float *copies, int64_t d, int64_t ld, const int32_t 
  *   rows_base     device [*][ld] fp32;  row_index_dev device [f] int32;  out device [d] fp32,
  *                 must not overlap the input rows (may be NULL when d == 0).
  * f odd, 1 <= f <= BYZ_MAX_F_WIDE.  A register selection network does the work for every
- * f <= 121: generated for f in {3,5,7,9,15,21,25,35,49,81,121} (the paper's file and worker
- * counts and MOLS over F_9, F_11), any other f on the next of those sizes with the spare wires
+ * f <= 169: generated for f in {3,5,7,9,15,21,25,35,49,81,121,169} (the paper's file and
+ * worker counts and MOLS over F_9, F_11, F_13), any other f on the next of those sizes with the spare wires
  * tied half to the smallest and half to the largest key (f = 27: 0.23 ms for 11.2 M
- * coordinates, f = 63: 1.1 ms).  121 < f keeps the f keys of a coordinate in LDS and finds the
+ * coordinates, f = 63: 1.1 ms).  169 < f keeps the f keys of a coordinate in LDS and finds the
  * median by bisection on the key (slow).  Errors: BYZ_EINVAL, BYZ_EUNSUPPORTED (even f),
  * BYZ_EDEVICE.
  */
@@ -204,8 +204,8 @@ int byz_median(const float *rows_base, int64_t d, int64_t ld, const int32_t *row
  * infinities go first).  b = 0 is the plain mean.  Not pure selection; the rounding contract
  * is: fp32, kept values added one by one in ascending order starting from +0, then one IEEE
  * division by float(f - 2b).
- *   f in {9,15,21,25,35,49,81,121} runs a generated register sorting network, any other
- *   f <= 121 the next of those sizes with the spare wires tied to the largest key, 121 < f <=
+ *   f in {9,15,21,25,35,49,81,121,169} runs a generated register sorting network, any other
+ *   f <= 169 the next of those sizes with the spare wires tied to the largest key, 169 < f <=
  *   BYZ_MAX_F_WIDE an insertion sort of the coordinate's keys in LDS (slow).
  * Errors: BYZ_EINVAL (null pointers, sizes, b < 0 or 2b >= f), BYZ_EDEVICE.
  */
@@ -286,7 +286,8 @@ size_t byz_aggregate_workspace_bytes(int f, int r);
  * the sample but differs elsewhere) the exact two-step path (vote, then median) runs on the
  * device right after; the result is the same, only slower.
  * The single pass is compiled for (f, r) = (9,3), (15,3), (21,3), (25,3), (25,5), (35,5),
- * (49,3), (49,5), (81,3), (121,3) (byz_aggregate_has_single_pass); for every other valid
+ * (49,3), (49,5), (81,3), (121,3), (169,3) (byz_aggregate_has_single_pass; (169,3) for the
+ * median only); for every other valid
  * (f, r), and for d < 4, the call runs byz_vote's kernels and then byz_median's, reading the
  * winners a second time.
  * Errors: as byz_vote / byz_median, plus BYZ_ENOMEM (workspace too small).

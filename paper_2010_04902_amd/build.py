@@ -12,7 +12,8 @@ LIB = os.path.join(PKG, "libbyzshield.so")
 KERNELS = os.path.join(CSRC, "kernels.hip")
 # kernels.hip is compiled once per part (-DBYZ_PART=n): the single-pass kernels are large and
 # build in parallel this way
-KERNEL_PARTS = (0, 1, 2, 3, 4, 5, 6)
+# the slowest parts first: the pool starts them in this order
+KERNEL_PARTS = (8, 10, 9, 11, 7, 4, 6, 5, 3, 2, 1, 0)
 OTHER_SOURCES = [os.path.join(CSRC, "krum.hip"), os.path.join(CSRC, "host.cpp")]
 
 
@@ -40,9 +41,11 @@ def build(verbose=False):
 
     def run(job):
         cmd, obj = job
-        if verbose:
-            print(" ".join(cmd), flush=True)
+        import time
+        t0 = time.time()
         subprocess.run(cmd, check=True)
+        if verbose:
+            print("%6.1f s  %s" % (time.time() - t0, " ".join(cmd[-6:])), flush=True)
         return obj
 
     workers = min(len(jobs), max(1, len(os.sched_getaffinity(0))), 16)

@@ -22,6 +22,7 @@ BYZ_DECLARE_SINGLE_PASS(1);
 BYZ_DECLARE_SINGLE_PASS(2);
 BYZ_DECLARE_SINGLE_PASS(3);
 BYZ_DECLARE_SINGLE_PASS(4);
+BYZ_DECLARE_SINGLE_PASS(5);
 
 // Coordinate-wise median / trimmed mean of the rows row_index[0..f-1] (kernels.hip, parts 5 and
 // 6): picks the network kernel for f; gate != NULL makes the kernels return at once unless one
@@ -31,6 +32,20 @@ int byz_internal_launch_median(const void *X, long long d, long long ld, const i
 int byz_internal_launch_trimmed_mean(const void *X, long long d, long long ld,
                                      const int *row_index, int f, int b, void *out,
                                      const void *gate, int gate_n, void *stream);
+
+// Median / trimmed mean on the 169-wire network, exactly 169 rows or fewer with spare wires
+// (kernels.hip, build parts 8..11).
+int byz_internal_launch_trimmed_mean_169(const void *X, long long d, long long ld,
+                                         const int *row_index, int f, int b, void *out,
+                                         const void *gate, int gate_n, void *stream);
+int byz_internal_launch_trimmed_mean_169_padded(const void *X, long long d, long long ld,
+                                                const int *row_index, int f, int b, void *out,
+                                                const void *gate, int gate_n, void *stream);
+int byz_internal_launch_median_169(const void *X, long long d, long long ld, const int *row_index,
+                                   int f, void *out, const void *gate, int gate_n, void *stream);
+int byz_internal_launch_median_169_padded(const void *X, long long d, long long ld,
+                                          const int *row_index, int f, void *out, const void *gate,
+                                          int gate_n, void *stream);
 
 // Records the event before (which = 0) or after (1) the dominant kernel of an aggregation, if
 // byz_profile_enable has armed any.  Returns a byz_status.

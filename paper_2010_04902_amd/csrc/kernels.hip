@@ -22,8 +22,9 @@
 
 // The build compiles this file once per BYZ_PART, in parallel, because the single-pass kernels
 // are large: part 0 holds every entry point, the vote and the Bulyan kernels, parts 1..4 one
-// group of single-pass instantiations each (byz_internal_launch_single_pass_<n>), part 5 the
-// median kernels and part 6 the trimmed-mean kernels.  Without BYZ_PART the whole library is
+// group of single-pass instantiations each (byz_internal_launch_single_pass_<n>; the fifth
+// group is part 7), part 5 the median kernels, part 6 the trimmed-mean kernels, parts 8..11 one
+// 169-wire network kernel each.  Without BYZ_PART the whole library is
 // this one translation unit.
 #ifndef BYZ_PART
 #define BYZ_PART -1
@@ -66,9 +67,10 @@ constexpr int prefetch_depth(int f, int slots) {
     return a < 1 ? 1 : (a > 5 ? 5 : a);
 }
 // f with a generated streamed network (gen_selnet.py STREAMED_SIZES): the paper's file counts
-// l^2 (MOLS, Ramanujan Case 1; 81 and 121 for l = 9, 11) and m*s (Ramanujan Case 2)
+// l^2 (MOLS, Ramanujan Case 1; 81, 121, 169 for l = 9, 11, 13) and m*s (Ramanujan Case 2)
 constexpr bool has_streamed_network(int f) {
-    return f == 9 || f == 15 || f == 21 || f == 25 || f == 35 || f == 49 || f == 81 || f == 121;
+    return f == 9 || f == 15 || f == 21 || f == 25 || f == 35 || f == 49 || f == 81 || f == 121 ||
+           f == 169;
 }
 // words per thread: fewer for the large networks, whose keys fill the register file
 constexpr int vec_for(int f) { return f <= 49 ? 4 : (f <= 81 ? 2 : 1); }
@@ -1107,7 +1109,7 @@ int launch_vote_pairs_tolerant(int r, const uint32_t *X, int64_t d, int64_t ld,
 
 #endif  // part 0
 
-#if BYZ_IN_PART(5) || BYZ_IN_PART(6)
+#if BYZ_IN_PART(5) || BYZ_IN_PART(6)  // (launch_column_wide serves both)
 // 64 < f <= 256 without a generated network
 int launch_column_wide(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
                        int b, uint32_t *out, const uint32_t *gate, int gate_n, hipStream_t s) {
@@ -1131,6 +1133,9 @@ int launch_median_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *r
     return BYZ_OK;
 }
 
+#endif  // part 5
+
+#if BYZ_IN_PART(5) || BYZ_IN_PART(9) || BYZ_IN_PART(11)
 template <int F, bool PAD>
 int launch_median_large(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
                         uint32_t *out, const uint32_t *gate, int gate_n, hipStream_t s) {
@@ -1141,6 +1146,9 @@ int launch_median_large(const uint32_t *X, int64_t d, int64_t ld, const int32_t 
     return BYZ_OK;
 }
 
+#endif  // parts 5, 9, 11
+
+#if BYZ_IN_PART(5)
 int launch_median(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
                   uint32_t *out, const uint32_t *gate, int gate_n, hipStream_t s) {
     if (d == 0) return BYZ_OK;
@@ -1175,31 +1183,37 @@ int launch_median(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_i
         return launch_median_large<81, true>(X, d, ld, row_index, f, out, gate, gate_n, s);
     if (f == 121) return launch_median_large<121, false>(X, d, ld, row_index, f, out, gate, gate_n, s);
     if (f <= 121) return launch_median_large<121, true>(X, d, ld, row_index, f, out, gate, gate_n, s);
+    if (f == 169) return byz_internal_launch_median_169(X, d, ld, row_index, f, out, gate, gate_n, s);
+    if (f <= 169) return byz_internal_launch_median_169_padded(X, d, ld, row_index, f, out, gate, gate_n, s);
     return launch_column_wide(X, d, ld, row_index, f, -1, out, gate, gate_n, s);
 }
 
 #endif  // part 5
 
-template <int F, int R>
+// WITH_TRIM = false leaves the trimmed-mean variant of the kernel out (the caller then sends
+// trimmed-mean requests down the two-kernel path)
+template <int F, int R, bool WITH_TRIM = true>
 int launch_fused(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, AggWorkspace *ws,
                  uint32_t *out, int early_majority, int trim_b, hipStream_t s) {
+    if (!WITH_TRIM && trim_b >= 0) return BYZ_EINTERNAL;
     probe_kernel<F, R><<<1, kProbeThreads, 0, s>>>(X, d, ld, rows, ws, early_majority);
     BYZ_HIP(hipGetLastError());
     int rc = byz_internal_profile_mark(0, s);
     if (rc != BYZ_OK) return rc;
     constexpr int V = vec_for(F);
     const unsigned g = blocks_for((d + V - 1) / V);
-    if (trim_b < 0)
+    if (trim_b < 0) {
         fused_kernel<F, R, false, V><<<g, kBlock, 0, s>>>(
             X, d, ld, ws->perm_off, ws->chain_mask, &ws->slots_per_file, ws, 0, out);
-    else
+    } else if constexpr (WITH_TRIM) {
         fused_kernel<F, R, true, V><<<g, kBlock, 0, s>>>(
             X, d, ld, ws->perm_off, ws->chain_mask, &ws->slots_per_file, ws, trim_b, out);
+    }
     BYZ_HIP(hipGetLastError());
     return byz_internal_profile_mark(1, s);
 }
 
-#if BYZ_IN_PART(6)
+#if BYZ_IN_PART(6) || BYZ_IN_PART(8) || BYZ_IN_PART(10)
 template <int F, bool PAD>
 int launch_trimmed_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
                        int b, uint32_t *O, const uint32_t *gate, int gate_n, hipStream_t s) {
@@ -1210,6 +1224,9 @@ int launch_trimmed_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *
     return BYZ_OK;
 }
 
+#endif  // parts 6, 8, 10
+
+#if BYZ_IN_PART(6)
 int launch_trimmed_mean(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
                         int b, uint32_t *O, const uint32_t *gate, int gate_n, hipStream_t s) {
     if (d == 0) return BYZ_OK;
@@ -1243,6 +1260,9 @@ int launch_trimmed_mean(const uint32_t *X, int64_t d, int64_t ld, const int32_t 
         return launch_trimmed_net<81, true>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
     if (f == 121) return launch_trimmed_net<121, false>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
     if (f <= 121) return launch_trimmed_net<121, true>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
+    if (f == 169) return byz_internal_launch_trimmed_mean_169(X, d, ld, row_index, f, b, O, gate, gate_n, s);
+    if (f <= 169)
+        return byz_internal_launch_trimmed_mean_169_padded(X, d, ld, row_index, f, b, O, gate, gate_n, s);
     return launch_column_wide(X, d, ld, row_index, f, b, O, gate, gate_n, s);
 }
 
@@ -1261,11 +1281,11 @@ int launch_bulyan_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *s
 
 // (f, r) with a compiled single-pass kernel: MOLS / Ramanujan Case 1 (f = l^2: 9, 25, 49) with
 // r = 3 or 5, the Ramanujan Case 2 shapes f = m*s with r = s: (15,3), (21,3), (35,5), and MOLS
-// over F_9 and F_11 with r = 3: (81,3), (121,3)
+// over F_9, F_11 and F_13 with r = 3: (81,3), (121,3), (169,3)
 bool has_fused(int f, int r) {
     return (f == 9 && r == 3) || ((f == 25 || f == 49) && (r == 3 || r == 5)) ||
            ((f == 15 || f == 21) && r == 3) || (f == 35 && r == 5) ||
-           ((f == 81 || f == 121) && r == 3);
+           ((f == 81 || f == 121 || f == 169) && r == 3);
 }
 
 int check_common(const void *copies, int64_t d, int64_t ld, const void *rows, int f, int r) {
@@ -1288,6 +1308,47 @@ int byz_internal_launch_median(const void *X, long long d, long long ld, const i
     return launch_median(static_cast<const uint32_t *>(X), d, ld, row_index, f,
                          static_cast<uint32_t *>(out), static_cast<const uint32_t *>(gate), gate_n,
                          (hipStream_t)stream);
+}
+#endif
+
+// the 169-wire networks (MOLS over F_13 and, padded, 121 < f < 169), a build part each
+#if BYZ_IN_PART(8)
+int byz_internal_launch_trimmed_mean_169(const void *X, long long d, long long ld,
+                                         const int *row_index, int f, int b, void *out,
+                                         const void *gate, int gate_n, void *stream) {
+    return launch_trimmed_net<169, false>(static_cast<const uint32_t *>(X), d, ld, row_index, f, b,
+                                          static_cast<uint32_t *>(out),
+                                          static_cast<const uint32_t *>(gate), gate_n,
+                                          (hipStream_t)stream);
+}
+#endif
+#if BYZ_IN_PART(10)
+int byz_internal_launch_trimmed_mean_169_padded(const void *X, long long d, long long ld,
+                                                const int *row_index, int f, int b, void *out,
+                                                const void *gate, int gate_n, void *stream) {
+    return launch_trimmed_net<169, true>(static_cast<const uint32_t *>(X), d, ld, row_index, f, b,
+                                         static_cast<uint32_t *>(out),
+                                         static_cast<const uint32_t *>(gate), gate_n,
+                                         (hipStream_t)stream);
+}
+#endif
+#if BYZ_IN_PART(9)
+int byz_internal_launch_median_169(const void *X, long long d, long long ld, const int *row_index,
+                                   int f, void *out, const void *gate, int gate_n, void *stream) {
+    return launch_median_large<169, false>(static_cast<const uint32_t *>(X), d, ld, row_index, f,
+                                           static_cast<uint32_t *>(out),
+                                           static_cast<const uint32_t *>(gate), gate_n,
+                                           (hipStream_t)stream);
+}
+#endif
+#if BYZ_IN_PART(11)
+int byz_internal_launch_median_169_padded(const void *X, long long d, long long ld,
+                                          const int *row_index, int f, void *out, const void *gate,
+                                          int gate_n, void *stream) {
+    return launch_median_large<169, true>(static_cast<const uint32_t *>(X), d, ld, row_index, f,
+                                          static_cast<uint32_t *>(out),
+                                          static_cast<const uint32_t *>(gate), gate_n,
+                                          (hipStream_t)stream);
 }
 #endif
 
@@ -1353,6 +1414,18 @@ int byz_internal_launch_single_pass_4(int f, int r, const void *X, long long d, 
                                       void *stream) {
     if (f == 121 && r == 3)
         return launch_fused<121, 3>(static_cast<const uint32_t *>(X), d, ld, rows,
+                                    static_cast<AggWorkspace *>(ws), static_cast<uint32_t *>(out),
+                                    early, trim_b, (hipStream_t)stream);
+    return BYZ_EINTERNAL;
+}
+#endif
+
+#if BYZ_IN_PART(7)
+int byz_internal_launch_single_pass_5(int f, int r, const void *X, long long d, long long ld,
+                                      const int *rows, void *ws, void *out, int early, int trim_b,
+                                      void *stream) {
+    if (f == 169 && r == 3)
+        return launch_fused<169, 3, false>(static_cast<const uint32_t *>(X), d, ld, rows,
                                     static_cast<AggWorkspace *>(ws), static_cast<uint32_t *>(out),
                                     early, trim_b, (hipStream_t)stream);
     return BYZ_EINTERNAL;
@@ -1500,7 +1573,8 @@ extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
     uint32_t *O = reinterpret_cast<uint32_t *>(out);
     AggWorkspace *ws = reinterpret_cast<AggWorkspace *>(workspace);
 
-    if (!has_fused(f, r) || d < kVec) {
+    // (the 169-file single pass is built for the median only)
+    if (!has_fused(f, r) || d < kVec || (f == 169 && trim_b >= 0)) {
         // two-step path, unconditionally: vote (a1, a2), then median (a3) over the winners
         reset_workspace_kernel<<<1, kWide, 0, s>>>(ws, 1u);
         BYZ_HIP(hipGetLastError());
@@ -1525,7 +1599,9 @@ extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
 
     // probe -> single pass -> exact path, whose two kernels return at once unless the single
     // pass recorded a violated assumption
-    if (f == 121)
+    if (f == 169)
+        rc = byz_internal_launch_single_pass_5(f, r, X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
+    else if (f == 121)
         rc = byz_internal_launch_single_pass_4(f, r, X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
     else if (f == 81)
         rc = byz_internal_launch_single_pass_3(f, r, X, d, ld, file_rows_dev, ws, O, early, trim_b, s);

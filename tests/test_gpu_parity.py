@@ -405,7 +405,8 @@ def test_trimmed_mean_special_values():
     (RAM, 5, 13, 5, MIXED),      # Ramanujan Case 2, f = 65, r = 5: first size past one lane per file
     (MOLS, 9, 3, 4, ALIE),       # F_9: f = 81
     (MOLS, 11, 3, 4, REVERSED),  # f = 121
-    (MOLS, 13, 3, 3, CONST),     # f = 169
+    (MOLS, 13, 3, 3, CONST),     # F_13: f = 169
+    (RAM, 3, 47, 2, ALIE),       # f = 141: the 169-wire network with spare wires
     (RAM, 3, 85, 2, ALIE)])      # f = 255, the largest odd f
 def test_more_than_64_files(scheme, a, b, q, attack):
     # vote with several 64-file groups, median by bisection in LDS, trimmed mean by LDS sort
