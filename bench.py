@@ -89,6 +89,10 @@ def main():
 
     # distinct input buffers: one per step for the multi-step workload (rotating), one otherwise
     n_buf = min(cfg.steps, 3)
+    # an input that fits the 256 MB last-level cache must not be served from it step after step
+    input_bytes = 4 * asg.f * asg.r * ld
+    if input_bytes < (1 << 30):
+        n_buf = max(n_buf, 4)
     bufs = []
     for t in range(n_buf):
         G = synth.honest_gradients(asg.f, d, cfg.seed, step=t, device=dev,
@@ -156,7 +160,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": cfg.name, "d": d, "ld": ld, "K": asg.K, "f": asg.f, "r": asg.r,
                    "l": asg.l, "q": cfg.q, "c_max": cmax, "attack": cfg.attack["kind"],
-                   "rows": asg.f * asg.r, "input_bytes": 4 * asg.f * asg.r * d,
+                   "rows": asg.f * asg.r, "input_bytes": 4 * asg.f * asg.r * d, "rotating_buffers": n_buf,
                    "took_exact_path": bool(exact)},
         "step_hbm_gbps_algorithmic": alg_bytes / (ms_per_step * 1e-3) / 1e9,
     }
@@ -169,7 +173,8 @@ def main():
             "frac": achieved / HBM_PEAK_GBPS,
             "traffic": _traffic_from_profiles(cfg.name, "fused_kernel" if single_pass else "vote_pairs_kernel"),
             "algorithmic_bytes_per_launch": kernel_bytes,
-            "avg_kernel_ms": avg_ms, "min_kernel_ms": min(kernel_ms), "launches_timed": len(kernel_ms),
+            "avg_kernel_ms": avg_ms, "median_kernel_ms": sorted(kernel_ms)[len(kernel_ms) // 2],
+            "min_kernel_ms": min(kernel_ms), "launches_timed": len(kernel_ms),
         }
 
     # Same result with fewer bytes: r' identical copies already are the majority, so the
@@ -267,8 +272,25 @@ def main():
         torch.cuda.synchronize()
         same = bool(np.array_equal(out.cpu().numpy().view(np.uint32), out_o.view(np.uint32))
                     and np.array_equal(wrep.cpu().numpy(), wrep_o))
+        # one core, on the first eighth of the coordinates (same rows, same row pitch)
+        d1 = max(d // 8, 1)
+        c0 = time.perf_counter()
+        C.aggregate(Xh, rows, d1, threads=1)
+        one_core = time.perf_counter() - c0
+        model = "unknown"
+        try:
+            with open("/proc/cpuinfo") as fh:
+                for line in fh:
+                    if line.startswith("model name"):
+                        model = line.split(":", 1)[1].strip()
+                        break
+        except OSError:
+            pass
         result["cpu_baseline"] = {
             "value": d / best, "unit": "coords/s", "cores": int(used), "kind": "oracle",
+            "cpu_model": model,
+            "one_core": {"value": d1 / one_core, "unit": "coords/s",
+                         "sample": "first %d coordinates of the same batch, one run" % d1},
             "sample": "whole %s batch (d=%d, %d rows), best of %d runs of the C oracle "
                       "(vote single-threaded memcmp, median OpenMP over coordinates)"
                       % (cfg.name, d, asg.f * asg.r, reps),
