@@ -713,3 +713,47 @@ def test_hip_graph_capture_of_the_other_entry_points(l):
         torch.cuda.synchronize()
         for got, want in zip(again, eager[which]):
             assert torch.equal(got.view(torch.int32), want.view(torch.int32))
+
+
+def test_random_shapes_sizes_and_layouts():
+    # a seeded sweep over assignments (every kernel family: generated, padded and 169-wire
+    # networks, single pass and two-step, more than 64 files, r = 3, 5, 7), sizes, row pitches,
+    # attacks and planted single-word differences; everything against the C oracle
+    import math
+    rng = np.random.default_rng(2010)
+    shapes = [(MOLS, 5, 3), (MOLS, 7, 3), (MOLS, 7, 5), (RAM, 5, 5), (RAM, 3, 3), (RAM, 5, 3),
+              (RAM, 7, 3), (RAM, 3, 5), (RAM, 3, 7), (RAM, 5, 7), (RAM, 7, 7), (RAM, 3, 9),
+              (RAM, 3, 11), (RAM, 5, 9), (RAM, 5, 13), (MOLS, 9, 3), (MOLS, 11, 3), (MOLS, 13, 3),
+              (MOLS, 9, 5), (FRC, 15, 3), (FRC, 25, 5), (FRC, 27, 3), (RAM, 3, 47), (RAM, 3, 85),
+              (RAM, 7, 9)]
+    attacks = [REVERSED, ALIE, CONST, MIXED]
+    for case in range(150):
+        scheme, a, b = shapes[rng.integers(len(shapes))]
+        asg = B.byz_build_assignment(scheme, a, b)
+        d = int(rng.choice([rng.integers(1, 20), rng.integers(20, 3000), rng.integers(3000, 60000)]))
+        ld = d + int(rng.integers(0, 9))
+        q = int(rng.integers(0, max(1, asg.K // 3)))
+        while math.comb(asg.K, q) > 2_000_000:
+            q -= 1
+        attack = attacks[rng.integers(len(attacks))]
+        w = W.make(scheme, a, b, q, d, attack, seed=int(rng.integers(1 << 30)), ld=ld, device=DEV)
+        X = w.X.clone()
+        for _ in range(int(rng.integers(0, 4))):
+            X[int(w.file_rows[rng.integers(w.f), rng.integers(w.r)]), int(rng.integers(d))] += 1.0
+        tag = (case, scheme, a, b, q, d, ld, attack["kind"])
+        rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+        Xh = X.cpu().numpy()
+        wrep_o, wrow_o, neq_o = C.vote(Xh, w.file_rows, d)
+        out_o = C.median(Xh, wrow_o, d)
+        wrep, wrow, neq = B.byz_vote(X, d, rows_dev, w.f, w.r)
+        assert np.array_equal(wrep.cpu().numpy(), wrep_o) and np.array_equal(W.bits(neq), neq_o), tag
+        assert np.array_equal(W.bits(B.byz_median(X, d, wrow)), W.bits(out_o)), tag
+        for flags in (0, B.BYZ_AGG_EARLY_MAJORITY):
+            out, wrep2, _ = B.byz_aggregate_opts(X, d, rows_dev, w.f, w.r, flags)
+            assert np.array_equal(W.bits(out), W.bits(out_o)), (tag, flags)
+            assert np.array_equal(wrep2.cpu().numpy(), wrep_o), (tag, flags)
+        trim = int(rng.integers(0, (w.f + 1) // 2))
+        _trimmed_mean_check(X, wrow_o, d, trim, tag)
+        out_t, _, _ = B.byz_aggregate_opts(X, d, rows_dev, w.f, w.r, B.BYZ_AGG_TRIM(trim))
+        assert np.array_equal(W.bits(out_t), W.bits(B.byz_trimmed_mean(X, d, wrow, trim))), tag
+        _tolerant_check(X, w.file_rows, d, w.f, w.r, 1e-6, 1e-5, tag)
