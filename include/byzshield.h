@@ -260,8 +260,9 @@ int byz_multi_krum(const float *rows_base, int64_t d, int64_t ld, const int32_t 
  *                 order chosen
  *   dist_out      device [f*f] double out, may be NULL
  *   workspace     device, >= byz_bulyan_workspace_bytes(f) bytes, 256-byte aligned
- * Errors: BYZ_EINVAL (null pointers, f < 4c + 3, f > BYZ_MAX_F, sizes), BYZ_ENOMEM (workspace
- * too small), BYZ_EDEVICE.
+ * Errors: BYZ_EINVAL (null pointers, f < 4c + 3, f > BYZ_MAX_F, sizes), BYZ_EUNSUPPORTED (even
+ * f: the median of the chosen values would not be one of them), BYZ_ENOMEM (workspace too
+ * small), BYZ_EDEVICE.
  */
 size_t byz_bulyan_workspace_bytes(int f);
 int byz_bulyan(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev, int f,

@@ -490,6 +490,7 @@ extern "C" int byz_bulyan(const float *rows_base, int64_t d, int64_t ld,
         return BYZ_EINVAL;
     if (d < 0 || ld < d || d > ((int64_t)1 << 30)) return BYZ_EINVAL;
     if (f < 3 || f > BYZ_MAX_F || c < 0 || f < 4 * c + 3) return BYZ_EINVAL;  // Sec. 6.1
+    if ((f % 2) == 0) return BYZ_EUNSUPPORTED;  // the median of the f - 2c chosen values must be one of them
     if (((uintptr_t)workspace & 255u) != 0) return BYZ_EINVAL;
     if (workspace_bytes < sizeof(KrumWorkspace)) return BYZ_ENOMEM;
     hipStream_t s = (hipStream_t)stream;

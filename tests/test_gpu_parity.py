@@ -582,6 +582,9 @@ def test_bulyan_on_the_vote_winners(scheme, a, b, q, attack):
         with pytest.raises(B.ByzError) as e:
             B.byz_bulyan(w.X, w.d, wrow, c)
         assert e.value.code == -1
+    with pytest.raises(B.ByzError) as e:  # even f
+        B.byz_bulyan(w.X, w.d, wrow[:w.f - 1], 0)
+    assert e.value.code == -2
 
 
 def test_bulyan_ties_and_identical_vectors():
