@@ -760,3 +760,27 @@ def test_random_shapes_sizes_and_layouts():
         out_t, _, _ = B.byz_aggregate_opts(X, d, rows_dev, w.f, w.r, B.BYZ_AGG_TRIM(trim))
         assert np.array_equal(W.bits(out_t), W.bits(B.byz_trimmed_mean(X, d, wrow, trim))), tag
         _tolerant_check(X, w.file_rows, d, w.f, w.r, 1e-6, 1e-5, tag)
+
+
+def test_multi_krum_and_bulyan_for_every_f():
+    # every f from 3 to 64 (all tile counts and staging shapes of the Gram kernel, every network
+    # size of Bulyan's second phase incl. the spare-wire cases), random d, row pitch, c and m;
+    # per-row scales keep the scores apart, so selections are compared exactly
+    rng = np.random.default_rng(64)
+    compared = []
+    for f in range(3, 65):
+        d = int(rng.choice([rng.integers(1, 10), rng.integers(10, 600), rng.integers(600, 40000)]))
+        ld = d + int(rng.integers(0, 6))
+        Xh = np.zeros((f + 2, ld), dtype=np.float32)
+        Xh[:, :d] = (rng.standard_normal((f + 2, d)) * rng.uniform(0.5, 2.0, size=(f + 2, 1))).astype(np.float32)
+        idx = rng.permutation(f + 2)[:f].astype(np.int32)
+        c = int(rng.integers(0, (f - 3) // 2 + 1))
+        n_far = int(rng.integers(0, c + 1))
+        Xh[idx[:n_far], :d] = (30.0 * rng.standard_normal((n_far, d))).astype(np.float32)
+        X = torch.tensor(Xh, device=DEV)
+        m = int(rng.integers(1, f - c + 1))
+        _multi_krum_check(X, idx, d, c, m, (f, d, ld, c, m))
+        if f % 2 == 1:
+            cb = int(rng.integers(0, (f - 3) // 4 + 1))
+            compared.append(_bulyan_check(X, idx, d, cb, (f, d, ld, cb)))
+    assert sum(compared) >= len(compared) - 2, compared
