@@ -186,94 +186,108 @@ __device__ inline double gram_at(const double *gram, int f, int i, int j) {
     return gram[tile_pair(nt, i / 16, j / 16) * kTile + v * 64 + l];
 }
 
-// Shared set-up of the selection kernels (one block of 256 threads): squared distances
-// d(i,j) = G_ii + G_jj - 2 G_ij (clamped at 0, exactly 0 on the diagonal) into dist_out, and for
-// every row i its distances to the other vectors in ascending order (value, then index) in
-// s_dist[i*f + t], t < f-1, with the vector they belong to in s_nbr[i*f + t].
-// s_stage: BYZ_MAX_F * BYZ_MAX_F / 2 doubles of scratch.  Ends with a block barrier.
-__device__ __forceinline__ void sorted_distance_rows(const double *__restrict__ gram, int f,
-                                                     double *dist_out, double *s_dist,
-                                                     double *s_stage, uint8_t *s_nbr) {
-    const int tid = threadIdx.x;
-    double *s_diag = s_stage;  // G_ii once per vector instead of two loads per pair
-    if (tid < f) s_diag[tid] = gram_at(gram, f, tid, tid);
-    __syncthreads();
-#pragma unroll 4
-    for (int e = tid; e < f * f; e += kBlock) {
-        const int i = e / f, j = e % f;
-        double dij = s_diag[i] + s_diag[j] - 2.0 * gram_at(gram, f, i, j);
-        if (dij < 0.0 || j == i) dij = 0.0;
-        s_dist[e] = dij;
-        if (dist_out != nullptr) dist_out[e] = dij;
+// The value lane `from` (the same for the whole wave) holds.
+__device__ __forceinline__ double lane_value(double v, int from) {
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), from);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), from);
+    return __hiloint2double(hi, lo);
+}
+
+// Set-up of the selections, one wave per vector i (4 per block): lane j computes the squared
+// distance d(i,j) = G_ii + G_jj - 2 G_ij (clamped at 0, exactly 0 on the diagonal) and writes
+// it to dist_out; a 64-lane bitonic network then sorts the distances to the other vectors in
+// ascending order (value, then index), the lanes j = i and j >= f carrying keys that sort
+// behind every distance.  The t-th nearest of vector i goes to sorted_dist[t*64 + i] and
+// sorted_nbr[t*64 + i] (t < f-1; the other entries are not written).  With n_terms >= 0 the
+// wave also adds the n_terms smallest distances one by one in ascending order from +0: the
+// Krum score, into scores and scores_out.
+__global__ __launch_bounds__(kBlock) void distance_rows_kernel(const double *__restrict__ gram, int f,
+                                                               int n_terms, double *dist_out,
+                                                               double *__restrict__ sorted_dist,
+                                                               uint8_t *__restrict__ sorted_nbr,
+                                                               double *__restrict__ scores,
+                                                               double *scores_out) {
+    const int lane = threadIdx.x & 63;
+    const int i = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
+    if (i >= f) return;  // whole wave
+    const bool spare = lane >= f || lane == i;
+    double v = 0.0;
+    if (lane < f) {
+        const double dij = gram_at(gram, f, i, i) + gram_at(gram, f, lane, lane) -
+                           2.0 * gram_at(gram, f, i, lane);
+        if (!(dij < 0.0) && lane != i) v = dij;
+        if (dist_out != nullptr) dist_out[i * f + lane] = v;
     }
-    __syncthreads();
-    // every (i, j) finds the rank of j among row i's other entries
-    for (int e = tid; e < f * f; e += kBlock) {
-        const int i = e / f, j = e % f;
-        if (i == j) continue;
-        const double v = s_dist[e];
-        int rank = 0;
-#pragma unroll 8
-        for (int k = 0; k < f; ++k) {
-            const double u = s_dist[i * f + k];
-            rank += (k != i && (u < v || (u == v && k < j))) ? 1 : 0;
+    int tag = lane | (spare ? 256 : 0);  // spare keys last, every key distinct
+#pragma unroll
+    for (int k = 2; k <= 64; k <<= 1) {
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            const double ov = __shfl_xor(v, j, 64);
+            const int otag = __shfl_xor(tag, j, 64);
+            // both lanes of a pair evaluate the same comparison (lower lane's key first), so
+            // the exchange is a permutation whatever the values are
+            const bool lower = (lane & j) == 0;
+            const double lo_v = lower ? v : ov, hi_v = lower ? ov : v;
+            const int lo_t = lower ? tag : otag, hi_t = lower ? otag : tag;
+            const bool lo_spare = lo_t >= 256, hi_spare = hi_t >= 256;
+            const bool lo_first =
+                lo_spare != hi_spare ? hi_spare : (lo_v < hi_v || (lo_v == hi_v && lo_t < hi_t));
+            const bool ascending = (lane & k) == 0;
+            if (lo_first != ascending) {
+                v = ov;
+                tag = otag;
+            }
         }
-        s_nbr[i * f + rank] = (uint8_t)j;
     }
-    __syncthreads();
-    // sort the rows in place, half of the rows at a time through the staging array
-    for (int half = 0; half < 2; ++half) {
-        const int i0 = half * (BYZ_MAX_F / 2);
-        for (int e = tid; e < (BYZ_MAX_F / 2) * f; e += kBlock) {
-            const int i = i0 + e / f, t = e % f;
-            if (i < f && t < f - 1) s_stage[(i - i0) * f + t] = s_dist[i * f + s_nbr[i * f + t]];
+    if (lane < f - 1) {
+        sorted_dist[lane * 64 + i] = v;
+        sorted_nbr[lane * 64 + i] = (uint8_t)tag;
+    }
+    if (n_terms >= 0) {
+        double score = 0.0;
+        for (int t = 0; t < n_terms; ++t) {
+            score += lane_value(v, t);
         }
-        __syncthreads();
-        for (int e = tid; e < (BYZ_MAX_F / 2) * f; e += kBlock) {
-            const int i = i0 + e / f, t = e % f;
-            if (i < f && t < f - 1) s_dist[i * f + t] = s_stage[(i - i0) * f + t];
+        if (lane == 0) {
+            scores[i] = score;
+            if (scores_out != nullptr) scores_out[i] = score;
         }
-        __syncthreads();
     }
 }
 
-// One block of 256 threads: sorted distance rows (all threads), then scores and selection
-// (thread i < f).
-__global__ __launch_bounds__(kBlock) void krum_select_kernel(const double *__restrict__ gram, int f,
-                                                             int c, int m, double *dist_out,
-                                                             double *scores_out, int32_t *selected_out,
-                                                             int32_t *selected_list,
-                                                             int32_t *n_selected) {
-    __shared__ double s_dist[BYZ_MAX_F * BYZ_MAX_F];
-    __shared__ double s_stage[BYZ_MAX_F * (BYZ_MAX_F / 2)];
-    __shared__ uint8_t s_nbr[BYZ_MAX_F * BYZ_MAX_F];
-    __shared__ double s_score[BYZ_MAX_F];
-    __shared__ int32_t s_sel[BYZ_MAX_F];
-    const int tid = threadIdx.x;
-    sorted_distance_rows(gram, f, dist_out, s_dist, s_stage, s_nbr);
-    const int i = tid;
-    if (i < f) {
-        // score = the f-c-2 smallest distances to others, added one by one in ascending order
-        double score = 0.0;
-#pragma unroll 8
-        for (int t = 0; t < f - c - 2; ++t) score += s_dist[i * f + t];
-        s_score[i] = score;
-        if (scores_out != nullptr) scores_out[i] = score;
+// Multi-Krum's choice, one wave with lane i = vector i: the m lowest scores, the lower index
+// first among equal scores.
+__global__ __launch_bounds__(64) void krum_select_kernel(const double *__restrict__ scores, int f,
+                                                         int m, int32_t *selected_out,
+                                                         int32_t *selected_list,
+                                                         int32_t *n_selected) {
+    const int i = threadIdx.x;
+    const double mine = i < f ? scores[i] : 0.0;
+    int rank = 0;
+    for (int k = 0; k < f; ++k) {
+        const double other = lane_value(mine, k);
+        rank += (other < mine || (other == mine && k < i)) ? 1 : 0;
     }
-    __syncthreads();
-    if (i < f) {
-        int rank = 0;
-        for (int k = 0; k < f; ++k)
-            rank += (s_score[k] < s_score[i] || (s_score[k] == s_score[i] && k < i)) ? 1 : 0;
-        s_sel[i] = rank < m ? 1 : 0;
-        selected_out[i] = s_sel[i];
-    }
-    __syncthreads();
-    if (tid == 0) {
-        int n = 0;
-        for (int k = 0; k < f; ++k)
-            if (s_sel[k] != 0) selected_list[n++] = k;
-        *n_selected = n;
+    const bool chosen = i < f && rank < m;
+    const uint64_t mask = __builtin_amdgcn_ballot_w64(chosen);
+    if (i < f) selected_out[i] = chosen ? 1 : 0;
+    if (chosen) selected_list[__builtin_popcountll(mask & ((1ull << i) - 1ull))] = i;
+    if (i == 0) *n_selected = __builtin_popcountll(mask);
+}
+
+// One exchange of a wave-wide search for the lowest (score, index): every lane looks at the
+// lane the data-parallel-primitive pattern CTRL pairs it with (a pairing inside a row of 16
+// lanes that is its own inverse) and keeps the lower of the two keys.
+template <int CTRL>
+__device__ __forceinline__ void argmin_exchange(double &score, int &best) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(score), CTRL, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(score), CTRL, 0xF, 0xF, false);
+    const int o_best = __builtin_amdgcn_update_dpp(0, best, CTRL, 0xF, 0xF, false);
+    const double o_score = __hiloint2double(hi, lo);
+    if (o_score < score || (o_score == score && o_best < best)) {
+        score = o_score;
+        best = o_best;
     }
 }
 
@@ -281,78 +295,95 @@ __global__ __launch_bounds__(kBlock) void krum_select_kernel(const double *__res
 // theta = f - 2c are chosen.  Round with n' vectors left: score(i) = the n' - c - 2 smallest
 // distances from i to the other vectors left, added one by one in ascending order (no terms
 // when that count is <= 0); lowest score wins, lowest index among equal scores.
-// One block of 256 threads sets up the sorted distance rows; then the first wave runs the
-// rounds with lane i = vector i: the vectors left are a 64-bit mask in registers, a score is
-// one walk over the lane's sorted row (held in registers), and the winner comes from a
-// wave-wide butterfly on (score, index).
-__global__ __launch_bounds__(kBlock) void bulyan_select_kernel(const double *__restrict__ gram, int f,
-                                                               int c, double *dist_out,
-                                                               int32_t *selected_out,
-                                                               int32_t *order_out,
-                                                               int32_t *selected_list,
-                                                               int32_t *n_selected,
-                                                               const int32_t *__restrict__ row_index,
-                                                               int32_t *selected_rows) {
-    __shared__ double s_dist[BYZ_MAX_F * BYZ_MAX_F];
-    __shared__ double s_stage[BYZ_MAX_F * (BYZ_MAX_F / 2)];
-    __shared__ uint8_t s_nbr[BYZ_MAX_F * BYZ_MAX_F];
-    const int tid = threadIdx.x;
-    sorted_distance_rows(gram, f, dist_out, s_dist, s_stage, s_nbr);
-    if (tid < f) selected_out[tid] = 0;
-    if (tid >= 64) return;
-    const int i = tid;
+// One wave with lane i = vector i, on the sorted rows distance_rows_kernel left.  The lane keeps
+// its sorted row in registers and, as a 64-bit mask over the positions of that row, the terms
+// of its next score.  A vector left has n' - 1 others left and takes n' - c - 2 of them, so the
+// terms are the others left without the c + 1 farthest; choosing a vector removes it from
+// every row: where it was a term the mask just loses it, elsewhere it was one of the c + 1
+// farthest and the farthest term takes its place there.  A score is then one walk over the
+// mask, and the winner is the lowest (score, index) of the wave.
+__global__ __launch_bounds__(64) void bulyan_select_kernel(const double *__restrict__ sorted_dist,
+                                                           const uint8_t *__restrict__ sorted_nbr,
+                                                           int f, int c, int32_t *selected_out,
+                                                           int32_t *order_out,
+                                                           int32_t *selected_list,
+                                                           int32_t *n_selected,
+                                                           const int32_t *__restrict__ row_index,
+                                                           int32_t *selected_rows) {
+    __shared__ uint8_t s_pos[BYZ_MAX_F * 64];  // [j*64 + i]: where vector j stands in i's row
+    const int i = threadIdx.x;
+    if (i < f) selected_out[i] = 0;
     const int theta = f - 2 * c;
-    uint64_t left = f == 64 ? ~0ull : ((1ull << f) - 1ull);
-    int first = 0;
-    // the lane's sorted row in registers: distance and index of its t-th nearest other vector
+    const int32_t my_row = row_index[i < f ? i : 0];  // a round then needs no load from memory
+    int32_t first_row = my_row;
+    // entries the set-up did not write are loaded and set aside
     constexpr int kMaxOthers = BYZ_MAX_F - 1;
     double rdist[kMaxOthers];
-    uint32_t rnbr[kMaxOthers];
 #pragma unroll
     for (int t = 0; t < kMaxOthers; ++t) {
         const bool have = i < f && t < f - 1;
-        rdist[t] = have ? s_dist[i * f + t] : 0.0;
-        rnbr[t] = have ? s_nbr[i * f + t] : 0u;
+        const double dv = sorted_dist[t * 64 + i];
+        const uint32_t nv = sorted_nbr[t * 64 + i];
+        rdist[t] = have ? dv : 0.0;
+        if (have) s_pos[nv * 64 + i] = (uint8_t)t;
     }
+    __syncthreads();
+    bool left = i < f;  // not chosen yet
+    uint64_t terms = left ? ((1ull << (f - c - 2)) - 1ull) : 0ull;  // f - c - 2 <= 62
     for (int round = 0; round < theta; ++round) {
-        int k = (f - round) - c - 2;
-        if (k < 0) k = 0;
-        const bool mine = i < f && ((left >> i) & 1ull) != 0;
-        double score = mine ? 0.0 : __builtin_huge_val();
-        int n = mine ? 0 : k;
-        bool done = false;
+        double score = left ? 0.0 : __builtin_huge_val();
+        bool done = __builtin_amdgcn_ballot_w64(terms != 0) == 0;
 #pragma unroll
-        for (int t0 = 0; t0 < kMaxOthers; t0 += 16) {
+        for (int t0 = 0; t0 < kMaxOthers; t0 += 8) {
             if (!done && t0 < f - 1) {
 #pragma unroll
-                for (int t = t0; t < t0 + 16 && t < kMaxOthers; ++t) {
-                    const bool take = t < f - 1 && ((left >> rnbr[t]) & 1ull) != 0 && n < k;
-                    score += take ? rdist[t] : 0.0;
-                    n += take ? 1 : 0;
-                }
-                done = __builtin_amdgcn_ballot_w64(n < k) == 0;  // every lane has its k terms
+                for (int t = t0; t < t0 + 8 && t < kMaxOthers; ++t)
+                    score += ((terms >> t) & 1ull) != 0 ? rdist[t] : 0.0;
+                if (t0 + 8 < 64) done = __builtin_amdgcn_ballot_w64((terms >> (t0 + 8)) != 0) == 0;
             }
         }
+        // lowest (score, index) of the wave: four exchanges inside each row of 16 lanes, then
+        // the four rows are compared from their first lanes
         int best = i;
-        for (int off = 1; off < 64; off <<= 1) {
-            const double o_score = __shfl_xor(score, off, 64);
-            const int o_best = __shfl_xor(best, off, 64);
-            if (o_score < score || (o_score == score && o_best < best)) {
-                score = o_score;
-                best = o_best;
+        argmin_exchange<0xB1>(score, best);   // quad_perm [1,0,3,2]: lane ^ 1
+        argmin_exchange<0x4E>(score, best);   // quad_perm [2,3,0,1]: lane ^ 2
+        argmin_exchange<0x141>(score, best);  // row_half_mirror: the other quad of the 8
+        argmin_exchange<0x140>(score, best);  // row_mirror: the other half of the 16
+        {
+            double w_score = lane_value(score, 0);
+            int w_best = __builtin_amdgcn_readlane(best, 0);
+#pragma unroll
+            for (int row = 1; row < 4; ++row) {
+                const double r_score = lane_value(score, 16 * row);
+                const int r_best = __builtin_amdgcn_readlane(best, 16 * row);
+                if (r_score < w_score || (r_score == w_score && r_best < w_best)) {
+                    w_score = r_score;
+                    w_best = r_best;
+                }
             }
+            best = w_best;
         }
-        left &= ~(1ull << best);
-        if (round == 0) first = best;
+        const int32_t best_row = __shfl(my_row, best, 64);
+        if (round == 0) first_row = best_row;
         if (i == 0) {
             selected_list[round] = best;
-            selected_rows[round] = row_index[best];
+            selected_rows[round] = best_row;
             selected_out[best] = 1;
             if (order_out != nullptr) order_out[round] = best;
         }
+        if (i == best) {
+            left = false;
+            terms = 0;
+        } else if (left) {
+            const uint64_t bit = 1ull << s_pos[best * 64 + i];
+            if ((terms & bit) != 0)
+                terms &= ~bit;
+            else if (terms != 0)
+                terms &= ~(1ull << (63 - __builtin_clzll(terms)));
+        }
     }
     // rows of the chosen vectors for the second phase; the spare entries repeat the first one
-    if (i >= theta) selected_rows[i] = row_index[first];
+    if (i >= theta) selected_rows[i] = first_row;
     if (i == 0) *n_selected = theta;
 }
 
@@ -396,6 +427,9 @@ struct KrumWorkspace {
     int32_t selected_rows[BYZ_MAX_F];  // Bulyan: rows of the chosen vectors, spare entries valid
     int32_t n_selected;
     int32_t pad[63 + BYZ_MAX_F];
+    double sorted_dist[BYZ_MAX_F * BYZ_MAX_F];  // [t*64 + i]: i's t-th smallest distance
+    double scores[BYZ_MAX_F];
+    uint8_t sorted_nbr[BYZ_MAX_F * BYZ_MAX_F];  // and the vector it leads to
     float partial[(size_t)kGramBlocks * kMaxPairs * kTile];
 };
 
@@ -467,8 +501,13 @@ extern "C" int byz_multi_krum(const float *rows_base, int64_t d, int64_t ld,
     KrumWorkspace *ws = reinterpret_cast<KrumWorkspace *>(workspace);
     int rc = launch_gram(rows_base, d, ld, row_index_dev, f, ws, s);
     if (rc != BYZ_OK) return rc;
-    krum_select_kernel<<<1, kBlock, 0, s>>>(ws->gram, f, c, m, dist_out, scores_out, selected_out,
-                                            ws->selected_list, &ws->n_selected);
+    const int row_blocks = (f + kBlock / 64 - 1) / (kBlock / 64);
+    distance_rows_kernel<<<row_blocks, kBlock, 0, s>>>(ws->gram, f, f - c - 2, dist_out,
+                                                       ws->sorted_dist, ws->sorted_nbr, ws->scores,
+                                                       scores_out);
+    BYZ_HIP(hipGetLastError());
+    krum_select_kernel<<<1, 64, 0, s>>>(ws->scores, f, m, selected_out, ws->selected_list,
+                                        &ws->n_selected);
     BYZ_HIP(hipGetLastError());
     if (d > 0) {
         const int64_t n_thr = d >= 4 ? (d + 3) / 4 : d;
@@ -497,9 +536,13 @@ extern "C" int byz_bulyan(const float *rows_base, int64_t d, int64_t ld,
     KrumWorkspace *ws = reinterpret_cast<KrumWorkspace *>(workspace);
     int rc = launch_gram(rows_base, d, ld, row_index_dev, f, ws, s);
     if (rc != BYZ_OK) return rc;
-    bulyan_select_kernel<<<1, kBlock, 0, s>>>(ws->gram, f, c, dist_out, selected_out, order_out,
-                                              ws->selected_list, &ws->n_selected, row_index_dev,
-                                              ws->selected_rows);
+    const int row_blocks = (f + kBlock / 64 - 1) / (kBlock / 64);
+    distance_rows_kernel<<<row_blocks, kBlock, 0, s>>>(ws->gram, f, -1, dist_out, ws->sorted_dist,
+                                                       ws->sorted_nbr, ws->scores, nullptr);
+    BYZ_HIP(hipGetLastError());
+    bulyan_select_kernel<<<1, 64, 0, s>>>(ws->sorted_dist, ws->sorted_nbr, f, c, selected_out,
+                                          order_out, ws->selected_list, &ws->n_selected,
+                                          row_index_dev, ws->selected_rows);
     BYZ_HIP(hipGetLastError());
     const int theta = f - 2 * c;
     return byz_internal_launch_bulyan_mean(rows_base, d, ld, ws->selected_rows, f, theta,
