@@ -218,7 +218,7 @@ def main():
         ms_agg_tm = timed_call(lambda: step(0, B.BYZ_AGG_TRIM(cmax)))
         mk_m = asg.f - cmax
         ms_mk = None
-        if asg.f <= B.BYZ_MAX_F:
+        if asg.f <= B.BYZ_MAX_F_KRUM:
             mk_ws = torch.empty(B.byz_multi_krum_workspace_bytes(asg.f), dtype=torch.uint8, device=dev)
             ms_mk = timed_call(lambda: B.byz_multi_krum(bufs[0], d, wrow_v, cmax, mk_m, out=out,
                                                         workspace=mk_ws, stream=stream))

@@ -52,7 +52,8 @@ typedef enum byz_scheme {
     BYZ_SCHEME_FRC = 2       /* Sec. 5.3.1 (DETOX / DRACO): a = K, b = r | K; f = K/r, l = 1           */
 } byz_scheme;
 
-#define BYZ_MAX_F 64       /* largest f of the register-network kernels, the trimmed mean and Multi-Krum */
+#define BYZ_MAX_F 64       /* largest f of Bulyan and of the per-thread-array kernels for d < 4          */
+#define BYZ_MAX_F_KRUM 128 /* largest f of Multi-Krum                                                    */
 #define BYZ_MAX_F_WIDE 256 /* largest f of byz_vote, byz_median, byz_aggregate and the search            */
 #define BYZ_MAX_R 7  /* largest replication factor                                           */
 
@@ -215,7 +216,8 @@ int byz_trimmed_mean(const float *rows_base, int64_t d, int64_t ld, const int32_
 /*
  * Multi-Krum over f vectors (the aggregator Sec. 6.1 and Sec. 7 name as an alternative to the
  * median on the vote winners; the rule itself is the published one): with c of the f vectors
- * possibly Byzantine, f >= 2c + 3 (the requirement Sec. 6.1 quotes),
+ * possibly Byzantine, 2c + 3 <= f <= BYZ_MAX_F_KRUM (the lower bound is the requirement Sec. 6.1
+ * quotes),
  *   score(i) = sum of the f - c - 2 smallest squared Euclidean distances from vector i to the
  *              other vectors,
  *   the m vectors of lowest score are selected (equal scores: lower index first), 1 <= m <= f - c
@@ -230,8 +232,8 @@ int byz_trimmed_mean(const float *rows_base, int64_t d, int64_t ld, const int32_
  *   scores_out    device [f] double out, may be NULL
  *   dist_out      device [f*f] double out, may be NULL
  *   workspace     device, >= byz_multi_krum_workspace_bytes(f) bytes, 256-byte aligned
- * Errors: BYZ_EINVAL (null pointers, f < 2c + 3, m outside [1, f - c], sizes), BYZ_ENOMEM
- * (workspace too small), BYZ_EDEVICE.
+ * Errors: BYZ_EINVAL (null pointers, f < 2c + 3, f > BYZ_MAX_F_KRUM, m outside [1, f - c],
+ * sizes), BYZ_ENOMEM (workspace too small), BYZ_EDEVICE.
  */
 size_t byz_multi_krum_workspace_bytes(int f);
 int byz_multi_krum(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev,

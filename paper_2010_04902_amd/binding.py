@@ -16,6 +16,7 @@ BYZ_SCHEME_MOLS = 0
 BYZ_SCHEME_RAMANUJAN = 1
 BYZ_SCHEME_FRC = 2
 BYZ_MAX_F = 64
+BYZ_MAX_F_KRUM = 128
 BYZ_MAX_F_WIDE = 256
 BYZ_MAX_R = 7
 

@@ -15,6 +15,7 @@
 // not depend on scheduling.
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
 #include <cstdint>
 
 #include "byz_internal.h"
@@ -37,13 +38,20 @@ constexpr int kStride = kChunk + 4;    // row pitch in LDS: rows stay 16-byte al
                                        // staging write per lane); see the column swizzle below
 constexpr int kGramBlocks = 512;       // partial Gram tiles (2 blocks per CU; 1024: 4 % faster, reduction 3 us slower)
 constexpr int kTile = 16 * 16;         // outputs of one MFMA tile
-constexpr int kMaxNT = BYZ_MAX_F / 16; // row tiles of the largest matrix
+constexpr int kMaxKrum = BYZ_MAX_F_KRUM;  // most vectors Multi-Krum takes (Bulyan: BYZ_MAX_F)
+constexpr int kMaxNT = kMaxKrum / 16;  // row tiles of the largest matrix
 constexpr int kMaxPairs = kMaxNT * (kMaxNT + 1) / 2;  // tiles on and above the diagonal
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4u __attribute__((ext_vector_type(4), aligned(4)));
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Row tiles of 16 the Gram matrix of f vectors is computed with (the compiled kernels have
+// 1, 2, 3, 4, 6 or 8); the tiles on and above the diagonal are stored.
+__host__ __device__ constexpr int row_tiles(int f) {
+    return f <= 64 ? (f + 15) / 16 : (f <= 96 ? 6 : 8);
+}
 
 // Tile (ti, tj), ti <= tj < nt, of the upper triangle, numbered row by row.
 __host__ __device__ constexpr int tile_pair(int nt, int ti, int tj) {
@@ -74,13 +82,26 @@ __global__ __launch_bounds__(kBlock) void gram_partial_kernel(const float *__res
     for (int p = 0; p < NP; ++p) acc[p] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
     const int64_t n_chunks = (d + kChunk - 1) / kChunk;
 
-    // this wave's rows; slots past f repeat the last row (loaded, never stored)
-    const float *rowp[RW];
+    // this wave's rows; slots past f repeat the last row (loaded, never stored).  The widest
+    // shapes keep row numbers instead of pointers: half the registers, one multiply per load.
+    constexpr bool kRowNumbers = RW > 24;
+    const float *rowp[kRowNumbers ? 1 : RW];
+    int32_t rown[kRowNumbers ? RW : 1];
 #pragma unroll
     for (int t = 0; t < RW; ++t) {
         const int j = wave + 4 * t;
-        rowp[t] = X + (int64_t)row_index[j < f ? j : f - 1] * ld + 4 * lane;
+        const int32_t row = row_index[j < f ? j : f - 1];
+        if constexpr (kRowNumbers)
+            rown[t] = row;
+        else
+            rowp[t] = X + (int64_t)row * ld + 4 * lane;
     }
+    auto row_ptr = [&](int t) -> const float * {
+        if constexpr (kRowNumbers)
+            return X + (int64_t)rown[t] * ld + 4 * lane;
+        else
+            return rowp[t];
+    };
     float reg[RW][4];
     auto fetch = [&](int64_t chunk) {
         const int64_t c0 = chunk * kChunk + 4 * lane;
@@ -88,7 +109,7 @@ __global__ __launch_bounds__(kBlock) void gram_partial_kernel(const float *__res
 #pragma unroll
             for (int t = 0; t < RW; ++t) {
                 const f32x4u v = __builtin_nontemporal_load(
-                    reinterpret_cast<const f32x4u *>(rowp[t] + chunk * kChunk));
+                    reinterpret_cast<const f32x4u *>(row_ptr(t) + chunk * kChunk));
                 reg[t][0] = v[0]; reg[t][1] = v[1]; reg[t][2] = v[2]; reg[t][3] = v[3];
             }
         } else {  // the ragged last chunk: missing coordinates count as zero
@@ -96,7 +117,7 @@ __global__ __launch_bounds__(kBlock) void gram_partial_kernel(const float *__res
             for (int t = 0; t < RW; ++t)
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    reg[t][e] = c0 + e < d ? rowp[t][chunk * kChunk + e] : 0.0f;
+                    reg[t][e] = c0 + e < d ? row_ptr(t)[chunk * kChunk + e] : 0.0f;
         }
     };
 
@@ -125,15 +146,16 @@ __global__ __launch_bounds__(kBlock) void gram_partial_kernel(const float *__res
         // wave w multiplies coordinates [64w, 64w+64) of the chunk, four per MFMA: lane l holds
         // A[row = l%16][k = l/16], which is also B[k][col = l%16] of the transposed operand
         const float *t0 = T + (lane & 15) * kStride + wave * 64 + ((lane >> 4) ^ ((lane & 8) >> 2));
+        constexpr int SB = NT > 6 ? 2 : (NT > 4 ? 4 : 8);  // steps whose operands are read ahead of their MFMAs
 #pragma unroll
-        for (int s0 = 0; s0 < 16; s0 += 8) {
-            float x[NT][8];
+        for (int s0 = 0; s0 < 16; s0 += SB) {
+            float x[NT][SB];
 #pragma unroll
-            for (int s = 0; s < 8; ++s)
+            for (int s = 0; s < SB; ++s)
 #pragma unroll
                 for (int t = 0; t < NT; ++t) x[t][s] = t0[16 * t * kStride + 4 * (s0 + s)];
 #pragma unroll
-            for (int s = 0; s < 8; ++s)
+            for (int s = 0; s < SB; ++s)
 #pragma unroll
                 for (int ti = 0; ti < NT; ++ti)
 #pragma unroll
@@ -143,16 +165,33 @@ __global__ __launch_bounds__(kBlock) void gram_partial_kernel(const float *__res
         }
         __syncthreads();
     }
-    // add the four waves' tiles through LDS (the staging tile is free now), then store
-    float *red = T;  // [4][NP][256] floats = at most 40 KiB <= the staging tile
-#pragma unroll
-    for (int p = 0; p < NP; ++p)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) red[(wave * NP + p) * kTile + v * 64 + lane] = acc[p][v];
-    __syncthreads();
+    // add the four waves' tiles through LDS (the staging tile is free now), then store:
+    // ((wave 0 + wave 1) + wave 2) + wave 3 either way
+    float *red = T;
     float *dst = partial + (int64_t)blockIdx.x * NP * kTile;
-    for (int i = tid; i < NP * kTile; i += kBlock)
-        dst[i] = ((red[i] + red[NP * kTile + i]) + red[2 * NP * kTile + i]) + red[3 * NP * kTile + i];
+    if constexpr (4 * NP * kTile <= 16 * NT * kStride) {  // [4][NP][256] floats fit the tile
+#pragma unroll
+        for (int p = 0; p < NP; ++p)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) red[(wave * NP + p) * kTile + v * 64 + lane] = acc[p][v];
+        __syncthreads();
+        for (int i = tid; i < NP * kTile; i += kBlock)
+            dst[i] = ((red[i] + red[NP * kTile + i]) + red[2 * NP * kTile + i]) + red[3 * NP * kTile + i];
+    } else {  // one [NP][256] array, the waves add their tiles in turn
+        for (int w = 0; w < 4; ++w) {
+            if (wave == w) {
+#pragma unroll
+                for (int p = 0; p < NP; ++p)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        float *cell = red + p * kTile + v * 64 + lane;
+                        *cell = w == 0 ? acc[p][v] : *cell + acc[p][v];
+                    }
+            }
+            __syncthreads();
+        }
+        for (int i = tid; i < NP * kTile; i += kBlock) dst[i] = red[i];
+    }
 }
 
 // gram[t][pos] = sum over blocks of partial[block][t][pos] in fp64, in a fixed order: thread
@@ -179,7 +218,7 @@ __global__ __launch_bounds__(kBlock) void gram_reduce_kernel(const float *__rest
 __device__ inline double gram_at(const double *gram, int f, int i, int j) {
     // entry (i, j) of the symmetric matrix from the stored upper-triangle tiles
     if (i > j) { const int t = i; i = j; j = t; }
-    const int nt = (f + 15) / 16;
+    const int nt = row_tiles(f);
     const int r = i % 16, c = j % 16;
     // row r = 4*(l/16) + v, column c = l%16  =>
     const int v = r % 4, l = c + 16 * (r / 4);
@@ -193,14 +232,24 @@ __device__ __forceinline__ double lane_value(double v, int from) {
     return __hiloint2double(hi, lo);
 }
 
-// Set-up of the selections, one wave per vector i (4 per block): lane j computes the squared
-// distance d(i,j) = G_ii + G_jj - 2 G_ij (clamped at 0, exactly 0 on the diagonal) and writes
-// it to dist_out; a 64-lane bitonic network then sorts the distances to the other vectors in
-// ascending order (value, then index), the lanes j = i and j >= f carrying keys that sort
-// behind every distance.  The t-th nearest of vector i goes to sorted_dist[t*64 + i] and
-// sorted_nbr[t*64 + i] (t < f-1; the other entries are not written).  With n_terms >= 0 the
-// wave also adds the n_terms smallest distances one by one in ascending order from +0: the
-// Krum score, into scores and scores_out.
+// (key, tag) pairs of the row sort: spare keys (tag >= 256) last, else by value, then by tag.
+__device__ __forceinline__ bool key_before(double a_v, int a_t, double b_v, int b_t) {
+    const bool a_spare = a_t >= 256, b_spare = b_t >= 256;
+    return a_spare != b_spare ? b_spare : (a_v < b_v || (a_v == b_v && a_t < b_t));
+}
+
+// Set-up of the selections, one wave per vector i (4 per block), for f <= 64*PER: the lane
+// computes the squared distances d(i,j) = G_ii + G_jj - 2 G_ij (clamped at 0, exactly 0 on the
+// diagonal) for j = lane and, with PER = 2, j = lane + 64, and writes them to dist_out; a
+// bitonic network over the 64*PER keys of the wave then sorts the distances to the other
+// vectors in ascending order (value, then index), the keys of j = i and j >= f sorting behind
+// every distance.  The t-th nearest of vector i goes to sorted_dist[t*kRowStride + i] and
+// sorted_nbr[t*kRowStride + i] (t < f-1; the other entries are not written).  With
+// n_terms >= 0 the wave also adds the n_terms smallest distances one by one in ascending
+// order from +0: the Krum score, into scores and scores_out.
+constexpr int kRowStride = kMaxKrum;
+
+template <int PER>
 __global__ __launch_bounds__(kBlock) void distance_rows_kernel(const double *__restrict__ gram, int f,
                                                                int n_terms, double *dist_out,
                                                                double *__restrict__ sorted_dist,
@@ -210,45 +259,68 @@ __global__ __launch_bounds__(kBlock) void distance_rows_kernel(const double *__r
     const int lane = threadIdx.x & 63;
     const int i = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
     if (i >= f) return;  // whole wave
-    const bool spare = lane >= f || lane == i;
-    double v = 0.0;
-    if (lane < f) {
-        const double dij = gram_at(gram, f, i, i) + gram_at(gram, f, lane, lane) -
-                           2.0 * gram_at(gram, f, i, lane);
-        if (!(dij < 0.0) && lane != i) v = dij;
-        if (dist_out != nullptr) dist_out[i * f + lane] = v;
-    }
-    int tag = lane | (spare ? 256 : 0);  // spare keys last, every key distinct
+    double v[PER];
+    int tag[PER];
+    const double g_ii = gram_at(gram, f, i, i);
 #pragma unroll
-    for (int k = 2; k <= 64; k <<= 1) {
+    for (int e = 0; e < PER; ++e) {
+        const int j = lane + 64 * e;
+        v[e] = 0.0;
+        if (j < f) {
+            const double dij = g_ii + gram_at(gram, f, j, j) - 2.0 * gram_at(gram, f, i, j);
+            if (!(dij < 0.0) && j != i) v[e] = dij;
+            if (dist_out != nullptr) dist_out[i * f + j] = v[e];
+        }
+        tag[e] = j | ((j >= f || j == i) ? 256 : 0);  // every key distinct
+    }
+#pragma unroll
+    for (int k = 2; k <= 64 * PER; k <<= 1) {
 #pragma unroll
         for (int j = k >> 1; j > 0; j >>= 1) {
-            const double ov = __shfl_xor(v, j, 64);
-            const int otag = __shfl_xor(tag, j, 64);
-            // both lanes of a pair evaluate the same comparison (lower lane's key first), so
-            // the exchange is a permutation whatever the values are
-            const bool lower = (lane & j) == 0;
-            const double lo_v = lower ? v : ov, hi_v = lower ? ov : v;
-            const int lo_t = lower ? tag : otag, hi_t = lower ? otag : tag;
-            const bool lo_spare = lo_t >= 256, hi_spare = hi_t >= 256;
-            const bool lo_first =
-                lo_spare != hi_spare ? hi_spare : (lo_v < hi_v || (lo_v == hi_v && lo_t < hi_t));
-            const bool ascending = (lane & k) == 0;
-            if (lo_first != ascending) {
-                v = ov;
-                tag = otag;
+            if (j == 64) {
+                // partner in the same lane; k = 128 here, so the order is ascending
+                if constexpr (PER == 2) {
+                    if (!key_before(v[0], tag[0], v[1], tag[1])) {
+                        const double tv = v[0];
+                        const int tt = tag[0];
+                        v[0] = v[1];
+                        tag[0] = tag[1];
+                        v[1] = tv;
+                        tag[1] = tt;
+                    }
+                }
+            } else {
+                const bool lower = (lane & j) == 0;
+#pragma unroll
+                for (int e = 0; e < PER; ++e) {
+                    const double ov = __shfl_xor(v[e], j, 64);
+                    const int otag = __shfl_xor(tag[e], j, 64);
+                    // both lanes of a pair evaluate the same comparison (lower lane's key
+                    // first), so the exchange is a permutation whatever the values are
+                    const bool lo_first = lower ? key_before(v[e], tag[e], ov, otag)
+                                                : key_before(ov, otag, v[e], tag[e]);
+                    const bool ascending = ((lane + 64 * e) & k) == 0;
+                    if (lo_first != ascending) {
+                        v[e] = ov;
+                        tag[e] = otag;
+                    }
+                }
             }
         }
     }
-    if (lane < f - 1) {
-        sorted_dist[lane * 64 + i] = v;
-        sorted_nbr[lane * 64 + i] = (uint8_t)tag;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+        const int t = lane + 64 * e;
+        if (t < f - 1) {
+            sorted_dist[t * kRowStride + i] = v[e];
+            sorted_nbr[t * kRowStride + i] = (uint8_t)tag[e];
+        }
     }
     if (n_terms >= 0) {
         double score = 0.0;
-        for (int t = 0; t < n_terms; ++t) {
-            score += lane_value(v, t);
-        }
+        for (int t = 0; t < n_terms && t < 64; ++t) score += lane_value(v[0], t);
+        if constexpr (PER == 2)
+            for (int t = 64; t < n_terms; ++t) score += lane_value(v[1], t - 64);
         if (lane == 0) {
             scores[i] = score;
             if (scores_out != nullptr) scores_out[i] = score;
@@ -256,24 +328,39 @@ __global__ __launch_bounds__(kBlock) void distance_rows_kernel(const double *__r
     }
 }
 
-// Multi-Krum's choice, one wave with lane i = vector i: the m lowest scores, the lower index
-// first among equal scores.
-__global__ __launch_bounds__(64) void krum_select_kernel(const double *__restrict__ scores, int f,
-                                                         int m, int32_t *selected_out,
-                                                         int32_t *selected_list,
-                                                         int32_t *n_selected) {
+// Multi-Krum's choice, thread i = vector i (one block of kMaxKrum threads): the m lowest
+// scores, the lower index first among equal scores.
+__global__ __launch_bounds__(kMaxKrum) void krum_select_kernel(const double *__restrict__ scores, int f,
+                                                               int m, int32_t *selected_out,
+                                                               int32_t *selected_list,
+                                                               int32_t *n_selected) {
+    __shared__ double s_score[kMaxKrum];
+    __shared__ uint64_t s_chosen[kMaxKrum / 64];
     const int i = threadIdx.x;
     const double mine = i < f ? scores[i] : 0.0;
+    s_score[i] = mine;
+    __syncthreads();
     int rank = 0;
+#pragma unroll 8
     for (int k = 0; k < f; ++k) {
-        const double other = lane_value(mine, k);
+        const double other = s_score[k];
         rank += (other < mine || (other == mine && k < i)) ? 1 : 0;
     }
     const bool chosen = i < f && rank < m;
     const uint64_t mask = __builtin_amdgcn_ballot_w64(chosen);
+    if ((i & 63) == 0) s_chosen[i >> 6] = mask;
+    __syncthreads();
+    int before = __builtin_popcountll(mask & ((1ull << (i & 63)) - 1ull));
+    int total = 0;
+#pragma unroll
+    for (int w = 0; w < kMaxKrum / 64; ++w) {
+        const int n = __builtin_popcountll(s_chosen[w]);
+        if (w < (i >> 6)) before += n;
+        total += n;
+    }
     if (i < f) selected_out[i] = chosen ? 1 : 0;
-    if (chosen) selected_list[__builtin_popcountll(mask & ((1ull << i) - 1ull))] = i;
-    if (i == 0) *n_selected = __builtin_popcountll(mask);
+    if (chosen) selected_list[before] = i;
+    if (i == 0) *n_selected = total;
 }
 
 // One exchange of a wave-wide search for the lowest (score, index): every lane looks at the
@@ -322,8 +409,8 @@ __global__ __launch_bounds__(64) void bulyan_select_kernel(const double *__restr
 #pragma unroll
     for (int t = 0; t < kMaxOthers; ++t) {
         const bool have = i < f && t < f - 1;
-        const double dv = sorted_dist[t * 64 + i];
-        const uint32_t nv = sorted_nbr[t * 64 + i];
+        const double dv = sorted_dist[t * kRowStride + i];
+        const uint32_t nv = sorted_nbr[t * kRowStride + i];
         rdist[t] = have ? dv : 0.0;
         if (have) s_pos[nv * 64 + i] = (uint8_t)t;
     }
@@ -423,57 +510,72 @@ __global__ __launch_bounds__(kBlock) void selected_mean_kernel(const float *__re
 
 struct KrumWorkspace {
     double gram[kMaxPairs * kTile];
-    int32_t selected_list[BYZ_MAX_F];
+    double sorted_dist[kMaxKrum * kRowStride];  // [t*kRowStride + i]: i's t-th smallest distance
+    double scores[kMaxKrum];
+    uint8_t sorted_nbr[kMaxKrum * kRowStride];  // and the vector it leads to
+    int32_t selected_list[kMaxKrum];
     int32_t selected_rows[BYZ_MAX_F];  // Bulyan: rows of the chosen vectors, spare entries valid
     int32_t n_selected;
-    int32_t pad[63 + BYZ_MAX_F];
-    double sorted_dist[BYZ_MAX_F * BYZ_MAX_F];  // [t*64 + i]: i's t-th smallest distance
-    double scores[BYZ_MAX_F];
-    uint8_t sorted_nbr[BYZ_MAX_F * BYZ_MAX_F];  // and the vector it leads to
-    float partial[(size_t)kGramBlocks * kMaxPairs * kTile];
+    int32_t pad[63];
+    float partial[1];  // [kGramBlocks][tiles of f][256], sized by krum_workspace_bytes
 };
 
+inline int stored_tiles(int f) { return row_tiles(f) * (row_tiles(f) + 1) / 2; }
+
+inline size_t krum_workspace_bytes(int f) {
+    return offsetof(KrumWorkspace, partial) +
+           sizeof(float) * (size_t)kGramBlocks * stored_tiles(f) * kTile;
+}
+
 // Gram matrix of the f rows into ws->gram (partial tiles, then the fp64 reduction).
+template <int NT, int RW>
+int launch_gram_shape(int grid, const float *rows_base, int64_t d, int64_t ld,
+                      const int32_t *row_index_dev, int f, float *partial, hipStream_t s) {
+    const size_t lds = (size_t)16 * NT * kStride * sizeof(float);
+    if (lds > 64 * 1024)  // more than a kernel may use without asking
+        BYZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&gram_partial_kernel<NT, RW>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    gram_partial_kernel<NT, RW><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f, partial);
+    BYZ_HIP(hipGetLastError());
+    return BYZ_OK;
+}
+
 int launch_gram(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev, int f,
                 KrumWorkspace *ws, hipStream_t s) {
-    const int nt = (f + 15) / 16;
-    const int ntiles = nt * (nt + 1) / 2;
     int64_t n_chunks = (d + kChunk - 1) / kChunk;
     if (n_chunks < 1) n_chunks = 1;  // d == 0: one block writes zero tiles
     const int grid = n_chunks < kGramBlocks ? (int)n_chunks : kGramBlocks;
-    const size_t lds = (size_t)16 * nt * kStride * sizeof(float);
     // (row tiles, rows a wave stages per chunk = ceil(f / 4) rounded up to a compiled value)
-    if (f <= 16) {
-        gram_partial_kernel<1, 4><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
-                                                           ws->partial);
-    } else if (f <= 28) {
-        gram_partial_kernel<2, 7><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
-                                                           ws->partial);
-    } else if (f <= 32) {
-        gram_partial_kernel<2, 8><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
-                                                           ws->partial);
-    } else if (f <= 36) {
-        gram_partial_kernel<3, 9><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
-                                                           ws->partial);
-    } else if (f <= 48) {
-        gram_partial_kernel<3, 12><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
-                                                            ws->partial);
-    } else {
-        // 64 rows x 260 words is a little over the 64 KiB a kernel may use without asking
-        if (f <= 52) {
-            BYZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&gram_partial_kernel<4, 13>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            gram_partial_kernel<4, 13><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
-                                                                ws->partial);
-        } else {
-            BYZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&gram_partial_kernel<4, 16>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            gram_partial_kernel<4, 16><<<grid, kBlock, lds, s>>>(rows_base, d, ld, row_index_dev, f,
-                                                                ws->partial);
-        }
-    }
-    BYZ_HIP(hipGetLastError());
+    int rc;
+    if (f <= 16) rc = launch_gram_shape<1, 4>(grid, rows_base, d, ld, row_index_dev, f, ws->partial, s);
+    else if (f <= 28) rc = launch_gram_shape<2, 7>(grid, rows_base, d, ld, row_index_dev, f, ws->partial, s);
+    else if (f <= 32) rc = launch_gram_shape<2, 8>(grid, rows_base, d, ld, row_index_dev, f, ws->partial, s);
+    else if (f <= 36) rc = launch_gram_shape<3, 9>(grid, rows_base, d, ld, row_index_dev, f, ws->partial, s);
+    else if (f <= 48) rc = launch_gram_shape<3, 12>(grid, rows_base, d, ld, row_index_dev, f, ws->partial, s);
+    else if (f <= 52) rc = launch_gram_shape<4, 13>(grid, rows_base, d, ld, row_index_dev, f, ws->partial, s);
+    else if (f <= 64) rc = launch_gram_shape<4, 16>(grid, rows_base, d, ld, row_index_dev, f, ws->partial, s);
+    else if (f <= 84) rc = launch_gram_shape<6, 21>(grid, rows_base, d, ld, row_index_dev, f, ws->partial, s);
+    else if (f <= 96) rc = launch_gram_shape<6, 24>(grid, rows_base, d, ld, row_index_dev, f, ws->partial, s);
+    else rc = launch_gram_shape<8, 32>(grid, rows_base, d, ld, row_index_dev, f, ws->partial, s);
+    if (rc != BYZ_OK) return rc;
+    const int ntiles = stored_tiles(f);
     gram_reduce_kernel<<<ntiles * kTile / 32, kBlock, 0, s>>>(ws->partial, grid, ntiles, ws->gram);
+    BYZ_HIP(hipGetLastError());
+    return BYZ_OK;
+}
+
+// Sorted distance rows (and Krum scores when n_terms >= 0) from ws->gram.
+int launch_distance_rows(int f, int n_terms, double *dist_out, double *scores_out, KrumWorkspace *ws,
+                         hipStream_t s) {
+    const int row_blocks = (f + kBlock / 64 - 1) / (kBlock / 64);
+    if (f <= 64)
+        distance_rows_kernel<1><<<row_blocks, kBlock, 0, s>>>(ws->gram, f, n_terms, dist_out,
+                                                              ws->sorted_dist, ws->sorted_nbr,
+                                                              ws->scores, scores_out);
+    else
+        distance_rows_kernel<2><<<row_blocks, kBlock, 0, s>>>(ws->gram, f, n_terms, dist_out,
+                                                              ws->sorted_dist, ws->sorted_nbr,
+                                                              ws->scores, scores_out);
     BYZ_HIP(hipGetLastError());
     return BYZ_OK;
 }
@@ -481,8 +583,8 @@ int launch_gram(const float *rows_base, int64_t d, int64_t ld, const int32_t *ro
 }  // namespace
 
 extern "C" size_t byz_multi_krum_workspace_bytes(int f) {
-    if (f < 1 || f > BYZ_MAX_F) return 0;
-    return sizeof(KrumWorkspace);
+    if (f < 1 || f > kMaxKrum) return 0;
+    return krum_workspace_bytes(f);
 }
 
 extern "C" int byz_multi_krum(const float *rows_base, int64_t d, int64_t ld,
@@ -493,21 +595,18 @@ extern "C" int byz_multi_krum(const float *rows_base, int64_t d, int64_t ld,
         workspace == nullptr || (out == nullptr && d > 0))
         return BYZ_EINVAL;
     if (d < 0 || ld < d || d > ((int64_t)1 << 30)) return BYZ_EINVAL;
-    if (f < 3 || f > BYZ_MAX_F || c < 0 || f < 2 * c + 3) return BYZ_EINVAL;  // Sec. 6.1
+    if (f < 3 || f > kMaxKrum || c < 0 || f < 2 * c + 3) return BYZ_EINVAL;  // Sec. 6.1
     if (m < 1 || m > f - c) return BYZ_EINVAL;
     if (((uintptr_t)workspace & 255u) != 0) return BYZ_EINVAL;
-    if (workspace_bytes < sizeof(KrumWorkspace)) return BYZ_ENOMEM;
+    if (workspace_bytes < krum_workspace_bytes(f)) return BYZ_ENOMEM;
     hipStream_t s = (hipStream_t)stream;
     KrumWorkspace *ws = reinterpret_cast<KrumWorkspace *>(workspace);
     int rc = launch_gram(rows_base, d, ld, row_index_dev, f, ws, s);
     if (rc != BYZ_OK) return rc;
-    const int row_blocks = (f + kBlock / 64 - 1) / (kBlock / 64);
-    distance_rows_kernel<<<row_blocks, kBlock, 0, s>>>(ws->gram, f, f - c - 2, dist_out,
-                                                       ws->sorted_dist, ws->sorted_nbr, ws->scores,
-                                                       scores_out);
-    BYZ_HIP(hipGetLastError());
-    krum_select_kernel<<<1, 64, 0, s>>>(ws->scores, f, m, selected_out, ws->selected_list,
-                                        &ws->n_selected);
+    rc = launch_distance_rows(f, f - c - 2, dist_out, scores_out, ws, s);
+    if (rc != BYZ_OK) return rc;
+    krum_select_kernel<<<1, kMaxKrum, 0, s>>>(ws->scores, f, m, selected_out, ws->selected_list,
+                                              &ws->n_selected);
     BYZ_HIP(hipGetLastError());
     if (d > 0) {
         const int64_t n_thr = d >= 4 ? (d + 3) / 4 : d;
@@ -518,7 +617,10 @@ extern "C" int byz_multi_krum(const float *rows_base, int64_t d, int64_t ld,
     return BYZ_OK;
 }
 
-extern "C" size_t byz_bulyan_workspace_bytes(int f) { return byz_multi_krum_workspace_bytes(f); }
+extern "C" size_t byz_bulyan_workspace_bytes(int f) {
+    if (f < 1 || f > BYZ_MAX_F) return 0;
+    return krum_workspace_bytes(f);
+}
 
 extern "C" int byz_bulyan(const float *rows_base, int64_t d, int64_t ld,
                           const int32_t *row_index_dev, int f, int c, float *out,
@@ -531,15 +633,13 @@ extern "C" int byz_bulyan(const float *rows_base, int64_t d, int64_t ld,
     if (f < 3 || f > BYZ_MAX_F || c < 0 || f < 4 * c + 3) return BYZ_EINVAL;  // Sec. 6.1
     if ((f % 2) == 0) return BYZ_EUNSUPPORTED;  // the median of the f - 2c chosen values must be one of them
     if (((uintptr_t)workspace & 255u) != 0) return BYZ_EINVAL;
-    if (workspace_bytes < sizeof(KrumWorkspace)) return BYZ_ENOMEM;
+    if (workspace_bytes < krum_workspace_bytes(f)) return BYZ_ENOMEM;
     hipStream_t s = (hipStream_t)stream;
     KrumWorkspace *ws = reinterpret_cast<KrumWorkspace *>(workspace);
     int rc = launch_gram(rows_base, d, ld, row_index_dev, f, ws, s);
     if (rc != BYZ_OK) return rc;
-    const int row_blocks = (f + kBlock / 64 - 1) / (kBlock / 64);
-    distance_rows_kernel<<<row_blocks, kBlock, 0, s>>>(ws->gram, f, -1, dist_out, ws->sorted_dist,
-                                                       ws->sorted_nbr, ws->scores, nullptr);
-    BYZ_HIP(hipGetLastError());
+    rc = launch_distance_rows(f, -1, dist_out, nullptr, ws, s);
+    if (rc != BYZ_OK) return rc;
     bulyan_select_kernel<<<1, 64, 0, s>>>(ws->sorted_dist, ws->sorted_nbr, f, c, selected_out,
                                           order_out, ws->selected_list, &ws->n_selected,
                                           row_index_dev, ws->selected_rows);

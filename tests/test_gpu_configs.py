@@ -164,6 +164,22 @@ def test_multi_krum_full_size():
     _multi_krum_check(w.X, wrow.cpu().numpy(), w.d, cfg.cmax, w.f - cfg.cmax, cfg.name)
 
 
+def test_multi_krum_81_files():
+    # Multi-Krum over the 81 vote winners of the F_9 cluster (six row tiles in the Gram kernel,
+    # two distances per lane in the row sort), c = c_max = 8, m = f - c = 73; 3,000,001
+    # coordinates (24 chunks per block and a ragged last one) keep the fp64 oracle to seconds
+    from tests.test_gpu_parity import _multi_krum_check
+    cfg = synth.CONFIGS[7]
+    d = 3000001
+    w = W.make(cfg.scheme, cfg.a, cfg.b, cfg.q, d, cfg.attack, cfg.seed, ld=synth.padded_ld(d, 64),
+               device=DEV)
+    assert w.f == 81 and w.cmax == cfg.cmax
+    rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+    _, wrow, _ = B.byz_vote(w.X, w.d, rows_dev, w.f, w.r)
+    torch.cuda.synchronize()
+    _multi_krum_check(w.X, wrow.cpu().numpy(), w.d, cfg.cmax, w.f - cfg.cmax, cfg.name)
+
+
 def test_bulyan_full_size():
     # Bulyan over the vote winners of workload 2 (f = 25, c = c_max = 5: theta = 15, beta = 5)
     # at full size, against the plain-C oracle
