@@ -223,7 +223,7 @@ def main():
             ms_mk = timed_call(lambda: B.byz_multi_krum(bufs[0], d, wrow_v, cmax, mk_m, out=out,
                                                         workspace=mk_ws, stream=stream))
         ms_bu, bu_c = None, min(cmax, (asg.f - 3) // 4)
-        if asg.f <= B.BYZ_MAX_F:
+        if asg.f <= B.BYZ_MAX_F_KRUM:
             ms_bu = timed_call(lambda: B.byz_bulyan(bufs[0], d, wrow_v, bu_c, out=out,
                                                     workspace=mk_ws, stream=stream))
         bb = 4.0 * asg.f * d + 4.0 * (asg.f - 2 * bu_c + 1) * d  # Gram pass + theta rows + output

@@ -52,8 +52,8 @@ typedef enum byz_scheme {
     BYZ_SCHEME_FRC = 2       /* Sec. 5.3.1 (DETOX / DRACO): a = K, b = r | K; f = K/r, l = 1           */
 } byz_scheme;
 
-#define BYZ_MAX_F 64       /* largest f of Bulyan and of the per-thread-array kernels for d < 4          */
-#define BYZ_MAX_F_KRUM 128 /* largest f of Multi-Krum                                                    */
+#define BYZ_MAX_F 64       /* largest f of the kernels that keep a column in a per-thread array (d < 4)  */
+#define BYZ_MAX_F_KRUM 128 /* largest f of Multi-Krum and Bulyan                                         */
 #define BYZ_MAX_F_WIDE 256 /* largest f of byz_vote, byz_median, byz_aggregate and the search            */
 #define BYZ_MAX_R 7  /* largest replication factor                                           */
 
@@ -243,7 +243,7 @@ int byz_multi_krum(const float *rows_base, int64_t d, int64_t ld, const int32_t 
 /*
  * Bulyan over f vectors (named with Multi-Krum in Sec. 6.1 and Sec. 7 as an aggregator for the
  * vote winners; the rule is the published one): with c of the f vectors possibly Byzantine,
- * f >= 4c + 3 (the requirement Sec. 6.1 quotes),
+ * 4c + 3 <= f <= BYZ_MAX_F_KRUM (the lower bound is the requirement Sec. 6.1 quotes),
  *   phase 1: theta = f - 2c vectors are chosen by applying Krum again and again to the vectors
  *            not yet chosen: with n' vectors left, score(i) = sum of the n' - c - 2 smallest
  *            squared distances from i to the other vectors left (no terms when n' - c - 2 <= 0,
@@ -262,7 +262,7 @@ int byz_multi_krum(const float *rows_base, int64_t d, int64_t ld, const int32_t 
  *                 order chosen
  *   dist_out      device [f*f] double out, may be NULL
  *   workspace     device, >= byz_bulyan_workspace_bytes(f) bytes, 256-byte aligned
- * Errors: BYZ_EINVAL (null pointers, f < 4c + 3, f > BYZ_MAX_F, sizes), BYZ_EUNSUPPORTED (even
+ * Errors: BYZ_EINVAL (null pointers, f < 4c + 3, f > BYZ_MAX_F_KRUM, sizes), BYZ_EUNSUPPORTED (even
  * f: the median of the chosen values would not be one of them), BYZ_ENOMEM (workspace too
  * small), BYZ_EDEVICE.
  */

@@ -6,11 +6,18 @@
 void byz_internal_set_hip_error(int code);
 
 // Second phase of Bulyan (kernels.hip): out[c] = mean of the beta values closest to the median
-// among the rows selected_rows_dev[0..theta-1] (a table of BYZ_MAX_F valid row numbers: the
+// among the rows selected_rows_dev[0..theta-1] (a table of BYZ_MAX_F_KRUM valid row numbers: the
 // entries from theta on are read but their values ignored).  Returns a byz_status.
 int byz_internal_launch_bulyan_mean(const float *rows_base, long long d, long long ld,
                                     const int *selected_rows_dev, int f, int theta, int beta,
                                     float *out, void *stream);
+// The same on the 81- and the 121-wire network (kernels.hip, build parts 12 and 13), d >= 4.
+int byz_internal_launch_bulyan_mean_81(const void *X, long long d, long long ld,
+                                       const int *selected_rows, int theta, int beta, void *out,
+                                       void *stream);
+int byz_internal_launch_bulyan_mean_121(const void *X, long long d, long long ld,
+                                        const int *selected_rows, int theta, int beta, void *out,
+                                        void *stream);
 
 // Probe + single-pass kernel for the (f, r) of group n (kernels.hip, part n); the arguments are
 // byz_aggregate_opts' after validation, ws its workspace.  Returns a byz_status.

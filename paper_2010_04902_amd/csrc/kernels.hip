@@ -24,7 +24,8 @@
 // are large: part 0 holds every entry point, the vote and the Bulyan kernels, parts 1..4 one
 // group of single-pass instantiations each (byz_internal_launch_single_pass_<n>; the fifth
 // group is part 7), part 5 the median kernels, part 6 the trimmed-mean kernels, parts 8..11 one
-// 169-wire network kernel each.  Without BYZ_PART the whole library is
+// 169-wire network kernel each, parts 12 and 13 the 81- and 121-wire second phase of Bulyan.
+// Without BYZ_PART the whole library is
 // this one translation unit.
 #ifndef BYZ_PART
 #define BYZ_PART -1
@@ -847,7 +848,7 @@ __global__ __launch_bounds__(kBlock) void bulyan_mean_kernel(
     store_vec<V>(out + c0, o);
 }
 
-// Second phase of Bulyan for theta > 49 and for d < 4: one coordinate a thread, the chosen
+// Second phase of Bulyan for theta > 121 and for d < 4: one coordinate a thread, the chosen
 // values insertion-sorted in the thread's LDS column.  Dynamic LDS: theta*kBlock*4 bytes.
 __global__ __launch_bounds__(kBlock) void bulyan_mean_generic_kernel(
     const uint32_t *__restrict__ X, int64_t d, int64_t ld,
@@ -1268,16 +1269,23 @@ int launch_trimmed_mean(const uint32_t *X, int64_t d, int64_t ld, const int32_t 
 
 #endif  // part 6
 
-#if BYZ_IN_PART(0)
+#if BYZ_IN_PART(0) || BYZ_IN_PART(12) || BYZ_IN_PART(13)
 template <int F>
 int launch_bulyan_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *selected_rows,
                       int theta, int beta, uint32_t *O, hipStream_t s) {
     constexpr int V = vec_for(F);
-    bulyan_mean_kernel<F, V><<<blocks_for((d + V - 1) / V), kBlock, (size_t)F * kBlock * 4, s>>>(
+    constexpr size_t lds = (size_t)F * kBlock * 4;
+    if (lds > 64 * 1024)  // more than a kernel may use without asking
+        BYZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&bulyan_mean_kernel<F, V>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    bulyan_mean_kernel<F, V><<<blocks_for((d + V - 1) / V), kBlock, lds, s>>>(
         X, d, ld, selected_rows, theta, beta, O);
     BYZ_HIP(hipGetLastError());
     return BYZ_OK;
 }
+#endif
+
+#if BYZ_IN_PART(0)
 
 // (f, r) with a compiled single-pass kernel: MOLS / Ramanujan Case 1 (f = l^2: 9, 25, 49) with
 // r = 3 or 5, the Ramanujan Case 2 shapes f = m*s with r = s: (15,3), (21,3), (35,5), and MOLS
@@ -1308,6 +1316,24 @@ int byz_internal_launch_median(const void *X, long long d, long long ld, const i
     return launch_median(static_cast<const uint32_t *>(X), d, ld, row_index, f,
                          static_cast<uint32_t *>(out), static_cast<const uint32_t *>(gate), gate_n,
                          (hipStream_t)stream);
+}
+#endif
+
+// second phase of Bulyan on the 81- and 121-wire networks, a build part each
+#if BYZ_IN_PART(12)
+int byz_internal_launch_bulyan_mean_81(const void *X, long long d, long long ld,
+                                       const int *selected_rows, int theta, int beta, void *out,
+                                       void *stream) {
+    return launch_bulyan_net<81>(static_cast<const uint32_t *>(X), d, ld, selected_rows, theta, beta,
+                                 static_cast<uint32_t *>(out), (hipStream_t)stream);
+}
+#endif
+#if BYZ_IN_PART(13)
+int byz_internal_launch_bulyan_mean_121(const void *X, long long d, long long ld,
+                                        const int *selected_rows, int theta, int beta, void *out,
+                                        void *stream) {
+    return launch_bulyan_net<121>(static_cast<const uint32_t *>(X), d, ld, selected_rows, theta, beta,
+                                  static_cast<uint32_t *>(out), (hipStream_t)stream);
 }
 #endif
 
@@ -1452,7 +1478,7 @@ int byz_internal_launch_bulyan_mean(const float *rows_base, long long d, long lo
                                     const int *selected_rows_dev, int f, int theta, int beta,
                                     float *out, void *stream) {
     if (d == 0) return BYZ_OK;
-    if (f < 1 || f > BYZ_MAX_F || theta < 1 || theta > f || (theta % 2) == 0 || beta < 1 ||
+    if (f < 1 || f > BYZ_MAX_F_KRUM || theta < 1 || theta > f || (theta % 2) == 0 || beta < 1 ||
         beta > theta)
         return BYZ_EINVAL;
     hipStream_t s = (hipStream_t)stream;
@@ -1466,8 +1492,16 @@ int byz_internal_launch_bulyan_mean(const float *rows_base, long long d, long lo
         if (theta <= 25) return launch_bulyan_net<25>(X, d, ld, selected_rows_dev, theta, beta, O, s);
         if (theta <= 35) return launch_bulyan_net<35>(X, d, ld, selected_rows_dev, theta, beta, O, s);
         if (theta <= 49) return launch_bulyan_net<49>(X, d, ld, selected_rows_dev, theta, beta, O, s);
+        if (theta <= 81)
+            return byz_internal_launch_bulyan_mean_81(X, d, ld, selected_rows_dev, theta, beta, O, s);
+        if (theta <= 121)
+            return byz_internal_launch_bulyan_mean_121(X, d, ld, selected_rows_dev, theta, beta, O, s);
     }
-    bulyan_mean_generic_kernel<<<blocks_for(d), kBlock, (size_t)theta * kBlock * 4, s>>>(
+    const size_t lds = (size_t)theta * kBlock * 4;
+    if (lds > 64 * 1024)
+        BYZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&bulyan_mean_generic_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    bulyan_mean_generic_kernel<<<blocks_for(d), kBlock, lds, s>>>(
         X, d, ld, selected_rows_dev, theta, beta, O);
     BYZ_HIP(hipGetLastError());
     return BYZ_OK;

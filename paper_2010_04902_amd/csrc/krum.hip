@@ -469,6 +469,118 @@ __global__ __launch_bounds__(64) void bulyan_select_kernel(const double *__restr
                 terms &= ~(1ull << (63 - __builtin_clzll(terms)));
         }
     }
+    // rows of the chosen vectors for the second phase; the spare entries of the whole table
+    // (the second phase's network may have more wires than this kernel has lanes) repeat the
+    // first one
+    for (int e = i; e < kMaxKrum; e += 64)
+        if (e >= theta) selected_rows[e] = first_row;
+    if (i == 0) *n_selected = theta;
+}
+
+// The same rounds for 64 < f <= kMaxKrum: one block of kMaxKrum threads, thread i = vector i.
+// The sorted rows do not fit registers and stay in LDS ([t*kRowStride + i], read once per
+// position of a walk), a vector's terms are a 128-bit mask, and the winner is the lower of the
+// two waves' winners.  Dynamic LDS: (f-1)*kRowStride doubles, then kMaxKrum*kRowStride bytes.
+__global__ __launch_bounds__(kMaxKrum) void bulyan_select_wide_kernel(
+    const double *__restrict__ sorted_dist, const uint8_t *__restrict__ sorted_nbr, int f, int c,
+    int32_t *selected_out, int32_t *order_out, int32_t *selected_list, int32_t *n_selected,
+    const int32_t *__restrict__ row_index, int32_t *selected_rows) {
+    extern __shared__ double s_rows[];
+    uint8_t *s_pos = reinterpret_cast<uint8_t *>(s_rows + (f - 1) * kRowStride);  // [j*kRowStride + i]
+    __shared__ double s_wave_score[kMaxKrum / 64];
+    __shared__ int s_wave_best[kMaxKrum / 64];
+    __shared__ int32_t s_row_of[kMaxKrum];
+    const int i = threadIdx.x;
+    const int theta = f - 2 * c;
+    if (i < f) selected_out[i] = 0;
+    s_row_of[i] = row_index[i < f ? i : 0];
+    for (int t = 0; t < f - 1; ++t) {
+        if (i < f) {
+            s_rows[t * kRowStride + i] = sorted_dist[t * kRowStride + i];
+            s_pos[sorted_nbr[t * kRowStride + i] * kRowStride + i] = (uint8_t)t;
+        }
+    }
+    __syncthreads();
+    bool left = i < f;  // not chosen yet
+    // the f - c - 2 <= 125 nearest: bits 0..63 in lo, 64.. in hi
+    const int k0 = f - c - 2;
+    uint64_t lo = !left ? 0ull : (k0 >= 64 ? ~0ull : ((1ull << k0) - 1ull));
+    uint64_t hi = !left || k0 <= 64 ? 0ull : ((1ull << (k0 - 64)) - 1ull);
+    int32_t first_row = 0;
+    for (int round = 0; round < theta; ++round) {
+        double score = left ? 0.0 : __builtin_huge_val();
+        for (int t0 = 0; t0 < f - 1; t0 += 8) {
+            const uint64_t rest = t0 < 64 ? ((lo >> t0) | hi) : (hi >> (t0 - 64));
+            if (__builtin_amdgcn_ballot_w64(rest != 0) == 0) break;  // this wave has its terms
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int t = t0 + u;  // the same for the whole block
+                if (t < f - 1) {
+                    const uint64_t word = t < 64 ? lo : hi;
+                    const double x = s_rows[t * kRowStride + i];
+                    score += ((word >> (t & 63)) & 1ull) != 0 ? x : 0.0;
+                }
+            }
+        }
+        int best = i;
+        argmin_exchange<0xB1>(score, best);   // quad_perm [1,0,3,2]: lane ^ 1
+        argmin_exchange<0x4E>(score, best);   // quad_perm [2,3,0,1]: lane ^ 2
+        argmin_exchange<0x141>(score, best);  // row_half_mirror: the other quad of the 8
+        argmin_exchange<0x140>(score, best);  // row_mirror: the other half of the 16
+        double w_score = lane_value(score, 0);
+        int w_best = __builtin_amdgcn_readlane(best, 0);
+#pragma unroll
+        for (int row = 1; row < 4; ++row) {
+            const double r_score = lane_value(score, 16 * row);
+            const int r_best = __builtin_amdgcn_readlane(best, 16 * row);
+            if (r_score < w_score || (r_score == w_score && r_best < w_best)) {
+                w_score = r_score;
+                w_best = r_best;
+            }
+        }
+        if ((i & 63) == 0) {
+            s_wave_score[i >> 6] = w_score;
+            s_wave_best[i >> 6] = w_best;
+        }
+        __syncthreads();
+        best = s_wave_best[0];
+        {
+            double b_score = s_wave_score[0];
+#pragma unroll
+            for (int w = 1; w < kMaxKrum / 64; ++w) {
+                const double o_score = s_wave_score[w];
+                const int o_best = s_wave_best[w];
+                if (o_score < b_score || (o_score == b_score && o_best < best)) {
+                    b_score = o_score;
+                    best = o_best;
+                }
+            }
+        }
+        const int32_t best_row = s_row_of[best];
+        __syncthreads();  // the waves' winners are read before the next round replaces them
+        if (round == 0) first_row = best_row;
+        if (i == 0) {
+            selected_list[round] = best;
+            selected_rows[round] = best_row;
+            selected_out[best] = 1;
+            if (order_out != nullptr) order_out[round] = best;
+        }
+        if (i == best) {
+            left = false;
+            lo = 0;
+            hi = 0;
+        } else if (left) {
+            const int p = s_pos[best * kRowStride + i];
+            const uint64_t bit = 1ull << (p & 63);
+            uint64_t &word = p < 64 ? lo : hi;
+            if ((word & bit) != 0)
+                word &= ~bit;
+            else if (hi != 0)
+                hi &= ~(1ull << (63 - __builtin_clzll(hi)));
+            else if (lo != 0)
+                lo &= ~(1ull << (63 - __builtin_clzll(lo)));
+        }
+    }
     // rows of the chosen vectors for the second phase; the spare entries repeat the first one
     if (i >= theta) selected_rows[i] = first_row;
     if (i == 0) *n_selected = theta;
@@ -514,7 +626,7 @@ struct KrumWorkspace {
     double scores[kMaxKrum];
     uint8_t sorted_nbr[kMaxKrum * kRowStride];  // and the vector it leads to
     int32_t selected_list[kMaxKrum];
-    int32_t selected_rows[BYZ_MAX_F];  // Bulyan: rows of the chosen vectors, spare entries valid
+    int32_t selected_rows[kMaxKrum];  // Bulyan: rows of the chosen vectors, spare entries valid
     int32_t n_selected;
     int32_t pad[63];
     float partial[1];  // [kGramBlocks][tiles of f][256], sized by krum_workspace_bytes
@@ -617,10 +729,7 @@ extern "C" int byz_multi_krum(const float *rows_base, int64_t d, int64_t ld,
     return BYZ_OK;
 }
 
-extern "C" size_t byz_bulyan_workspace_bytes(int f) {
-    if (f < 1 || f > BYZ_MAX_F) return 0;
-    return krum_workspace_bytes(f);
-}
+extern "C" size_t byz_bulyan_workspace_bytes(int f) { return byz_multi_krum_workspace_bytes(f); }
 
 extern "C" int byz_bulyan(const float *rows_base, int64_t d, int64_t ld,
                           const int32_t *row_index_dev, int f, int c, float *out,
@@ -630,7 +739,7 @@ extern "C" int byz_bulyan(const float *rows_base, int64_t d, int64_t ld,
         workspace == nullptr || (out == nullptr && d > 0))
         return BYZ_EINVAL;
     if (d < 0 || ld < d || d > ((int64_t)1 << 30)) return BYZ_EINVAL;
-    if (f < 3 || f > BYZ_MAX_F || c < 0 || f < 4 * c + 3) return BYZ_EINVAL;  // Sec. 6.1
+    if (f < 3 || f > kMaxKrum || c < 0 || f < 4 * c + 3) return BYZ_EINVAL;  // Sec. 6.1
     if ((f % 2) == 0) return BYZ_EUNSUPPORTED;  // the median of the f - 2c chosen values must be one of them
     if (((uintptr_t)workspace & 255u) != 0) return BYZ_EINVAL;
     if (workspace_bytes < krum_workspace_bytes(f)) return BYZ_ENOMEM;
@@ -640,9 +749,18 @@ extern "C" int byz_bulyan(const float *rows_base, int64_t d, int64_t ld,
     if (rc != BYZ_OK) return rc;
     rc = launch_distance_rows(f, -1, dist_out, nullptr, ws, s);
     if (rc != BYZ_OK) return rc;
-    bulyan_select_kernel<<<1, 64, 0, s>>>(ws->sorted_dist, ws->sorted_nbr, f, c, selected_out,
-                                          order_out, ws->selected_list, &ws->n_selected,
-                                          row_index_dev, ws->selected_rows);
+    if (f <= BYZ_MAX_F) {
+        bulyan_select_kernel<<<1, 64, 0, s>>>(ws->sorted_dist, ws->sorted_nbr, f, c, selected_out,
+                                              order_out, ws->selected_list, &ws->n_selected,
+                                              row_index_dev, ws->selected_rows);
+    } else {
+        const size_t lds = (size_t)(f - 1) * kRowStride * sizeof(double) + (size_t)kMaxKrum * kRowStride;
+        BYZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&bulyan_select_wide_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        bulyan_select_wide_kernel<<<1, kMaxKrum, lds, s>>>(
+            ws->sorted_dist, ws->sorted_nbr, f, c, selected_out, order_out, ws->selected_list,
+            &ws->n_selected, row_index_dev, ws->selected_rows);
+    }
     BYZ_HIP(hipGetLastError());
     const int theta = f - 2 * c;
     return byz_internal_launch_bulyan_mean(rows_base, d, ld, ws->selected_rows, f, theta,

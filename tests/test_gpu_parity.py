@@ -763,13 +763,14 @@ def test_random_shapes_sizes_and_layouts():
 
 
 def test_multi_krum_and_bulyan_for_every_f():
-    # every f from 3 to 64 and a spread of the wider ones Multi-Krum takes (all tile counts and
-    # staging shapes of the Gram kernel, one and two distances per lane in the row sort, every
-    # network size of Bulyan's second phase incl. the spare-wire cases), random d, row pitch, c
-    # and m; per-row scales keep the scores apart, so selections are compared exactly
+    # every f from 3 to 64 and a spread of the wider ones (all tile counts and staging shapes of
+    # the Gram kernel, one and two distances per lane in the row sort, Bulyan's rounds in
+    # registers and in LDS, every network size of its second phase incl. the spare-wire cases
+    # and the sorted-column kernel past 121), random d, row pitch, c and m; per-row scales keep
+    # the scores apart, so selections are compared exactly
     rng = np.random.default_rng(64)
     compared = []
-    for f in list(range(3, 65)) + [65, 66, 80, 81, 84, 85, 96, 97, 112, 113, 121, 127, 128]:
+    for f in list(range(3, 65)) + [65, 66, 80, 81, 84, 85, 96, 97, 112, 113, 121, 123, 127, 128]:
         d = int(rng.choice([rng.integers(1, 10), rng.integers(10, 600), rng.integers(600, 40000)]))
         ld = d + int(rng.integers(0, 6))
         Xh = np.zeros((f + 2, ld), dtype=np.float32)
@@ -781,14 +782,14 @@ def test_multi_krum_and_bulyan_for_every_f():
         X = torch.tensor(Xh, device=DEV)
         m = int(rng.integers(1, f - c + 1))
         _multi_krum_check(X, idx, d, c, m, (f, d, ld, c, m))
-        if f % 2 == 1 and f <= B.BYZ_MAX_F:
+        if f % 2 == 1:
             cb = int(rng.integers(0, (f - 3) // 4 + 1))
             compared.append(_bulyan_check(X, idx, d, cb, (f, d, ld, cb)))
     assert sum(compared) >= len(compared) - 2, compared
-    # one vector too many for each of the two
+    # one vector too many
     X = torch.zeros((B.BYZ_MAX_F_KRUM + 1, 8), device=DEV)
-    for call, n in ((lambda i: B.byz_multi_krum(X, 8, i, 1, 1), B.BYZ_MAX_F_KRUM + 1),
-                    (lambda i: B.byz_bulyan(X, 8, i, 1), B.BYZ_MAX_F + 1)):
+    too_many = torch.arange(B.BYZ_MAX_F_KRUM + 1, dtype=torch.int32, device=DEV)
+    for call in (lambda: B.byz_multi_krum(X, 8, too_many, 1, 1), lambda: B.byz_bulyan(X, 8, too_many, 1)):
         with pytest.raises(B.ByzError) as e:
-            call(torch.arange(n, dtype=torch.int32, device=DEV))
+            call()
         assert e.value.code == -1
