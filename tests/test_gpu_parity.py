@@ -606,6 +606,18 @@ def test_bulyan_ties_and_identical_vectors():
     Y = torch.tensor(np.repeat(vals[:, None], 16, axis=1), device=DEV)
     assert _bulyan_check(Y, np.arange(15, dtype=np.int32), 16, 2, "integer ties", exact_order=True)
     assert _bulyan_check(Y, np.arange(15, dtype=np.int32), 16, 3, "integer ties", exact_order=True)
+    # the same two situations past 64 vectors (rounds on rows in LDS, winner across two waves)
+    f = 81
+    X = base.repeat(f, 1).contiguous()
+    out, sel, order, dist = B.byz_bulyan(X, d, torch.arange(f, dtype=torch.int32, device=DEV), 10)
+    torch.cuda.synchronize()
+    assert order.cpu().tolist() == list(range(f - 20)) and (dist == 0).all()
+    assert (out - base[0]).abs().max().item() <= 41 * 2.0 ** -24 * base.abs().max().item()
+    rng = np.random.default_rng(85)
+    vals = rng.permutation(np.arange(-42, 43)).astype(np.float32)  # 85 distinct integers
+    Y = torch.tensor(np.repeat(vals[:, None], 16, axis=1), device=DEV)
+    for c in (0, 3, 20):
+        assert _bulyan_check(Y, np.arange(85, dtype=np.int32), 16, c, ("integer ties", c), exact_order=True)
 
 
 def _tolerant_check(X, rows_np, d, f, r, atol, rtol, tag):
