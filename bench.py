@@ -226,6 +226,19 @@ def main():
         if asg.f <= B.BYZ_MAX_F_KRUM:
             ms_bu = timed_call(lambda: B.byz_bulyan(bufs[0], d, wrow_v, bu_c, out=out,
                                                     workspace=mk_ws, stream=stream))
+        # the path taken when the single pass finds its assumption violated: one word of one honest
+        # copy (not the first of its file) differs at a coordinate the probe does not sample
+        ms_exact, exact_taken = None, False
+        if B.byz_aggregate_has_single_pass(asg.f, asg.r) and d > 1000:
+            clean = [j for j in range(asg.f) if not any(int(w) in set(int(b) for b in byz) for w in fw[j])]
+            if clean:
+                planted = bufs[0].clone()
+                planted[int(rows[clean[0], 1]), d // 2 + 7] += 1.0
+                ms_exact = timed_call(lambda: B.byz_aggregate_opts(planted, d, rows_dev, asg.f, asg.r, 0,
+                                                                   out=out, winner_replica=wrep,
+                                                                   workspace=ws, stream=stream))
+                exact_taken = bool(B.byz_aggregate_took_exact_path(ws))
+                del planted
         bb = 4.0 * asg.f * d + 4.0 * (asg.f - 2 * bu_c + 1) * d  # Gram pass + theta rows + output
         kb = 4.0 * asg.f * d + 4.0 * (mk_m + 1) * d  # Gram pass over f rows + mean of m rows
         vb, mb = 4.0 * asg.r * asg.f * d, 4.0 * (asg.f + 1) * d
@@ -243,6 +256,13 @@ def main():
                                            "gbps": alg_bytes / ms_agg_tm / 1e6,
                                            "frac": alg_bytes / ms_agg_tm / 1e6 / HBM_PEAK_GBPS,
                                            "note": "whole path with the trimmed mean instead of the median"},
+            "byz_aggregate_exact_path": None if ms_exact is None else {
+                "ms": ms_exact, "took_exact_path": exact_taken,
+                "algorithmic_bytes": alg_bytes + vb + mb,
+                "gbps": (alg_bytes + vb + mb) / ms_exact / 1e6,
+                "frac": (alg_bytes + vb + mb) / ms_exact / 1e6 / HBM_PEAK_GBPS,
+                "note": "one planted difference outside the probe's sample: single pass, then the "
+                        "vote over all copies and the median of the winners"},
             "byz_multi_krum": None if ms_mk is None else {
                 "ms": ms_mk, "c": cmax, "m": mk_m, "algorithmic_bytes": kb,
                 "gbps": kb / ms_mk / 1e6, "frac": kb / ms_mk / 1e6 / HBM_PEAK_GBPS,

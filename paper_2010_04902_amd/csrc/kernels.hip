@@ -193,17 +193,6 @@ __device__ __forceinline__ void merge_flags(uint32_t *words, int f, int lane, ui
     }
 }
 
-// True in every thread of exactly one block of the grid: the one that finishes last.  Each
-// block calls it once, after all its global updates; `ticket` must be 0 at launch.
-__device__ __forceinline__ bool last_block_done(uint32_t *ticket) {
-    __shared__ uint32_t s_last;
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) s_last = (atomicAdd(ticket, 1u) == gridDim.x - 1) ? 1u : 0u;
-    __syncthreads();
-    return s_last != 0;
-}
-
 // ------------------------------------------------------------------- selection networks
 
 #define BYZ_CE(i, j)                                   \
@@ -296,7 +285,6 @@ struct AggWorkspace {
     int32_t winner_row[kWide];       // exact path result
     uint32_t need_exact;             // 1 iff the exact path ran
     uint32_t slots_per_file;         // slots of every file the single pass reads: r or r'
-    uint32_t ticket_vote;            // blocks of the exact-path vote kernel that have finished
     uint32_t pad[61];
 };
 
@@ -311,7 +299,6 @@ __global__ void reset_workspace_kernel(AggWorkspace *ws, uint32_t need_exact) {
     }
     if (i == 0) {
         ws->need_exact = need_exact;
-        ws->ticket_vote = 0;
     }
 }
 
@@ -348,26 +335,35 @@ __global__ void vote_decide_kernel(const uint32_t *pair_neq, const int32_t *__re
     decide_files(pair_neq, file_rows, f, r, winner_replica, winner_row);
 }
 
+// The decision of the exact path behind the single pass (one block): if none of gate[0..f-1]
+// is set the single pass stands and its probable winners (gate_off_winner) are published as
+// the winners; otherwise the winners come from the pair bits the gated vote kernel just
+// collected, and took_exact records that the exact path ran.  (A kernel of its own rather
+// than the last block of the vote kernel: finding that block takes a device-wide fence in
+// every block, which made the vote five times slower.)
+__global__ void vote_decide_gated_kernel(const uint32_t *pair_neq,
+                                         const int32_t *__restrict__ file_rows, int f, int r,
+                                         const uint32_t *__restrict__ gate,
+                                         const int32_t *__restrict__ gate_off_winner,
+                                         int32_t *winner_replica, int32_t *winner_row,
+                                         uint32_t *took_exact) {
+    if (!any_word_set(gate, f)) {
+        if ((int)threadIdx.x < f && winner_replica != nullptr)
+            winner_replica[threadIdx.x] = gate_off_winner[threadIdx.x];
+        return;
+    }
+    if (threadIdx.x == 0) *took_exact = 1;
+    decide_files(pair_neq, file_rows, f, r, winner_replica, winner_row);
+}
+
 // Vote, comparison: for every file, which pairs of copies differ anywhere in [0, d).  Threads own
 // vectors of V words; the d % V trailing words go to the first threads of the last block.
-// If `ticket` is given (zero at launch), the block
-// that finishes last also takes the decision.  If `gate` is given, the kernel only runs when one of
-// gate[0..f-1] is nonzero; otherwise it publishes gate_off_winner as the winners and returns.
+// If `gate` is given, the kernel only runs when one of gate[0..f-1] is nonzero.
 template <int R, int V>
 __global__ __launch_bounds__(kBlock) void vote_pairs_kernel(
     const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ file_rows,
-    int f, uint32_t *pair_neq, const uint32_t *__restrict__ gate, uint32_t *ticket,
-    int32_t *winner_replica, int32_t *winner_row, const int32_t *__restrict__ gate_off_winner,
-    uint32_t *took_exact) {
-    if (gate != nullptr) {
-        if (!any_word_set(gate, f)) {
-            // nothing to redo: the single pass stands, its probable winners are final
-            if (blockIdx.x == 0 && (int)threadIdx.x < f && winner_replica != nullptr)
-                winner_replica[threadIdx.x] = gate_off_winner[threadIdx.x];
-            return;
-        }
-        if (blockIdx.x == 0 && threadIdx.x == 0) *took_exact = 1;
-    }
+    int f, uint32_t *pair_neq, const uint32_t *__restrict__ gate) {
+    if (gate != nullptr && !any_word_set(gate, f)) return;
     const int lane = threadIdx.x & 63;
     const int64_t n_vec = d / V;
     const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
@@ -410,8 +406,6 @@ __global__ __launch_bounds__(kBlock) void vote_pairs_kernel(
             if (bits != 0) atomicOr(&pair_neq[j], bits);
         }
     }
-    if (ticket != nullptr && last_block_done(ticket))
-        decide_files(pair_neq, file_rows, f, R, winner_replica, winner_row);
 }
 
 // Nonzero iff some word of the two chunks is not close: bit patterns differ and
@@ -895,7 +889,6 @@ __global__ __launch_bounds__(kProbeThreads) void probe_kernel(const uint32_t *__
     if (tid == 0) {
         s_all_majority = 1;
         ws->need_exact = 0;
-        ws->ticket_vote = 0;
     }
     __syncthreads();
 
@@ -1060,30 +1053,18 @@ inline unsigned blocks_for(int64_t n_vec) {
 #if BYZ_IN_PART(0)
 template <int R>
 int launch_vote_pairs(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, int f,
-                      uint32_t *neq, const uint32_t *gate, uint32_t *ticket,
-                      int32_t *winner_replica, int32_t *winner_row, const int32_t *gate_off_winner,
-                      uint32_t *took_exact, hipStream_t s) {
-    vote_pairs_kernel<R, kVec><<<blocks_for(d / kVec), kBlock, 0, s>>>(
-        X, d, ld, rows, f, neq, gate, ticket, winner_replica, winner_row, gate_off_winner,
-        took_exact);
+                      uint32_t *neq, const uint32_t *gate, hipStream_t s) {
+    vote_pairs_kernel<R, kVec><<<blocks_for(d / kVec), kBlock, 0, s>>>(X, d, ld, rows, f, neq, gate);
     BYZ_HIP(hipGetLastError());
     return BYZ_OK;
 }
 
 int launch_vote_pairs_r(int r, const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows,
-                        int f, uint32_t *neq, const uint32_t *gate, uint32_t *ticket,
-                        int32_t *winner_replica, int32_t *winner_row,
-                        const int32_t *gate_off_winner, uint32_t *took_exact, hipStream_t s) {
+                        int f, uint32_t *neq, const uint32_t *gate, hipStream_t s) {
     switch (r) {
-        case 3:
-            return launch_vote_pairs<3>(X, d, ld, rows, f, neq, gate, ticket, winner_replica,
-                                        winner_row, gate_off_winner, took_exact, s);
-        case 5:
-            return launch_vote_pairs<5>(X, d, ld, rows, f, neq, gate, ticket, winner_replica,
-                                        winner_row, gate_off_winner, took_exact, s);
-        case 7:
-            return launch_vote_pairs<7>(X, d, ld, rows, f, neq, gate, ticket, winner_replica,
-                                        winner_row, gate_off_winner, took_exact, s);
+        case 3: return launch_vote_pairs<3>(X, d, ld, rows, f, neq, gate, s);
+        case 5: return launch_vote_pairs<5>(X, d, ld, rows, f, neq, gate, s);
+        case 7: return launch_vote_pairs<7>(X, d, ld, rows, f, neq, gate, s);
         default: return BYZ_EINVAL;
     }
 }
@@ -1523,8 +1504,7 @@ extern "C" int byz_vote(const float *copies, int64_t d, int64_t ld, const int32_
     fill_u32_kernel<<<1, kWide, 0, s>>>(pair_neq, f, 0u);
     BYZ_HIP(hipGetLastError());
     if (d > 0) {
-        rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, pair_neq, nullptr, nullptr,
-                                 nullptr, nullptr, nullptr, nullptr, s);
+        rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, pair_neq, nullptr, s);
         if (rc != BYZ_OK) return rc;
     }
     vote_decide_kernel<<<1, kWide, 0, s>>>(pair_neq, file_rows_dev, f, r, winner_replica,
@@ -1609,15 +1589,13 @@ extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
 
     // (the 169-file single pass is built for the median only)
     if (!has_fused(f, r) || d < kVec || (f == 169 && trim_b >= 0)) {
-        // two-step path, unconditionally: vote (a1, a2), then median (a3) over the winners
+        // two-step path, unconditionally: vote, then median over the winners
         reset_workspace_kernel<<<1, kWide, 0, s>>>(ws, 1u);
         BYZ_HIP(hipGetLastError());
-        // (no last-block ticket here: its per-block fence costs more than a third launch)
         if (d > 0) {
             rc = byz_internal_profile_mark(0, s);
             if (rc != BYZ_OK) return rc;
-            rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, nullptr, nullptr,
-                                     nullptr, nullptr, nullptr, nullptr, s);
+            rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, nullptr, s);
             if (rc != BYZ_OK) return rc;
             rc = byz_internal_profile_mark(1, s);
             if (rc != BYZ_OK) return rc;
@@ -1631,7 +1609,7 @@ extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
         return byz_internal_launch_median(X, d, ld, ws->winner_row, f, O, nullptr, 0, s);
     }
 
-    // probe -> single pass -> exact path, whose two kernels return at once unless the single
+    // probe -> single pass -> exact path, whose three kernels return at once unless the single
     // pass recorded a violated assumption
     if (f == 169)
         rc = byz_internal_launch_single_pass_5(f, r, X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
@@ -1644,10 +1622,12 @@ extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
     else
         rc = byz_internal_launch_single_pass_1(f, r, X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
     if (rc != BYZ_OK) return rc;
-    rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, ws->viol,
-                             &ws->ticket_vote, winner_replica, ws->winner_row, ws->prov_winner,
-                             &ws->need_exact, s);
+    rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, ws->viol, s);
     if (rc != BYZ_OK) return rc;
+    vote_decide_gated_kernel<<<1, kWide, 0, s>>>(ws->pair_neq, file_rows_dev, f, r, ws->viol,
+                                                 ws->prov_winner, winner_replica, ws->winner_row,
+                                                 &ws->need_exact);
+    BYZ_HIP(hipGetLastError());
     if (trim_b >= 0)
         return byz_internal_launch_trimmed_mean(X, d, ld, ws->winner_row, f, trim_b, O, ws->viol, f,
                                                 s);
