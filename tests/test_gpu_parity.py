@@ -684,10 +684,11 @@ def test_tolerant_vote_special_values_and_errors():
     assert (wrep == 0).all() and (far == 0).all()
 
 
-@pytest.mark.parametrize("l", [5, 7])
+@pytest.mark.parametrize("l", [5, 7, 9])
 def test_hip_graph_capture_of_the_other_entry_points(l):
     # vote (exact and tolerant), trimmed mean, Multi-Krum and Bulyan also enqueue kernels only;
-    # f = 49 uses the Gram kernel that asks for more than 64 KiB of LDS
+    # f = 49 uses the Gram kernel that asks for more than 64 KiB of LDS, f = 81 the wide
+    # selection kernels and the 81-wire second phase of Bulyan, which do so too
     w = W.make(MOLS, l, 3, 3, 50_001, dict(REVERSED, file_scales=True), seed=14, device=DEV)
     rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
     c = 2
