@@ -802,16 +802,17 @@ __device__ __forceinline__ float mean_around_median(const float *col, int stride
 // N - theta spare wires load whatever valid row the table names and are tied to the largest
 // key, so wires 0..theta-1
 // end up holding the chosen values in ascending order.  They go to an LDS column of the thread
-// (word i*kBlock + thread: conflict-free), where the window around the median is found with
+// (word i*BLOCK + thread: conflict-free), where the window around the median is found with
 // run-time indices.  Thread t owns the words from min(V*t, d - V); needs d >= V.
-// Dynamic LDS: N*kBlock*4 bytes.
-template <int F, int V>
-__global__ __launch_bounds__(kBlock) void bulyan_mean_kernel(
+// Dynamic LDS: N*BLOCK*4 bytes; the widest networks run one wave a block, so that several
+// blocks' columns fit a CU and the number of waves is again what the registers allow.
+template <int F, int V, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void bulyan_mean_kernel(
     const uint32_t *__restrict__ X, int64_t d, int64_t ld,
     const int32_t *__restrict__ selected_rows, int theta, int beta, uint32_t *__restrict__ out) {
     extern __shared__ float s_bulyan_col[];
     const int64_t n_thr = (d + V - 1) / V;
-    const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t gt = (int64_t)blockIdx.x * BLOCK + threadIdx.x;
     if (gt >= n_thr) return;
     const int64_t c0 = gt * V + V <= d ? gt * V : d - V;
     uint32_t key[V][F];
@@ -836,8 +837,8 @@ __global__ __launch_bounds__(kBlock) void bulyan_mean_kernel(
 #pragma unroll
     for (int v = 0; v < V; ++v) {
 #pragma unroll
-        for (int i = 0; i < F; ++i) col[i * kBlock] = __uint_as_float(from_key(key[v][i]));
-        o[v] = __float_as_uint(mean_around_median(col, kBlock, theta, beta));
+        for (int i = 0; i < F; ++i) col[i * BLOCK] = __uint_as_float(from_key(key[v][i]));
+        o[v] = __float_as_uint(mean_around_median(col, BLOCK, theta, beta));
     }
     store_vec<V>(out + c0, o);
 }
@@ -1255,11 +1256,11 @@ template <int F>
 int launch_bulyan_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *selected_rows,
                       int theta, int beta, uint32_t *O, hipStream_t s) {
     constexpr int V = vec_for(F);
-    constexpr size_t lds = (size_t)F * kBlock * 4;
-    if (lds > 64 * 1024)  // more than a kernel may use without asking
-        BYZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&bulyan_mean_kernel<F, V>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    bulyan_mean_kernel<F, V><<<blocks_for((d + V - 1) / V), kBlock, lds, s>>>(
+    constexpr int BLOCK = F > 49 ? 64 : kBlock;
+    constexpr size_t lds = (size_t)F * BLOCK * 4;
+    static_assert(lds <= 64 * 1024, "more than a kernel may use without asking");
+    const int64_t n_thr = (d + V - 1) / V;
+    bulyan_mean_kernel<F, V, BLOCK><<<(unsigned)((n_thr + BLOCK - 1) / BLOCK), BLOCK, lds, s>>>(
         X, d, ld, selected_rows, theta, beta, O);
     BYZ_HIP(hipGetLastError());
     return BYZ_OK;
