@@ -316,6 +316,13 @@ int byz_aggregate(const float *copies, int64_t d, int64_t ld, const int32_t *fil
  *     contract.  May be combined with BYZ_AGG_EARLY_MAJORITY. */
 #define BYZ_AGG_TRIMMED_MEAN 2u
 #define BYZ_AGG_TRIM(b) (BYZ_AGG_TRIMMED_MEAN | ((unsigned)(b) << 8))
+/*   BYZ_AGG_PROBE_SHIFT(s)  moves the <= 256 coordinates on which the single pass first compares
+ *     the copies of a file (16 runs of 16 words, evenly spaced from a start that s, 0..65535,
+ *     picks).  The output never depends on it.  The time can: copies that agree on the sampled
+ *     coordinates and differ elsewhere make byz_aggregate redo the vote over all copies (about
+ *     2.2 times the time), and workers who know where the sample lies could send such copies
+ *     on purpose; a caller who draws s afresh for every call takes that knowledge away. */
+#define BYZ_AGG_PROBE_SHIFT(s) (((unsigned)(s) & 0xFFFFu) << 16)
 int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld, const int32_t *file_rows_dev,
                        int f, int r, float *out, int32_t *winner_replica, void *workspace,
                        size_t workspace_bytes, unsigned flags, void *stream);

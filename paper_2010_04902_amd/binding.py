@@ -328,6 +328,11 @@ def BYZ_AGG_TRIM(b):
     return BYZ_AGG_TRIMMED_MEAN | (int(b) << 8)
 
 
+def BYZ_AGG_PROBE_SHIFT(s):
+    """Flag value that moves the single pass's probe sample (s in 0..65535); see byzshield.h."""
+    return (int(s) & 0xFFFF) << 16
+
+
 def byz_aggregate_opts(copies, d, file_rows_dev, f, r, flags, out=None, winner_replica=None,
                        workspace=None, stream=None):
     """byz_aggregate with option flags (BYZ_AGG_EARLY_MAJORITY); same returns."""

@@ -20,11 +20,12 @@ int byz_internal_launch_bulyan_mean_121(const void *X, long long d, long long ld
                                         void *stream);
 
 // Probe + single-pass kernel for the (f, r) of group n (kernels.hip, part n); the arguments are
-// byz_aggregate_opts' after validation, ws its workspace.  Returns a byz_status.
+// byz_aggregate_opts' after validation, ws its workspace; probe_opts: bit 0 early-majority mode,
+// bits 16..31 the shift of the probe's sample.  Returns a byz_status.
 #define BYZ_DECLARE_SINGLE_PASS(n)                                                              \
     int byz_internal_launch_single_pass_##n(int f, int r, const void *X, long long d,           \
                                             long long ld, const int *rows, void *ws, void *out, \
-                                            int early, int trim_b, void *stream)
+                                            int probe_opts, int trim_b, void *stream)
 BYZ_DECLARE_SINGLE_PASS(1);
 BYZ_DECLARE_SINGLE_PASS(2);
 BYZ_DECLARE_SINGLE_PASS(3);

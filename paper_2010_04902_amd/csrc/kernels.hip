@@ -876,7 +876,9 @@ template <int F, int R>
 __global__ __launch_bounds__(kProbeThreads) void probe_kernel(const uint32_t *__restrict__ X,
                                                            int64_t d, int64_t ld,
                                                            const int32_t *__restrict__ file_rows,
-                                                           AggWorkspace *ws, int early_majority) {
+                                                           AggWorkspace *ws, int probe_opts) {
+    const int early_majority = probe_opts & 1;        // bit 0: early-majority mode
+    const uint32_t shift = (uint32_t)probe_opts >> 16;  // bits 16..31: moves the sample
     __shared__ uint32_t s_neq[kWide];
     __shared__ uint32_t s_all_majority;
     const int tid = threadIdx.x;
@@ -900,8 +902,11 @@ __global__ __launch_bounds__(kProbeThreads) void probe_kernel(const uint32_t *__
     if (d <= kProbe) {
         if (ct < d) c = ct;
     } else {
+        // runs start (d - 16) / 15 apart from a point the caller's shift picks, wrapping
+        // around so that a run stays inside [0, d)
         const int64_t run = ct >> 4, off = ct & 15;
-        c = run * ((d - 16) / (kProbe / 16 - 1)) + off;
+        const uint64_t start = ((uint64_t)shift * 2654435761ull) % (uint64_t)(d - 15);
+        c = (int64_t)(((uint64_t)(run * ((d - 16) / (kProbe / 16 - 1))) + start) % (uint64_t)(d - 15)) + off;
     }
     // this group's files in batches of G: all loads of a batch are issued before the first
     // ballot waits; the bits of file j are parked in lane j % 64, word j / 64
@@ -1177,9 +1182,9 @@ int launch_median(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_i
 // trimmed-mean requests down the two-kernel path)
 template <int F, int R, bool WITH_TRIM = true>
 int launch_fused(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, AggWorkspace *ws,
-                 uint32_t *out, int early_majority, int trim_b, hipStream_t s) {
+                 uint32_t *out, int probe_opts, int trim_b, hipStream_t s) {
     if (!WITH_TRIM && trim_b >= 0) return BYZ_EINTERNAL;
-    probe_kernel<F, R><<<1, kProbeThreads, 0, s>>>(X, d, ld, rows, ws, early_majority);
+    probe_kernel<F, R><<<1, kProbeThreads, 0, s>>>(X, d, ld, rows, ws, probe_opts);
     BYZ_HIP(hipGetLastError());
     int rc = byz_internal_profile_mark(0, s);
     if (rc != BYZ_OK) return rc;
@@ -1374,68 +1379,68 @@ int byz_internal_launch_trimmed_mean(const void *X, long long d, long long ld,
 
 #if BYZ_IN_PART(1)
 int byz_internal_launch_single_pass_1(int f, int r, const void *X, long long d, long long ld,
-                                      const int *rows, void *ws, void *out, int early, int trim_b,
+                                      const int *rows, void *ws, void *out, int probe_opts, int trim_b,
                                       void *stream) {
     const uint32_t *x = static_cast<const uint32_t *>(X);
     AggWorkspace *w = static_cast<AggWorkspace *>(ws);
     uint32_t *o = static_cast<uint32_t *>(out);
     hipStream_t s = (hipStream_t)stream;
-    if (f == 9 && r == 3) return launch_fused<9, 3>(x, d, ld, rows, w, o, early, trim_b, s);
-    if (f == 15 && r == 3) return launch_fused<15, 3>(x, d, ld, rows, w, o, early, trim_b, s);
-    if (f == 21 && r == 3) return launch_fused<21, 3>(x, d, ld, rows, w, o, early, trim_b, s);
-    if (f == 25 && r == 3) return launch_fused<25, 3>(x, d, ld, rows, w, o, early, trim_b, s);
-    if (f == 25 && r == 5) return launch_fused<25, 5>(x, d, ld, rows, w, o, early, trim_b, s);
-    if (f == 35 && r == 5) return launch_fused<35, 5>(x, d, ld, rows, w, o, early, trim_b, s);
+    if (f == 9 && r == 3) return launch_fused<9, 3>(x, d, ld, rows, w, o, probe_opts, trim_b, s);
+    if (f == 15 && r == 3) return launch_fused<15, 3>(x, d, ld, rows, w, o, probe_opts, trim_b, s);
+    if (f == 21 && r == 3) return launch_fused<21, 3>(x, d, ld, rows, w, o, probe_opts, trim_b, s);
+    if (f == 25 && r == 3) return launch_fused<25, 3>(x, d, ld, rows, w, o, probe_opts, trim_b, s);
+    if (f == 25 && r == 5) return launch_fused<25, 5>(x, d, ld, rows, w, o, probe_opts, trim_b, s);
+    if (f == 35 && r == 5) return launch_fused<35, 5>(x, d, ld, rows, w, o, probe_opts, trim_b, s);
     return BYZ_EINTERNAL;
 }
 #endif
 
 #if BYZ_IN_PART(2)
 int byz_internal_launch_single_pass_2(int f, int r, const void *X, long long d, long long ld,
-                                      const int *rows, void *ws, void *out, int early, int trim_b,
+                                      const int *rows, void *ws, void *out, int probe_opts, int trim_b,
                                       void *stream) {
     const uint32_t *x = static_cast<const uint32_t *>(X);
     AggWorkspace *w = static_cast<AggWorkspace *>(ws);
     uint32_t *o = static_cast<uint32_t *>(out);
     hipStream_t s = (hipStream_t)stream;
-    if (f == 49 && r == 3) return launch_fused<49, 3>(x, d, ld, rows, w, o, early, trim_b, s);
-    if (f == 49 && r == 5) return launch_fused<49, 5>(x, d, ld, rows, w, o, early, trim_b, s);
+    if (f == 49 && r == 3) return launch_fused<49, 3>(x, d, ld, rows, w, o, probe_opts, trim_b, s);
+    if (f == 49 && r == 5) return launch_fused<49, 5>(x, d, ld, rows, w, o, probe_opts, trim_b, s);
     return BYZ_EINTERNAL;
 }
 #endif
 
 #if BYZ_IN_PART(3)
 int byz_internal_launch_single_pass_3(int f, int r, const void *X, long long d, long long ld,
-                                      const int *rows, void *ws, void *out, int early, int trim_b,
+                                      const int *rows, void *ws, void *out, int probe_opts, int trim_b,
                                       void *stream) {
     if (f == 81 && r == 3)
         return launch_fused<81, 3>(static_cast<const uint32_t *>(X), d, ld, rows,
                                    static_cast<AggWorkspace *>(ws), static_cast<uint32_t *>(out),
-                                   early, trim_b, (hipStream_t)stream);
+                                   probe_opts, trim_b, (hipStream_t)stream);
     return BYZ_EINTERNAL;
 }
 #endif
 
 #if BYZ_IN_PART(4)
 int byz_internal_launch_single_pass_4(int f, int r, const void *X, long long d, long long ld,
-                                      const int *rows, void *ws, void *out, int early, int trim_b,
+                                      const int *rows, void *ws, void *out, int probe_opts, int trim_b,
                                       void *stream) {
     if (f == 121 && r == 3)
         return launch_fused<121, 3>(static_cast<const uint32_t *>(X), d, ld, rows,
                                     static_cast<AggWorkspace *>(ws), static_cast<uint32_t *>(out),
-                                    early, trim_b, (hipStream_t)stream);
+                                    probe_opts, trim_b, (hipStream_t)stream);
     return BYZ_EINTERNAL;
 }
 #endif
 
 #if BYZ_IN_PART(7)
 int byz_internal_launch_single_pass_5(int f, int r, const void *X, long long d, long long ld,
-                                      const int *rows, void *ws, void *out, int early, int trim_b,
+                                      const int *rows, void *ws, void *out, int probe_opts, int trim_b,
                                       void *stream) {
     if (f == 169 && r == 3)
         return launch_fused<169, 3, false>(static_cast<const uint32_t *>(X), d, ld, rows,
                                     static_cast<AggWorkspace *>(ws), static_cast<uint32_t *>(out),
-                                    early, trim_b, (hipStream_t)stream);
+                                    probe_opts, trim_b, (hipStream_t)stream);
     return BYZ_EINTERNAL;
 }
 #endif
@@ -1570,9 +1575,10 @@ extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
                                   const int32_t *file_rows_dev, int f, int r, float *out,
                                   int32_t *winner_replica, void *workspace, size_t workspace_bytes,
                                   unsigned flags, void *stream) {
-    if ((flags & ~(unsigned)(BYZ_AGG_EARLY_MAJORITY | BYZ_AGG_TRIMMED_MEAN | 0xFF00u)) != 0)
+    if ((flags & ~(unsigned)(BYZ_AGG_EARLY_MAJORITY | BYZ_AGG_TRIMMED_MEAN | 0xFFFFFF00u)) != 0)
         return BYZ_EINVAL;
-    const int early = (flags & BYZ_AGG_EARLY_MAJORITY) != 0 ? 1 : 0;
+    // what the probe needs to know: bit 0 early-majority mode, bits 16..31 the sample shift
+    const int probe_opts = (int)((flags & BYZ_AGG_EARLY_MAJORITY) | (flags & 0xFFFF0000u));
     // trim_b < 0: median; otherwise trimmed mean dropping trim_b values at each end
     const int trim_b = (flags & BYZ_AGG_TRIMMED_MEAN) != 0 ? (int)((flags >> 8) & 0xFFu) : -1;
     if (trim_b < 0 && (flags & 0xFF00u) != 0) return BYZ_EINVAL;
@@ -1613,15 +1619,15 @@ extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
     // probe -> single pass -> exact path, whose three kernels return at once unless the single
     // pass recorded a violated assumption
     if (f == 169)
-        rc = byz_internal_launch_single_pass_5(f, r, X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
+        rc = byz_internal_launch_single_pass_5(f, r, X, d, ld, file_rows_dev, ws, O, probe_opts, trim_b, s);
     else if (f == 121)
-        rc = byz_internal_launch_single_pass_4(f, r, X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
+        rc = byz_internal_launch_single_pass_4(f, r, X, d, ld, file_rows_dev, ws, O, probe_opts, trim_b, s);
     else if (f == 81)
-        rc = byz_internal_launch_single_pass_3(f, r, X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
+        rc = byz_internal_launch_single_pass_3(f, r, X, d, ld, file_rows_dev, ws, O, probe_opts, trim_b, s);
     else if (f == 49)
-        rc = byz_internal_launch_single_pass_2(f, r, X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
+        rc = byz_internal_launch_single_pass_2(f, r, X, d, ld, file_rows_dev, ws, O, probe_opts, trim_b, s);
     else
-        rc = byz_internal_launch_single_pass_1(f, r, X, d, ld, file_rows_dev, ws, O, early, trim_b, s);
+        rc = byz_internal_launch_single_pass_1(f, r, X, d, ld, file_rows_dev, ws, O, probe_opts, trim_b, s);
     if (rc != BYZ_OK) return rc;
     rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, ws->viol, s);
     if (rc != BYZ_OK) return rc;

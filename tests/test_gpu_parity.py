@@ -255,6 +255,46 @@ def test_argument_errors():
     assert out.numel() == 0 and (wrep2 == 0).all()
 
 
+@pytest.mark.parametrize("scheme,a,b,q", [(MOLS, 5, 3, 4), (MOLS, 7, 3, 5), (RAM, 5, 5, 6)])
+def test_probe_sample_shift(scheme, a, b, q):
+    # BYZ_AGG_PROBE_SHIFT moves the coordinates the single pass samples first: the output and
+    # the winners never change; which inputs send byz_aggregate down the exact path does
+    d = 70_001
+    w = W.make(scheme, a, b, q, d, ALIE, seed=77, ld=synth.padded_ld(d, 4), device=DEV)
+    rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+    Xh = w.X.cpu().numpy()
+    wrep_o, wrow_o, _ = C.vote(Xh, w.file_rows, d)
+    out_o = C.median(Xh, wrow_o, d)
+    shifts = (0, 1, 2, 7, 255, 12345, 40000, 65535)
+    for s in shifts:
+        for extra in (0, B.BYZ_AGG_EARLY_MAJORITY):
+            out, wrep, ws = B.byz_aggregate_opts(w.X, d, rows_dev, w.f, w.r, B.BYZ_AGG_PROBE_SHIFT(s) | extra)
+            torch.cuda.synchronize()
+            assert np.array_equal(W.bits(out), W.bits(out_o)), (s, extra)
+            assert np.array_equal(wrep.cpu().numpy(), wrep_o), (s, extra)
+            assert not B.byz_aggregate_took_exact_path(ws), (s, extra)
+    # one honest copy (not the first of its file) differs in a single word.  With shift 0 that
+    # word is one of the sampled ones (run 3, word 5 of the 16 runs (d - 16) / 15 apart): the
+    # probe sees the difference and the single pass stands.  Other shifts sample elsewhere: the
+    # single pass finds its assumption violated and the exact path runs.  Same result always.
+    clean = [j for j in range(w.f) if not any(int(x) in w.byz for x in w.file_workers[j])]
+    c_star = 3 * ((d - 16) // 15) + 5
+    P = w.X.clone()
+    P[int(w.file_rows[clean[0], 1]), c_star] += 1.0
+    Ph = P.cpu().numpy()
+    wrep_p, wrow_p, neq_p = C.vote(Ph, w.file_rows, d)
+    out_p = C.median(Ph, wrow_p, d)
+    assert neq_p[clean[0]] != 0 and np.array_equal(wrep_p, wrep_o)
+    took = {}
+    for s in shifts:
+        out, wrep, ws = B.byz_aggregate_opts(P, d, rows_dev, w.f, w.r, B.BYZ_AGG_PROBE_SHIFT(s))
+        torch.cuda.synchronize()
+        assert np.array_equal(W.bits(out), W.bits(out_p)), s
+        assert np.array_equal(wrep.cpu().numpy(), wrep_p), s
+        took[s] = bool(B.byz_aggregate_took_exact_path(ws))
+    assert took[0] is False and sum(took.values()) >= len(shifts) - 2, took
+
+
 def test_generator_same_bytes_on_cpu_and_gpu():
     for fs in (False, True):
         Gc = synth.honest_gradients(9, 5000, 77, step=3, device="cpu", file_scales=fs)
