@@ -41,6 +41,33 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, n), n
 
 
+def test_header_is_plain_c_and_agrees_with_the_binding(tmp_path):
+    # the boundary is a C header: it compiles as C, and its limits, status codes and flag
+    # macros have the values the Python binding uses
+    src = tmp_path / "consts.c"
+    src.write_text('''#include <stdio.h>
+#include "byzshield.h"
+int main(void) {
+    printf("%d %d %d %d\\n", BYZ_MAX_F, BYZ_MAX_F_KRUM, BYZ_MAX_F_WIDE, BYZ_MAX_R);
+    printf("%u %u %u %u\\n", BYZ_AGG_EARLY_MAJORITY, BYZ_AGG_TRIM(7), BYZ_AGG_PROBE_SHIFT(0x1234),
+           BYZ_AGG_PROBE_SHIFT(0x12345));
+    printf("%d %d %d\\n", (int)BYZ_SCHEME_MOLS, (int)BYZ_SCHEME_RAMANUJAN, (int)BYZ_SCHEME_FRC);
+    printf("%u %u\\n", (unsigned)BYZ_SEARCH_EXHAUSTIVE, (unsigned)BYZ_SEARCH_SYMMETRY);
+    return 0;
+}
+''')
+    exe = tmp_path / "consts"
+    import subprocess
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src),
+                    "-o", str(exe)], check=True)
+    lines = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    assert [int(x) for x in lines[0].split()] == [B.BYZ_MAX_F, B.BYZ_MAX_F_KRUM, B.BYZ_MAX_F_WIDE, B.BYZ_MAX_R]
+    assert [int(x) for x in lines[1].split()] == [B.BYZ_AGG_EARLY_MAJORITY, B.BYZ_AGG_TRIM(7),
+                                                  B.BYZ_AGG_PROBE_SHIFT(0x1234), B.BYZ_AGG_PROBE_SHIFT(0x12345)]
+    assert [int(x) for x in lines[2].split()] == [B.BYZ_SCHEME_MOLS, B.BYZ_SCHEME_RAMANUJAN, B.BYZ_SCHEME_FRC]
+    assert [int(x) for x in lines[3].split()] == [B.BYZ_SEARCH_EXHAUSTIVE, B.BYZ_SEARCH_SYMMETRY]
+
+
 def test_table2_through_the_library():
     asg = _build("mols", 5, 3)
     assert (asg.K, asg.f, asg.l, asg.r) == (15, 25, 5, 3)
