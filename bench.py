@@ -239,6 +239,11 @@ def main():
                                                                    workspace=ws, stream=stream))
                 exact_taken = bool(B.byz_aggregate_took_exact_path(ws))
                 del planted
+        # what a kernel that only reads the r*f rows the way the single pass does can reach,
+        # without and with the one output row
+        n_rows = asg.f * asg.r
+        ms_rd = timed_call(lambda: B.byz_calibration_read_rows(bufs[0], d, n_rows, out, 0, stream=stream))
+        ms_rdst = timed_call(lambda: B.byz_calibration_read_rows(bufs[0], d, n_rows, out, 1, stream=stream))
         bb = 4.0 * asg.f * d + 4.0 * (asg.f - 2 * bu_c + 1) * d  # Gram pass + theta rows + output
         kb = 4.0 * asg.f * d + 4.0 * (mk_m + 1) * d  # Gram pass over f rows + mean of m rows
         vb, mb = 4.0 * asg.r * asg.f * d, 4.0 * (asg.f + 1) * d
@@ -256,6 +261,14 @@ def main():
                                            "gbps": alg_bytes / ms_agg_tm / 1e6,
                                            "frac": alg_bytes / ms_agg_tm / 1e6 / HBM_PEAK_GBPS,
                                            "note": "whole path with the trimmed mean instead of the median"},
+            "access_pattern_ceiling": {
+                "read_only_ms": ms_rd, "read_only_gbps": 4.0 * n_rows * d / ms_rd / 1e6,
+                "read_and_store_ms": ms_rdst,
+                "read_and_store_gbps": 4.0 * (n_rows + 1) * d / ms_rdst / 1e6,
+                "read_and_store_frac": 4.0 * (n_rows + 1) * d / ms_rdst / 1e6 / HBM_PEAK_GBPS,
+                "note": "byz_calibration_read_rows: the single pass's loads (and its store) with "
+                        "no vote and no median; the gap between the two is what writing 1/(rf+1) "
+                        "of the bytes costs"},
             "byz_aggregate_exact_path": None if ms_exact is None else {
                 "ms": ms_exact, "took_exact_path": exact_taken,
                 "algorithmic_bytes": alg_bytes + vb + mb,

@@ -364,6 +364,19 @@ int byz_profile_collect(float *ms_out, int capacity, int *n_out);
  */
 int byz_calibration_copy(const void *src, void *dst, size_t bytes, void *stream);
 
+/*
+ * Reference kernel for the single pass's ceiling: reads the first 4*floor(d/4) words of rows
+ * 0..n_rows-1 of the device matrix rows_base (row pitch ld words) with the access pattern of
+ * byz_aggregate's single pass -- every thread 16 bytes of each row, non-temporal -- and does
+ * nothing with them but XOR; with store != 0 it writes the XOR to out[0..4*floor(d/4)-1]
+ * (device, non-temporal 16-byte stores), with store == 0 it writes nothing (out must still be
+ * a valid device pointer).  The two timings bound what a kernel of this shape can reach with
+ * and without its output.  4 <= d <= 2^30, 1 <= n_rows <= BYZ_MAX_F_WIDE * BYZ_MAX_R.
+ * Asynchronous on `stream`.  Errors: BYZ_EINVAL, BYZ_EDEVICE.
+ */
+int byz_calibration_read_rows(const void *rows_base, int64_t d, int64_t ld, int n_rows, void *out,
+                              int store, void *stream);
+
 /* ------------------------------------------------------------------------------ misc */
 
 const char *byz_strerror(int code);

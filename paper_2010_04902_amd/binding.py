@@ -76,6 +76,7 @@ def _load():
                                        ctypes.c_uint, vp]),
         "byz_aggregate_took_exact_path": (c_int, [vp, ip, vp]),
         "byz_calibration_copy": (c_int, [vp, vp, sz, vp]),
+        "byz_calibration_read_rows": (c_int, [vp, i64, i64, c_int, vp, c_int, vp]),
         "byz_profile_enable": (c_int, [c_int]),
         "byz_profile_collect": (c_int, [ctypes.POINTER(ctypes.c_float), c_int, ip]),
         "byz_strerror": (ctypes.c_char_p, [c_int]),
@@ -391,6 +392,18 @@ def byz_profile_collect(capacity):
     n = ctypes.c_int()
     _check(_load().byz_profile_collect(buf, int(capacity), ctypes.byref(n)), "byz_profile_collect")
     return [float(buf[i]) for i in range(n.value)]
+
+
+def byz_calibration_read_rows(rows_base, d, n_rows, out, store, stream=None):
+    """Reads rows 0..n_rows-1 of rows_base the way the single pass does; store != 0 also writes."""
+    ld = _rows_2d(rows_base)
+    if int(n_rows) > rows_base.shape[0]:
+        raise ValueError("rows_base has fewer than n_rows rows")
+    _need(out, int(d), "out")
+    _check(_load().byz_calibration_read_rows(_dev_ptr(rows_base, ("float32",), "rows_base"), int(d), ld,
+                                             int(n_rows), _dev_ptr(out, ("float32",), "out"),
+                                             int(bool(store)), _stream_ptr(stream)),
+           "byz_calibration_read_rows")
 
 
 def byz_calibration_copy(src, dst, stream=None):

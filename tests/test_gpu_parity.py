@@ -360,6 +360,29 @@ def test_hip_graph_capture_and_replay():
     assert wrep_e2[3].item() == 1 and B.byz_aggregate_took_exact_path(ws_e2)
 
 
+def test_read_rows_reference_kernel():
+    # the access-pattern reference kernel XORs the rows it reads; without the store it leaves
+    # the output alone
+    rng = np.random.default_rng(6)
+    for (n_rows, d, ld) in [(1, 4, 4), (5, 1000, 1003), (6, 1027, 1028), (7, 70001, 70004), (75, 5003, 5003)]:
+        Xh = rng.integers(0, 2 ** 32, size=(n_rows + 1, ld), dtype=np.uint64).astype(np.uint32)
+        X = torch.tensor(Xh.view(np.float32), device=DEV)
+        out = torch.full((d,), 7.0, dtype=torch.float32, device=DEV)
+        B.byz_calibration_read_rows(X, d, n_rows, out, 0)
+        torch.cuda.synchronize()
+        assert (out == 7.0).all()
+        B.byz_calibration_read_rows(X, d, n_rows, out, 1)
+        torch.cuda.synchronize()
+        n4 = d // 4 * 4
+        want = np.bitwise_xor.reduce(Xh[:n_rows, :n4], axis=0)
+        assert np.array_equal(W.bits(out)[:n4], want), (n_rows, d)
+        assert (out[n4:] == 7.0).all()
+    with pytest.raises(B.ByzError):
+        B.byz_calibration_read_rows(X, 3, 1, out, 1)  # d < 4
+    with pytest.raises(ValueError):
+        B.byz_calibration_read_rows(X, 8, 500, out, 1)  # more rows than the matrix has
+
+
 def test_measurement_aids():
     src = torch.randn(1 << 20, device=DEV)
     dst = torch.zeros_like(src)
