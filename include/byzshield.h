@@ -327,6 +327,23 @@ int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld, const int32_t
                        int f, int r, float *out, int32_t *winner_replica, void *workspace,
                        size_t workspace_bytes, unsigned flags, void *stream);
 
+/*
+ * byz_aggregate_opts for callers that cannot allocate device memory and so have no workspace
+ * to hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, results and errors, minus the workspace: the scratch is a fixed
+ * 24 KiB array in the library's device image (every GPU the library runs on holds its own copy
+ * until the process ends), large enough for every (f, r) the library accepts, i.e. f <=
+ * BYZ_MAX_F_WIDE and r <= BYZ_MAX_R; anything beyond that is refused with BYZ_ENOMEM.  The call
+ * allocates nothing and frees nothing; on its first use on a device it looks the array's
+ * address up (BYZ_EDEVICE if that fails, BYZ_EUNSUPPORTED for a device ordinal above 63).
+ * All calls on one GPU share that array, which keeps whatever the last call left in it (each
+ * call clears what it needs): calls that overlap in time on one GPU -- different streams,
+ * different threads -- race and give undefined results; calls on one stream are fine.
+ */
+int byz_aggregate_static(const float *copies, int64_t d, int64_t ld, const int32_t *file_rows_dev,
+                         int f, int r, float *out, int32_t *winner_replica, unsigned flags,
+                         void *stream);
+
 /* 1 if byz_aggregate runs (f, r) as the single pass described above, 0 if it runs byz_vote's and
  * byz_median's kernels one after the other (shapes without a compiled single-pass kernel, or
  * invalid (f, r)). */

@@ -74,6 +74,7 @@ def _load():
         "byz_aggregate": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, sz, vp]),
         "byz_aggregate_opts": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, sz,
                                        ctypes.c_uint, vp]),
+        "byz_aggregate_static": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, ctypes.c_uint, vp]),
         "byz_aggregate_took_exact_path": (c_int, [vp, ip, vp]),
         "byz_calibration_copy": (c_int, [vp, vp, sz, vp]),
         "byz_calibration_read_rows": (c_int, [vp, i64, i64, c_int, vp, c_int, vp]),
@@ -368,6 +369,20 @@ def byz_aggregate(copies, d, file_rows_dev, f, r, out=None, winner_replica=None,
     else:
         _check(_load().byz_aggregate_opts(*args, _flags, _stream_ptr(stream)), "byz_aggregate_opts")
     return out, winner_replica, workspace
+
+
+def byz_aggregate_static(copies, d, file_rows_dev, f, r, out, winner_replica, flags=0, stream=None):
+    """byz_aggregate_opts on the library's own fixed scratch; the caller supplies every buffer."""
+    ld = _rows_2d(copies)
+    _need(file_rows_dev, int(f) * int(r), "file_rows_dev")
+    _need(out, int(d), "out")
+    _need(winner_replica, int(f), "winner_replica")
+    _check(_load().byz_aggregate_static(_dev_ptr(copies, ("float32",), "copies"), int(d), ld,
+                                        _dev_ptr(file_rows_dev, ("int32",), "file_rows_dev"),
+                                        int(f), int(r), _dev_ptr(out, ("float32",), "out"),
+                                        _dev_ptr(winner_replica, ("int32",), "winner_replica"),
+                                        int(flags), _stream_ptr(stream)), "byz_aggregate_static")
+    return out, winner_replica
 
 
 def byz_aggregate_has_single_pass(f, r):

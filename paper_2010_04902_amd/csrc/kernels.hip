@@ -14,6 +14,7 @@
 // atomicOr per file and wave that is skipped when the bits are already set.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 #include <new>
 
@@ -1604,10 +1605,12 @@ extern "C" size_t byz_aggregate_workspace_bytes(int f, int r) {
 
 extern "C" int byz_aggregate_has_single_pass(int f, int r) { return has_fused(f, r) ? 1 : 0; }
 
-extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
+// byz_aggregate_opts after its workspace has been settled: validates the rest and enqueues
+// the launches.  ws is device memory of sizeof(AggWorkspace) bytes, 256-byte aligned.
+static int aggregate_on_workspace(const float *copies, int64_t d, int64_t ld,
                                   const int32_t *file_rows_dev, int f, int r, float *out,
-                                  int32_t *winner_replica, void *workspace, size_t workspace_bytes,
-                                  unsigned flags, void *stream) {
+                                  int32_t *winner_replica, AggWorkspace *ws, unsigned flags,
+                                  void *stream) {
     if ((flags & ~(unsigned)(BYZ_AGG_EARLY_MAJORITY | BYZ_AGG_TRIMMED_MEAN | 0xFFFFFF00u)) != 0)
         return BYZ_EINVAL;
     // what the probe needs to know: bit 0 early-majority mode, bits 16..31 the sample shift
@@ -1618,14 +1621,11 @@ extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
     if (trim_b >= 0 && 2 * trim_b >= f) return BYZ_EINVAL;
     int rc = check_common(copies, d, ld, file_rows_dev, f, r);
     if (rc != BYZ_OK) return rc;
-    if ((out == nullptr && d > 0) || workspace == nullptr) return BYZ_EINVAL;
+    if ((out == nullptr && d > 0) || ws == nullptr) return BYZ_EINVAL;
     if ((f % 2) == 0) return BYZ_EUNSUPPORTED;
-    if (((uintptr_t)workspace & 255u) != 0) return BYZ_EINVAL;
-    if (workspace_bytes < sizeof(AggWorkspace)) return BYZ_ENOMEM;
     hipStream_t s = (hipStream_t)stream;
     const uint32_t *X = reinterpret_cast<const uint32_t *>(copies);
     uint32_t *O = reinterpret_cast<uint32_t *>(out);
-    AggWorkspace *ws = reinterpret_cast<AggWorkspace *>(workspace);
 
     // (the 169-file single pass is built for the median only)
     if (!has_fused(f, r) || d < kVec || (f == 169 && trim_b >= 0)) {
@@ -1674,12 +1674,55 @@ extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
     return byz_internal_launch_median(X, d, ld, ws->winner_row, f, O, ws->viol, f, s);
 }
 
+extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
+                                  const int32_t *file_rows_dev, int f, int r, float *out,
+                                  int32_t *winner_replica, void *workspace, size_t workspace_bytes,
+                                  unsigned flags, void *stream) {
+    if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0) return BYZ_EINVAL;
+    // the reasons that come before "workspace too small" keep their codes
+    const int rc = check_common(copies, d, ld, file_rows_dev, f, r);
+    if (rc != BYZ_OK) return rc;
+    if (workspace_bytes < sizeof(AggWorkspace)) return BYZ_ENOMEM;
+    return aggregate_on_workspace(copies, d, ld, file_rows_dev, f, r, out, winner_replica,
+                                  reinterpret_cast<AggWorkspace *>(workspace), flags, stream);
+}
+
 extern "C" int byz_aggregate(const float *copies, int64_t d, int64_t ld,
                              const int32_t *file_rows_dev, int f, int r, float *out,
                              int32_t *winner_replica, void *workspace, size_t workspace_bytes,
                              void *stream) {
     return byz_aggregate_opts(copies, d, ld, file_rows_dev, f, r, out, winner_replica, workspace,
                               workspace_bytes, 0u, stream);
+}
+
+// Scratch of byz_aggregate_static: one AggWorkspace per GPU, part of the loaded code object
+// (so it is there without any allocation) and held until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; what the kernels get is the device
+// address that call returns, looked up once per device.
+constexpr size_t kStaticScratchBytes = 24 * 1024;
+static_assert(sizeof(AggWorkspace) <= kStaticScratchBytes, "byz_aggregate_static's scratch");
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+extern "C" int byz_aggregate_static(const float *copies, int64_t d, int64_t ld,
+                                    const int32_t *file_rows_dev, int f, int r, float *out,
+                                    int32_t *winner_replica, unsigned flags, void *stream) {
+    // sizes first: what the fixed scratch cannot hold is refused before anything else happens
+    if (f > kWide || r > BYZ_MAX_R) return BYZ_ENOMEM;
+    int dev = -1;
+    BYZ_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return BYZ_EUNSUPPORTED;
+    void *ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (ptr == nullptr) {
+        // first call on this device (which is current): every GPU has its own copy of the array
+        BYZ_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (ptr == nullptr || ((uintptr_t)ptr & 255u) != 0) return BYZ_EINTERNAL;
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    }
+    return aggregate_on_workspace(copies, d, ld, file_rows_dev, f, r, out, winner_replica,
+                                  static_cast<AggWorkspace *>(ptr), flags, stream);
 }
 
 extern "C" int byz_calibration_copy(const void *src, void *dst, size_t bytes, void *stream) {
