@@ -113,7 +113,7 @@ def main():
         for i in range(args.warmup):
             step(i, flags)
         torch.cuda.synchronize()
-        exact = B.byz_aggregate_took_exact_path(ws)
+        exact = B.byz_aggregate_path(ws)
         B.byz_profile_enable(args.steps)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -161,7 +161,7 @@ def main():
         "config": {"workload": cfg.name, "d": d, "ld": ld, "K": asg.K, "f": asg.f, "r": asg.r,
                    "l": asg.l, "q": cfg.q, "c_max": cmax, "attack": cfg.attack["kind"],
                    "rows": asg.f * asg.r, "input_bytes": 4 * asg.f * asg.r * d, "rotating_buffers": n_buf,
-                   "took_exact_path": bool(exact)},
+                   "path": int(exact)},
         "step_hbm_gbps_algorithmic": alg_bytes / (ms_per_step * 1e-3) / 1e9,
     }
     if kernel_ms:
@@ -187,7 +187,7 @@ def main():
         e_avg = sum(e_kernel_ms) / len(e_kernel_ms) if e_kernel_ms else None
         result["early_majority"] = {
             "value": d / (e_ms * 1e-3), "unit": "coords/s", "ms_per_step": e_ms,
-            "took_exact_path": bool(e_exact),
+            "path": int(e_exact),
             "note": "reads r'=%d of r=%d copies of a file when the probe finds a majority class; "
                     "falls back to all r (as the headline run) if any file has none" % (rp, asg.r),
             "roofline": None if e_avg is None else {
@@ -237,7 +237,7 @@ def main():
                 ms_exact = timed_call(lambda: B.byz_aggregate_opts(planted, d, rows_dev, asg.f, asg.r, 0,
                                                                    out=out, winner_replica=wrep,
                                                                    workspace=ws, stream=stream))
-                exact_taken = bool(B.byz_aggregate_took_exact_path(ws))
+                exact_taken = int(B.byz_aggregate_path(ws))
                 del planted
         # what a kernel that only reads the r*f rows the way the single pass does can reach,
         # without and with the one output row
@@ -270,7 +270,7 @@ def main():
                         "no vote and no median; the gap between the two is what writing 1/(rf+1) "
                         "of the bytes costs"},
             "byz_aggregate_exact_path": None if ms_exact is None else {
-                "ms": ms_exact, "took_exact_path": exact_taken,
+                "ms": ms_exact, "path": exact_taken,
                 "algorithmic_bytes": alg_bytes + vb + mb,
                 "gbps": (alg_bytes + vb + mb) / ms_exact / 1e6,
                 "frac": (alg_bytes + vb + mb) / ms_exact / 1e6 / HBM_PEAK_GBPS,

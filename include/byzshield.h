@@ -40,7 +40,7 @@ extern "C" {
 typedef enum byz_status {
     BYZ_OK = 0,
     BYZ_EINVAL = -1,       /* null pointer, size out of range, even r, q outside [0,K], ...      */
-    BYZ_EUNSUPPORTED = -2, /* valid in the paper but not built: even f, f > 64, l > 255 ...         */
+    BYZ_EUNSUPPORTED = -2, /* valid in the paper but not built: even f, l > 255, s not prime ...     */
     BYZ_ENOMEM = -3,       /* host allocation failed, or the workspace is too small               */
     BYZ_EDEVICE = -4,      /* a HIP call failed; see byz_last_hip_error()                          */
     BYZ_EINTERNAL = -5     /* an assignment invariant did not hold (a bug)                         */
@@ -132,9 +132,6 @@ int byz_worst_case(const byz_assignment *g, int q, int32_t *byz_workers_out, int
 #define BYZ_SEARCH_SYMMETRY 2u   /* symmetry-reduced search whatever the size        */
 int byz_worst_case_opts(const byz_assignment *g, int q, unsigned flags, int32_t *byz_workers_out,
                         int32_t *cmax_out, uint64_t *distorted_mask_out);
-
-/* Subsets evaluated by the calling thread's last byz_worst_case / byz_worst_case_opts call. */
-uint64_t byz_worst_case_last_visited(void);
 
 /* Upper bound gamma on c_max^(q): Eq. 5 with mu_1 = 1/r (Lemma 2) put into Claim 1.
  * Returns NaN if g is NULL or q is outside [0, K]. */
@@ -283,11 +280,16 @@ size_t byz_aggregate_workspace_bytes(int f, int r);
  *   winner_replica device [f] int32 out, may be NULL
  *   workspace      device, >= byz_aggregate_workspace_bytes(f, r) bytes, 256-byte aligned,
  *                  contents irrelevant on entry; calls sharing a workspace must not overlap.
- * A small probe compares the copies on a sample of coordinates; the streaming pass then
- * feeds the probable winner of each file to the median network while checking, over all d
- * coordinates, every equality the probe assumed.  If a check fails (a copy that matches on
- * the sample but differs elsewhere) the exact two-step path (vote, then median) runs on the
- * device right after; the result is the same, only slower.
+ * A small probe compares the copies on a sample of coordinates and guesses each file's
+ * winner; the streaming pass feeds that copy to the median network while it compares every
+ * pair of copies of every file over all d coordinates -- the whole of Eq. 3's comparison, so
+ * the true winners are known when the pass ends, whatever the probe guessed.  If every guessed
+ * copy is bit-identical to its file's winner (the case whenever the attacked copies differ
+ * from the honest ones on the sample, and also when a copy other than the guessed one differs
+ * off the sample) the output stands: one pass, 4(rf+1) bytes per coordinate.  Otherwise (a
+ * guessed copy that matches on the sample and differs elsewhere) the median is redone from
+ * the true winners, 4(f+1) more bytes; the copies are never compared a second time.  The
+ * result is the same either way; byz_aggregate_path tells which it was.
  * The single pass is compiled for (f, r) = (9,3), (15,3), (21,3), (25,3), (25,5), (35,5),
  * (49,3), (49,5), (81,3), (121,3), (169,3) (byz_aggregate_has_single_pass; (169,3) for the
  * median only); for every other valid
@@ -304,8 +306,12 @@ int byz_aggregate(const float *copies, int64_t d, int64_t ld, const int32_t *fil
  *   BYZ_AGG_EARLY_MAJORITY  r' = (r+1)/2 copies that are identical on all d coordinates are the
  *     majority whatever the other r - r' copies hold (Sec. 2: a file is distorted only if at
  *     least r' of its copies are), so for every file whose probable winner's class has at
- *     least r' members only r' copies are read and verified.  Same output as flags = 0 for
+ *     least r' members only r' copies are read and compared.  Same output as flags = 0 for
  *     every input; HBM traffic drops from 4(rf+1) towards 4(r'f+1) bytes per coordinate.
+ *     If the r' copies read of some file turn out to differ (off the probe's sample), nothing
+ *     is known about the copies that were skipped: the vote is then redone over all copies
+ *     and the median after it (BYZ_PATH_REVOTED), about 2.2 times the time of flags = 0.  One
+ *     worker can cause that with one changed word, so the mode suits trusted-timing settings.
  *     Ignored where the single pass does not run.
  * Errors: as byz_aggregate; BYZ_EINVAL for unknown flag bits.
  */
@@ -316,12 +322,12 @@ int byz_aggregate(const float *copies, int64_t d, int64_t ld, const int32_t *fil
  *     contract.  May be combined with BYZ_AGG_EARLY_MAJORITY. */
 #define BYZ_AGG_TRIMMED_MEAN 2u
 #define BYZ_AGG_TRIM(b) (BYZ_AGG_TRIMMED_MEAN | ((unsigned)(b) << 8))
-/*   BYZ_AGG_PROBE_SHIFT(s)  moves the <= 256 coordinates on which the single pass first compares
- *     the copies of a file (16 runs of 16 words, evenly spaced from a start that s, 0..65535,
- *     picks).  The output never depends on it.  The time can: copies that agree on the sampled
- *     coordinates and differ elsewhere make byz_aggregate redo the vote over all copies (about
- *     2.2 times the time), and workers who know where the sample lies could send such copies
- *     on purpose; a caller who draws s afresh for every call takes that knowledge away. */
+/*   BYZ_AGG_PROBE_SHIFT(s)  moves the <= 256 coordinates on which the probe compares the copies
+ *     of a file (16 runs of 16 words, evenly spaced from a start that s, 0..65535, picks).  The
+ *     output never depends on it.  It is no defence: a worker that changes a single word of its
+ *     honest vector misses any sample of 256 coordinates with probability 1 - 256/d wherever
+ *     the sample lies.  What such a copy can cost is bounded instead: nothing if it is not the
+ *     copy the probe guessed for its file, one median over the winners if it is. */
 #define BYZ_AGG_PROBE_SHIFT(s) (((unsigned)(s) & 0xFFFFu) << 16)
 int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld, const int32_t *file_rows_dev,
                        int f, int r, float *out, int32_t *winner_replica, void *workspace,
@@ -350,49 +356,21 @@ int byz_aggregate_static(const float *copies, int64_t d, int64_t ld, const int32
 int byz_aggregate_has_single_pass(int f, int r);
 
 /*
- * After byz_aggregate's work on `stream` has completed: copies 0/1 into *took_exact_path
- * (host) from the workspace (device) -- 1 if the two-step path had to run.  Synchronises the
- * stream.  Diagnostic only.
+ * What the last byz_aggregate / byz_aggregate_opts call on this workspace did, once its work on
+ * `stream` has completed: copies a byz_path value from the workspace (device) into *path
+ * (host).  Synchronises the stream.  Diagnostic only.
  */
-int byz_aggregate_took_exact_path(const void *workspace, int *took_exact_path, void *stream);
-
-/* ------------------------------------------------------------------------- measurement */
-
-/*
- * Timing aid for benchmarks.  byz_profile_enable(n) with n > 0 creates n HIP event pairs for
- * the calling thread; from then on each byz_aggregate call of that thread records one pair
- * around its dominant kernel -- the single-pass kernel (its main launch, not the probe or the
- * finalisation), or the vote kernel for shapes without one -- on the call's stream, until n
- * calls have been recorded.
- * byz_profile_enable(0) releases the events.  Errors: BYZ_EINVAL (n < 0 or n > 100000),
- * BYZ_ENOMEM, BYZ_EDEVICE.
- * byz_profile_collect waits for the recorded events, writes the kernel durations in
- * milliseconds to host ms_out[0..*n_out-1] (at most `capacity`), and restarts recording at
- * the first pair.
- */
-int byz_profile_enable(int max_calls);
-int byz_profile_collect(float *ms_out, int capacity, int *n_out);
-
-/*
- * Reference kernel for hardware HBM counters: copies `bytes` (a multiple of 16) from device
- * src to device dst, non-overlapping, with the same 16-byte non-temporal loads and stores the
- * streaming kernels use, so that it reads exactly `bytes` and writes exactly `bytes`.
- * Asynchronous on `stream`.  Errors: BYZ_EINVAL, BYZ_EDEVICE.
- */
-int byz_calibration_copy(const void *src, void *dst, size_t bytes, void *stream);
-
-/*
- * Reference kernel for the single pass's ceiling: reads the first 4*floor(d/4) words of rows
- * 0..n_rows-1 of the device matrix rows_base (row pitch ld words) with the access pattern of
- * byz_aggregate's single pass -- every thread 16 bytes of each row, non-temporal -- and does
- * nothing with them but XOR; with store != 0 it writes the XOR to out[0..4*floor(d/4)-1]
- * (device, non-temporal 16-byte stores), with store == 0 it writes nothing (out must still be
- * a valid device pointer).  The two timings bound what a kernel of this shape can reach with
- * and without its output.  4 <= d <= 2^30, 1 <= n_rows <= BYZ_MAX_F_WIDE * BYZ_MAX_R.
- * Asynchronous on `stream`.  Errors: BYZ_EINVAL, BYZ_EDEVICE.
- */
-int byz_calibration_read_rows(const void *rows_base, int64_t d, int64_t ld, int n_rows, void *out,
-                              int store, void *stream);
+typedef enum byz_path {
+    BYZ_PATH_SINGLE_PASS = 0,   /* the single pass's output stood                                 */
+    BYZ_PATH_MEDIAN_REDONE = 1, /* some guessed copy was not its file's winner: the median was
+                                   redone from the true winners (bit 0)                          */
+    BYZ_PATH_REVOTED = 2,       /* early-majority mode only: the r' copies read of some file
+                                   differed; vote over all copies, then median (bit 1, always
+                                   together with bit 0: the value read back is 3)                */
+    BYZ_PATH_TWO_STEP = 4       /* no single pass for this (f, r) or d < 4: byz_vote's and
+                                   byz_median's kernels one after the other                      */
+} byz_path;
+int byz_aggregate_path(const void *workspace, int *path, void *stream);
 
 /* ------------------------------------------------------------------------------ misc */
 

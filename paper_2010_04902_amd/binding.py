@@ -75,7 +75,7 @@ def _load():
         "byz_aggregate_opts": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, sz,
                                        ctypes.c_uint, vp]),
         "byz_aggregate_static": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, ctypes.c_uint, vp]),
-        "byz_aggregate_took_exact_path": (c_int, [vp, ip, vp]),
+        "byz_aggregate_path": (c_int, [vp, ip, vp]),
         "byz_calibration_copy": (c_int, [vp, vp, sz, vp]),
         "byz_calibration_read_rows": (c_int, [vp, i64, i64, c_int, vp, c_int, vp]),
         "byz_profile_enable": (c_int, [c_int]),
@@ -389,12 +389,18 @@ def byz_aggregate_has_single_pass(f, r):
     return bool(_load().byz_aggregate_has_single_pass(int(f), int(r)))
 
 
-def byz_aggregate_took_exact_path(workspace, stream=None):
-    flag = ctypes.c_int()
-    _check(_load().byz_aggregate_took_exact_path(_dev_ptr(workspace, ("uint8",), "workspace"),
-                                                 ctypes.byref(flag), _stream_ptr(stream)),
-           "byz_aggregate_took_exact_path")
-    return bool(flag.value)
+BYZ_PATH_SINGLE_PASS = 0
+BYZ_PATH_MEDIAN_REDONE = 1
+BYZ_PATH_REVOTED = 2
+BYZ_PATH_TWO_STEP = 4
+
+
+def byz_aggregate_path(workspace, stream=None):
+    """-> byz_path bits of the last byz_aggregate call on this workspace (synchronises the stream)."""
+    path = ctypes.c_int()
+    _check(_load().byz_aggregate_path(_dev_ptr(workspace, ("uint8",), "workspace"),
+                                      ctypes.byref(path), _stream_ptr(stream)), "byz_aggregate_path")
+    return int(path.value)
 
 
 def byz_profile_enable(max_calls):

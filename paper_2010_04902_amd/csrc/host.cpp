@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "byzshield.h"
+#include "byzshield_bench.h"
 
 struct byz_assignment {
     int scheme = 0;

@@ -20,6 +20,7 @@
 
 #include "byz_internal.h"
 #include "byzshield.h"
+#include "byzshield_bench.h"
 
 // The build compiles this file once per BYZ_PART, in parallel, because the single-pass kernels
 // are large: part 0 holds every entry point, the vote and the Bulyan kernels, parts 1..4 one
@@ -130,6 +131,16 @@ __device__ __forceinline__ uint32_t differ(const uint32_t (&a)[V], const uint32_
 #pragma unroll
     for (int v = 0; v < V; ++v) acc |= a[v] ^ b[v];
     return acc;
+}
+
+// 1 iff the two chunks differ in any active lane of the wave (wave-uniform result).  One ballot
+// per word, merged as scalars: each is a single vector compare that writes its lane mask.
+template <int V>
+__device__ __forceinline__ uint32_t wave_differ(const uint32_t (&a)[V], const uint32_t (&b)[V]) {
+    uint64_t m = 0;
+#pragma unroll
+    for (int v = 0; v < V; ++v) m |= __builtin_amdgcn_ballot_w64(a[v] != b[v]);
+    return m != 0 ? 1u : 0u;
 }
 
 // 1 iff any active lane of the wave has a nonzero x (wave-uniform result)
@@ -277,29 +288,38 @@ template <> struct SelNet<49> {
 // --------------------------------------------------------------------- device workspace
 
 struct AggWorkspace {
-    uint32_t viol[kWide];            // single pass: assumed-equal neighbours that differ
-    uint32_t pair_neq[kWide];        // exact path: all pair bits
+    // single pass: bit pair_bit(NS, p, q) set iff the copies in slots p < q of the file's
+    // permuted row list differ anywhere in [0, d) (NS = slots the pass read: r, or r' when every
+    // file ran in early-majority mode)
+    uint32_t pneq[kWide];
+    uint32_t pair_neq[kWide];        // two-step path and re-vote: all pair bits, replica numbering
     // byte offsets row*ld*4 of a file's rows, probable winner's class first
     uint64_t perm_off[kWide * kRowStride];
-    uint32_t chain_mask[kWide];      // bit k-1: permuted copies k-1 and k were equal on the sample
-    int32_t prov_winner[kWide];      // probable winner (original replica index)
-    int32_t winner_row[kWide];       // exact path result
-    uint32_t need_exact;             // 1 iff the exact path ran
+    // bits 3p..3p+2: replica in slot p; bits 24..27: slots of the file that hold a copy of their
+    // own (r, or r' for a file read in early-majority mode; the other slots repeat slot 0)
+    uint32_t perm[kWide];
+    int32_t winner_row[kWide];       // rows of the true winners (decided after the pass)
+    uint32_t need_median;            // 1: some file's slot 0 was not its winner -> median redone
+    uint32_t need_revote;            // 1: early-majority mode met a file whose r' copies differ
+    uint32_t path;                   // byz_path of the call, for byz_aggregate_path
     uint32_t slots_per_file;         // slots of every file the single pass reads: r or r'
-    uint32_t pad[61];
+    uint32_t pad[60];
 };
+static_assert(sizeof(AggWorkspace) % 256 == 0, "whole 256-byte lines");
 
 // ------------------------------------------------------------------------------ kernels
 
 // Clears the accumulators of one two-step aggregation (no hipMemset: callers may capture).
-__global__ void reset_workspace_kernel(AggWorkspace *ws, uint32_t need_exact) {
+__global__ void reset_workspace_kernel(AggWorkspace *ws, uint32_t path) {
     const int i = threadIdx.x;
     if (i < kWide) {
-        ws->viol[i] = 0;
+        ws->pneq[i] = 0;
         ws->pair_neq[i] = 0;
     }
     if (i == 0) {
-        ws->need_exact = need_exact;
+        ws->need_median = 0;
+        ws->need_revote = 0;
+        ws->path = path;
     }
 }
 
@@ -369,35 +389,80 @@ __global__ void vote_decide_kernel(const uint32_t *pair_neq, const int32_t *__re
     decide_files(pair_neq, file_rows, f, r, winner_replica, winner_row);
 }
 
-// The decision of the exact path behind the single pass (one block): if none of gate[0..f-1]
-// is set the single pass stands and its probable winners (gate_off_winner) are published as
-// the winners; otherwise the winners come from the pair bits the gated vote kernel just
-// collected, and took_exact records that the exact path ran.  (A kernel of its own rather
-// than the last block of the vote kernel: finding that block takes a device-wide fence in
-// every block, which made the vote five times slower.)
-__global__ void vote_decide_gated_kernel(const uint32_t *pair_neq,
-                                         const int32_t *__restrict__ file_rows, int f, int r,
-                                         const uint32_t *__restrict__ gate,
-                                         const int32_t *__restrict__ gate_off_winner,
-                                         int32_t *winner_replica, int32_t *winner_row,
-                                         uint32_t *took_exact) {
-    if (!any_word_set(gate, f)) {
-        if ((int)threadIdx.x < f && winner_replica != nullptr)
-            winner_replica[threadIdx.x] = gate_off_winner[threadIdx.x];
-        return;
+// Replica held by slot p of a file's permuted row list (AggWorkspace::perm).
+__device__ __forceinline__ int perm_slot(uint32_t packed, int p) { return (int)((packed >> (3 * p)) & 7u); }
+
+// The decision behind the single pass (one block, thread j = file j).  The pass compared every
+// pair of the slots it read over all d coordinates, so its bits are the vote's pair bits up to
+// the slot numbering: the true winner of every file follows by Eq. 3, whatever the probe
+// guessed.  The pass's output stands iff, for every file, the copy in slot 0 (the one that fed
+// the network) is bit-identical to the winner; otherwise need_median makes the gated median
+// kernel redo the output from the true winners (the inputs are not compared again).
+// A file read in early-majority mode has only r' slots of its own: if they are identical they
+// are the majority (Sec. 2) and slot 0 is the winner; if not, nothing is known about the
+// copies that were skipped and need_revote sends the call through the gated vote kernel.
+__global__ void single_pass_decide_kernel(AggWorkspace *ws, const int32_t *__restrict__ file_rows,
+                                          int f, int r, int32_t *winner_replica) {
+    __shared__ uint32_t s_median, s_revote;
+    if (threadIdx.x == 0) { s_median = 0; s_revote = 0; }
+    __syncthreads();
+    const int j = threadIdx.x;
+    if (j < f) {
+        const uint32_t pn = load_shared_word(&ws->pneq[j]);
+        const uint32_t packed = ws->perm[j];
+        const int own = (int)(packed >> 24);       // slots with a copy of their own
+        const int ns = (int)ws->slots_per_file;    // slots the pass read and numbered its bits by
+        if (own == r) {
+            uint32_t neq = 0;
+            for (int p = 0; p < r; ++p)
+                for (int q = p + 1; q < r; ++q)
+                    if ((pn >> pair_bit(ns, p, q)) & 1u) {
+                        const int a = perm_slot(packed, p), b = perm_slot(packed, q);
+                        neq |= 1u << pair_bit(r, a < b ? a : b, a < b ? b : a);
+                    }
+            const int w = decide_winner(neq, r);
+            if (winner_replica != nullptr) winner_replica[j] = w;
+            ws->winner_row[j] = file_rows[j * r + w];
+            if (!copies_equal(neq, r, perm_slot(packed, 0), w)) s_median = 1;
+        } else {
+            uint32_t differ_bits = 0;
+            for (int p = 0; p < own; ++p)
+                for (int q = p + 1; q < own; ++q) differ_bits |= (pn >> pair_bit(ns, p, q)) & 1u;
+            const int w = perm_slot(packed, 0);
+            if (winner_replica != nullptr) winner_replica[j] = w;
+            ws->winner_row[j] = file_rows[j * r + w];
+            if (differ_bits != 0) s_revote = 1;
+        }
     }
-    if (threadIdx.x == 0) *took_exact = 1;
-    decide_files(pair_neq, file_rows, f, r, winner_replica, winner_row);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        ws->need_median = s_median;
+        ws->need_revote = s_revote;
+        ws->path = (s_median != 0 ? (uint32_t)BYZ_PATH_MEDIAN_REDONE : 0u) |
+                   (s_revote != 0 ? (uint32_t)BYZ_PATH_REVOTED : 0u);
+    }
+}
+
+// Early-majority mode only, after the gated vote kernel: if the decision above asked for a
+// re-vote, the winners come from the pair bits that kernel collected and the median is redone.
+__global__ void revote_decide_kernel(AggWorkspace *ws, const int32_t *__restrict__ file_rows, int f,
+                                     int r, int32_t *winner_replica) {
+    if (ws->need_revote == 0) return;
+    decide_files(ws->pair_neq, file_rows, f, r, winner_replica, ws->winner_row);
+    if (threadIdx.x == 0) {
+        ws->need_median = 1;
+        ws->path = (uint32_t)BYZ_PATH_REVOTED | (uint32_t)BYZ_PATH_MEDIAN_REDONE;
+    }
 }
 
 // Vote, comparison: for every file, which pairs of copies differ anywhere in [0, d).  Threads own
 // vectors of V words; the d % V trailing words go to the first threads of the last block.
-// If `gate` is given, the kernel only runs when one of gate[0..f-1] is nonzero.
+// If `gate` is given, the kernel only runs when one of gate[0..gate_n-1] is nonzero.
 template <int R, int V>
 __global__ __launch_bounds__(kBlock) void vote_pairs_kernel(
     const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ file_rows,
-    int f, uint32_t *pair_neq, const uint32_t *__restrict__ gate) {
-    if (gate != nullptr && !any_word_set(gate, f)) return;
+    int f, uint32_t *pair_neq, const uint32_t *__restrict__ gate, int gate_n) {
+    if (gate != nullptr && !any_word_set(gate, gate_n)) return;
     const int lane = threadIdx.x & 63;
     const int64_t n_vec = d / V;
     const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
@@ -510,10 +575,19 @@ __global__ __launch_bounds__(kBlock) void vote_pairs_tolerant_kernel(
 
 // Steps of the generated streamed programs (selnet_stream_<f>.inc), written against local names
 // of the kernel that includes them: NS slots per file, V words per thread, kAhead, stage, key,
-// o, lane, flags (one word per 64 files), chain_mask, and BYZ_S_ROW_ADDR(j, k) = address of this thread's vector in
+// o, lane, flags (one word per 64 files), and BYZ_S_ROW_ADDR(j, k) = address of this thread's vector in
 // slot k of file j.
 // Hook a kernel may redefine around the include: BYZ_S_KEY(j, x) = key of word x of file j.
+// BYZ_S_STEP(j) opens file j's share of the program and BYZ_S_PIN(w) follows the comparators of
+// a share for every wire they changed; both do nothing unless a kernel redefines them.
 #define BYZ_S_KEY(j, x) to_key(x)
+#define BYZ_S_STEP(j)
+#define BYZ_S_PIN(w)
+// An empty statement the compiler may not execute speculatively: keeps the one-lane update of a
+// file's pair bits a real branch, and with it the file boundaries of the program (left as one
+// straight-line block, the compiler keeps every ballot alive to the end and runs out of
+// registers).
+#define BYZ_S_KEEP_BRANCH asm volatile("" ::: "memory");
 #define BYZ_S_LOAD_(j)                                                                        \
     _Pragma("unroll") for (int k_ = 0; k_ < NS; ++k_)                                         \
         load_vec<V>(reinterpret_cast<const uint32_t *>(BYZ_S_ROW_ADDR(j, k_)),                \
@@ -528,11 +602,14 @@ __global__ __launch_bounds__(kBlock) void vote_pairs_tolerant_kernel(
     {                                                                                         \
         if constexpr (NS > 1) {                                                               \
         uint32_t wb_ = 0;                                                                     \
-        _Pragma("unroll") for (int k_ = 1; k_ < NS; ++k_)                                     \
-            wb_ |= wave_any(differ<V>(stage[(j) % (kAhead + 1)][k_ - 1],                      \
-                                      stage[(j) % (kAhead + 1)][k_])) << (k_ - 1);            \
-        wb_ &= chain_mask[j];                                                                 \
-        if (lane == ((j) & 63)) flags[(j) >> 6] |= wb_;                                       \
+        _Pragma("unroll") for (int a_ = 0; a_ < NS; ++a_)                                     \
+        _Pragma("unroll") for (int b_ = a_ + 1; b_ < NS; ++b_)                                \
+            wb_ |= wave_differ<V>(stage[(j) % (kAhead + 1)][a_],                              \
+                                  stage[(j) % (kAhead + 1)][b_]) << pair_bit(NS, a_, b_);     \
+        if (lane == ((j) & 63)) {                                                             \
+            flags[(j) >> 6] |= wb_;                                                           \
+            BYZ_S_KEEP_BRANCH                                                                 \
+        }                                                                                     \
         }                                                                                     \
         _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_)                                      \
             key[v_][j] = BYZ_S_KEY(j, stage[(j) % (kAhead + 1)][0][v_]);                      \
@@ -571,10 +648,9 @@ __global__ __launch_bounds__(kBlock) void median_kernel(
             const uint32_t voff = (uint32_t)(gt * (V * 4));
             const char *Xb = reinterpret_cast<const char *>(X);
             uint32_t stage[kAhead + 1][NS][V];
-            const uint32_t *chain_mask = nullptr;  // unused with one slot per file
             const int lane = 0;
             uint32_t flags[(F + 63) / 64] = {};
-            (void)chain_mask; (void)lane; (void)flags;
+            (void)lane; (void)flags;
 #define BYZ_S_ROW_ADDR(j, k) (Xb + (uint64_t)(uint32_t)row_index[j] * (uint64_t)ld * 4u + voff)
 #include "generated/selnet_stream_dispatch.inc"
 #undef BYZ_S_ROW_ADDR
@@ -626,10 +702,9 @@ __global__ __launch_bounds__(kBlock) void median_large_kernel(
     const uint32_t voff = (uint32_t)(c0 * 4);
     const char *Xb = reinterpret_cast<const char *>(X);
     uint32_t stage[kAhead + 1][NS][V];
-    const uint32_t *chain_mask = nullptr;  // unused with one slot per file
     const int lane = 0;
     uint32_t flags[(F + 63) / 64] = {};
-    (void)chain_mask; (void)lane; (void)flags;
+    (void)lane; (void)flags;
 #undef BYZ_S_KEY
 #define BYZ_S_KEY(j, x) \
     (!PAD || (j) < f ? to_key(x) : ((j) < pad_low_end ? 0u : 0xFFFFFFFFu))
@@ -700,10 +775,9 @@ __global__ __launch_bounds__(kBlock) void trimmed_mean_kernel(
     const uint32_t voff = (uint32_t)(c0 * 4);
     const char *Xb = reinterpret_cast<const char *>(X);
     uint32_t stage[kAhead + 1][NS][V];
-    const uint32_t *chain_mask = nullptr;  // unused with one slot per file
     const int lane = 0;
     uint32_t flags[(F + 63) / 64] = {};
-    (void)chain_mask; (void)lane; (void)flags;
+    (void)lane; (void)flags;
     // PAD: f < F rows on the next generated size; the spare wires reload row_index[0] and carry
     // the largest key, so wires 0..f-1 end up holding the f values in ascending order
 #undef BYZ_S_KEY
@@ -855,10 +929,9 @@ __global__ __launch_bounds__(BLOCK) void bulyan_mean_kernel(
     const uint32_t voff = (uint32_t)(c0 * 4);
     const char *Xb = reinterpret_cast<const char *>(X);
     uint32_t stage[kAhead + 1][NS][V];
-    const uint32_t *chain_mask = nullptr;  // unused with one slot per file
     const int lane = 0;
     uint32_t flags[(F + 63) / 64] = {};
-    (void)chain_mask; (void)lane; (void)flags;
+    (void)lane; (void)flags;
 #undef BYZ_S_KEY
 #define BYZ_S_KEY(j, x) ((j) < theta ? to_key(x) : 0xFFFFFFFFu)
 #define BYZ_S_ROW_ADDR(j, k) (Xb + (uint64_t)(uint32_t)selected_rows[j] * (uint64_t)ld * 4u + voff)
@@ -901,8 +974,9 @@ __global__ __launch_bounds__(kBlock) void bulyan_mean_generic_kernel(
 
 // Probe: compares the copies of every file on a sample of <= kProbe coordinates (kProbe/16 runs
 // of 16 consecutive words spread over [0, d); all of [0, d) when d <= kProbe), derives the probable
-// equality classes, and lays out the rows of each file with the probable winner first and
-// equal-looking copies adjacent.  Also clears the state the later kernels accumulate into.
+// equality classes, and lays out the rows of each file with the probable winner first (slot 0
+// feeds the median network) and equal-looking copies adjacent.  Only the speed of the call
+// depends on this guess.  Also clears the state the later kernels accumulate into.
 // One block of kProbeThreads threads: thread group q = tid / kProbe takes the files
 // q, q + kProbeSplit, ..., every group on the same kProbe sample coordinates, so a thread waits
 // for F*R / kProbeSplit loads.
@@ -920,12 +994,14 @@ __global__ __launch_bounds__(kProbeThreads) void probe_kernel(const uint32_t *__
     static_assert(kProbe >= kWide, "one probe thread per file");
     if (tid < kWide) {
         s_neq[tid] = 0;
-        ws->viol[tid] = 0;
+        ws->pneq[tid] = 0;
         ws->pair_neq[tid] = 0;
     }
     if (tid == 0) {
         s_all_majority = 1;
-        ws->need_exact = 0;
+        ws->need_median = 0;
+        ws->need_revote = 0;
+        ws->path = 0;
     }
     __syncthreads();
 
@@ -1006,14 +1082,13 @@ __global__ __launch_bounds__(kProbeThreads) void probe_kernel(const uint32_t *__
         for (int k = 0; k < R; ++k) members += label[k] == label[w] ? 1 : 0;
         const int need = (R + 1) / 2;
         const int slots = (early_majority != 0 && members >= need) ? need : R;
-        uint32_t chain = 0;
+        uint32_t packed = (uint32_t)slots << 24;
         for (int p = 0; p < R; ++p) {
-            const int32_t row = file_rows[j * R + perm[p < slots ? p : 0]];
-            ws->perm_off[j * kRowStride + p] = (uint64_t)row * (uint64_t)ld * 4u;
-            if (p > 0 && p < slots && label[perm[p]] == label[perm[p - 1]]) chain |= 1u << (p - 1);
+            const int k = perm[p < slots ? p : 0];
+            ws->perm_off[j * kRowStride + p] = (uint64_t)file_rows[j * R + k] * (uint64_t)ld * 4u;
+            packed |= (uint32_t)k << (3 * p);
         }
-        ws->chain_mask[j] = chain;
-        ws->prov_winner[j] = w;
+        ws->perm[j] = packed;
         if (slots != need) s_all_majority = 0;
     }
     __syncthreads();
@@ -1023,15 +1098,13 @@ __global__ __launch_bounds__(kProbeThreads) void probe_kernel(const uint32_t *__
 
 // Vote and median in one pass: streams the first NS slots of every file's permuted row list once (NS = R:
 // every copy; NS = r' = (R+1)/2 in early-majority mode when every file has a probable
-// majority).  Slot 0 (the probable winner) feeds the median network; every equality the
-// probe assumed between neighbouring slots is checked over all coordinates and violations are
-// recorded per file (ws->viol).  No violation -> the probable classes are the true ones, the
-// output and the probable winners are final; otherwise the kernels of the exact path, gated
-// on ws->viol, redo the aggregation.
+// majority).  Slot 0 (the probable winner) feeds the median network, and every pair of slots is
+// compared over all coordinates (ws->pneq), which is the whole of the vote's comparison: the
+// decision kernel behind this one knows the true winners and whether slot 0 held one for
+// every file.
 template <int F, int R, int NS, bool TRIM, int V>
 __device__ __forceinline__ void fused_body(const uint32_t *__restrict__ X, int64_t d, int64_t ld,
                                            const uint64_t *__restrict__ perm_off,
-                                           const uint32_t *__restrict__ chain_mask,
                                            AggWorkspace *ws, int trim_b,
                                            uint32_t *__restrict__ out) {
     const int lane = threadIdx.x & 63;
@@ -1041,7 +1114,14 @@ __device__ __forceinline__ void fused_body(const uint32_t *__restrict__ X, int64
     const int64_t n_thr = (d + V - 1) / V;
     const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     const int64_t c0 = (gt + 1) * V <= d ? gt * V : d - V;
-    uint32_t flags[(F + 63) / 64] = {};  // lane j%64 collects the violation bits of file j
+    uint32_t flags[(F + 63) / 64] = {};  // lane j%64 collects the pair bits of file j
+    // What other waves have published so far, read now so that the wait is over long before the
+    // end: a wave whose bits were all there when it started (all but the first waves of a
+    // launch) ends without touching the shared words at all.
+    uint32_t seen[(F + 63) / 64];
+#pragma unroll
+    for (int w = 0; w < (F + 63) / 64; ++w)
+        seen[w] = 64 * w + lane < F ? load_shared_word(&ws->pneq[64 * w + lane]) : 0u;
     const uint32_t voff = (uint32_t)(c0 * 4);
     const char *Xb = reinterpret_cast<const char *>(X);
     uint32_t key[V][F];       // wire j of the network = file j
@@ -1054,7 +1134,19 @@ __device__ __forceinline__ void fused_body(const uint32_t *__restrict__ X, int64
     // (or, for the trimmed mean, sorting) network whose inputs are complete by then.
 #define BYZ_S_ROW_ADDR(j, k) (Xb + perm_off[(j) * kRowStride + (k)] + voff)
     if constexpr (!TRIM) {
+        // median: every comparator is made to run in the share of the file that completes its
+        // inputs (empty statements the compiler may not move: loads stay in their share, the
+        // wires a share changed are computed by its end), so that a wave has loads in flight
+        // while it works through the network instead of running the whole network at the end
+#undef BYZ_S_STEP
+#undef BYZ_S_PIN
+#define BYZ_S_STEP(j) asm volatile("" ::: "memory");
+#define BYZ_S_PIN(w) _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_) asm volatile("" : "+v"(key[v_][w]));
 #include "generated/selnet_stream_dispatch.inc"
+#undef BYZ_S_STEP
+#undef BYZ_S_PIN
+#define BYZ_S_STEP(j)
+#define BYZ_S_PIN(w)
     } else {
 #include "generated/selnet_sort_stream_dispatch.inc"
         trimmed_mean_of_sorted<F, V>(key, F, trim_b, o);
@@ -1063,19 +1155,20 @@ __device__ __forceinline__ void fused_body(const uint32_t *__restrict__ X, int64
     if (gt < n_thr) store_vec<V>(out + c0, o);
 #pragma unroll
     for (int w = 0; w < (F + 63) / 64; ++w)
-        merge_flags(ws->viol + 64 * w, F - 64 * w < 64 ? F - 64 * w : 64, lane, flags[w]);
+        merge_flags(ws->pneq + 64 * w, F - 64 * w < 64 ? F - 64 * w : 64, lane,
+                    flags[w] & ~seen[w]);
 }
 
 template <int F, int R, bool TRIM, int V>
 __global__ __launch_bounds__(kBlock) void fused_kernel(
     const uint32_t *__restrict__ X, int64_t d, int64_t ld, const uint64_t *__restrict__ perm_off,
-    const uint32_t *__restrict__ chain_mask, const uint32_t *__restrict__ slots_per_file,
-    AggWorkspace *ws, int trim_b, uint32_t *__restrict__ out) {
+    const uint32_t *__restrict__ slots_per_file, AggWorkspace *ws, int trim_b,
+    uint32_t *__restrict__ out) {
     // wave-uniform choice written by the probe
     if (*slots_per_file == (R + 1) / 2)
-        fused_body<F, R, (R + 1) / 2, TRIM, V>(X, d, ld, perm_off, chain_mask, ws, trim_b, out);
+        fused_body<F, R, (R + 1) / 2, TRIM, V>(X, d, ld, perm_off, ws, trim_b, out);
     else
-        fused_body<F, R, R, TRIM, V>(X, d, ld, perm_off, chain_mask, ws, trim_b, out);
+        fused_body<F, R, R, TRIM, V>(X, d, ld, perm_off, ws, trim_b, out);
 }
 
 // ---------------------------------------------------------------------------- launchers
@@ -1093,18 +1186,19 @@ inline unsigned blocks_for(int64_t n_vec) {
 #if BYZ_IN_PART(0)
 template <int R>
 int launch_vote_pairs(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, int f,
-                      uint32_t *neq, const uint32_t *gate, hipStream_t s) {
-    vote_pairs_kernel<R, kVec><<<blocks_for(d / kVec), kBlock, 0, s>>>(X, d, ld, rows, f, neq, gate);
+                      uint32_t *neq, const uint32_t *gate, int gate_n, hipStream_t s) {
+    vote_pairs_kernel<R, kVec><<<blocks_for(d / kVec), kBlock, 0, s>>>(X, d, ld, rows, f, neq, gate,
+                                                                      gate_n);
     BYZ_HIP(hipGetLastError());
     return BYZ_OK;
 }
 
 int launch_vote_pairs_r(int r, const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows,
-                        int f, uint32_t *neq, const uint32_t *gate, hipStream_t s) {
+                        int f, uint32_t *neq, const uint32_t *gate, int gate_n, hipStream_t s) {
     switch (r) {
-        case 3: return launch_vote_pairs<3>(X, d, ld, rows, f, neq, gate, s);
-        case 5: return launch_vote_pairs<5>(X, d, ld, rows, f, neq, gate, s);
-        case 7: return launch_vote_pairs<7>(X, d, ld, rows, f, neq, gate, s);
+        case 3: return launch_vote_pairs<3>(X, d, ld, rows, f, neq, gate, gate_n, s);
+        case 5: return launch_vote_pairs<5>(X, d, ld, rows, f, neq, gate, gate_n, s);
+        case 7: return launch_vote_pairs<7>(X, d, ld, rows, f, neq, gate, gate_n, s);
         default: return BYZ_EINVAL;
     }
 }
@@ -1226,10 +1320,10 @@ int launch_fused(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, 
     const unsigned g = blocks_for((d + V - 1) / V);
     if (trim_b < 0) {
         fused_kernel<F, R, false, V><<<g, kBlock, 0, s>>>(
-            X, d, ld, ws->perm_off, ws->chain_mask, &ws->slots_per_file, ws, 0, out);
+            X, d, ld, ws->perm_off, &ws->slots_per_file, ws, 0, out);
     } else if constexpr (WITH_TRIM) {
         fused_kernel<F, R, true, V><<<g, kBlock, 0, s>>>(
-            X, d, ld, ws->perm_off, ws->chain_mask, &ws->slots_per_file, ws, trim_b, out);
+            X, d, ld, ws->perm_off, &ws->slots_per_file, ws, trim_b, out);
     }
     BYZ_HIP(hipGetLastError());
     return byz_internal_profile_mark(1, s);
@@ -1544,7 +1638,7 @@ extern "C" int byz_vote(const float *copies, int64_t d, int64_t ld, const int32_
     fill_u32_kernel<<<1, kWide, 0, s>>>(pair_neq, f, 0u);
     BYZ_HIP(hipGetLastError());
     if (d > 0) {
-        rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, pair_neq, nullptr, s);
+        rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, pair_neq, nullptr, 0, s);
         if (rc != BYZ_OK) return rc;
     }
     vote_decide_kernel<<<1, kWide, 0, s>>>(pair_neq, file_rows_dev, f, r, winner_replica,
@@ -1630,12 +1724,12 @@ static int aggregate_on_workspace(const float *copies, int64_t d, int64_t ld,
     // (the 169-file single pass is built for the median only)
     if (!has_fused(f, r) || d < kVec || (f == 169 && trim_b >= 0)) {
         // two-step path, unconditionally: vote, then median over the winners
-        reset_workspace_kernel<<<1, kWide, 0, s>>>(ws, 1u);
+        reset_workspace_kernel<<<1, kWide, 0, s>>>(ws, (uint32_t)BYZ_PATH_TWO_STEP);
         BYZ_HIP(hipGetLastError());
         if (d > 0) {
             rc = byz_internal_profile_mark(0, s);
             if (rc != BYZ_OK) return rc;
-            rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, nullptr, s);
+            rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, nullptr, 0, s);
             if (rc != BYZ_OK) return rc;
             rc = byz_internal_profile_mark(1, s);
             if (rc != BYZ_OK) return rc;
@@ -1649,8 +1743,9 @@ static int aggregate_on_workspace(const float *copies, int64_t d, int64_t ld,
         return byz_internal_launch_median(X, d, ld, ws->winner_row, f, O, nullptr, 0, s);
     }
 
-    // probe -> single pass -> exact path, whose three kernels return at once unless the single
-    // pass recorded a violated assumption
+    // probe -> single pass -> decision (one block) -> median, which returns at once unless the
+    // decision found a file whose slot 0 did not hold its winner.  Early-majority mode adds the
+    // gated vote kernel and its decision between the two, for the files whose r' copies differ.
     if (f == 169)
         rc = byz_internal_launch_single_pass_5(f, r, X, d, ld, file_rows_dev, ws, O, probe_opts, trim_b, s);
     else if (f == 121)
@@ -1662,16 +1757,18 @@ static int aggregate_on_workspace(const float *copies, int64_t d, int64_t ld,
     else
         rc = byz_internal_launch_single_pass_1(f, r, X, d, ld, file_rows_dev, ws, O, probe_opts, trim_b, s);
     if (rc != BYZ_OK) return rc;
-    rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, ws->viol, s);
-    if (rc != BYZ_OK) return rc;
-    vote_decide_gated_kernel<<<1, kWide, 0, s>>>(ws->pair_neq, file_rows_dev, f, r, ws->viol,
-                                                 ws->prov_winner, winner_replica, ws->winner_row,
-                                                 &ws->need_exact);
+    single_pass_decide_kernel<<<1, kWide, 0, s>>>(ws, file_rows_dev, f, r, winner_replica);
     BYZ_HIP(hipGetLastError());
+    if ((flags & BYZ_AGG_EARLY_MAJORITY) != 0) {
+        rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, &ws->need_revote, 1, s);
+        if (rc != BYZ_OK) return rc;
+        revote_decide_kernel<<<1, kWide, 0, s>>>(ws, file_rows_dev, f, r, winner_replica);
+        BYZ_HIP(hipGetLastError());
+    }
     if (trim_b >= 0)
-        return byz_internal_launch_trimmed_mean(X, d, ld, ws->winner_row, f, trim_b, O, ws->viol, f,
-                                                s);
-    return byz_internal_launch_median(X, d, ld, ws->winner_row, f, O, ws->viol, f, s);
+        return byz_internal_launch_trimmed_mean(X, d, ld, ws->winner_row, f, trim_b, O,
+                                                &ws->need_median, 1, s);
+    return byz_internal_launch_median(X, d, ld, ws->winner_row, f, O, &ws->need_median, 1, s);
 }
 
 extern "C" int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld,
@@ -1795,15 +1892,14 @@ extern "C" int byz_profile_collect(float *ms_out, int capacity, int *n_out) {
     return BYZ_OK;
 }
 
-extern "C" int byz_aggregate_took_exact_path(const void *workspace, int *took_exact_path,
-                                             void *stream) {
-    if (workspace == nullptr || took_exact_path == nullptr) return BYZ_EINVAL;
+extern "C" int byz_aggregate_path(const void *workspace, int *path, void *stream) {
+    if (workspace == nullptr || path == nullptr) return BYZ_EINVAL;
     const AggWorkspace *ws = reinterpret_cast<const AggWorkspace *>(workspace);
     uint32_t v = 0;
     hipStream_t s = (hipStream_t)stream;
-    BYZ_HIP(hipMemcpyAsync(&v, &ws->need_exact, sizeof(v), hipMemcpyDeviceToHost, s));
+    BYZ_HIP(hipMemcpyAsync(&v, &ws->path, sizeof(v), hipMemcpyDeviceToHost, s));
     BYZ_HIP(hipStreamSynchronize(s));
-    *took_exact_path = (int)v;
+    *path = (int)v;
     return BYZ_OK;
 }
 

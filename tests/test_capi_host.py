@@ -32,10 +32,15 @@ def _build(scheme, a, b):
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "byzshield.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    names = sorted(set(re.findall(r"\b(byz_[a-z_0-9]+)\s*\(", header)))
-    assert len(names) >= 14
+    names = set()
+    for h in ("byzshield.h", "byzshield_bench.h"):
+        header = open(os.path.join(ROOT, "include", h)).read()
+        header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+        found = set(re.findall(r"\b(byz_[a-z_0-9]+)\s*\(", header))
+        assert len(found) >= 5, h
+        names |= found
+    names = sorted(names)
+    assert len(names) >= 30
     lib = ctypes.CDLL(B.library_path())
     for n in names:
         assert hasattr(lib, n), n
@@ -47,12 +52,15 @@ def test_header_is_plain_c_and_agrees_with_the_binding(tmp_path):
     src = tmp_path / "consts.c"
     src.write_text('''#include <stdio.h>
 #include "byzshield.h"
+#include "byzshield_bench.h"
 int main(void) {
     printf("%d %d %d %d\\n", BYZ_MAX_F, BYZ_MAX_F_KRUM, BYZ_MAX_F_WIDE, BYZ_MAX_R);
     printf("%u %u %u %u\\n", BYZ_AGG_EARLY_MAJORITY, BYZ_AGG_TRIM(7), BYZ_AGG_PROBE_SHIFT(0x1234),
            BYZ_AGG_PROBE_SHIFT(0x12345));
     printf("%d %d %d\\n", (int)BYZ_SCHEME_MOLS, (int)BYZ_SCHEME_RAMANUJAN, (int)BYZ_SCHEME_FRC);
     printf("%u %u\\n", (unsigned)BYZ_SEARCH_EXHAUSTIVE, (unsigned)BYZ_SEARCH_SYMMETRY);
+    printf("%d %d %d %d\\n", (int)BYZ_PATH_SINGLE_PASS, (int)BYZ_PATH_MEDIAN_REDONE,
+           (int)BYZ_PATH_REVOTED, (int)BYZ_PATH_TWO_STEP);
     return 0;
 }
 ''')
@@ -66,6 +74,8 @@ int main(void) {
                                                   B.BYZ_AGG_PROBE_SHIFT(0x1234), B.BYZ_AGG_PROBE_SHIFT(0x12345)]
     assert [int(x) for x in lines[2].split()] == [B.BYZ_SCHEME_MOLS, B.BYZ_SCHEME_RAMANUJAN, B.BYZ_SCHEME_FRC]
     assert [int(x) for x in lines[3].split()] == [B.BYZ_SEARCH_EXHAUSTIVE, B.BYZ_SEARCH_SYMMETRY]
+    assert [int(x) for x in lines[4].split()] == [B.BYZ_PATH_SINGLE_PASS, B.BYZ_PATH_MEDIAN_REDONE,
+                                                  B.BYZ_PATH_REVOTED, B.BYZ_PATH_TWO_STEP]
 
 
 def test_table2_through_the_library():

@@ -24,7 +24,11 @@ CONST = {"kind": "constant", "value": 1e3}
 MIXED = {"kind": "mixed", "z": 1.0, "value": 1e3, "file_scales": True}
 
 
-def _check_all(X, rows_np, d, f, r, expect_exact=None, tag=""):
+SINGLE, REDONE, REVOTED, TWO_STEP = (B.BYZ_PATH_SINGLE_PASS, B.BYZ_PATH_MEDIAN_REDONE,
+                                     B.BYZ_PATH_REVOTED, B.BYZ_PATH_TWO_STEP)
+
+
+def _check_all(X, rows_np, d, f, r, expect_path=None, tag=""):
     """Runs vote, median-on-winners and aggregate on the GPU and compares with the oracle."""
     Xh = X.detach().cpu().numpy()
     rows_dev = torch.tensor(rows_np.reshape(-1), dtype=torch.int32, device=DEV)
@@ -46,9 +50,14 @@ def _check_all(X, rows_np, d, f, r, expect_exact=None, tag=""):
         torch.cuda.synchronize()
         assert np.array_equal(W.bits(out), W.bits(out_o)), (tag, flags)
         assert np.array_equal(wrep2.cpu().numpy(), wrep_o), (tag, flags)
-        took_exact = B.byz_aggregate_took_exact_path(ws)
-        if expect_exact is not None and flags == 0:
-            assert took_exact == expect_exact, tag
+        path = B.byz_aggregate_path(ws)
+        if flags == 0:
+            # without early-majority mode the copies are never compared a second time
+            assert path in (SINGLE, REDONE, TWO_STEP), (tag, path)
+            if expect_path is not None:
+                assert path == expect_path, (tag, path)
+        else:
+            assert path in (SINGLE, REDONE, REDONE | REVOTED, TWO_STEP), (tag, path)
     out, wrep2, ws = B.byz_aggregate(X, d, rows_dev, f, r)
     torch.cuda.synchronize()
     assert np.array_equal(W.bits(out), W.bits(out_o)), tag
@@ -62,7 +71,7 @@ def _check_all(X, rows_np, d, f, r, expect_exact=None, tag=""):
         torch.cuda.synchronize()
         assert np.array_equal(W.bits(out_t), W.bits(out_t2)), (tag, flags)
         assert np.array_equal(wrep3.cpu().numpy(), wrep_o), (tag, flags)
-    return out_o, wrep_o, took_exact
+    return out_o, wrep_o, path
 
 
 SMALL_D = [1, 2, 3, 5, 63, 64, 255, 1000, 4099, 70001]
@@ -85,7 +94,7 @@ def test_small_sizes_all_layouts(scheme, a, b, q, attack):
 
 def test_all_honest_reproduces_the_honest_median():
     w = W.make(MOLS, 5, 3, 0, 5000, REVERSED, seed=1, device=DEV)
-    out_o, wrep_o, took_exact = _check_all(w.X, w.file_rows, w.d, w.f, w.r, expect_exact=False)
+    out_o, wrep_o, _ = _check_all(w.X, w.file_rows, w.d, w.f, w.r, expect_path=SINGLE)
     assert (wrep_o == 0).all()
     honest = np.median(w.G.cpu().numpy(), axis=0)
     assert np.array_equal(W.bits(out_o), W.bits(honest))
@@ -99,7 +108,7 @@ def test_unaligned_base_pointer():
     Xs = buf[1:].view(R, ld)
     Xs.copy_(w.X)
     assert Xs.data_ptr() % 8 == 4
-    _check_all(Xs, w.file_rows, w.d, w.f, w.r, expect_exact=False)
+    _check_all(Xs, w.file_rows, w.d, w.f, w.r, expect_path=SINGLE)
 
 
 def test_generic_shapes_without_a_generated_network():
@@ -107,7 +116,7 @@ def test_generic_shapes_without_a_generated_network():
     # r = 7 (Ramanujan s=7, m=7): two-step path with the f = 49 network
     for (a, b, q) in [(3, 9, 2), (7, 7, 5)]:
         w = W.make(RAM, a, b, q, 2222, CONST, seed=3, device=DEV)
-        _check_all(w.X, w.file_rows, w.d, w.f, w.r, expect_exact=True)
+        _check_all(w.X, w.file_rows, w.d, w.f, w.r, expect_path=TWO_STEP)
     # byz_median alone for assorted odd f, including rows used more than once
     rng = np.random.default_rng(5)
     X = torch.randn(70, 1500, device=DEV)
@@ -124,32 +133,64 @@ def _plant(X, rows_np, j, k, coords, value):
 
 
 def test_copy_that_matches_on_the_probe_sample_but_differs_elsewhere():
-    # The probe looks at 16 runs of 16 coordinates; a copy that differs only outside them
-    # is caught by the streaming pass and the exact path must take over.
+    # The probe looks at 16 runs of 16 coordinates; a copy that differs only outside them is
+    # found by the streaming pass, which compares every pair of copies everywhere.  What that
+    # costs depends on which copy it is: nothing unless it is the one the probe guessed as its
+    # file's winner (slot 0 of the file: the lowest replica of the class that looked largest),
+    # one more median over the winners if it is.  The copies are never compared again.
     d = 100_000
     w = W.make(MOLS, 5, 3, 0, d, REVERSED, seed=4, device=DEV)
     stride = (d - 16) // 15  # start of run u is u * stride
     unsampled = [c for c in (17, stride - 1, d - 17, d // 2 + 19) if (c % stride) >= 16]
     assert unsampled
-    X = w.X.clone()
-    # replicas 0 and 2 of file 3 both deviate (identically) at unsampled coordinates:
-    # the true winner is replica 0's value {0,2}; the probe thinks all three are equal
-    for k in (0, 2):
-        _plant(X, w.file_rows, 3, k, unsampled, 7.0)
-    # replica 0 of file 8 deviates alone: winner class {1,2}, winner replica 1
-    _plant(X, w.file_rows, 8, 0, unsampled[:1], -3.0)
-    out_o, wrep_o, took_exact = _check_all(X, w.file_rows, d, w.f, w.r, expect_exact=True)
-    assert wrep_o[3] == 0 and wrep_o[8] == 1
-    # a copy that differs only in the very last coordinate (outside the sample) -> exact path
+    # one changed word in a copy that is not the guessed one (replica 1, replica 2; first,
+    # middle, last coordinate region): the true classes {0,2},{1} resp. {0,1},{2} are known
+    # after the pass, replica 0 fed the network and is the winner -> no further pass
+    for k, c in [(1, unsampled[0]), (2, unsampled[1]), (1, d - 1), (2, d // 2 + 19)]:
+        X1 = w.X.clone()
+        _plant(X1, w.file_rows, 5, k, [c], 9.0)
+        out_o, wrep_o, _ = _check_all(X1, w.file_rows, d, w.f, w.r, expect_path=SINGLE, tag=(k, c))
+        assert wrep_o[5] == 0
+    # one changed word in the guessed copy (replica 0): classes {0},{1,2}, winner replica 1 ->
+    # the median is redone from the true winners, nothing else
     X2 = w.X.clone()
-    _plant(X2, w.file_rows, 5, 1, [d - 1], 9.0)
-    out_o, wrep_o, _ = _check_all(X2, w.file_rows, d, w.f, w.r, expect_exact=True)
-    assert wrep_o[5] == 0
-    # a copy that differs at one sampled coordinate only -> the probe sees it, fast path
+    _plant(X2, w.file_rows, 8, 0, unsampled[:1], -3.0)
+    out_o, wrep_o, _ = _check_all(X2, w.file_rows, d, w.f, w.r, expect_path=REDONE)
+    assert wrep_o[8] == 1
+    # replicas 0 and 2 of file 3 both deviate (identically) off the sample: the probe thinks all
+    # three are equal, the true classes are {0,2},{1}, and the guessed copy is still a winner
     X3 = w.X.clone()
-    _plant(X3, w.file_rows, 5, 0, [5 * stride + 3], 9.0)
-    out_o, wrep_o, _ = _check_all(X3, w.file_rows, d, w.f, w.r, expect_exact=False)
+    for k in (0, 2):
+        _plant(X3, w.file_rows, 3, k, unsampled, 7.0)
+    out_o, wrep_o, _ = _check_all(X3, w.file_rows, d, w.f, w.r, expect_path=SINGLE)
+    assert wrep_o[3] == 0
+    # replicas 0 and 2 deviate differently: three distinct copies, replica 0 wins the tie and
+    # is the guessed copy
+    X4 = X3.clone()
+    _plant(X4, w.file_rows, 3, 2, unsampled[:1], 8.0)
+    out_o, wrep_o, _ = _check_all(X4, w.file_rows, d, w.f, w.r, expect_path=SINGLE)
+    assert wrep_o[3] == 0
+    # a copy that differs at one sampled coordinate only -> the probe sees it and guesses right
+    X5 = w.X.clone()
+    _plant(X5, w.file_rows, 5, 0, [5 * stride + 3], 9.0)
+    out_o, wrep_o, _ = _check_all(X5, w.file_rows, d, w.f, w.r, expect_path=SINGLE)
     assert wrep_o[5] == 1
+    # r = 5: the guessed copy of a file differs off the sample while two Byzantine copies agree
+    # with each other: 1 + 2 + 2 -> the lowest honest replica left wins; median redone once
+    w5 = W.make(RAM, 5, 5, 0, d, REVERSED, seed=5, device=DEV)
+    Y = w5.X.clone()
+    _plant(Y, w5.file_rows, 6, 0, unsampled[:1], 5.0)
+    for k in (3, 4):
+        Y[int(w5.file_rows[6, k])] = -100.0 * w5.G[6]
+    out_o, wrep_o, _ = _check_all(Y, w5.file_rows, d, w5.f, w5.r, expect_path=REDONE)
+    assert wrep_o[6] == 1
+    # the same with the off-sample word in replica 2 instead: nothing to redo
+    Y2 = w5.X.clone()
+    _plant(Y2, w5.file_rows, 6, 2, unsampled[:1], 5.0)
+    for k in (3, 4):
+        Y2[int(w5.file_rows[6, k])] = -100.0 * w5.G[6]
+    out_o, wrep_o, _ = _check_all(Y2, w5.file_rows, d, w5.f, w5.r, expect_path=SINGLE)
+    assert wrep_o[6] == 0
 
 
 def test_no_majority_and_ties():
@@ -215,7 +256,7 @@ def test_special_values_nan_inf_signed_zero():
     for j in range(w.f):
         for k in range(w.r):
             Xr[int(w.file_rows[j, k])] = U[j]
-    _check_all(Xr.view(torch.float32), w.file_rows, d, w.f, w.r, expect_exact=False)
+    _check_all(Xr.view(torch.float32), w.file_rows, d, w.f, w.r, expect_path=SINGLE)
 
 
 def test_argument_errors():
@@ -272,27 +313,34 @@ def test_probe_sample_shift(scheme, a, b, q):
             torch.cuda.synchronize()
             assert np.array_equal(W.bits(out), W.bits(out_o)), (s, extra)
             assert np.array_equal(wrep.cpu().numpy(), wrep_o), (s, extra)
-            assert not B.byz_aggregate_took_exact_path(ws), (s, extra)
-    # one honest copy (not the first of its file) differs in a single word.  With shift 0 that
-    # word is one of the sampled ones (run 3, word 5 of the 16 runs (d - 16) / 15 apart): the
-    # probe sees the difference and the single pass stands.  Other shifts sample elsewhere: the
-    # single pass finds its assumption violated and the exact path runs.  Same result always.
+            assert B.byz_aggregate_path(ws) == SINGLE, (s, extra)
+    # One honest copy differs in a single word.  With shift 0 that word is one of the sampled
+    # ones (run 3, word 5 of the 16 runs (d - 16) / 15 apart), other shifts sample elsewhere.
+    # If the copy is not the first of its file nothing depends on that: the first copy is guessed
+    # and is the winner either way.  If it is the first, the probe that sees the word guesses
+    # the second copy (right), the others guess the first and the median is redone.  Moving the
+    # sample is therefore no protection; the bounded cost is.  Same result always.
     clean = [j for j in range(w.f) if not any(int(x) in w.byz for x in w.file_workers[j])]
     c_star = 3 * ((d - 16) // 15) + 5
-    P = w.X.clone()
-    P[int(w.file_rows[clean[0], 1]), c_star] += 1.0
-    Ph = P.cpu().numpy()
-    wrep_p, wrow_p, neq_p = C.vote(Ph, w.file_rows, d)
-    out_p = C.median(Ph, wrow_p, d)
-    assert neq_p[clean[0]] != 0 and np.array_equal(wrep_p, wrep_o)
-    took = {}
-    for s in shifts:
-        out, wrep, ws = B.byz_aggregate_opts(P, d, rows_dev, w.f, w.r, B.BYZ_AGG_PROBE_SHIFT(s))
-        torch.cuda.synchronize()
-        assert np.array_equal(W.bits(out), W.bits(out_p)), s
-        assert np.array_equal(wrep.cpu().numpy(), wrep_p), s
-        took[s] = bool(B.byz_aggregate_took_exact_path(ws))
-    assert took[0] is False and sum(took.values()) >= len(shifts) - 2, took
+    for k in (1, 0):
+        P = w.X.clone()
+        P[int(w.file_rows[clean[0], k]), c_star] += 1.0
+        Ph = P.cpu().numpy()
+        wrep_p, wrow_p, neq_p = C.vote(Ph, w.file_rows, d)
+        out_p = C.median(Ph, wrow_p, d)
+        assert neq_p[clean[0]] != 0 and wrep_p[clean[0]] == (1 if k == 0 else 0)
+        paths = {}
+        for s in shifts:
+            out, wrep, ws = B.byz_aggregate_opts(P, d, rows_dev, w.f, w.r, B.BYZ_AGG_PROBE_SHIFT(s))
+            torch.cuda.synchronize()
+            assert np.array_equal(W.bits(out), W.bits(out_p)), s
+            assert np.array_equal(wrep.cpu().numpy(), wrep_p), s
+            paths[s] = B.byz_aggregate_path(ws)
+        if k == 1:
+            assert all(v == SINGLE for v in paths.values()), paths
+        else:
+            assert paths[0] == SINGLE and set(paths.values()) <= {SINGLE, REDONE}, paths
+            assert sum(v == REDONE for v in paths.values()) >= len(shifts) - 2, paths
 
 
 def test_generator_same_bytes_on_cpu_and_gpu():
@@ -308,14 +356,14 @@ def test_largest_shapes_f63_r7():
     # l=9: two-step path, 21 pair bits per file, rank-counting median
     w = W.make(RAM, 7, 9, 6, 1537, MIXED, seed=12, device=DEV)
     assert (w.K, w.f, w.l, w.r) == (49, 63, 9, 7)
-    _check_all(w.X, w.file_rows, w.d, w.f, w.r, expect_exact=True)
+    _check_all(w.X, w.file_rows, w.d, w.f, w.r, expect_path=TWO_STEP)
     # every copy of one file different (seven singletons), 3-3-1 and 2-2-2-1 splits on others
     X = w.X.clone()
     for j, labels in enumerate([[0, 1, 2, 3, 4, 5, 6], [1, 0, 1, 0, 1, 0, 2], [0, 0, 1, 1, 2, 2, 3],
                                 [3, 2, 2, 1, 1, 1, 0]]):
         for k, lab in enumerate(labels):
             X[int(w.file_rows[j, k])] = w.G[j] * float(1 + lab)
-    out_o, wrep_o, _ = _check_all(X, w.file_rows, w.d, w.f, w.r, expect_exact=True)
+    out_o, wrep_o, _ = _check_all(X, w.file_rows, w.d, w.f, w.r, expect_path=TWO_STEP)
     assert wrep_o[:4].tolist() == [0, 0, 0, 3]
 
 
@@ -339,7 +387,7 @@ def test_hip_graph_capture_and_replay():
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         B.byz_aggregate(Xs, w.d, rows_dev, w.f, w.r, out=out, winner_replica=wrep, workspace=ws)
-    # second input: another Byzantine payload, a copy that defeats the probe (exact path)
+    # second input: a guessed copy that differs off the probe's sample (the median is redone)
     X2 = w.X.clone()
     X2[int(w.file_rows[3, 0]), 12345] = 7.0
     out_e2, wrep_e2, ws_e2 = B.byz_aggregate(X2, w.d, rows_dev, w.f, w.r)
@@ -357,7 +405,7 @@ def test_hip_graph_capture_and_replay():
         chk, _, _ = B.byz_aggregate(src, w.d, rows_dev, w.f, w.r)
         torch.cuda.synchronize()
         assert torch.equal(chk.view(torch.int32), want_out.view(torch.int32))
-    assert wrep_e2[3].item() == 1 and B.byz_aggregate_took_exact_path(ws_e2)
+    assert wrep_e2[3].item() == 1 and B.byz_aggregate_path(ws_e2) == REDONE
 
 
 def test_read_rows_reference_kernel():
@@ -477,7 +525,7 @@ def test_more_than_64_files(scheme, a, b, q, attack):
         ld = d if i % 2 == 0 else synth.padded_ld(d, 4) + 4
         w = W.make(scheme, a, b, q, d, attack, seed=700 + i, ld=ld, device=DEV)
         assert w.f > 64
-        out_o, wrep_o, took_exact = _check_all(w.X, w.file_rows, d, w.f, w.r, tag=(w.f, d))
+        out_o, wrep_o, _ = _check_all(w.X, w.file_rows, d, w.f, w.r, tag=(w.f, d))
         idx = np.array([w.file_rows[j, wrep_o[j]] for j in range(w.f)], dtype=np.int32)
         for trim in (0, w.cmax, (w.f - 1) // 2):
             _trimmed_mean_check(w.X, idx, d, trim, (w.f, d, trim))
