@@ -1,8 +1,8 @@
 """Benchmark of the ByzShield aggregation path (majority vote + coordinate-wise median) on one MI355X.
 
 A step is one pass of the whole path (byz_aggregate: probe, single-pass vote+median kernel,
-gated exact path) over one batch of stacked worker returns that is
-already resident in HBM.  Prints ONE JSON line.
+decision, gated median) over one batch of stacked worker returns that is already resident in
+HBM.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--unpadded] [--no-cpu]
 """
@@ -34,10 +34,13 @@ def kernel_code_digest():
 
 
 def _traffic_from_profiles(workload, kernel="fused_kernel"):
-    """HBM bytes per launch from the committed counter summary, or None if absent or stale."""
-    path = os.path.join(ROOT, "profiles", "%s_%s_hbm_traffic.txt" % (kernel, workload))
+    """(HBM bytes per launch, where the figure comes from) from the committed rocprofv3 counter
+    summary of this kernel and workload; (None, why) if there is none or the kernels' code has
+    changed since the counters were taken.  Nothing is counted during the benchmark run."""
+    name = "%s_%s_hbm_traffic.txt" % (kernel, workload)
+    path = os.path.join(ROOT, "profiles", name)
     if not os.path.exists(path):
-        return None
+        return None, "no counter summary profiles/%s" % name
     kv = {}
     with open(path) as fh:
         for line in fh:
@@ -45,11 +48,35 @@ def _traffic_from_profiles(workload, kernel="fused_kernel"):
                 k, v = line.strip().split("=", 1)
                 kv[k.strip()] = v.strip()
     if kv.get("kernels_hip_code_sha256") != kernel_code_digest():
-        return None  # the kernels' code changed since the counters were taken
+        return None, "profiles/%s is older than the kernels' code" % name
     try:
-        return float(kv["hbm_bytes_per_launch"])
+        return float(kv["hbm_bytes_per_launch"]), (
+            "profiles/%s: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this "
+            "command, scaled by the calibration copy; code digest matches" % name)
     except (KeyError, ValueError):
-        return None
+        return None, "profiles/%s has no hbm_bytes_per_launch" % name
+
+
+def _cpu_model():
+    """'model name' of /proc/cpuinfo plus family/model/stepping (virtual machines often shorten
+    the name) and the number of logical CPUs this process may use."""
+    info = {}
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if ":" in line:
+                    k, v = line.split(":", 1)
+                    k = k.strip()
+                    if k in ("model name", "vendor_id", "cpu family", "model", "stepping") and k not in info:
+                        info[k] = v.strip()
+                if len(info) == 5:
+                    break
+    except OSError:
+        pass
+    usable = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    return "%s (%s family %s model %s stepping %s), %d logical CPUs usable" % (
+        info.get("model name", "unknown"), info.get("vendor_id", "?"), info.get("cpu family", "?"),
+        info.get("model", "?"), info.get("stepping", "?"), usable)
 
 
 def main():
@@ -61,6 +88,8 @@ def main():
     ap.add_argument("--unpadded", action="store_true", help="row pitch ld = d instead of d rounded up to 64")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-early", action="store_true", help="skip the early-majority leg")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="skip the adversarial, repeat and graph-replay legs (profiling runs)")
     ap.add_argument("--components", action="store_true",
                     help="also time the two-step path's kernels (byz_vote, byz_median) on their own")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -104,26 +133,29 @@ def main():
     ws = torch.empty(B.byz_aggregate_workspace_bytes(asg.f, asg.r), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
 
-    def step(i, flags=0):
+    def step(i, flags=0, on=stream):
         B.byz_aggregate_opts(bufs[i % n_buf], d, rows_dev, asg.f, asg.r, flags, out=out,
-                             winner_replica=wrep, workspace=ws, stream=stream)
+                             winner_replica=wrep, workspace=ws, stream=on)
 
-    def timed(flags):
-        """W warm-up steps, then K timed steps; returns (ms per step, kernel ms list, exact?)."""
+    def timed(flags, profile=True):
+        """W warm-up steps, then K timed steps; returns (ms per step, kernel ms list, byz_path)."""
         for i in range(args.warmup):
             step(i, flags)
         torch.cuda.synchronize()
-        exact = B.byz_aggregate_path(ws)
-        B.byz_profile_enable(args.steps)
+        path = B.byz_aggregate_path(ws)
+        if profile:
+            B.byz_profile_enable(args.steps)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(args.steps):
             step(i, flags)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        kernel_ms = B.byz_profile_collect(args.steps)
-        B.byz_profile_enable(0)
-        return (t1 - t0) * 1e3 / args.steps, kernel_ms, exact
+        kernel_ms = []
+        if profile:
+            kernel_ms = B.byz_profile_collect(args.steps)
+            B.byz_profile_enable(0)
+        return (t1 - t0) * 1e3 / args.steps, kernel_ms, path
 
     if args.calibration_copy:
         # a plain copy of known size: reads 2^30 bytes and writes 2^30 bytes
@@ -136,7 +168,12 @@ def main():
         del src, dst
 
     single_pass = B.byz_aggregate_has_single_pass(asg.f, asg.r)
-    ms_per_step, kernel_ms, exact = timed(0)
+    # The timed region: K steps back to back, nothing else on the stream.  The dominant kernel's
+    # duration comes from a second region of the same K steps with a HIP event before and after
+    # that kernel in every step (byz_profile_enable); those events sit between the launches and
+    # cost a few microseconds per step, so they stay out of the headline region.
+    ms_per_step, _, path = timed(0, profile=False)
+    ms_per_step_events, kernel_ms, _ = timed(0)
     coords_per_s = d / (ms_per_step * 1e-3)
     if single_pass:
         alg_bytes = 4.0 * (asg.r * asg.f + 1) * d  # every copy read once, one value written
@@ -161,33 +198,94 @@ def main():
         "config": {"workload": cfg.name, "d": d, "ld": ld, "K": asg.K, "f": asg.f, "r": asg.r,
                    "l": asg.l, "q": cfg.q, "c_max": cmax, "attack": cfg.attack["kind"],
                    "rows": asg.f * asg.r, "input_bytes": 4 * asg.f * asg.r * d, "rotating_buffers": n_buf,
-                   "path": int(exact)},
+                   "byz_path": int(path)},
         "step_hbm_gbps_algorithmic": alg_bytes / (ms_per_step * 1e-3) / 1e9,
+        "step_hbm_frac_algorithmic": alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "ms_per_step_with_kernel_events": ms_per_step_events,
     }
     if kernel_ms:
         avg_ms = sum(kernel_ms) / len(kernel_ms)
         achieved = kernel_bytes / (avg_ms * 1e-3) / 1e9
+        traffic, traffic_source = _traffic_from_profiles(
+            cfg.name, "fused_kernel" if single_pass else "vote_pairs_kernel")
         result["roofline"] = {
             "bound": "hbm", "kernel": kernel_name,
             "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBPS,
-            "traffic": _traffic_from_profiles(cfg.name, "fused_kernel" if single_pass else "vote_pairs_kernel"),
+            "traffic": traffic, "traffic_source": traffic_source,
             "algorithmic_bytes_per_launch": kernel_bytes,
             "avg_kernel_ms": avg_ms, "median_kernel_ms": sorted(kernel_ms)[len(kernel_ms) // 2],
             "min_kernel_ms": min(kernel_ms), "launches_timed": len(kernel_ms),
+            "timed_by": "HIP events around this kernel in each of K steps on the launch stream "
+                        "(second region; see ms_per_step_with_kernel_events)",
         }
+
+    if not args.no_extra:
+        # the same K-step region four more times: how much one region scatters
+        result["ms_per_step_repeats"] = [timed(0, profile=False)[0] for _ in range(4)]
+
+    # What a Byzantine worker can do to the time (Sec. 2: the adversary knows everything): send
+    # its honest vector with one word changed where the probe does not look.  If that copy is
+    # not the one the probe guessed for its file, nothing happens; if it is (here: the first
+    # copy of a file no Byzantine worker holds), the median is redone from the true winners.
+    # `adversarial_ms_per_step` is that worst case; the output stays the oracle's either way.
+    clean = [j for j in range(asg.f) if not any(int(w) in set(int(b) for b in byz) for w in fw[j])]
+    if single_pass and not args.no_extra and clean and d > 1000:
+        c_hidden = d // 2 + 7
+        for k, key in ((1, "changed_word_in_another_copy"), (0, "changed_word_in_the_guessed_copy")):
+            saved = [b[int(rows[clean[0], k]), c_hidden].clone() for b in bufs]
+            for b in bufs:
+                b[int(rows[clean[0], k]), c_hidden] += 1.0
+            a_ms, _, a_path = timed(0, profile=False)
+            for b, s in zip(bufs, saved):
+                b[int(rows[clean[0], k]), c_hidden] = s
+            result[key] = {"ms_per_step": a_ms, "byz_path": int(a_path),
+                           "value": d / (a_ms * 1e-3), "unit": "coords/s"}
+        result["adversarial_ms_per_step"] = result["changed_word_in_the_guessed_copy"]["ms_per_step"]
+        result["adversarial_note"] = (
+            "one word of one copy changed off the probe's sample; worst case = the copy the probe "
+            "guessed (byz_path 1: single pass + median over the winners), other copies cost nothing")
+
+    # The same steps replayed from a HIP graph (n_buf consecutive steps captured once): what is
+    # left of the launch gaps between the four kernels of a step.
+    if not args.no_extra:
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            for i in range(n_buf):
+                step(i, 0, on=side)
+        stream.wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(n_buf):
+                step(i, 0, on=torch.cuda.current_stream())
+        reps = max(args.steps // n_buf, 1)
+        for _ in range(2):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - t0) * 1e3 / (reps * n_buf)
+        result["hip_graph_replay"] = {"ms_per_step": g_ms, "value": d / (g_ms * 1e-3), "unit": "coords/s",
+                                      "steps_per_graph": n_buf, "replays": reps,
+                                      "step_hbm_frac_algorithmic": alg_bytes / (g_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+        del graph
 
     # Same result with fewer bytes: r' identical copies already are the majority, so the
     # other r - r' copies of a file need not be read (BYZ_AGG_EARLY_MAJORITY).  Reported
     # beside the headline, never as `value`.
     if not args.no_early and single_pass:
         rp = (asg.r + 1) // 2
-        e_ms, e_kernel_ms, e_exact = timed(B.BYZ_AGG_EARLY_MAJORITY)
+        e_ms, _, e_path = timed(B.BYZ_AGG_EARLY_MAJORITY, profile=False)
+        _, e_kernel_ms, _ = timed(B.BYZ_AGG_EARLY_MAJORITY)
         e_bytes = 4.0 * (rp * asg.f + 1) * d
         e_avg = sum(e_kernel_ms) / len(e_kernel_ms) if e_kernel_ms else None
         result["early_majority"] = {
             "value": d / (e_ms * 1e-3), "unit": "coords/s", "ms_per_step": e_ms,
-            "path": int(e_exact),
+            "byz_path": int(e_path),
             "note": "reads r'=%d of r=%d copies of a file when the probe finds a majority class; "
                     "falls back to all r (as the headline run) if any file has none" % (rp, asg.r),
             "roofline": None if e_avg is None else {
@@ -226,19 +324,17 @@ def main():
         if asg.f <= B.BYZ_MAX_F_KRUM:
             ms_bu = timed_call(lambda: B.byz_bulyan(bufs[0], d, wrow_v, bu_c, out=out,
                                                     workspace=mk_ws, stream=stream))
-        # the path taken when the single pass finds its assumption violated: one word of one honest
-        # copy (not the first of its file) differs at a coordinate the probe does not sample
-        ms_exact, exact_taken = None, False
-        if B.byz_aggregate_has_single_pass(asg.f, asg.r) and d > 1000:
-            clean = [j for j in range(asg.f) if not any(int(w) in set(int(b) for b in byz) for w in fw[j])]
-            if clean:
-                planted = bufs[0].clone()
-                planted[int(rows[clean[0], 1]), d // 2 + 7] += 1.0
-                ms_exact = timed_call(lambda: B.byz_aggregate_opts(planted, d, rows_dev, asg.f, asg.r, 0,
-                                                                   out=out, winner_replica=wrep,
-                                                                   workspace=ws, stream=stream))
-                exact_taken = int(B.byz_aggregate_path(ws))
-                del planted
+        # early-majority mode when its assumption breaks (one changed word in one of the r' copies
+        # it reads of a clean file): single pass, vote over all copies, median
+        ms_revote, revote_path = None, None
+        if single_pass and d > 1000 and clean:
+            planted = bufs[0].clone()
+            planted[int(rows[clean[0], 1]), d // 2 + 7] += 1.0
+            ms_revote = timed_call(lambda: B.byz_aggregate_opts(
+                planted, d, rows_dev, asg.f, asg.r, B.BYZ_AGG_EARLY_MAJORITY, out=out,
+                winner_replica=wrep, workspace=ws, stream=stream))
+            revote_path = int(B.byz_aggregate_path(ws))
+            del planted
         # what a kernel that only reads the r*f rows the way the single pass does can reach,
         # without and with the one output row
         n_rows = asg.f * asg.r
@@ -269,13 +365,11 @@ def main():
                 "note": "byz_calibration_read_rows: the single pass's loads (and its store) with "
                         "no vote and no median; the gap between the two is what writing 1/(rf+1) "
                         "of the bytes costs"},
-            "byz_aggregate_exact_path": None if ms_exact is None else {
-                "ms": ms_exact, "path": exact_taken,
-                "algorithmic_bytes": alg_bytes + vb + mb,
-                "gbps": (alg_bytes + vb + mb) / ms_exact / 1e6,
-                "frac": (alg_bytes + vb + mb) / ms_exact / 1e6 / HBM_PEAK_GBPS,
-                "note": "one planted difference outside the probe's sample: single pass, then the "
-                        "vote over all copies and the median of the winners"},
+            "early_majority_revote": None if ms_revote is None else {
+                "ms": ms_revote, "byz_path": revote_path,
+                "algorithmic_bytes": 4.0 * (((asg.r + 1) // 2) * asg.f + 1) * d + vb + mb,
+                "note": "early-majority mode with one changed word in one of the r' copies it reads: "
+                        "single pass over r' copies, then the vote over all copies and the median"},
             "byz_multi_krum": None if ms_mk is None else {
                 "ms": ms_mk, "c": cmax, "m": mk_m, "algorithmic_bytes": kb,
                 "gbps": kb / ms_mk / 1e6, "frac": kb / ms_mk / 1e6 / HBM_PEAK_GBPS,
@@ -291,16 +385,23 @@ def main():
         }
 
     if not args.no_cpu:
+        # The oracle as it stands, on the host cores of this machine: vote (memcmp per pair of copies,
+        # files spread over the threads) and median (sort per coordinate, coordinates spread over
+        # the threads), each timed on its own, on the whole batch.
         from oracle import c_oracle as C
         Xh = bufs[0].cpu().numpy()
         threads = C.default_threads()
-        best = None
         reps = 2
+        best_vote = best_med = None
         for _ in range(reps):
             c0 = time.perf_counter()
-            out_o, wrep_o, used = C.aggregate(Xh, rows, d, threads=threads)
+            wrep_o, wrow_o, _, vote_threads = C.vote(Xh, rows, d, threads=threads)
             c1 = time.perf_counter()
-            best = (c1 - c0) if best is None else min(best, c1 - c0)
+            out_o = C.median(Xh, wrow_o, d, threads=threads)
+            c2 = time.perf_counter()
+            best_vote = (c1 - c0) if best_vote is None else min(best_vote, c1 - c0)
+            best_med = (c2 - c1) if best_med is None else min(best_med, c2 - c1)
+        best = best_vote + best_med
         step(0)
         torch.cuda.synchronize()
         same = bool(np.array_equal(out.cpu().numpy().view(np.uint32), out_o.view(np.uint32))
@@ -310,23 +411,17 @@ def main():
         c0 = time.perf_counter()
         C.aggregate(Xh, rows, d1, threads=1)
         one_core = time.perf_counter() - c0
-        model = "unknown"
-        try:
-            with open("/proc/cpuinfo") as fh:
-                for line in fh:
-                    if line.startswith("model name"):
-                        model = line.split(":", 1)[1].strip()
-                        break
-        except OSError:
-            pass
         result["cpu_baseline"] = {
-            "value": d / best, "unit": "coords/s", "cores": int(used), "kind": "oracle",
-            "cpu_model": model,
+            "value": d / best, "unit": "coords/s", "cores": int(threads), "kind": "oracle",
+            "cpu_model": _cpu_model(),
+            "vote_seconds": best_vote, "vote_threads": int(vote_threads),
+            "median_seconds": best_med, "median_threads": int(threads),
             "one_core": {"value": d1 / one_core, "unit": "coords/s",
                          "sample": "first %d coordinates of the same batch, one run" % d1},
-            "sample": "whole %s batch (d=%d, %d rows), best of %d runs of the C oracle "
-                      "(vote single-threaded memcmp, median OpenMP over coordinates)"
-                      % (cfg.name, d, asg.f * asg.r, reps),
+            "sample": "whole %s batch (d=%d, %d rows), best of %d runs of the C oracle: vote = memcmp "
+                      "per pair of copies with the %d files spread over %d threads, median = sort per "
+                      "coordinate with the coordinates spread over %d threads (OpenMP)"
+                      % (cfg.name, d, asg.f * asg.r, reps, asg.f, vote_threads, threads),
             "seconds": best, "gpu_matches_oracle": same,
         }
     print(json.dumps(result))

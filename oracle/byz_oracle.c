@@ -40,32 +40,55 @@ static int pair_bit(int r, int a, int b) {
     return -1;
 }
 
+/* Eq. 3 for one file j: the files are independent of each other. */
+static void vote_one_file(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, int j, int r,
+                          int32_t *winner_replica, int32_t *winner_row, uint32_t *pair_neq) {
+    int eq[8][8];
+    for (int a = 0; a < r; ++a)
+        for (int b = 0; b < r; ++b) {
+            const uint32_t *pa = X + (int64_t)rows[j * r + a] * ld;
+            const uint32_t *pb = X + (int64_t)rows[j * r + b] * ld;
+            eq[a][b] = (memcmp(pa, pb, (size_t)d * 4) == 0);
+        }
+    int best = -1, a_star = 0;
+    for (int a = 0; a < r; ++a) {
+        int count = 0;
+        for (int b = 0; b < r; ++b) count += eq[a][b];
+        if (count > best) { best = count; a_star = a; }
+    }
+    winner_replica[j] = a_star;
+    winner_row[j] = rows[j * r + a_star];
+    uint32_t bits = 0;
+    for (int a = 0; a < r; ++a)
+        for (int b = a + 1; b < r; ++b)
+            if (!eq[a][b]) bits |= 1u << pair_bit(r, a, b);
+    pair_neq[j] = bits;
+}
+
 int oracle_vote(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, int f, int r,
                 int32_t *winner_replica, int32_t *winner_row, uint32_t *pair_neq) {
     if (r < 1 || r > 7 || f < 1) return -1;
-    for (int j = 0; j < f; ++j) {
-        int eq[8][8];
-        for (int a = 0; a < r; ++a)
-            for (int b = 0; b < r; ++b) {
-                const uint32_t *pa = X + (int64_t)rows[j * r + a] * ld;
-                const uint32_t *pb = X + (int64_t)rows[j * r + b] * ld;
-                eq[a][b] = (memcmp(pa, pb, (size_t)d * 4) == 0);
-            }
-        int best = -1, a_star = 0;
-        for (int a = 0; a < r; ++a) {
-            int count = 0;
-            for (int b = 0; b < r; ++b) count += eq[a][b];
-            if (count > best) { best = count; a_star = a; }
-        }
-        winner_replica[j] = a_star;
-        winner_row[j] = rows[j * r + a_star];
-        uint32_t bits = 0;
-        for (int a = 0; a < r; ++a)
-            for (int b = a + 1; b < r; ++b)
-                if (!eq[a][b]) bits |= 1u << pair_bit(r, a, b);
-        pair_neq[j] = bits;
-    }
+    for (int j = 0; j < f; ++j)
+        vote_one_file(X, d, ld, rows, j, r, winner_replica, winner_row, pair_neq);
     return 0;
+}
+
+/* The same vote with the loop over files spread over `threads` host threads (each file is
+ * decided by one thread exactly as above).  Returns the number of threads used, or <0. */
+int oracle_vote_threads(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, int f, int r,
+                        int32_t *winner_replica, int32_t *winner_row, uint32_t *pair_neq,
+                        int threads) {
+    if (r < 1 || r > 7 || f < 1) return -1;
+    int used = 1;
+#ifdef _OPENMP
+    if (threads < 1) threads = 1;
+    if (threads > f) threads = f;
+    used = threads;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(threads)
+#endif
+    for (int j = 0; j < f; ++j)
+        vote_one_file(X, d, ld, rows, j, r, winner_replica, winner_row, pair_neq);
+    return used;
 }
 
 /*
@@ -323,8 +346,8 @@ int oracle_aggregate(const uint32_t *X, int64_t d, int64_t ld, const int32_t *ro
     int32_t *wrow = (int32_t *)malloc(sizeof(int32_t) * (size_t)f);
     uint32_t *neq = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)f);
     if (!wrow || !neq) { free(wrow); free(neq); return -2; }
-    int rc = oracle_vote(X, d, ld, rows, f, r, winner_replica, wrow, neq);
-    if (rc == 0) rc = oracle_median(X, d, ld, wrow, f, out, threads);
+    int rc = oracle_vote_threads(X, d, ld, rows, f, r, winner_replica, wrow, neq, threads);
+    if (rc >= 0) rc = oracle_median(X, d, ld, wrow, f, out, threads);
     free(wrow);
     free(neq);
     return rc;

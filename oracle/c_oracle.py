@@ -20,6 +20,9 @@ def lib():
         L.oracle_vote.argtypes = [u32p, ctypes.c_int64, ctypes.c_int64, i32p, ctypes.c_int,
                                   ctypes.c_int, i32p, i32p, u32p]
         L.oracle_vote.restype = ctypes.c_int
+        L.oracle_vote_threads.argtypes = [u32p, ctypes.c_int64, ctypes.c_int64, i32p, ctypes.c_int,
+                                          ctypes.c_int, i32p, i32p, u32p, ctypes.c_int]
+        L.oracle_vote_threads.restype = ctypes.c_int
         L.oracle_vote_tolerant.argtypes = [u32p, ctypes.c_int64, ctypes.c_int64, i32p, ctypes.c_int,
                                            ctypes.c_int, ctypes.c_float, ctypes.c_float, i32p,
                                            i32p, u32p]
@@ -63,19 +66,28 @@ def default_threads():
     return len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
 
 
-def vote(X, rows, d):
+def vote(X, rows, d, threads=None):
+    """Returns (winner_replica[f], winner_row[f], pair_neq[f]); with `threads` the files are spread
+    over that many host threads (same decisions) and the number used is returned as a 4th item."""
     U = _u32(X)
     rows = np.ascontiguousarray(rows, dtype=np.int32)
     f, r = rows.shape
     wrep = np.zeros(f, dtype=np.int32)
     wrow = np.zeros(f, dtype=np.int32)
     neq = np.zeros(f, dtype=np.uint32)
-    rc = lib().oracle_vote(_ptr(U, ctypes.c_uint32), d, U.shape[1], _ptr(rows, ctypes.c_int32),
-                           f, r, _ptr(wrep, ctypes.c_int32), _ptr(wrow, ctypes.c_int32),
-                           _ptr(neq, ctypes.c_uint32))
-    if rc != 0:
-        raise ValueError("oracle_vote rc=%d" % rc)
-    return wrep, wrow, neq
+    if threads is None:
+        rc = lib().oracle_vote(_ptr(U, ctypes.c_uint32), d, U.shape[1], _ptr(rows, ctypes.c_int32),
+                               f, r, _ptr(wrep, ctypes.c_int32), _ptr(wrow, ctypes.c_int32),
+                               _ptr(neq, ctypes.c_uint32))
+        if rc != 0:
+            raise ValueError("oracle_vote rc=%d" % rc)
+        return wrep, wrow, neq
+    rc = lib().oracle_vote_threads(_ptr(U, ctypes.c_uint32), d, U.shape[1], _ptr(rows, ctypes.c_int32),
+                                   f, r, _ptr(wrep, ctypes.c_int32), _ptr(wrow, ctypes.c_int32),
+                                   _ptr(neq, ctypes.c_uint32), int(threads))
+    if rc < 0:
+        raise ValueError("oracle_vote_threads rc=%d" % rc)
+    return wrep, wrow, neq, rc
 
 
 def vote_tolerant(X, rows, d, atol, rtol):

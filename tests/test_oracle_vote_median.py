@@ -530,3 +530,40 @@ def test_tolerant_vote_majority_property_under_rounding_noise(name, tvote):
         assert honest_wins == (n_byz < (r + 1) // 2), j
     assert np.array_equal(np.stack(O.vote_tolerant(X, rows, d, 1e-6, 1e-5)),
                           np.stack(C.vote_tolerant(X, rows, d, 1e-6, 1e-5)))
+
+
+def test_c_vote_spread_over_threads_takes_the_same_decisions():
+    # the loop over files may run on several host threads (used when the oracle is timed as the
+    # CPU baseline); every file is still decided exactly as in the plain loop and as the NumPy
+    # definition decides it, including ties, a difference in the last word only, and +-0
+    rng = np.random.default_rng(77)
+    for (f, r, d) in [(9, 3, 257), (25, 5, 1000), (7, 7, 33)]:
+        G = rng.standard_normal((f, d)).astype(np.float32)
+        X = np.zeros((f * r, d + 3), dtype=np.float32)
+        rows = rng.permutation(f * r).astype(np.int32).reshape(f, r)
+        for j in range(f):
+            for k in range(r):
+                X[rows[j, k], :d] = G[j]
+        for j in range(f):
+            kind = j % 5
+            if kind == 1:
+                X[rows[j, 0], d - 1] += 1.0
+            elif kind == 2:
+                for k in range(r):
+                    X[rows[j, k], 0] = float(k)
+            elif kind == 3:
+                X[rows[j, r - 1], :d] = -100.0 * G[j]
+                X[rows[j, r - 2], :d] = -100.0 * G[j]
+            elif kind == 4:
+                X[rows[j, 1], 5] = 0.0
+                X[rows[j, 0], 5] = -0.0
+        X[:, d:] = rng.standard_normal((f * r, 3)).astype(np.float32)  # padding differs everywhere
+        want = O.vote(X, rows, d)
+        plain = C.vote(X, rows, d)
+        for t in (1, 3, 64):
+            got = C.vote(X, rows, d, threads=t)
+            assert got[3] == min(t, f)
+            for a, b, c in zip(want, plain, got[:3]):
+                assert np.array_equal(a, b) and np.array_equal(a, c)
+        out_t, wrep_t, _ = C.aggregate(X, rows, d, threads=3) if f % 2 else (None, want[0], None)
+        assert np.array_equal(wrep_t, want[0])
