@@ -25,8 +25,9 @@
 // The build compiles this file once per BYZ_PART, in parallel, because the single-pass kernels
 // are large: part 0 holds every entry point, the vote and the Bulyan kernels, parts 1..4 one
 // group of single-pass instantiations each (byz_internal_launch_single_pass_<n>; the fifth
-// group is part 7), part 5 the median kernels, part 6 the trimmed-mean kernels, parts 8..11 one
-// 169-wire network kernel each, parts 12 and 13 the 81- and 121-wire second phase of Bulyan.
+// group is part 7, the sixth and seventh parts 14 and 15), part 5 the median kernels, part 6 the
+// trimmed-mean kernels, parts 8..11 one 169-wire network kernel each, parts 12 and 13 the 81- and
+// 121-wire second phase of Bulyan.
 // Without BYZ_PART the whole library is
 // this one translation unit.
 #ifndef BYZ_PART
@@ -72,11 +73,13 @@ constexpr int prefetch_depth(int f, int slots) {
 // f with a generated streamed network (gen_selnet.py STREAMED_SIZES): the paper's file counts
 // l^2 (MOLS, Ramanujan Case 1; 81, 121, 169 for l = 9, 11, 13) and m*s (Ramanujan Case 2)
 constexpr bool has_streamed_network(int f) {
-    return f == 9 || f == 15 || f == 21 || f == 25 || f == 35 || f == 49 || f == 81 || f == 121 ||
-           f == 169;
+    return f == 9 || f == 15 || f == 21 || f == 25 || f == 35 || f == 49 || f == 63 || f == 65 ||
+           f == 81 || f == 121 || f == 169;
 }
 // words per thread: fewer for the large networks, whose keys fill the register file
 constexpr int vec_for(int f) { return f <= 49 ? 4 : (f <= 81 ? 2 : 1); }
+// ... and of the single pass, where seven copies of a file in flight leave less room for keys
+constexpr int vec_for_pass(int f, int r) { return (r == 7 && f > 25 && f <= 49) ? 2 : vec_for(f); }
 constexpr int kProbe = 256;  // sampled coordinates of the probe (512: 2x slower)
 constexpr int kProbeSplit = 4;  // the files are dealt out to this many groups of kProbe threads
 constexpr int kProbeThreads = kProbe * kProbeSplit;
@@ -1096,6 +1099,18 @@ __global__ __launch_bounds__(kProbeThreads) void probe_kernel(const uint32_t *__
     if (tid == 0) ws->slots_per_file = (early_majority != 0 && s_all_majority != 0) ? (R + 1) / 2 : R;
 }
 
+// Which tile of kBlock threads a block works on.  Blocks go to the eight XCDs round-robin
+// (block b runs on XCD b mod 8).  A launch that is over after a round or two of resident blocks
+// is dominated by its start: there every XCD gets one contiguous eighth of the tiles, so that
+// its L2 and address translation see one range of every row instead of all of it (d = 2^20,
+// 75 rows: 56 -> 52.5 us).  Long launches keep the plain order, which measured 1-3 % faster there.
+constexpr unsigned kShortLaunchBlocks = 2048;
+__device__ __forceinline__ unsigned tile_of_block(unsigned b, unsigned n_blocks) {
+    if (n_blocks > kShortLaunchBlocks) return b;
+    const unsigned q = n_blocks / 8, rem = n_blocks % 8, x = b % 8, i = b / 8;
+    return x * q + (x < rem ? x : rem) + i;  // XCD x owns q tiles, one more if x < rem
+}
+
 // Vote and median in one pass: streams the first NS slots of every file's permuted row list once (NS = R:
 // every copy; NS = r' = (R+1)/2 in early-majority mode when every file has a probable
 // majority).  Slot 0 (the probable winner) feeds the median network, and every pair of slots is
@@ -1112,7 +1127,7 @@ __device__ __forceinline__ void fused_body(const uint32_t *__restrict__ X, int64
     // its neighbour instead of a scalar tail, and threads past the end redo it, so there are
     // no branches around loads and ballots (d >= V is the launcher's business).
     const int64_t n_thr = (d + V - 1) / V;
-    const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t gt = (int64_t)tile_of_block(blockIdx.x, gridDim.x) * kBlock + threadIdx.x;
     const int64_t c0 = (gt + 1) * V <= d ? gt * V : d - V;
     uint32_t flags[(F + 63) / 64] = {};  // lane j%64 collects the pair bits of file j
     // What other waves have published so far, read now so that the wait is over long before the
@@ -1135,18 +1150,11 @@ __device__ __forceinline__ void fused_body(const uint32_t *__restrict__ X, int64
 #define BYZ_S_ROW_ADDR(j, k) (Xb + perm_off[(j) * kRowStride + (k)] + voff)
     if constexpr (!TRIM) {
         // median: every comparator is made to run in the share of the file that completes its
-        // inputs (empty statements the compiler may not move: loads stay in their share, the
-        // wires a share changed are computed by its end), so that a wave has loads in flight
-        // while it works through the network instead of running the whole network at the end
-#undef BYZ_S_STEP
-#undef BYZ_S_PIN
-#define BYZ_S_STEP(j) asm volatile("" ::: "memory");
-#define BYZ_S_PIN(w) _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_) asm volatile("" : "+v"(key[v_][w]));
+        // inputs, so that a wave has loads in flight while it works through the network instead
+        // of running the whole network at the end
+#include "selnet_pin_on.inc"
 #include "generated/selnet_stream_dispatch.inc"
-#undef BYZ_S_STEP
-#undef BYZ_S_PIN
-#define BYZ_S_STEP(j)
-#define BYZ_S_PIN(w)
+#include "selnet_pin_off.inc"
     } else {
 #include "generated/selnet_sort_stream_dispatch.inc"
         trimmed_mean_of_sorted<F, V>(key, F, trim_b, o);
@@ -1316,7 +1324,7 @@ int launch_fused(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, 
     BYZ_HIP(hipGetLastError());
     int rc = byz_internal_profile_mark(0, s);
     if (rc != BYZ_OK) return rc;
-    constexpr int V = vec_for(F);
+    constexpr int V = vec_for_pass(F, R);
     const unsigned g = blocks_for((d + V - 1) / V);
     if (trim_b < 0) {
         fused_kernel<F, R, false, V><<<g, kBlock, 0, s>>>(
@@ -1403,12 +1411,19 @@ int launch_bulyan_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *s
 #if BYZ_IN_PART(0)
 
 // (f, r) with a compiled single-pass kernel: MOLS / Ramanujan Case 1 (f = l^2: 9, 25, 49) with
-// r = 3 or 5, the Ramanujan Case 2 shapes f = m*s with r = s: (15,3), (21,3), (35,5), and MOLS
-// over F_9, F_11 and F_13 with r = 3: (81,3), (121,3), (169,3)
+// r = 3, 5 (and 7 for f = 49, which is also Ramanujan Case 2 with m = s = 7), the Ramanujan Case 2
+// shapes f = m*s with r = s: (15,3), (21,3), (35,5), (65,5), (63,7), and MOLS over F_9, F_11 and
+// F_13 with r = 3: (81,3), (121,3), (169,3)
 bool has_fused(int f, int r) {
-    return (f == 9 && r == 3) || ((f == 25 || f == 49) && (r == 3 || r == 5)) ||
-           ((f == 15 || f == 21) && r == 3) || (f == 35 && r == 5) ||
+    return (f == 9 && r == 3) || (f == 25 && (r == 3 || r == 5)) ||
+           (f == 49 && (r == 3 || r == 5 || r == 7)) || ((f == 15 || f == 21) && r == 3) ||
+           (f == 35 && r == 5) || (f == 65 && r == 5) || (f == 63 && r == 7) ||
            ((f == 81 || f == 121 || f == 169) && r == 3);
+}
+// ... whose trimmed-mean variant is compiled as well (the others run the trimmed mean as vote
+// kernel + trimmed-mean kernel)
+bool has_fused_trim(int f, int r) {
+    return has_fused(f, r) && f != 169 && f != 63 && f != 65 && r != 7;
 }
 
 int check_common(const void *copies, int64_t d, int64_t ld, const void *rows, int f, int r) {
@@ -1533,6 +1548,7 @@ int byz_internal_launch_single_pass_2(int f, int r, const void *X, long long d, 
     hipStream_t s = (hipStream_t)stream;
     if (f == 49 && r == 3) return launch_fused<49, 3>(x, d, ld, rows, w, o, probe_opts, trim_b, s);
     if (f == 49 && r == 5) return launch_fused<49, 5>(x, d, ld, rows, w, o, probe_opts, trim_b, s);
+    if (f == 49 && r == 7) return launch_fused<49, 7, false>(x, d, ld, rows, w, o, probe_opts, trim_b, s);
     return BYZ_EINTERNAL;
 }
 #endif
@@ -1567,6 +1583,30 @@ int byz_internal_launch_single_pass_5(int f, int r, const void *X, long long d, 
                                       void *stream) {
     if (f == 169 && r == 3)
         return launch_fused<169, 3, false>(static_cast<const uint32_t *>(X), d, ld, rows,
+                                    static_cast<AggWorkspace *>(ws), static_cast<uint32_t *>(out),
+                                    probe_opts, trim_b, (hipStream_t)stream);
+    return BYZ_EINTERNAL;
+}
+#endif
+
+#if BYZ_IN_PART(14)
+int byz_internal_launch_single_pass_6(int f, int r, const void *X, long long d, long long ld,
+                                      const int *rows, void *ws, void *out, int probe_opts, int trim_b,
+                                      void *stream) {
+    if (f == 63 && r == 7)
+        return launch_fused<63, 7, false>(static_cast<const uint32_t *>(X), d, ld, rows,
+                                    static_cast<AggWorkspace *>(ws), static_cast<uint32_t *>(out),
+                                    probe_opts, trim_b, (hipStream_t)stream);
+    return BYZ_EINTERNAL;
+}
+#endif
+
+#if BYZ_IN_PART(15)
+int byz_internal_launch_single_pass_7(int f, int r, const void *X, long long d, long long ld,
+                                      const int *rows, void *ws, void *out, int probe_opts, int trim_b,
+                                      void *stream) {
+    if (f == 65 && r == 5)
+        return launch_fused<65, 5, false>(static_cast<const uint32_t *>(X), d, ld, rows,
                                     static_cast<AggWorkspace *>(ws), static_cast<uint32_t *>(out),
                                     probe_opts, trim_b, (hipStream_t)stream);
     return BYZ_EINTERNAL;
@@ -1721,8 +1761,7 @@ static int aggregate_on_workspace(const float *copies, int64_t d, int64_t ld,
     const uint32_t *X = reinterpret_cast<const uint32_t *>(copies);
     uint32_t *O = reinterpret_cast<uint32_t *>(out);
 
-    // (the 169-file single pass is built for the median only)
-    if (!has_fused(f, r) || d < kVec || (f == 169 && trim_b >= 0)) {
+    if (!has_fused(f, r) || d < kVec || (trim_b >= 0 && !has_fused_trim(f, r))) {
         // two-step path, unconditionally: vote, then median over the winners
         reset_workspace_kernel<<<1, kWide, 0, s>>>(ws, (uint32_t)BYZ_PATH_TWO_STEP);
         BYZ_HIP(hipGetLastError());
@@ -1752,6 +1791,10 @@ static int aggregate_on_workspace(const float *copies, int64_t d, int64_t ld,
         rc = byz_internal_launch_single_pass_4(f, r, X, d, ld, file_rows_dev, ws, O, probe_opts, trim_b, s);
     else if (f == 81)
         rc = byz_internal_launch_single_pass_3(f, r, X, d, ld, file_rows_dev, ws, O, probe_opts, trim_b, s);
+    else if (f == 63)
+        rc = byz_internal_launch_single_pass_6(f, r, X, d, ld, file_rows_dev, ws, O, probe_opts, trim_b, s);
+    else if (f == 65)
+        rc = byz_internal_launch_single_pass_7(f, r, X, d, ld, file_rows_dev, ws, O, probe_opts, trim_b, s);
     else if (f == 49)
         rc = byz_internal_launch_single_pass_2(f, r, X, d, ld, file_rows_dev, ws, O, probe_opts, trim_b, s);
     else

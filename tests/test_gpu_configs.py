@@ -114,9 +114,28 @@ def test_ramanujan_case2_cluster_full_size():
     assert _full_check(w, cfg.name) == cmax_o
 
 
+@pytest.mark.parametrize("s_,m_,q,shape", [(7, 7, 5, (49, 49, 7, 7)), (7, 9, 5, (49, 63, 9, 7)),
+                                           (5, 13, 5, (25, 65, 13, 5))])
+def test_ramanujan_case2_wide_clusters_full_size(s_, m_, q, shape):
+    # Sec. 4.2.1, Eq. 6, Case 2 (m >= s): (K,f,l,r) = (s^2, m*s, m, s) with r = 7 and with r = 5 at
+    # f > 64, at the ResNet-18 size (343, 441 and 325 rows); single-pass kernels with seven copies
+    # of a file in flight resp. 65 keys.  c_max from the library's search (no table has these).
+    free_bytes, _ = torch.cuda.mem_get_info()
+    d = 11173962
+    if free_bytes < (shape[1] * shape[3] + 2 * shape[1] + 8) * 4 * d:
+        pytest.skip("needs more device memory")
+    attack = {"kind": "mixed", "z": 1.0, "value": 1e3, "file_scales": True}
+    w = W.make(B.BYZ_SCHEME_RAMANUJAN, s_, m_, q, d, attack, seed=20101004 + 10 * s_ + m_,
+               ld=synth.padded_ld(d, 64), device=DEV)
+    assert (w.K, w.f, w.l, w.r) == shape and B.byz_aggregate_has_single_pass(w.f, w.r)
+    assert _full_check(w, "ram%dx%d" % (s_, m_)) == w.cmax
+    del w
+    torch.cuda.empty_cache()
+
+
 def test_prime_power_cluster_full_size():
     # MOLS over F_9: (K,f,l,r) = (27,81,9,3), 243 rows of the ResNet-18 size, q = 5 worst-case
-    # set, ALIE.  f > 64: vote in two 64-file groups, median by bisection in LDS.
+    # set, ALIE.  f > 64: pair bits in two 64-file groups, 81-wire network with two words a thread.
     from oracle import byz_oracle as O
     cfg = synth.CONFIGS[7]
     w = W.from_config(cfg, DEV, ld=synth.padded_ld(cfg.d, 64))

@@ -82,7 +82,10 @@ SMALL_D = [1, 2, 3, 5, 63, 64, 255, 1000, 4099, 70001]
     (RAM, 5, 5, 6, MIXED), (MOLS, 7, 3, 6, ALIE), (RAM, 3, 3, 2, CONST), (MOLS, 7, 5, 5, MIXED),
     (RAM, 5, 3, 3, CONST), (FRC, 15, 3, 4, REVERSED), (FRC, 25, 5, 7, MIXED),
     # Ramanujan Case 2 (m > s): f = m*s = 15, 21, 35
-    (RAM, 3, 5, 2, CONST), (RAM, 3, 7, 2, ALIE), (RAM, 5, 7, 6, MIXED)])
+    (RAM, 3, 5, 2, CONST), (RAM, 3, 7, 2, ALIE), (RAM, 5, 7, 6, MIXED),
+    # r = 7 and r = 5 with f > 64 (Sec. 4.2.1, Eq. 6, Case 2): (K,f,l,r) = (49,49,7,7), (49,63,9,7),
+    # (25,65,13,5)
+    (RAM, 7, 7, 5, MIXED), (RAM, 7, 9, 4, ALIE), (RAM, 5, 13, 4, REVERSED)])
 def test_small_sizes_all_layouts(scheme, a, b, q, attack):
     # sizes below one tile, several tiles and ragged tails; row pitches that give 16-byte,
     # 8-byte and 4-byte aligned rows
@@ -112,10 +115,11 @@ def test_unaligned_base_pointer():
 
 
 def test_generic_shapes_without_a_generated_network():
-    # f = 27 (Ramanujan s=3, m=9): two-step path and rank-counting median;
-    # r = 7 (Ramanujan s=7, m=7): two-step path with the f = 49 network
-    for (a, b, q) in [(3, 9, 2), (7, 7, 5)]:
+    # f = 27 (Ramanujan s=3, m=9) and f = 33 (s=3, m=11): no single pass; vote kernel, then the
+    # median on the next generated network with spare wires
+    for (a, b, q) in [(3, 9, 2), (3, 11, 2)]:
         w = W.make(RAM, a, b, q, 2222, CONST, seed=3, device=DEV)
+        assert not B.byz_aggregate_has_single_pass(w.f, w.r)
         _check_all(w.X, w.file_rows, w.d, w.f, w.r, expect_path=TWO_STEP)
     # byz_median alone for assorted odd f, including rows used more than once
     rng = np.random.default_rng(5)
@@ -352,18 +356,30 @@ def test_generator_same_bytes_on_cpu_and_gpu():
 
 
 def test_largest_shapes_f63_r7():
-    # Ramanujan s=7, m=9 (Case 2): K=49 workers, f=63 files (largest odd f), r=7 (largest r),
-    # l=9: two-step path, 21 pair bits per file, rank-counting median
+    # Ramanujan s=7, m=9 (Case 2): K=49 workers, f=63 files, r=7 (largest r), l=9: 21 pair bits
+    # per file, seven copies of a file in flight in the single pass
     w = W.make(RAM, 7, 9, 6, 1537, MIXED, seed=12, device=DEV)
-    assert (w.K, w.f, w.l, w.r) == (49, 63, 9, 7)
-    _check_all(w.X, w.file_rows, w.d, w.f, w.r, expect_path=TWO_STEP)
+    assert (w.K, w.f, w.l, w.r) == (49, 63, 9, 7) and B.byz_aggregate_has_single_pass(63, 7)
+    _check_all(w.X, w.file_rows, w.d, w.f, w.r, expect_path=SINGLE)
     # every copy of one file different (seven singletons), 3-3-1 and 2-2-2-1 splits on others
     X = w.X.clone()
     for j, labels in enumerate([[0, 1, 2, 3, 4, 5, 6], [1, 0, 1, 0, 1, 0, 2], [0, 0, 1, 1, 2, 2, 3],
                                 [3, 2, 2, 1, 1, 1, 0]]):
         for k, lab in enumerate(labels):
             X[int(w.file_rows[j, k])] = w.G[j] * float(1 + lab)
-    out_o, wrep_o, _ = _check_all(X, w.file_rows, w.d, w.f, w.r, expect_path=TWO_STEP)
+    out_o, wrep_o, _ = _check_all(X, w.file_rows, w.d, w.f, w.r, expect_path=SINGLE)
+    assert wrep_o[:4].tolist() == [0, 0, 0, 3]
+    # the same splits where the copies differ in one word off the probe's sample only: the probe
+    # sees seven equal copies and guesses replica 0; wherever that is not the winner (file 3:
+    # replicas 3, 4, 5 agree) the median is redone, and nothing is compared twice
+    X2 = w.X.clone()
+    hidden = w.d // 2 + 37
+    for j, labels in enumerate([[0, 1, 2, 3, 4, 5, 6], [1, 0, 1, 0, 1, 0, 2], [0, 0, 1, 1, 2, 2, 3],
+                                [3, 2, 2, 1, 1, 1, 0]]):
+        for k, lab in enumerate(labels):
+            X2[int(w.file_rows[j, k])] = w.G[j]
+            X2[int(w.file_rows[j, k]), hidden] = float(lab)
+    out_o, wrep_o, _ = _check_all(X2, w.file_rows, w.d, w.f, w.r, expect_path=REDONE)
     assert wrep_o[:4].tolist() == [0, 0, 0, 3]
 
 
