@@ -57,6 +57,15 @@ int byz_internal_launch_median_169_padded(const void *X, long long d, long long 
                                           const int *row_index, int f, void *out, const void *gate,
                                           int gate_n, void *stream);
 
+// ... and on the widest networks: median 169 < f <= 255 on 255 wires, trimmed mean
+// 169 < f <= 256 on 256 wires (build parts 16 and 17).
+int byz_internal_launch_median_255_padded(const void *X, long long d, long long ld,
+                                          const int *row_index, int f, void *out, const void *gate,
+                                          int gate_n, void *stream);
+int byz_internal_launch_trimmed_mean_256_padded(const void *X, long long d, long long ld,
+                                                const int *row_index, int f, int b, void *out,
+                                                const void *gate, int gate_n, void *stream);
+
 // Records the event before (which = 0) or after (1) the dominant kernel of an aggregation, if
 // byz_profile_enable has armed any.  Returns a byz_status.
 int byz_internal_profile_mark(int which, void *stream);

@@ -27,7 +27,7 @@
 // group of single-pass instantiations each (byz_internal_launch_single_pass_<n>; the fifth
 // group is part 7, the sixth and seventh parts 14 and 15), part 5 the median kernels, part 6 the
 // trimmed-mean kernels, parts 8..11 one 169-wire network kernel each, parts 12 and 13 the 81- and
-// 121-wire second phase of Bulyan.
+// 121-wire second phase of Bulyan, parts 16 and 17 the 255-wire median and the 256-wire sorting network.
 // Without BYZ_PART the whole library is
 // this one translation unit.
 #ifndef BYZ_PART
@@ -74,18 +74,21 @@ constexpr int prefetch_depth(int f, int slots) {
 // l^2 (MOLS, Ramanujan Case 1; 81, 121, 169 for l = 9, 11, 13) and m*s (Ramanujan Case 2)
 constexpr bool has_streamed_network(int f) {
     return f == 9 || f == 15 || f == 21 || f == 25 || f == 35 || f == 49 || f == 63 || f == 65 ||
-           f == 81 || f == 121 || f == 169;
+           f == 81 || f == 121 || f == 169 || f == 255;
 }
 // words per thread: fewer for the large networks, whose keys fill the register file
 constexpr int vec_for(int f) { return f <= 49 ? 4 : (f <= 81 ? 2 : 1); }
-// ... and of the single pass, where seven copies of a file in flight leave less room for keys
-constexpr int vec_for_pass(int f, int r) { return (r == 7 && f > 25 && f <= 49) ? 2 : vec_for(f); }
+// ... and of the single pass: with five or seven copies of a file in flight two words per thread
+// (more waves per SIMD, 8-byte loads) measured 1-2 % faster than four (r = 7 would not fit
+// the registers with four); with three copies four words are faster
+constexpr int vec_for_pass(int f, int r) { return (r >= 5 && f <= 49) ? 2 : vec_for(f); }
 constexpr int kProbe = 256;  // sampled coordinates of the probe (512: 2x slower)
 constexpr int kProbeSplit = 4;  // the files are dealt out to this many groups of kProbe threads
 constexpr int kProbeThreads = kProbe * kProbeSplit;
 constexpr int kBlock = 256;  // threads per block of the streaming kernels (128/512/1024: slower)
-constexpr int kWide = BYZ_MAX_F_WIDE;  // largest f of the vote and the LDS column kernels
+constexpr int kWide = BYZ_MAX_F_WIDE;  // largest f of the vote and of the widest network (255 wires)
 static_assert(kWide <= kBlock, "one thread per file in the deciding block");
+constexpr int kPinFrom = 169;  // network sizes from which the median / trimmed-mean kernels pin their schedule
 constexpr int kRowStride = 8;  // slots per file in the permuted row table (>= BYZ_MAX_R)
 
 // ----------------------------------------------------------------------------- helpers
@@ -713,7 +716,15 @@ __global__ __launch_bounds__(kBlock) void median_large_kernel(
     (!PAD || (j) < f ? to_key(x) : ((j) < pad_low_end ? 0u : 0xFFFFFFFFu))
 #define BYZ_S_ROW_ADDR(j, k) \
     (Xb + (uint64_t)(uint32_t)row_index[!PAD || (j) < f ? (j) : 0] * (uint64_t)ld * 4u + voff)
+    // the widest networks run with their schedule pinned (wires the pruned network has dropped
+    // give their registers back early: 168 instead of 226 registers at F = 169)
+    if constexpr (F >= kPinFrom) {
+#include "selnet_pin_on.inc"
 #include "generated/selnet_stream_dispatch.inc"
+#include "selnet_pin_off.inc"
+    } else {
+#include "generated/selnet_stream_dispatch.inc"
+    }
 #undef BYZ_S_ROW_ADDR
 #undef BYZ_S_KEY
 #define BYZ_S_KEY(j, x) to_key(x)
@@ -787,7 +798,13 @@ __global__ __launch_bounds__(kBlock) void trimmed_mean_kernel(
 #define BYZ_S_KEY(j, x) (!PAD || (j) < f ? to_key(x) : 0xFFFFFFFFu)
 #define BYZ_S_ROW_ADDR(j, k) \
     (Xb + (uint64_t)(uint32_t)row_index[!PAD || (j) < f ? (j) : 0] * (uint64_t)ld * 4u + voff)
+    if constexpr (F >= kPinFrom) {
+#include "selnet_pin_on.inc"
 #include "generated/selnet_sort_stream_dispatch.inc"
+#include "selnet_pin_off.inc"
+    } else {
+#include "generated/selnet_sort_stream_dispatch.inc"
+    }
 #undef BYZ_S_ROW_ADDR
 #undef BYZ_S_KEY
 #define BYZ_S_KEY(j, x) to_key(x)
@@ -814,52 +831,6 @@ __global__ __launch_bounds__(kBlock) void trimmed_mean_generic_kernel(
     float acc = 0.0f;
     for (int i = b; i < f - b; ++i) acc += __uint_as_float(from_key(key[i]));
     out[c] = __float_as_uint(acc / (float)(f - 2 * b));
-}
-
-// Median and trimmed mean for 64 < f <= 256: one wave a block, one coordinate a lane, the f keys
-// of a coordinate in an LDS column (word j*64 + lane: conflict-free).  Dynamic LDS: f*256 bytes.
-//   b < 0   median by bisection on the key: the result is the largest u with
-//           #{keys < u} <= (f-1)/2, built from the top bit down (32 counting passes).
-//   b >= 0  trimmed mean: insertion sort of the column, then the rounding contract of
-//           trimmed_mean_kernel (fp32, kept values added in ascending order, one division).
-__global__ __launch_bounds__(64) void column_wide_kernel(
-    const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
-    int f, int b, uint32_t *__restrict__ out, const uint32_t *__restrict__ gate, int gate_n) {
-    if (gate != nullptr && !any_word_set(gate, gate_n)) return;
-    extern __shared__ uint32_t s_col[];
-    const int lane = threadIdx.x;
-    const int64_t c_raw = (int64_t)blockIdx.x * 64 + lane;
-    const int64_t c = c_raw < d ? c_raw : d - 1;  // lanes past the end redo the last coordinate
-    uint32_t *col = s_col + lane;
-#pragma unroll 8
-    for (int j = 0; j < f; ++j) col[j * 64] = to_key(X[(int64_t)row_index[j] * ld + c]);
-    uint32_t o;
-    if (b < 0) {
-        const int mid = (f - 1) / 2;
-        uint32_t result = 0;
-        for (int bit = 31; bit >= 0; --bit) {
-            const uint32_t trial = result | (1u << bit);
-            int below = 0;
-#pragma unroll 8
-            for (int j = 0; j < f; ++j) below += col[j * 64] < trial ? 1 : 0;
-            if (below <= mid) result = trial;
-        }
-        o = from_key(result);
-    } else {
-        for (int i = 1; i < f; ++i) {
-            const uint32_t x = col[i * 64];
-            int t = i - 1;
-            while (t >= 0 && col[t * 64] > x) {
-                col[(t + 1) * 64] = col[t * 64];
-                --t;
-            }
-            col[(t + 1) * 64] = x;
-        }
-        float acc = 0.0f;
-        for (int i = b; i < f - b; ++i) acc += __uint_as_float(from_key(col[i * 64]));
-        o = __float_as_uint(acc / (float)(f - 2 * b));
-    }
-    if (c_raw < d) out[c_raw] = o;
 }
 
 // Mean around the median (second phase of Bulyan) for one coordinate whose theta values sit
@@ -1233,20 +1204,6 @@ int launch_vote_pairs_tolerant(int r, const uint32_t *X, int64_t d, int64_t ld,
 
 #endif  // part 0
 
-#if BYZ_IN_PART(5) || BYZ_IN_PART(6)  // (launch_column_wide serves both)
-// 64 < f <= 256 without a generated network
-int launch_column_wide(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
-                       int b, uint32_t *out, const uint32_t *gate, int gate_n, hipStream_t s) {
-    if (d == 0) return BYZ_OK;
-    const size_t lds = (size_t)f * 64 * sizeof(uint32_t);  // <= 64 KiB for f <= 256
-    column_wide_kernel<<<(unsigned)((d + 63) / 64), 64, lds, s>>>(X, d, ld, row_index, f, b, out,
-                                                                 gate, gate_n);
-    BYZ_HIP(hipGetLastError());
-    return BYZ_OK;
-}
-
-#endif  // parts 5, 6
-
 #if BYZ_IN_PART(5)
 template <int F>
 int launch_median_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index,
@@ -1259,7 +1216,7 @@ int launch_median_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *r
 
 #endif  // part 5
 
-#if BYZ_IN_PART(5) || BYZ_IN_PART(9) || BYZ_IN_PART(11)
+#if BYZ_IN_PART(5) || BYZ_IN_PART(9) || BYZ_IN_PART(11) || BYZ_IN_PART(16)
 template <int F, bool PAD>
 int launch_median_large(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
                         uint32_t *out, const uint32_t *gate, int gate_n, hipStream_t s) {
@@ -1270,7 +1227,7 @@ int launch_median_large(const uint32_t *X, int64_t d, int64_t ld, const int32_t 
     return BYZ_OK;
 }
 
-#endif  // parts 5, 9, 11
+#endif  // parts 5, 9, 11, 16
 
 #if BYZ_IN_PART(5)
 int launch_median(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
@@ -1309,7 +1266,7 @@ int launch_median(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_i
     if (f <= 121) return launch_median_large<121, true>(X, d, ld, row_index, f, out, gate, gate_n, s);
     if (f == 169) return byz_internal_launch_median_169(X, d, ld, row_index, f, out, gate, gate_n, s);
     if (f <= 169) return byz_internal_launch_median_169_padded(X, d, ld, row_index, f, out, gate, gate_n, s);
-    return launch_column_wide(X, d, ld, row_index, f, -1, out, gate, gate_n, s);
+    return byz_internal_launch_median_255_padded(X, d, ld, row_index, f, out, gate, gate_n, s);
 }
 
 #endif  // part 5
@@ -1337,7 +1294,7 @@ int launch_fused(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, 
     return byz_internal_profile_mark(1, s);
 }
 
-#if BYZ_IN_PART(6) || BYZ_IN_PART(8) || BYZ_IN_PART(10)
+#if BYZ_IN_PART(6) || BYZ_IN_PART(8) || BYZ_IN_PART(10) || BYZ_IN_PART(17)
 template <int F, bool PAD>
 int launch_trimmed_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
                        int b, uint32_t *O, const uint32_t *gate, int gate_n, hipStream_t s) {
@@ -1348,7 +1305,7 @@ int launch_trimmed_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *
     return BYZ_OK;
 }
 
-#endif  // parts 6, 8, 10
+#endif  // parts 6, 8, 10, 17
 
 #if BYZ_IN_PART(6)
 int launch_trimmed_mean(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
@@ -1387,7 +1344,7 @@ int launch_trimmed_mean(const uint32_t *X, int64_t d, int64_t ld, const int32_t 
     if (f == 169) return byz_internal_launch_trimmed_mean_169(X, d, ld, row_index, f, b, O, gate, gate_n, s);
     if (f <= 169)
         return byz_internal_launch_trimmed_mean_169_padded(X, d, ld, row_index, f, b, O, gate, gate_n, s);
-    return launch_column_wide(X, d, ld, row_index, f, b, O, gate, gate_n, s);
+    return byz_internal_launch_trimmed_mean_256_padded(X, d, ld, row_index, f, b, O, gate, gate_n, s);
 }
 
 #endif  // part 6
@@ -1505,6 +1462,29 @@ int byz_internal_launch_median_169_padded(const void *X, long long d, long long 
                                           static_cast<uint32_t *>(out),
                                           static_cast<const uint32_t *>(gate), gate_n,
                                           (hipStream_t)stream);
+}
+#endif
+
+// the widest networks: 255 wires for the median (169 < f <= 255), 256 for the trimmed mean
+// (169 < f <= 256; it also takes even f), spare wires when f is smaller; a build part each
+#if BYZ_IN_PART(16)
+int byz_internal_launch_median_255_padded(const void *X, long long d, long long ld,
+                                          const int *row_index, int f, void *out, const void *gate,
+                                          int gate_n, void *stream) {
+    return launch_median_large<255, true>(static_cast<const uint32_t *>(X), d, ld, row_index, f,
+                                          static_cast<uint32_t *>(out),
+                                          static_cast<const uint32_t *>(gate), gate_n,
+                                          (hipStream_t)stream);
+}
+#endif
+#if BYZ_IN_PART(17)
+int byz_internal_launch_trimmed_mean_256_padded(const void *X, long long d, long long ld,
+                                                const int *row_index, int f, int b, void *out,
+                                                const void *gate, int gate_n, void *stream) {
+    return launch_trimmed_net<256, true>(static_cast<const uint32_t *>(X), d, ld, row_index, f, b,
+                                         static_cast<uint32_t *>(out),
+                                         static_cast<const uint32_t *>(gate), gate_n,
+                                         (hipStream_t)stream);
 }
 #endif
 

@@ -1,4 +1,4 @@
-"""The five workloads: cluster shapes of the paper's tables with seeded Gaussian gradients.
+"""The five workloads (and six more shapes): cluster shapes of the paper's tables with seeded Gaussian gradients.
 
 scheme/a/b follow the library's byz_build_assignment arguments: MOLS (l, r) or
 Ramanujan (s, m).  `cmax` is the value the paper's Tables 3, 4, 6 print for that (graph, q) where one does.
@@ -34,7 +34,15 @@ CONFIGS = [
     Config("cfg7_ram5x7_resnet18_reversed", RAMANUJAN, 5, 7, 25, 35, 7, 5, 6, 6, 11173962,
            {"kind": "reversed", "c": 100.0}, 1, 20101004 + 57),
     # MOLS over F_9 (prime-power l, Sec. 4.1.1): (K,f,l,r) = (27,81,9,3), 243 rows, ALIE, q = 5;
-    # c_max = 8 from the exhaustive search.  f > 64: two-step path with the LDS median kernel
+    # c_max = 8 from the exhaustive search.  f > 64: single pass with two words per thread
     Config("cfg8_mols9x3_resnet18_alie", MOLS, 9, 3, 27, 81, 9, 3, 5, 8, 11173962,
            {"kind": "alie", "z": 1.0}, 1, 20101004 + 93),
+    # Ramanujan Case 2 (Eq. 6) with r = 7 and with r = 5 at f > 64: (K,f,l,r) = (49,49,7,7),
+    # (49,63,9,7), (25,65,13,5); 343, 441 and 325 rows; q = 5, c_max from the exhaustive search
+    Config("cfg9_ram7x7_resnet18_mixed", RAMANUJAN, 7, 7, 49, 49, 7, 7, 5, 1, 11173962,
+           {"kind": "mixed", "z": 1.0, "value": 1e3, "file_scales": True}, 1, 20101004 + 77),
+    Config("cfg10_ram7x9_resnet18_mixed", RAMANUJAN, 7, 9, 49, 63, 9, 7, 5, 2, 11173962,
+           {"kind": "mixed", "z": 1.0, "value": 1e3, "file_scales": True}, 1, 20101004 + 79),
+    Config("cfg11_ram5x13_resnet18_mixed", RAMANUJAN, 5, 13, 25, 65, 13, 5, 5, 6, 11173962,
+           {"kind": "mixed", "z": 1.0, "value": 1e3, "file_scales": True}, 1, 20101004 + 63),
 ]

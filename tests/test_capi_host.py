@@ -217,7 +217,7 @@ def test_selection_network_zero_one_exhaustive(f):
     assert np.array_equal(v[wire], (pop > f // 2).astype(np.uint8))
 
 
-@pytest.mark.parametrize("f", [35, 49, 81, 121, 169])
+@pytest.mark.parametrize("f", [35, 49, 63, 65, 81, 121, 169, 255])
 def test_selection_network_near_balanced_inputs(f):
     ops, wire = gen_selnet.best_network(f)
     rng = np.random.default_rng(f)
@@ -237,6 +237,73 @@ def test_selection_network_near_balanced_inputs(f):
     vals = rng.integers(0, 1000, size=(2000, f))
     for row in vals:
         assert gen_selnet.apply_network(ops, row.tolist())[wire] == sorted(row.tolist())[f // 2]
+
+
+def _run_network_columns(ops, cols):
+    """cols: list of numpy arrays, one per wire; applies (i, j, lo, hi) comparators in place."""
+    for (i, j, lo, hi) in ops:
+        a, b = cols[i], cols[j]
+        if lo:
+            cols[i] = np.minimum(a, b)
+        if hi:
+            cols[j] = np.maximum(a, b)
+    return cols
+
+
+@pytest.mark.parametrize("f", [49, 63, 65, 81, 121])
+def test_pruned_median_network_equals_the_unpruned_sort_on_tie_heavy_data(f):
+    # a second check that shares nothing with the pruning: Batcher's sort on the next power of
+    # two, every comparator kept, spare wires holding the largest value, must leave on wire
+    # (f-1)/2 what the pruned network selects -- on two million columns drawn from a four-letter
+    # alphabet (ties everywhere) and, for one in eight of them, with a single outlier
+    n_pow = 1
+    while n_pow < f:
+        n_pow *= 2
+    full = [(i, j, True, True) for (i, j) in gen_selnet.batcher_sort(n_pow)]
+    ops, wire = gen_selnet.best_network(f)
+    rng = np.random.default_rng(1000 + f)
+    n = 2_000_000
+    data = rng.integers(0, 4, size=(f, n), dtype=np.uint8)
+    data[rng.integers(0, f, size=n // 8), np.arange(n // 8)] = 9
+    pruned = _run_network_columns(ops, [data[i].copy() for i in range(f)])
+    cols = [data[i].copy() for i in range(f)] + [np.full(n, 255, dtype=np.uint8)] * (n_pow - f)
+    sorted_cols = _run_network_columns(full, cols)
+    assert np.array_equal(pruned[wire], sorted_cols[(f - 1) // 2])
+    # and the unpruned sort really sorts: equal to numpy's sort on a slice
+    ref = np.sort(data[:, :20000], axis=0)
+    for i in range(f):
+        assert np.array_equal(sorted_cols[i][:20000], ref[i])
+
+
+@pytest.mark.parametrize("f", gen_selnet.SORT_SIZES)
+def test_sorting_network_sorts(f):
+    # the full-sort networks behind the trimmed mean and Bulyan's second phase: every 0/1 input
+    # for small f (0/1 principle), random 0/1 inputs of every weight and tie-heavy integers
+    # against numpy's sort otherwise; and the streamed order is a valid order of the same network
+    ops, _ = gen_selnet.best_network(f, True)
+    assert all(lo and hi for (_, _, lo, hi) in ops)
+    rng = np.random.default_rng(2000 + f)
+    if f <= 21:
+        idx = np.arange(1 << f, dtype=np.uint32)
+        cols = [((idx >> i) & 1).astype(np.uint8) for i in range(f)]
+    else:
+        n = 300_000
+        w = rng.integers(0, f + 1, size=n)
+        M = (np.argsort(rng.random((n, f)), axis=1) < w[:, None]).astype(np.uint8)
+        cols = [M[:, i].copy() for i in range(f)]
+    ones = sum(c.astype(np.int32) for c in cols)
+    out = _run_network_columns(ops, cols)
+    for i in range(f):
+        assert np.array_equal(out[i], (ones > f - 1 - i).astype(np.uint8)), i
+    vals = rng.integers(0, 7, size=(f, 50_000)).astype(np.int32)
+    out = _run_network_columns(ops, [vals[i].copy() for i in range(f)])
+    assert np.array_equal(np.stack(out), np.sort(vals, axis=0))
+    prog = gen_selnet.streamed_program(f, True)
+    assert len([s_ for s_ in prog if s_[0] == "ce"]) == len(ops)
+    for depth in gen_selnet.DEPTHS:
+        for _ in range(20):
+            v = rng.integers(0, 60, size=f).tolist()
+            assert gen_selnet.run_streamed(prog, v, depth) == sorted(v)
 
 
 @pytest.mark.parametrize("f", gen_selnet.STREAMED_SIZES)
