@@ -158,9 +158,9 @@ int byz_vote(const float *copies, int64_t d, int64_t ld, const int32_t *file_row
              void *stream);
 
 /*
- * Majority vote for honest copies that agree only up to rounding.  Sec. 2 notes that precision
- * issues between honest workers "can be handled by ... defining appropriate clusters amongst
- * the returned gradients" and gives no rule; the rule here: two words are close iff their bit
+ * Majority vote for honest copies that agree only up to rounding.  Sec. 2 remarks that such
+ * precision differences between honest workers could be dealt with by voting over clusters of
+ * nearby vectors and gives no rule; the rule here: two words are close iff their bit
  * patterns are identical or |a - b| <= atol + rtol * max(|a|, |b|), the subtraction, the
  * product and the sum each rounded to fp32 (a NaN is close only to an identical NaN); two
  * copies are close iff all d words are; the winner of a file is the copy with the most close
@@ -181,13 +181,11 @@ int byz_vote_tolerant(const float *copies, int64_t d, int64_t ld, const int32_t 
  * out[c] = element of rank (f-1)/2 of { rows_base[row_index[j]*ld + c] : j < f }.
  *   rows_base     device [*][ld] fp32;  row_index_dev device [f] int32;  out device [d] fp32,
  *                 must not overlap the input rows (may be NULL when d == 0).
- * f odd, 1 <= f <= BYZ_MAX_F_WIDE.  A register selection network does the work for every
- * f <= 169: generated for f in {3,5,7,9,15,21,25,35,49,81,121,169} (the paper's file and
- * worker counts and MOLS over F_9, F_11, F_13), any other f on the next of those sizes with the spare wires
- * tied half to the smallest and half to the largest key (f = 27: 0.23 ms for 11.2 M
- * coordinates, f = 63: 1.1 ms).  169 < f keeps the f keys of a coordinate in LDS and finds the
- * median by bisection on the key (slow).  Errors: BYZ_EINVAL, BYZ_EUNSUPPORTED (even f),
- * BYZ_EDEVICE.
+ * f odd, 1 <= f <= 255.  A register selection network does the work for every f: generated for
+ * f in {3,5,7,9,15,21,25,35,49,81,121,169,255} (the paper's file and worker counts, MOLS over
+ * F_9, F_11, F_13, and the widest size), any other f on the next of those sizes with the spare
+ * wires tied half to the smallest and half to the largest key (11.2 M coordinates: f = 27 0.23 ms,
+ * f = 63 1.1 ms, f = 255 3.9 ms).  Errors: BYZ_EINVAL, BYZ_EUNSUPPORTED (even f), BYZ_EDEVICE.
  */
 int byz_median(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev,
                int f, float *out, void *stream);
@@ -202,9 +200,9 @@ int byz_median(const float *rows_base, int64_t d, int64_t ld, const int32_t *row
  * infinities go first).  b = 0 is the plain mean.  Not pure selection; the rounding contract
  * is: fp32, kept values added one by one in ascending order starting from +0, then one IEEE
  * division by float(f - 2b).
- *   f in {9,15,21,25,35,49,81,121,169} runs a generated register sorting network, any other
- *   f <= 169 the next of those sizes with the spare wires tied to the largest key, 169 < f <=
- *   BYZ_MAX_F_WIDE an insertion sort of the coordinate's keys in LDS (slow).
+ *   f in {9,15,21,25,35,49,81,121,169,256} runs a generated register sorting network, any other
+ *   f <= BYZ_MAX_F_WIDE the next of those sizes with the spare wires tied to the largest key
+ *   (11.2 M coordinates: f = 25 0.19 ms, f = 81 0.85 ms, f = 255 5.7 ms).
  * Errors: BYZ_EINVAL (null pointers, sizes, b < 0 or 2b >= f), BYZ_EDEVICE.
  */
 int byz_trimmed_mean(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev,

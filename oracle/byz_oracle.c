@@ -92,8 +92,8 @@ int oracle_vote_threads(const uint32_t *X, int64_t d, int64_t ld, const int32_t 
 }
 
 /*
- * Tolerant vote (Sec. 2: precision issues "can be handled by ... appropriate clusters"; the
- * paper gives no rule).  Two words are close iff their bit patterns are identical or
+ * Tolerant vote (Sec. 2 suggests voting over clusters of nearby vectors when honest copies
+ * differ by rounding; the paper gives no rule).  Two words are close iff their bit patterns are identical or
  * |a - b| <= atol + rtol * max(|a|, |b|), every operation rounded to fp32; two copies are close
  * iff all d words are; count[a] = copies close to a (itself included); smallest a with the
  * largest count wins.  pair_far: bit p set iff pair p is not close.

@@ -324,9 +324,9 @@ def words_close(xa, xb, atol, rtol):
 
 
 def vote_tolerant(X, rows, d, atol, rtol):
-    """Majority vote for honest copies that agree only up to rounding (Sec. 2 notes that
-    precision issues "can be handled by deciding the majority by defining appropriate clusters"
-    and gives no rule).  Reading used here: two copies are close iff every one of their d
+    """Majority vote for honest copies that agree only up to rounding (Sec. 2 remarks that
+    precision differences between honest workers could be dealt with by voting over clusters of
+    nearby vectors, without giving a rule).  Reading used here: two copies are close iff every one of their d
     coordinates is close (words_close); count[a] = number of copies close to copy a, itself
     included; the winner is the smallest a with the largest count.  Closeness is not
     transitive, so this is a count of neighbours, not a partition.

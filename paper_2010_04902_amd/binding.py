@@ -6,6 +6,7 @@ library cannot be loaded the import of this module's functions raises.
 """
 import ctypes
 import os
+import weakref
 
 import numpy as np
 
@@ -192,6 +193,37 @@ def _need(t, n, what):
         raise ValueError("%s has %d elements, the call needs %d" % (what, int(t.numel()), n))
 
 
+_checked_tables = {}
+
+
+def _need_rows_in_range(table, count, n_rows, what):
+    """The kernels trust the row numbers they are given (they are not range-checked on the
+    device): refuse, before any launch, a table whose first `count` entries do not all lie in
+    [0, n_rows).  The minimum and maximum are read back once per tensor object -- remembered
+    through a weak reference, with torch's modification counter -- so repeated calls with one
+    table cost nothing, and a new tensor that happens to reuse the memory is looked at afresh."""
+    if count <= 0:
+        return
+    _need(table, count, what)
+    if table.is_cuda and _torch().cuda.is_current_stream_capturing():
+        # nothing can be read back while a graph is being captured, and a table a captured
+        # kernel will write (winner rows of a vote in the same graph) has no contents yet:
+        # there the caller vouches for the table
+        return
+    entry = _checked_tables.get(id(table))
+    if entry is not None and entry[0]() is table and entry[1] == (int(table._version), int(count)):
+        bounds = entry[2]
+    else:
+        head = table.reshape(-1)[:count]
+        bounds = (int(head.min()), int(head.max()))
+        if len(_checked_tables) >= 256:
+            _checked_tables.clear()
+        _checked_tables[id(table)] = (weakref.ref(table), (int(table._version), int(count)), bounds)
+    if bounds[0] < 0 or bounds[1] >= n_rows:
+        raise ValueError("%s names rows %d..%d, the matrix has rows 0..%d"
+                         % (what, bounds[0], bounds[1], n_rows - 1))
+
+
 def _rows_2d(copies):
     if copies.dim() != 2:
         raise ValueError("copies must be [rows, ld]")
@@ -202,7 +234,7 @@ def byz_vote(copies, d, file_rows_dev, f, r, stream=None):
     """-> (winner_replica[f] int32, winner_row[f] int32, pair_neq[f] int32 bit masks), on device."""
     torch = _torch()
     ld = _rows_2d(copies)
-    _need(file_rows_dev, int(f) * int(r), "file_rows_dev")
+    _need_rows_in_range(file_rows_dev, int(f) * int(r), int(copies.shape[0]), "file_rows_dev")
     wrep = torch.empty(max(int(f), 0), dtype=torch.int32, device=copies.device)
     wrow = torch.empty(max(int(f), 0), dtype=torch.int32, device=copies.device)
     neq = torch.empty(max(int(f), 0), dtype=torch.int32, device=copies.device)
@@ -219,7 +251,7 @@ def byz_vote_tolerant(copies, d, file_rows_dev, f, r, atol, rtol, stream=None):
     """-> (winner_replica[f] int32, winner_row[f] int32, pair_far[f] int32 bit masks), on device."""
     torch = _torch()
     ld = _rows_2d(copies)
-    _need(file_rows_dev, int(f) * int(r), "file_rows_dev")
+    _need_rows_in_range(file_rows_dev, int(f) * int(r), int(copies.shape[0]), "file_rows_dev")
     wrep = torch.empty(max(int(f), 0), dtype=torch.int32, device=copies.device)
     wrow = torch.empty(max(int(f), 0), dtype=torch.int32, device=copies.device)
     far = torch.empty(max(int(f), 0), dtype=torch.int32, device=copies.device)
@@ -237,6 +269,7 @@ def byz_median(rows_base, d, row_index_dev, out=None, stream=None):
     torch = _torch()
     ld = _rows_2d(rows_base)
     f = int(row_index_dev.numel())
+    _need_rows_in_range(row_index_dev, f, int(rows_base.shape[0]), "row_index_dev")
     if out is None:
         out = torch.empty(int(d), dtype=torch.float32, device=rows_base.device)
     _need(out, int(d), "out")
@@ -251,6 +284,7 @@ def byz_trimmed_mean(rows_base, d, row_index_dev, b, out=None, stream=None):
     torch = _torch()
     ld = _rows_2d(rows_base)
     f = int(row_index_dev.numel())
+    _need_rows_in_range(row_index_dev, f, int(rows_base.shape[0]), "row_index_dev")
     if out is None:
         out = torch.empty(int(d), dtype=torch.float32, device=rows_base.device)
     _need(out, int(d), "out")
@@ -271,8 +305,10 @@ def byz_multi_krum(rows_base, d, row_index_dev, c, m, out=None, workspace=None, 
     ld = _rows_2d(rows_base)
     f = int(row_index_dev.numel())
     dev = rows_base.device
+    _need_rows_in_range(row_index_dev, f, int(rows_base.shape[0]), "row_index_dev")
     if out is None:
         out = torch.empty(int(d), dtype=torch.float32, device=dev)
+    _need(out, int(d), "out")
     if workspace is None:
         workspace = torch.empty(max(byz_multi_krum_workspace_bytes(f), 256), dtype=torch.uint8, device=dev)
     selected = torch.empty(f, dtype=torch.int32, device=dev)
@@ -299,6 +335,7 @@ def byz_bulyan(rows_base, d, row_index_dev, c, out=None, workspace=None, stream=
     ld = _rows_2d(rows_base)
     f = int(row_index_dev.numel())
     dev = rows_base.device
+    _need_rows_in_range(row_index_dev, f, int(rows_base.shape[0]), "row_index_dev")
     if out is None:
         out = torch.empty(int(d), dtype=torch.float32, device=dev)
     _need(out, int(d), "out")
@@ -356,7 +393,7 @@ def byz_aggregate(copies, d, file_rows_dev, f, r, out=None, winner_replica=None,
         if nbytes == 0:
             raise ByzError(-1, "byz_aggregate_workspace_bytes")
         workspace = torch.empty(nbytes, dtype=torch.uint8, device=copies.device)
-    _need(file_rows_dev, int(f) * int(r), "file_rows_dev")
+    _need_rows_in_range(file_rows_dev, int(f) * int(r), int(copies.shape[0]), "file_rows_dev")
     _need(out, int(d), "out")
     _need(winner_replica, int(f), "winner_replica")
     args = [_dev_ptr(copies, ("float32",), "copies"), int(d), ld,
@@ -374,7 +411,7 @@ def byz_aggregate(copies, d, file_rows_dev, f, r, out=None, winner_replica=None,
 def byz_aggregate_static(copies, d, file_rows_dev, f, r, out, winner_replica, flags=0, stream=None):
     """byz_aggregate_opts on the library's own fixed scratch; the caller supplies every buffer."""
     ld = _rows_2d(copies)
-    _need(file_rows_dev, int(f) * int(r), "file_rows_dev")
+    _need_rows_in_range(file_rows_dev, int(f) * int(r), int(copies.shape[0]), "file_rows_dev")
     _need(out, int(d), "out")
     _need(winner_replica, int(f), "winner_replica")
     _check(_load().byz_aggregate_static(_dev_ptr(copies, ("float32",), "copies"), int(d), ld,

@@ -401,3 +401,38 @@ def test_symmetry_reduced_search_on_the_largest_table_row():
         with pytest.raises(B.ByzError) as e:
             B.byz_worst_case(big, 3, flags)
         assert e.value.code == -1
+
+
+def test_binding_refuses_row_tables_that_point_outside_the_matrix():
+    # the kernels do not range-check row numbers; the binding does, before anything is launched
+    # (the check comes first, so it can be exercised here with host tensors and no GPU)
+    import torch
+    X = torch.zeros((75, 64), dtype=torch.float32)
+    good = torch.arange(75, dtype=torch.int32)
+    for bad in (good.clone().index_fill_(0, torch.tensor([7]), 75),
+                good.clone().index_fill_(0, torch.tensor([74]), -1),
+                good + 1):
+        with pytest.raises(ValueError, match="names rows"):
+            B.byz_vote(X, 64, bad, 25, 3)
+        with pytest.raises(ValueError, match="names rows"):
+            B.byz_aggregate(X, 64, bad, 25, 3)
+        with pytest.raises(ValueError, match="names rows"):
+            B.byz_aggregate_static(X, 64, bad, 25, 3, torch.zeros(64), torch.zeros(25, dtype=torch.int32))
+        for fn in (lambda t: B.byz_median(X, 64, t[:25]), lambda t: B.byz_trimmed_mean(X, 64, t[:25], 2),
+                   lambda t: B.byz_multi_krum(X, 64, t[:25], 3, 20), lambda t: B.byz_bulyan(X, 64, t[:25], 3)):
+            if int(bad[:25].min()) < 0 or int(bad[:25].max()) >= 75:
+                with pytest.raises(ValueError, match="names rows"):
+                    fn(bad)
+    # a table that is too short is still refused by length, and a good one gets past the row
+    # check (to the next complaint: these are host tensors)
+    with pytest.raises(ValueError, match="elements"):
+        B.byz_vote(X, 64, good[:74], 25, 3)
+    with pytest.raises(ValueError, match="CUDA"):
+        B.byz_vote(X, 64, good, 25, 3)
+    # an edit in place is seen (torch's modification counter is part of the cache key)
+    t = good.clone()
+    with pytest.raises(ValueError, match="CUDA"):
+        B.byz_median(X, 64, t[:25])
+    t[3] = 1000
+    with pytest.raises(ValueError, match="names rows"):
+        B.byz_median(X, 64, t[:25])
