@@ -1,4 +1,4 @@
-"""The five workloads (and six more shapes): cluster shapes of the paper's tables with seeded Gaussian gradients.
+"""The five workloads (and eight more shapes): cluster shapes of the paper's tables with seeded Gaussian gradients.
 
 scheme/a/b follow the library's byz_build_assignment arguments: MOLS (l, r) or
 Ramanujan (s, m).  `cmax` is the value the paper's Tables 3, 4, 6 print for that (graph, q) where one does.
@@ -45,4 +45,10 @@ CONFIGS = [
            {"kind": "mixed", "z": 1.0, "value": 1e3, "file_scales": True}, 1, 20101004 + 79),
     Config("cfg11_ram5x13_resnet18_mixed", RAMANUJAN, 5, 13, 25, 65, 13, 5, 5, 6, 11173962,
            {"kind": "mixed", "z": 1.0, "value": 1e3, "file_scales": True}, 1, 20101004 + 63),
+    # MOLS over F_11 and F_13: (K,f,l,r) = (33,121,11,3) and (39,169,13,3), 363 and 507 rows,
+    # ALIE, q = 4; c_max = 5 from the exhaustive search
+    Config("cfg12_mols11x3_resnet18_alie", MOLS, 11, 3, 33, 121, 11, 3, 4, 5, 11173962,
+           {"kind": "alie", "z": 1.0}, 1, 20101004 + 113),
+    Config("cfg13_mols13x3_resnet18_alie", MOLS, 13, 3, 39, 169, 13, 3, 4, 5, 11173962,
+           {"kind": "alie", "z": 1.0}, 1, 20101004 + 133),
 ]
