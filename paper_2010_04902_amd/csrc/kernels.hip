@@ -1252,6 +1252,9 @@ int launch_median(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_i
     if (f <= 25) return launch_median_large<25, true>(X, d, ld, row_index, f, out, gate, gate_n, s);
     if (f <= 35) return launch_median_large<35, true>(X, d, ld, row_index, f, out, gate, gate_n, s);
     if (f <= 49) return launch_median_large<49, true>(X, d, ld, row_index, f, out, gate, gate_n, s);
+    if ((f == 63 || f == 65) && d >= vec_for(81))  // Ramanujan Case 2 shapes (63,7), (65,5)
+        return f == 63 ? launch_median_large<63, false>(X, d, ld, row_index, f, out, gate, gate_n, s)
+                       : launch_median_large<65, false>(X, d, ld, row_index, f, out, gate, gate_n, s);
     if (f == 81 && d >= vec_for(81))
         return launch_median_large<81, false>(X, d, ld, row_index, f, out, gate, gate_n, s);
     if (f <= 81 && d >= vec_for(81))
