@@ -325,7 +325,7 @@ def main():
             ms_bu = timed_call(lambda: B.byz_bulyan(bufs[0], d, wrow_v, bu_c, out=out,
                                                     workspace=mk_ws, stream=stream))
         # early-majority mode when its assumption breaks (one changed word in one of the r' copies
-        # it reads of a clean file): single pass, vote over all copies, median
+        # it reads of a clean file): single pass, then all copies of that file are compared
         ms_revote, revote_path = None, None
         if single_pass and d > 1000 and clean:
             planted = bufs[0].clone()
@@ -367,9 +367,10 @@ def main():
                         "of the bytes costs"},
             "early_majority_revote": None if ms_revote is None else {
                 "ms": ms_revote, "byz_path": revote_path,
-                "algorithmic_bytes": 4.0 * (((asg.r + 1) // 2) * asg.f + 1) * d + vb + mb,
-                "note": "early-majority mode with one changed word in one of the r' copies it reads: "
-                        "single pass over r' copies, then the vote over all copies and the median"},
+                "algorithmic_bytes": 4.0 * (((asg.r + 1) // 2) * asg.f + 1) * d + 4.0 * asg.r * d,
+                "note": "early-majority mode with one changed word in one of the r' copies it reads "
+                        "(not the guessed one): single pass over r' copies, then all r copies of "
+                        "that one file are compared; the guessed copy is still a winner, no median"},
             "byz_multi_krum": None if ms_mk is None else {
                 "ms": ms_mk, "c": cmax, "m": mk_m, "algorithmic_bytes": kb,
                 "gbps": kb / ms_mk / 1e6, "frac": kb / ms_mk / 1e6 / HBM_PEAK_GBPS,

@@ -307,9 +307,10 @@ int byz_aggregate(const float *copies, int64_t d, int64_t ld, const int32_t *fil
  *     least r' members only r' copies are read and compared.  Same output as flags = 0 for
  *     every input; HBM traffic drops from 4(rf+1) towards 4(r'f+1) bytes per coordinate.
  *     If the r' copies read of some file turn out to differ (off the probe's sample), nothing
- *     is known about the copies that were skipped: the vote is then redone over all copies
- *     and the median after it (BYZ_PATH_REVOTED), about 2.2 times the time of flags = 0.  One
- *     worker can cause that with one changed word, so the mode suits trusted-timing settings.
+ *     is known about the copies that were skipped: all copies of those files are then compared
+ *     (BYZ_PATH_REVOTED; 4rd more bytes per such file) and, if a guessed copy lost, the median
+ *     is redone.  Every Byzantine worker can do that to the l files it holds, so in the worst
+ *     case the mode costs more than flags = 0; it suits settings where timing is not attacked.
  *     Ignored where the single pass does not run.
  * Errors: as byz_aggregate; BYZ_EINVAL for unknown flag bits.
  */
@@ -362,9 +363,9 @@ typedef enum byz_path {
     BYZ_PATH_SINGLE_PASS = 0,   /* the single pass's output stood                                 */
     BYZ_PATH_MEDIAN_REDONE = 1, /* some guessed copy was not its file's winner: the median was
                                    redone from the true winners (bit 0)                          */
-    BYZ_PATH_REVOTED = 2,       /* early-majority mode only: the r' copies read of some file
-                                   differed; vote over all copies, then median (bit 1, always
-                                   together with bit 0: the value read back is 3)                */
+    BYZ_PATH_REVOTED = 2,       /* early-majority mode only: the r' copies read of some files
+                                   differed and all copies of those files were compared (bit 1;
+                                   with bit 0 if the median was redone as well: 3)               */
     BYZ_PATH_TWO_STEP = 4       /* no single pass for this (f, r) or d < 4: byz_vote's and
                                    byz_median's kernels one after the other                      */
 } byz_path;

@@ -78,6 +78,12 @@ constexpr bool has_streamed_network(int f) {
 }
 // words per thread: fewer for the large networks, whose keys fill the register file
 constexpr int vec_for(int f) { return f <= 49 ? 4 : (f <= 81 ? 2 : 1); }
+// ... of the median kernels: above 49 wires they are bound by min/max issue, and one word per
+// thread (fewer registers, more waves per SIMD) measured 4-8 % faster than two at f = 63, 81
+constexpr int vec_for_median(int f) { return f <= 49 ? 4 : 1; }
+// ... and of the sorting-network kernels (trimmed mean, second phase of Bulyan), where narrower
+// threads gained nothing at f = 49 and 81
+constexpr int vec_for_sort(int f) { return vec_for(f); }
 // ... and of the single pass: with five or seven copies of a file in flight two words per thread
 // (more waves per SIMD, 8-byte loads) measured 1-2 % faster than four (r = 7 would not fit
 // the registers with four); with three copies four words are faster
@@ -305,6 +311,7 @@ struct AggWorkspace {
     // own (r, or r' for a file read in early-majority mode; the other slots repeat slot 0)
     uint32_t perm[kWide];
     int32_t winner_row[kWide];       // rows of the true winners (decided after the pass)
+    uint32_t revote_file[kWide];     // early-majority mode: 1 for the files whose r' copies differed
     uint32_t need_median;            // 1: some file's slot 0 was not its winner -> median redone
     uint32_t need_revote;            // 1: early-majority mode met a file whose r' copies differ
     uint32_t path;                   // byz_path of the call, for byz_aggregate_path
@@ -438,7 +445,9 @@ __global__ void single_pass_decide_kernel(AggWorkspace *ws, const int32_t *__res
             if (winner_replica != nullptr) winner_replica[j] = w;
             ws->winner_row[j] = file_rows[j * r + w];
             if (differ_bits != 0) s_revote = 1;
+            ws->revote_file[j] = differ_bits;
         }
+        if (own == r) ws->revote_file[j] = 0;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -450,12 +459,25 @@ __global__ void single_pass_decide_kernel(AggWorkspace *ws, const int32_t *__res
 }
 
 // Early-majority mode only, after the gated vote kernel: if the decision above asked for a
-// re-vote, the winners come from the pair bits that kernel collected and the median is redone.
+// re-vote, the winners of the files it named come from the pair bits that kernel collected
+// for them, and the median is redone if one of those files' guessed copies lost.
 __global__ void revote_decide_kernel(AggWorkspace *ws, const int32_t *__restrict__ file_rows, int f,
                                      int r, int32_t *winner_replica) {
     if (ws->need_revote == 0) return;
-    decide_files(ws->pair_neq, file_rows, f, r, winner_replica, ws->winner_row);
-    if (threadIdx.x == 0) {
+    __shared__ uint32_t s_median;
+    if (threadIdx.x == 0) s_median = 0;
+    __syncthreads();
+    const int j = threadIdx.x;
+    if (j < f && ws->revote_file[j] != 0) {  // the other files keep the winners decided above
+        const uint32_t neq = load_shared_word(&ws->pair_neq[j]);
+        const int a = decide_winner(neq, r);
+        if (winner_replica != nullptr) winner_replica[j] = a;
+        ws->winner_row[j] = file_rows[j * r + a];
+        // the output stands if the copy that fed the network is one of the winners after all
+        if (!copies_equal(neq, r, perm_slot(ws->perm[j], 0), a)) s_median = 1;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0 && s_median != 0) {
         ws->need_median = 1;
         ws->path = (uint32_t)BYZ_PATH_REVOTED | (uint32_t)BYZ_PATH_MEDIAN_REDONE;
     }
@@ -463,11 +485,13 @@ __global__ void revote_decide_kernel(AggWorkspace *ws, const int32_t *__restrict
 
 // Vote, comparison: for every file, which pairs of copies differ anywhere in [0, d).  Threads own
 // vectors of V words; the d % V trailing words go to the first threads of the last block.
-// If `gate` is given, the kernel only runs when one of gate[0..gate_n-1] is nonzero.
+// If `gate` is given, the kernel only runs when one of gate[0..gate_n-1] is nonzero; if
+// `only_files` is given, only the files j with only_files[j] != 0 are read and compared.
 template <int R, int V>
 __global__ __launch_bounds__(kBlock) void vote_pairs_kernel(
     const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ file_rows,
-    int f, uint32_t *pair_neq, const uint32_t *__restrict__ gate, int gate_n) {
+    int f, uint32_t *pair_neq, const uint32_t *__restrict__ gate, int gate_n,
+    const uint32_t *__restrict__ only_files) {
     if (gate != nullptr && !any_word_set(gate, gate_n)) return;
     const int lane = threadIdx.x & 63;
     const int64_t n_vec = d / V;
@@ -480,6 +504,7 @@ __global__ __launch_bounds__(kBlock) void vote_pairs_kernel(
             const int j1 = j0 + 64 < f ? j0 + 64 : f;
             uint32_t flags = 0;
             for (int j = j0; j < j1; ++j) {
+                if (only_files != nullptr && only_files[j] == 0) continue;  // the same for every thread
                 uint32_t x[R][V];
 #pragma unroll
                 for (int k = 0; k < R; ++k)
@@ -499,6 +524,7 @@ __global__ __launch_bounds__(kBlock) void vote_pairs_kernel(
     if (blockIdx.x == gridDim.x - 1 && (int)threadIdx.x < tail) {
         const int64_t c = n_vec * V + threadIdx.x;
         for (int j = 0; j < f; ++j) {
+            if (only_files != nullptr && only_files[j] == 0) continue;
             uint32_t x[R];
 #pragma unroll
             for (int k = 0; k < R; ++k) x[k] = X[(int64_t)file_rows[j * R + k] * ld + c];
@@ -684,7 +710,7 @@ __global__ __launch_bounds__(kBlock) void median_kernel(
     }
 }
 
-// Coordinate-wise median by the streamed program of the generated network on F wires with V = vec_for(F)
+// Coordinate-wise median by the streamed program of the generated network on F wires with V = vec_for_median(F)
 // words per thread: the large networks (F = 81, 121: MOLS over F_9 and F_11) and, with PAD,
 // any odd f < F on the next generated size -- the F - f spare wires reload row_index[0] and
 // are tied half to the smallest and half to the largest key, which leaves the median where
@@ -704,7 +730,8 @@ __global__ __launch_bounds__(kBlock) void median_large_kernel(
     uint32_t key[V][F];
     uint32_t o[V];
     constexpr int NS = 1;
-    constexpr int kAhead = prefetch_depth(F, NS);
+    // one word per thread: 4-byte loads, twenty files ahead (as measured best at F = 121)
+    constexpr int kAhead = V == 1 ? 20 : prefetch_depth(F, NS);
     const uint32_t voff = (uint32_t)(c0 * 4);
     const char *Xb = reinterpret_cast<const char *>(X);
     uint32_t stage[kAhead + 1][NS][V];
@@ -1159,19 +1186,21 @@ inline unsigned blocks_for(int64_t n_vec) {
 #if BYZ_IN_PART(0)
 template <int R>
 int launch_vote_pairs(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, int f,
-                      uint32_t *neq, const uint32_t *gate, int gate_n, hipStream_t s) {
+                      uint32_t *neq, const uint32_t *gate, int gate_n, const uint32_t *only_files,
+                      hipStream_t s) {
     vote_pairs_kernel<R, kVec><<<blocks_for(d / kVec), kBlock, 0, s>>>(X, d, ld, rows, f, neq, gate,
-                                                                      gate_n);
+                                                                      gate_n, only_files);
     BYZ_HIP(hipGetLastError());
     return BYZ_OK;
 }
 
 int launch_vote_pairs_r(int r, const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows,
-                        int f, uint32_t *neq, const uint32_t *gate, int gate_n, hipStream_t s) {
+                        int f, uint32_t *neq, const uint32_t *gate, int gate_n,
+                        const uint32_t *only_files, hipStream_t s) {
     switch (r) {
-        case 3: return launch_vote_pairs<3>(X, d, ld, rows, f, neq, gate, gate_n, s);
-        case 5: return launch_vote_pairs<5>(X, d, ld, rows, f, neq, gate, gate_n, s);
-        case 7: return launch_vote_pairs<7>(X, d, ld, rows, f, neq, gate, gate_n, s);
+        case 3: return launch_vote_pairs<3>(X, d, ld, rows, f, neq, gate, gate_n, only_files, s);
+        case 5: return launch_vote_pairs<5>(X, d, ld, rows, f, neq, gate, gate_n, only_files, s);
+        case 7: return launch_vote_pairs<7>(X, d, ld, rows, f, neq, gate, gate_n, only_files, s);
         default: return BYZ_EINVAL;
     }
 }
@@ -1214,7 +1243,7 @@ int launch_median_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *r
 template <int F, bool PAD>
 int launch_median_large(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
                         uint32_t *out, const uint32_t *gate, int gate_n, hipStream_t s) {
-    constexpr int V = vec_for(F);
+    constexpr int V = vec_for_median(F);
     median_large_kernel<F, V, PAD><<<blocks_for((d + V - 1) / V), kBlock, 0, s>>>(
         X, d, ld, row_index, f, out, gate, gate_n);
     BYZ_HIP(hipGetLastError());
@@ -1252,12 +1281,12 @@ int launch_median(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_i
     if (f <= 25) return launch_median_large<25, true>(X, d, ld, row_index, f, out, gate, gate_n, s);
     if (f <= 35) return launch_median_large<35, true>(X, d, ld, row_index, f, out, gate, gate_n, s);
     if (f <= 49) return launch_median_large<49, true>(X, d, ld, row_index, f, out, gate, gate_n, s);
-    if ((f == 63 || f == 65) && d >= vec_for(81))  // Ramanujan Case 2 shapes (63,7), (65,5)
+    if ((f == 63 || f == 65) && d >= vec_for_median(81))  // Ramanujan Case 2 shapes (63,7), (65,5)
         return f == 63 ? launch_median_large<63, false>(X, d, ld, row_index, f, out, gate, gate_n, s)
                        : launch_median_large<65, false>(X, d, ld, row_index, f, out, gate, gate_n, s);
-    if (f == 81 && d >= vec_for(81))
+    if (f == 81 && d >= vec_for_median(81))
         return launch_median_large<81, false>(X, d, ld, row_index, f, out, gate, gate_n, s);
-    if (f <= 81 && d >= vec_for(81))
+    if (f <= 81 && d >= vec_for_median(81))
         return launch_median_large<81, true>(X, d, ld, row_index, f, out, gate, gate_n, s);
     if (f == 121) return launch_median_large<121, false>(X, d, ld, row_index, f, out, gate, gate_n, s);
     if (f <= 121) return launch_median_large<121, true>(X, d, ld, row_index, f, out, gate, gate_n, s);
@@ -1295,7 +1324,7 @@ int launch_fused(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, 
 template <int F, bool PAD>
 int launch_trimmed_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
                        int b, uint32_t *O, const uint32_t *gate, int gate_n, hipStream_t s) {
-    constexpr int V = vec_for(F);
+    constexpr int V = vec_for_sort(F);
     trimmed_mean_kernel<F, V, PAD><<<blocks_for((d + V - 1) / V), kBlock, 0, s>>>(
         X, d, ld, row_index, f, b, O, gate, gate_n);
     BYZ_HIP(hipGetLastError());
@@ -1332,9 +1361,9 @@ int launch_trimmed_mean(const uint32_t *X, int64_t d, int64_t ld, const int32_t 
         if (f <= 35) return launch_trimmed_net<35, true>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
         if (f <= 49) return launch_trimmed_net<49, true>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
     }
-    if (f == 81 && d >= vec_for(81))
+    if (f == 81 && d >= vec_for_sort(81))
         return launch_trimmed_net<81, false>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
-    if (f <= 81 && d >= vec_for(81))
+    if (f <= 81 && d >= vec_for_sort(81))
         return launch_trimmed_net<81, true>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
     if (f == 121) return launch_trimmed_net<121, false>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
     if (f <= 121) return launch_trimmed_net<121, true>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
@@ -1350,7 +1379,7 @@ int launch_trimmed_mean(const uint32_t *X, int64_t d, int64_t ld, const int32_t 
 template <int F>
 int launch_bulyan_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *selected_rows,
                       int theta, int beta, uint32_t *O, hipStream_t s) {
-    constexpr int V = vec_for(F);
+    constexpr int V = vec_for_sort(F);
     constexpr int BLOCK = F > 49 ? 64 : kBlock;
     constexpr size_t lds = (size_t)F * BLOCK * 4;
     static_assert(lds <= 64 * 1024, "more than a kernel may use without asking");
@@ -1655,7 +1684,7 @@ extern "C" int byz_vote(const float *copies, int64_t d, int64_t ld, const int32_
     fill_u32_kernel<<<1, kWide, 0, s>>>(pair_neq, f, 0u);
     BYZ_HIP(hipGetLastError());
     if (d > 0) {
-        rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, pair_neq, nullptr, 0, s);
+        rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, pair_neq, nullptr, 0, nullptr, s);
         if (rc != BYZ_OK) return rc;
     }
     vote_decide_kernel<<<1, kWide, 0, s>>>(pair_neq, file_rows_dev, f, r, winner_replica,
@@ -1745,7 +1774,7 @@ static int aggregate_on_workspace(const float *copies, int64_t d, int64_t ld,
         if (d > 0) {
             rc = byz_internal_profile_mark(0, s);
             if (rc != BYZ_OK) return rc;
-            rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, nullptr, 0, s);
+            rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, nullptr, 0, nullptr, s);
             if (rc != BYZ_OK) return rc;
             rc = byz_internal_profile_mark(1, s);
             if (rc != BYZ_OK) return rc;
@@ -1780,7 +1809,8 @@ static int aggregate_on_workspace(const float *copies, int64_t d, int64_t ld,
     single_pass_decide_kernel<<<1, kWide, 0, s>>>(ws, file_rows_dev, f, r, winner_replica);
     BYZ_HIP(hipGetLastError());
     if ((flags & BYZ_AGG_EARLY_MAJORITY) != 0) {
-        rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, &ws->need_revote, 1, s);
+        rc = launch_vote_pairs_r(r, X, d, ld, file_rows_dev, f, ws->pair_neq, &ws->need_revote, 1,
+                                 ws->revote_file, s);
         if (rc != BYZ_OK) return rc;
         revote_decide_kernel<<<1, kWide, 0, s>>>(ws, file_rows_dev, f, r, winner_replica);
         BYZ_HIP(hipGetLastError());

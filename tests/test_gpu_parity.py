@@ -57,7 +57,7 @@ def _check_all(X, rows_np, d, f, r, expect_path=None, tag=""):
             if expect_path is not None:
                 assert path == expect_path, (tag, path)
         else:
-            assert path in (SINGLE, REDONE, REDONE | REVOTED, TWO_STEP), (tag, path)
+            assert path in (SINGLE, REDONE, REVOTED, REDONE | REVOTED, TWO_STEP), (tag, path)
     out, wrep2, ws = B.byz_aggregate(X, d, rows_dev, f, r)
     torch.cuda.synchronize()
     assert np.array_equal(W.bits(out), W.bits(out_o)), tag
@@ -164,6 +164,17 @@ def test_copy_that_matches_on_the_probe_sample_but_differs_elsewhere():
     _plant(X2, w.file_rows, 8, 0, unsampled[:1], -3.0)
     out_o, wrep_o, _ = _check_all(X2, w.file_rows, d, w.f, w.r, expect_path=REDONE)
     assert wrep_o[8] == 1
+    # early-majority mode reads replicas 0 and 1 of such a file: a changed word in replica 2 is
+    # never seen (and cannot matter); in replica 1 it makes the two copies differ, all three
+    # copies of that one file are compared, replica 0 turns out to be a winner: no median; in
+    # replica 0 the median is redone as well.  (_check_all has compared the outputs above.)
+    rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+    for k, want in [(2, SINGLE), (1, REVOTED), (0, REVOTED | REDONE)]:
+        Xe = w.X.clone()
+        _plant(Xe, w.file_rows, 8, k, unsampled[:1], -3.0)
+        _, _, ws = B.byz_aggregate_opts(Xe, d, rows_dev, w.f, w.r, B.BYZ_AGG_EARLY_MAJORITY)
+        torch.cuda.synchronize()
+        assert B.byz_aggregate_path(ws) == want, (k, want)
     # replicas 0 and 2 of file 3 both deviate (identically) off the sample: the probe thinks all
     # three are equal, the true classes are {0,2},{1}, and the guessed copy is still a winner
     X3 = w.X.clone()
