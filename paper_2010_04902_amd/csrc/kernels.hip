@@ -81,8 +81,11 @@ constexpr int vec_for(int f) { return f <= 49 ? 4 : (f <= 81 ? 2 : 1); }
 // ... of the median kernels: above 49 wires they are bound by min/max issue, and one word per
 // thread (fewer registers, more waves per SIMD) measured 4-8 % faster than two at f = 63, 81
 constexpr int vec_for_median(int f) { return f <= 49 ? 4 : 1; }
-// ... and of the sorting-network kernels (trimmed mean, second phase of Bulyan), where narrower
-// threads gained nothing at f = 49 and 81
+// ... of the trimmed-mean kernels: the same above 49 wires (f = 81: 5 % faster, fewer files on
+// the 81-wire network: 15 %); at f = 49 the kernel runs at the vector ALU's practical limit
+// whatever the width (0.43 ms for 11.2 M coordinates with four, two or one word per thread)
+constexpr int vec_for_trimmed(int f) { return f <= 49 ? 4 : 1; }
+// ... and of the second phase of Bulyan, where narrower threads measured slightly slower
 constexpr int vec_for_sort(int f) { return vec_for(f); }
 // ... and of the single pass: with five or seven copies of a file in flight two words per thread
 // (more waves per SIMD, 8-byte loads) measured 1-2 % faster than four (r = 7 would not fit
@@ -804,7 +807,7 @@ __global__ __launch_bounds__(kBlock) void trimmed_mean_kernel(
     const int64_t c0 = gt * V + V <= d ? gt * V : d - V;
     uint32_t key[V][F];
     constexpr int NS = 1;
-    constexpr int kAhead = prefetch_depth(F, NS);
+    constexpr int kAhead = V == 1 ? 20 : prefetch_depth(F, NS);  // as the one-word median kernels
     const uint32_t voff = (uint32_t)(c0 * 4);
     const char *Xb = reinterpret_cast<const char *>(X);
     uint32_t stage[kAhead + 1][NS][V];
@@ -1324,7 +1327,7 @@ int launch_fused(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, 
 template <int F, bool PAD>
 int launch_trimmed_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
                        int b, uint32_t *O, const uint32_t *gate, int gate_n, hipStream_t s) {
-    constexpr int V = vec_for_sort(F);
+    constexpr int V = vec_for_trimmed(F);
     trimmed_mean_kernel<F, V, PAD><<<blocks_for((d + V - 1) / V), kBlock, 0, s>>>(
         X, d, ld, row_index, f, b, O, gate, gate_n);
     BYZ_HIP(hipGetLastError());
@@ -1361,9 +1364,9 @@ int launch_trimmed_mean(const uint32_t *X, int64_t d, int64_t ld, const int32_t 
         if (f <= 35) return launch_trimmed_net<35, true>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
         if (f <= 49) return launch_trimmed_net<49, true>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
     }
-    if (f == 81 && d >= vec_for_sort(81))
+    if (f == 81 && d >= vec_for_trimmed(81))
         return launch_trimmed_net<81, false>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
-    if (f <= 81 && d >= vec_for_sort(81))
+    if (f <= 81 && d >= vec_for_trimmed(81))
         return launch_trimmed_net<81, true>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
     if (f == 121) return launch_trimmed_net<121, false>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
     if (f <= 121) return launch_trimmed_net<121, true>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
