@@ -199,8 +199,8 @@ __device__ __forceinline__ uint32_t load_shared_word(const uint32_t *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Wave-uniform: is any of words[0..n-1] nonzero?  Used by the kernels of the exact path to
-// return at once when the single pass recorded no violation.
+// Wave-uniform: is any of words[0..n-1] nonzero?  Used by the gated kernels behind the single
+// pass to return at once when the decision kernel did not ask for them.
 __device__ __forceinline__ bool any_word_set(const uint32_t *__restrict__ words, int n) {
     const int lane = threadIdx.x & 63;
     bool any = false;

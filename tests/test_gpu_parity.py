@@ -317,7 +317,7 @@ def test_argument_errors():
 @pytest.mark.parametrize("scheme,a,b,q", [(MOLS, 5, 3, 4), (MOLS, 7, 3, 5), (RAM, 5, 5, 6)])
 def test_probe_sample_shift(scheme, a, b, q):
     # BYZ_AGG_PROBE_SHIFT moves the coordinates the single pass samples first: the output and
-    # the winners never change; which inputs send byz_aggregate down the exact path does
+    # the winners never change; for which inputs byz_aggregate has to redo the median does
     d = 70_001
     w = W.make(scheme, a, b, q, d, ALIE, seed=77, ld=synth.padded_ld(d, 4), device=DEV)
     rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
