@@ -340,7 +340,8 @@ int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld, const int32_t
  * until the process ends), large enough for every (f, r) the library accepts, i.e. f <=
  * BYZ_MAX_F_WIDE and r <= BYZ_MAX_R; anything beyond that is refused with BYZ_ENOMEM.  The call
  * allocates nothing and frees nothing; on its first use on a device it looks the array's
- * address up (BYZ_EDEVICE if that fails, BYZ_EUNSUPPORTED for a device ordinal above 63).
+ * address up (BYZ_EDEVICE if that fails, BYZ_EUNSUPPORTED for a device ordinal above 63), so
+ * make that first call outside a graph capture; every later call only enqueues kernels.
  * All calls on one GPU share that array, which keeps whatever the last call left in it (each
  * call clears what it needs): calls that overlap in time on one GPU -- different streams,
  * different threads -- race and give undefined results; calls on one stream are fine.
