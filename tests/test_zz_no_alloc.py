@@ -62,3 +62,44 @@ def test_static_scratch_refuses_what_it_cannot_hold():
         with pytest.raises(B.ByzError) as e:
             B.byz_aggregate_static(w.X, 100, rows_long, f, r, out, wrep)
         assert e.value.code == code, (f, r)
+
+
+def test_static_scratch_under_graph_capture():
+    # the use the entry point is for: captured into a HIP graph (after a first eager call on
+    # the device) and replayed, with eager calls in between; every replay gives the result of
+    # byz_aggregate_opts on the same input, also when the input sends the call past the single pass
+    w = W.make(MOLS, 5, 3, 4, 50_003, ALIE, seed=36, ld=synth.padded_ld(50_003, 64), device=DEV)
+    rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+    X2 = w.X.clone()
+    X2[int(w.file_rows[3, 0]), 33_333] += 1.0   # the guessed copy of file 3, off the probe's sample
+    want = []
+    for X in (w.X, X2):
+        o, r_, _ = B.byz_aggregate_opts(X, w.d, rows_dev, w.f, w.r, 0)
+        want.append((o.clone(), r_.clone()))
+    torch.cuda.synchronize()
+    Xs = w.X.clone()
+    out = torch.empty(w.d, dtype=torch.float32, device=DEV)
+    wrep = torch.empty(w.f, dtype=torch.int32, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        B.byz_aggregate_static(Xs, w.d, rows_dev, w.f, w.r, out, wrep, 0)   # first call: eager
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.byz_aggregate_static(Xs, w.d, rows_dev, w.f, w.r, out, wrep, 0)
+    for rep, which in enumerate([0, 1, 1, 0]):
+        Xs.copy_((w.X, X2)[which])
+        out.zero_()
+        wrep.fill_(-1)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int32), want[which][0].view(torch.int32)), (rep, which)
+        assert torch.equal(wrep, want[which][1]), (rep, which)
+        o2 = torch.empty_like(out)
+        r2 = torch.empty_like(wrep)
+        B.byz_aggregate_static((w.X, X2)[1 - which], w.d, rows_dev, w.f, w.r, o2, r2, 0)  # eager, other input
+        torch.cuda.synchronize()
+        assert torch.equal(o2.view(torch.int32), want[1 - which][0].view(torch.int32)), (rep, which)
+    assert want[1][1][3].item() == 1
