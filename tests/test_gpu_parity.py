@@ -885,6 +885,46 @@ def test_hip_graph_capture_of_the_other_entry_points(l):
             assert torch.equal(got.view(torch.int32), want.view(torch.int32))
 
 
+def test_hidden_equality_patterns_of_wide_files():
+    # r = 3 ... 13: random equality patterns among the copies of random files, the classes one
+    # changed word apart at random coordinates (mostly outside the probe's sample, so the
+    # comparison over all of d is what finds them): with and without a majority, ties between
+    # classes, the guessed copy inside and outside the winning class; both modes, and every
+    # path code has to turn up
+    rng = np.random.default_rng(5)
+    shapes = [(RAM, 5, 5), (RAM, 3, 5), (RAM, 3, 7), (RAM, 5, 7), (RAM, 7, 7), (RAM, 7, 9),
+              (RAM, 5, 13), (MOLS, 7, 5), (MOLS, 9, 5), (MOLS, 5, 3), (MOLS, 13, 3), (FRC, 25, 5)]
+    seen = set()
+    for case in range(90):
+        scheme, a, b = shapes[case % len(shapes)]
+        d = int(rng.choice([rng.integers(300, 3000), rng.integers(3000, 90000)]))
+        w = W.make(scheme, a, b, 0, d, REVERSED, seed=int(rng.integers(1 << 30)), device=DEV)
+        X = w.X.clone()
+        for j in rng.permutation(w.f)[:int(rng.integers(1, max(2, w.f // 2)))]:
+            n_classes = int(rng.integers(1, w.r + 1))
+            labels = rng.integers(0, n_classes, size=w.r)
+            where = rng.integers(0, d, size=n_classes)
+            for k in range(w.r):
+                if labels[k] or rng.integers(2):
+                    X[int(w.file_rows[j, k]), int(where[labels[k]])] += float(1 + labels[k])
+        rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+        Xh = X.cpu().numpy()
+        wrep_o, wrow_o, _ = C.vote(Xh, w.file_rows, d)
+        out_o = C.median(Xh, wrow_o, d)
+        ws = torch.empty(B.byz_aggregate_workspace_bytes(w.f, w.r), dtype=torch.uint8, device=DEV)
+        for flags in (0, B.BYZ_AGG_EARLY_MAJORITY):
+            out, wrep, _ = B.byz_aggregate_opts(X, d, rows_dev, w.f, w.r, flags, workspace=ws)
+            path = B.byz_aggregate_path(ws)
+            seen.add((flags, path))
+            tag = (case, scheme, a, b, d, flags, path)
+            assert np.array_equal(W.bits(out), W.bits(out_o)), tag
+            assert np.array_equal(wrep.cpu().numpy(), wrep_o), tag
+    assert {p for fl, p in seen if fl == 0} >= {B.BYZ_PATH_SINGLE_PASS, B.BYZ_PATH_MEDIAN_REDONE,
+                                                B.BYZ_PATH_TWO_STEP}, seen
+    assert {p for fl, p in seen if fl} >= {B.BYZ_PATH_SINGLE_PASS, B.BYZ_PATH_REVOTED,
+                                           B.BYZ_PATH_REVOTED | B.BYZ_PATH_MEDIAN_REDONE}, seen
+
+
 def test_random_shapes_sizes_and_layouts():
     # a seeded sweep over assignments (every kernel family: generated, padded and 169-wire
     # networks, single pass and two-step, more than 64 files, r = 3, 5, 7), sizes, row pitches,
