@@ -278,16 +278,19 @@ size_t byz_aggregate_workspace_bytes(int f, int r);
  *   winner_replica device [f] int32 out, may be NULL
  *   workspace      device, >= byz_aggregate_workspace_bytes(f, r) bytes, 256-byte aligned,
  *                  contents irrelevant on entry; calls sharing a workspace must not overlap.
- * A small probe compares the copies on a sample of coordinates and guesses each file's
- * winner; the streaming pass feeds that copy to the median network while it compares every
- * pair of copies of every file over all d coordinates -- the whole of Eq. 3's comparison, so
- * the true winners are known when the pass ends, whatever the probe guessed.  If every guessed
- * copy is bit-identical to its file's winner (the case whenever the attacked copies differ
- * from the honest ones on the sample, and also when a copy other than the guessed one differs
- * off the sample) the output stands: one pass, 4(rf+1) bytes per coordinate.  Otherwise (a
- * guessed copy that matches on the sample and differs elsewhere) the median is redone from
- * the true winners, 4(f+1) more bytes; the copies are never compared a second time.  The
- * result is the same either way; byz_aggregate_path tells which it was.
+ * The streaming pass compares every pair of copies of every file over all d coordinates -- the
+ * whole of Eq. 3's comparison, so the true winners are known when the pass ends -- and, as it
+ * goes, every wavefront feeds the median network from the first copy of the class of copies
+ * that is largest on the 64..256 coordinates it has just compared.  A class that
+ * holds a strict majority of a file's copies over all of d lies inside the largest class on
+ * every such stretch, so for a file with a majority the values fed are the winner's
+ * everywhere, whichever copies were tampered with and where: the output stands, one pass,
+ * 4(rf+1) bytes per coordinate.  Only a file without a majority (copies that agree on most
+ * coordinates and are told apart by a few words, so that Eq. 3's tie rule picks a winner that
+ * most stretches saw outnumbered) can make the pass feed a loser's values; the decision behind
+ * the pass sees that, and the median is redone from the true winners, 4(f+1) more bytes; the
+ * copies are never compared a second time.  Workers that do this give up the vote in those
+ * files.  The result is the same either way; byz_aggregate_path tells which it was.
  * The single pass is compiled for (f, r) = (9,3), (15,3), (21,3), (25,3), (25,5), (35,5),
  * (49,3), (49,5), (49,7), (63,7), (65,5), (81,3), (121,3), (169,3)
  * (byz_aggregate_has_single_pass; with BYZ_AGG_TRIM only for r <= 5 and f <= 49, 81, 121); for
@@ -303,15 +306,16 @@ int byz_aggregate(const float *copies, int64_t d, int64_t ld, const int32_t *fil
  * byz_aggregate with options.  flags = 0 is byz_aggregate.
  *   BYZ_AGG_EARLY_MAJORITY  r' = (r+1)/2 copies that are identical on all d coordinates are the
  *     majority whatever the other r - r' copies hold (Sec. 2: a file is distorted only if at
- *     least r' of its copies are), so for every file whose probable winner's class has at
- *     least r' members only r' copies are read and compared.  Same output as flags = 0 for
- *     every input; HBM traffic drops from 4(rf+1) towards 4(r'f+1) bytes per coordinate.
- *     If the r' copies read of some file turn out to differ (off the probe's sample), nothing
- *     is known about the copies that were skipped: all copies of those files are then compared
- *     (BYZ_PATH_REVOTED; 4rd more bytes per such file) and, if a guessed copy lost, the median
- *     is redone.  Every Byzantine worker can do that to the l files it holds, so in the worst
- *     case the mode costs more than flags = 0; it suits settings where timing is not attacked.
- *     Ignored where the single pass does not run.
+ *     least r' of its copies are).  A probe compares the copies on a sample of coordinates, and
+ *     for every file whose probable winner's class has at least r' members only r' copies of
+ *     that class are read and compared.  Same output as flags = 0 for every input; HBM traffic
+ *     drops from 4(rf+1) towards 4(r'f+1) bytes per coordinate.  If the r' copies read of some
+ *     file turn out to differ (off the probe's sample), nothing is known about the copies that
+ *     were skipped: all copies of those files are then compared (BYZ_PATH_REVOTED; 4rd more
+ *     bytes per such file) and, unless what the pass fed there was the winner's all along, the
+ *     median is redone.  Every Byzantine worker can do that to the l files it holds, so in the
+ *     worst case the mode costs more than flags = 0; it suits settings where timing is not
+ *     attacked.  Ignored where the single pass does not run.
  * Errors: as byz_aggregate; BYZ_EINVAL for unknown flag bits.
  */
 #define BYZ_AGG_EARLY_MAJORITY 1u
@@ -321,12 +325,12 @@ int byz_aggregate(const float *copies, int64_t d, int64_t ld, const int32_t *fil
  *     contract.  May be combined with BYZ_AGG_EARLY_MAJORITY. */
 #define BYZ_AGG_TRIMMED_MEAN 2u
 #define BYZ_AGG_TRIM(b) (BYZ_AGG_TRIMMED_MEAN | ((unsigned)(b) << 8))
-/*   BYZ_AGG_PROBE_SHIFT(s)  moves the <= 256 coordinates on which the probe compares the copies
- *     of a file (16 runs of 16 words, evenly spaced from a start that s, 0..65535, picks).  The
- *     output never depends on it.  It is no defence: a worker that changes a single word of its
- *     honest vector misses any sample of 256 coordinates with probability 1 - 256/d wherever
- *     the sample lies.  What such a copy can cost is bounded instead: nothing if it is not the
- *     copy the probe guessed for its file, one median over the winners if it is. */
+/*   BYZ_AGG_PROBE_SHIFT(s)  with BYZ_AGG_EARLY_MAJORITY only (ignored otherwise): moves the
+ *     <= 256 coordinates on which that mode's probe compares the copies of a file to decide
+ *     which r' of them to read (16 runs of 16 words, evenly spaced from a start that s,
+ *     0..65535, picks).  The output never depends on it.  It is no defence: a worker that
+ *     changes a single word of its vector misses any sample of 256 coordinates with
+ *     probability 1 - 256/d wherever the sample lies. */
 #define BYZ_AGG_PROBE_SHIFT(s) (((unsigned)(s) & 0xFFFFu) << 16)
 int byz_aggregate_opts(const float *copies, int64_t d, int64_t ld, const int32_t *file_rows_dev,
                        int f, int r, float *out, int32_t *winner_replica, void *workspace,
@@ -362,7 +366,8 @@ int byz_aggregate_has_single_pass(int f, int r);
  */
 typedef enum byz_path {
     BYZ_PATH_SINGLE_PASS = 0,   /* the single pass's output stood                                 */
-    BYZ_PATH_MEDIAN_REDONE = 1, /* some guessed copy was not its file's winner: the median was
+    BYZ_PATH_MEDIAN_REDONE = 1, /* somewhere the pass fed the median a value that was not the
+                                   file's winner's (a file without a majority): the median was
                                    redone from the true winners (bit 0)                          */
     BYZ_PATH_REVOTED = 2,       /* early-majority mode only: the r' copies read of some files
                                    differed and all copies of those files were compared (bit 1;

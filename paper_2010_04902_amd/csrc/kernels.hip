@@ -195,6 +195,40 @@ __device__ __forceinline__ int decide_winner(uint32_t neq, int r) {
     return arg;
 }
 
+// All pair bits that involve slot a, of n slots.
+__device__ __host__ __forceinline__ constexpr uint32_t pairs_of_slot(int n, int a) {
+    uint32_t m = 0;
+    for (int b = 0; b < n; ++b)
+        if (b != a) m |= 1u << pair_bit(n, a < b ? a : b, a < b ? b : a);
+    return m;
+}
+
+// Which of a file's NS slots feeds the median network on one wave's coordinates, from the pair
+// bits wb the wave found there (all wave-uniform): the first slot of the largest class of slots
+// that are identical on these coordinates.  Being identical on a fixed set of coordinates is an
+// equivalence, so a class that holds a strict majority of the copies over all of d is inside the
+// largest class here, and the chosen slot then carries the majority's values on this wave's
+// coordinates whether or not it belongs to the majority elsewhere.  differs gets bit b set iff
+// slot b differs from the chosen one here.
+template <int NS>
+__device__ __forceinline__ int local_choice(uint32_t wb, uint32_t &differs) {
+    int pick = 0, fewest = NS;
+#pragma unroll
+    for (int a = 0; a < NS; ++a) {
+        const int n = __builtin_popcount(wb & pairs_of_slot(NS, a));
+        if (n < fewest) { fewest = n; pick = a; }
+    }
+    differs = 0;
+#pragma unroll
+    for (int a = 0; a < NS; ++a)
+        if (pick == a) {
+#pragma unroll
+            for (int b = 0; b < NS; ++b)
+                if (b != a) differs |= ((wb >> pair_bit(NS, a < b ? a : b, a < b ? b : a)) & 1u) << b;
+        }
+    return pick;
+}
+
 __device__ __forceinline__ uint32_t load_shared_word(const uint32_t *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -305,7 +339,8 @@ template <> struct SelNet<49> {
 struct AggWorkspace {
     // single pass: bit pair_bit(NS, p, q) set iff the copies in slots p < q of the file's
     // permuted row list differ anywhere in [0, d) (NS = slots the pass read: r, or r' when every
-    // file ran in early-majority mode)
+    // file ran in early-majority mode); above them, bit NS(NS-1)/2 + p set iff some wave fed the
+    // network from a slot that differed from slot p on that wave's coordinates
     uint32_t pneq[kWide];
     uint32_t pair_neq[kWide];        // two-step path and re-vote: all pair bits, replica numbering
     // byte offsets row*ld*4 of a file's rows, probable winner's class first
@@ -408,14 +443,18 @@ __global__ void vote_decide_kernel(const uint32_t *pair_neq, const int32_t *__re
 // Replica held by slot p of a file's permuted row list (AggWorkspace::perm).
 __device__ __forceinline__ int perm_slot(uint32_t packed, int p) { return (int)((packed >> (3 * p)) & 7u); }
 
+// Bit of a file's word in AggWorkspace::pneq that says: on some wave's coordinates, the slot that
+// fed the network there differed from slot p (ns = slots the pass numbered its bits by).
+__device__ __forceinline__ uint32_t fed_differs_bit(int ns, int p) { return 1u << (ns * (ns - 1) / 2 + p); }
+
 // The decision behind the single pass (one block, thread j = file j).  The pass compared every
 // pair of the slots it read over all d coordinates, so its bits are the vote's pair bits up to
-// the slot numbering: the true winner of every file follows by Eq. 3, whatever the probe
-// guessed.  The pass's output stands iff, for every file, the copy in slot 0 (the one that fed
-// the network) is bit-identical to the winner; otherwise need_median makes the gated median
-// kernel redo the output from the true winners (the inputs are not compared again).
+// the slot numbering: the true winner of every file follows by Eq. 3, whatever order the
+// slots are in.  The pass's output stands iff, for every file, no wave fed the network from a slot
+// that differed from the winner's on that wave's coordinates; otherwise need_median makes the
+// gated median kernel redo the output from the true winners (the inputs are not compared again).
 // A file read in early-majority mode has only r' slots of its own: if they are identical they
-// are the majority (Sec. 2) and slot 0 is the winner; if not, nothing is known about the
+// are the majority (Sec. 2) and any of them is the winner; if not, nothing is known about the
 // copies that were skipped and need_revote sends the call through the gated vote kernel.
 __global__ void single_pass_decide_kernel(AggWorkspace *ws, const int32_t *__restrict__ file_rows,
                                           int f, int r, int32_t *winner_replica) {
@@ -439,7 +478,8 @@ __global__ void single_pass_decide_kernel(AggWorkspace *ws, const int32_t *__res
             const int w = decide_winner(neq, r);
             if (winner_replica != nullptr) winner_replica[j] = w;
             ws->winner_row[j] = file_rows[j * r + w];
-            if (!copies_equal(neq, r, perm_slot(packed, 0), w)) s_median = 1;
+            for (int p = 0; p < r; ++p)
+                if (perm_slot(packed, p) == w && (pn & fed_differs_bit(ns, p)) != 0) s_median = 1;
         } else {
             uint32_t differ_bits = 0;
             for (int p = 0; p < own; ++p)
@@ -463,7 +503,8 @@ __global__ void single_pass_decide_kernel(AggWorkspace *ws, const int32_t *__res
 
 // Early-majority mode only, after the gated vote kernel: if the decision above asked for a
 // re-vote, the winners of the files it named come from the pair bits that kernel collected
-// for them, and the median is redone if one of those files' guessed copies lost.
+// for them, and the median is redone unless, for each of those files, the winner's copy was
+// among the slots the pass read and no wave fed the network from a slot that differed from it.
 __global__ void revote_decide_kernel(AggWorkspace *ws, const int32_t *__restrict__ file_rows, int f,
                                      int r, int32_t *winner_replica) {
     if (ws->need_revote == 0) return;
@@ -476,8 +517,13 @@ __global__ void revote_decide_kernel(AggWorkspace *ws, const int32_t *__restrict
         const int a = decide_winner(neq, r);
         if (winner_replica != nullptr) winner_replica[j] = a;
         ws->winner_row[j] = file_rows[j * r + a];
-        // the output stands if the copy that fed the network is one of the winners after all
-        if (!copies_equal(neq, r, perm_slot(ws->perm[j], 0), a)) s_median = 1;
+        const uint32_t pn = load_shared_word(&ws->pneq[j]);
+        const uint32_t packed = ws->perm[j];
+        const int own = (int)(packed >> 24), ns = (int)ws->slots_per_file;
+        bool stands = false;
+        for (int p = 0; p < own; ++p)
+            if (perm_slot(packed, p) == a && (pn & fed_differs_bit(ns, p)) == 0) stands = true;
+        if (!stands) s_median = 1;
     }
     __syncthreads();
     if (threadIdx.x == 0 && s_median != 0) {
@@ -635,19 +681,25 @@ __global__ __launch_bounds__(kBlock) void vote_pairs_tolerant_kernel(
 #define BYZ_S_LOAD20(j) if constexpr (kAhead == 20) { BYZ_S_LOAD_(j) }
 #define BYZ_S_USE(j)                                                                          \
     {                                                                                         \
+        [[maybe_unused]] int pick_ = 0;                                                       \
         if constexpr (NS > 1) {                                                               \
-        uint32_t wb_ = 0;                                                                     \
+        uint32_t wb_ = 0, df_ = 0;                                                            \
         _Pragma("unroll") for (int a_ = 0; a_ < NS; ++a_)                                     \
         _Pragma("unroll") for (int b_ = a_ + 1; b_ < NS; ++b_)                                \
             wb_ |= wave_differ<V>(stage[(j) % (kAhead + 1)][a_],                              \
                                   stage[(j) % (kAhead + 1)][b_]) << pair_bit(NS, a_, b_);     \
+        if (wb_ != 0) pick_ = local_choice<NS>(wb_, df_);                                     \
         if (lane == ((j) & 63)) {                                                             \
-            flags[(j) >> 6] |= wb_;                                                           \
+            flags[(j) >> 6] |= wb_ | (df_ << (NS * (NS - 1) / 2));                            \
             BYZ_S_KEEP_BRANCH                                                                 \
         }                                                                                     \
         }                                                                                     \
-        _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_)                                      \
-            key[v_][j] = BYZ_S_KEY(j, stage[(j) % (kAhead + 1)][0][v_]);                      \
+        _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_) {                                    \
+            uint32_t x_ = stage[(j) % (kAhead + 1)][0][v_];                                   \
+            _Pragma("unroll") for (int k_ = 1; k_ < NS; ++k_)                                 \
+                x_ = pick_ == k_ ? stage[(j) % (kAhead + 1)][k_][v_] : x_;                    \
+            key[v_][j] = BYZ_S_KEY(j, x_);                                                    \
+        }                                                                                     \
     }
 #define BYZ_S_CE(i, j)                                                                        \
     _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_) {                                        \
@@ -970,11 +1022,14 @@ __global__ __launch_bounds__(kBlock) void bulyan_mean_generic_kernel(
     out[c] = __float_as_uint(mean_around_median(s_bulyan_col + threadIdx.x, kBlock, theta, beta));
 }
 
-// Probe: compares the copies of every file on a sample of <= kProbe coordinates (kProbe/16 runs
-// of 16 consecutive words spread over [0, d); all of [0, d) when d <= kProbe), derives the probable
-// equality classes, and lays out the rows of each file with the probable winner first (slot 0
-// feeds the median network) and equal-looking copies adjacent.  Only the speed of the call
-// depends on this guess.  Also clears the state the later kernels accumulate into.
+// First kernel of a single-pass call: clears the state the later kernels accumulate into and
+// lays out the rows of each file for the pass.  When every copy is read, that is the replica
+// order as it stands: each wave chooses for itself which copy feeds the median.
+// In early-majority mode the kernel is a probe: it compares the copies of every file on a
+// sample of <= kProbe coordinates (kProbe/16 runs of 16 consecutive words spread over [0, d); all
+// of [0, d) when d <= kProbe), derives the probable equality classes, and puts the probable
+// winner's class first (the copies that mode reads) and equal-looking copies adjacent.  Only
+// the speed of the call depends on this guess.
 // One block of kProbeThreads threads: thread group q = tid / kProbe takes the files
 // q, q + kProbeSplit, ..., every group on the same kProbe sample coordinates, so a thread waits
 // for F*R / kProbeSplit loads.
@@ -1002,6 +1057,18 @@ __global__ __launch_bounds__(kProbeThreads) void probe_kernel(const uint32_t *__
         ws->path = 0;
     }
     __syncthreads();
+    if (early_majority == 0) {
+        if (tid < F) {
+            uint32_t packed = (uint32_t)R << 24;
+            for (int p = 0; p < R; ++p) {
+                ws->perm_off[tid * kRowStride + p] = (uint64_t)file_rows[tid * R + p] * (uint64_t)ld * 4u;
+                packed |= (uint32_t)p << (3 * p);
+            }
+            ws->perm[tid] = packed;
+        }
+        if (tid == 0) ws->slots_per_file = R;
+        return;
+    }
 
     // threads without a sample coordinate of their own redo coordinate 0
     const int ct = tid % kProbe;  // which sample coordinate
@@ -1108,10 +1175,13 @@ __device__ __forceinline__ unsigned tile_of_block(unsigned b, unsigned n_blocks)
 
 // Vote and median in one pass: streams the first NS slots of every file's permuted row list once (NS = R:
 // every copy; NS = r' = (R+1)/2 in early-majority mode when every file has a probable
-// majority).  Slot 0 (the probable winner) feeds the median network, and every pair of slots is
-// compared over all coordinates (ws->pneq), which is the whole of the vote's comparison: the
-// decision kernel behind this one knows the true winners and whether slot 0 held one for
-// every file.
+// majority).  Every pair of slots is compared over all coordinates (ws->pneq), which is the whole
+// of the vote's comparison, and each wave feeds the median network from the slot that
+// local_choice picks by what it has just compared: where a file has a strict majority over all
+// of d, that slot holds the majority's values on the wave's coordinates, so a copy that was
+// tampered with somewhere else costs nothing.  The decision kernel behind this one knows the
+// true winners and, from the bits that say which slots the fed ones differed from, whether
+// every wave fed the winner's values.
 template <int F, int R, int NS, bool TRIM, int V>
 __device__ __forceinline__ void fused_body(const uint32_t *__restrict__ X, int64_t d, int64_t ld,
                                            const uint64_t *__restrict__ perm_off,
@@ -1151,7 +1221,9 @@ __device__ __forceinline__ void fused_body(const uint32_t *__restrict__ X, int64
 #include "generated/selnet_stream_dispatch.inc"
 #include "selnet_pin_off.inc"
     } else {
+#include "selnet_pin_on.inc"
 #include "generated/selnet_sort_stream_dispatch.inc"
+#include "selnet_pin_off.inc"
         trimmed_mean_of_sorted<F, V>(key, F, trim_b, o);
     }
 #undef BYZ_S_ROW_ADDR

@@ -256,12 +256,16 @@ def test_largest_d():
         for k in range(1, r):
             X[int(rows_np[j, k])].copy_(X[int(rows_np[j, 0])])
     # file 2: copies 0 and 1 carry the same wrong vector (they win); file 5: copy 2 differs in
-    # the last word only; file 7: copy 0 differs in one word no probe sample touches
+    # the last word only; file 7: copy 0 differs in one word no probe sample touches; file 4:
+    # copies 1 and 2 carry the same wrong vector but for one such word (three distinct copies)
     X[int(rows_np[2, 0])].mul_(-100.0)
     X[int(rows_np[2, 1])].copy_(X[int(rows_np[2, 0])])
     X[int(rows_np[5, 2]), d - 1] += 1.0
     hidden = (d // 2) + 12345
     X[int(rows_np[7, 0]), hidden] += 1.0
+    X[int(rows_np[4, 1])].mul_(-100.0)
+    X[int(rows_np[4, 2])].copy_(X[int(rows_np[4, 1])])
+    X[int(rows_np[4, 2]), hidden + 777] += 1.0
     rows_dev = torch.tensor(rows_np.reshape(-1), dtype=torch.int32, device=DEV)
     out, wrep, ws = B.byz_aggregate(X, d, rows_dev, f, r)
     wrep_v, wrow_v, neq_v = B.byz_vote(X, d, rows_dev, f, r)
@@ -273,15 +277,17 @@ def test_largest_d():
     want_neq[2] = 0b110                               # pairs (0,2), (1,2)
     want_neq[5] = 0b110
     want_neq[7] = 0b011                               # pairs (0,1), (0,2)
+    want_neq[4] = 0b111                               # no two alike: copy 0 wins the tie
     assert np.array_equal(wrep.cpu().numpy(), want_rep)
     assert np.array_equal(wrep_v.cpu().numpy(), want_rep)
     assert np.array_equal(W.bits(neq_v), want_neq)
-    # file 7's difference is off the sample and in the guessed copy: one more median
+    # file 7 keeps a majority, so its changed word costs nothing; file 4 has none, nearly every
+    # wave fed the median from copy 1 where copy 0 is the winner: one more median
     assert B.byz_aggregate_path(ws) == B.BYZ_PATH_MEDIAN_REDONE
     assert torch.equal(out.view(torch.int32), out_m.view(torch.int32))
     rng = np.random.default_rng(30)
     cols = np.unique(np.concatenate([np.arange(0, 2048), np.arange(d - 2048, d),
-                                     np.array([hidden - 1, hidden, hidden + 1]),
+                                     np.array([hidden - 1, hidden, hidden + 1, hidden + 777]),
                                      rng.integers(0, d, size=200_000)]))
     cols_dev = torch.tensor(cols, dtype=torch.int64, device=DEV)
     Xs = X[:, cols_dev].cpu().numpy()

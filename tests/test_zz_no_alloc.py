@@ -70,13 +70,18 @@ def test_static_scratch_under_graph_capture():
     # byz_aggregate_opts on the same input, also when the input sends the call past the single pass
     w = W.make(MOLS, 5, 3, 4, 50_003, ALIE, seed=36, ld=synth.padded_ld(50_003, 64), device=DEV)
     rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+    # second input: replicas 1 and 2 of file 3 hold a false vector, equal but for one word off
+    # the probe's sample; without a majority replica 0 wins the tie and the median is redone
     X2 = w.X.clone()
-    X2[int(w.file_rows[3, 0]), 33_333] += 1.0   # the guessed copy of file 3, off the probe's sample
+    X2[int(w.file_rows[3, 1]), :w.d] = -50.0 * w.G[3]
+    X2[int(w.file_rows[3, 2])] = X2[int(w.file_rows[3, 1])]
+    X2[int(w.file_rows[3, 2]), 33_333] += 1.0
     want = []
     for X in (w.X, X2):
-        o, r_, _ = B.byz_aggregate_opts(X, w.d, rows_dev, w.f, w.r, 0)
-        want.append((o.clone(), r_.clone()))
+        o, r_, ws_ = B.byz_aggregate_opts(X, w.d, rows_dev, w.f, w.r, 0)
+        want.append((o.clone(), r_.clone(), B.byz_aggregate_path(ws_)))
     torch.cuda.synchronize()
+    assert [p for _, _, p in want] == [B.BYZ_PATH_SINGLE_PASS, B.BYZ_PATH_MEDIAN_REDONE]
     Xs = w.X.clone()
     out = torch.empty(w.d, dtype=torch.float32, device=DEV)
     wrep = torch.empty(w.f, dtype=torch.int32, device=DEV)
@@ -102,4 +107,4 @@ def test_static_scratch_under_graph_capture():
         B.byz_aggregate_static((w.X, X2)[1 - which], w.d, rows_dev, w.f, w.r, o2, r2, 0)  # eager, other input
         torch.cuda.synchronize()
         assert torch.equal(o2.view(torch.int32), want[1 - which][0].view(torch.int32)), (rep, which)
-    assert want[1][1][3].item() == 1
+    assert want[1][1][3].item() == 0
