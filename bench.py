@@ -241,7 +241,7 @@ def main():
         c_hidden = d // 2 + 7
         legs = []
         if clean:
-            for k, key in ((1, "changed_word_in_another_copy"), (0, "changed_word_in_the_guessed_copy")):
+            for k, key in ((1, "changed_word_in_second_copy"), (0, "changed_word_in_first_copy")):
                 legs.append((key, [(int(rows[clean[0], k]), c_hidden)], {}))
         if held:
             words = []

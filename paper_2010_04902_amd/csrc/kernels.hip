@@ -210,23 +210,66 @@ __device__ __host__ __forceinline__ constexpr uint32_t pairs_of_slot(int n, int 
 // largest class here, and the chosen slot then carries the majority's values on this wave's
 // coordinates whether or not it belongs to the majority elsewhere.  differs gets bit b set iff
 // slot b differs from the chosen one here.
-template <int NS>
-__device__ __forceinline__ int local_choice(uint32_t wb, uint32_t &differs) {
-    int pick = 0, fewest = NS;
-#pragma unroll
-    for (int a = 0; a < NS; ++a) {
-        const int n = __builtin_popcount(wb & pairs_of_slot(NS, a));
+// Packed as pick | differs << 3.
+__device__ __host__ __forceinline__ constexpr uint32_t local_choice_packed(int ns, uint32_t wb) {
+    int pick = 0, fewest = ns;
+    for (int a = 0; a < ns; ++a) {
+        int n = 0;
+        for (int b = 0; b < ns; ++b)
+            if (b != a) n += (int)((wb >> pair_bit(ns, a < b ? a : b, a < b ? b : a)) & 1u);
         if (n < fewest) { fewest = n; pick = a; }
     }
-    differs = 0;
+    uint32_t differs = 0;
+    for (int b = 0; b < ns; ++b)
+        if (b != pick)
+            differs |= ((wb >> pair_bit(ns, pick < b ? pick : b, pick < b ? b : pick)) & 1u) << b;
+    return (uint32_t)pick | differs << 3;
+}
+static_assert(local_choice_packed(3, 0b110u) == (0u | 0b100u << 3), "{0,1},{2}: slot 0 feeds, 2 differs");
+static_assert(local_choice_packed(3, 0b011u) == (1u | 0b001u << 3), "{0},{1,2}: slot 1 feeds, 0 differs");
+static_assert(local_choice_packed(3, 0b111u) == (0u | 0b110u << 3), "three singletons: slot 0 feeds");
+static_assert(local_choice_packed(5, 0u) == 0u, "all alike");
+// The eight cases of three slots as one constant, a byte each: pick in bits 0..1, above it what
+// the wave adds to the file's word in the workspace (its pair bits, then the differs bits).
+__device__ __host__ __forceinline__ constexpr uint64_t local_choice_table3() {
+    uint64_t t = 0;
+    for (uint32_t wb = 0; wb < 8; ++wb) {
+        const uint32_t p = local_choice_packed(3, wb);
+        t |= (uint64_t)((p & 3u) | (wb | (p >> 3) << 3) << 2) << (8 * wb);
+    }
+    return t;
+}
+// -> the slot that feeds; word = what the wave adds to the file's word in the workspace.
+template <int NS>
+__device__ __forceinline__ int local_choice(uint32_t wb, uint32_t &word) {
+    if constexpr (NS == 2) {
+        word = wb | wb << 2;  // two unequal slots: the first feeds, the second differs from it
+        return 0;
+    } else if constexpr (NS == 3) {
+        constexpr uint64_t kTable = local_choice_table3();
+        const uint32_t e = (uint32_t)(kTable >> (8 * wb)) & 255u;
+        word = e >> 2;
+        return (int)(e & 3u);
+    } else {
+        word = wb;
+        if (wb == 0) return 0;
+        int pick = 0, fewest = NS;
 #pragma unroll
-    for (int a = 0; a < NS; ++a)
-        if (pick == a) {
-#pragma unroll
-            for (int b = 0; b < NS; ++b)
-                if (b != a) differs |= ((wb >> pair_bit(NS, a < b ? a : b, a < b ? b : a)) & 1u) << b;
+        for (int a = 0; a < NS; ++a) {
+            const int n = __builtin_popcount(wb & pairs_of_slot(NS, a));
+            if (n < fewest) { fewest = n; pick = a; }
         }
-    return pick;
+        uint32_t differs = 0;
+#pragma unroll
+        for (int a = 0; a < NS; ++a)
+            if (pick == a) {
+#pragma unroll
+                for (int b = 0; b < NS; ++b)
+                    if (b != a) differs |= ((wb >> pair_bit(NS, a < b ? a : b, a < b ? b : a)) & 1u) << b;
+            }
+        word |= differs << (NS * (NS - 1) / 2);
+        return pick;
+    }
 }
 
 __device__ __forceinline__ uint32_t load_shared_word(const uint32_t *p) {
@@ -683,22 +726,30 @@ __global__ __launch_bounds__(kBlock) void vote_pairs_tolerant_kernel(
     {                                                                                         \
         [[maybe_unused]] int pick_ = 0;                                                       \
         if constexpr (NS > 1) {                                                               \
-        uint32_t wb_ = 0, df_ = 0;                                                            \
+        uint32_t wb_ = 0, word_ = 0;                                                          \
         _Pragma("unroll") for (int a_ = 0; a_ < NS; ++a_)                                     \
         _Pragma("unroll") for (int b_ = a_ + 1; b_ < NS; ++b_)                                \
             wb_ |= wave_differ<V>(stage[(j) % (kAhead + 1)][a_],                              \
                                   stage[(j) % (kAhead + 1)][b_]) << pair_bit(NS, a_, b_);     \
-        if (wb_ != 0) pick_ = local_choice<NS>(wb_, df_);                                     \
+        pick_ = local_choice<NS>(wb_, word_);                                                 \
         if (lane == ((j) & 63)) {                                                             \
-            flags[(j) >> 6] |= wb_ | (df_ << (NS * (NS - 1) / 2));                            \
+            flags[(j) >> 6] |= word_;                                                         \
             BYZ_S_KEEP_BRANCH                                                                 \
         }                                                                                     \
         }                                                                                     \
-        _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_) {                                    \
-            uint32_t x_ = stage[(j) % (kAhead + 1)][0][v_];                                   \
-            _Pragma("unroll") for (int k_ = 1; k_ < NS; ++k_)                                 \
-                x_ = pick_ == k_ ? stage[(j) % (kAhead + 1)][k_][v_] : x_;                    \
-            key[v_][j] = BYZ_S_KEY(j, x_);                                                    \
+        _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_)                                      \
+            key[v_][j] = BYZ_S_KEY(j, stage[(j) % (kAhead + 1)][0][v_]);                      \
+        if constexpr (NS > 1) {                                                               \
+        /* wave-uniform and rare: slot 0 is outside the largest class of this wave */         \
+        if (__builtin_expect(pick_ != 0, 0)) {                                                \
+            _Pragma("unroll") for (int v_ = 0; v_ < V; ++v_) {                                \
+                uint32_t x_ = stage[(j) % (kAhead + 1)][1][v_];                               \
+                _Pragma("unroll") for (int k_ = 2; k_ < NS; ++k_)                             \
+                    x_ = pick_ == k_ ? stage[(j) % (kAhead + 1)][k_][v_] : x_;                \
+                key[v_][j] = BYZ_S_KEY(j, x_);                                                \
+            }                                                                                 \
+            BYZ_S_KEEP_BRANCH                                                                 \
+        }                                                                                     \
         }                                                                                     \
     }
 #define BYZ_S_CE(i, j)                                                                        \
