@@ -140,26 +140,26 @@ def _plant(X, rows_np, j, k, coords, value):
 
 
 def test_copy_that_matches_on_the_probe_sample_but_differs_elsewhere():
-    # The probe looks at 16 runs of 16 coordinates; a copy that differs only outside them is
-    # found by the streaming pass, which compares every pair of copies everywhere, and each wave
-    # feeds the median from a copy of the class that is largest on its own coordinates.  So a
-    # changed word costs nothing while its file keeps a strict majority, whichever copy it is
-    # in; only a file without one can make the pass feed values of a copy that loses the vote,
-    # and then the median over the winners is redone.  The copies are never compared again.
+    # The streaming pass compares every pair of copies everywhere, and each wave feeds the median
+    # from a copy of the class that is largest on its own coordinates.  So a changed word costs
+    # nothing while its file keeps a strict majority, whichever copy it is in; only a file
+    # without one can make the pass feed values of a copy that loses the vote, and then the
+    # median over the winners is redone.  The copies are never compared again.  The changed
+    # words sit off the 16 runs of 16 coordinates that early-majority mode's probe samples.
     d = 100_000
     w = W.make(MOLS, 5, 3, 0, d, REVERSED, seed=4, device=DEV)
     stride = (d - 16) // 15  # start of run u is u * stride
     unsampled = [c for c in (17, stride - 1, d - 17, d // 2 + 19) if (c % stride) >= 16]
     assert unsampled
-    # one changed word in a copy that is not the guessed one (replica 1, replica 2; first,
-    # middle, last coordinate region): the true classes {0,2},{1} resp. {0,1},{2} are known
-    # after the pass, replica 0 fed the network and is the winner -> no further pass
+    # one changed word in replica 1 or 2 (first, middle, last coordinate region): the true
+    # classes {0,2},{1} resp. {0,1},{2} are known after the pass, replica 0 fed the network
+    # everywhere and is the winner -> no further pass
     for k, c in [(1, unsampled[0]), (2, unsampled[1]), (1, d - 1), (2, d // 2 + 19)]:
         X1 = w.X.clone()
         _plant(X1, w.file_rows, 5, k, [c], 9.0)
         out_o, wrep_o, _ = _check_all(X1, w.file_rows, d, w.f, w.r, expect_path=SINGLE, tag=(k, c))
         assert wrep_o[5] == 0
-    # one changed word in the guessed copy (replica 0): classes {0},{1,2}, winner replica 1.
+    # one changed word in replica 0: classes {0},{1,2}, winner replica 1.
     # The wave that holds the word feeds from replica 1 there, the others from replica 0, which
     # equals the winner on their coordinates -> the output stands
     X2 = w.X.clone()
@@ -190,25 +190,25 @@ def test_copy_that_matches_on_the_probe_sample_but_differs_elsewhere():
         _, _, ws = B.byz_aggregate_opts(Xe, d, rows_dev, w.f, w.r, B.BYZ_AGG_EARLY_MAJORITY)
         torch.cuda.synchronize()
         assert B.byz_aggregate_path(ws) == want, (k, want)
-    # replicas 0 and 2 of file 3 both deviate (identically) off the sample: the probe thinks all
-    # three are equal, the true classes are {0,2},{1}, and the guessed copy is still a winner
+    # replicas 0 and 2 of file 3 both deviate (identically) in a few words: the true classes are
+    # {0,2},{1}, and replica 0, which every wave fed, is a winner
     X3 = w.X.clone()
     for k in (0, 2):
         _plant(X3, w.file_rows, 3, k, unsampled, 7.0)
     out_o, wrep_o, _ = _check_all(X3, w.file_rows, d, w.f, w.r, expect_path=SINGLE)
     assert wrep_o[3] == 0
     # replicas 0 and 2 deviate differently: three distinct copies, replica 0 wins the tie and
-    # is the guessed copy
+    # is what every wave fed (first of the largest class everywhere)
     X4 = X3.clone()
     _plant(X4, w.file_rows, 3, 2, unsampled[:1], 8.0)
     out_o, wrep_o, _ = _check_all(X4, w.file_rows, d, w.f, w.r, expect_path=SINGLE)
     assert wrep_o[3] == 0
-    # a copy that differs at one sampled coordinate only -> the probe sees it and guesses right
+    # replica 0 differs at one coordinate that early-majority mode's probe samples
     X5 = w.X.clone()
     _plant(X5, w.file_rows, 5, 0, [5 * stride + 3], 9.0)
     out_o, wrep_o, _ = _check_all(X5, w.file_rows, d, w.f, w.r, expect_path=SINGLE)
     assert wrep_o[5] == 1
-    # r = 5: the guessed copy of a file differs off the sample while two Byzantine copies agree
+    # r = 5: replica 0 of a file has a changed word while two Byzantine copies agree
     # with each other: 1 + 2 + 2 -> the lowest honest replica left wins; the wave with the word
     # sees {1,2} first among the classes of two and feeds replica 1, the others feed replica 0,
     # which equals it there
@@ -921,10 +921,9 @@ def test_hip_graph_capture_of_the_other_entry_points(l):
 
 def test_hidden_equality_patterns_of_wide_files():
     # r = 3 ... 13: random equality patterns among the copies of random files, the classes one
-    # changed word apart at random coordinates (mostly outside the probe's sample, so the
-    # comparison over all of d is what finds them): with and without a majority, ties between
-    # classes, the guessed copy inside and outside the winning class; both modes, and every
-    # path code has to turn up
+    # changed word apart at random coordinates (the comparison over all of d is what finds
+    # them): with and without a majority, ties between classes, the first copy inside and
+    # outside the winning class; both modes, and every path code has to turn up
     rng = np.random.default_rng(5)
     shapes = [(RAM, 5, 5), (RAM, 3, 5), (RAM, 3, 7), (RAM, 5, 7), (RAM, 7, 7), (RAM, 7, 9),
               (RAM, 5, 13), (MOLS, 7, 5), (MOLS, 9, 5), (MOLS, 5, 3), (MOLS, 13, 3), (FRC, 25, 5)]
