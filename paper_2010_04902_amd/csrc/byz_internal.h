@@ -43,6 +43,15 @@ int byz_internal_launch_trimmed_mean(const void *X, long long d, long long ld,
                                      const int *row_index, int f, int b, void *out,
                                      const void *gate, int gate_n, void *stream);
 
+// Trimmed mean of 49 < f <= 63 and 63 < f <= 65 rows on the 63- and 65-wire sorting networks
+// (kernels.hip, build parts 14 and 15).
+int byz_internal_launch_trimmed_mean_63(const void *X, long long d, long long ld,
+                                        const int *row_index, int f, int b, void *out,
+                                        const void *gate, int gate_n, void *stream);
+int byz_internal_launch_trimmed_mean_65(const void *X, long long d, long long ld,
+                                        const int *row_index, int f, int b, void *out,
+                                        const void *gate, int gate_n, void *stream);
+
 // Median / trimmed mean on the 169-wire network, exactly 169 rows or fewer with spare wires
 // (kernels.hip, build parts 8..11).
 int byz_internal_launch_trimmed_mean_169(const void *X, long long d, long long ld,

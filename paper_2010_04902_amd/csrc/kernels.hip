@@ -1446,7 +1446,7 @@ int launch_fused(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, 
     return byz_internal_profile_mark(1, s);
 }
 
-#if BYZ_IN_PART(6) || BYZ_IN_PART(8) || BYZ_IN_PART(10) || BYZ_IN_PART(17)
+#if BYZ_IN_PART(6) || BYZ_IN_PART(8) || BYZ_IN_PART(10) || BYZ_IN_PART(14) || BYZ_IN_PART(15) || BYZ_IN_PART(17)
 template <int F, bool PAD>
 int launch_trimmed_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
                        int b, uint32_t *O, const uint32_t *gate, int gate_n, hipStream_t s) {
@@ -1457,7 +1457,7 @@ int launch_trimmed_net(const uint32_t *X, int64_t d, int64_t ld, const int32_t *
     return BYZ_OK;
 }
 
-#endif  // parts 6, 8, 10, 17
+#endif  // parts 6, 8, 10, 14, 15, 17
 
 #if BYZ_IN_PART(6)
 int launch_trimmed_mean(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_index, int f,
@@ -1487,6 +1487,8 @@ int launch_trimmed_mean(const uint32_t *X, int64_t d, int64_t ld, const int32_t 
         if (f <= 35) return launch_trimmed_net<35, true>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
         if (f <= 49) return launch_trimmed_net<49, true>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
     }
+    if (f <= 63) return byz_internal_launch_trimmed_mean_63(X, d, ld, row_index, f, b, O, gate, gate_n, s);
+    if (f <= 65) return byz_internal_launch_trimmed_mean_65(X, d, ld, row_index, f, b, O, gate, gate_n, s);
     if (f == 81 && d >= vec_for_trimmed(81))
         return launch_trimmed_net<81, false>(X, d, ld, row_index, f, b, O, gate, gate_n, s);
     if (f <= 81 && d >= vec_for_trimmed(81))
@@ -1531,9 +1533,7 @@ bool has_fused(int f, int r) {
 }
 // ... whose trimmed-mean variant is compiled as well (the others run the trimmed mean as vote
 // kernel + trimmed-mean kernel)
-bool has_fused_trim(int f, int r) {
-    return has_fused(f, r) && f != 169 && f != 63 && f != 65 && r != 7;
-}
+bool has_fused_trim(int f, int r) { return has_fused(f, r) && f != 169; }
 
 int check_common(const void *copies, int64_t d, int64_t ld, const void *rows, int f, int r) {
     if (copies == nullptr || rows == nullptr) return BYZ_EINVAL;
@@ -1573,6 +1573,33 @@ int byz_internal_launch_bulyan_mean_121(const void *X, long long d, long long ld
                                         void *stream) {
     return launch_bulyan_net<121>(static_cast<const uint32_t *>(X), d, ld, selected_rows, theta, beta,
                                   static_cast<uint32_t *>(out), (hipStream_t)stream);
+}
+#endif
+
+// the 63- and 65-wire sorting networks (Ramanujan Case 2 with (m, s) = (9, 7) and (13, 5), and
+// padded the f between 49 and 65), in the build parts of those shapes' single-pass kernels
+#if BYZ_IN_PART(14)
+int byz_internal_launch_trimmed_mean_63(const void *X, long long d, long long ld,
+                                        const int *row_index, int f, int b, void *out,
+                                        const void *gate, int gate_n, void *stream) {
+    const uint32_t *x = static_cast<const uint32_t *>(X), *g = static_cast<const uint32_t *>(gate);
+    if (f == 63)
+        return launch_trimmed_net<63, false>(x, d, ld, row_index, f, b, static_cast<uint32_t *>(out),
+                                             g, gate_n, (hipStream_t)stream);
+    return launch_trimmed_net<63, true>(x, d, ld, row_index, f, b, static_cast<uint32_t *>(out), g,
+                                        gate_n, (hipStream_t)stream);
+}
+#endif
+#if BYZ_IN_PART(15)
+int byz_internal_launch_trimmed_mean_65(const void *X, long long d, long long ld,
+                                        const int *row_index, int f, int b, void *out,
+                                        const void *gate, int gate_n, void *stream) {
+    const uint32_t *x = static_cast<const uint32_t *>(X), *g = static_cast<const uint32_t *>(gate);
+    if (f == 65)
+        return launch_trimmed_net<65, false>(x, d, ld, row_index, f, b, static_cast<uint32_t *>(out),
+                                             g, gate_n, (hipStream_t)stream);
+    return launch_trimmed_net<65, true>(x, d, ld, row_index, f, b, static_cast<uint32_t *>(out), g,
+                                        gate_n, (hipStream_t)stream);
 }
 #endif
 
@@ -1680,7 +1707,7 @@ int byz_internal_launch_single_pass_2(int f, int r, const void *X, long long d, 
     hipStream_t s = (hipStream_t)stream;
     if (f == 49 && r == 3) return launch_fused<49, 3>(x, d, ld, rows, w, o, probe_opts, trim_b, s);
     if (f == 49 && r == 5) return launch_fused<49, 5>(x, d, ld, rows, w, o, probe_opts, trim_b, s);
-    if (f == 49 && r == 7) return launch_fused<49, 7, false>(x, d, ld, rows, w, o, probe_opts, trim_b, s);
+    if (f == 49 && r == 7) return launch_fused<49, 7>(x, d, ld, rows, w, o, probe_opts, trim_b, s);
     return BYZ_EINTERNAL;
 }
 #endif
@@ -1726,7 +1753,7 @@ int byz_internal_launch_single_pass_6(int f, int r, const void *X, long long d, 
                                       const int *rows, void *ws, void *out, int probe_opts, int trim_b,
                                       void *stream) {
     if (f == 63 && r == 7)
-        return launch_fused<63, 7, false>(static_cast<const uint32_t *>(X), d, ld, rows,
+        return launch_fused<63, 7>(static_cast<const uint32_t *>(X), d, ld, rows,
                                     static_cast<AggWorkspace *>(ws), static_cast<uint32_t *>(out),
                                     probe_opts, trim_b, (hipStream_t)stream);
     return BYZ_EINTERNAL;
@@ -1738,7 +1765,7 @@ int byz_internal_launch_single_pass_7(int f, int r, const void *X, long long d, 
                                       const int *rows, void *ws, void *out, int probe_opts, int trim_b,
                                       void *stream) {
     if (f == 65 && r == 5)
-        return launch_fused<65, 5, false>(static_cast<const uint32_t *>(X), d, ld, rows,
+        return launch_fused<65, 5>(static_cast<const uint32_t *>(X), d, ld, rows,
                                     static_cast<AggWorkspace *>(ws), static_cast<uint32_t *>(out),
                                     probe_opts, trim_b, (hipStream_t)stream);
     return BYZ_EINTERNAL;
