@@ -293,7 +293,7 @@ size_t byz_aggregate_workspace_bytes(int f, int r);
  * files.  The result is the same either way; byz_aggregate_path tells which it was.
  * The single pass is compiled for (f, r) = (9,3), (15,3), (21,3), (25,3), (25,5), (35,5),
  * (49,3), (49,5), (49,7), (63,7), (65,5), (81,3), (121,3), (169,3)
- * (byz_aggregate_has_single_pass; with BYZ_AGG_TRIM all of them but (169,3)); for
+ * (byz_aggregate_has_single_pass; with and without BYZ_AGG_TRIM); for
  * every other valid (f, r), and for d < 4, the call runs byz_vote's kernels and then
  * byz_median's (or byz_trimmed_mean's), reading the winners a second time.
  * Errors: as byz_vote / byz_median, plus BYZ_ENOMEM (workspace too small).

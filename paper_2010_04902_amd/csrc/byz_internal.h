@@ -33,6 +33,7 @@ BYZ_DECLARE_SINGLE_PASS(4);
 BYZ_DECLARE_SINGLE_PASS(5);
 BYZ_DECLARE_SINGLE_PASS(6);
 BYZ_DECLARE_SINGLE_PASS(7);
+BYZ_DECLARE_SINGLE_PASS(8);  // (169, 3) with the trimmed mean only
 
 // Coordinate-wise median / trimmed mean of the rows row_index[0..f-1] (kernels.hip, parts 5 and
 // 6): picks the network kernel for f; gate != NULL makes the kernels return at once unless one

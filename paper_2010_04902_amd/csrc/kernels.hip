@@ -25,7 +25,8 @@
 // The build compiles this file once per BYZ_PART, in parallel, because the single-pass kernels
 // are large: part 0 holds every entry point, the vote and the Bulyan kernels, parts 1..4 one
 // group of single-pass instantiations each (byz_internal_launch_single_pass_<n>; the fifth
-// group is part 7, the sixth and seventh parts 14 and 15), part 5 the median kernels, part 6 the
+// group is part 7, the sixth and seventh parts 14 and 15, which also hold the 63- and 65-wire
+// trimmed-mean kernels, the eighth part 18), part 5 the median kernels, part 6 the
 // trimmed-mean kernels, parts 8..11 one 169-wire network kernel each, parts 12 and 13 the 81- and
 // 121-wire second phase of Bulyan, parts 16 and 17 the 255-wire median and the 256-wire sorting network.
 // Without BYZ_PART the whole library is
@@ -1423,12 +1424,12 @@ int launch_median(const uint32_t *X, int64_t d, int64_t ld, const int32_t *row_i
 
 #endif  // part 5
 
-// WITH_TRIM = false leaves the trimmed-mean variant of the kernel out (the caller then sends
-// trimmed-mean requests down the two-kernel path)
-template <int F, int R, bool WITH_TRIM = true>
+// WITH_TRIM = false / WITH_MEDIAN = false leave that variant of the kernel out (a shape whose two
+// variants are compiled in different build parts)
+template <int F, int R, bool WITH_TRIM = true, bool WITH_MEDIAN = true>
 int launch_fused(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, AggWorkspace *ws,
                  uint32_t *out, int probe_opts, int trim_b, hipStream_t s) {
-    if (!WITH_TRIM && trim_b >= 0) return BYZ_EINTERNAL;
+    if ((!WITH_TRIM && trim_b >= 0) || (!WITH_MEDIAN && trim_b < 0)) return BYZ_EINTERNAL;
     probe_kernel<F, R><<<1, kProbeThreads, 0, s>>>(X, d, ld, rows, ws, probe_opts);
     BYZ_HIP(hipGetLastError());
     int rc = byz_internal_profile_mark(0, s);
@@ -1436,8 +1437,9 @@ int launch_fused(const uint32_t *X, int64_t d, int64_t ld, const int32_t *rows, 
     constexpr int V = vec_for_pass(F, R);
     const unsigned g = blocks_for((d + V - 1) / V);
     if (trim_b < 0) {
-        fused_kernel<F, R, false, V><<<g, kBlock, 0, s>>>(
-            X, d, ld, ws->perm_off, &ws->slots_per_file, ws, 0, out);
+        if constexpr (WITH_MEDIAN)
+            fused_kernel<F, R, false, V><<<g, kBlock, 0, s>>>(
+                X, d, ld, ws->perm_off, &ws->slots_per_file, ws, 0, out);
     } else if constexpr (WITH_TRIM) {
         fused_kernel<F, R, true, V><<<g, kBlock, 0, s>>>(
             X, d, ld, ws->perm_off, &ws->slots_per_file, ws, trim_b, out);
@@ -1531,9 +1533,8 @@ bool has_fused(int f, int r) {
            (f == 35 && r == 5) || (f == 65 && r == 5) || (f == 63 && r == 7) ||
            ((f == 81 || f == 121 || f == 169) && r == 3);
 }
-// ... whose trimmed-mean variant is compiled as well (the others run the trimmed mean as vote
-// kernel + trimmed-mean kernel)
-bool has_fused_trim(int f, int r) { return has_fused(f, r) && f != 169; }
+// ... whose trimmed-mean variant is compiled as well: all of them
+bool has_fused_trim(int f, int r) { return has_fused(f, r); }
 
 int check_common(const void *copies, int64_t d, int64_t ld, const void *rows, int f, int r) {
     if (copies == nullptr || rows == nullptr) return BYZ_EINVAL;
@@ -1748,6 +1749,19 @@ int byz_internal_launch_single_pass_5(int f, int r, const void *X, long long d, 
 }
 #endif
 
+#if BYZ_IN_PART(18)
+// (169, 3) with the trimmed mean: the widest sorting network in the single pass, a part of its own
+int byz_internal_launch_single_pass_8(int f, int r, const void *X, long long d, long long ld,
+                                      const int *rows, void *ws, void *out, int probe_opts, int trim_b,
+                                      void *stream) {
+    if (f == 169 && r == 3)
+        return launch_fused<169, 3, true, false>(static_cast<const uint32_t *>(X), d, ld, rows,
+                                    static_cast<AggWorkspace *>(ws), static_cast<uint32_t *>(out),
+                                    probe_opts, trim_b, (hipStream_t)stream);
+    return BYZ_EINTERNAL;
+}
+#endif
+
 #if BYZ_IN_PART(14)
 int byz_internal_launch_single_pass_6(int f, int r, const void *X, long long d, long long ld,
                                       const int *rows, void *ws, void *out, int probe_opts, int trim_b,
@@ -1944,7 +1958,9 @@ static int aggregate_on_workspace(const float *copies, int64_t d, int64_t ld,
     // probe -> single pass -> decision (one block) -> median, which returns at once unless the
     // decision found a file whose slot 0 did not hold its winner.  Early-majority mode adds the
     // gated vote kernel and its decision between the two, for the files whose r' copies differ.
-    if (f == 169)
+    if (f == 169 && trim_b >= 0)
+        rc = byz_internal_launch_single_pass_8(f, r, X, d, ld, file_rows_dev, ws, O, probe_opts, trim_b, s);
+    else if (f == 169)
         rc = byz_internal_launch_single_pass_5(f, r, X, d, ld, file_rows_dev, ws, O, probe_opts, trim_b, s);
     else if (f == 121)
         rc = byz_internal_launch_single_pass_4(f, r, X, d, ld, file_rows_dev, ws, O, probe_opts, trim_b, s);
