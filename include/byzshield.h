@@ -182,10 +182,11 @@ int byz_vote_tolerant(const float *copies, int64_t d, int64_t ld, const int32_t 
  *   rows_base     device [*][ld] fp32;  row_index_dev device [f] int32;  out device [d] fp32,
  *                 must not overlap the input rows (may be NULL when d == 0).
  * f odd, 1 <= f <= 255.  A register selection network does the work for every f: generated for
- * f in {3,5,7,9,15,21,25,35,49,81,121,169,255} (the paper's file and worker counts, MOLS over
- * F_9, F_11, F_13, and the widest size), any other f on the next of those sizes with the spare
- * wires tied half to the smallest and half to the largest key (11.2 M coordinates: f = 27 0.23 ms,
- * f = 63 1.1 ms, f = 255 3.9 ms).  Errors: BYZ_EINVAL, BYZ_EUNSUPPORTED (even f), BYZ_EDEVICE.
+ * f in {3,5,7,9,15,21,25,35,49,63,65,81,121,169} (the paper's file and worker counts and MOLS
+ * over F_9, F_11, F_13), any other f <= 169 on the next of those sizes with the spare wires tied
+ * half to the smallest and half to the largest key; past 169 the rows are split over two
+ * wavefronts that sort a half each (11.2 M coordinates: f = 27 0.23 ms, f = 63 0.44 ms,
+ * f = 255 3.0 ms).  Errors: BYZ_EINVAL, BYZ_EUNSUPPORTED (even f), BYZ_EDEVICE.
  */
 int byz_median(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev,
                int f, float *out, void *stream);
@@ -200,9 +201,10 @@ int byz_median(const float *rows_base, int64_t d, int64_t ld, const int32_t *row
  * infinities go first).  b = 0 is the plain mean.  Not pure selection; the rounding contract
  * is: fp32, kept values added one by one in ascending order starting from +0, then one IEEE
  * division by float(f - 2b).
- *   f in {9,15,21,25,35,49,81,121,169,256} runs a generated register sorting network, any other
- *   f <= BYZ_MAX_F_WIDE the next of those sizes with the spare wires tied to the largest key
- *   (11.2 M coordinates: f = 25 0.19 ms, f = 81 0.85 ms, f = 255 5.7 ms).
+ *   f in {9,15,21,25,35,49,63,65,81,121,169} runs a generated register sorting network, any
+ *   other f <= 169 the next of those sizes with the spare wires tied to the largest key, and
+ *   169 < f <= BYZ_MAX_F_WIDE two wavefronts that sort half of the rows each and merge
+ *   (11.2 M coordinates: f = 25 0.19 ms, f = 81 0.80 ms, f = 255 4.6 ms).
  * Errors: BYZ_EINVAL (null pointers, sizes, b < 0 or 2b >= f), BYZ_EDEVICE.
  */
 int byz_trimmed_mean(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev,

@@ -67,8 +67,8 @@ int byz_internal_launch_median_169_padded(const void *X, long long d, long long 
                                           const int *row_index, int f, void *out, const void *gate,
                                           int gate_n, void *stream);
 
-// ... and on the widest networks: median 169 < f <= 255 on 255 wires, trimmed mean
-// 169 < f <= 256 on 256 wires (build parts 16 and 17).
+// ... and past 169 rows, with the rows split over two waves that sort a half each: median
+// 169 < f <= 255, trimmed mean 169 < f <= 256 (build parts 16 and 17).
 int byz_internal_launch_median_255_padded(const void *X, long long d, long long ld,
                                           const int *row_index, int f, void *out, const void *gate,
                                           int gate_n, void *stream);

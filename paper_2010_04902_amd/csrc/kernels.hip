@@ -28,7 +28,7 @@
 // group is part 7, the sixth and seventh parts 14 and 15, which also hold the 63- and 65-wire
 // trimmed-mean kernels, the eighth part 18), part 5 the median kernels, part 6 the
 // trimmed-mean kernels, parts 8..11 one 169-wire network kernel each, parts 12 and 13 the 81- and
-// 121-wire second phase of Bulyan, parts 16 and 17 the 255-wire median and the 256-wire sorting network.
+// 121-wire second phase of Bulyan, parts 16 and 17 the two-wave median and trimmed-mean kernels for f > 169.
 // Without BYZ_PART the whole library is
 // this one translation unit.
 #ifndef BYZ_PART
@@ -75,7 +75,7 @@ constexpr int prefetch_depth(int f, int slots) {
 // l^2 (MOLS, Ramanujan Case 1; 81, 121, 169 for l = 9, 11, 13) and m*s (Ramanujan Case 2)
 constexpr bool has_streamed_network(int f) {
     return f == 9 || f == 15 || f == 21 || f == 25 || f == 35 || f == 49 || f == 63 || f == 65 ||
-           f == 81 || f == 121 || f == 169 || f == 255;
+           f == 81 || f == 121 || f == 169;
 }
 // words per thread: fewer for the large networks, whose keys fill the register file
 constexpr int vec_for(int f) { return f <= 49 ? 4 : (f <= 81 ? 2 : 1); }
@@ -96,7 +96,7 @@ constexpr int kProbe = 256;  // sampled coordinates of the probe (512: 2x slower
 constexpr int kProbeSplit = 4;  // the files are dealt out to this many groups of kProbe threads
 constexpr int kProbeThreads = kProbe * kProbeSplit;
 constexpr int kBlock = 256;  // threads per block of the streaming kernels (128/512/1024: slower)
-constexpr int kWide = BYZ_MAX_F_WIDE;  // largest f of the vote and of the widest network (255 wires)
+constexpr int kWide = BYZ_MAX_F_WIDE;  // largest f of the vote, the median (255) and the trimmed mean
 static_assert(kWide <= kBlock, "one thread per file in the deciding block");
 constexpr int kPinFrom = 169;  // network sizes from which the trimmed-mean kernel pins its schedule
 constexpr int kRowStride = 8;  // slots per file in the permuted row table (>= BYZ_MAX_R)
@@ -857,6 +857,66 @@ __global__ __launch_bounds__(kBlock) void median_large_kernel(
     store_vec<V>(out + c0, o);
 }
 
+// Coordinate-wise median of H < f <= 2H - 1 rows (H = 96, 112, 128: up to 255 rows), two waves per
+// 64 coordinates: wave h of a block sorts wires [hH, hH + H) of its coordinates in registers
+// (H-wire sorting network, one word per thread), wave 1 hands its sorted keys over through LDS,
+// and wave 0 takes rank H - 1 of the union of the two sorted halves A and B as
+//     min( B[H-1], A[H-1], min over m = 0..H-2 of max(A[m], B[H-2-m]) )
+// (the H smallest of the union are the i smallest of A and the H - i smallest of B for some i;
+// the largest of those is max(A[i-1], B[H-1-i]), and the right i minimises it).  The 2H - f
+// spare wires sit at the end of half B, H - 1 - (f-1)/2 of them with the smallest key and the
+// rest with the largest, which puts the median of the f values at rank H - 1.  Half the
+// registers of one network over all rows, so two or three waves per SIMD instead of one and no
+// spills; the schedule is not pinned (pinned as in the single pass it was 14 % slower).
+// The waves-per-SIMD attribute states what the registers allow anyway; without it the compiler
+// schedules the H = 128 kernel half as fast (4.7 instead of 3.0 ms on 11.2 M coordinates).
+template <int F>  // = H
+__global__ __launch_bounds__(128)
+__attribute__((amdgpu_waves_per_eu(F <= 96 ? 3 : 2, F <= 96 ? 3 : 2)))
+void median_halves_kernel(
+    const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
+    int f, uint32_t *__restrict__ out, const uint32_t *__restrict__ gate, int gate_n) {
+    if (gate != nullptr && !any_word_set(gate, gate_n)) return;
+    __shared__ uint32_t s_half[F * 64];
+    const int ln = threadIdx.x & 63;
+    const int first = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) * F;  // first wire of this wave
+    const int64_t c = (int64_t)blockIdx.x * 64 + ln;
+    const int64_t cc = c < d ? c : d - 1;  // lanes past the end redo the last coordinate
+    const int pad_low_end = f + (F - 1 - (f - 1) / 2);
+    constexpr int V = 1, NS = 1, kAhead = 20;
+    uint32_t key[V][F];
+    const uint32_t voff = (uint32_t)(cc * 4);
+    const char *Xb = reinterpret_cast<const char *>(X);
+    uint32_t stage[kAhead + 1][NS][V];
+    const int lane = 0;
+    uint32_t flags[(F + 63) / 64] = {};
+    (void)lane; (void)flags;
+#undef BYZ_S_KEY
+#define BYZ_S_KEY(j, x) \
+    (first + (j) < f ? to_key(x) : (first + (j) < pad_low_end ? 0u : 0xFFFFFFFFu))
+#define BYZ_S_ROW_ADDR(j, k) \
+    (Xb + (uint64_t)(uint32_t)row_index[first + (j) < f ? first + (j) : 0] * (uint64_t)ld * 4u + voff)
+#include "generated/selnet_sort_stream_dispatch.inc"
+#undef BYZ_S_ROW_ADDR
+#undef BYZ_S_KEY
+#define BYZ_S_KEY(j, x) to_key(x)
+    if (first != 0) {
+#pragma unroll
+        for (int m = 0; m < F; ++m) s_half[m * 64 + ln] = key[0][m];
+    }
+    __syncthreads();
+    if (first == 0) {
+        uint32_t best = key[0][F - 1] < s_half[(F - 1) * 64 + ln] ? key[0][F - 1] : s_half[(F - 1) * 64 + ln];
+#pragma unroll
+        for (int m = 0; m < F - 1; ++m) {
+            const uint32_t b = s_half[(F - 2 - m) * 64 + ln];
+            const uint32_t t = key[0][m] > b ? key[0][m] : b;
+            best = best < t ? best : t;
+        }
+        if (c < d) out[c] = from_key(best);
+    }
+}
+
 // Coordinate-wise median for d below the vector width of the network kernels (f <= 64): rank
 // counting, one coordinate a thread.
 __global__ __launch_bounds__(kBlock) void median_generic_kernel(
@@ -939,6 +999,86 @@ __global__ __launch_bounds__(kBlock) void trimmed_mean_kernel(
     uint32_t o[V];
     trimmed_mean_of_sorted<F, V>(key, PAD ? f : F, b, o);
     store_vec<V>(out + c0, o);
+}
+
+// Coordinate-wise trimmed mean of F < f <= 2F rows (F = 128), two waves per 64 coordinates, same
+// rounding contract as trimmed_mean_kernel.  Wave h sorts wires [hF, hF + F) of its coordinates
+// in registers (the 2F - f spare wires at the end carry the largest key).  With A and B the two
+// sorted halves, min(A[m], B[F-1-m]) over m holds the F smallest of the union and max(...) the
+// F largest, each as a bitonic sequence: wave 1 passes B through LDS, wave 0 keeps the minima
+// and passes the maxima back through the same words, and each wave sorts its bitonic half with
+// log2(F) rounds of comparators F/2, F/4, ..., 1 apart.  Wave 0 then holds ranks 0..F-1 and
+// wave 1 ranks F..2F-1; the kept ranks are added in ascending order, wave 0's partial sum
+// going to wave 1 through LDS.  Half the registers of one 256-wire network per thread.
+template <int F>
+__global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void trimmed_halves_kernel(
+    const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
+    int f, int b, uint32_t *__restrict__ out, const uint32_t *__restrict__ gate, int gate_n) {
+    static_assert((F & (F - 1)) == 0, "the bitonic rounds below need a power of two");
+    if (gate != nullptr && !any_word_set(gate, gate_n)) return;
+    __shared__ uint32_t s_half[F * 64];
+    __shared__ float s_sum[64];
+    const int ln = threadIdx.x & 63;
+    const int first = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) * F;  // first wire of this wave
+    const int64_t c = (int64_t)blockIdx.x * 64 + ln;
+    const int64_t cc = c < d ? c : d - 1;  // lanes past the end redo the last coordinate
+    constexpr int V = 1, NS = 1, kAhead = 20;
+    uint32_t key[V][F];
+    const uint32_t voff = (uint32_t)(cc * 4);
+    const char *Xb = reinterpret_cast<const char *>(X);
+    uint32_t stage[kAhead + 1][NS][V];
+    const int lane = 0;
+    uint32_t flags[(F + 63) / 64] = {};
+    (void)lane; (void)flags;
+#undef BYZ_S_KEY
+#define BYZ_S_KEY(j, x) (first + (j) < f ? to_key(x) : 0xFFFFFFFFu)
+#define BYZ_S_ROW_ADDR(j, k) \
+    (Xb + (uint64_t)(uint32_t)row_index[first + (j) < f ? first + (j) : 0] * (uint64_t)ld * 4u + voff)
+#include "generated/selnet_sort_stream_dispatch.inc"
+#undef BYZ_S_ROW_ADDR
+#undef BYZ_S_KEY
+#define BYZ_S_KEY(j, x) to_key(x)
+    uint32_t(&k)[F] = key[0];
+    if (first != 0) {
+#pragma unroll
+        for (int m = 0; m < F; ++m) s_half[m * 64 + ln] = k[m];
+    }
+    __syncthreads();
+    if (first == 0) {
+#pragma unroll
+        for (int m = 0; m < F; ++m) {
+            const uint32_t a_ = k[m], b_ = s_half[(F - 1 - m) * 64 + ln];
+            k[m] = a_ < b_ ? a_ : b_;
+            s_half[(F - 1 - m) * 64 + ln] = a_ < b_ ? b_ : a_;
+        }
+    }
+    __syncthreads();
+    if (first != 0) {
+#pragma unroll
+        for (int m = 0; m < F; ++m) k[m] = s_half[m * 64 + ln];
+    }
+#pragma unroll
+    for (int apart = F / 2; apart >= 1; apart /= 2)
+#pragma unroll
+        for (int i = 0; i < F; ++i)
+            if ((i & apart) == 0) BYZ_CE(i, i + apart)
+    // ranks first .. first + F - 1, ascending; wave 0 adds its kept ranks first
+    float acc = 0.0f;
+    if (first == 0) {
+#pragma unroll
+        for (int i = 0; i < F; ++i)
+            if (i >= b && i < f - b) acc += __uint_as_float(from_key(k[i]));
+        s_sum[ln] = acc;
+    }
+    __syncthreads();
+    if (first != 0) {
+        acc = s_sum[ln];
+#pragma unroll
+        for (int i = 0; i < F; ++i)
+            if (F + i >= b && F + i < f - b) acc += __uint_as_float(from_key(k[i]));
+        if (c < d) out[c] = __float_as_uint(acc / (float)(f - 2 * b));
+    }
 }
 
 // Trimmed mean for d below the vector width of the network kernels (f <= 64): insertion sort
@@ -1645,26 +1785,40 @@ int byz_internal_launch_median_169_padded(const void *X, long long d, long long 
 }
 #endif
 
-// the widest networks: 255 wires for the median (169 < f <= 255), 256 for the trimmed mean
-// (169 < f <= 256; it also takes even f), spare wires when f is smaller; a build part each
+// more than 169 rows: the two-wave kernels, median for 169 < f <= 255, trimmed mean for
+// 169 < f <= 256 (it also takes even f); a build part each
 #if BYZ_IN_PART(16)
 int byz_internal_launch_median_255_padded(const void *X, long long d, long long ld,
                                           const int *row_index, int f, void *out, const void *gate,
                                           int gate_n, void *stream) {
-    return launch_median_large<255, true>(static_cast<const uint32_t *>(X), d, ld, row_index, f,
-                                          static_cast<uint32_t *>(out),
-                                          static_cast<const uint32_t *>(gate), gate_n,
-                                          (hipStream_t)stream);
+    if (d <= 0) return BYZ_OK;
+    if (f <= 128 || f > 255) return BYZ_EINTERNAL;
+    const unsigned g = (unsigned)((d + 63) / 64);
+    const uint32_t *x = static_cast<const uint32_t *>(X), *gt = static_cast<const uint32_t *>(gate);
+    uint32_t *o = static_cast<uint32_t *>(out);
+    hipStream_t s = (hipStream_t)stream;
+    // the smallest pair of halves that holds f rows
+    if (f <= 2 * 96 - 1)
+        median_halves_kernel<96><<<g, 128, 0, s>>>(x, d, ld, row_index, f, o, gt, gate_n);
+    else if (f <= 2 * 112 - 1)
+        median_halves_kernel<112><<<g, 128, 0, s>>>(x, d, ld, row_index, f, o, gt, gate_n);
+    else
+        median_halves_kernel<128><<<g, 128, 0, s>>>(x, d, ld, row_index, f, o, gt, gate_n);
+    BYZ_HIP(hipGetLastError());
+    return BYZ_OK;
 }
 #endif
 #if BYZ_IN_PART(17)
 int byz_internal_launch_trimmed_mean_256_padded(const void *X, long long d, long long ld,
                                                 const int *row_index, int f, int b, void *out,
                                                 const void *gate, int gate_n, void *stream) {
-    return launch_trimmed_net<256, true>(static_cast<const uint32_t *>(X), d, ld, row_index, f, b,
-                                         static_cast<uint32_t *>(out),
-                                         static_cast<const uint32_t *>(gate), gate_n,
-                                         (hipStream_t)stream);
+    if (d <= 0) return BYZ_OK;
+    if (f <= 128 || f > 256) return BYZ_EINTERNAL;
+    trimmed_halves_kernel<128><<<(unsigned)((d + 63) / 64), 128, 0, (hipStream_t)stream>>>(
+        static_cast<const uint32_t *>(X), d, ld, row_index, f, b, static_cast<uint32_t *>(out),
+        static_cast<const uint32_t *>(gate), gate_n);
+    BYZ_HIP(hipGetLastError());
+    return BYZ_OK;
 }
 #endif
 

@@ -589,8 +589,9 @@ def test_trimmed_mean_special_values():
     (RAM, 3, 47, 2, ALIE),       # f = 141: the 169-wire network with spare wires
     (RAM, 3, 85, 2, ALIE)])      # f = 255, the largest odd f
 def test_more_than_64_files(scheme, a, b, q, attack):
-    # pair bits in several 64-file groups; median and trimmed mean on the 81-, 121-, 169- and
-    # 255/256-wire register networks, with spare wires where f lies between two sizes
+    # pair bits in several 64-file groups; median and trimmed mean on the 81-, 121- and 169-wire
+    # register networks, with spare wires where f lies between two sizes, and on the two-wave
+    # kernels past 169
     for i, d in enumerate([1, 5, 64, 65, 1000, 4099]):
         ld = d if i % 2 == 0 else synth.padded_ld(d, 4) + 4
         w = W.make(scheme, a, b, q, d, attack, seed=700 + i, ld=ld, device=DEV)
@@ -609,15 +610,17 @@ def test_more_than_64_rows_of_raw_bit_patterns():
     U = rng.integers(0, 2**32, size=(300, d), dtype=np.uint64).astype(np.uint32)
     U[:, :200] &= np.uint32(0x80000003)  # few distinct values: ties everywhere
     X = torch.tensor(U.view(np.int32), device=DEV).view(torch.float32)
-    for f in (65, 67, 127, 129, 191, 255):
+    # 171 ... 255: the two-wave kernels, every size of their halves at both ends of its range
+    for f in (65, 67, 127, 129, 171, 191, 193, 223, 225, 255):
         idx = rng.integers(0, 300, size=f).astype(np.int32)
         out = B.byz_median(X, d, torch.tensor(idx, device=DEV))
         torch.cuda.synchronize()
         assert np.array_equal(W.bits(out), W.bits(C.median(U, idx, d))), f
         for b in (0, 7, (f - 1) // 2):
             _trimmed_mean_check(X, idx, d, b, (f, b))
-    idx = rng.integers(0, 300, size=256).astype(np.int32)  # even f: trimmed mean only
-    _trimmed_mean_check(X, idx, d, 100, 256)
+    for f, b in ((256, 100), (256, 0), (256, 127), (170, 84), (200, 1)):  # even f: trimmed mean only
+        idx = rng.integers(0, 300, size=f).astype(np.int32)
+        _trimmed_mean_check(X, idx, d, b, (f, b))
     for f in (257, 1000):
         with pytest.raises(B.ByzError) as e:
             B.byz_median(X, d, torch.zeros(f, dtype=torch.int32, device=DEV))
