@@ -1001,21 +1001,74 @@ __global__ __launch_bounds__(kBlock) void trimmed_mean_kernel(
     store_vec<V>(out + c0, o);
 }
 
-// Coordinate-wise trimmed mean of F < f <= 2F rows (F = 128), two waves per 64 coordinates, same
+// Sorts a bitonic sequence of F keys ascending with the log2(P) rounds of comparators P/2, P/4,
+// ..., 1 apart of the P-wire bitonic merger, P the power of two at or above F.  The P - F spare
+// wires carry the smallest key in front of a sequence that rises and then falls (LOW), the
+// largest key behind one that falls and then rises (!LOW), which keeps either bitonic;
+// comparators that only see spare wires fold away at compile time.
+template <int F, int P, bool LOW>
+__device__ __forceinline__ void sort_bitonic(uint32_t (&keys)[F]) {
+    static_assert((P & (P - 1)) == 0 && P >= F && P < 2 * F, "P = power of two at or above F");
+    if constexpr (P == F) {
+        uint32_t(&k)[F] = keys;
+#pragma unroll
+        for (int apart = P / 2; apart >= 1; apart /= 2)
+#pragma unroll
+            for (int i = 0; i < P; ++i)
+                if ((i & apart) == 0) BYZ_CE(i, i + apart)
+    } else {
+        uint32_t k[P];
+#pragma unroll
+        for (int i = 0; i < P; ++i)
+            k[i] = LOW ? (i < P - F ? 0u : keys[i - (P - F) < 0 ? 0 : i - (P - F)])
+                       : (i < F ? keys[i < F ? i : 0] : 0xFFFFFFFFu);
+#pragma unroll
+        for (int apart = P / 2; apart >= 1; apart /= 2)
+#pragma unroll
+            for (int i = 0; i < P; ++i)
+                if ((i & apart) == 0) BYZ_CE(i, i + apart)
+#pragma unroll
+        for (int i = 0; i < F; ++i) keys[i] = k[LOW ? P - F + i : i];
+    }
+}
+
+// acc += the keys' values whose ranks rank0 + i lie in [b, f - b), in ascending order.  b and f are
+// wave-uniform: runs of eight ranks that lie wholly inside are added without a test, runs
+// wholly outside are skipped.
+template <int F>
+__device__ __forceinline__ float add_kept_ranks(const uint32_t (&k)[F], int rank0, int b, int f,
+                                                float acc) {
+    static_assert(F % 8 == 0, "runs of eight");
+#pragma unroll
+    for (int i0 = 0; i0 < F; i0 += 8) {
+        const int lo = rank0 + i0, hi = lo + 7;
+        if (lo >= b && hi < f - b) {
+#pragma unroll
+            for (int i = i0; i < i0 + 8; ++i) acc += __uint_as_float(from_key(k[i]));
+        } else if (hi >= b && lo < f - b) {
+#pragma unroll
+            for (int i = i0; i < i0 + 8; ++i)
+                if (rank0 + i >= b && rank0 + i < f - b) acc += __uint_as_float(from_key(k[i]));
+        }
+    }
+    return acc;
+}
+
+// Coordinate-wise trimmed mean of F < f <= 2F rows (F = 96, 112, 128), two waves per 64 coordinates, same
 // rounding contract as trimmed_mean_kernel.  Wave h sorts wires [hF, hF + F) of its coordinates
 // in registers (the 2F - f spare wires at the end carry the largest key).  With A and B the two
 // sorted halves, min(A[m], B[F-1-m]) over m holds the F smallest of the union and max(...) the
 // F largest, each as a bitonic sequence: wave 1 passes B through LDS, wave 0 keeps the minima
-// and passes the maxima back through the same words, and each wave sorts its bitonic half with
-// log2(F) rounds of comparators F/2, F/4, ..., 1 apart.  Wave 0 then holds ranks 0..F-1 and
+// and passes the maxima back through the same words, and each wave sorts its bitonic half
+// (sort_bitonic).  Wave 0 then holds ranks 0..F-1 and
 // wave 1 ranks F..2F-1; the kept ranks are added in ascending order, wave 0's partial sum
 // going to wave 1 through LDS.  Half the registers of one 256-wire network per thread.
 template <int F>
-__global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__global__ __launch_bounds__(128)
+__attribute__((amdgpu_waves_per_eu(2, 2)))
 void trimmed_halves_kernel(
     const uint32_t *__restrict__ X, int64_t d, int64_t ld, const int32_t *__restrict__ row_index,
     int f, int b, uint32_t *__restrict__ out, const uint32_t *__restrict__ gate, int gate_n) {
-    static_assert((F & (F - 1)) == 0, "the bitonic rounds below need a power of two");
     if (gate != nullptr && !any_word_set(gate, gate_n)) return;
     __shared__ uint32_t s_half[F * 64];
     __shared__ float s_sum[64];
@@ -1054,29 +1107,29 @@ void trimmed_halves_kernel(
         }
     }
     __syncthreads();
-    if (first != 0) {
-#pragma unroll
-        for (int m = 0; m < F; ++m) k[m] = s_half[m * 64 + ln];
-    }
-#pragma unroll
-    for (int apart = F / 2; apart >= 1; apart /= 2)
-#pragma unroll
-        for (int i = 0; i < F; ++i)
-            if ((i & apart) == 0) BYZ_CE(i, i + apart)
     // ranks first .. first + F - 1, ascending; wave 0 adds its kept ranks first
     float acc = 0.0f;
-    if (first == 0) {
+    constexpr int P = 128;  // wires of the bitonic merger
+    if constexpr (F == P) {
+        if (first != 0) {
 #pragma unroll
-        for (int i = 0; i < F; ++i)
-            if (i >= b && i < f - b) acc += __uint_as_float(from_key(k[i]));
+            for (int m = 0; m < F; ++m) k[m] = s_half[m * 64 + ln];
+        }
+        sort_bitonic<F, P, true>(k);  // no spare wires: one code path for both waves
+    }
+    if (first == 0) {
+        if constexpr (F != P) sort_bitonic<F, P, true>(k);
+        acc = add_kept_ranks<F>(k, 0, b, f, acc);
         s_sum[ln] = acc;
     }
     __syncthreads();
     if (first != 0) {
-        acc = s_sum[ln];
+        if constexpr (F != P) {
 #pragma unroll
-        for (int i = 0; i < F; ++i)
-            if (F + i >= b && F + i < f - b) acc += __uint_as_float(from_key(k[i]));
+            for (int m = 0; m < F; ++m) k[m] = s_half[m * 64 + ln];
+            sort_bitonic<F, P, false>(k);
+        }
+        acc = add_kept_ranks<F>(k, F, b, f, s_sum[ln]);
         if (c < d) out[c] = __float_as_uint(acc / (float)(f - 2 * b));
     }
 }
@@ -1814,9 +1867,17 @@ int byz_internal_launch_trimmed_mean_256_padded(const void *X, long long d, long
                                                 const void *gate, int gate_n, void *stream) {
     if (d <= 0) return BYZ_OK;
     if (f <= 128 || f > 256) return BYZ_EINTERNAL;
-    trimmed_halves_kernel<128><<<(unsigned)((d + 63) / 64), 128, 0, (hipStream_t)stream>>>(
-        static_cast<const uint32_t *>(X), d, ld, row_index, f, b, static_cast<uint32_t *>(out),
-        static_cast<const uint32_t *>(gate), gate_n);
+    const unsigned g = (unsigned)((d + 63) / 64);
+    const uint32_t *x = static_cast<const uint32_t *>(X), *gt = static_cast<const uint32_t *>(gate);
+    uint32_t *o = static_cast<uint32_t *>(out);
+    hipStream_t s = (hipStream_t)stream;
+    // the smallest pair of halves that holds f rows
+    if (f <= 2 * 96)
+        trimmed_halves_kernel<96><<<g, 128, 0, s>>>(x, d, ld, row_index, f, b, o, gt, gate_n);
+    else if (f <= 2 * 112)
+        trimmed_halves_kernel<112><<<g, 128, 0, s>>>(x, d, ld, row_index, f, b, o, gt, gate_n);
+    else
+        trimmed_halves_kernel<128><<<g, 128, 0, s>>>(x, d, ld, row_index, f, b, o, gt, gate_n);
     BYZ_HIP(hipGetLastError());
     return BYZ_OK;
 }
