@@ -627,6 +627,32 @@ def test_more_than_64_rows_of_raw_bit_patterns():
         assert e.value.code == -1
 
 
+def test_more_than_169_rows_random_sizes():
+    # the two-wave kernels (rows split over two waves that sort a half each): random f in
+    # 170..256 (every size of the halves, spare wires of both kinds), d from one coordinate to
+    # several blocks with ragged tails, row pitches, raw bit patterns with ties and signed zeros
+    # as well as normal data; median for odd f, trimmed mean with b = 0, random, largest
+    rng = np.random.default_rng(169)
+    for case in range(36):
+        f = int(rng.integers(170, 257))
+        d = int(rng.choice([rng.integers(1, 70), rng.integers(70, 700), rng.integers(700, 9000)]))
+        ld = d + int(rng.integers(0, 7))
+        n_rows = f + int(rng.integers(0, 40))
+        U = rng.integers(0, 2**32, size=(n_rows, ld), dtype=np.uint64).astype(np.uint32)
+        if case % 3 == 0:
+            U[:, : d // 2] &= np.uint32(0x80000007)
+        if case % 3 == 1:
+            U = rng.standard_normal((n_rows, ld)).astype(np.float32).view(np.uint32)
+        X = torch.tensor(U.view(np.int32), device=DEV).view(torch.float32)
+        idx = rng.integers(0, n_rows, size=f).astype(np.int32)
+        if f % 2 == 1:
+            out = B.byz_median(X, d, torch.tensor(idx, device=DEV))
+            torch.cuda.synchronize()
+            assert np.array_equal(W.bits(out), W.bits(C.median(U, idx, d))), (case, f, d, ld)
+        for b in sorted({0, int(rng.integers(0, (f + 1) // 2)), (f - 1) // 2}):
+            _trimmed_mean_check(X, idx, d, b, (case, f, d, ld, b))
+
+
 def _multi_krum_check(X, idx_np, d, c, m, tag):
     """GPU Multi-Krum against the fp64 oracle.
 
