@@ -268,6 +268,19 @@ int byz_bulyan(const float *rows_base, int64_t d, int64_t ld, const int32_t *row
                int c, float *out, int32_t *selected_out, int32_t *order_out, double *dist_out,
                void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Mean around the median, the coordinate-wise aggregator Sec. 1 names beside the median (the
+ * average of the values of a coordinate that lie closest to its median) and the second phase
+ * of byz_bulyan, on its own: out[t] = mean of the beta values of
+ * { rows_base[row_index[j]*ld + t] : j < f } closest to their median, window and arithmetic
+ * exactly as in phase 2 of byz_bulyan (beta = 1 is byz_median, beta = f the plain mean in
+ * ascending order).  f odd, 1 <= f <= BYZ_MAX_F_KRUM, 1 <= beta <= f.
+ * Errors: BYZ_EINVAL (null pointers, sizes, beta), BYZ_EUNSUPPORTED (even f), BYZ_EDEVICE.
+ */
+int byz_mean_around_median(const float *rows_base, int64_t d, int64_t ld,
+                           const int32_t *row_index_dev, int f, int beta, float *out,
+                           void *stream);
+
 /* --------------------------------------------------- device: fused vote + median (whole path) */
 
 /* Bytes of device scratch byz_aggregate needs for (f, r); 0 if (f, r) is invalid. */

@@ -72,6 +72,7 @@ def _load():
         "byz_aggregate_has_single_pass": (c_int, [c_int, c_int]),
         "byz_bulyan_workspace_bytes": (sz, [c_int]),
         "byz_bulyan": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, vp, vp, sz, vp]),
+        "byz_mean_around_median": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp]),
         "byz_aggregate": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, sz, vp]),
         "byz_aggregate_opts": (c_int, [vp, i64, i64, vp, c_int, c_int, vp, vp, vp, sz,
                                        ctypes.c_uint, vp]),
@@ -353,6 +354,22 @@ def byz_bulyan(rows_base, d, row_index_dev, c, out=None, workspace=None, stream=
                               _dev_ptr(workspace, ("uint8",), "workspace"),
                               int(workspace.numel()), _stream_ptr(stream)), "byz_bulyan")
     return out, selected, order[:max(f - 2 * int(c), 0)], dist
+
+
+def byz_mean_around_median(rows_base, d, row_index_dev, beta, out=None, stream=None):
+    """-> out[d] float32 on device: mean of the beta values closest to the median, per coordinate."""
+    torch = _torch()
+    ld = _rows_2d(rows_base)
+    f = int(row_index_dev.numel())
+    _need_rows_in_range(row_index_dev, f, int(rows_base.shape[0]), "row_index_dev")
+    if out is None:
+        out = torch.empty(int(d), dtype=torch.float32, device=rows_base.device)
+    _need(out, int(d), "out")
+    _check(_load().byz_mean_around_median(_dev_ptr(rows_base, ("float32",), "rows_base"), int(d), ld,
+                                          _dev_ptr(row_index_dev, ("int32",), "row_index_dev"), f,
+                                          int(beta), _dev_ptr(out, ("float32",), "out"),
+                                          _stream_ptr(stream)), "byz_mean_around_median")
+    return out
 
 
 def byz_aggregate_workspace_bytes(f, r):

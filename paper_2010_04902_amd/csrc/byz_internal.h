@@ -6,8 +6,7 @@
 void byz_internal_set_hip_error(int code);
 
 // Second phase of Bulyan (kernels.hip): out[c] = mean of the beta values closest to the median
-// among the rows selected_rows_dev[0..theta-1] (a table of BYZ_MAX_F_KRUM valid row numbers: the
-// entries from theta on are read but their values ignored).  Returns a byz_status.
+// among the rows selected_rows_dev[0..theta-1].  Returns a byz_status.
 int byz_internal_launch_bulyan_mean(const float *rows_base, long long d, long long ld,
                                     const int *selected_rows_dev, int f, int theta, int beta,
                                     float *out, void *stream);

@@ -1202,7 +1202,7 @@ __device__ __forceinline__ float mean_around_median(const float *col, int stride
 
 // Second phase of Bulyan: the theta rows selected_rows[0..theta-1] are sorted per coordinate
 // by the streamed full-sort network on N >= theta wires (N the next generated size); the
-// N - theta spare wires load whatever valid row the table names and are tied to the largest
+// N - theta spare wires reload the first row and are tied to the largest
 // key, so wires 0..theta-1
 // end up holding the chosen values in ascending order.  They go to an LDS column of the thread
 // (word i*BLOCK + thread: conflict-free), where the window around the median is found with
@@ -1229,7 +1229,8 @@ __global__ __launch_bounds__(BLOCK) void bulyan_mean_kernel(
     (void)lane; (void)flags;
 #undef BYZ_S_KEY
 #define BYZ_S_KEY(j, x) ((j) < theta ? to_key(x) : 0xFFFFFFFFu)
-#define BYZ_S_ROW_ADDR(j, k) (Xb + (uint64_t)(uint32_t)selected_rows[j] * (uint64_t)ld * 4u + voff)
+#define BYZ_S_ROW_ADDR(j, k) \
+    (Xb + (uint64_t)(uint32_t)selected_rows[(j) < theta ? (j) : 0] * (uint64_t)ld * 4u + voff)
 #include "generated/selnet_sort_stream_dispatch.inc"
 #undef BYZ_S_ROW_ADDR
 #undef BYZ_S_KEY

@@ -766,3 +766,14 @@ extern "C" int byz_bulyan(const float *rows_base, int64_t d, int64_t ld,
     return byz_internal_launch_bulyan_mean(rows_base, d, ld, ws->selected_rows, f, theta,
                                            theta - 2 * c, out, stream);
 }
+
+extern "C" int byz_mean_around_median(const float *rows_base, int64_t d, int64_t ld,
+                                      const int32_t *row_index_dev, int f, int beta, float *out,
+                                      void *stream) {
+    if (rows_base == nullptr || row_index_dev == nullptr || (out == nullptr && d > 0))
+        return BYZ_EINVAL;
+    if (d < 0 || ld < d || d > ((int64_t)1 << 30)) return BYZ_EINVAL;
+    if (f < 1 || f > kMaxKrum || beta < 1 || beta > f) return BYZ_EINVAL;
+    if ((f % 2) == 0) return BYZ_EUNSUPPORTED;  // the median must be one of the values
+    return byz_internal_launch_bulyan_mean(rows_base, d, ld, row_index_dev, f, f, beta, out, stream);
+}

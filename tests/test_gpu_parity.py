@@ -653,6 +653,38 @@ def test_more_than_169_rows_random_sizes():
             _trimmed_mean_check(X, idx, d, b, (case, f, d, ld, b))
 
 
+def test_mean_around_median_alone():
+    # byz_mean_around_median = the second phase of Bulyan on rows of the caller's choice: every
+    # network size of that kernel and the sizes between (spare wires), d below and above the
+    # vector width, beta = 1 (the median, bit for bit), a random beta, beta = f (plain mean);
+    # normal data and small integers (ties in the window rule)
+    rng = np.random.default_rng(183)
+    for f in (1, 3, 9, 13, 15, 25, 27, 49, 51, 63, 81, 99, 121, 127):
+        d = int(rng.choice([rng.integers(1, 4), rng.integers(4, 300), rng.integers(300, 20000)]))
+        ld = d + int(rng.integers(0, 5))
+        Xh = np.zeros((f + 3, ld), dtype=np.float32)
+        Xh[:, :d] = rng.standard_normal((f + 3, d)).astype(np.float32) * rng.uniform(0.1, 30.0, size=(f + 3, 1))
+        Xh[:, : d // 3] = rng.integers(-3, 4, size=(f + 3, d // 3)).astype(np.float32)
+        X = torch.tensor(Xh, device=DEV)
+        idx = rng.permutation(f + 3)[:f].astype(np.int32)
+        idx_dev = torch.tensor(idx, device=DEV)
+        chosen = np.arange(f, dtype=np.int32)
+        vmax = np.abs(Xh[idx][:, :d].astype(np.float64)).max(axis=0)
+        for beta in sorted({1, int(rng.integers(1, f + 1)), f}):
+            out = B.byz_mean_around_median(X, d, idx_dev, beta)
+            torch.cuda.synchronize()
+            out_o = C.mean_around_median(Xh, idx, chosen, d, beta)
+            tol = 1.5 * beta * 2.0 ** -24 * vmax + 1e-44
+            assert (np.abs(out.cpu().numpy().astype(np.float64) - out_o) <= tol).all(), (f, d, beta)
+            if beta == 1:
+                assert np.array_equal(W.bits(out), W.bits(B.byz_median(X, d, idx_dev))), (f, d)
+    X = torch.zeros((130, 8), device=DEV)
+    for n, beta, code in [(4, 1, -2), (5, 0, -1), (5, 6, -1), (129, 1, -1)]:
+        with pytest.raises(B.ByzError) as e:
+            B.byz_mean_around_median(X, 8, torch.arange(n, dtype=torch.int32, device=DEV), beta)
+        assert e.value.code == code, (n, beta)
+
+
 def _multi_krum_check(X, idx_np, d, c, m, tag):
     """GPU Multi-Krum against the fp64 oracle.
 
