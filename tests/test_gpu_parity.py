@@ -1019,6 +1019,37 @@ def test_hidden_equality_patterns_of_wide_files():
                                            B.BYZ_PATH_REVOTED | B.BYZ_PATH_MEDIAN_REDONE}, seen
 
 
+def test_repeated_calls_on_one_workspace_never_change():
+    # what the waves publish through atomics (pair bits, which copies were fed) may arrive in
+    # any order: the same call forty times on one workspace, on an input that takes the single
+    # pass and on one that sends it past it, has to give the same words, winners and path
+    d = 300_007
+    w = W.make(MOLS, 5, 3, 4, d, ALIE, seed=91, ld=synth.padded_ld(d, 64), device=DEV)
+    rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+    split = w.X.clone()
+    for j in range(w.f):
+        ks = [k for k in range(w.r) if int(w.file_workers[j, k]) in w.byz]
+        if len(ks) >= 2:
+            for i, k in enumerate(ks):
+                split[int(w.file_rows[j, k]), d // 2 + 7 + 64 * i] += 1.0
+    seen_paths = set()
+    for X in (w.X, split):
+        for flags in (0, B.BYZ_AGG_EARLY_MAJORITY, B.BYZ_AGG_TRIM(w.cmax)):
+            ws = torch.empty(B.byz_aggregate_workspace_bytes(w.f, w.r), dtype=torch.uint8, device=DEV)
+            out0, wrep0, _ = B.byz_aggregate_opts(X, d, rows_dev, w.f, w.r, flags, workspace=ws)
+            path0 = B.byz_aggregate_path(ws)
+            seen_paths.add(path0)
+            out0, wrep0 = out0.clone(), wrep0.clone()
+            out, wrep = torch.empty_like(out0), torch.empty_like(wrep0)
+            for it in range(40):
+                B.byz_aggregate_opts(X, d, rows_dev, w.f, w.r, flags, out=out, winner_replica=wrep,
+                                     workspace=ws)
+                assert B.byz_aggregate_path(ws) == path0, (flags, it)
+                assert torch.equal(out.view(torch.int32), out0.view(torch.int32)), (flags, it)
+                assert torch.equal(wrep, wrep0), (flags, it)
+    assert SINGLE in seen_paths and REDONE in seen_paths, seen_paths
+
+
 def test_random_shapes_sizes_and_layouts():
     # a seeded sweep over assignments (every kernel family: generated, padded and 169-wire
     # networks, single pass and two-step, more than 64 files, r = 3, 5, 7), sizes, row pitches,
