@@ -204,7 +204,7 @@ int byz_median(const float *rows_base, int64_t d, int64_t ld, const int32_t *row
  *   f in {9,15,21,25,35,49,63,65,81,121,169} runs a generated register sorting network, any
  *   other f <= 169 the next of those sizes with the spare wires tied to the largest key, and
  *   169 < f <= BYZ_MAX_F_WIDE two wavefronts that sort half of the rows each and merge
- *   (11.2 M coordinates: f = 25 0.19 ms, f = 81 0.80 ms, f = 255 4.6 ms).
+ *   (11.2 M coordinates: f = 25 0.19 ms, f = 81 0.80 ms, f = 255 4.0 ms).
  * Errors: BYZ_EINVAL (null pointers, sizes, b < 0 or 2b >= f), BYZ_EDEVICE.
  */
 int byz_trimmed_mean(const float *rows_base, int64_t d, int64_t ld, const int32_t *row_index_dev,
