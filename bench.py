@@ -336,6 +336,10 @@ def main():
                                                              1e-5, stream=stream))
         ms_med = timed_call(lambda: B.byz_median(bufs[0], d, wrow_v, out=out, stream=stream))
         ms_tm = timed_call(lambda: B.byz_trimmed_mean(bufs[0], d, wrow_v, cmax, out=out, stream=stream))
+        ms_mam, mam_beta = None, max(1, asg.f - 2 * cmax)
+        if asg.f <= B.BYZ_MAX_F_KRUM:
+            ms_mam = timed_call(lambda: B.byz_mean_around_median(bufs[0], d, wrow_v, mam_beta, out=out,
+                                                                 stream=stream))
         ms_agg_tm = timed_call(lambda: step(0, B.BYZ_AGG_TRIM(cmax)))
         mk_m = asg.f - cmax
         ms_mk = None
@@ -406,6 +410,9 @@ def main():
                 "note": "Gram + reduce + repeated Krum + mean around the median of theta rows"},
             "byz_trimmed_mean": {"ms": ms_tm, "b": cmax, "algorithmic_bytes": mb,
                                  "gbps": mb / ms_tm / 1e6, "frac": mb / ms_tm / 1e6 / HBM_PEAK_GBPS},
+            "byz_mean_around_median": None if ms_mam is None else {
+                "ms": ms_mam, "beta": mam_beta, "algorithmic_bytes": mb,
+                "gbps": mb / ms_mam / 1e6, "frac": mb / ms_mam / 1e6 / HBM_PEAK_GBPS},
         }
 
     if not args.no_cpu:
