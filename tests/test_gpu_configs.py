@@ -39,8 +39,25 @@ def _full_check(w, tag):
     assert np.array_equal(wrep_e.cpu().numpy(), wrep_o), tag
     assert B.byz_aggregate_path(ws_e) == B.BYZ_PATH_SINGLE_PASS, tag
     assert np.array_equal(W.bits(out_m), W.bits(out_o)), tag
-    # these attacks differ from the honest copy on the probe sample
+    # every file has a majority among its copies
     assert path == B.BYZ_PATH_SINGLE_PASS, tag
+    # the trimmed mean in the single pass at this size (b = c_max per side): the same words as
+    # vote + byz_trimmed_mean, and within the rounding contract's bound of the fp64 oracle on
+    # the head, the tail and 100,000 random coordinates
+    from tests.test_gpu_parity import _assert_trimmed_mean_close
+    b = min(w.cmax, (w.f - 1) // 2)
+    out_t, wrep_t, ws_t = B.byz_aggregate_opts(w.X, w.d, rows_dev, w.f, w.r, B.BYZ_AGG_TRIM(b))
+    out_t2 = B.byz_trimmed_mean(w.X, w.d, wrow_v, b)
+    torch.cuda.synchronize()
+    assert B.byz_aggregate_path(ws_t) == B.BYZ_PATH_SINGLE_PASS, tag
+    assert np.array_equal(wrep_t.cpu().numpy(), wrep_o), tag
+    assert torch.equal(out_t.view(torch.int32), out_t2.view(torch.int32)), tag
+    rng = np.random.default_rng(w.f * 1000 + w.r)
+    cols = np.unique(np.concatenate([np.arange(0, 1024), np.arange(w.d - 1024, w.d),
+                                     rng.integers(0, w.d, size=100_000)]))
+    cols_dev = torch.tensor(cols, dtype=torch.int64, device=DEV)
+    Xs = np.ascontiguousarray(w.X[:, cols_dev].cpu().numpy())
+    _assert_trimmed_mean_close(out_t[cols_dev], Xs, wrow_o, len(cols), b, tag)
     # Sec. 2: exactly the files with >= r' Byzantine copies lose the vote; the paper's c_max
     wrong = 0
     for j in range(w.f):
