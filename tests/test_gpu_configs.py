@@ -150,6 +150,23 @@ def test_ramanujan_case2_wide_clusters_full_size(s_, m_, q, shape):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("idx,shape", [(11, (33, 121, 11, 3)), (12, (39, 169, 13, 3))])
+def test_mols_over_f11_and_f13_full_size(idx, shape):
+    # MOLS over F_11 and F_13 at the ResNet-18 size (363 and 507 rows, 16 and 23 GB): the
+    # single pass with one word per thread on the 121- and 169-wire networks, median and
+    # trimmed mean, in the launch configuration the measurements use
+    cfg = synth.CONFIGS[idx]
+    free_bytes, _ = torch.cuda.mem_get_info()
+    if free_bytes < (cfg.f * cfg.r + 2 * cfg.f + 8) * 4 * cfg.d:
+        pytest.skip("needs more device memory")
+    w = W.from_config(cfg, DEV, ld=synth.padded_ld(cfg.d, 64))
+    assert (w.K, w.f, w.l, w.r) == shape and w.cmax == cfg.cmax
+    assert B.byz_aggregate_has_single_pass(w.f, w.r)
+    assert _full_check(w, cfg.name) == cfg.cmax
+    del w
+    torch.cuda.empty_cache()
+
+
 def test_prime_power_cluster_full_size():
     # MOLS over F_9: (K,f,l,r) = (27,81,9,3), 243 rows of the ResNet-18 size, q = 5 worst-case
     # set, ALIE.  f > 64: pair bits in two 64-file groups, 81-wire network with two words a thread.
