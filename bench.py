@@ -84,7 +84,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, help="workload 1..13 (default 2, the headline)")
+    ap.add_argument("--config", type=int, default=2, help="workload 1..14 (default 2, the headline)")
     ap.add_argument("--unpadded", action="store_true", help="row pitch ld = d instead of d rounded up to 64")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-early", action="store_true", help="skip the early-majority leg")

@@ -1,4 +1,4 @@
-"""The five workloads (and eight more shapes): cluster shapes of the paper's tables with seeded Gaussian gradients.
+"""The five workloads (and nine more shapes): cluster shapes of the paper's tables with seeded Gaussian gradients.
 
 scheme/a/b follow the library's byz_build_assignment arguments: MOLS (l, r) or
 Ramanujan (s, m).  `cmax` is the value the paper's Tables 3, 4, 6 print for that (graph, q) where one does.
@@ -51,4 +51,9 @@ CONFIGS = [
            {"kind": "alie", "z": 1.0}, 1, 20101004 + 113),
     Config("cfg13_mols13x3_resnet18_alie", MOLS, 13, 3, 39, 169, 13, 3, 4, 5, 11173962,
            {"kind": "alie", "z": 1.0}, 1, 20101004 + 133),
+    # the widest file count the library takes: Ramanujan Case 2 with s = 3, m = 85,
+    # (K,f,l,r) = (9,255,85,3), 765 rows (34 GB); q = 2, c_max = 29 from the exhaustive search.
+    # No single pass at this width: vote kernel, then the median over 255 winners
+    Config("cfg14_ram3x85_resnet18_alie", RAMANUJAN, 3, 85, 9, 255, 85, 3, 2, 29, 11173962,
+           {"kind": "alie", "z": 1.0}, 1, 20101004 + 385),
 ]

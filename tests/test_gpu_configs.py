@@ -167,6 +167,41 @@ def test_mols_over_f11_and_f13_full_size(idx, shape):
     torch.cuda.empty_cache()
 
 
+def test_widest_cluster_full_size():
+    # 255 files (Ramanujan Case 2, s = 3, m = 85: (K,f,l,r) = (9,255,85,3)), 765 rows of the
+    # ResNet-18 size: no single pass at this width, so byz_aggregate runs the vote kernel and the
+    # two-wave median over the 255 winners.  The vote is checked in full, the median and the
+    # trimmed mean on the head, the tail and 60,000 random coordinates
+    from tests.test_gpu_parity import _assert_trimmed_mean_close
+    cfg = synth.CONFIGS[13]
+    free_bytes, _ = torch.cuda.mem_get_info()
+    if free_bytes < (cfg.f * cfg.r + 2 * cfg.f + 8) * 4 * cfg.d:
+        pytest.skip("needs more device memory")
+    w = W.from_config(cfg, DEV, ld=synth.padded_ld(cfg.d, 64))
+    assert (w.K, w.f, w.l, w.r) == (9, 255, 85, 3) and w.cmax == cfg.cmax
+    assert not B.byz_aggregate_has_single_pass(w.f, w.r)
+    rows_dev = torch.tensor(w.file_rows.reshape(-1), dtype=torch.int32, device=DEV)
+    out, wrep, ws = B.byz_aggregate(w.X, w.d, rows_dev, w.f, w.r)
+    out_t, wrep_t, _ = B.byz_aggregate_opts(w.X, w.d, rows_dev, w.f, w.r, B.BYZ_AGG_TRIM(w.cmax))
+    torch.cuda.synchronize()
+    assert B.byz_aggregate_path(ws) == B.BYZ_PATH_TWO_STEP
+    Xh = w.X.cpu().numpy()
+    wrep_o, wrow_o, _ = C.vote(Xh, w.file_rows, w.d)
+    del Xh
+    assert np.array_equal(wrep.cpu().numpy(), wrep_o) and np.array_equal(wrep_t.cpu().numpy(), wrep_o)
+    lost = sum(1 for j in range(w.f) if int(w.file_workers[j, wrep_o[j]]) in w.byz)
+    assert lost == cfg.cmax
+    rng = np.random.default_rng(255)
+    cols = np.unique(np.concatenate([np.arange(0, 1024), np.arange(w.d - 1024, w.d),
+                                     rng.integers(0, w.d, size=60_000)]))
+    cols_dev = torch.tensor(cols, dtype=torch.int64, device=DEV)
+    Xs = np.ascontiguousarray(w.X[:, cols_dev].cpu().numpy())
+    assert np.array_equal(W.bits(out[cols_dev]), W.bits(C.median(Xs, wrow_o, len(cols))))
+    _assert_trimmed_mean_close(out_t[cols_dev], Xs, wrow_o, len(cols), w.cmax, cfg.name)
+    del w
+    torch.cuda.empty_cache()
+
+
 def test_prime_power_cluster_full_size():
     # MOLS over F_9: (K,f,l,r) = (27,81,9,3), 243 rows of the ResNet-18 size, q = 5 worst-case
     # set, ALIE.  f > 64: pair bits in two 64-file groups, 81-wire network with two words a thread.
