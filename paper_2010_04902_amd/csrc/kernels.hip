@@ -939,18 +939,50 @@ __global__ __launch_bounds__(kBlock) void median_generic_kernel(
 
 // Rounding contract of the trimmed mean: fp32, the kept values (ranks b .. F-b-1 of the sorted
 // keys) are added one by one in ascending order starting from +0, then one IEEE division.
-template <int F, int V>
+template <int F, int V, bool RUNS = false>
 __device__ __forceinline__ void trimmed_mean_of_sorted(const uint32_t (&key)[V][F], int f, int b,
                                                        uint32_t (&o)[V]) {
     // wires 0..f-1 hold the f values in ascending order (f = F unless the network is padded)
     const float denom = (float)(f - 2 * b);
+    if constexpr (RUNS) {
+        // b and f are wave-uniform: runs of eight ranks that lie wholly inside [b, f - b) are
+        // added without a test, runs wholly outside are skipped (for the kernels whose
+        // schedule is pinned; the others lose registers to it)
+        float acc[V];
 #pragma unroll
-    for (int v = 0; v < V; ++v) {
-        float acc = 0.0f;
+        for (int v = 0; v < V; ++v) acc[v] = 0.0f;
 #pragma unroll
-        for (int i = 0; i < F; ++i)
-            if (i >= b && i < f - b) acc += __uint_as_float(from_key(key[v][i]));
-        o[v] = __float_as_uint(acc / denom);
+        for (int i0 = 0; i0 < F; i0 += 8) {
+            const int lo = i0, hi = (i0 + 8 < F ? i0 + 8 : F) - 1;
+            if (lo >= b && hi < f - b) {
+#pragma unroll
+                for (int i = i0; i < i0 + 8; ++i)
+                    if (i < F) {
+#pragma unroll
+                        for (int v = 0; v < V; ++v)
+                            acc[v] += __uint_as_float(from_key(key[v][i < F ? i : 0]));
+                    }
+            } else if (hi >= b && lo < f - b) {
+#pragma unroll
+                for (int i = i0; i < i0 + 8; ++i)
+                    if (i < F && i >= b && i < f - b) {
+#pragma unroll
+                        for (int v = 0; v < V; ++v)
+                            acc[v] += __uint_as_float(from_key(key[v][i < F ? i : 0]));
+                    }
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < V; ++v) o[v] = __float_as_uint(acc[v] / denom);
+    } else {
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int i = 0; i < F; ++i)
+                if (i >= b && i < f - b) acc += __uint_as_float(from_key(key[v][i]));
+            o[v] = __float_as_uint(acc / denom);
+        }
     }
 }
 
@@ -997,7 +1029,7 @@ __global__ __launch_bounds__(kBlock) void trimmed_mean_kernel(
 #undef BYZ_S_KEY
 #define BYZ_S_KEY(j, x) to_key(x)
     uint32_t o[V];
-    trimmed_mean_of_sorted<F, V>(key, PAD ? f : F, b, o);
+    trimmed_mean_of_sorted<F, V, (F >= kPinFrom)>(key, PAD ? f : F, b, o);
     store_vec<V>(out + c0, o);
 }
 
@@ -1470,7 +1502,7 @@ __device__ __forceinline__ void fused_body(const uint32_t *__restrict__ X, int64
 #include "selnet_pin_on.inc"
 #include "generated/selnet_sort_stream_dispatch.inc"
 #include "selnet_pin_off.inc"
-        trimmed_mean_of_sorted<F, V>(key, F, trim_b, o);
+        trimmed_mean_of_sorted<F, V, true>(key, F, trim_b, o);
     }
 #undef BYZ_S_ROW_ADDR
     if (gt < n_thr) store_vec<V>(out + c0, o);
