@@ -1,9 +1,11 @@
-"""The two identities the kernels for more than 169 rows rest on, checked on the CPU by brute force.
+"""Identities the kernels rest on, checked on the CPU by brute force.
 
-Nothing here calls the library or the oracle: these are statements about sorted sequences, tried
-on every 0/1 input of small sizes (comparator networks and min/max formulas that are right on
-all 0/1 inputs are right on all inputs) and on random integers with many ties at the sizes the
-kernels use.
+Nothing here calls the library or the oracle.  The rank formula and the exchange + bitonic
+rounds of the kernels for more than 169 rows are statements about sorted sequences, tried on
+every 0/1 input of small sizes (comparator networks and min/max formulas that are right on all
+0/1 inputs are right on all inputs) and on random integers with many ties at the sizes the
+kernels use.  The single pass's rule for the copy that feeds the median, and the condition
+under which its output stands, are modelled on small vectors.
 """
 import itertools
 
@@ -80,3 +82,52 @@ def test_exchange_and_bitonic_rounds_sort_at_the_kernels_sizes(H):
     for _ in range(60):
         v = rng.integers(0, 12, size=2 * H).tolist()
         assert split_and_sort(sorted(v[:H]), sorted(v[H:]), 128) == sorted(v)
+
+
+def _single_pass_model(copies, wave):
+    """The single pass's choice of the copy that feeds the median, modelled on small vectors:
+    per stretch of `wave` coordinates the first copy of the largest class of copies identical on
+    that stretch feeds; `differs[b]` says whether some stretch fed a copy that differed from copy
+    b there.  -> (fed vector, differs, winner by plurality with the lowest index on ties)."""
+    r, n = copies.shape
+    fed = np.zeros(n, dtype=copies.dtype)
+    differs = [False] * r
+    for c0 in range(0, n, wave):
+        seg = copies[:, c0:c0 + wave]
+        same = [[bool((seg[a] == seg[b]).all()) for b in range(r)] for a in range(r)]
+        sizes = [sum(row) for row in same]
+        pick = sizes.index(max(sizes))
+        fed[c0:c0 + wave] = seg[pick]
+        for b in range(r):
+            differs[b] = differs[b] or not same[pick][b]
+    same_all = [[bool((copies[a] == copies[b]).all()) for b in range(r)] for a in range(r)]
+    counts = [sum(row) for row in same_all]
+    winner = counts.index(max(counts))
+    return fed, differs, winner, counts[winner]
+
+
+@pytest.mark.parametrize("r", [3, 5, 7])
+def test_wave_local_choice_feeds_the_winner_or_says_so(r):
+    # (1) if no stretch fed a copy that differed from the winner there, the fed vector is the
+    # winner's; (2) a winner with a strict majority of the copies is never differed from
+    rng = np.random.default_rng(r)
+    stood = redone = 0
+    for _ in range(6000):
+        n, wave = 12, 4
+        n_kinds = int(rng.integers(1, r + 1))
+        kinds = rng.integers(0, 2, size=(n_kinds, n))
+        # kinds that agree on most stretches: start from one vector, change a few words
+        kinds[1:] = kinds[0]
+        for k in range(1, n_kinds):
+            for c in rng.integers(0, n, size=int(rng.integers(1, 3))):
+                kinds[k, c] = rng.integers(2, 5)
+        copies = kinds[rng.integers(0, n_kinds, size=r)]
+        fed, differs, winner, count = _single_pass_model(copies, wave)
+        if not differs[winner]:
+            assert (fed == copies[winner]).all()
+            stood += 1
+        else:
+            redone += 1
+        if 2 * count > r:
+            assert not differs[winner]
+    assert stood > 0 and redone > 0
